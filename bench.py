@@ -1,0 +1,160 @@
+#!/usr/bin/env python3
+"""Benchmark of the forward sparse convolution layer with attention on one MI355X.
+
+A step = one pass of the whole hot path (index build, candidate sites, convolution,
+k-selection, ReLU, compaction and write) over one batch of the r = 128 workload:
+3-D shell-surface voxel grid 128^3, batch 4, 32 -> 64 channels, dense 3x3x3 filter,
+rho_up = 0.05, ReLU.  Inputs are synthetic (seeded) and resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+PEAK_MFMA_FP32_TFLOPS = 157.3
+PEAK_FP64_VECTOR_TFLOPS = 78.6
+
+
+def cpu_baseline(wl, layer, w, mac_total):
+    """The oracle, as it stands, on a bounded sample of the same workload: sample 0, all output channels."""
+    import numpy as np
+    import oracle
+    sel = wl.coords[:, 0] == 0
+    coords = wl.coords[sel].copy()
+    feats = wl.feats[sel]
+    n_oc = w.shape[2]
+    ws = np.ascontiguousarray(w[:, :, :n_oc])
+    threads = min(16, os.cpu_count() or 1)
+    k = oracle.k_from_rho(layer.rho_up, int(np.prod(wl.extent)))
+    t0 = time.perf_counter()
+    _, _, info = oracle.sparse_conv_fwd(wl.extent, 1, coords, feats, layer.ksize, ws, k=k, relu=layer.relu,
+                                        pool=layer.pool, threads=threads, return_info=True)
+    dt = time.perf_counter() - t0
+    return {"value": info["macs"] / dt / 1e9, "unit": "GMAC/s (non-zero MACs)", "cores": info["threads"],
+            "kind": "oracle", "seconds": dt,
+            "sample": f"sample 0 of {wl.batch}, output channels 0..{n_oc - 1} of {w.shape[2]} "
+                      f"({info['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload index (1..5); 4 is the headline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the layer shards by sample with no exchange; "
+              "no multi-GPU path exists) -- use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_1801_10585_amd as scnn
+    from workloads import make_config
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    wl = make_config(args.config)
+    layer = wl.layers[0]
+    w = wl.filters[0]
+    ndim = wl.ndim
+    mac_nz = scnn.count_mac_nz(wl.extent, wl.coords, wl.feats, layer.ksize, w)
+
+    coords = torch.from_numpy(wl.coords).to(dev)
+    feats = torch.from_numpy(wl.feats).to(dev)
+    wd = torch.from_numpy(w).to(dev)
+    nnz_in, c_in = wl.feats.shape
+    c_out = w.shape[2]
+    # size the buffers from a first (untimed) run: candidate count is data dependent
+    oc0, of0, n0 = scnn.sparse_conv_fwd(wl.extent, wl.batch, coords, feats, layer.ksize, wd, rho_up=layer.rho_up,
+                                        relu=layer.relu, pool=layer.pool)
+    rows_out, n_cand = int(n0[0]), int(n0[1])
+    del oc0, of0
+    cand_cap = n_cand
+    fuse = (1 if layer.relu else 0) | (2 if layer.pool else 0)
+    ws_bytes = scnn.sparse_conv_fwd_workspace(wl.extent, wl.batch, nnz_in, c_in, c_out, layer.ksize, fuse, cand_cap)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    out = (torch.empty((cand_cap, 1 + ndim), dtype=torch.int32, device=dev),
+           torch.empty((cand_cap, c_out), dtype=torch.float32, device=dev),
+           torch.zeros(4, dtype=torch.int64, device=dev))
+
+    def step():
+        scnn.sparse_conv_fwd(wl.extent, wl.batch, coords, feats, layer.ksize, wd, rho_up=layer.rho_up,
+                             relu=layer.relu, pool=layer.pool, out_capacity=cand_cap, cand_capacity=cand_cap,
+                             workspace=workspace, out=out, sync=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # timed region: per-stage HIP events are recorded on the launch stream inside the library
+    scnn.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    scnn.profile_enable(False)
+    stage_ms, calls = scnn.profile_collect()
+    n_chk = out[2].cpu()
+    assert int(n_chk[0]) == rows_out and int(n_chk[2]) == 0, "timed runs disagree with the sizing run"
+
+    # the same region once more without the events, to state their overhead
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt_plain = time.perf_counter() - t1
+
+    ms_per_step = dt / args.steps * 1e3
+    gmacs = mac_nz * args.steps / dt / 1e9
+    conv_ms = stage_ms["conv"] / max(calls, 1)
+    conv_tflops = 2.0 * mac_nz / (conv_ms * 1e-3) / 1e12
+    bytes_alg = scnn.algorithmic_bytes(ndim, nnz_in, c_in, w.shape[0], c_out, n_cand, rows_out)
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"conv_cfg{args.config}_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    conv_kernel = os.environ.get("SCNN_CONV_KERNEL_NAME", "conv")
+    line = {
+        "metric": "effective non-zero GMAC/s of sparse conv+attention; % of HBM roofline",
+        "value": gmacs, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "grid": list(wl.extent), "batch": wl.batch, "c_in": c_in, "c_out": c_out,
+                   "ksize": list(layer.ksize), "filter_density": layer.filter_density, "rho_up": layer.rho_up,
+                   "relu": layer.relu, "pool": layer.pool, "rows_in": int(nnz_in), "candidate_sites": n_cand,
+                   "rows_out": rows_out, "mac_nz": int(mac_nz), "input_density": wl.density, "seed": wl.seed},
+        "roofline": {"bound": "mfma", "kernel": conv_kernel, "achieved": conv_tflops, "peak": PEAK_MFMA_FP32_TFLOPS,
+                     "unit": "TFLOP/s", "frac": conv_tflops / PEAK_MFMA_FP32_TFLOPS, "traffic": traffic,
+                     "kernel_ms": conv_ms, "flops_per_launch": 2 * int(mac_nz)},
+        "hbm": {"algorithmic_bytes": bytes_alg["alg"], "achieved_GBs": bytes_alg["alg"] / (ms_per_step * 1e-3) / 1e9,
+                "frac_of_8TBs": bytes_alg["alg"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "whole_layer_roofline_frac": max(bytes_alg["alg"] / (PEAK_HBM_GBS * 1e9),
+                                                 2.0 * mac_nz / (PEAK_MFMA_FP32_TFLOPS * 1e12)) / (ms_per_step * 1e-3)},
+        "stage_ms": {k: v / max(calls, 1) for k, v in stage_ms.items()},
+        "ms_per_step_without_events": dt_plain / args.steps * 1e3,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, layer, w, mac_nz)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,161 @@
+/*
+ * scnn.h -- C ABI of the MI355X (gfx950) forward sparse convolution layer with
+ * attention, after Hackel et al., "Inference, Learning and Attention Mechanisms
+ * that Exploit and Preserve Sparsity in CNNs".
+ *
+ * Data model (Sec. 3 of the paper: a sparse tensor is a coordinate list plus
+ * values, sorted so that memory access coalesces).  This library stores one row
+ * per occupied site with a channel vector:
+ *
+ *   coords  int32 [rows, 1+ndim]   (b, c_1 .. c_ndim); rows unique and sorted
+ *                                  ascending by (b, lin); lin is the row-major
+ *                                  site index, last coordinate fastest
+ *   feats   fp32  [rows, C]        row-major; exact 0.0f means "entry absent"
+ *   filter  fp32  [T, C_in, C_out] T = prod(ksize); tap t is row-major over
+ *                                  (delta_1..delta_ndim) + h, h = (ksize-1)/2;
+ *                                  exact 0.0f means "weight pruned"
+ *
+ * Pointers.  `extent` and `ksize` are HOST pointers (ndim int32 each).  Every
+ * other array pointer is a DEVICE pointer owned by the caller.  The library
+ * allocates no device memory: scratch comes from the caller's `workspace`
+ * (device, 256-byte aligned), sized by the matching *_workspace() query.
+ *
+ * Execution.  All work is enqueued on `hip_stream` (a hipStream_t passed as
+ * void*; NULL = the default stream).  No call synchronises with the host.
+ *
+ * Result counters.  `nnz_out` points to SCNN_NNZ_LEN device int64 values:
+ *   [0] rows produced (the true count, even when it exceeds out_capacity;
+ *       rows beyond out_capacity are not written)
+ *   [1] number of candidate output sites examined (conv) / input rows (others)
+ *   [2] status bits, see SCNN_FLAG_*; 0 = fine
+ *   [3] reserved
+ * The caller reads them after its own synchronisation.
+ *
+ * Return value: SCNN_OK or a negative SCNN_E* code; scnn_last_error() gives a
+ * host string for the calling thread's last failure.  No exception crosses
+ * this boundary.  Preconditions that are not checked on the host (sorted,
+ * unique, in-range coordinates; finite values) are reported through the
+ * status bits where the kernels can see them cheaply; rows with out-of-range
+ * coordinates are skipped, never dereferenced.
+ */
+#ifndef SCNN_H_
+#define SCNN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SCNN_OK 0
+#define SCNN_EINVAL (-1)     /* null pointer, ndim not 2/3, even or zero filter size, C <= 0, rho_up not in [0,1], ... */
+#define SCNN_ECAPACITY (-2)  /* a size does not fit the library's 31-bit row / site indices */
+#define SCNN_EWORKSPACE (-3) /* workspace_bytes smaller than the query's answer, or workspace misaligned */
+#define SCNN_EUNSORTED (-4)  /* only from scnn_validate_rows */
+#define SCNN_EHIP (-5)       /* a HIP call or kernel launch failed */
+
+#define SCNN_NNZ_LEN 4
+#define SCNN_FLAG_CAND_OVERFLOW 1u /* more candidate sites than cand_capacity: output is empty */
+#define SCNN_FLAG_OUT_OVERFLOW 2u  /* more output rows than out_capacity: output truncated */
+#define SCNN_FLAG_BAD_COORD 4u     /* an input row had a coordinate outside the grid: row skipped */
+#define SCNN_FLAG_UNSORTED 8u      /* input rows not strictly ascending by (b, lin): result undefined */
+
+#define SCNN_TOPK_ABS 0    /* keep the k responses of largest magnitude (Sec. 3.2, second variant) */
+#define SCNN_TOPK_SIGNED 1 /* keep the k largest raw responses       (Sec. 3.2, first variant)  */
+
+#define SCNN_FUSE_RELU 1u     /* sparse ReLU after the selection */
+#define SCNN_FUSE_MAXPOOL2 2u /* then sparse max-pooling, window = stride = 2 (Sec. 3.3) */
+
+const char* scnn_last_error(void);
+int scnn_version(void);
+
+/* k of the k-selection from the density bound rho_up (Sec. 1, Sec. 3.2: at
+ * most rho_up of the n_sites sites of one channel of one sample stay non-zero).
+ * floor(rho_up * n_sites), except that a product within 1e-9 (relative) of an
+ * integer counts as that integer; clamped to [0, n_sites].  Host only. */
+int64_t scnn_k_from_rho(double rho_up, int64_t n_sites);
+
+/* Upper bound on the number of candidate output sites of a convolution:
+ * min(batch * prod(extent), nnz_in * prod(ksize)).  Host only; < 0 on error. */
+int64_t sparse_conv_fwd_max_rows(int ndim, const int32_t* extent, int batch, int64_t nnz_in, const int32_t* ksize);
+
+/* Bytes of workspace sparse_conv_fwd needs for these sizes.  cand_capacity <= 0
+ * means the bound above.  Host only; 0 on error. */
+size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int64_t nnz_in, int c_in, int c_out,
+                                 const int32_t* ksize, unsigned fuse, int64_t cand_capacity);
+
+/* Forward direct sparse convolution with attention (Algorithm 1), optionally
+ * followed by sparse ReLU and sparse 2^ndim max-pooling.
+ *
+ *   out[b, p, oc] = sum over taps delta, channels ic of
+ *                   w[tap(delta), ic, oc] * in[b, p + delta, ic]
+ * (stride 1, zero "same" padding: an input at q updates p = q - delta, updates
+ * leaving the grid are dropped -- Alg. 1 steps 5-9).  Inputs, weights and
+ * responses are fp32; each response is summed in a fixed order (tap ascending,
+ * ic ascending) in wider-than-fp32 arithmetic and rounded to fp32 once, so the
+ * result is reproducible bit for bit.  Responses that are exactly 0 are
+ * not entries (step 13).  bias (nullable, device, [c_out]) is added to the
+ * entries (step 14); an entry whose biased value is exactly 0 stops being one.
+ * Per (sample b, output channel oc) only the k = scnn_k_from_rho(rho_up, N)
+ * entries with the largest score survive (step 15; score = |v| or v by
+ * topk_mode); ties at the k-th score go to the lower lin.  Fewer than k entries:
+ * all survive.  Then, by `fuse`: entries with v <= 0 are dropped; then entries
+ * are max-pooled over the present members of each 2^ndim block, the output grid
+ * being ceil(extent/2).  Output rows = sites with at least one surviving entry,
+ * ascending by (b, lin), absent entries stored as 0.0f (steps 16-17).
+ *
+ * out_coords int32 [out_capacity, 1+ndim], out_feats fp32 [out_capacity, c_out].
+ * cand_capacity: as given to the workspace query (<= 0: the default bound). */
+int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, const float* bias, int c_out,
+                    double rho_up, int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats,
+                    int64_t out_capacity, int64_t cand_capacity, int64_t* nnz_out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream);
+
+/* The attention step alone (Sec. 3.2; Alg. 1 steps 13, 15-17): k-selection per
+ * (sample, channel) over the non-zero entries of a site-major response matrix
+ * resp[rows, channels] whose rows are given by `coords`.  k is the integer
+ * count per (sample, channel).  Same tie rule and output format as above. */
+size_t attention_topk_workspace(int ndim, const int32_t* extent, int batch, int64_t rows, int channels);
+int attention_topk(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* resp,
+                   int64_t rows, int channels, int64_t k, int topk_mode, int32_t* out_coords, float* out_feats,
+                   int64_t out_capacity, int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Sparse ReLU (listed among the paper's layers, Sec. 1): entries with v > 0
+ * survive, rows left without an entry are removed. */
+size_t sparse_relu_workspace(int64_t rows, int channels);
+int sparse_relu(int ndim, const int32_t* coords, const float* feats, int64_t rows, int channels,
+                int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t* nnz_out, void* workspace,
+                size_t workspace_bytes, void* hip_stream);
+
+/* Sparse max-pooling (Sec. 3.3): output site = floor(p / window), output extent
+ * = ceil(extent / window), maximum over the present entries of each cluster,
+ * per channel.  window == stride; only window = 2 is implemented. */
+size_t sparse_maxpool_workspace(int ndim, const int32_t* extent, int batch, int64_t rows, int channels);
+int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const int32_t* coords, const float* feats,
+                   int64_t rows, int channels, int32_t* out_coords, float* out_feats, int64_t out_capacity,
+                   int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Optional precondition check of a coordinate list (synchronises the stream):
+ * SCNN_OK, SCNN_EINVAL (coordinate outside the grid) or SCNN_EUNSORTED (rows
+ * not strictly ascending by (b, lin)).  workspace: at least 256 bytes. */
+int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Measurement support (not part of the method): when enabled on the calling
+ * thread, every sparse_conv_fwd call records HIP events on its stream at the
+ * boundaries of its stages (index build, candidate sites, convolution,
+ * k-selection, compaction + write, pooling).  scnn_profile_collect waits for
+ * the recorded calls, adds their per-stage milliseconds into stage_ms
+ * [scnn_profile_stage_count()] and the number of calls into *calls, then
+ * forgets them.  Host pointers. */
+int scnn_profile_enable(int on);
+int scnn_profile_stage_count(void);
+const char* scnn_profile_stage_name(int stage);
+int scnn_profile_collect(double* stage_ms, int64_t* calls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCNN_H_ */

@@ -1,0 +1,288 @@
+"""ctypes binding of libscnn.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libscnn.so")
+_lib = None
+
+ABS, SIGNED = 0, 1
+FUSE_RELU, FUSE_MAXPOOL2 = 1, 2
+FLAG_CAND_OVERFLOW, FLAG_OUT_OVERFLOW, FLAG_BAD_COORD, FLAG_UNSORTED = 1, 2, 4, 8
+NNZ_LEN = 4
+
+EXPORTED_SYMBOLS = [
+    "scnn_last_error", "scnn_version", "scnn_k_from_rho", "sparse_conv_fwd_max_rows", "sparse_conv_fwd_workspace",
+    "sparse_conv_fwd", "attention_topk_workspace", "attention_topk", "sparse_relu_workspace", "sparse_relu",
+    "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
+    "scnn_profile_stage_count", "scnn_profile_stage_name", "scnn_profile_collect",
+]
+
+
+class ScnnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libscnn error {code}: {msg}")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libscnn.so.  If it was never built, build it once (tests and the benchmark
+    normally find it already built in-tree); a missing compiler is an error, not a fallback."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build(force=False)
+    L = ctypes.CDLL(_LIB_PATH)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    vp, i64, sz, ci, cu, dbl = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t, ctypes.c_int, ctypes.c_uint, ctypes.c_double
+    L.scnn_last_error.restype = ctypes.c_char_p
+    L.scnn_version.restype = ci
+    L.scnn_k_from_rho.restype = i64
+    L.scnn_k_from_rho.argtypes = [dbl, i64]
+    L.sparse_conv_fwd_max_rows.restype = i64
+    L.sparse_conv_fwd_max_rows.argtypes = [ci, i32p, ci, i64, i32p]
+    L.sparse_conv_fwd_workspace.restype = sz
+    L.sparse_conv_fwd_workspace.argtypes = [ci, i32p, ci, i64, ci, ci, i32p, cu, i64]
+    L.sparse_conv_fwd.restype = ci
+    L.sparse_conv_fwd.argtypes = [ci, i32p, ci, vp, vp, i64, ci, i32p, vp, vp, ci, dbl, ci, cu, vp, vp, i64, i64, vp,
+                                  vp, sz, vp]
+    L.attention_topk_workspace.restype = sz
+    L.attention_topk_workspace.argtypes = [ci, i32p, ci, i64, ci]
+    L.attention_topk.restype = ci
+    L.attention_topk.argtypes = [ci, i32p, ci, vp, vp, i64, ci, i64, ci, vp, vp, i64, vp, vp, sz, vp]
+    L.sparse_relu_workspace.restype = sz
+    L.sparse_relu_workspace.argtypes = [i64, ci]
+    L.sparse_relu.restype = ci
+    L.sparse_relu.argtypes = [ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
+    L.sparse_maxpool_workspace.restype = sz
+    L.sparse_maxpool_workspace.argtypes = [ci, i32p, ci, i64, ci]
+    L.sparse_maxpool.restype = ci
+    L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
+    L.scnn_validate_rows.restype = ci
+    L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
+    L.scnn_profile_enable.restype = ci
+    L.scnn_profile_enable.argtypes = [ci]
+    L.scnn_profile_stage_count.restype = ci
+    L.scnn_profile_stage_name.restype = ctypes.c_char_p
+    L.scnn_profile_stage_name.argtypes = [ci]
+    L.scnn_profile_collect.restype = ci
+    L.scnn_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i64)]
+    _lib = L
+    return L
+
+
+def _check(L, rc: int):
+    if rc != 0:
+        raise ScnnError(rc, L.scnn_last_error().decode())
+
+
+def _i32arr(v: Sequence[int]):
+    return (ctypes.c_int32 * len(v))(*[int(x) for x in v])
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}")
+    return t.contiguous()
+
+
+def k_from_rho(rho_up: float, n_sites: int) -> int:
+    return int(load_library().scnn_k_from_rho(float(rho_up), int(n_sites)))
+
+
+def sparse_conv_fwd_max_rows(extent, batch, nnz_in, ksize) -> int:
+    L = load_library()
+    r = int(L.sparse_conv_fwd_max_rows(len(extent), _i32arr(extent), int(batch), int(nnz_in), _i32arr(ksize)))
+    if r < 0:
+        _check(L, r)
+    return r
+
+
+def sparse_conv_fwd_workspace(extent, batch, nnz_in, c_in, c_out, ksize, fuse=0, cand_capacity=0) -> int:
+    L = load_library()
+    r = int(L.sparse_conv_fwd_workspace(len(extent), _i32arr(extent), int(batch), int(nnz_in), int(c_in), int(c_out),
+                                        _i32arr(ksize), int(fuse), int(cand_capacity)))
+    if r == 0:
+        raise ScnnError(-1, L.scnn_last_error().decode())
+    return r
+
+
+def _finish(out_coords, out_feats, nnz, sync):
+    if not sync:
+        return out_coords, out_feats, nnz
+    n = nnz.cpu()
+    rows, flags = int(n[0]), int(n[2])
+    if flags & (FLAG_CAND_OVERFLOW | FLAG_OUT_OVERFLOW):
+        raise ScnnError(-2, f"capacity exceeded (rows={rows}, candidates={int(n[1])}, flags={flags})")
+    return out_coords[:rows], out_feats[:rows], n
+
+
+def sparse_conv_fwd(extent, batch, coords, feats, ksize, w, bias=None, *, rho_up=1.0, topk_mode=ABS, relu=False,
+                    pool=False, out_capacity: Optional[int] = None, cand_capacity: int = 0, workspace=None,
+                    out=None, stream=None, sync=True):
+    """Forward sparse convolution + attention (+ReLU, +2^d max-pool).  Returns (out_coords, out_feats, nnz)
+    where nnz is the int64[4] counter vector (device tensor when sync=False, host tensor otherwise)."""
+    L = load_library()
+    ndim = len(extent)
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    w = _dev(w, torch.float32, "w")
+    if bias is not None:
+        bias = _dev(bias, torch.float32, "bias")
+    nnz_in, c_in = feats.shape
+    taps, c_in_w, c_out = w.shape
+    if c_in_w != c_in or coords.shape != (nnz_in, 1 + ndim):
+        raise ValueError("shape mismatch between coords, feats and w")
+    t = 1
+    for s in ksize:
+        t *= int(s)
+    if t != taps:
+        raise ValueError("w.shape[0] != prod(ksize)")
+    if bias is not None and bias.shape != (c_out,):
+        raise ValueError("bias must be [c_out]")
+    fuse = (FUSE_RELU if relu else 0) | (FUSE_MAXPOOL2 if pool else 0)
+    ext, ks = _i32arr(extent), _i32arr(ksize)
+    dev = feats.device
+    if cand_capacity <= 0:
+        cand_capacity = int(L.sparse_conv_fwd_max_rows(ndim, ext, int(batch), nnz_in, ks))
+    if out_capacity is None:
+        out_capacity = cand_capacity
+    need = int(L.sparse_conv_fwd_workspace(ndim, ext, int(batch), nnz_in, c_in, c_out, ks, fuse, cand_capacity))
+    if need == 0:
+        raise ScnnError(-1, L.scnn_last_error().decode())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if out is None:
+        out_coords = torch.empty((out_capacity, 1 + ndim), dtype=torch.int32, device=dev)
+        out_feats = torch.empty((out_capacity, c_out), dtype=torch.float32, device=dev)
+        nnz = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+    else:
+        out_coords, out_feats, nnz = out
+    rc = L.sparse_conv_fwd(ndim, ext, int(batch), _ptr(coords), _ptr(feats), nnz_in, c_in, ks, _ptr(w), _ptr(bias),
+                           c_out, float(rho_up), int(topk_mode), fuse, _ptr(out_coords), _ptr(out_feats),
+                           int(out_capacity), int(cand_capacity), _ptr(nnz), _ptr(workspace), workspace.numel(),
+                           _stream(stream))
+    _check(L, rc)
+    return _finish(out_coords, out_feats, nnz, sync)
+
+
+def attention_topk(extent, batch, coords, resp, k, topk_mode=ABS, *, out_capacity=None, workspace=None, stream=None,
+                   sync=True):
+    L = load_library()
+    ndim = len(extent)
+    coords = _dev(coords, torch.int32, "coords")
+    resp = _dev(resp, torch.float32, "resp")
+    rows, ch = resp.shape
+    ext = _i32arr(extent)
+    dev = resp.device
+    if out_capacity is None:
+        out_capacity = rows
+    need = int(L.attention_topk_workspace(ndim, ext, int(batch), rows, ch))
+    if need == 0:
+        raise ScnnError(-1, "attention_topk_workspace: bad arguments")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out_coords = torch.empty((out_capacity, 1 + ndim), dtype=torch.int32, device=dev)
+    out_feats = torch.empty((out_capacity, ch), dtype=torch.float32, device=dev)
+    nnz = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+    rc = L.attention_topk(ndim, ext, int(batch), _ptr(coords), _ptr(resp), rows, ch, int(k), int(topk_mode),
+                          _ptr(out_coords), _ptr(out_feats), int(out_capacity), _ptr(nnz), _ptr(workspace),
+                          workspace.numel(), _stream(stream))
+    _check(L, rc)
+    return _finish(out_coords, out_feats, nnz, sync)
+
+
+def sparse_relu(ndim, coords, feats, *, out_capacity=None, workspace=None, stream=None, sync=True):
+    L = load_library()
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    rows, ch = feats.shape
+    dev = feats.device
+    if out_capacity is None:
+        out_capacity = rows
+    need = int(L.sparse_relu_workspace(rows, ch))
+    if need == 0:
+        raise ScnnError(-1, "sparse_relu_workspace: bad arguments")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out_coords = torch.empty((out_capacity, 1 + ndim), dtype=torch.int32, device=dev)
+    out_feats = torch.empty((out_capacity, ch), dtype=torch.float32, device=dev)
+    nnz = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+    rc = L.sparse_relu(int(ndim), _ptr(coords), _ptr(feats), rows, ch, _ptr(out_coords), _ptr(out_feats),
+                       int(out_capacity), _ptr(nnz), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(L, rc)
+    return _finish(out_coords, out_feats, nnz, sync)
+
+
+def sparse_maxpool(extent, batch, coords, feats, window=2, *, out_capacity=None, workspace=None, stream=None,
+                   sync=True):
+    L = load_library()
+    ndim = len(extent)
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    rows, ch = feats.shape
+    ext = _i32arr(extent)
+    dev = feats.device
+    if out_capacity is None:
+        out_capacity = rows
+    need = int(L.sparse_maxpool_workspace(ndim, ext, int(batch), rows, ch))
+    if need == 0:
+        raise ScnnError(-1, "sparse_maxpool_workspace: bad arguments")
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    out_coords = torch.empty((out_capacity, 1 + ndim), dtype=torch.int32, device=dev)
+    out_feats = torch.empty((out_capacity, ch), dtype=torch.float32, device=dev)
+    nnz = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+    rc = L.sparse_maxpool(ndim, ext, int(batch), int(window), _ptr(coords), _ptr(feats), rows, ch, _ptr(out_coords),
+                          _ptr(out_feats), int(out_capacity), _ptr(nnz), _ptr(workspace), workspace.numel(),
+                          _stream(stream))
+    _check(L, rc)
+    return _finish(out_coords, out_feats, nnz, sync)
+
+
+def validate_rows(extent, batch, coords, stream=None) -> None:
+    """Raises ScnnError if coords are out of the grid (-1) or not strictly ascending (-4).  Synchronises."""
+    L = load_library()
+    coords = _dev(coords, torch.int32, "coords")
+    ws = torch.empty(256, dtype=torch.uint8, device=coords.device)
+    rc = L.scnn_validate_rows(len(extent), _i32arr(extent), int(batch), _ptr(coords), coords.shape[0], _ptr(ws), 256,
+                              _stream(stream))
+    _check(L, rc)
+
+
+def profile_enable(on: bool) -> None:
+    """Per-stage HIP-event timing of sparse_conv_fwd calls made from this thread."""
+    _check(load_library(), load_library().scnn_profile_enable(1 if on else 0))
+
+
+def profile_collect():
+    """Waits for the recorded calls; returns ({stage name: total ms}, number of calls)."""
+    L = load_library()
+    n = L.scnn_profile_stage_count()
+    ms = (ctypes.c_double * n)()
+    calls = ctypes.c_int64(0)
+    _check(L, L.scnn_profile_collect(ms, ctypes.byref(calls)))
+    return {L.scnn_profile_stage_name(i).decode(): float(ms[i]) for i in range(n)}, int(calls.value)

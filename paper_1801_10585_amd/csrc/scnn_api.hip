@@ -1,0 +1,578 @@
+// Host side of the C ABI: argument checks, workspace layout, launch sequences.
+// Nothing here touches values; every step of the layer runs in the kernels.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "scnn_internal.h"
+
+namespace scnn {
+
+static thread_local char g_err[256] = "";
+
+static int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+static int fail_hip(hipError_t e, const char* what) {
+    return fail(SCNN_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define SCNN_TRY(expr)                                         \
+    do {                                                       \
+        hipError_t e__ = (expr);                               \
+        if (e__ != hipSuccess) return fail_hip(e__, #expr);    \
+    } while (0)
+
+static constexpr long long kMaxIndex = 0x7fffffffLL;  // rows, candidates and sites use 31-bit indices
+static constexpr int kMaxChannels = 1024;
+
+// Right-align the real axes in three internal axes.
+static int make_geom(int ndim, const int32_t* extent, int batch, const int32_t* ksize, Geom* g) {
+    if (ndim != 2 && ndim != 3) return fail(SCNN_EINVAL, "ndim must be 2 or 3 (got %d)", ndim);
+    if (!extent) return fail(SCNN_EINVAL, "extent is null");
+    if (batch < 1) return fail(SCNN_EINVAL, "batch must be >= 1 (got %d)", batch);
+    memset(g, 0, sizeof(*g));
+    g->ndim = ndim;
+    g->batch = batch;
+    for (int a = 0; a < 3; ++a) { g->E[a] = 1; g->K[a] = 1; g->H[a] = 0; }
+    long long n = 1;
+    for (int a = 0; a < ndim; ++a) {
+        if (extent[a] < 1) return fail(SCNN_EINVAL, "extent[%d] = %d", a, extent[a]);
+        g->E[3 - ndim + a] = extent[a];
+        n *= extent[a];
+        if (n > kMaxIndex) return fail(SCNN_ECAPACITY, "more than 2^31-1 sites per sample");
+    }
+    long long t = 1;
+    if (ksize) {
+        for (int a = 0; a < ndim; ++a) {
+            if (ksize[a] < 1 || ksize[a] % 2 == 0) return fail(SCNN_EINVAL, "ksize[%d] = %d must be odd", a, ksize[a]);
+            g->K[3 - ndim + a] = ksize[a];
+            g->H[3 - ndim + a] = (ksize[a] - 1) / 2;
+            t *= ksize[a];
+            if (t > 1 << 20) return fail(SCNN_ECAPACITY, "filter has too many taps");
+        }
+    }
+    g->T = (int)t;
+    g->N = n;
+    g->Npad = round_up(n, 64);
+    g->Wps = (int)(g->Npad / 64);
+    if ((long long)batch * g->Wps > kMaxIndex) return fail(SCNN_ECAPACITY, "batch * sites too large");
+    return SCNN_OK;
+}
+
+static Geom pooled_geom(const Geom& g) {
+    Geom p = g;
+    long long n = 1;
+    for (int a = 0; a < 3; ++a) {
+        p.E[a] = (g.E[a] + 1) / 2;
+        p.K[a] = 1;
+        p.H[a] = 0;
+        n *= p.E[a];
+    }
+    p.T = 1;
+    p.N = n;
+    p.Npad = round_up(n, 64);
+    p.Wps = (int)(p.Npad / 64);
+    return p;
+}
+
+// Bump allocator over the caller's workspace; with base == nullptr it only measures.
+struct Carver {
+    char* base;
+    size_t off = 0;
+    explicit Carver(void* b) : base((char*)b) {}
+    template <typename T>
+    T* take(size_t count) {
+        off = (off + 255) & ~(size_t)255;
+        T* p = base ? (T*)(base + off) : nullptr;
+        off += count * sizeof(T);
+        return p;
+    }
+    size_t total() const { return (off + 255) & ~(size_t)255; }
+};
+
+static long long scan_blocks(long long cap) { return (cap + kScanChunk - 1) / kScanChunk + 2; }
+
+static long long default_cand_bound(const Geom& g, long long nnz_in) {
+    const long long grid = (long long)g.batch * g.N;
+    const long long reach = nnz_in * (long long)g.T;
+    return grid < reach ? grid : reach;
+}
+
+
+// ---------------------------------------------------------------- per-stage timing (measurement support)
+static const char* const kStageNames[] = {"index_build", "candidates", "conv", "topk_select", "compact_write", "pool_finish"};
+static constexpr int kStages = 6;
+struct ProfCall { hipEvent_t ev[kStages + 1]; };
+static thread_local bool g_prof_on = false;
+static thread_local std::vector<ProfCall>* g_prof_calls = nullptr;   // recorded, not yet collected
+static thread_local std::vector<ProfCall>* g_prof_pool = nullptr;    // idle events for reuse
+
+struct StageTimer {
+    ProfCall call;
+    bool on = false;
+    int next = 0;
+    hipStream_t s;
+    explicit StageTimer(hipStream_t stream) : s(stream) {
+        if (!g_prof_on) return;
+        if (!g_prof_calls) g_prof_calls = new std::vector<ProfCall>();
+        if (!g_prof_pool) g_prof_pool = new std::vector<ProfCall>();
+        if (!g_prof_pool->empty()) {
+            call = g_prof_pool->back();
+            g_prof_pool->pop_back();
+        } else {
+            for (int i = 0; i <= kStages; ++i)
+                if (hipEventCreate(&call.ev[i]) != hipSuccess) return;
+        }
+        on = true;
+    }
+    void mark() {  // boundary between stage next-1 and stage next
+        if (on && next <= kStages) (void)hipEventRecord(call.ev[next++], s);
+    }
+    void done() {
+        if (!on) return;
+        while (next <= kStages) (void)hipEventRecord(call.ev[next++], s);
+        g_prof_calls->push_back(call);
+        on = false;
+    }
+};
+
+// ---------------------------------------------------------------- sparse_conv_fwd
+struct ConvWs {
+    // zeroed at the start of every call (contiguous)
+    Counters* ctr;
+    unsigned long long* occ;
+    unsigned long long* cand;
+    unsigned long long* pbits;
+    unsigned* hist;
+    ColState* cols;
+    size_t zero_bytes;
+    // not zeroed
+    unsigned* occ_prefix;
+    unsigned* cand_prefix;
+    unsigned* pprefix;
+    unsigned* block_sums;
+    int* cand_start;
+    int* tile_start;
+    int* tap_active;
+    double* wp;
+    unsigned* cand_lin;
+    float* resp;
+    unsigned* eqcnt;
+    unsigned* tile_rows;
+    int32_t* tmp_coords;
+    float* tmp_feats;
+    long long* pool_key;
+    size_t total;
+    long long cand_cap, tiles_cap, pool_cap;
+    int c_out_pad;
+};
+
+static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_in, int c_in, int c_out, unsigned fuse,
+                       long long cand_cap, ConvWs* w) {
+    Carver c(base);
+    const long long nw = (long long)g.batch * g.Wps;
+    const long long nwp = (long long)gp.batch * gp.Wps;
+    const bool pool = (fuse & SCNN_FUSE_MAXPOOL2) != 0;
+    const long long ncols = (long long)g.batch * c_out;
+    w->cand_cap = cand_cap;
+    w->tiles_cap = (cand_cap + kTileRows - 1) / kTileRows + g.batch;
+    const long long grid_p = (long long)gp.batch * gp.N;
+    w->pool_cap = cand_cap < grid_p ? cand_cap : grid_p;
+    w->c_out_pad = (int)round_up(c_out, 16);
+    w->ctr = c.take<Counters>(1);
+    w->occ = c.take<unsigned long long>(nw);
+    w->cand = c.take<unsigned long long>(nw);
+    w->pbits = c.take<unsigned long long>(pool ? nwp : 0);
+    w->hist = c.take<unsigned>(ncols * kHistBins);
+    w->cols = c.take<ColState>(ncols);
+    w->zero_bytes = c.total();
+    w->occ_prefix = c.take<unsigned>(nw);
+    w->cand_prefix = c.take<unsigned>(nw);
+    w->pprefix = c.take<unsigned>(pool ? nwp : 0);
+    long long sb = scan_blocks(nw);
+    if (scan_blocks(w->tiles_cap) > sb) sb = scan_blocks(w->tiles_cap);
+    if (scan_blocks(nwp) > sb) sb = scan_blocks(nwp);
+    w->block_sums = c.take<unsigned>(sb);
+    w->cand_start = c.take<int>(g.batch + 1);
+    w->tile_start = c.take<int>(g.batch + 1);
+    w->tap_active = c.take<int>(g.T);
+    w->wp = c.take<double>((size_t)g.T * c_in * w->c_out_pad);
+    w->cand_lin = c.take<unsigned>(cand_cap);
+    w->resp = c.take<float>((size_t)w->tiles_cap * c_out * kTileRows);
+    w->eqcnt = c.take<unsigned>((size_t)w->tiles_cap * c_out);
+    w->tile_rows = c.take<unsigned>(w->tiles_cap);
+    w->tmp_coords = c.take<int32_t>(pool ? (size_t)cand_cap * (1 + g.ndim) : 0);
+    w->tmp_feats = c.take<float>(pool ? (size_t)cand_cap * c_out : 0);
+    w->pool_key = c.take<long long>(pool ? w->pool_cap : 0);
+    w->total = c.total();
+    (void)nnz_in;
+}
+
+static int check_conv_sizes(const Geom& g, long long nnz_in, int c_in, int c_out, long long* cand_cap) {
+    if (nnz_in < 0 || nnz_in > kMaxIndex) return fail(SCNN_ECAPACITY, "nnz_in = %lld out of range", nnz_in);
+    if (c_in < 1 || c_out < 1) return fail(SCNN_EINVAL, "channel counts must be positive");
+    if (c_in > kMaxChannels || c_out > kMaxChannels) return fail(SCNN_ECAPACITY, "at most %d channels", kMaxChannels);
+    long long bound = default_cand_bound(g, nnz_in);
+    if (*cand_cap <= 0 || *cand_cap > bound) *cand_cap = bound;
+    if (*cand_cap < 1) *cand_cap = 1;
+    if (*cand_cap + (long long)g.batch * kTileRows > kMaxIndex) return fail(SCNN_ECAPACITY, "too many candidate sites");
+    return SCNN_OK;
+}
+
+}  // namespace scnn
+
+using namespace scnn;
+
+extern "C" {
+
+const char* scnn_last_error(void) { return g_err; }
+int scnn_version(void) { return 1; }
+
+int64_t scnn_k_from_rho(double rho_up, int64_t n_sites) {
+    if (!(rho_up >= 0.0) || n_sites < 0) return 0;
+    const double x = rho_up * (double)n_sites;
+    const double rx = std::floor(x + 0.5);
+    int64_t k = (std::fabs(x - rx) <= 1e-9 * (x > 1.0 ? x : 1.0)) ? (int64_t)rx : (int64_t)std::floor(x);
+    if (k < 0) k = 0;
+    if (k > n_sites) k = n_sites;
+    return k;
+}
+
+int64_t sparse_conv_fwd_max_rows(int ndim, const int32_t* extent, int batch, int64_t nnz_in, const int32_t* ksize) {
+    Geom g;
+    int rc = make_geom(ndim, extent, batch, ksize, &g);
+    if (rc != SCNN_OK) return rc;
+    if (!ksize) return fail(SCNN_EINVAL, "ksize is null");
+    if (nnz_in < 0) return fail(SCNN_EINVAL, "nnz_in < 0");
+    return default_cand_bound(g, nnz_in);
+}
+
+size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int64_t nnz_in, int c_in, int c_out,
+                                 const int32_t* ksize, unsigned fuse, int64_t cand_capacity) {
+    Geom g;
+    if (!ksize || make_geom(ndim, extent, batch, ksize, &g) != SCNN_OK) return 0;
+    long long cap = cand_capacity;
+    if (check_conv_sizes(g, nnz_in, c_in, c_out, &cap) != SCNN_OK) return 0;
+    ConvWs w;
+    carve_conv(nullptr, g, pooled_geom(g), nnz_in, c_in, c_out, fuse, cap, &w);
+    return w.total;
+}
+
+int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, const float* bias, int c_out,
+                    double rho_up, int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats,
+                    int64_t out_capacity, int64_t cand_capacity, int64_t* nnz_out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    Geom g;
+    if (!ksize) return fail(SCNN_EINVAL, "ksize is null");
+    int rc = make_geom(ndim, extent, batch, ksize, &g);
+    if (rc != SCNN_OK) return rc;
+    long long cap = cand_capacity;
+    rc = check_conv_sizes(g, nnz_in, c_in, c_out, &cap);
+    if (rc != SCNN_OK) return rc;
+    if (!(rho_up >= 0.0 && rho_up <= 1.0)) return fail(SCNN_EINVAL, "rho_up = %g not in [0, 1]", rho_up);
+    if (topk_mode != SCNN_TOPK_ABS && topk_mode != SCNN_TOPK_SIGNED) return fail(SCNN_EINVAL, "bad topk_mode");
+    if (fuse & ~(SCNN_FUSE_RELU | SCNN_FUSE_MAXPOOL2)) return fail(SCNN_EINVAL, "unknown fuse bits");
+    if (!w || !nnz_out || !workspace) return fail(SCNN_EINVAL, "null pointer (w, nnz_out or workspace)");
+    if (nnz_in > 0 && (!in_coords || !in_feats)) return fail(SCNN_EINVAL, "null input arrays");
+    if (out_capacity < 0 || out_capacity > kMaxIndex) return fail(SCNN_EINVAL, "bad out_capacity");
+    if (out_capacity > 0 && (!out_coords || !out_feats)) return fail(SCNN_EINVAL, "null output arrays");
+    if (((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "workspace must be 256-byte aligned");
+    const Geom gp = pooled_geom(g);
+    ConvWs ws;
+    carve_conv(workspace, g, gp, nnz_in, c_in, c_out, fuse, cap, &ws);
+    if (ws.total > workspace_bytes)
+        return fail(SCNN_EWORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const long long k = scnn_k_from_rho(rho_up, g.N);
+    const long long nw = (long long)g.batch * g.Wps;
+    const bool pool = (fuse & SCNN_FUSE_MAXPOOL2) != 0;
+    const int relu = (fuse & SCNN_FUSE_RELU) ? 1 : 0;
+
+    StageTimer timer(s);
+    timer.mark();
+    SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
+    SCNN_TRY(launch_filter_prep(g, w, c_in, c_out, ws.c_out_pad, ws.wp, ws.tap_active, s));
+    SCNN_TRY(launch_index_build(g, in_coords, nnz_in, nullptr, nnz_in, ws.occ, ws.occ_prefix, ws.ctr, s));
+    timer.mark();
+    SCNN_TRY(launch_cand_mark(g, in_coords, nnz_in, ws.tap_active, ws.cand, s));
+    SCNN_TRY(launch_popcount(ws.cand, nw, ws.cand_prefix, s));
+    SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
+    SCNN_TRY(launch_sample_info(g, ws.cand_prefix, ws.cand_cap, ws.cand_start, ws.tile_start, ws.ctr, s));
+    SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, s));
+    timer.mark();
+    SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
+                              ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+    timer.mark();
+    SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.eqcnt, ws.ctr,
+                         ws.tiles_cap, s));
+    timer.mark();
+    if (!pool) {
+        SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
+                                     ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr,
+                                     out_coords, out_feats, out_capacity, &ws.ctr->n_rows, s));
+        timer.mark();
+        SCNN_TRY(launch_finish(ws.ctr, 0, 0, 1, out_capacity, (long long*)nnz_out, s));
+    } else {
+        SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
+                                     ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr,
+                                     ws.tmp_coords, ws.tmp_feats, ws.cand_cap, &ws.ctr->n_rows, s));
+        timer.mark();
+        SCNN_TRY(launch_zero(ws.occ, (size_t)nw * sizeof(unsigned long long), s));
+        SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1, ws.occ,
+                                ws.occ_prefix, ws.pbits, ws.pprefix, ws.block_sums, ws.pool_key, ws.pool_cap,
+                                out_coords, out_feats, out_capacity, ws.ctr, s));
+        SCNN_TRY(launch_finish(ws.ctr, 1, 0, 1, out_capacity, (long long*)nnz_out, s));
+    }
+    timer.done();
+    return SCNN_OK;
+}
+
+int scnn_profile_enable(int on) {
+    g_prof_on = on != 0;
+    return SCNN_OK;
+}
+
+int scnn_profile_stage_count(void) { return kStages; }
+
+const char* scnn_profile_stage_name(int i) { return (i >= 0 && i < kStages) ? kStageNames[i] : ""; }
+
+int scnn_profile_collect(double* stage_ms, int64_t* calls) {
+    if (!stage_ms || !calls) return fail(SCNN_EINVAL, "null pointer");
+    for (int i = 0; i < kStages; ++i) stage_ms[i] = 0.0;
+    *calls = 0;
+    if (!g_prof_calls) return SCNN_OK;
+    for (ProfCall& c : *g_prof_calls) {
+        SCNN_TRY(hipEventSynchronize(c.ev[kStages]));
+        for (int i = 0; i < kStages; ++i) {
+            float ms = 0.0f;
+            SCNN_TRY(hipEventElapsedTime(&ms, c.ev[i], c.ev[i + 1]));
+            stage_ms[i] += (double)ms;
+        }
+        ++*calls;
+        g_prof_pool->push_back(c);
+    }
+    g_prof_calls->clear();
+    return SCNN_OK;
+}
+
+// ---------------------------------------------------------------- attention_topk
+namespace {
+struct TopkWs {
+    Counters* ctr;
+    unsigned* hist;
+    ColState* cols;
+    size_t zero_bytes;
+    unsigned* block_sums;
+    int* cand_start;
+    int* tile_start;
+    unsigned* cand_lin;
+    float* resp;
+    unsigned* eqcnt;
+    unsigned* tile_rows;
+    long long tiles_cap;
+    size_t total;
+};
+void carve_topk(void* base, const Geom& g, long long rows, int channels, TopkWs* w) {
+    Carver c(base);
+    const long long ncols = (long long)g.batch * channels;
+    w->tiles_cap = (rows + kTileRows - 1) / kTileRows + g.batch;
+    w->ctr = c.take<Counters>(1);
+    w->hist = c.take<unsigned>(ncols * kHistBins);
+    w->cols = c.take<ColState>(ncols);
+    w->zero_bytes = c.total();
+    w->block_sums = c.take<unsigned>(scan_blocks(w->tiles_cap));
+    w->cand_start = c.take<int>(g.batch + 1);
+    w->tile_start = c.take<int>(g.batch + 1);
+    w->cand_lin = c.take<unsigned>(rows > 0 ? rows : 1);
+    w->resp = c.take<float>((size_t)w->tiles_cap * channels * kTileRows);
+    w->eqcnt = c.take<unsigned>((size_t)w->tiles_cap * channels);
+    w->tile_rows = c.take<unsigned>(w->tiles_cap);
+    w->total = c.total();
+}
+}  // namespace
+
+size_t attention_topk_workspace(int ndim, const int32_t* extent, int batch, int64_t rows, int channels) {
+    Geom g;
+    if (make_geom(ndim, extent, batch, nullptr, &g) != SCNN_OK) return 0;
+    if (rows < 0 || rows > kMaxIndex - (long long)batch * kTileRows || channels < 1 || channels > kMaxChannels) return 0;
+    TopkWs w;
+    carve_topk(nullptr, g, rows, channels, &w);
+    return w.total;
+}
+
+int attention_topk(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* resp,
+                   int64_t rows, int channels, int64_t k, int topk_mode, int32_t* out_coords, float* out_feats,
+                   int64_t out_capacity, int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Geom g;
+    int rc = make_geom(ndim, extent, batch, nullptr, &g);
+    if (rc != SCNN_OK) return rc;
+    if (rows < 0 || rows > kMaxIndex - (long long)batch * kTileRows) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (channels < 1) return fail(SCNN_EINVAL, "channels must be positive");
+    if (channels > kMaxChannels) return fail(SCNN_ECAPACITY, "at most %d channels", kMaxChannels);
+    if (k < 0) return fail(SCNN_EINVAL, "k < 0");
+    if (topk_mode != SCNN_TOPK_ABS && topk_mode != SCNN_TOPK_SIGNED) return fail(SCNN_EINVAL, "bad topk_mode");
+    if (!nnz_out || !workspace) return fail(SCNN_EINVAL, "null pointer (nnz_out or workspace)");
+    if (rows > 0 && (!coords || !resp)) return fail(SCNN_EINVAL, "null input arrays");
+    if (out_capacity < 0 || out_capacity > kMaxIndex) return fail(SCNN_EINVAL, "bad out_capacity");
+    if (out_capacity > 0 && (!out_coords || !out_feats)) return fail(SCNN_EINVAL, "null output arrays");
+    if (((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "workspace must be 256-byte aligned");
+    TopkWs ws;
+    carve_topk(workspace, g, rows, channels, &ws);
+    if (ws.total > workspace_bytes)
+        return fail(SCNN_EWORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
+    SCNN_TRY(launch_rows_sample_bounds(g, coords, rows, ws.cand_start, ws.tile_start, ws.ctr, s));
+    SCNN_TRY(launch_rows_to_planar(g, coords, resp, channels, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
+                                   ws.cand_lin, ws.resp, s));
+    SCNN_TRY(launch_topk(g, channels, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.eqcnt, ws.ctr,
+                         ws.tiles_cap, s));
+    SCNN_TRY(launch_select_write(g, channels, topk_mode, 0, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
+                                 ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr, out_coords,
+                                 out_feats, out_capacity, &ws.ctr->n_rows, s));
+    SCNN_TRY(launch_finish(ws.ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
+    return SCNN_OK;
+}
+
+// ---------------------------------------------------------------- sparse_relu
+size_t sparse_relu_workspace(int64_t rows, int channels) {
+    if (rows < 0 || rows > kMaxIndex || channels < 1) return 0;
+    Carver c(nullptr);
+    c.take<Counters>(1);
+    c.take<unsigned>(rows > 0 ? rows : 1);
+    c.take<unsigned>(rows > 0 ? rows : 1);
+    c.take<unsigned>(scan_blocks(rows));
+    return c.total();
+}
+
+int sparse_relu(int ndim, const int32_t* coords, const float* feats, int64_t rows, int channels,
+                int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t* nnz_out, void* workspace,
+                size_t workspace_bytes, void* hip_stream) {
+    if (ndim != 2 && ndim != 3) return fail(SCNN_EINVAL, "ndim must be 2 or 3 (got %d)", ndim);
+    if (rows < 0 || rows > kMaxIndex) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (channels < 1) return fail(SCNN_EINVAL, "channels must be positive");
+    if (!nnz_out || !workspace) return fail(SCNN_EINVAL, "null pointer (nnz_out or workspace)");
+    if (rows > 0 && (!coords || !feats)) return fail(SCNN_EINVAL, "null input arrays");
+    if (out_capacity < 0 || out_capacity > kMaxIndex) return fail(SCNN_EINVAL, "bad out_capacity");
+    if (out_capacity > 0 && (!out_coords || !out_feats)) return fail(SCNN_EINVAL, "null output arrays");
+    if (((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "workspace must be 256-byte aligned");
+    Carver c(workspace);
+    Counters* ctr = c.take<Counters>(1);
+    const size_t zero_bytes = c.total();
+    unsigned* flags = c.take<unsigned>(rows > 0 ? rows : 1);
+    unsigned* offs = c.take<unsigned>(rows > 0 ? rows : 1);
+    unsigned* block_sums = c.take<unsigned>(scan_blocks(rows));
+    if (c.total() > workspace_bytes)
+        return fail(SCNN_EWORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, c.total());
+    Geom g;
+    memset(&g, 0, sizeof(g));
+    g.ndim = ndim;
+    hipStream_t s = (hipStream_t)hip_stream;
+    SCNN_TRY(launch_zero(workspace, zero_bytes, s));
+    SCNN_TRY(launch_relu(g, coords, feats, rows, channels, flags, offs, block_sums, out_coords, out_feats,
+                         out_capacity, ctr, s));
+    SCNN_TRY(launch_finish(ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
+    return SCNN_OK;
+}
+
+// ---------------------------------------------------------------- sparse_maxpool
+namespace {
+struct PoolWs {
+    Counters* ctr;
+    unsigned long long* occ;
+    unsigned long long* pbits;
+    size_t zero_bytes;
+    unsigned* occ_prefix;
+    unsigned* pprefix;
+    unsigned* block_sums;
+    long long* pool_key;
+    long long pool_cap;
+    size_t total;
+};
+void carve_pool(void* base, const Geom& g, const Geom& gp, long long rows, PoolWs* w) {
+    Carver c(base);
+    const long long nw = (long long)g.batch * g.Wps, nwp = (long long)gp.batch * gp.Wps;
+    const long long grid_p = (long long)gp.batch * gp.N;
+    w->pool_cap = rows < grid_p ? rows : grid_p;
+    if (w->pool_cap < 1) w->pool_cap = 1;
+    w->ctr = c.take<Counters>(1);
+    w->occ = c.take<unsigned long long>(nw);
+    w->pbits = c.take<unsigned long long>(nwp);
+    w->zero_bytes = c.total();
+    w->occ_prefix = c.take<unsigned>(nw);
+    w->pprefix = c.take<unsigned>(nwp);
+    w->block_sums = c.take<unsigned>(scan_blocks(nwp));
+    w->pool_key = c.take<long long>(w->pool_cap);
+    w->total = c.total();
+}
+}  // namespace
+
+size_t sparse_maxpool_workspace(int ndim, const int32_t* extent, int batch, int64_t rows, int channels) {
+    Geom g;
+    if (make_geom(ndim, extent, batch, nullptr, &g) != SCNN_OK) return 0;
+    if (rows < 0 || rows > kMaxIndex || channels < 1) return 0;
+    PoolWs w;
+    carve_pool(nullptr, g, pooled_geom(g), rows, &w);
+    return w.total;
+}
+
+int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const int32_t* coords, const float* feats,
+                   int64_t rows, int channels, int32_t* out_coords, float* out_feats, int64_t out_capacity,
+                   int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Geom g;
+    int rc = make_geom(ndim, extent, batch, nullptr, &g);
+    if (rc != SCNN_OK) return rc;
+    if (window != 2) return fail(SCNN_EINVAL, "only window = stride = 2 is implemented (got %d)", window);
+    if (rows < 0 || rows > kMaxIndex) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (channels < 1) return fail(SCNN_EINVAL, "channels must be positive");
+    if (!nnz_out || !workspace) return fail(SCNN_EINVAL, "null pointer (nnz_out or workspace)");
+    if (rows > 0 && (!coords || !feats)) return fail(SCNN_EINVAL, "null input arrays");
+    if (out_capacity < 0 || out_capacity > kMaxIndex) return fail(SCNN_EINVAL, "bad out_capacity");
+    if (out_capacity > 0 && (!out_coords || !out_feats)) return fail(SCNN_EINVAL, "null output arrays");
+    if (((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "workspace must be 256-byte aligned");
+    const Geom gp = pooled_geom(g);
+    PoolWs ws;
+    carve_pool(workspace, g, gp, rows, &ws);
+    if (ws.total > workspace_bytes)
+        return fail(SCNN_EWORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
+    SCNN_TRY(launch_maxpool(g, gp, coords, feats, rows, nullptr, rows, channels, 0, ws.occ, ws.occ_prefix, ws.pbits,
+                            ws.pprefix, ws.block_sums, ws.pool_key, ws.pool_cap, out_coords, out_feats, out_capacity,
+                            ws.ctr, s));
+    SCNN_TRY(launch_finish(ws.ctr, 1, rows, 0, out_capacity, (long long*)nnz_out, s));
+    return SCNN_OK;
+}
+
+// ---------------------------------------------------------------- validation
+int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Geom g;
+    int rc = make_geom(ndim, extent, batch, nullptr, &g);
+    if (rc != SCNN_OK) return rc;
+    if (rows < 0 || rows > kMaxIndex) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (rows == 0) return SCNN_OK;
+    if (!coords || !workspace) return fail(SCNN_EINVAL, "null pointer");
+    if (workspace_bytes < 256 || ((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "need 256 aligned bytes");
+    hipStream_t s = (hipStream_t)hip_stream;
+    Counters* ctr = (Counters*)workspace;
+    SCNN_TRY(launch_zero(workspace, 256, s));
+    SCNN_TRY(launch_validate(g, coords, rows, ctr, s));
+    Counters host;
+    SCNN_TRY(hipMemcpyAsync(&host, ctr, sizeof(host), hipMemcpyDeviceToHost, s));
+    SCNN_TRY(hipStreamSynchronize(s));
+    if (host.flags & SCNN_FLAG_BAD_COORD) return fail(SCNN_EINVAL, "a coordinate lies outside the grid");
+    if (host.flags & SCNN_FLAG_UNSORTED) return fail(SCNN_EUNSORTED, "rows are not strictly ascending by (b, lin)");
+    return SCNN_OK;
+}
+
+}  // extern "C"

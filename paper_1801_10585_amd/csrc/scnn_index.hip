@@ -1,0 +1,276 @@
+// Index build, candidate-site generation and the small device-wide scan.
+//
+// Step "decompress indices" of Algorithm 1 becomes: mark every occupied site in
+// a bitmap over (sample, lin) and remember, per 64-bit word, the row index of
+// its first occupied site.  Rows are sorted by (b, lin), so the row of any
+// occupied site is  prefix[word] + popcount(bits below it)  -- the inverse of
+// get_update_id without a hash table and without an r^d value buffer.
+//
+// Candidate output sites (the sites Algorithm 1's dense buffer could become
+// non-zero at) are the occupied sites dilated by the filter's non-zero taps;
+// they are marked in a second bitmap, counted per word, scanned, and written
+// out as a sorted list of per-sample site indices.
+#include "scnn_internal.h"
+
+namespace scnn {
+
+// ------------------------------------------------------------------ zero fill
+__global__ void k_zero(uint4* __restrict__ p, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t s) {
+    size_t n16 = (bytes + 15) / 16;
+    if (n16 == 0) return hipSuccess;
+    int blocks = (int)((n16 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_zero, dim3(blocks), dim3(256), 0, s, (uint4*)p, n16);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ scan
+__global__ __launch_bounds__(256) void k_scan_local(unsigned* __restrict__ vals, long long n_imm,
+                                                    const long long* __restrict__ n_dev,
+                                                    unsigned* __restrict__ block_sums) {
+    __shared__ unsigned s_wave[4];
+    const long long n = n_dev ? *n_dev : n_imm;
+    const long long base = (long long)blockIdx.x * kScanChunk + (long long)threadIdx.x * 8;
+    unsigned v[8];
+    unsigned sum = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        v[i] = (base + i < n) ? vals[base + i] : 0u;
+        sum += v[i];
+    }
+    unsigned total;
+    unsigned excl = block_exclusive_scan_256(sum, s_wave, total);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        if (base + i < n) vals[base + i] = excl;
+        excl += v[i];
+    }
+    if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(256) void k_scan_top(unsigned* __restrict__ block_sums, long long n_blocks,
+                                                  long long* __restrict__ total_out) {
+    __shared__ unsigned s_wave[4];
+    unsigned carry = 0;
+    for (long long start = 0; start < n_blocks; start += 256) {
+        long long i = start + threadIdx.x;
+        unsigned v = (i < n_blocks) ? block_sums[i] : 0u;
+        unsigned total;
+        unsigned excl = block_exclusive_scan_256(v, s_wave, total);
+        if (i < n_blocks) block_sums[i] = carry + excl;
+        carry += total;
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = (long long)carry;
+}
+
+__global__ __launch_bounds__(256) void k_scan_add(unsigned* __restrict__ vals, long long n_imm,
+                                                  const long long* __restrict__ n_dev,
+                                                  const unsigned* __restrict__ block_sums) {
+    const long long n = n_dev ? *n_dev : n_imm;
+    const long long base = (long long)blockIdx.x * kScanChunk + (long long)threadIdx.x * 8;
+    const unsigned add = block_sums[blockIdx.x];
+    if (add == 0) return;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (base + i < n) vals[base + i] += add;
+}
+
+hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n_imm, const long long* n_dev,
+                                 unsigned* block_sums, long long* total, hipStream_t s) {
+    long long blocks = (capacity + kScanChunk - 1) / kScanChunk;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_scan_local, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums);
+    hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(256), 0, s, block_sums, blocks, total);
+    hipLaunchKernelGGL(k_scan_add, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ index build
+// One thread per input row: set the row's bit; the first row of each word
+// records its own index as that word's prefix.  Rows outside the grid are
+// skipped and reported; a row not strictly above its predecessor is reported.
+__global__ __launch_bounds__(256) void k_index_build(Geom g, const int32_t* __restrict__ coords, long long n_imm,
+                                                     const long long* __restrict__ n_dev,
+                                                     unsigned long long* __restrict__ occ,
+                                                     unsigned* __restrict__ occ_prefix, Counters* ctr) {
+    const long long n = n_dev ? *n_dev : n_imm;
+    const int stride = 1 + g.ndim;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < n;
+         r += (long long)gridDim.x * blockDim.x) {
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        if (!site_in_grid(g, b, c0, c1, c2)) {
+            atomicOr(&ctr->flags, SCNN_FLAG_BAD_COORD);
+            continue;
+        }
+        const long long key = (long long)b * g.Npad + lin_of(g, c0, c1, c2);
+        long long prev_key = -1;
+        if (r > 0) {
+            int pb, p0, p1, p2;
+            load_site(g, coords + (r - 1) * stride, pb, p0, p1, p2);
+            if (site_in_grid(g, pb, p0, p1, p2)) prev_key = (long long)pb * g.Npad + lin_of(g, p0, p1, p2);
+        }
+        if (prev_key >= key) atomicOr(&ctr->flags, SCNN_FLAG_UNSORTED);
+        atomicOr(&occ[key >> 6], 1ull << (key & 63));
+        if ((prev_key >> 6) != (key >> 6)) occ_prefix[key >> 6] = (unsigned)r;
+    }
+}
+
+hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_imm, const long long* n_dev,
+                              long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
+                              hipStream_t s) {
+    long long blocks = (n_cap + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_index_build, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, n_imm, n_dev, occ,
+                       occ_prefix, ctr);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ filter preparation
+// One block per tap: widen the tap's [C_in, C_out] slice to fp64 in a layout whose
+// out-channel stride is padded to a multiple of 16, and record whether the tap
+// has any non-zero weight (pruned taps generate no candidate sites).
+__global__ __launch_bounds__(256) void k_filter_prep(const float* __restrict__ w, int c_in, int c_out, int c_out_pad,
+                                                     double* __restrict__ wp, int* __restrict__ tap_active) {
+    __shared__ int s_any;
+    const int t = blockIdx.x;
+    if (threadIdx.x == 0) s_any = 0;
+    __syncthreads();
+    int any = 0;
+    const int n = c_in * c_out_pad;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+        const int ic = i / c_out_pad, oc = i % c_out_pad;
+        float v = 0.0f;
+        if (oc < c_out) v = w[((size_t)t * c_in + ic) * c_out + oc];
+        wp[(size_t)t * n + i] = (double)v;
+        any |= (v != 0.0f);
+    }
+    if (any) s_any = 1;
+    __syncthreads();
+    if (threadIdx.x == 0) tap_active[t] = s_any;
+}
+
+hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
+                              int* tap_active, hipStream_t s) {
+    hipLaunchKernelGGL(k_filter_prep, dim3(g.T), dim3(256), 0, s, w, c_in, c_out, c_out_pad, wp, tap_active);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ candidate sites
+// One thread per (input row, tap): an input at q reaches p = q - delta.
+__global__ __launch_bounds__(256) void k_cand_mark(Geom g, const int32_t* __restrict__ coords, long long nnz,
+                                                   const int* __restrict__ tap_active,
+                                                   unsigned long long* __restrict__ cand) {
+    const long long total = nnz * g.T;
+    const int stride = 1 + g.ndim;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long r = i / g.T;
+        const int t = (int)(i - r * g.T);
+        if (!tap_active[t]) continue;
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        if (!site_in_grid(g, b, c0, c1, c2)) continue;
+        const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
+        const int p0 = c0 - (t0 - g.H[0]), p1 = c1 - (t1 - g.H[1]), p2 = c2 - (t2 - g.H[2]);
+        if (!site_in_grid(g, b, p0, p1, p2)) continue;
+        const long long key = (long long)b * g.Npad + lin_of(g, p0, p1, p2);
+        atomicOr(&cand[key >> 6], 1ull << (key & 63));
+    }
+}
+
+hipError_t launch_cand_mark(const Geom& g, const int32_t* coords, long long nnz, const int* tap_active,
+                            unsigned long long* cand, hipStream_t s) {
+    long long total = nnz * g.T;
+    long long blocks = (total + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_cand_mark, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, nnz, tap_active, cand);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void k_popcount(const unsigned long long* __restrict__ bits, long long n_words,
+                                                  unsigned* __restrict__ out) {
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n_words;
+         i += (long long)gridDim.x * blockDim.x)
+        out[i] = (unsigned)__popcll(bits[i]);
+}
+
+hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s) {
+    long long blocks = (n_words + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_popcount, dim3((unsigned)blocks), dim3(256), 0, s, bits, n_words, out);
+    return hipGetLastError();
+}
+
+// Per-sample candidate ranges and tile ranges.  Each sample's candidates are
+// padded to whole tiles so that a tile never spans two samples.
+__global__ __launch_bounds__(256) void k_sample_info(Geom g, const unsigned* __restrict__ cand_prefix,
+                                                     long long cand_cap, int* __restrict__ cand_start,
+                                                     int* __restrict__ tile_start, Counters* ctr) {
+    const long long n_cand = ctr->n_cand;  // written by the scan
+    const bool overflow = n_cand > cand_cap;
+    for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) {
+        int v = 0;
+        if (!overflow) v = (b == g.batch) ? (int)n_cand : (int)cand_prefix[(long long)b * g.Wps];
+        cand_start[b] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int b = 0; b < g.batch; ++b) {
+            tile_start[b] = acc;
+            acc += (cand_start[b + 1] - cand_start[b] + kTileRows - 1) / kTileRows;
+        }
+        tile_start[g.batch] = acc;
+        ctr->n_tiles = acc;
+        if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+    }
+}
+
+hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
+                              int* tile_start, Counters* ctr, hipStream_t s) {
+    hipLaunchKernelGGL(k_sample_info, dim3(1), dim3(256), 0, s, g, cand_prefix, cand_cap, cand_start, tile_start,
+                       ctr);
+    return hipGetLastError();
+}
+
+// One thread per bitmap word: write the per-sample site index of every set bit
+// at its rank.  The list comes out sorted by (b, lin).
+__global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long long* __restrict__ cand,
+                                                   const unsigned* __restrict__ cand_prefix, long long n_words,
+                                                   unsigned* __restrict__ cand_lin, long long cand_cap) {
+    for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
+         w += (long long)gridDim.x * blockDim.x) {
+        unsigned long long bits = cand[w];
+        if (!bits) continue;
+        long long o = cand_prefix[w];
+        const unsigned base = (unsigned)((w % g.Wps) * 64);
+        while (bits) {
+            const int bit = __ffsll((long long)bits) - 1;
+            bits &= bits - 1;
+            if (o < cand_cap) cand_lin[o] = base + (unsigned)bit;
+            ++o;
+        }
+    }
+}
+
+hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
+                            long long n_words, unsigned* cand_lin, long long cand_cap, hipStream_t s) {
+    long long blocks = (n_words + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)blocks), dim3(256), 0, s, g, cand, cand_prefix, n_words,
+                       cand_lin, cand_cap);
+    return hipGetLastError();
+}
+
+}  // namespace scnn

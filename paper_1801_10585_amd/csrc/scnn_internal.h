@@ -1,0 +1,218 @@
+// Internal declarations shared by the HIP translation units of libscnn.
+// gfx950 only: 64-wide wavefronts, 64-bit ballots, 64-bit occupancy words.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/scnn.h"
+
+namespace scnn {
+
+constexpr int kTileRows = 128;    // candidate sites per response tile
+constexpr int kHistBins = 2048;   // bins per radix-select pass (11-bit digits)
+constexpr int kScanChunk = 2048;  // elements per block in the device scan
+
+// Grid geometry, passed by value to kernels.
+struct Geom {
+    int ndim;
+    int batch;
+    int E[3];          // extent, unused axes = 1 (axis order: c_1 slowest .. c_ndim fastest)
+    int K[3];          // filter size per axis, unused = 1
+    int H[3];          // (K-1)/2
+    int T;             // taps = prod(K)
+    long long N;       // sites per sample
+    long long Npad;    // N rounded up to a multiple of 64
+    int Wps;           // 64-bit occupancy words per sample = Npad / 64
+};
+
+// One per (sample, channel) column of the response matrix.
+struct ColState {
+    unsigned prefix;    // radix prefix found so far (high bits of the threshold key)
+    unsigned tau;       // final threshold key
+    long long k_rem;    // entries still to take from the current bin
+    unsigned n_eq;      // entries whose key equals tau
+    unsigned q;         // how many of those survive (lowest lin first)
+    unsigned n_nz;      // non-zero entries in the column
+    int done;           // 1 = selection settled (bypass or k == 0), later passes skip the column
+    int need_tie;       // 1 = q < n_eq: ranks among equals decide
+};
+
+// Device-resident counters produced on the way.
+struct Counters {
+    long long n_cand;     // candidate sites
+    long long n_tiles;    // response tiles (each sample padded to a multiple of kTileRows)
+    long long n_rows;     // rows after selection / ReLU
+    long long n_pool;     // rows after pooling
+    unsigned flags;       // SCNN_FLAG_*
+    int any_tie;          // some column needs tie ranks
+    int pad[2];
+};
+
+__host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
+
+__device__ inline long long lin_of(const Geom& g, int c0, int c1, int c2) {
+    // unused leading axes have extent 1 and coordinate 0
+    return ((long long)c0 * g.E[1] + c1) * g.E[2] + c2;
+}
+
+__device__ inline void site_of(const Geom& g, long long lin, int& c0, int& c1, int& c2) {
+    c2 = (int)(lin % g.E[2]);
+    lin /= g.E[2];
+    c1 = (int)(lin % g.E[1]);
+    c0 = (int)(lin / g.E[1]);
+}
+
+// coords rows are (b, c_1..c_ndim); internally sites always use three axes with
+// the real axes right-aligned (2-D: axis 0 has extent 1).
+__device__ inline void load_site(const Geom& g, const int32_t* row, int& b, int& c0, int& c1, int& c2) {
+    b = row[0];
+    if (g.ndim == 3) {
+        c0 = row[1]; c1 = row[2]; c2 = row[3];
+    } else {
+        c0 = 0; c1 = row[1]; c2 = row[2];
+    }
+}
+
+__device__ inline void store_site(const Geom& g, int32_t* row, int b, int c0, int c1, int c2) {
+    row[0] = b;
+    if (g.ndim == 3) {
+        row[1] = c0; row[2] = c1; row[3] = c2;
+    } else {
+        row[1] = c1; row[2] = c2;
+    }
+}
+
+__device__ inline bool site_in_grid(const Geom& g, int b, int c0, int c1, int c2) {
+    return (unsigned)b < (unsigned)g.batch && (unsigned)c0 < (unsigned)g.E[0] && (unsigned)c1 < (unsigned)g.E[1] &&
+           (unsigned)c2 < (unsigned)g.E[2];
+}
+
+// Order-preserving key of a response: larger key = stronger response.
+// 0 is reserved for "not an entry".
+__device__ inline unsigned score_key(float v, int mode) {
+    unsigned u = __float_as_uint(v);
+    if ((u & 0x7fffffffu) == 0u) return 0u;
+    if (mode == SCNN_TOPK_ABS) return u & 0x7fffffffu;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// Locate the sample of a tile: tile_start[b] <= tile < tile_start[b+1].
+__device__ inline int sample_of_tile(const int* tile_start, int batch, int tile) {
+    int lo = 0, hi = batch - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (tile_start[mid] <= tile) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+// Row index of the occupied site (b, c0, c1, c2), or -1: the inverse of get_update_id.
+__device__ inline int lookup_row(const Geom& g, const unsigned long long* __restrict__ occ,
+                                 const unsigned* __restrict__ occ_prefix, long long nnz_in, int b, int c0, int c1,
+                                 int c2) {
+    if (!site_in_grid(g, b, c0, c1, c2)) return -1;
+    const long long key = (long long)b * g.Npad + lin_of(g, c0, c1, c2);
+    const unsigned long long word = occ[key >> 6];
+    const int bit = (int)(key & 63);
+    if (!((word >> bit) & 1ull)) return -1;
+    const long long row = (long long)occ_prefix[key >> 6] + __popcll(word & ((1ull << bit) - 1ull));
+    return row < nnz_in ? (int)row : -1;  // only an unsorted input can trip this guard
+}
+
+// Exclusive scan across a 256-thread block; `total` receives the block sum.
+// Contains __syncthreads(): every thread of the block must call it.
+__device__ inline unsigned block_exclusive_scan_256(unsigned v, unsigned* s_wave /*[4], shared*/, unsigned& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        unsigned t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    if (lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    unsigned base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        unsigned x = s_wave[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    total = tot;
+    __syncthreads();
+    return base + inc - v;
+}
+
+// ---- host-side launchers (one per kernel family), all asynchronous on `s` ----
+struct ScanBufs {
+    unsigned* block_sums;  // ceil(capacity / kScanChunk) + 1 entries
+};
+
+// fill `words` 32-bit words with zero
+hipError_t launch_zero(void* p, size_t bytes, hipStream_t s);
+
+// In-place exclusive scan of vals[0..n) (n read from *n_dev if n_dev != nullptr, else n_imm; n <= capacity).
+// total (if non-null) receives the sum as long long.
+hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n_imm, const long long* n_dev,
+                                 unsigned* block_sums, long long* total, hipStream_t s);
+
+}  // namespace scnn
+
+// ---------------------------------------------------------------------------
+// Launchers implemented in the individual .hip files.
+// A count that lives on the device is passed as (n_imm, n_dev): n_dev wins
+// when non-null.
+// ---------------------------------------------------------------------------
+namespace scnn {
+
+// scnn_index.hip
+hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_imm, const long long* n_dev,
+                              long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
+                              hipStream_t s);
+hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
+                              int* tap_active, hipStream_t s);
+hipError_t launch_cand_mark(const Geom& g, const int32_t* coords, long long nnz, const int* tap_active,
+                            unsigned long long* cand, hipStream_t s);
+hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
+hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
+                              int* tile_start, Counters* ctr, hipStream_t s);
+hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
+                            long long n_words, unsigned* cand_lin, long long cand_cap, hipStream_t s);
+
+// scnn_conv.hip
+hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                            long long nnz_in, const float* feats, int c_in, const double* wp, int c_out,
+                            int c_out_pad, const float* bias, const int* tap_active, const unsigned* cand_lin,
+                            const int* cand_start, const int* tile_start, const Counters* ctr, float* resp,
+                            hipStream_t s);
+
+// scnn_topk.hip
+hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,
+                                     int* tile_start, Counters* ctr, hipStream_t s);
+hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const float* feats, int channels,
+                                 const int* cand_start, const int* tile_start, const Counters* ctr,
+                                 long long tiles_cap, unsigned* cand_lin, float* resp, hipStream_t s);
+hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
+                       const float* resp, ColState* cols, unsigned* hist, unsigned* eqcnt, Counters* ctr,
+                       long long tiles_cap, hipStream_t s);
+hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,
+                               const int* tile_start, const unsigned* cand_lin, const float* resp,
+                               const ColState* cols, const unsigned* eqcnt, unsigned* tile_rows,
+                               unsigned* scan_block_sums, long long tiles_cap, Counters* ctr, int32_t* out_coords,
+                               float* out_feats, long long out_capacity, long long* n_rows_out, hipStream_t s);
+
+// scnn_rows.hip
+hipError_t launch_relu(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
+                       unsigned* flags, unsigned* offs, unsigned* scan_block_sums, int32_t* out_coords, float* out_feats,
+                       long long out_capacity, Counters* ctr, hipStream_t s);
+hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, const float* feats,
+                          long long n_imm, const long long* n_dev, long long n_cap, int channels,
+                          int rows_have_entries, unsigned long long* occ, unsigned* occ_prefix, unsigned long long* pbits,
+                          unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
+                          int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
+                          hipStream_t s);
+hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows, Counters* ctr, hipStream_t s);
+hipError_t launch_finish(const Counters* ctr, int which_rows /*0 n_rows, 1 n_pool*/, long long aux_imm,
+                         int aux_is_cand, long long out_capacity, long long* nnz_out, hipStream_t s);
+
+}  // namespace scnn

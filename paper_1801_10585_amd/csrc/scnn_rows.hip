@@ -1,0 +1,214 @@
+// Row-list operators: sparse ReLU, sparse max-pooling (Sec. 3.3), validation.
+//
+// Pooling in the paper is: rewrite keys (divide the spatial index by the
+// stride), sort, reduce each cluster.  Here the sort is replaced by a bitmap
+// over the pooled grid: marking every row's pooled site and prefix-counting the
+// bitmap yields the output rows already in ascending (b, lin) order; each
+// output site then gathers its 2^d children through the occupancy index of the
+// input rows and takes the maximum over the entries that are present.  No
+// atomics on values, so the result does not depend on scheduling.
+#include "scnn_internal.h"
+
+namespace scnn {
+
+// ------------------------------------------------------------------ ReLU
+__global__ __launch_bounds__(256) void k_relu_flag(const float* __restrict__ feats, long long rows, int channels,
+                                                   unsigned* __restrict__ flags, unsigned* __restrict__ offs) {
+    // 16 lanes per row
+    const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int sub = threadIdx.x & 15;
+    const int lane = threadIdx.x & 63;
+    for (long long r0 = gid >> 4; r0 < round_up(rows, 16); r0 += ((long long)gridDim.x * blockDim.x) >> 4) {
+        bool any = false;
+        if (r0 < rows)
+            for (int c = sub; c < channels; c += 16) any |= feats[r0 * channels + c] > 0.0f;
+        const unsigned long long m = __ballot(any);
+        const unsigned seg = (unsigned)((m >> (lane & ~15)) & 0xffffull);
+        if (sub == 0 && r0 < rows) {
+            flags[r0] = seg ? 1u : 0u;
+            offs[r0] = seg ? 1u : 0u;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_relu_write(Geom g, const int32_t* __restrict__ coords,
+                                                    const float* __restrict__ feats, long long rows, int channels,
+                                                    const unsigned* __restrict__ flags,
+                                                    const unsigned* __restrict__ offs,
+                                                    int32_t* __restrict__ out_coords, float* __restrict__ out_feats,
+                                                    long long out_capacity) {
+    const long long total = rows * channels;
+    const int stride = 1 + g.ndim;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long r = i / channels;
+        const int c = (int)(i - r * channels);
+        if (!flags[r]) continue;
+        const long long o = offs[r];
+        if (o >= out_capacity) continue;
+        const float v = feats[i];
+        out_feats[o * channels + c] = v > 0.0f ? v : 0.0f;
+        if (c == 0)
+            for (int j = 0; j < stride; ++j) out_coords[o * stride + j] = coords[r * stride + j];
+    }
+}
+
+hipError_t launch_relu(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
+                       unsigned* flags, unsigned* offs, unsigned* scan_block_sums, int32_t* out_coords,
+                       float* out_feats, long long out_capacity, Counters* ctr, hipStream_t s) {
+    long long blocks = (rows * 16 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_relu_flag, dim3((unsigned)blocks), dim3(256), 0, s, feats, rows, channels, flags, offs);
+    hipError_t e = launch_exclusive_scan(offs, rows, rows, nullptr, scan_block_sums, &ctr->n_rows, s);
+    if (e != hipSuccess) return e;
+    blocks = (rows * channels + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_relu_write, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, feats, rows, channels,
+                       flags, offs, out_coords, out_feats, out_capacity);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ max-pooling
+// rows_have_entries != 0: the caller guarantees that every row holds a non-zero entry (skip the check).
+__global__ __launch_bounds__(256) void k_pool_mark(Geom g, Geom gp, const int32_t* __restrict__ coords,
+                                                   const float* __restrict__ feats, int channels,
+                                                   int rows_have_entries, long long n_imm,
+                                                   const long long* __restrict__ n_dev,
+                                                   unsigned long long* __restrict__ pbits) {
+    const long long n = n_dev ? *n_dev : n_imm;
+    const int stride = 1 + g.ndim;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < n;
+         r += (long long)gridDim.x * blockDim.x) {
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        if (!site_in_grid(g, b, c0, c1, c2)) continue;
+        if (!rows_have_entries) {  // a row of zeros holds no entry and creates no output site
+            bool any = false;
+            for (int c = 0; c < channels; ++c) any |= feats[r * channels + c] != 0.0f;
+            if (!any) continue;
+        }
+        const long long key = (long long)b * gp.Npad + lin_of(gp, c0 >> 1, c1 >> 1, c2 >> 1);
+        atomicOr(&pbits[key >> 6], 1ull << (key & 63));
+    }
+}
+
+__global__ __launch_bounds__(256) void k_pool_emit(const unsigned long long* __restrict__ pbits,
+                                                   const unsigned* __restrict__ pprefix, long long n_words,
+                                                   long long* __restrict__ pool_key, long long pool_cap) {
+    for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
+         w += (long long)gridDim.x * blockDim.x) {
+        unsigned long long bits = pbits[w];
+        long long o = pprefix[w];
+        while (bits) {
+            const int bit = __ffsll((long long)bits) - 1;
+            bits &= bits - 1;
+            if (o < pool_cap) pool_key[o] = w * 64 + bit;
+            ++o;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void k_pool_gather(Geom g, Geom gp, const unsigned long long* __restrict__ occ,
+                                                     const unsigned* __restrict__ occ_prefix, long long n_imm,
+                                                     const long long* __restrict__ n_dev,
+                                                     const float* __restrict__ feats, int channels,
+                                                     const long long* __restrict__ pool_key, long long pool_cap,
+                                                     const Counters* __restrict__ ctr,
+                                                     int32_t* __restrict__ out_coords, float* __restrict__ out_feats,
+                                                     long long out_capacity) {
+    const long long n_in = n_dev ? *n_dev : n_imm;
+    long long n_out = ctr->n_pool;
+    if (n_out > pool_cap) n_out = pool_cap;
+    if (n_out > out_capacity) n_out = out_capacity;
+    const long long total = n_out * channels;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long o = i / channels;
+        const int c = (int)(i - o * channels);
+        const long long key = pool_key[o];
+        const int b = (int)(key / gp.Npad);
+        int p0, p1, p2;
+        site_of(gp, key - (long long)b * gp.Npad, p0, p1, p2);
+        bool present = false;
+        float best = 0.0f;
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int row = lookup_row(g, occ, occ_prefix, n_in, b, 2 * p0 + (d >> 2), 2 * p1 + ((d >> 1) & 1),
+                                       2 * p2 + (d & 1));
+            if (row < 0) continue;
+            const float v = feats[(size_t)row * channels + c];
+            if (v == 0.0f) continue;
+            best = present ? fmaxf(best, v) : v;
+            present = true;
+        }
+        out_feats[i] = present ? best : 0.0f;
+        if (c == 0) store_site(gp, out_coords + o * (1 + gp.ndim), b, p0, p1, p2);
+    }
+}
+
+hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, const float* feats,
+                          long long n_imm, const long long* n_dev, long long n_cap, int channels,
+                          int rows_have_entries, unsigned long long* occ, unsigned* occ_prefix, unsigned long long* pbits,
+                          unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
+                          int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
+                          hipStream_t s) {
+    // occ / pbits must be zero on entry
+    hipError_t e = launch_index_build(g, coords, n_imm, n_dev, n_cap, occ, occ_prefix, ctr, s);
+    if (e != hipSuccess) return e;
+    long long blocks = (n_cap + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_pool_mark, dim3((unsigned)blocks), dim3(256), 0, s, g, gp, coords, feats, channels,
+                       rows_have_entries, n_imm, n_dev, pbits);
+    const long long n_words = (long long)gp.batch * gp.Wps;
+    e = launch_popcount(pbits, n_words, pprefix, s);
+    if (e != hipSuccess) return e;
+    e = launch_exclusive_scan(pprefix, n_words, n_words, nullptr, scan_block_sums, &ctr->n_pool, s);
+    if (e != hipSuccess) return e;
+    blocks = (n_words + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_pool_emit, dim3((unsigned)blocks), dim3(256), 0, s, pbits, pprefix, n_words, pool_key,
+                       pool_cap);
+    blocks = (pool_cap * channels + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(k_pool_gather, dim3((unsigned)blocks), dim3(256), 0, s, g, gp, occ, occ_prefix, n_imm, n_dev,
+                       feats, channels, pool_key, pool_cap, ctr, out_coords, out_feats, out_capacity);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ validation
+__global__ __launch_bounds__(256) void k_validate(Geom g, const int32_t* __restrict__ coords, long long rows,
+                                                  Counters* ctr) {
+    const int stride = 1 + g.ndim;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < rows;
+         r += (long long)gridDim.x * blockDim.x) {
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        if (!site_in_grid(g, b, c0, c1, c2)) {
+            atomicOr(&ctr->flags, SCNN_FLAG_BAD_COORD);
+            continue;
+        }
+        if (r > 0) {
+            int pb, p0, p1, p2;
+            load_site(g, coords + (r - 1) * stride, pb, p0, p1, p2);
+            if (site_in_grid(g, pb, p0, p1, p2)) {
+                const long long key = (long long)b * g.Npad + lin_of(g, c0, c1, c2);
+                const long long prev = (long long)pb * g.Npad + lin_of(g, p0, p1, p2);
+                if (prev >= key) atomicOr(&ctr->flags, SCNN_FLAG_UNSORTED);
+            }
+        }
+    }
+}
+
+hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows, Counters* ctr, hipStream_t s) {
+    long long blocks = (rows + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_validate, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, rows, ctr);
+    return hipGetLastError();
+}
+
+}  // namespace scnn

@@ -1,0 +1,339 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_1801_10585_amd as scnn
+from tests.parity import assert_rows_well_formed, check_column, column, lin_index
+from workloads import make_config, make_filter, random_sparse_sites
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+def gpu_conv(extent, batch, coords, feats, ksize, w, bias=None, **kw):
+    c, f, n = scnn.sparse_conv_fwd(extent, batch, dev(coords), dev(feats), ksize, dev(w),
+                                   None if bias is None else dev(bias), **kw)
+    return host(c), host(f), n
+
+
+def check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, rho_up, mode, columns=None, tag=""):
+    """Band-rule comparison of the un-fused layer on all (or sampled) columns, then exact checks that the
+    fused ReLU / pooling outputs equal the oracle's ReLU / pooling applied to the HIP path's own output."""
+    c_out = w.shape[2]
+    gc, gf, n = gpu_conv(extent, batch, coords, feats, ksize, w, bias, rho_up=rho_up, topk_mode=mode)
+    assert int(n[2]) == 0, f"{tag}: status flags {int(n[2])}"
+    assert_rows_well_formed(gc, gf, extent, batch)
+    if columns is None:
+        columns = [(b, oc) for b in range(batch) for oc in range(c_out)]
+    band_total = 0
+    for (b, oc) in columns:
+        sel = coords[:, 0] == b
+        cb = coords[sel].copy()
+        cb[:, 0] = 0
+        rc, rf = oracle.sparse_conv_fwd(extent, 1, cb, feats[sel], ksize, w[:, :, oc:oc + 1],
+                                        None if bias is None else bias[oc:oc + 1], resp_only=True)
+        all_lin, all_val = lin_index(rc, extent), rf[:, 0]
+        got_lin, got_val = column(gc, gf, extent, b, oc)
+        band_total += check_column(all_lin, all_val, got_lin, got_val, k, mode, where=f"{tag} (b={b}, oc={oc})")
+        assert len(got_lin) <= k
+    # fused variants: exact against the oracle's operators applied to the HIP result
+    rcg, rfg, _ = gpu_conv(extent, batch, coords, feats, ksize, w, bias, rho_up=rho_up, topk_mode=mode, relu=True)
+    rco, rfo = oracle.sparse_relu(extent, gc, gf)
+    assert np.array_equal(rcg, rco) and np.array_equal(rfg, rfo), f"{tag}: fused ReLU differs"
+    pcg, pfg, _ = gpu_conv(extent, batch, coords, feats, ksize, w, bias, rho_up=rho_up, topk_mode=mode, relu=True,
+                           pool=True)
+    pco, pfo = oracle.sparse_maxpool(extent, rco, rfo)
+    assert np.array_equal(pcg, pco) and np.array_equal(pfg, pfo), f"{tag}: fused ReLU+pool differs"
+    pcg, pfg, _ = gpu_conv(extent, batch, coords, feats, ksize, w, bias, rho_up=rho_up, topk_mode=mode, pool=True)
+    pco, pfo = oracle.sparse_maxpool(extent, gc, gf)
+    assert np.array_equal(pcg, pco) and np.array_equal(pfg, pfo), f"{tag}: fused pool differs"
+    return gc, gf, band_total
+
+
+# ------------------------------------------------------------------ standalone operators: bit-exact
+def _random_rows(rng, extent, batch, density, channels, levels=None, fill=0.7):
+    coords = random_sparse_sites(rng, extent, batch, density)
+    if levels:
+        feats = rng.integers(-levels, levels + 1, size=(coords.shape[0], channels)).astype(np.float32) * 0.25
+    else:
+        feats = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    feats *= rng.random(feats.shape) < fill
+    return coords, np.ascontiguousarray(feats.astype(np.float32))
+
+
+@pytest.mark.parametrize("extent,batch,channels,density", [
+    ((9, 11), 1, 1, 0.5), ((16, 16), 3, 5, 0.4), ((12, 10, 9), 2, 64, 0.3), ((20, 20, 20), 4, 70, 0.12),
+    ((33, 17, 5), 2, 130, 0.2), ((40, 40, 40), 2, 16, 0.1)])
+@pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
+def test_attention_topk_bit_exact_with_heavy_ties(extent, batch, channels, density, mode):
+    rng = np.random.default_rng(abs(hash((extent, batch, channels, mode))) % 2 ** 32)
+    for levels in (2, 40, None):  # few distinct values -> long runs of equal scores at the threshold
+        coords, resp = _random_rows(rng, extent, batch, density, channels, levels)
+        n_per = max(1, coords.shape[0] // batch)
+        for k in (0, 1, n_per // 7 + 1, n_per // 2, n_per, 10 ** 9):
+            say(f"attention_topk extent={extent} B={batch} C={channels} mode={mode} levels={levels} k={k}")
+            gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+            oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+            assert int(n[2]) == 0
+            assert np.array_equal(host(gc), oc_), (k, levels)
+            assert np.array_equal(host(gf), of_), (k, levels)
+
+
+def test_attention_topk_empty_and_single_sample_cases():
+    extent, batch = (8, 8, 8), 3
+    coords = np.zeros((0, 4), np.int32)
+    resp = np.zeros((0, 4), np.float32)
+    gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), 5)
+    assert gc.shape[0] == 0 and int(n[0]) == 0
+    # only the middle sample populated
+    rng = np.random.default_rng(1)
+    coords, resp = _random_rows(rng, extent, 1, 0.4, 4, 3)
+    coords[:, 0] = 1
+    gc, gf, _ = scnn.attention_topk(extent, batch, dev(coords), dev(resp), 9)
+    oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, 9)
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+
+
+@pytest.mark.parametrize("extent,batch,channels", [((8, 6), 2, 3), ((7, 5), 1, 1), ((6, 4, 8), 2, 17), ((5, 7, 3), 3, 64),
+                                                   ((31, 33, 29), 2, 40)])
+def test_relu_and_maxpool_bit_exact(extent, batch, channels):
+    rng = np.random.default_rng(sum(extent) + channels)
+    coords, feats = _random_rows(rng, extent, batch, 0.3, channels)
+    say(f"relu/maxpool extent={extent} B={batch} C={channels} rows={coords.shape[0]}")
+    gc, gf, n = scnn.sparse_relu(len(extent), dev(coords), dev(feats))
+    oc_, of_ = oracle.sparse_relu(extent, coords, feats)
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+    gc, gf, n = scnn.sparse_maxpool(extent, batch, dev(coords), dev(feats))
+    oc_, of_ = oracle.sparse_maxpool(extent, coords, feats)
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+    # all-negative clusters keep their (negative) maximum
+    neg = -np.abs(feats) - (feats == 0)
+    gc, gf, n = scnn.sparse_maxpool(extent, batch, dev(coords), dev(neg.astype(np.float32)))
+    oc_, of_ = oracle.sparse_maxpool(extent, coords, neg.astype(np.float32))
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+
+
+def test_relu_and_pool_on_empty_input():
+    c = np.zeros((0, 3), np.int32)
+    f = np.zeros((0, 2), np.float32)
+    gc, gf, n = scnn.sparse_relu(2, dev(c), dev(f))
+    assert gc.shape[0] == 0
+    gc, gf, n = scnn.sparse_maxpool((4, 4), 1, dev(c), dev(f))
+    assert gc.shape[0] == 0
+
+
+# ------------------------------------------------------------------ the layer on small random cases (all columns)
+SMALL = [
+    # extent, batch, c_in, c_out, ksize, density, filter density
+    ((12, 13), 2, 1, 3, (3, 3), 0.3, 0.6),
+    ((28, 28), 1, 1, 8, (3, 3), 0.2, 0.5),
+    ((9, 10, 11), 2, 2, 5, (3, 3, 3), 0.15, 0.5),
+    ((16, 16, 16), 3, 4, 24, (3, 3, 3), 0.1, 0.5),
+    ((20, 9, 14), 1, 3, 40, (5, 1, 3), 0.1, 0.7),
+    ((14, 14, 14), 2, 8, 70, (3, 3, 3), 0.08, 1.0),
+    ((10, 10, 10), 1, 33, 17, (1, 1, 1), 0.3, 0.9),
+    ((24, 24, 24), 2, 16, 32, (5, 5, 5), 0.03, 0.3),
+]
+
+
+@pytest.mark.parametrize("case", SMALL)
+@pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
+def test_layer_small_cases_all_columns(case, mode):
+    extent, batch, c_in, c_out, ksize, density, fdens = case
+    rng = np.random.default_rng(abs(hash((case, mode))) % 2 ** 32)
+    coords = random_sparse_sites(rng, extent, batch, density)
+    feats = rng.normal(size=(coords.shape[0], c_in)).astype(np.float32)
+    feats *= rng.random(feats.shape) < 0.85
+    feats = np.ascontiguousarray(feats.astype(np.float32))
+    w = make_filter(rng, ksize, c_in, c_out, fdens, 0.4)
+    bias = rng.normal(size=c_out).astype(np.float32) if rng.random() < 0.5 else None
+    n = int(np.prod(extent))
+    for rho in (0.02, 0.2, 1.0):
+        k = scnn.k_from_rho(rho, n)
+        say(f"layer small extent={extent} B={batch} {c_in}->{c_out} ks={ksize} mode={mode} rho={rho} k={k}")
+        check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, rho, mode, tag=f"small {case}")
+
+
+def test_layer_exact_ties_integer_data():
+    """Dyadic inputs and weights: fp32 sums are exact on both sides, so the outputs must be bit-identical,
+    including the choice among equal scores at the threshold (lower lin wins)."""
+    rng = np.random.default_rng(99)
+    extent, batch, c_in, c_out, ksize = (18, 18, 18), 2, 2, 6, (3, 3, 3)
+    coords = random_sparse_sites(rng, extent, batch, 0.12)
+    feats = (rng.integers(1, 3, size=(coords.shape[0], c_in)) * 0.5).astype(np.float32)
+    w = (rng.integers(-2, 3, size=(27, c_in, c_out)) * 0.25).astype(np.float32)
+    n = int(np.prod(extent))
+    for mode in (scnn.ABS, scnn.SIGNED):
+        for rho in (0.01, 0.05, 0.2):
+            k = scnn.k_from_rho(rho, n)
+            say(f"layer ties mode={mode} rho={rho} k={k}")
+            for relu, pool in ((False, False), (True, False), (True, True)):
+                gc, gf, _ = gpu_conv(extent, batch, coords, feats, ksize, w, rho_up=rho, topk_mode=mode, relu=relu,
+                                     pool=pool)
+                oc_, of_ = oracle.sparse_conv_fwd(extent, batch, coords, feats, ksize, w, k=k, topk_mode=mode,
+                                                  relu=relu, pool=pool)
+                assert np.array_equal(gc, oc_) and np.array_equal(gf, of_), (mode, rho, relu, pool)
+
+
+# ------------------------------------------------------------------ the five configurations
+def test_config1_strokes_2d():
+    wl = make_config(1)
+    L = wl.layers[0]
+    k = scnn.k_from_rho(L.rho_up, 28 * 28)
+    say(f"cfg1 rows={wl.coords.shape[0]} k={k}")
+    check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k, L.rho_up,
+                              scnn.ABS, tag="cfg1")
+    gc, gf, _ = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=L.rho_up, relu=True,
+                         pool=True)
+    assert gc[:, 1:].max() < 14
+
+
+def test_config2_shells_unit_values_with_ties():
+    wl = make_config(2)
+    L = wl.layers[0]
+    k = scnn.k_from_rho(L.rho_up, 32 ** 3)
+    say(f"cfg2 rows={wl.coords.shape[0]} k={k}")
+    _, _, band = check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k,
+                                           L.rho_up, scnn.ABS, tag="cfg2")
+    say(f"cfg2 band entries: {band}")
+
+
+def _sampled_columns(rng, batch, c_out, count):
+    cols = {(0, 0), (batch - 1, c_out - 1)}
+    while len(cols) < min(count, batch * c_out):
+        cols.add((int(rng.integers(batch)), int(rng.integers(c_out))))
+    return sorted(cols)
+
+
+def test_config3_two_layers_full_size():
+    wl = make_config(3)
+    L1, L2 = wl.layers
+    rng = np.random.default_rng(3)
+    k1 = scnn.k_from_rho(L1.rho_up, 64 ** 3)
+    say(f"cfg3 layer 1 rows={wl.coords.shape[0]} k={k1}")
+    check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L1.ksize, wl.filters[0], None, k1, L1.rho_up,
+                              scnn.ABS, columns=_sampled_columns(rng, wl.batch, L1.c_out, 12), tag="cfg3-L1")
+    c1, f1, _ = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L1.ksize, wl.filters[0], rho_up=L1.rho_up,
+                         relu=True, pool=True)
+    ext2 = (32, 32, 32)
+    k2 = scnn.k_from_rho(L2.rho_up, 32 ** 3)
+    say(f"cfg3 layer 2 rows={c1.shape[0]} k={k2}")
+    check_conv_against_oracle(ext2, wl.batch, c1, f1, L2.ksize, wl.filters[1], None, k2, L2.rho_up, scnn.ABS,
+                              columns=_sampled_columns(rng, wl.batch, L2.c_out, 12), tag="cfg3-L2")
+
+
+def test_config4_r128_dense_filter_full_size_sampled_columns():
+    wl = make_config(4)
+    L = wl.layers[0]
+    rng = np.random.default_rng(4)
+    k = scnn.k_from_rho(L.rho_up, 128 ** 3)
+    say(f"cfg4 rows={wl.coords.shape[0]} k={k}")
+    gc, gf, band = check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k,
+                                             L.rho_up, scnn.ABS, columns=_sampled_columns(rng, wl.batch, L.c_out, 10),
+                                             tag="cfg4")
+    say(f"cfg4 out rows={gc.shape[0]} band entries={band}")
+    for b in range(wl.batch):
+        assert ((gf[gc[:, 0] == b] != 0).sum(axis=0) <= k).all()
+
+
+@pytest.mark.parametrize("rho", [0.02, 0.05, 0.10])
+def test_config5_r256_5x5x5_full_size_sampled_columns(rho):
+    wl = make_config(5)
+    L = wl.layers[0]
+    rng = np.random.default_rng(5)
+    k = scnn.k_from_rho(rho, 256 ** 3)
+    say(f"cfg5 rows={wl.coords.shape[0]} rho={rho} k={k}")
+    gc, gf, n = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=rho)
+    assert int(n[2]) == 0
+    assert_rows_well_formed(gc, gf, wl.extent, wl.batch)
+    assert ((gf != 0).sum(axis=0) <= k).all()
+    for (b, oc) in _sampled_columns(rng, 1, L.c_out, 3):
+        rc, rf = oracle.sparse_conv_fwd(wl.extent, 1, wl.coords, wl.feats, L.ksize, wl.filters[0][:, :, oc:oc + 1],
+                                        resp_only=True)
+        got_lin, got_val = column(gc, gf, wl.extent, b, oc)
+        band = check_column(lin_index(rc, wl.extent), rf[:, 0], got_lin, got_val, k, scnn.ABS,
+                            where=f"cfg5 rho={rho} oc={oc}")
+        say(f"cfg5 rho={rho} oc={oc} kept={len(got_lin)} band={band}")
+
+
+# ------------------------------------------------------------------ edge cases and error reporting
+def test_empty_input_and_zero_k():
+    extent = (8, 8, 8)
+    w = np.ones((27, 2, 3), np.float32)
+    gc, gf, n = gpu_conv(extent, 2, np.zeros((0, 4), np.int32), np.zeros((0, 2), np.float32), (3, 3, 3), w, rho_up=0.5)
+    assert gc.shape[0] == 0 and int(n[0]) == 0 and int(n[2]) == 0
+    rng = np.random.default_rng(0)
+    coords = random_sparse_sites(rng, extent, 2, 0.2)
+    feats = rng.normal(size=(coords.shape[0], 2)).astype(np.float32)
+    gc, gf, n = gpu_conv(extent, 2, coords, feats, (3, 3, 3), w, rho_up=0.0)
+    assert gc.shape[0] == 0 and int(n[1]) > 0
+    # all-zero filter: no candidate sites at all
+    gc, gf, n = gpu_conv(extent, 2, coords, feats, (3, 3, 3), np.zeros_like(w), rho_up=0.5)
+    assert gc.shape[0] == 0 and int(n[1]) == 0
+
+
+def test_capacity_flags_and_validation():
+    extent = (10, 10, 10)
+    rng = np.random.default_rng(2)
+    coords = random_sparse_sites(rng, extent, 1, 0.2)
+    feats = rng.normal(size=(coords.shape[0], 2)).astype(np.float32)
+    w = rng.normal(size=(27, 2, 3)).astype(np.float32)
+    full_c, full_f, n = gpu_conv(extent, 1, coords, feats, (3, 3, 3), w, rho_up=1.0)
+    rows, n_cand = int(n[0]), int(n[1])
+    # output truncated: true count still reported, prefix intact, flag set
+    c, f, nn = scnn.sparse_conv_fwd(extent, 1, dev(coords), dev(feats), (3, 3, 3), dev(w), rho_up=1.0,
+                                    out_capacity=rows // 2, sync=False)
+    nn = nn.cpu()
+    assert int(nn[0]) == rows and int(nn[2]) & scnn.FLAG_OUT_OVERFLOW
+    assert np.array_equal(host(c)[: rows // 2], full_c[: rows // 2])
+    assert np.array_equal(host(f)[: rows // 2], full_f[: rows // 2])
+    # candidate capacity too small: flagged, empty output
+    c, f, nn = scnn.sparse_conv_fwd(extent, 1, dev(coords), dev(feats), (3, 3, 3), dev(w), rho_up=1.0,
+                                    cand_capacity=n_cand // 2, sync=False)
+    nn = nn.cpu()
+    assert int(nn[2]) & scnn.FLAG_CAND_OVERFLOW and int(nn[0]) == 0 and int(nn[1]) == n_cand
+    # exactly enough capacity works
+    c, f, nn = gpu_conv(extent, 1, coords, feats, (3, 3, 3), w, rho_up=1.0, cand_capacity=n_cand)
+    assert np.array_equal(c, full_c) and np.array_equal(f, full_f)
+    # validation entry point
+    scnn.validate_rows(extent, 1, dev(coords))
+    bad = coords[::-1].copy()
+    with pytest.raises(scnn.ScnnError) as e:
+        scnn.validate_rows(extent, 1, dev(bad))
+    assert e.value.code == -4
+    oob = coords.copy()
+    oob[3, 2] = 10
+    with pytest.raises(scnn.ScnnError) as e:
+        scnn.validate_rows(extent, 1, dev(oob))
+    assert e.value.code == -1
+    # an out-of-grid row is skipped and reported, never dereferenced
+    c, f, nn = scnn.sparse_conv_fwd(extent, 1, dev(oob), dev(feats), (3, 3, 3), dev(w), rho_up=1.0, sync=False)
+    assert int(nn.cpu()[2]) & scnn.FLAG_BAD_COORD
+
+
+def test_runs_on_a_side_stream_and_is_repeatable():
+    wl = make_config(2, r=24, batch=3)
+    L = wl.layers[0]
+    a = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=L.rho_up, relu=True)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        b = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=L.rho_up, relu=True)
+    s.synchronize()
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
