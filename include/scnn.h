@@ -143,6 +143,13 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
 int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Kernel choice for the convolution step of sparse_conv_fwd, process-wide:
+ * 0 = by shape (matrix-core kernel when C_in is a multiple of 32 up to 128 and
+ * C_out a multiple of 16 up to 64, else the vector kernel), 1 = always the
+ * vector kernel.  Both compute the same sums to the same rounding rule; the
+ * switch exists so that tests and measurements can reach either. */
+int scnn_set_conv_path(int path);
+
 /* Measurement support (not part of the method): when enabled on the calling
  * thread, every sparse_conv_fwd call records HIP events on its stream at the
  * boundaries of its stages (index build, candidate sites, convolution,

@@ -19,6 +19,7 @@ from .binding import (  # noqa: F401
     profile_collect,
     profile_enable,
     load_library,
+    set_conv_path,
     sparse_conv_fwd,
     sparse_conv_fwd_max_rows,
     sparse_conv_fwd_workspace,

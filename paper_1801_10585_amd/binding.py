@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "scnn_last_error", "scnn_version", "scnn_k_from_rho", "sparse_conv_fwd_max_rows", "sparse_conv_fwd_workspace",
     "sparse_conv_fwd", "attention_topk_workspace", "attention_topk", "sparse_relu_workspace", "sparse_relu",
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
-    "scnn_profile_stage_count", "scnn_profile_stage_name", "scnn_profile_collect",
+    "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_profile_stage_name", "scnn_profile_collect",
 ]
 
 
@@ -71,6 +71,8 @@ def load_library():
     L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
     L.scnn_validate_rows.restype = ci
     L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
+    L.scnn_set_conv_path.restype = ci
+    L.scnn_set_conv_path.argtypes = [ci]
     L.scnn_profile_enable.restype = ci
     L.scnn_profile_enable.argtypes = [ci]
     L.scnn_profile_stage_count.restype = ci
@@ -286,3 +288,9 @@ def profile_collect():
     calls = ctypes.c_int64(0)
     _check(L, L.scnn_profile_collect(ms, ctypes.byref(calls)))
     return {L.scnn_profile_stage_name(i).decode(): float(ms[i]) for i in range(n)}, int(calls.value)
+
+
+def set_conv_path(path: int) -> None:
+    """0 = choose the convolution kernel by shape, 1 = always the vector kernel."""
+    L = load_library()
+    _check(L, L.scnn_set_conv_path(int(path)))

@@ -11,6 +11,7 @@
 namespace scnn {
 
 static thread_local char g_err[256] = "";
+static int g_conv_path = 0;  // 0 = choose by shape, 1 = always the vector kernel
 
 static int fail(int code, const char* fmt, ...) {
     va_list ap;
@@ -53,6 +54,7 @@ static int make_geom(int ndim, const int32_t* extent, int batch, const int32_t* 
     if (ksize) {
         for (int a = 0; a < ndim; ++a) {
             if (ksize[a] < 1 || ksize[a] % 2 == 0) return fail(SCNN_EINVAL, "ksize[%d] = %d must be odd", a, ksize[a]);
+            if (ksize[a] > 63) return fail(SCNN_ECAPACITY, "ksize[%d] = %d exceeds 63", a, ksize[a]);
             g->K[3 - ndim + a] = ksize[a];
             g->H[3 - ndim + a] = (ksize[a] - 1) / 2;
             t *= ksize[a];
@@ -162,6 +164,7 @@ struct ConvWs {
     int* cand_start;
     int* tile_start;
     int* tap_active;
+    int* tap_coord;
     double* wp;
     unsigned* cand_lin;
     float* resp;
@@ -204,6 +207,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cand_start = c.take<int>(g.batch + 1);
     w->tile_start = c.take<int>(g.batch + 1);
     w->tap_active = c.take<int>(g.T);
+    w->tap_coord = c.take<int>(g.T);
     w->wp = c.take<double>((size_t)g.T * c_in * w->c_out_pad);
     w->cand_lin = c.take<unsigned>(cand_cap);
     w->resp = c.take<float>((size_t)w->tiles_cap * c_out * kTileRows);
@@ -300,17 +304,21 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     StageTimer timer(s);
     timer.mark();
     SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
-    SCNN_TRY(launch_filter_prep(g, w, c_in, c_out, ws.c_out_pad, ws.wp, ws.tap_active, s));
+    SCNN_TRY(launch_filter_prep(g, w, c_in, c_out, ws.c_out_pad, ws.wp, ws.tap_active, ws.tap_coord, s));
     SCNN_TRY(launch_index_build(g, in_coords, nnz_in, nullptr, nnz_in, ws.occ, ws.occ_prefix, ws.ctr, s));
     timer.mark();
-    SCNN_TRY(launch_cand_mark(g, in_coords, nnz_in, ws.tap_active, ws.cand, s));
-    SCNN_TRY(launch_popcount(ws.cand, nw, ws.cand_prefix, s));
+    SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
     SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
     SCNN_TRY(launch_sample_info(g, ws.cand_prefix, ws.cand_cap, ws.cand_start, ws.tile_start, ws.ctr, s));
     SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, s));
     timer.mark();
-    SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
-                              ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+    if (g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0) {
+        SCNN_TRY(launch_conv_mfma(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, w, c_out, bias, ws.tap_active,
+                                  ws.tap_coord, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+    } else {
+        SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
+                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+    }
     timer.mark();
     SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.eqcnt, ws.ctr,
                          ws.tiles_cap, s));
@@ -333,6 +341,12 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
         SCNN_TRY(launch_finish(ws.ctr, 1, 0, 1, out_capacity, (long long*)nnz_out, s));
     }
     timer.done();
+    return SCNN_OK;
+}
+
+int scnn_set_conv_path(int path) {
+    if (path != 0 && path != 1) return fail(SCNN_EINVAL, "conv path must be 0 (auto) or 1 (vector kernel)");
+    g_conv_path = path;
     return SCNN_OK;
 }
 

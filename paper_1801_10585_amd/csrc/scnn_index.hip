@@ -137,8 +137,9 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
 // One block per tap: widen the tap's [C_in, C_out] slice to fp64 in a layout whose
 // out-channel stride is padded to a multiple of 16, and record whether the tap
 // has any non-zero weight (pruned taps generate no candidate sites).
-__global__ __launch_bounds__(256) void k_filter_prep(const float* __restrict__ w, int c_in, int c_out, int c_out_pad,
-                                                     double* __restrict__ wp, int* __restrict__ tap_active) {
+__global__ __launch_bounds__(256) void k_filter_prep(Geom g, const float* __restrict__ w, int c_in, int c_out,
+                                                     int c_out_pad, double* __restrict__ wp,
+                                                     int* __restrict__ tap_active, int* __restrict__ tap_coord) {
     __shared__ int s_any;
     const int t = blockIdx.x;
     if (threadIdx.x == 0) s_any = 0;
@@ -154,45 +155,101 @@ __global__ __launch_bounds__(256) void k_filter_prep(const float* __restrict__ w
     }
     if (any) s_any = 1;
     __syncthreads();
-    if (threadIdx.x == 0) tap_active[t] = s_any;
+    if (threadIdx.x == 0) {
+        tap_active[t] = s_any;
+        // tap coordinates (t0, t1, t2), one byte each: delta = coordinate - H
+        tap_coord[t] = (t / (g.K[2] * g.K[1])) | (((t / g.K[2]) % g.K[1]) << 8) | ((t % g.K[2]) << 16);
+    }
 }
 
 hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
-                              int* tap_active, hipStream_t s) {
-    hipLaunchKernelGGL(k_filter_prep, dim3(g.T), dim3(256), 0, s, w, c_in, c_out, c_out_pad, wp, tap_active);
+                              int* tap_active, int* tap_coord, hipStream_t s) {
+    hipLaunchKernelGGL(k_filter_prep, dim3(g.T), dim3(256), 0, s, g, w, c_in, c_out, c_out_pad, wp, tap_active,
+                       tap_coord);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ candidate sites
-// One thread per (input row, tap): an input at q reaches p = q - delta.
-__global__ __launch_bounds__(256) void k_cand_mark(Geom g, const int32_t* __restrict__ coords, long long nnz,
-                                                   const int* __restrict__ tap_active,
-                                                   unsigned long long* __restrict__ cand) {
-    const long long total = nnz * g.T;
-    const int stride = 1 + g.ndim;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const long long r = i / g.T;
-        const int t = (int)(i - r * g.T);
-        if (!tap_active[t]) continue;
-        int b, c0, c1, c2;
-        load_site(g, coords + r * stride, b, c0, c1, c2);
-        if (!site_in_grid(g, b, c0, c1, c2)) continue;
-        const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
-        const int p0 = c0 - (t0 - g.H[0]), p1 = c1 - (t1 - g.H[1]), p2 = c2 - (t2 - g.H[2]);
-        if (!site_in_grid(g, b, p0, p1, p2)) continue;
-        const long long key = (long long)b * g.Npad + lin_of(g, p0, p1, p2);
-        atomicOr(&cand[key >> 6], 1ull << (key & 63));
+// Candidate sites = occupied sites dilated by the filter's non-zero taps: an input at q reaches p = q - delta,
+// i.e. p is a candidate iff some active tap has an occupied site at p + delta.  One thread produces one 64-bit
+// word of the candidate bitmap by OR-ing shifted windows of the occupancy bitmap (no atomics).  A word is cut
+// into the runs it shares with grid lines (last axis); for a run and a (delta_0, delta_1) pair the source bits
+// of all delta_2 lie in one window of at most three occupancy words.
+__device__ inline unsigned long long funnel64(unsigned long long lo, unsigned long long hi, int s) {
+    return s ? ((lo >> s) | (hi << (64 - s))) : lo;
+}
+
+__global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long long* __restrict__ occ,
+                                                     const int* __restrict__ tap_active,
+                                                     unsigned long long* __restrict__ cand,
+                                                     unsigned* __restrict__ cand_count) {
+    const long long n_words = (long long)g.batch * g.Wps;
+    for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
+         w += (long long)gridDim.x * blockDim.x) {
+        const int b = (int)(w / g.Wps);
+        const long long p_first = (w - (long long)b * g.Wps) * 64;  // lin of bit 0
+        long long remaining = g.N - p_first;                         // bits of this word that are sites
+        if (remaining > 64) remaining = 64;
+        unsigned long long out = 0;
+        const long long sample_bit0 = (long long)b * g.Npad;
+        const long long word_lo = (long long)b * g.Wps, word_hi = word_lo + g.Wps;  // this sample's words
+        long long line = p_first / g.E[2];
+        int c2 = (int)(p_first - line * g.E[2]);
+        int c1 = (int)(line % g.E[1]), c0 = (int)(line / g.E[1]);
+        int bit = 0;
+        while (remaining > 0) {
+            int len = g.E[2] - c2;
+            if (len > remaining) len = (int)remaining;
+            unsigned long long run = 0;
+            for (int t0 = 0; t0 < g.K[0]; ++t0) {
+                const int q0 = c0 + t0 - g.H[0];
+                if ((unsigned)q0 >= (unsigned)g.E[0]) continue;
+                for (int t1 = 0; t1 < g.K[1]; ++t1) {
+                    const int q1 = c1 + t1 - g.H[1];
+                    if ((unsigned)q1 >= (unsigned)g.E[1]) continue;
+                    // window of occupancy bits [s - H2, s + len + H2) of line (q0, q1), s = site (q0, q1, c2)
+                    const long long s = sample_bit0 + ((long long)q0 * g.E[1] + q1) * g.E[2] + c2;
+                    const long long wb = (s - g.H[2]) >> 6;  // arithmetic shift: floor also for negatives
+                    unsigned long long win[3];
+#pragma unroll
+                    for (int i = 0; i < 3; ++i) {
+                        const long long wi = wb + i;
+                        win[i] = (wi >= word_lo && wi < word_hi) ? occ[wi] : 0ull;
+                    }
+                    const int* act = tap_active + (t0 * g.K[1] + t1) * g.K[2];
+                    for (int t2 = 0; t2 < g.K[2]; ++t2) {
+                        if (!act[t2]) continue;
+                        const int d2 = t2 - g.H[2];
+                        // source z = c2 + i + d2 must stay on the line: i in [lo, hi)
+                        int lo = -d2 - c2, hi = g.E[2] - d2 - c2;
+                        if (lo < 0) lo = 0;
+                        if (hi > len) hi = len;
+                        if (lo >= hi) continue;
+                        const int o = (int)(s + d2 - wb * 64);  // 0 <= o < 128 for H2 <= 32
+                        unsigned long long bits = o < 64 ? funnel64(win[0], win[1], o) : funnel64(win[1], win[2], o - 64);
+                        unsigned long long m = (hi - lo) >= 64 ? ~0ull : (((1ull << (hi - lo)) - 1ull) << lo);
+                        run |= bits & m;
+                    }
+                }
+            }
+            out |= run << bit;
+            bit += len;
+            remaining -= len;
+            c2 = 0;
+            if (++c1 == g.E[1]) { c1 = 0; ++c0; }
+        }
+        cand[w] = out;
+        cand_count[w] = (unsigned)__popcll(out);
     }
 }
 
-hipError_t launch_cand_mark(const Geom& g, const int32_t* coords, long long nnz, const int* tap_active,
-                            unsigned long long* cand, hipStream_t s) {
-    long long total = nnz * g.T;
-    long long blocks = (total + 255) / 256;
+hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
+                              unsigned long long* cand, unsigned* cand_count, hipStream_t s) {
+    const long long n_words = (long long)g.batch * g.Wps;
+    long long blocks = (n_words + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 16384) blocks = 16384;
-    hipLaunchKernelGGL(k_cand_mark, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, nnz, tap_active, cand);
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(k_cand_dilate, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active, cand, cand_count);
     return hipGetLastError();
 }
 

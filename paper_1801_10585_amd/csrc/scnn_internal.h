@@ -170,9 +170,9 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
                               long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
                               hipStream_t s);
 hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
-                              int* tap_active, hipStream_t s);
-hipError_t launch_cand_mark(const Geom& g, const int32_t* coords, long long nnz, const int* tap_active,
-                            unsigned long long* cand, hipStream_t s);
+                              int* tap_active, int* tap_coord, hipStream_t s);
+hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
+                              unsigned long long* cand, unsigned* cand_count, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
 hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
                               int* tile_start, Counters* ctr, hipStream_t s);
@@ -185,6 +185,13 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
                             int c_out_pad, const float* bias, const int* tap_active, const unsigned* cand_lin,
                             const int* cand_start, const int* tile_start, const Counters* ctr, float* resp,
                             hipStream_t s);
+
+bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
+hipError_t launch_conv_mfma(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                            long long nnz_in, const float* feats, int c_in, const float* w, int c_out,
+                            const float* bias, const int* tap_active, const int* tap_coord,
+                            const unsigned* cand_lin, const int* cand_start, const int* tile_start,
+                            const Counters* ctr, float* resp, hipStream_t s);
 
 // scnn_topk.hip
 hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,

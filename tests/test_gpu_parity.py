@@ -67,6 +67,13 @@ def check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, r
     return gc, gf, band_total
 
 
+def _sampled_columns(rng, batch, c_out, count):
+    cols = {(0, 0), (batch - 1, c_out - 1)}
+    while len(cols) < min(count, batch * c_out):
+        cols.add((int(rng.integers(batch)), int(rng.integers(c_out))))
+    return sorted(cols)
+
+
 # ------------------------------------------------------------------ standalone operators: bit-exact
 def _random_rows(rng, extent, batch, density, channels, levels=None, fill=0.7):
     coords = random_sparse_sites(rng, extent, batch, density)
@@ -171,6 +178,52 @@ def test_layer_small_cases_all_columns(case, mode):
         check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, rho, mode, tag=f"small {case}")
 
 
+MFMA_CASES = [
+    # extent, batch, c_in, c_out, ksize, density, filter density  (shapes the matrix-core kernel accepts)
+    ((14, 14, 14), 2, 32, 16, (3, 3, 3), 0.08, 1.0),
+    ((20, 20, 20), 2, 32, 64, (3, 3, 3), 0.05, 1.0),
+    ((16, 16, 16), 1, 64, 48, (3, 3, 3), 0.06, 0.5),
+    ((18, 18, 18), 2, 32, 32, (5, 5, 5), 0.03, 0.3),
+    ((40, 40), 3, 96, 32, (3, 3), 0.15, 0.8),
+    ((12, 12, 12), 1, 128, 64, (1, 3, 3), 0.2, 1.0),
+]
+
+
+@pytest.mark.parametrize("case", MFMA_CASES)
+@pytest.mark.parametrize("path", [0, 1])
+def test_layer_wide_channels_both_kernels(case, path):
+    extent, batch, c_in, c_out, ksize, density, fdens = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 32)
+    coords = random_sparse_sites(rng, extent, batch, density)
+    feats = rng.random(size=(coords.shape[0], c_in)).astype(np.float32)
+    feats *= rng.random(feats.shape) < 0.9
+    feats = np.ascontiguousarray(feats.astype(np.float32))
+    w = make_filter(rng, ksize, c_in, c_out, fdens, 0.2)
+    bias = rng.normal(size=c_out).astype(np.float32) if c_out == 32 else None
+    n = int(np.prod(extent))
+    scnn.set_conv_path(path)
+    try:
+        for mode, rho in ((scnn.ABS, 0.03), (scnn.SIGNED, 0.1), (scnn.ABS, 1.0)):
+            k = scnn.k_from_rho(rho, n)
+            say(f"layer wide extent={extent} B={batch} {c_in}->{c_out} ks={ksize} path={path} mode={mode} rho={rho}")
+            check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, rho, mode,
+                                      tag=f"wide {case} path={path}")
+    finally:
+        scnn.set_conv_path(0)
+
+
+def test_matrix_core_kernel_keeps_small_responses_accurate():
+    """Shell workload at the r=128 configuration's channel widths with the selection bypassed (rho_up = 1):
+    every response, however small against the products it is summed from, must meet the value tolerance."""
+    wl = make_config(4, r=48, batch=2)
+    L = wl.layers[0]
+    rng = np.random.default_rng(44)
+    n = 48 ** 3
+    say(f"cfg4@48 bypass rows={wl.coords.shape[0]}")
+    check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, n, 1.0, scnn.ABS,
+                              columns=_sampled_columns(rng, wl.batch, L.c_out, 16), tag="cfg4@48 bypass")
+
+
 def test_layer_exact_ties_integer_data():
     """Dyadic inputs and weights: fp32 sums are exact on both sides, so the outputs must be bit-identical,
     including the choice among equal scores at the threshold (lower lin wins)."""
@@ -213,13 +266,6 @@ def test_config2_shells_unit_values_with_ties():
     _, _, band = check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k,
                                            L.rho_up, scnn.ABS, tag="cfg2")
     say(f"cfg2 band entries: {band}")
-
-
-def _sampled_columns(rng, batch, c_out, count):
-    cols = {(0, 0), (batch - 1, c_out - 1)}
-    while len(cols) < min(count, batch * c_out):
-        cols.add((int(rng.integers(batch)), int(rng.integers(c_out))))
-    return sorted(cols)
 
 
 def test_config3_two_layers_full_size():
