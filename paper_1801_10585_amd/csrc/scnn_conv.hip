@@ -16,6 +16,8 @@
 // Responses are written as tiles of kTileRows candidate sites in a planar
 // layout  resp[tile][oc][row]  so that the per-channel selection that follows
 // streams contiguous segments.
+#include <type_traits>
+
 #include "scnn_internal.h"
 
 namespace scnn {
@@ -145,25 +147,25 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kMfmaTapChunk = 32;                 // taps staged per stage (pair lists in LDS)
 constexpr unsigned kPairRowShift = 24;            // pair = (local output row << 24) | input row
 constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
-constexpr int kMaxRounds = 8 * kMfmaTapChunk;     // >= sum over a stage's taps of ceil(blocks / RB), RB >= 1
+constexpr unsigned kPadPair = (unsigned)kTileRows << kPairRowShift;  // list padding: dummy accumulator row, input row 0
+constexpr int kMaxBlocks = kMfmaTapChunk * (kTileRows / 16);          // 16-pair blocks of one stage, at most
 
 __host__ __device__ inline int conv_mfma_tap_chunk(int taps) { return taps < kMfmaTapChunk ? taps : kMfmaTapChunk; }
 
 __host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out, int taps) {
-    return (size_t)kTileRows * (c_out + 1) * sizeof(double)                        // accumulators
-           + (size_t)conv_mfma_tap_chunk(taps) * kTileRows * sizeof(unsigned)       // pair lists
-           + kMfmaTapChunk * sizeof(int)                                            // pair counts
-           + (size_t)kTileRows * 3 * sizeof(short)                                  // candidate sites
-           + (size_t)kMaxRounds * sizeof(unsigned short) + 16;                      // round list + its length
+    return (size_t)(kTileRows + 1) * (c_out + 1) * sizeof(double)                  // accumulators + one dummy row
+           + (size_t)conv_mfma_tap_chunk(taps) * kTileRows * sizeof(unsigned)       // packed pair list
+           + (size_t)kTileRows * 3 * sizeof(short)                                  // candidate sites, later reused
+                                                                                    // for the tap of each block
+           + kMfmaTapChunk;                                                         // blocks per tap
 }
 
-// One "round" = up to RB consecutive 16-pair blocks of one tap.  Its operands are fetched one round ahead of
-// their use (fixed number of loads per round, so the hardware wait counters can be set exactly).
-template <int KC, int RB>
-struct RoundRegs {
-    f32x4 a[RB][KC][2];   // A operand: lane holds x[in(pair 16j + jj)][kc*32 + 8*gq .. + 8)
-    float b[KC][8];       // B operand: lane holds w[t][kc*32 + 8*gq + s][16*wave + jj]
-    int orow[RB][4];      // output rows of result rows 4*gq + v (or -1)
+// Operands of one group of GB consecutive 16-pair blocks, fetched one group ahead of their use.
+template <int KC, int GB>
+struct GroupRegs {
+    f32x4 a[GB][KC][2];     // A operand: lane holds x[in(pair 16j + jj)][kc*32 + 8*gq .. + 8)
+    float b[GB][KC][8];     // B operand: lane holds w[tap of block][kc*32 + 8*gq + s][16*wave + jj]
+    unsigned oaddr[GB][4];  // LDS byte offset of the accumulator of result row 4*gq + v, this lane's channel
 };
 
 template <int KC /* C_in / 32 */, int NB /* C_out / 16 = waves per workgroup */>
@@ -178,22 +180,25 @@ __global__ __launch_bounds__(NB * 64) void k_conv_mfma(Geom g, const unsigned lo
                                                        const int* __restrict__ tile_start,
                                                        const Counters* __restrict__ ctr, float* __restrict__ resp) {
     constexpr int C_IN = KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
-    constexpr int RB = KC == 1 ? 4 : (KC == 2 ? 2 : 1);
+    constexpr int GB = KC == 1 ? 4 : (KC == 2 ? 2 : 1);        // blocks per group
     constexpr int NT = NB * 64;
+    constexpr int TPW = (kMfmaTapChunk + NB - 1) / NB;          // taps a wave looks up and packs per stage
     extern __shared__ __align__(16) unsigned char smem[];
     const int chunk = conv_mfma_tap_chunk(g.T);
-    double* s_c = (double*)smem;                                             // [128][CS]
-    unsigned* s_pair = (unsigned*)(s_c + kTileRows * CS);                    // [chunk][128]
-    int* s_cnt = (int*)(s_pair + chunk * kTileRows);                         // [32]
-    short* s_site = (short*)(s_cnt + kMfmaTapChunk);                         // [128][3]
-    unsigned short* s_round = (unsigned short*)(s_site + kTileRows * 3);     // [kMaxRounds]: tap | j0 << 5 | nb << 9
-    int* s_nrounds = (int*)(s_round + kMaxRounds);
+    double* s_c = (double*)smem;                                             // [129][CS]; row 128 absorbs padding
+    unsigned* s_flat = (unsigned*)(s_c + (kTileRows + 1) * CS);              // packed pairs, blocks of 16
+    short* s_site = (short*)(s_flat + chunk * kTileRows);                    // [128][3], dead once read into registers
+    unsigned char* s_btap = (unsigned char*)s_site;                          // [kMaxBlocks] tap of each block
+    unsigned char* s_nblk = (unsigned char*)(s_site + kTileRows * 3);        // [32] blocks per tap
+    static_assert(kMaxBlocks <= kTileRows * 3 * (int)sizeof(short), "block-tap table must fit the site table");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int jj = lane & 15, gq = lane >> 4;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     const int n_tiles = (int)ctr->n_tiles;
+    const unsigned lane_off = (unsigned)(wave * 16 + jj) * (unsigned)sizeof(double);
+    const unsigned in_max = (unsigned)(nnz_in - 1);
 
     // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
     // the input rows shared by neighbouring tiles stay in that XCD's L2.
@@ -215,155 +220,175 @@ __global__ __launch_bounds__(NB * 64) void k_conv_mfma(Geom g, const unsigned lo
             s_site[r * 3 + 1] = (short)c1;
             s_site[r * 3 + 2] = (short)c2;
         }
-        for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;
+        for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;  // the dummy row needs no reset
+        __syncthreads();
+        int sc[2][3];  // sites of rows lane and lane + 64
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int a = 0; a < 3; ++a) sc[h][a] = s_site[(h * 64 + lane) * 3 + a];
 
         for (int tc = 0; tc < g.T; tc += chunk) {
             const int tmax = (g.T - tc) < chunk ? (g.T - tc) : chunk;
-            __syncthreads();  // sites written; pair lists of the previous stage consumed; accumulators zeroed
-            // ---- neighbour lookup, all (tap, row) items independent so that many loads are in flight
-            for (int base = 0; base < tmax * kTileRows; base += NT * 8) {
-                long long key[8];
-                unsigned long long word[8];
+            __syncthreads();  // sites read; pair list of the previous stage consumed; accumulators zeroed
+            // ---- neighbour lookup: wave handles taps wave, wave + NB, ... for rows lane and lane + 64.  All occupancy
+            //      words are requested first, then all prefixes, so that the loads overlap.
+            long long key[TPW][2];
+            unsigned long long word[TPW][2];
+            unsigned nbr[TPW][2];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int idx = base + u * NT + threadIdx.x;
-                    const int tt = idx >> 7, r = idx & (kTileRows - 1);
-                    key[u] = -1;
-                    word[u] = 0;
-                    if (idx < tmax * kTileRows && r < nrows && tap_active[tc + tt]) {
-                        const int tc3 = tap_coord[tc + tt];  // (t0, t1, t2) packed one byte each
-                        const int q0 = s_site[r * 3 + 0] + (tc3 & 255) - g.H[0],
-                                  q1 = s_site[r * 3 + 1] + ((tc3 >> 8) & 255) - g.H[1],
-                                  q2 = s_site[r * 3 + 2] + (tc3 >> 16) - g.H[2];
-                        if (site_in_grid(g, b, q0, q1, q2)) {
-                            key[u] = (long long)b * g.Npad + lin_of(g, q0, q1, q2);
-                            word[u] = occ[key[u] >> 6];
-                        }
-                    }
-                }
+            for (int m = 0; m < TPW; ++m) {
+                const int tt = wave + m * NB;
+                const bool live = tt < tmax && tap_active[tc + (tt < tmax ? tt : 0)];
+                const int tc3 = tap_coord[tc + (tt < tmax ? tt : 0)];  // (t0, t1, t2) packed one byte each
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int idx = base + u * NT + threadIdx.x;
-                    if (idx < tmax * kTileRows) {
-                        unsigned n = 0xffffffffu;
-                        const int bit = (int)(key[u] & 63);
-                        if (key[u] >= 0 && ((word[u] >> bit) & 1ull)) {
-                            const long long row =
-                                (long long)occ_prefix[key[u] >> 6] + __popcll(word[u] & ((1ull << bit) - 1ull));
-                            if (row < nnz_in) n = (unsigned)row;
-                        }
-                        s_pair[idx] = n;
+                for (int h = 0; h < 2; ++h) {
+                    key[m][h] = -1;
+                    word[m][h] = 0;
+                    const int q0 = sc[h][0] + (tc3 & 255) - g.H[0], q1 = sc[h][1] + ((tc3 >> 8) & 255) - g.H[1],
+                              q2 = sc[h][2] + (tc3 >> 16) - g.H[2];
+                    if (live && h * 64 + lane < nrows && site_in_grid(g, b, q0, q1, q2)) {
+                        key[m][h] = (long long)b * g.Npad + lin_of(g, q0, q1, q2);
+                        word[m][h] = occ[key[m][h] >> 6];
                     }
                 }
             }
-            __syncthreads();
-            // ---- pack each tap's present pairs to the front of its list (in place, ascending output row)
-            for (int tt = wave; tt < tmax; tt += NB) {
-                unsigned* pl = s_pair + tt * kTileRows;
-                const unsigned n0 = pl[lane], n1 = pl[64 + lane];
-                const unsigned long long m0 = __ballot(n0 != 0xffffffffu), m1 = __ballot(n1 != 0xffffffffu);
-                const int c0 = __popcll(m0);
-                if (n0 != 0xffffffffu) pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | n0;
-                if (n1 != 0xffffffffu)
-                    pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | n1;
-                if (lane == 0) s_cnt[tt] = c0 + __popcll(m1);
+#pragma unroll
+            for (int m = 0; m < TPW; ++m)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    unsigned n = 0xffffffffu;
+                    const int bit = (int)(key[m][h] & 63);
+                    if (key[m][h] >= 0 && ((word[m][h] >> bit) & 1ull)) {
+                        const long long row = (long long)occ_prefix[key[m][h] >> 6] +
+                                              __popcll(word[m][h] & ((1ull << bit) - 1ull));
+                        if (row < nnz_in) n = (unsigned)row;
+                    }
+                    nbr[m][h] = n;
+                }
+            // ---- blocks per tap
+#pragma unroll
+            for (int m = 0; m < TPW; ++m) {
+                const int tt = wave + m * NB;
+                const int cnt = __popcll(__ballot(nbr[m][0] != 0xffffffffu)) + __popcll(__ballot(nbr[m][1] != 0xffffffffu));
+                if (lane == 0 && tt < kMfmaTapChunk) s_nblk[tt] = (unsigned char)((cnt + 15) >> 4);
             }
             __syncthreads();
-            // ---- round list: (tap, first block, block count <= RB), taps ascending
-            if (wave == 0) {
-                int nr = 0, nblk = 0;
-                if (lane < tmax) {
-                    nblk = (s_cnt[lane] + 15) >> 4;
-                    nr = (nblk + RB - 1) / RB;
-                }
-                int inc = nr;
+            // ---- pack: taps in ascending order, each tap's present pairs in ascending output row, padded to whole
+            //      blocks of 16 with entries that point at the dummy accumulator row
+            int blk_incl = lane < tmax ? (int)s_nblk[lane] : 0;
 #pragma unroll
-                for (int d = 1; d < 64; d <<= 1) {
-                    const int t = __shfl_up(inc, d, 64);
-                    if (lane >= d) inc += t;
-                }
-                int o = inc - nr;
-                for (int j0 = 0; j0 < nblk; j0 += RB, ++o) {
-                    const int nb = (nblk - j0) < RB ? (nblk - j0) : RB;
-                    s_round[o] = (unsigned short)(lane | (j0 << 5) | (nb << 9));
-                }
-                if (lane == 63) *s_nrounds = inc;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(blk_incl, d, 64);
+                if (lane >= d) blk_incl += t;
+            }
+            const int n_blocks = __shfl(blk_incl, 63, 64);
+#pragma unroll
+            for (int m = 0; m < TPW; ++m) {
+                const int tt = wave + m * NB;
+                const int src = tt < 64 ? tt : 63;
+                const int incl = __shfl(blk_incl, src, 64);
+                const int nblk = tt < tmax ? (int)s_nblk[tt < kMfmaTapChunk ? tt : 0] : 0;
+                const int blk0 = incl - nblk;
+                unsigned* pl = s_flat + blk0 * 16;
+                const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu), m1 = __ballot(nbr[m][1] != 0xffffffffu);
+                const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
+                if (nbr[m][0] != 0xffffffffu) pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
+                if (nbr[m][1] != 0xffffffffu)
+                    pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
+                if (cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
+                if (lane < nblk) s_btap[blk0 + lane] = (unsigned char)tt;
             }
             __syncthreads();
 
-            // ---- contraction: this wave's 16 output channels, every round in ascending (tap, block) order
-            const int n_rounds = __builtin_amdgcn_readfirstlane(*s_nrounds);
-            if (n_rounds > 0) {
-                auto load_round = [&](int i, RoundRegs<KC, RB>& R) {
-                    const unsigned rd = s_round[i < n_rounds ? i : n_rounds - 1];  // clamped: loads are unconditional
-                    const int tt = rd & 31, j0 = (rd >> 5) & 15, nb = rd >> 9;
-                    const int n_t = s_cnt[tt];
-                    const unsigned* pl = s_pair + tt * kTileRows;
-                    const float* wt = w + ((size_t)(tc + tt) * C_IN) * C_OUT + wave * 16 + jj;
+            // ---- contraction: this wave's 16 output channels, every block in ascending (tap, output row) order
+            if (n_blocks > 0) {
+                const int n_groups = (n_blocks + GB - 1) / GB;
+                // All loads of a group are unconditional so that their number is fixed: a group past the end repeats
+                // the last one, a block past the end reads whatever the list holds there (tap and input row are
+                // clamped) and is never computed.
+                auto load_group = [&](int gi, GroupRegs<KC, GB>& R) {
+                    const int g0 = (gi < n_groups ? gi : n_groups - 1) * GB;
+                    unsigned e_in[GB];
+                    uint4 e_out[GB];
+                    int tap[GB];
 #pragma unroll
-                    for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-                        for (int s = 0; s < 8; ++s) R.b[kc][s] = wt[(size_t)(kc * 32 + 8 * gq + s) * C_OUT];
-                    // every LDS read below is unconditional (clamped index) so that they issue back to back
-                    unsigned e_in[RB];
-                    uint4 e_out[RB];
-#pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        const int p = 16 * (j0 + k) + jj, pv = 16 * (j0 + k) + 4 * gq;
-                        e_in[k] = pl[p < kTileRows ? p : kTileRows - 1];
-                        e_out[k] = *(const uint4*)(pl + (pv < kTileRows ? pv : kTileRows - 4));
+                    for (int k = 0; k < GB; ++k) {
+                        e_in[k] = s_flat[16 * (g0 + k) + jj];
+                        e_out[k] = *(const uint4*)(s_flat + 16 * (g0 + k) + 4 * gq);
+                        tap[k] = s_btap[g0 + k];
                     }
 #pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        const int p = 16 * (j0 + k) + jj, pv = 16 * (j0 + k) + 4 * gq;
-                        // pairs beyond the list read input row 0: their results are never stored
-                        const unsigned in = (k < nb && p < n_t) ? (e_in[k] & kPairInMask) : 0u;
+                    for (int k = 0; k < GB; ++k) {
+                        int tt = __builtin_amdgcn_readfirstlane(tap[k]);
+                        tt = tt < tmax ? tt : tmax - 1;
+                        const float* wt = w + ((size_t)(tc + tt) * C_IN) * C_OUT + wave * 16 + jj;
+#pragma unroll
+                        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+                            for (int s = 0; s < 8; ++s) R.b[k][kc][s] = wt[(size_t)(kc * 32 + 8 * gq + s) * C_OUT];
+                        unsigned in = e_in[k] & kPairInMask;
+                        in = in < in_max ? in : in_max;
                         const f32x4* src = (const f32x4*)(feats + (size_t)in * C_IN + 8 * gq);
 #pragma unroll
                         for (int kc = 0; kc < KC; ++kc) {
                             R.a[k][kc][0] = src[kc * 8];
                             R.a[k][kc][1] = src[kc * 8 + 1];
                         }
-                        const bool kv = k < nb;
-                        R.orow[k][0] = (kv && pv + 0 < n_t) ? (int)(e_out[k].x >> kPairRowShift) : -1;
-                        R.orow[k][1] = (kv && pv + 1 < n_t) ? (int)(e_out[k].y >> kPairRowShift) : -1;
-                        R.orow[k][2] = (kv && pv + 2 < n_t) ? (int)(e_out[k].z >> kPairRowShift) : -1;
-                        R.orow[k][3] = (kv && pv + 3 < n_t) ? (int)(e_out[k].w >> kPairRowShift) : -1;
+                        R.oaddr[k][0] = (e_out[k].x >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][1] = (e_out[k].y >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][2] = (e_out[k].z >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][3] = (e_out[k].w >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
                     }
                 };
-                auto compute_round = [&](int i, const RoundRegs<KC, RB>& R) {
-                    const int nb = s_round[i] >> 9;
+                // NBK blocks as straight-line code: independent fp32 MFMA chains (one per block and per 32 input
+                // channels), then the 16 x 16 results (rows = pairs 4*gq + v, column = channel 16*wave + jj) are added
+                // to the fp64 accumulators.  Padding pairs land in the dummy row.
+                auto compute_blocks = [&](auto nbk_tag, const GroupRegs<KC, GB>& R) {
+                    constexpr int NBK = decltype(nbk_tag)::value;
+                    f32x4 acc[NBK][KC];
 #pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        if (k < nb) {
-                            // one fp32 MFMA chain per 32 input channels; each chain's 16 x 16 result (rows = pairs
-                            // 4*gq + v, column = channel 16*wave + jj) is added to the fp64 accumulators
+                    for (int k = 0; k < NBK; ++k)
 #pragma unroll
-                            for (int kc = 0; kc < KC; ++kc) {
-                                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+                        for (int kc = 0; kc < KC; ++kc) {
+                            f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                                for (int s = 0; s < 4; ++s)
-                                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[kc][s], acc, 0, 0, 0);
+                            for (int s = 0; s < 4; ++s)
+                                c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[k][kc][s], c, 0, 0, 0);
 #pragma unroll
-                                for (int s = 0; s < 4; ++s)
-                                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][4 + s], acc, 0,
-                                                                               0, 0);
+                            for (int s = 0; s < 4; ++s)
+                                c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[k][kc][4 + s], c, 0, 0, 0);
+                            acc[k][kc] = c;
+                        }
 #pragma unroll
-                                for (int v = 0; v < 4; ++v)
-                                    if (R.orow[k][v] >= 0)
-                                        __hip_atomic_fetch_add(&s_c[R.orow[k][v] * CS + wave * 16 + jj], (double)acc[v],
-                                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                            }
+                    for (int k = 0; k < NBK; ++k)
+#pragma unroll
+                        for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+                            for (int v = 0; v < 4; ++v)
+                                __hip_atomic_fetch_add((double*)((unsigned char*)s_c + R.oaddr[k][v]),
+                                                       (double)acc[k][kc][v], __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                };
+                auto compute_group = [&](int gi, const GroupRegs<KC, GB>& R) {
+                    const int nb = n_blocks - gi * GB;  // >= 1
+                    if (nb >= GB) {
+                        compute_blocks(std::integral_constant<int, GB>{}, R);
+                    } else if constexpr (GB >= 2) {
+                        if (nb == 1) compute_blocks(std::integral_constant<int, 1>{}, R);
+                        if constexpr (GB >= 4) {
+                            if (nb == 2) compute_blocks(std::integral_constant<int, 2>{}, R);
+                            if (nb == 3) compute_blocks(std::integral_constant<int, 3>{}, R);
                         }
                     }
                 };
-                RoundRegs<KC, RB> r0, r1;
-                load_round(0, r0);
-                for (int i = 0; i < n_rounds; i += 2) {
-                    load_round(i + 1, r1);
-                    compute_round(i, r0);
-                    load_round(i + 2, r0);
-                    if (i + 1 < n_rounds) compute_round(i + 1, r1);
+                GroupRegs<KC, GB> r0, r1;
+                load_group(0, r0);
+                for (int gi = 0; gi < n_groups; gi += 2) {
+                    load_group(gi + 1, r1);
+                    compute_group(gi, r0);
+                    load_group(gi + 2, r0);
+                    if (gi + 1 < n_groups) compute_group(gi + 1, r1);
                 }
             }
         }
