@@ -92,9 +92,13 @@ size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int
  *                   w[tap(delta), ic, oc] * in[b, p + delta, ic]
  * (stride 1, zero "same" padding: an input at q updates p = q - delta, updates
  * leaving the grid are dropped -- Alg. 1 steps 5-9).  Inputs, weights and
- * responses are fp32; each response is summed in a fixed order (tap ascending,
- * ic ascending) in wider-than-fp32 arithmetic and rounded to fp32 once, so the
- * result is reproducible bit for bit.  Responses that are exactly 0 are
+ * responses are fp32; each response is summed in fp64 (the matrix-core kernel
+ * sums 32 products at a time in fp32 first) and rounded to fp32 once.  The
+ * vector kernel adds in a fixed order and is reproducible bit for bit; the
+ * matrix-core kernel adds the per-tap partial sums to its fp64 accumulators
+ * with LDS atomics in no fixed order, so a run can differ from another in the
+ * last bits of the fp64 sum, which survives the rounding to fp32 for about one
+ * response in 10^8.  Responses that are exactly 0 are
  * not entries (step 13).  bias (nullable, device, [c_out]) is added to the
  * entries (step 14); an entry whose biased value is exactly 0 stops being one.
  * Per (sample b, output channel oc) only the k = scnn_k_from_rho(rho_up, N)

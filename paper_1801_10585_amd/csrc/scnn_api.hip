@@ -170,6 +170,11 @@ struct ConvWs {
     float* resp;
     unsigned* eqcnt;
     unsigned* tile_rows;
+    unsigned* pairs;
+    unsigned short* block_tap;
+    float* wb;
+    uint2* tile_hdr;
+    long long block_cap;
     int32_t* tmp_coords;
     float* tmp_feats;
     long long* pool_key;
@@ -213,6 +218,12 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->resp = c.take<float>((size_t)w->tiles_cap * c_out * kTileRows);
     w->eqcnt = c.take<unsigned>((size_t)w->tiles_cap * c_out);
     w->tile_rows = c.take<unsigned>(w->tiles_cap);
+    // matrix-core path: every (input row, tap) gives at most one pair; a tile reserves whole blocks per active tap
+    w->block_cap = conv_mfma_supported(g, c_in, c_out, nnz_in) ? (long long)g.T * (cand_cap / 16 + w->tiles_cap) : 0;
+    w->pairs = c.take<unsigned>((size_t)w->block_cap * 16);
+    w->block_tap = c.take<unsigned short>((size_t)w->block_cap);
+    w->wb = c.take<float>(w->block_cap ? (size_t)g.T * c_in * c_out : 0);
+    w->tile_hdr = c.take<uint2>(w->block_cap ? w->tiles_cap : 0);
     w->tmp_coords = c.take<int32_t>(pool ? (size_t)cand_cap * (1 + g.ndim) : 0);
     w->tmp_feats = c.take<float>(pool ? (size_t)cand_cap * c_out : 0);
     w->pool_key = c.take<long long>(pool ? w->pool_cap : 0);
@@ -313,8 +324,12 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, s));
     timer.mark();
     if (g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0) {
-        SCNN_TRY(launch_conv_mfma(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, w, c_out, bias, ws.tap_active,
-                                  ws.tap_coord, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+        SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,
+                                   ws.cand_start, ws.tile_start, ws.ctr, ws.pairs, ws.block_tap, ws.tile_hdr,
+                                   ws.block_cap, ws.tiles_cap, s));
+        SCNN_TRY(launch_filter_mfma_layout(g, w, c_in, c_out, ws.wb, s));
+        SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,
+                                  ws.ctr, ws.resp, s));
     } else {
         SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
                                   ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));

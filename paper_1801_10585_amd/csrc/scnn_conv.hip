@@ -124,123 +124,104 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
 }
 
 // ---------------------------------------------------------------------------
-// Matrix-core kernel for wide channels (C_in a multiple of 32, C_out a multiple
+// Matrix-core path for wide channels (C_in a multiple of 32, C_out a multiple
 // of 16 up to 64): the gathered neighbour block of one tap really is a dense
 // [pairs x C_in] . [C_in x C_out] contraction.
 //
 // Only about a third of a surface candidate's taps have a neighbour, and which
 // ones varies from site to site, so zero-padding absent neighbours would waste
 // most of the matrix cores.  Instead, per tile of 128 candidate sites and per
-// tap, the present (output row, input row) pairs are packed into blocks of 16;
-// each block is an fp32 MFMA chain per 32 input channels; its 16 x 16 results
-// are added to the tile's accumulators in LDS.  Those accumulators are fp64
-// (native LDS ds_add_f64): the fp32 matrix cores only ever sum 32 products of a
-// single tap, the long cancelling sum over channels and taps is carried in
-// double and rounded to fp32 once.
+// tap, the present (output row, input row) pairs are packed into blocks of 16
+// (k_pair_build, a light kernel that runs at high occupancy and leaves the
+// lists in global memory); k_conv_mfma then runs one fp32 MFMA chain per block
+// and per 32 input channels and adds the 16 x 16 results to the tile's
+// accumulators in LDS.  Those accumulators are fp64 (native LDS ds_add_f64):
+// the fp32 matrix cores only ever sum 32 products of a single tap, the long
+// cancelling sum over channels and taps is carried in double and rounded to
+// fp32 once.
 //
-// Wave w of a workgroup owns output channels [16w, 16w+16) and walks every
-// (tap, block) in ascending order, so each accumulator has a single writer and
-// a fixed summation order: the result is bit-reproducible.
+// A wave multiplies its blocks against a whole filter tap (all C_out channels):
+// an input row is fetched once per pair and a tap's weights once per round of
+// up to three blocks, which keeps the L1 traffic well below what the matrix
+// cores could consume.  Waves of a workgroup share the tile's accumulators
+// through the LDS atomic, so the order of the fp64 additions is not fixed.
 // ---------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kMfmaTapChunk = 32;                 // taps staged per stage (pair lists in LDS)
+constexpr int kPairTapChunk = 32;                 // taps looked up per pass of the pair builder
 constexpr unsigned kPairRowShift = 24;            // pair = (local output row << 24) | input row
 constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
 constexpr unsigned kPadPair = (unsigned)kTileRows << kPairRowShift;  // list padding: dummy accumulator row, input row 0
-constexpr int kMaxBlocks = kMfmaTapChunk * (kTileRows / 16);          // 16-pair blocks of one stage, at most
+constexpr int kStageBlocks = 216;                 // 16-pair blocks staged in LDS at a time by the contraction
 
-__host__ __device__ inline int conv_mfma_tap_chunk(int taps) { return taps < kMfmaTapChunk ? taps : kMfmaTapChunk; }
-
-__host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out, int taps) {
-    return (size_t)(kTileRows + 1) * (c_out + 1) * sizeof(double)                  // accumulators + one dummy row
-           + (size_t)conv_mfma_tap_chunk(taps) * kTileRows * sizeof(unsigned)       // packed pair list
-           + (size_t)kTileRows * 3 * sizeof(short)                                  // candidate sites, later reused
-                                                                                    // for the tap of each block
-           + kMfmaTapChunk;                                                         // blocks per tap
-}
-
-// Operands of one group of GB consecutive 16-pair blocks, fetched one group ahead of their use.
-template <int KC, int GB>
-struct GroupRegs {
-    f32x4 a[GB][KC][2];     // A operand: lane holds x[in(pair 16j + jj)][kc*32 + 8*gq .. + 8)
-    float b[GB][KC][8];     // B operand: lane holds w[tap of block][kc*32 + 8*gq + s][16*wave + jj]
-    unsigned oaddr[GB][4];  // LDS byte offset of the accumulator of result row 4*gq + v, this lane's channel
-};
-
-template <int KC /* C_in / 32 */, int NB /* C_out / 16 = waves per workgroup */>
-__global__ __launch_bounds__(NB * 64) void k_conv_mfma(Geom g, const unsigned long long* __restrict__ occ,
-                                                       const unsigned* __restrict__ occ_prefix, long long nnz_in,
-                                                       const float* __restrict__ feats,
-                                                       const float* __restrict__ w, const float* __restrict__ bias,
-                                                       const int* __restrict__ tap_active,
-                                                       const int* __restrict__ tap_coord,
-                                                       const unsigned* __restrict__ cand_lin,
-                                                       const int* __restrict__ cand_start,
-                                                       const int* __restrict__ tile_start,
-                                                       const Counters* __restrict__ ctr, float* __restrict__ resp) {
-    constexpr int C_IN = KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
-    constexpr int GB = KC == 1 ? 4 : (KC == 2 ? 2 : 1);        // blocks per group
-    constexpr int NT = NB * 64;
-    constexpr int TPW = (kMfmaTapChunk + NB - 1) / NB;          // taps a wave looks up and packs per stage
-    extern __shared__ __align__(16) unsigned char smem[];
-    const int chunk = conv_mfma_tap_chunk(g.T);
-    double* s_c = (double*)smem;                                             // [129][CS]; row 128 absorbs padding
-    unsigned* s_flat = (unsigned*)(s_c + (kTileRows + 1) * CS);              // packed pairs, blocks of 16
-    short* s_site = (short*)(s_flat + chunk * kTileRows);                    // [128][3], dead once read into registers
-    unsigned char* s_btap = (unsigned char*)s_site;                          // [kMaxBlocks] tap of each block
-    unsigned char* s_nblk = (unsigned char*)(s_site + kTileRows * 3);        // [32] blocks per tap
-    static_assert(kMaxBlocks <= kTileRows * 3 * (int)sizeof(short), "block-tap table must fit the site table");
-
+// Pair lists of all tiles live in one global array of 16-entry blocks; a tile's blocks are contiguous, in
+// ascending (tap, output row) order.  tile_hdr[tile] = {first block, block count};
+// block_tap[block] = tap | (index of the block within its tap) << 8.
+__global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long long* __restrict__ occ,
+                                                    const unsigned* __restrict__ occ_prefix, long long nnz_in,
+                                                    const int* __restrict__ tap_active,
+                                                    const int* __restrict__ tap_coord,
+                                                    const unsigned* __restrict__ cand_lin,
+                                                    const int* __restrict__ cand_start,
+                                                    const int* __restrict__ tile_start, Counters* ctr,
+                                                    unsigned* __restrict__ pairs, unsigned short* __restrict__ block_tap,
+                                                    uint2* __restrict__ tile_hdr, long long block_cap) {
+    constexpr int TPW = kPairTapChunk / 4;  // taps per wave and pass
+    __shared__ unsigned char s_nblk[kPairTapChunk];
+    __shared__ unsigned s_base;   // first global block of the current pass
+    __shared__ unsigned s_total;  // blocks of this tile so far
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int jj = lane & 15, gq = lane >> 4;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     const int n_tiles = (int)ctr->n_tiles;
-    const unsigned lane_off = (unsigned)(wave * 16 + jj) * (unsigned)sizeof(double);
-    const unsigned in_max = (unsigned)(nnz_in - 1);
+    __shared__ int s_active;  // taps with a non-zero weight
+    if (wave == 0) {
+        int active = 0;
+        for (int t0 = 0; t0 < g.T; t0 += 64)
+            active += __popcll(__ballot(t0 + lane < g.T && tap_active[t0 + lane < g.T ? t0 + lane : 0] != 0));
+        if (lane == 0) s_active = active;
+    }
+    __syncthreads();
 
-    // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
-    // the input rows shared by neighbouring tiles stay in that XCD's L2.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
-    const int span = (n_tiles + 7) >> 3;
-    const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
-
-    for (int tile = xcd * span + slot; tile < tile_end; tile += per_xcd) {
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
         int nrows = cand_start[b + 1] - first;
         if (nrows > kTileRows) nrows = kTileRows;
-
-        __syncthreads();  // previous tile's epilogue has read the accumulators
-        for (int r = threadIdx.x; r < kTileRows; r += NT) {
-            int c0 = 0, c1 = 0, c2 = 0;
-            if (r < nrows) site_of(g, cand_lin[first + r], c0, c1, c2);
-            s_site[r * 3 + 0] = (short)c0;
-            s_site[r * 3 + 1] = (short)c1;
-            s_site[r * 3 + 2] = (short)c2;
-        }
-        for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;  // the dummy row needs no reset
-        __syncthreads();
         int sc[2][3];  // sites of rows lane and lane + 64
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int a = 0; a < 3; ++a) sc[h][a] = s_site[(h * 64 + lane) * 3 + a];
-
-        for (int tc = 0; tc < g.T; tc += chunk) {
-            const int tmax = (g.T - tc) < chunk ? (g.T - tc) : chunk;
-            __syncthreads();  // sites read; pair list of the previous stage consumed; accumulators zeroed
-            // ---- neighbour lookup: wave handles taps wave, wave + NB, ... for rows lane and lane + 64.  All occupancy
+        for (int h = 0; h < 2; ++h) {
+            sc[h][0] = sc[h][1] = sc[h][2] = 0;
+            if (h * 64 + lane < nrows) site_of(g, cand_lin[first + h * 64 + lane], sc[h][0], sc[h][1], sc[h][2]);
+        }
+        // A tile's blocks must be contiguous, so its space is reserved in one piece up front: at most
+        // ceil(nrows / 16) blocks per active tap.  Unused blocks of the reservation are simply never read.
+        __syncthreads();  // s_base / s_total of the previous tile consumed
+        if (threadIdx.x == 0) {
+            const unsigned want = (unsigned)s_active * (unsigned)((nrows + 15) >> 4);
+            unsigned base = atomicAdd(&ctr->pair_blocks, want);
+            if ((long long)base + want > block_cap) {  // cannot happen with the documented workspace size
+                atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+                base = 0xffffffffu;
+            }
+            s_base = base;
+            s_total = 0;
+        }
+        __syncthreads();
+        const unsigned tile_base = s_base;
+        for (int tc = 0; tc < g.T; tc += kPairTapChunk) {
+            const int tmax = (g.T - tc) < kPairTapChunk ? (g.T - tc) : kPairTapChunk;
+            // ---- neighbour lookup: wave handles taps wave, wave + 4, ... for rows lane and lane + 64.  All occupancy
             //      words are requested first, then all prefixes, so that the loads overlap.
             long long key[TPW][2];
             unsigned long long word[TPW][2];
             unsigned nbr[TPW][2];
 #pragma unroll
             for (int m = 0; m < TPW; ++m) {
-                const int tt = wave + m * NB;
-                const bool live = tt < tmax && tap_active[tc + (tt < tmax ? tt : 0)];
-                const int tc3 = tap_coord[tc + (tt < tmax ? tt : 0)];  // (t0, t1, t2) packed one byte each
+                const int tt = wave + m * 4;
+                const int tcl = tc + (tt < tmax ? tt : 0);
+                const bool live = tt < tmax && tap_active[tcl];
+                const int tc3 = tap_coord[tcl];  // (t0, t1, t2) packed one byte each
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     key[m][h] = -1;
@@ -266,67 +247,207 @@ __global__ __launch_bounds__(NB * 64) void k_conv_mfma(Geom g, const unsigned lo
                     }
                     nbr[m][h] = n;
                 }
-            // ---- blocks per tap
 #pragma unroll
             for (int m = 0; m < TPW; ++m) {
-                const int tt = wave + m * NB;
-                const int cnt = __popcll(__ballot(nbr[m][0] != 0xffffffffu)) + __popcll(__ballot(nbr[m][1] != 0xffffffffu));
-                if (lane == 0 && tt < kMfmaTapChunk) s_nblk[tt] = (unsigned char)((cnt + 15) >> 4);
+                const int tt = wave + m * 4;
+                const int cnt =
+                    __popcll(__ballot(nbr[m][0] != 0xffffffffu)) + __popcll(__ballot(nbr[m][1] != 0xffffffffu));
+                if (lane == 0) s_nblk[tt] = (unsigned char)((cnt + 15) >> 4);
             }
             __syncthreads();
-            // ---- pack: taps in ascending order, each tap's present pairs in ascending output row, padded to whole
-            //      blocks of 16 with entries that point at the dummy accumulator row
+            // ---- pack: taps ascending, each tap's present pairs in ascending output row, padded to whole blocks
+            //      of 16 with entries that point at the dummy accumulator row
             int blk_incl = lane < tmax ? (int)s_nblk[lane] : 0;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
                 const int t = __shfl_up(blk_incl, d, 64);
                 if (lane >= d) blk_incl += t;
             }
-            const int n_blocks = __shfl(blk_incl, 63, 64);
+            const unsigned pass_blocks = (unsigned)__shfl(blk_incl, 63, 64);
+            const unsigned pass_base = tile_base + s_total;
+            if (tile_base != 0xffffffffu) {
 #pragma unroll
-            for (int m = 0; m < TPW; ++m) {
-                const int tt = wave + m * NB;
-                const int src = tt < 64 ? tt : 63;
-                const int incl = __shfl(blk_incl, src, 64);
-                const int nblk = tt < tmax ? (int)s_nblk[tt < kMfmaTapChunk ? tt : 0] : 0;
-                const int blk0 = incl - nblk;
-                unsigned* pl = s_flat + blk0 * 16;
-                const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu), m1 = __ballot(nbr[m][1] != 0xffffffffu);
-                const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
-                if (nbr[m][0] != 0xffffffffu) pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
-                if (nbr[m][1] != 0xffffffffu)
-                    pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
-                if (cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
-                if (lane < nblk) s_btap[blk0 + lane] = (unsigned char)tt;
+                for (int m = 0; m < TPW; ++m) {
+                    const int tt = wave + m * 4;
+                    const int incl = __shfl(blk_incl, tt, 64);
+                    const int nblk = tt < tmax ? (int)s_nblk[tt] : 0;
+                    const unsigned blk0 = pass_base + (unsigned)(incl - nblk);
+                    unsigned* pl = pairs + (size_t)blk0 * 16;
+                    const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu),
+                                             m1 = __ballot(nbr[m][1] != 0xffffffffu);
+                    const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
+                    if (nbr[m][0] != 0xffffffffu)
+                        pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
+                    if (nbr[m][1] != 0xffffffffu)
+                        pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
+                    if (cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
+                    if (lane < nblk) block_tap[blk0 + lane] = (unsigned short)((tc + tt) | (lane << 8));
+                }
+            }
+            __syncthreads();  // every wave has read s_total and s_nblk
+            if (threadIdx.x == 0) s_total += pass_blocks;
+            __syncthreads();
+        }
+        if (threadIdx.x == 0)
+            tile_hdr[tile] = make_uint2(tile_base == 0xffffffffu ? 0u : tile_base, tile_base == 0xffffffffu ? 0u : s_total);
+    }
+}
+
+hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                             long long nnz_in, const int* tap_active, const int* tap_coord,
+                             const unsigned* cand_lin, const int* cand_start, const int* tile_start, Counters* ctr,
+                             unsigned* pairs, unsigned short* block_tap, uint2* tile_hdr, long long block_cap,
+                             long long tiles_cap, hipStream_t s) {
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 16 ? 256 * 16 : tiles_cap);
+    hipLaunchKernelGGL(k_pair_build, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, tap_active,
+                       tap_coord, cand_lin, cand_start, tile_start, ctr, pairs, block_tap, tile_hdr, block_cap);
+    return hipGetLastError();
+}
+
+// Weights in matrix-core operand order: wb[((t * KC + kc) * NB + cb) * 64 + lane][s] = w[t][kc*32 + 8*gq + s][cb*16 + jj]
+// (lane = 16*gq + jj), so that a lane fetches its eight B values of one (tap, kc, cb) with two 16-byte loads.
+__global__ __launch_bounds__(256) void k_filter_mfma_layout(const float* __restrict__ w, int taps, int c_in, int c_out,
+                                                            float* __restrict__ wb) {
+    const int kcn = c_in / 32, nb = c_out / 16;
+    const long long total = (long long)taps * c_in * c_out;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
+        long long r = i >> 9;
+        const int cb = (int)(r % nb);
+        r /= nb;
+        const int kc = (int)(r % kcn), t = (int)(r / kcn);
+        const int jj = lane & 15, gq = lane >> 4;
+        wb[i] = w[((size_t)t * c_in + kc * 32 + 8 * gq + s) * c_out + cb * 16 + jj];
+    }
+}
+
+hipError_t launch_filter_mfma_layout(const Geom& g, const float* w, int c_in, int c_out, float* wb, hipStream_t s) {
+    const long long total = (long long)g.T * c_in * c_out;
+    long long blocks = (total + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_filter_mfma_layout, dim3((unsigned)blocks), dim3(256), 0, s, w, g.T, c_in, c_out, wb);
+    return hipGetLastError();
+}
+
+constexpr int kConvWaves = 4;  // waves per workgroup of the contraction kernel
+
+__host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out) {
+    return (size_t)(kTileRows + 1) * (c_out + 1) * sizeof(double)   // accumulators + one dummy row
+           + (size_t)kStageBlocks * 16 * sizeof(unsigned)            // staged pair blocks
+           + (size_t)kStageBlocks * sizeof(unsigned short)           // tap / position of each staged block
+           + (size_t)kStageBlocks * sizeof(unsigned short)           // round list
+           + 16;
+}
+
+// Operands of one round = up to RB consecutive 16-pair blocks of ONE tap, fetched one round ahead of their use.
+template <int KC, int NB, int RB>
+struct RoundRegs {
+    f32x4 a[RB][KC][2];     // A operand: lane holds x[in(pair 16j + jj)][kc*32 + 8*gq .. + 8)
+    f32x4 b[KC][NB][2];     // B operand: lane holds w[tap][kc*32 + 8*gq + s][16*cb + jj], s = 0..7
+    unsigned oaddr[RB][4];  // LDS byte offset of accumulator (row of result row 4*gq + v, channel jj)
+};
+
+// Work split: wave i of the workgroup takes rounds i, i + 4, ...  A wave multiplies its blocks against the whole
+// filter tap (all C_out channels), so an input row is fetched once per pair and a tap's weights once per round;
+// the price is that two waves may add to the same accumulator, which the LDS fp64 atomic makes safe but not
+// ordered: the fp64 sum can differ in its last bits from run to run.
+template <int KC /* C_in / 32 */, int NB /* C_out / 16 */>
+__global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long long nnz_in,
+                                                               const float* __restrict__ feats,
+                                                               const float* __restrict__ wb,
+                                                               const float* __restrict__ bias,
+                                                               const unsigned* __restrict__ pairs,
+                                                               const unsigned short* __restrict__ block_tap,
+                                                               const uint2* __restrict__ tile_hdr,
+                                                               const Counters* __restrict__ ctr,
+                                                               float* __restrict__ resp) {
+    constexpr int C_IN = KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
+    constexpr int RB = (KC * NB <= 4) ? 3 : ((KC * NB <= 8) ? 2 : 1);  // blocks per round
+    constexpr int NT = kConvWaves * 64;
+    static_assert(kStageBlocks % 4 == 0 && kStageBlocks <= 256, "stage size");
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* s_c = (double*)smem;                                               // [129][CS]; row 128 absorbs padding
+    unsigned* s_flat = (unsigned*)(s_c + (kTileRows + 1) * CS);                // [kStageBlocks][16] packed pairs
+    unsigned short* s_btap = (unsigned short*)(s_flat + kStageBlocks * 16);    // [kStageBlocks]
+    unsigned short* s_round = s_btap + kStageBlocks;                           // [kStageBlocks] first block | nb << 8
+    int* s_nrounds = (int*)(s_round + kStageBlocks);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int jj = lane & 15, gq = lane >> 4;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const int n_tiles = (int)ctr->n_tiles;
+    const unsigned lane_off = (unsigned)jj * (unsigned)sizeof(double);
+    const unsigned in_max = (unsigned)(nnz_in - 1);
+
+    // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
+    // the input rows shared by neighbouring tiles stay in that XCD's L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
+    const int span = (n_tiles + 7) >> 3;
+    const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
+
+    for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;  // the dummy row needs no reset
+
+    for (int tile = xcd * span + slot; tile < tile_end; tile += per_xcd) {
+        const uint2 hdr = tile_hdr[tile];
+        for (unsigned s0 = 0; s0 < hdr.y; s0 += kStageBlocks) {
+            const int n_blocks = (int)((hdr.y - s0) < (unsigned)kStageBlocks ? (hdr.y - s0) : (unsigned)kStageBlocks);
+            __syncthreads();  // previous stage consumed (and, for the first stage, the accumulators are zero)
+            {   // ---- stage this tile's next blocks: a contiguous copy, 16 bytes per thread and step
+                const uint4* src = (const uint4*)(pairs + (size_t)(hdr.x + s0) * 16);
+                uint4* dst = (uint4*)s_flat;
+                for (int i = threadIdx.x; i < n_blocks * 4; i += NT) dst[i] = src[i];
+                for (int i = threadIdx.x; i < n_blocks; i += NT) s_btap[i] = block_tap[hdr.x + s0 + i];
             }
             __syncthreads();
-
-            // ---- contraction: this wave's 16 output channels, every block in ascending (tap, output row) order
-            if (n_blocks > 0) {
-                const int n_groups = (n_blocks + GB - 1) / GB;
-                // All loads of a group are unconditional so that their number is fixed: a group past the end repeats
-                // the last one, a block past the end reads whatever the list holds there (tap and input row are
+            // ---- round list: a round starts at every RB-th block of a tap (and at the start of the stage)
+            if (wave == 0) {
+                int base = 0;
+                for (int i0 = 0; i0 < n_blocks; i0 += 64) {
+                    const int i = i0 + lane;
+                    const bool start = i < n_blocks && (i == 0 || ((s_btap[i] >> 8) % RB) == 0);
+                    const unsigned long long m = __ballot(start);
+                    if (start) s_round[base + __popcll(m & lt_mask)] = (unsigned short)i;
+                    base += __popcll(m);
+                }
+                if (lane == 0) *s_nrounds = base;
+            }
+            __syncthreads();
+            const int n_rounds = __builtin_amdgcn_readfirstlane(*s_nrounds);
+            const int my_rounds = (n_rounds - wave + kConvWaves - 1) / kConvWaves;  // rounds wave, wave + 4, ...
+            if (my_rounds > 0) {
+                // All loads of a round are unconditional so that their number is fixed: a round past the end
+                // repeats the wave's last one, a block past the round's end repeats list entries (input row
                 // clamped) and is never computed.
-                auto load_group = [&](int gi, GroupRegs<KC, GB>& R) {
-                    const int g0 = (gi < n_groups ? gi : n_groups - 1) * GB;
-                    unsigned e_in[GB];
-                    uint4 e_out[GB];
-                    int tap[GB];
+                auto round_blocks = [&](int r) {
+                    const int first = s_round[r];
+                    const int next = r + 1 < n_rounds ? (int)s_round[r + 1] : n_blocks;
+                    return make_int2(first, next - first);
+                };
+                auto load_round = [&](int k_round, RoundRegs<KC, NB, RB>& R) {
+                    const int r = wave + kConvWaves * (k_round < my_rounds ? k_round : my_rounds - 1);
+                    const int first = __builtin_amdgcn_readfirstlane(s_round[r]);
+                    int tt = __builtin_amdgcn_readfirstlane(s_btap[first] & 0xff);
+                    tt = tt < taps ? tt : taps - 1;
+                    const f32x4* wt = (const f32x4*)(wb + ((size_t)tt * KC * NB * 64 + lane) * 8);
 #pragma unroll
-                    for (int k = 0; k < GB; ++k) {
-                        e_in[k] = s_flat[16 * (g0 + k) + jj];
-                        e_out[k] = *(const uint4*)(s_flat + 16 * (g0 + k) + 4 * gq);
-                        tap[k] = s_btap[g0 + k];
+                    for (int kc = 0; kc < KC; ++kc)
+#pragma unroll
+                        for (int cb = 0; cb < NB; ++cb) {
+                            R.b[kc][cb][0] = wt[(kc * NB + cb) * 128];
+                            R.b[kc][cb][1] = wt[(kc * NB + cb) * 128 + 1];
+                        }
+                    unsigned e_in[RB];
+                    uint4 e_out[RB];
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        const int blk = (first + k) < kStageBlocks ? (first + k) : kStageBlocks - 1;
+                        e_in[k] = s_flat[16 * blk + jj];
+                        e_out[k] = *(const uint4*)(s_flat + 16 * blk + 4 * gq);
                     }
 #pragma unroll
-                    for (int k = 0; k < GB; ++k) {
-                        int tt = __builtin_amdgcn_readfirstlane(tap[k]);
-                        tt = tt < tmax ? tt : tmax - 1;
-                        const float* wt = w + ((size_t)(tc + tt) * C_IN) * C_OUT + wave * 16 + jj;
-#pragma unroll
-                        for (int kc = 0; kc < KC; ++kc)
-#pragma unroll
-                            for (int s = 0; s < 8; ++s) R.b[k][kc][s] = wt[(size_t)(kc * 32 + 8 * gq + s) * C_OUT];
+                    for (int k = 0; k < RB; ++k) {
                         unsigned in = e_in[k] & kPairInMask;
                         in = in < in_max ? in : in_max;
                         const f32x4* src = (const f32x4*)(feats + (size_t)in * C_IN + 8 * gq);
@@ -335,81 +456,94 @@ __global__ __launch_bounds__(NB * 64) void k_conv_mfma(Geom g, const unsigned lo
                             R.a[k][kc][0] = src[kc * 8];
                             R.a[k][kc][1] = src[kc * 8 + 1];
                         }
-                        R.oaddr[k][0] = (e_out[k].x >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][1] = (e_out[k].y >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][2] = (e_out[k].z >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][3] = (e_out[k].w >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        // a stale entry past the end may name any row: keep the address inside the accumulators
+                        const unsigned r0 = e_out[k].x >> kPairRowShift, r1 = e_out[k].y >> kPairRowShift,
+                                       r2 = e_out[k].z >> kPairRowShift, r3 = e_out[k].w >> kPairRowShift;
+                        R.oaddr[k][0] = (r0 < kTileRows ? r0 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][1] = (r1 < kTileRows ? r1 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][2] = (r2 < kTileRows ? r2 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][3] = (r3 < kTileRows ? r3 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
                     }
                 };
-                // NBK blocks as straight-line code: independent fp32 MFMA chains (one per block and per 32 input
-                // channels), then the 16 x 16 results (rows = pairs 4*gq + v, column = channel 16*wave + jj) are added
-                // to the fp64 accumulators.  Padding pairs land in the dummy row.
-                auto compute_blocks = [&](auto nbk_tag, const GroupRegs<KC, GB>& R) {
+                // NBK blocks as straight-line code: independent fp32 MFMA chains (one per block, per 16 output
+                // channels and per 32 input channels), then the 16 x 16 results (rows = pairs 4*gq + v, column =
+                // channel 16*cb + jj) are added to the fp64 accumulators.  Padding pairs land in the dummy row.
+                auto compute_blocks = [&](auto nbk_tag, const RoundRegs<KC, NB, RB>& R) {
                     constexpr int NBK = decltype(nbk_tag)::value;
-                    f32x4 acc[NBK][KC];
 #pragma unroll
-                    for (int k = 0; k < NBK; ++k)
+                    for (int kc = 0; kc < KC; ++kc) {
+                        f32x4 acc[NBK][NB];
 #pragma unroll
-                        for (int kc = 0; kc < KC; ++kc) {
-                            f32x4 c = {0.f, 0.f, 0.f, 0.f};
+                        for (int k = 0; k < NBK; ++k)
 #pragma unroll
-                            for (int s = 0; s < 4; ++s)
-                                c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[k][kc][s], c, 0, 0, 0);
+                            for (int cb = 0; cb < NB; ++cb) {
+                                f32x4 c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                            for (int s = 0; s < 4; ++s)
-                                c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[k][kc][4 + s], c, 0, 0, 0);
-                            acc[k][kc] = c;
-                        }
+                                for (int s = 0; s < 4; ++s)
+                                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[kc][cb][0][s], c, 0, 0, 0);
 #pragma unroll
-                    for (int k = 0; k < NBK; ++k)
+                                for (int s = 0; s < 4; ++s)
+                                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][cb][1][s], c, 0, 0, 0);
+                                acc[k][cb] = c;
+                            }
 #pragma unroll
-                        for (int kc = 0; kc < KC; ++kc)
+                        for (int k = 0; k < NBK; ++k)
 #pragma unroll
-                            for (int v = 0; v < 4; ++v)
-                                __hip_atomic_fetch_add((double*)((unsigned char*)s_c + R.oaddr[k][v]),
-                                                       (double)acc[k][kc][v], __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_WORKGROUP);
+                            for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+                                for (int v = 0; v < 4; ++v)
+                                    __hip_atomic_fetch_add(
+                                        (double*)((unsigned char*)s_c + R.oaddr[k][v] + cb * 16 * sizeof(double)),
+                                        (double)acc[k][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
                 };
-                auto compute_group = [&](int gi, const GroupRegs<KC, GB>& R) {
-                    const int nb = n_blocks - gi * GB;  // >= 1
-                    if (nb >= GB) {
-                        compute_blocks(std::integral_constant<int, GB>{}, R);
-                    } else if constexpr (GB >= 2) {
+                auto compute_round = [&](int k_round, const RoundRegs<KC, NB, RB>& R) {
+                    const int nb = round_blocks(wave + kConvWaves * k_round).y;  // 1 .. RB
+                    if (nb >= RB) {
+                        compute_blocks(std::integral_constant<int, RB>{}, R);
+                    } else if constexpr (RB >= 2) {
                         if (nb == 1) compute_blocks(std::integral_constant<int, 1>{}, R);
-                        if constexpr (GB >= 4) {
+                        if constexpr (RB >= 3) {
                             if (nb == 2) compute_blocks(std::integral_constant<int, 2>{}, R);
+                        }
+                        if constexpr (RB >= 4) {
                             if (nb == 3) compute_blocks(std::integral_constant<int, 3>{}, R);
                         }
                     }
                 };
-                GroupRegs<KC, GB> r0, r1;
-                load_group(0, r0);
-                for (int gi = 0; gi < n_groups; gi += 2) {
-                    load_group(gi + 1, r1);
-                    compute_group(gi, r0);
-                    load_group(gi + 2, r0);
-                    if (gi + 1 < n_groups) compute_group(gi + 1, r1);
+                RoundRegs<KC, NB, RB> r0, r1;
+                load_round(0, r0);
+                for (int k_round = 0; k_round < my_rounds; k_round += 2) {
+                    load_round(k_round + 1, r1);
+                    compute_round(k_round, r0);
+                    load_round(k_round + 2, r0);
+                    if (k_round + 1 < my_rounds) compute_round(k_round + 1, r1);
                 }
             }
         }
         __syncthreads();
-        // ---- epilogue: one rounding to fp32, bias on the non-zero entries, planar store
-        for (int i = threadIdx.x; i < kTileRows * C_OUT; i += NT) {
-            const int r = i & (kTileRows - 1), oc = i >> 7;
-            float v = (float)s_c[r * CS + oc];
-            if (bias && v != 0.0f) v += bias[oc];
-            resp[((size_t)tile * C_OUT + oc) * kTileRows + r] = v;
+        // ---- epilogue: one rounding to fp32, bias on the non-zero entries, planar store; the accumulators are
+        //      reset on the way.  A thread handles four consecutive rows of one channel: one 16-byte store.
+        for (int i = threadIdx.x; i < (kTileRows / 4) * C_OUT; i += NT) {
+            const int r4 = (i & (kTileRows / 4 - 1)) * 4, oc = i / (kTileRows / 4);
+            f32x4 v;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float x = (float)s_c[(r4 + u) * CS + oc];
+                s_c[(r4 + u) * CS + oc] = 0.0;
+                if (bias && x != 0.0f) x += bias[oc];
+                v[u] = x;
+            }
+            *(f32x4*)(resp + ((size_t)tile * C_OUT + oc) * kTileRows + r4) = v;
         }
     }
 }
 
 template <int KC, int NB>
-static hipError_t launch_conv_mfma_t(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
-                                     long long nnz_in, const float* feats, const float* w, const float* bias,
-                                     const int* tap_active, const int* tap_coord, const unsigned* cand_lin,
-                                     const int* cand_start, const int* tile_start, const Counters* ctr, float* resp,
-                                     hipStream_t s) {
-    const size_t lds = conv_mfma_lds_bytes(NB * 16, g.T);
+static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* feats, const float* wb, const float* bias,
+                                     const unsigned* pairs, const unsigned short* block_tap, const uint2* tile_hdr,
+                                     const Counters* ctr, float* resp, hipStream_t s) {
+    const size_t lds = conv_mfma_lds_bytes(NB * 16);
     static size_t attr_lds = 0;
     if (attr_lds < lds) {
         hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<KC, NB>,
@@ -419,28 +553,25 @@ static hipError_t launch_conv_mfma_t(const Geom& g, const unsigned long long* oc
     }
     int per_cu = (int)((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;
-    if (per_cu * NB > 16) per_cu = 16 / NB;  // at most 16 waves per CU are useful here
-    const int grid = 256 * per_cu;           // a multiple of 8 (one span of tiles per XCD)
-    hipLaunchKernelGGL((k_conv_mfma<KC, NB>), dim3(grid), dim3(NB * 64), lds, s, g, occ, occ_prefix, nnz_in, feats, w,
-                       bias, tap_active, tap_coord, cand_lin, cand_start, tile_start, ctr, resp);
+    if (per_cu > 4) per_cu = 4;    // 16 waves per CU
+    const int grid = 256 * per_cu;  // a multiple of 8 (one span of tiles per XCD)
+    hipLaunchKernelGGL((k_conv_mfma<KC, NB>), dim3(grid), dim3(kConvWaves * 64), lds, s, taps, nnz_in, feats, wb, bias,
+                       pairs, block_tap, tile_hdr, ctr, resp);
     return hipGetLastError();
 }
 
 bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
-    if (g.E[0] > 32767 || g.E[1] > 32767 || g.E[2] > 32767) return false;  // sites are staged as 16-bit coordinates
+    if (g.T > 255) return false;  // block_tap holds the tap in one byte
     return c_in % 32 == 0 && c_in <= 128 && c_out % 16 == 0 && c_out <= 64 && nnz_in > 0 &&
            nnz_in < (1ll << kPairRowShift);
 }
 
-hipError_t launch_conv_mfma(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
-                            long long nnz_in, const float* feats, int c_in, const float* w, int c_out,
-                            const float* bias, const int* tap_active, const int* tap_coord,
-                            const unsigned* cand_lin, const int* cand_start, const int* tile_start,
-                            const Counters* ctr, float* resp, hipStream_t s) {
+hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
+                            const float* bias, const unsigned* pairs, const unsigned short* block_tap,
+                            const uint2* tile_hdr, const Counters* ctr, float* resp, hipStream_t s) {
 #define SCNN_MFMA_CASE(KC_, NB_)                                                                                  \
     if (c_in == KC_ * 32 && c_out == NB_ * 16)                                                                    \
-        return launch_conv_mfma_t<KC_, NB_>(g, occ, occ_prefix, nnz_in, feats, w, bias, tap_active, tap_coord,    \
-                                            cand_lin, cand_start, tile_start, ctr, resp, s);
+        return launch_conv_mfma_t<KC_, NB_>(g.T, nnz_in, feats, wb, bias, pairs, block_tap, tile_hdr, ctr, resp, s);
     SCNN_MFMA_CASE(1, 1) SCNN_MFMA_CASE(1, 2) SCNN_MFMA_CASE(1, 3) SCNN_MFMA_CASE(1, 4)
     SCNN_MFMA_CASE(2, 1) SCNN_MFMA_CASE(2, 2) SCNN_MFMA_CASE(2, 3) SCNN_MFMA_CASE(2, 4)
     SCNN_MFMA_CASE(3, 1) SCNN_MFMA_CASE(3, 2) SCNN_MFMA_CASE(3, 3) SCNN_MFMA_CASE(3, 4)

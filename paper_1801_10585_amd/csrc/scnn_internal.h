@@ -45,7 +45,8 @@ struct Counters {
     long long n_pool;     // rows after pooling
     unsigned flags;       // SCNN_FLAG_*
     int any_tie;          // some column needs tie ranks
-    int pad[2];
+    unsigned pair_blocks; // 16-pair blocks handed out to tiles so far (matrix-core path)
+    int pad[1];
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
@@ -187,11 +188,15 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
                             hipStream_t s);
 
 bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
-hipError_t launch_conv_mfma(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
-                            long long nnz_in, const float* feats, int c_in, const float* w, int c_out,
-                            const float* bias, const int* tap_active, const int* tap_coord,
-                            const unsigned* cand_lin, const int* cand_start, const int* tile_start,
-                            const Counters* ctr, float* resp, hipStream_t s);
+hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                             long long nnz_in, const int* tap_active, const int* tap_coord,
+                             const unsigned* cand_lin, const int* cand_start, const int* tile_start, Counters* ctr,
+                             unsigned* pairs, unsigned short* block_tap, uint2* tile_hdr, long long block_cap,
+                             long long tiles_cap, hipStream_t s);
+hipError_t launch_filter_mfma_layout(const Geom& g, const float* w, int c_in, int c_out, float* wb, hipStream_t s);
+hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
+                            const float* bias, const unsigned* pairs, const unsigned short* block_tap,
+                            const uint2* tile_hdr, const Counters* ctr, float* resp, hipStream_t s);
 
 // scnn_topk.hip
 hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,
