@@ -156,8 +156,8 @@ int scnn_set_conv_path(int path);
 
 /* Measurement support (not part of the method): when enabled on the calling
  * thread, every sparse_conv_fwd call records HIP events on its stream at the
- * boundaries of its stages (index build, candidate sites, convolution,
- * k-selection, compaction + write, pooling).  scnn_profile_collect waits for
+ * boundaries of its stages (index build, candidate sites, pair lists + weight
+ * layout, convolution, k-selection, compaction + write, pooling).  scnn_profile_collect waits for
  * the recorded calls, adds their per-stage milliseconds into stage_ms
  * [scnn_profile_stage_count()] and the number of calls into *calls, then
  * forgets them.  Host pointers. */
@@ -165,6 +165,11 @@ int scnn_profile_enable(int on);
 int scnn_profile_stage_count(void);
 const char* scnn_profile_stage_name(int stage);
 int scnn_profile_collect(double* stage_ms, int64_t* calls);
+
+/* A plain device-to-device streaming copy (bytes a multiple of 16, device
+ * pointers): the kernel of known traffic against which hardware memory
+ * counters are scaled when the library's kernels are profiled. */
+int scnn_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream);
 
 #ifdef __cplusplus
 }

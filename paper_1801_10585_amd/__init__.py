@@ -14,6 +14,7 @@ from .binding import (  # noqa: F401
     FLAG_UNSORTED,
     ScnnError,
     attention_topk,
+    calibration_copy,
     k_from_rho,
     library_path,
     profile_collect,

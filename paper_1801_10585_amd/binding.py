@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "scnn_last_error", "scnn_version", "scnn_k_from_rho", "sparse_conv_fwd_max_rows", "sparse_conv_fwd_workspace",
     "sparse_conv_fwd", "attention_topk_workspace", "attention_topk", "sparse_relu_workspace", "sparse_relu",
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
-    "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_profile_stage_name", "scnn_profile_collect",
+    "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
 ]
 
 
@@ -71,6 +71,8 @@ def load_library():
     L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
     L.scnn_validate_rows.restype = ci
     L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
+    L.scnn_calibration_copy.restype = ci
+    L.scnn_calibration_copy.argtypes = [vp, vp, sz, vp]
     L.scnn_set_conv_path.restype = ci
     L.scnn_set_conv_path.argtypes = [ci]
     L.scnn_profile_enable.restype = ci
@@ -294,3 +296,12 @@ def set_conv_path(path: int) -> None:
     """0 = choose the convolution kernel by shape, 1 = always the vector kernel."""
     L = load_library()
     _check(L, L.scnn_set_conv_path(int(path)))
+
+
+def calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Plain streaming copy of src into dst (same byte size, a multiple of 16)."""
+    L = load_library()
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("size mismatch")
+    _check(L, L.scnn_calibration_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)))

@@ -110,8 +110,8 @@ static long long default_cand_bound(const Geom& g, long long nnz_in) {
 
 
 // ---------------------------------------------------------------- per-stage timing (measurement support)
-static const char* const kStageNames[] = {"index_build", "candidates", "conv", "topk_select", "compact_write", "pool_finish"};
-static constexpr int kStages = 6;
+static const char* const kStageNames[] = {"index_build", "candidates", "conv_prepare", "conv", "topk_select", "compact_write", "pool_finish"};
+static constexpr int kStages = 7;
 struct ProfCall { hipEvent_t ev[kStages + 1]; };
 static thread_local bool g_prof_on = false;
 static thread_local std::vector<ProfCall>* g_prof_calls = nullptr;   // recorded, not yet collected
@@ -328,9 +328,11 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                                    ws.cand_start, ws.tile_start, ws.ctr, ws.pairs, ws.block_tap, ws.tile_hdr,
                                    ws.block_cap, ws.tiles_cap, s));
         SCNN_TRY(launch_filter_mfma_layout(g, w, c_in, c_out, ws.wb, s));
+        timer.mark();
         SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,
                                   ws.ctr, ws.resp, s));
     } else {
+        timer.mark();
         SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
                                   ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
     }
@@ -362,6 +364,12 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
 int scnn_set_conv_path(int path) {
     if (path != 0 && path != 1) return fail(SCNN_EINVAL, "conv path must be 0 (auto) or 1 (vector kernel)");
     g_conv_path = path;
+    return SCNN_OK;
+}
+
+int scnn_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!dst || !src || bytes % 16 != 0) return fail(SCNN_EINVAL, "calibration copy needs non-null pointers and a multiple of 16 bytes");
+    SCNN_TRY(launch_calibration_copy(dst, src, bytes, (hipStream_t)hip_stream));
     return SCNN_OK;
 }
 

@@ -465,49 +465,38 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                         R.oaddr[k][3] = (r3 < kTileRows ? r3 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
                     }
                 };
-                // NBK blocks as straight-line code: independent fp32 MFMA chains (one per block, per 16 output
-                // channels and per 32 input channels), then the 16 x 16 results (rows = pairs 4*gq + v, column =
-                // channel 16*cb + jj) are added to the fp64 accumulators.  Padding pairs land in the dummy row.
-                auto compute_blocks = [&](auto nbk_tag, const RoundRegs<KC, NB, RB>& R) {
-                    constexpr int NBK = decltype(nbk_tag)::value;
-#pragma unroll
-                    for (int kc = 0; kc < KC; ++kc) {
-                        f32x4 acc[NBK][NB];
-#pragma unroll
-                        for (int k = 0; k < NBK; ++k)
-#pragma unroll
-                            for (int cb = 0; cb < NB; ++cb) {
-                                f32x4 c = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                                for (int s = 0; s < 4; ++s)
-                                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[kc][cb][0][s], c, 0, 0, 0);
-#pragma unroll
-                                for (int s = 0; s < 4; ++s)
-                                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][cb][1][s], c, 0, 0, 0);
-                                acc[k][cb] = c;
-                            }
-#pragma unroll
-                        for (int k = 0; k < NBK; ++k)
-#pragma unroll
-                            for (int cb = 0; cb < NB; ++cb)
-#pragma unroll
-                                for (int v = 0; v < 4; ++v)
-                                    __hip_atomic_fetch_add(
-                                        (double*)((unsigned char*)s_c + R.oaddr[k][v] + cb * 16 * sizeof(double)),
-                                        (double)acc[k][cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    }
-                };
+                // A block = NB independent fp32 MFMA chains per 32 input channels (one per 16 output channels); the
+                // 16 x 16 results (rows = pairs 4*gq + v, column = channel 16*cb + jj) are added to the fp64
+                // accumulators.  Padding pairs land in the dummy row.  Blocks are guarded one by one (uniform
+                // branches) rather than through per-count variants, which the compiler would merge again through
+                // scratch memory.
                 auto compute_round = [&](int k_round, const RoundRegs<KC, NB, RB>& R) {
                     const int nb = round_blocks(wave + kConvWaves * k_round).y;  // 1 .. RB
-                    if (nb >= RB) {
-                        compute_blocks(std::integral_constant<int, RB>{}, R);
-                    } else if constexpr (RB >= 2) {
-                        if (nb == 1) compute_blocks(std::integral_constant<int, 1>{}, R);
-                        if constexpr (RB >= 3) {
-                            if (nb == 2) compute_blocks(std::integral_constant<int, 2>{}, R);
-                        }
-                        if constexpr (RB >= 4) {
-                            if (nb == 3) compute_blocks(std::integral_constant<int, 3>{}, R);
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        if (k < nb) {
+#pragma unroll
+                            for (int kc = 0; kc < KC; ++kc) {
+                                f32x4 acc[NB];
+#pragma unroll
+                                for (int cb = 0; cb < NB; ++cb) {
+                                    f32x4 c = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                    for (int s = 0; s < 4; ++s)
+                                        c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[kc][cb][0][s], c, 0, 0, 0);
+#pragma unroll
+                                    for (int s = 0; s < 4; ++s)
+                                        c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][cb][1][s], c, 0, 0, 0);
+                                    acc[cb] = c;
+                                }
+#pragma unroll
+                                for (int cb = 0; cb < NB; ++cb)
+#pragma unroll
+                                    for (int v = 0; v < 4; ++v)
+                                        __hip_atomic_fetch_add(
+                                            (double*)((unsigned char*)s_c + R.oaddr[k][v] + cb * 16 * sizeof(double)),
+                                            (double)acc[cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            }
                         }
                     }
                 };

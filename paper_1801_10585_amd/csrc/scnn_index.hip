@@ -30,6 +30,23 @@ hipError_t launch_zero(void* p, size_t bytes, hipStream_t s) {
     return hipGetLastError();
 }
 
+// Plain streaming copy of a known size: the yardstick against which the memory-traffic counters of the
+// other kernels are scaled.
+__global__ void k_calibration_copy(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(k_calibration_copy, dim3((unsigned)blocks), dim3(256), 0, s, (uint4*)dst, (const uint4*)src, n16);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ scan
 __global__ __launch_bounds__(256) void k_scan_local(unsigned* __restrict__ vals, long long n_imm,
                                                     const long long* __restrict__ n_dev,

@@ -151,6 +151,7 @@ struct ScanBufs {
 
 // fill `words` 32-bit words with zero
 hipError_t launch_zero(void* p, size_t bytes, hipStream_t s);
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t s);
 
 // In-place exclusive scan of vals[0..n) (n read from *n_dev if n_dev != nullptr, else n_imm; n <= capacity).
 // total (if non-null) receives the sum as long long.
