@@ -60,6 +60,7 @@ extern "C" {
 #define SCNN_FLAG_OUT_OVERFLOW 2u  /* more output rows than out_capacity: output truncated */
 #define SCNN_FLAG_BAD_COORD 4u     /* an input row had a coordinate outside the grid: row skipped */
 #define SCNN_FLAG_UNSORTED 8u      /* input rows not strictly ascending by (b, lin): result undefined */
+#define SCNN_FLAG_INTERNAL 16u     /* a bounded device-side wait ran out: result invalid (should never happen) */
 
 #define SCNN_TOPK_ABS 0    /* keep the k responses of largest magnitude (Sec. 3.2, second variant) */
 #define SCNN_TOPK_SIGNED 1 /* keep the k largest raw responses       (Sec. 3.2, first variant)  */

@@ -155,6 +155,7 @@ struct ConvWs {
     unsigned long long* pbits;
     unsigned* hist;
     ColState* cols;
+    unsigned long long* tile_state;
     size_t zero_bytes;
     // not zeroed
     unsigned* occ_prefix;
@@ -168,8 +169,8 @@ struct ConvWs {
     double* wp;
     unsigned* cand_lin;
     float* resp;
-    unsigned* eqcnt;
-    unsigned* tile_rows;
+    uint2* side;
+    unsigned long long side_cap;
     unsigned* pairs;
     unsigned short* block_tap;
     float* wb;
@@ -201,6 +202,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->pbits = c.take<unsigned long long>(pool ? nwp : 0);
     w->hist = c.take<unsigned>(ncols * kHistBins);
     w->cols = c.take<ColState>(ncols);
+    w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
     w->occ_prefix = c.take<unsigned>(nw);
     w->cand_prefix = c.take<unsigned>(nw);
@@ -216,8 +218,8 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->wp = c.take<double>((size_t)g.T * c_in * w->c_out_pad);
     w->cand_lin = c.take<unsigned>(cand_cap);
     w->resp = c.take<float>((size_t)w->tiles_cap * c_out * kTileRows);
-    w->eqcnt = c.take<unsigned>((size_t)w->tiles_cap * c_out);
-    w->tile_rows = c.take<unsigned>(w->tiles_cap);
+    w->side_cap = (unsigned long long)w->tiles_cap * kTileRows * c_out;
+    w->side = c.take<uint2>((size_t)w->side_cap);
     // matrix-core path: every (input row, tap) gives at most one pair; a tile reserves whole blocks per active tap
     w->block_cap = conv_mfma_supported(g, c_in, c_out, nnz_in) ? (long long)g.T * (cand_cap / 16 + w->tiles_cap) : 0;
     w->pairs = c.take<unsigned>((size_t)w->block_cap * 16);
@@ -337,19 +339,19 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                                   ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
     }
     timer.mark();
-    SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.eqcnt, ws.ctr,
-                         ws.tiles_cap, s));
+    SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
+                         ws.ctr, s));
     timer.mark();
     if (!pool) {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
-                                     ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr,
-                                     out_coords, out_feats, out_capacity, &ws.ctr->n_rows, s));
+                                     ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats,
+                                     out_capacity, s));
         timer.mark();
         SCNN_TRY(launch_finish(ws.ctr, 0, 0, 1, out_capacity, (long long*)nnz_out, s));
     } else {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
-                                     ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr,
-                                     ws.tmp_coords, ws.tmp_feats, ws.cand_cap, &ws.ctr->n_rows, s));
+                                     ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, ws.tmp_coords, ws.tmp_feats,
+                                     ws.cand_cap, s));
         timer.mark();
         SCNN_TRY(launch_zero(ws.occ, (size_t)nw * sizeof(unsigned long long), s));
         SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1, ws.occ,
@@ -407,14 +409,15 @@ struct TopkWs {
     Counters* ctr;
     unsigned* hist;
     ColState* cols;
+    unsigned long long* tile_state;
     size_t zero_bytes;
     unsigned* block_sums;
     int* cand_start;
     int* tile_start;
     unsigned* cand_lin;
     float* resp;
-    unsigned* eqcnt;
-    unsigned* tile_rows;
+    uint2* side;
+    unsigned long long side_cap;
     long long tiles_cap;
     size_t total;
 };
@@ -425,14 +428,15 @@ void carve_topk(void* base, const Geom& g, long long rows, int channels, TopkWs*
     w->ctr = c.take<Counters>(1);
     w->hist = c.take<unsigned>(ncols * kHistBins);
     w->cols = c.take<ColState>(ncols);
+    w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
     w->block_sums = c.take<unsigned>(scan_blocks(w->tiles_cap));
     w->cand_start = c.take<int>(g.batch + 1);
     w->tile_start = c.take<int>(g.batch + 1);
     w->cand_lin = c.take<unsigned>(rows > 0 ? rows : 1);
     w->resp = c.take<float>((size_t)w->tiles_cap * channels * kTileRows);
-    w->eqcnt = c.take<unsigned>((size_t)w->tiles_cap * channels);
-    w->tile_rows = c.take<unsigned>(w->tiles_cap);
+    w->side_cap = (unsigned long long)w->tiles_cap * kTileRows * channels;
+    w->side = c.take<uint2>((size_t)w->side_cap);
     w->total = c.total();
 }
 }  // namespace
@@ -471,11 +475,11 @@ int attention_topk(int ndim, const int32_t* extent, int batch, const int32_t* co
     SCNN_TRY(launch_rows_sample_bounds(g, coords, rows, ws.cand_start, ws.tile_start, ws.ctr, s));
     SCNN_TRY(launch_rows_to_planar(g, coords, resp, channels, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
                                    ws.cand_lin, ws.resp, s));
-    SCNN_TRY(launch_topk(g, channels, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.eqcnt, ws.ctr,
-                         ws.tiles_cap, s));
+    SCNN_TRY(launch_topk(g, channels, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
+                         ws.ctr, s));
     SCNN_TRY(launch_select_write(g, channels, topk_mode, 0, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
-                                 ws.cols, ws.eqcnt, ws.tile_rows, ws.block_sums, ws.tiles_cap, ws.ctr, out_coords,
-                                 out_feats, out_capacity, &ws.ctr->n_rows, s));
+                                 ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats, out_capacity,
+                                 s));
     SCNN_TRY(launch_finish(ws.ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
     return SCNN_OK;
 }

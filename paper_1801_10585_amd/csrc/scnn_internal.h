@@ -34,7 +34,10 @@ struct ColState {
     unsigned q;         // how many of those survive (lowest lin first)
     unsigned n_nz;      // non-zero entries in the column
     int done;           // 1 = selection settled (bypass or k == 0), later passes skip the column
-    int need_tie;       // 1 = q < n_eq: ranks among equals decide
+    unsigned cut;       // equal entries survive up to this position in the column (0xffffffff: all of them)
+    unsigned side_fill; // side-buffer entries written so far
+    unsigned pad;
+    unsigned long long side_off;  // first side-buffer entry of the column
 };
 
 // Device-resident counters produced on the way.
@@ -46,7 +49,8 @@ struct Counters {
     unsigned flags;       // SCNN_FLAG_*
     int any_tie;          // some column needs tie ranks
     unsigned pair_blocks; // 16-pair blocks handed out to tiles so far (matrix-core path)
-    int pad[1];
+    unsigned ticket;      // next tile of the compaction pass
+    unsigned long long side_cursor;  // side-buffer entries handed out to columns so far
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
@@ -206,13 +210,13 @@ hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const flo
                                  const int* cand_start, const int* tile_start, const Counters* ctr,
                                  long long tiles_cap, unsigned* cand_lin, float* resp, hipStream_t s);
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
-                       const float* resp, ColState* cols, unsigned* hist, unsigned* eqcnt, Counters* ctr,
-                       long long tiles_cap, hipStream_t s);
+                       const float* resp, ColState* cols, unsigned* hist, uint2* side, unsigned long long side_cap,
+                       Counters* ctr, hipStream_t s);
 hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
-                               const ColState* cols, const unsigned* eqcnt, unsigned* tile_rows,
-                               unsigned* scan_block_sums, long long tiles_cap, Counters* ctr, int32_t* out_coords,
-                               float* out_feats, long long out_capacity, long long* n_rows_out, hipStream_t s);
+                               const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
+                               Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
+                               hipStream_t s);
 
 // scnn_rows.hip
 hipError_t launch_relu(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,

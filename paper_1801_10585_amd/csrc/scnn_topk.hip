@@ -3,12 +3,18 @@
 // surviving sites into sorted output rows.
 //
 // Selection = most-significant-digit radix select on an order-preserving 32-bit
-// key of the score (three passes of 11 + 11 + 10 bits, histogram in LDS, one
-// (column, slice) per workgroup).  It yields the exact k-th largest key tau,
-// the number n_eq of entries equal to it and how many of those, q, still fit.
-// An entry survives iff  key > tau, or key == tau and it is among the q equal
-// entries of lowest lin.  Candidate sites are stored in ascending lin, so that
-// rank is a prefix count over the column.
+// key of the score.  The first digit (11 bits) is histogrammed over the whole
+// response matrix; the entries that fall into the bin holding the k-th
+// strongest one -- a few percent -- are then copied, with their position in the
+// column, to a side buffer, and the remaining digits (11 + 10 bits) are settled
+// there by one workgroup per column.  That yields the exact k-th largest key
+// tau, the number n_eq of entries equal to it and how many of those, q, still
+// fit.  An entry survives iff  key > tau, or key == tau and it is among the q
+// equal entries of lowest lin; candidate sites are stored in ascending lin, so
+// "lowest lin" is "smallest position", and the q-th smallest position among the
+// equal entries (a second, ascending radix select on the side buffer) is the
+// cut.  The response matrix is read three times in all: histogram, collection,
+// and the final mask + compaction + write.
 #include "scnn_internal.h"
 
 namespace scnn {
@@ -97,34 +103,50 @@ hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const flo
 }
 
 // ------------------------------------------------------------------ radix select
-__device__ inline void pass_bits(int pass, int& shift, int& bits) {
-    shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0);
-    bits = pass == 2 ? 10 : 11;
+constexpr int kSideStage = 2048;  // side-buffer entries staged in LDS per workgroup before a flush
+
+// Rank search in a 2048-bin histogram held in LDS.  descending: find the bin holding the kk-th entry counted from
+// the top bin; else from the bottom bin.  Returns the bin and the number of entries strictly before it in that
+// order.  1 <= kk <= total must hold.  Contains __syncthreads(); s_res is two shared words.
+__device__ inline void block_pick(const unsigned* s_h, long long kk, bool descending, unsigned* s_wave, int* s_res,
+                                  int& bin_out, unsigned& before_out) {
+    unsigned local = 0;  // thread t owns bins [8t, 8t+8)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) local += s_h[threadIdx.x * 8 + i];
+    unsigned total;
+    const unsigned excl = block_exclusive_scan_256(local, s_wave, total);
+    const unsigned before_threads = descending ? total - excl - local : excl;
+    if ((long long)before_threads < kk && kk <= (long long)before_threads + (long long)local) {
+        unsigned before = before_threads;
+        int bin = descending ? threadIdx.x * 8 + 7 : threadIdx.x * 8;
+        for (int i = 0; i < 7; ++i) {
+            const unsigned c = s_h[bin];
+            if (kk <= (long long)before + (long long)c) break;
+            before += c;
+            bin += descending ? -1 : 1;
+        }
+        s_res[0] = bin;
+        s_res[1] = (int)before;
+    }
+    __syncthreads();
+    bin_out = s_res[0];
+    before_out = (unsigned)s_res[1];
+    __syncthreads();
 }
 
-// grid = (columns, slices).  Histogram of the current digit over the entries of
-// the column that match the prefix found so far.
-__global__ __launch_bounds__(256) void k_hist(int pass, int mode, int channels,
-                                              const int* __restrict__ tile_start, const float* __restrict__ resp,
-                                              const ColState* __restrict__ cols, unsigned* __restrict__ hist) {
+// grid = (columns, slices).  Histogram of the top 11 key bits over the column's entries.
+__global__ __launch_bounds__(256) void k_hist0(int mode, int channels, const int* __restrict__ tile_start,
+                                               const float* __restrict__ resp, unsigned* __restrict__ hist) {
     __shared__ unsigned s_hist[kHistBins];
     const int col = blockIdx.x;
-    const ColState st = cols[col];
-    if (pass > 0 && st.done) return;
     const int b = col / channels, oc = col - b * channels;
     for (int i = threadIdx.x; i < kHistBins; i += 256) s_hist[i] = 0;
     __syncthreads();
-    int shift, bits;
-    pass_bits(pass, shift, bits);
-    const unsigned mask = (1u << bits) - 1u;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
     const int r = threadIdx.x & (kTileRows - 1);
     for (int tile = t0 + blockIdx.y * 2 + (threadIdx.x >> 7); tile < t1; tile += 2 * gridDim.y) {
-        const float v = resp[((size_t)tile * channels + oc) * kTileRows + r];
-        const unsigned key = score_key(v, mode);
-        if (key == 0u) continue;
-        if (pass > 0 && (key >> (shift + bits)) != st.prefix) continue;
-        atomicAdd(&s_hist[(key >> shift) & mask], 1u);
+        const unsigned key = score_key(resp[((size_t)tile * channels + oc) * kTileRows + r], mode);
+        if (key != 0u) atomicAdd(&s_hist[key >> 21], 1u);
     }
     __syncthreads();
     unsigned* gh = hist + (size_t)col * kHistBins;
@@ -134,154 +156,200 @@ __global__ __launch_bounds__(256) void k_hist(int pass, int mode, int channels,
     }
 }
 
-// One block per column: find the bin that holds the k_rem-th strongest entry,
-// extend the prefix, clear the histogram for the next pass.
-__global__ __launch_bounds__(256) void k_pick(int pass, long long k, ColState* __restrict__ cols,
-                                              unsigned* __restrict__ hist, Counters* ctr) {
+// One block per column: the bin of the k-th strongest entry, and a slice of the side buffer for that bin.
+__global__ __launch_bounds__(256) void k_pick0(long long k, ColState* __restrict__ cols,
+                                               const unsigned* __restrict__ hist, Counters* ctr,
+                                               unsigned long long side_cap) {
     __shared__ unsigned s_h[kHistBins];
     __shared__ unsigned s_wave[4];
+    __shared__ int s_res[2];
     const int col = blockIdx.x;
-    ColState st;
-    if (pass == 0) {
-        st.prefix = 0; st.tau = 0; st.k_rem = k; st.n_eq = 0; st.q = 0; st.n_nz = 0; st.done = 0; st.need_tie = 0;
-    } else {
-        st = cols[col];
-        if (st.done) return;  // uniform over the block
-    }
-    unsigned* gh = hist + (size_t)col * kHistBins;
-    unsigned local = 0;  // thread t owns bins [8t, 8t+8); bin 2047 is the strongest
+    const unsigned* gh = hist + (size_t)col * kHistBins;
+    unsigned local = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const unsigned c = gh[threadIdx.x * 8 + i];
         s_h[threadIdx.x * 8 + i] = c;
-        gh[threadIdx.x * 8 + i] = 0;
         local += c;
     }
     unsigned total;
-    const unsigned excl = block_exclusive_scan_256(local, s_wave, total);
-    if (pass == 0) {
-        st.n_nz = total;
-        if (k <= 0) {
-            st.done = 1;
-            st.tau = 0xffffffffu;  // no key is stronger: nothing survives
-        } else if ((long long)total <= k) {
-            st.done = 1;           // fewer entries than k: all survive (tau = 0, every non-zero key is above it)
-        }
-        if (st.done) {
-            if (threadIdx.x == 0) cols[col] = st;
-            return;
-        }
+    (void)block_exclusive_scan_256(local, s_wave, total);
+    ColState st;
+    st.prefix = 0; st.tau = 0; st.k_rem = k; st.n_eq = 0; st.q = 0; st.n_nz = total; st.done = 0; st.cut = 0xffffffffu;
+    st.side_off = 0; st.side_fill = 0; st.pad = 0;
+    if (k <= 0) {
+        st.done = 1;
+        st.tau = 0xffffffffu;  // no key is stronger: nothing survives
+    } else if ((long long)total <= k) {
+        st.done = 1;           // fewer entries than k: all survive (tau = 0, every non-zero key is above it)
     }
-    // Here 1 <= k_rem <= total, so exactly one thread owns the crossing bin.
-    const unsigned above_threads = total - excl - local;  // entries in bins owned by higher threads
-    const long long k_rem = st.k_rem;
-    if ((long long)above_threads < k_rem && k_rem <= (long long)above_threads + (long long)local) {
-        unsigned above = above_threads;
-        int bin = threadIdx.x * 8 + 7;
-        for (; bin > (int)threadIdx.x * 8; --bin) {
-            const unsigned c = s_h[bin];
-            if (k_rem <= (long long)above + (long long)c) break;
-            above += c;
+    if (st.done) {
+        if (threadIdx.x == 0) cols[col] = st;
+        return;
+    }
+    int bin;
+    unsigned before;
+    block_pick(s_h, k, true, s_wave, s_res, bin, before);
+    if (threadIdx.x == 0) {
+        st.prefix = (unsigned)bin;
+        st.k_rem = k - (long long)before;
+        st.n_eq = s_h[bin];  // for now: entries in the bin = entries the side buffer will hold
+        const unsigned long long off = atomicAdd(&ctr->side_cursor, (unsigned long long)st.n_eq);
+        if (off + st.n_eq > side_cap) {  // cannot happen with the documented workspace size
+            atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+            st.done = 1;
+            st.tau = 0xffffffffu;
         }
-        int shift, bits;
-        pass_bits(pass, shift, bits);
-        st.prefix = (st.prefix << bits) | (unsigned)bin;
-        st.k_rem = k_rem - (long long)above;
-        if (pass == 2) {
-            st.tau = st.prefix;
-            st.n_eq = s_h[bin];
-            st.q = (unsigned)st.k_rem;
-            st.need_tie = st.q < st.n_eq ? 1 : 0;
-            if (st.need_tie) ctr->any_tie = 1;
-        }
+        st.side_off = off;
         cols[col] = st;
     }
 }
 
-// Tiles are in ascending (b, lin): the rank of an entry among the entries equal
-// to tau is (equal entries in earlier tiles of its column) + (equal entries
-// before it in its tile).  These two kernels produce the first term, only for
-// columns whose equal entries do not all survive.
-__global__ __launch_bounds__(256) void k_tie_count(Geom g, int mode, int channels,
-                                                   const int* __restrict__ tile_start,
-                                                   const float* __restrict__ resp,
-                                                   const ColState* __restrict__ cols,
-                                                   unsigned* __restrict__ eqcnt, const Counters* __restrict__ ctr) {
-    if (!ctr->any_tie) return;
-    const int n_tiles = (int)ctr->n_tiles;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        const int b = sample_of_tile(tile_start, g.batch, tile);
-        for (int oc = wave; oc < channels; oc += 4) {
-            const ColState* st = cols + (size_t)b * channels + oc;
-            if (!st->need_tie) continue;
-            const unsigned tau = st->tau;
-            const float* seg = resp + ((size_t)tile * channels + oc) * kTileRows;
-            const unsigned long long m0 = __ballot(score_key(seg[lane], mode) == tau);
-            const unsigned long long m1 = __ballot(score_key(seg[64 + lane], mode) == tau);
-            if (lane == 0) eqcnt[(size_t)tile * channels + oc] = (unsigned)(__popcll(m0) + __popcll(m1));
-        }
-    }
-}
-
-__global__ __launch_bounds__(256) void k_tie_scan(int channels, const int* __restrict__ tile_start,
-                                                  const ColState* __restrict__ cols, unsigned* __restrict__ eqcnt,
-                                                  const Counters* __restrict__ ctr) {
-    __shared__ unsigned s_wave[4];
-    if (!ctr->any_tie) return;
+// grid = (columns, slices).  Copy the entries of the threshold bin, with their position in the column, to the
+// column's slice of the side buffer (order within the slice does not matter).
+__global__ __launch_bounds__(256) void k_collect(int mode, int channels, const int* __restrict__ tile_start,
+                                                 const float* __restrict__ resp, ColState* __restrict__ cols,
+                                                 uint2* __restrict__ side) {
+    __shared__ uint2 s_buf[kSideStage];
+    __shared__ unsigned s_n;
+    __shared__ unsigned s_base;
     const int col = blockIdx.x;
-    if (!cols[col].need_tie) return;
+    const ColState st = cols[col];
+    if (st.done) return;
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    unsigned carry = 0;
-    for (int start = t0; start < t1; start += 256) {
-        const int tile = start + threadIdx.x;
-        const unsigned v = tile < t1 ? eqcnt[(size_t)tile * channels + oc] : 0u;
-        unsigned total;
-        const unsigned excl = block_exclusive_scan_256(v, s_wave, total);
-        if (tile < t1) eqcnt[(size_t)tile * channels + oc] = carry + excl;
-        carry += total;
+    const int r = threadIdx.x & (kTileRows - 1);
+    if (threadIdx.x == 0) s_n = 0;
+    __syncthreads();
+    auto flush = [&]() {  // called by all threads, with s_n stable
+        const unsigned n = s_n;
+        if (threadIdx.x == 0) s_base = atomicAdd(&cols[col].side_fill, n);
+        __syncthreads();
+        for (unsigned i = threadIdx.x; i < n; i += 256) side[st.side_off + s_base + i] = s_buf[i];
+        __syncthreads();
+        if (threadIdx.x == 0) s_n = 0;
+        __syncthreads();
+    };
+    for (int tile0 = t0 + blockIdx.y * 2; tile0 < t1; tile0 += 2 * gridDim.y) {
+        const int tile = tile0 + (threadIdx.x >> 7);
+        if (tile < t1) {
+            const unsigned key = score_key(resp[((size_t)tile * channels + oc) * kTileRows + r], mode);
+            if (key != 0u && (key >> 21) == st.prefix) {
+                const unsigned idx = atomicAdd(&s_n, 1u);
+                s_buf[idx] = make_uint2(key, (unsigned)(tile - t0) * kTileRows + (unsigned)r);
+            }
+        }
+        __syncthreads();
+        if (s_n > kSideStage - 256) flush();
+    }
+    if (s_n > 0) flush();
+}
+
+// One block per column: settle the remaining 21 key bits on the side buffer, then, if the equal entries do not all
+// fit, the position below which they do.
+__global__ __launch_bounds__(256) void k_side_select(ColState* __restrict__ cols, const uint2* __restrict__ side) {
+    __shared__ unsigned s_h[kHistBins];
+    __shared__ unsigned s_wave[4];
+    __shared__ int s_res[2];
+    const int col = blockIdx.x;
+    ColState st = cols[col];
+    if (st.done) return;
+    const uint2* e = side + st.side_off;
+    const unsigned m = st.n_eq;
+    auto clear = [&]() {
+        for (int i = threadIdx.x; i < kHistBins; i += 256) s_h[i] = 0;
+        __syncthreads();
+    };
+    // key bits [20:10]
+    clear();
+    for (unsigned i = threadIdx.x; i < m; i += 256) atomicAdd(&s_h[(e[i].x >> 10) & 0x7ffu], 1u);
+    __syncthreads();
+    int bin;
+    unsigned before;
+    block_pick(s_h, st.k_rem, true, s_wave, s_res, bin, before);
+    const unsigned prefix2 = (st.prefix << 11) | (unsigned)bin;
+    long long k_rem = st.k_rem - (long long)before;
+    // key bits [9:0]
+    clear();
+    for (unsigned i = threadIdx.x; i < m; i += 256) {
+        const unsigned key = e[i].x;
+        if ((key >> 10) == prefix2) atomicAdd(&s_h[key & 0x3ffu], 1u);
+    }
+    __syncthreads();
+    block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);
+    const unsigned tau = (prefix2 << 10) | (unsigned)bin;
+    const unsigned n_eq = s_h[bin];
+    const unsigned q = (unsigned)(k_rem - (long long)before);  // 1 <= q <= n_eq
+    __syncthreads();
+    unsigned cut = 0xffffffffu;
+    if (q < n_eq) {
+        // q-th smallest position among the entries equal to tau: ascending radix select on the position
+        unsigned pprefix = 0;
+        long long rank = q;
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0), bits = pass == 2 ? 10 : 11;
+            clear();
+            for (unsigned i = threadIdx.x; i < m; i += 256) {
+                const uint2 x = e[i];
+                if (x.x == tau && (pass == 0 || (x.y >> (shift + bits)) == pprefix))
+                    atomicAdd(&s_h[(x.y >> shift) & ((1u << bits) - 1u)], 1u);
+            }
+            __syncthreads();
+            block_pick(s_h, rank, false, s_wave, s_res, bin, before);
+            pprefix = (pprefix << bits) | (unsigned)bin;
+            rank -= (long long)before;
+        }
+        cut = pprefix;
+    }
+    if (threadIdx.x == 0) {
+        st.tau = tau;
+        st.n_eq = n_eq;
+        st.q = q;
+        st.cut = cut;
+        cols[col] = st;
     }
 }
 
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
-                       const float* resp, ColState* cols, unsigned* hist, unsigned* eqcnt, Counters* ctr,
-                       long long tiles_cap, hipStream_t s) {
+                       const float* resp, ColState* cols, unsigned* hist, uint2* side, unsigned long long side_cap,
+                       Counters* ctr, hipStream_t s) {
     const int ncols = g.batch * channels;
     int slices = 2048 / (ncols > 0 ? ncols : 1);
     if (slices < 1) slices = 1;
     if (slices > 64) slices = 64;
-    for (int pass = 0; pass < 3; ++pass) {
-        hipLaunchKernelGGL(k_hist, dim3(ncols, slices), dim3(256), 0, s, pass, mode, channels, tile_start, resp,
-                           cols, hist);
-        hipLaunchKernelGGL(k_pick, dim3(ncols), dim3(256), 0, s, pass, k, cols, hist, ctr);
-    }
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 2048 ? 2048 : tiles_cap);
-    hipLaunchKernelGGL(k_tie_count, dim3((unsigned)blocks), dim3(256), 0, s, g, mode, channels, tile_start, resp,
-                       cols, eqcnt, ctr);
-    hipLaunchKernelGGL(k_tie_scan, dim3(ncols), dim3(256), 0, s, channels, tile_start, cols, eqcnt, ctr);
+    hipLaunchKernelGGL(k_hist0, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, hist);
+    hipLaunchKernelGGL(k_pick0, dim3(ncols), dim3(256), 0, s, k, cols, hist, ctr, side_cap);
+    hipLaunchKernelGGL(k_collect, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, cols, side);
+    hipLaunchKernelGGL(k_side_select, dim3(ncols), dim3(256), 0, s, cols, side);
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ keep mask, ReLU, compaction
-// WRITE = false: count the surviving rows of every tile.
-// WRITE = true : tile_rows holds the scanned row offsets; write the rows.
-template <bool WRITE>
-__global__ __launch_bounds__(256) void k_select(Geom g, int channels, int mode, int relu,
-                                                const int* __restrict__ cand_start,
-                                                const int* __restrict__ tile_start,
-                                                const unsigned* __restrict__ cand_lin,
-                                                const float* __restrict__ resp, const ColState* __restrict__ cols,
-                                                const unsigned* __restrict__ eqcnt, unsigned* __restrict__ tile_rows,
-                                                const Counters* __restrict__ ctr, int32_t* __restrict__ out_coords,
-                                                float* __restrict__ out_feats, long long out_capacity) {
+// ------------------------------------------------------------------ keep mask, ReLU, compaction, write (one pass)
+// Tiles are taken in ascending order through a ticket counter; the number of surviving rows before a tile comes
+// from a decoupled look-back over per-tile status words {status, count}: a tile first publishes its own count,
+// then walks back over its predecessors' words until it meets an inclusive prefix.  A predecessor always belongs
+// to a workgroup that is already running (tickets are handed out in order), so the wait is short; it is bounded
+// all the same, and a wait that runs out is reported in the status bits instead of hanging.
+constexpr unsigned long long kStateAggregate = 1ull << 62, kStateInclusive = 2ull << 62, kStateValueMask = (1ull << 62) - 1;
+constexpr int kLookbackSpinLimit = 1 << 22;
+
+__global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int mode, int relu,
+                                                      const int* __restrict__ cand_start,
+                                                      const int* __restrict__ tile_start,
+                                                      const unsigned* __restrict__ cand_lin,
+                                                      const float* __restrict__ resp,
+                                                      const ColState* __restrict__ cols,
+                                                      unsigned long long* tile_state, Counters* ctr,
+                                                      int32_t* __restrict__ out_coords, float* __restrict__ out_feats,
+                                                      long long out_capacity) {
     __shared__ unsigned s_tau[1024];
-    __shared__ unsigned s_q[1024];
-    __shared__ unsigned char s_tie[1024];
+    __shared__ unsigned s_cut[1024];
     __shared__ unsigned s_flag[kTileRows];
     __shared__ int s_rank[kTileRows];
     __shared__ int s_wcount[2];
-    __shared__ float s_v[WRITE ? kTileRows : 1][65];
+    __shared__ float s_v[kTileRows][65];
+    __shared__ int s_ticket;
+    __shared__ long long s_base;
 
     const int n_tiles = (int)ctr->n_tiles;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -289,79 +357,101 @@ __global__ __launch_bounds__(256) void k_select(Geom g, int channels, int mode, 
     const int n_chunks = (channels + 63) / 64;
     int cur_b = -1;
 
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    for (;;) {
+        __syncthreads();  // s_ticket and the tile buffers of the previous round are no longer read
+        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        __syncthreads();
+        const int tile = s_ticket;
+        if (tile >= n_tiles) break;
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
-        __syncthreads();
+        const unsigned pos0 = (unsigned)(tile - tile_start[b]) * kTileRows;  // position of row 0 in its column
         if (b != cur_b) {
             for (int c = threadIdx.x; c < channels; c += 256) {
                 const ColState* st = cols + (size_t)b * channels + c;
                 s_tau[c] = st->tau;
-                s_q[c] = st->q;
-                s_tie[c] = (unsigned char)st->need_tie;
+                s_cut[c] = st->cut;
             }
             cur_b = b;
         }
         if (threadIdx.x < kTileRows) s_flag[threadIdx.x] = 0;
         __syncthreads();
 
-        // One wave handles one channel over the tile's 128 rows (two halves, ascending lin).
+        // One wave handles one channel over the tile's 128 rows.
         auto process = [&](int oc, bool stage, int cc) {
             const float* seg = resp + ((size_t)tile * channels + oc) * kTileRows;
-            const unsigned tau = s_tau[oc], q = s_q[oc];
-            unsigned running = s_tie[oc] ? eqcnt[(size_t)tile * channels + oc] : 0u;
+            const unsigned tau = s_tau[oc], cut = s_cut[oc];
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const int r = half * 64 + lane;
                 const float v = seg[r];
                 const unsigned key = score_key(v, mode);
-                const bool eq = (key == tau) && key != 0u;
-                const unsigned long long m = __ballot(eq);
-                bool keep = key > tau;
-                if (eq) keep = (running + (unsigned)__popcll(m & lt_mask)) < q;
-                running += (unsigned)__popcll(m);
+                bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
                 if (relu) keep = keep && (v > 0.0f);
                 if (keep) s_flag[r] = 1u;
-                if (WRITE && stage) s_v[r][oc - cc] = keep ? v : 0.0f;
+                if (stage) s_v[r][oc - cc] = keep ? v : 0.0f;
             }
         };
-
-        if (!WRITE || n_chunks > 1) {
+        if (n_chunks > 1) {  // row flags need every channel before the first chunk can be written
             for (int oc = wave; oc < channels; oc += 4) process(oc, false, 0);
-            __syncthreads();
+        } else {
+            for (int oc = wave; oc < channels; oc += 4) process(oc, true, 0);
         }
-        if (!WRITE) {
-            if (threadIdx.x < kTileRows) {
-                const unsigned long long m = __ballot(s_flag[threadIdx.x] != 0u);
-                if (lane == 0) s_wcount[wave] = __popcll(m);
+        __syncthreads();
+        if (threadIdx.x < kTileRows) {
+            const unsigned long long m = __ballot(s_flag[threadIdx.x] != 0u);
+            s_rank[threadIdx.x] = __popcll(m & lt_mask);
+            if (lane == 0) s_wcount[wave] = __popcll(m);
+        }
+        __syncthreads();
+        const int count = s_wcount[0] + s_wcount[1];
+        if (threadIdx.x == 0) {
+            long long base = 0;
+            if (tile == 0) {
+                __hip_atomic_store(&tile_state[0], kStateInclusive | (unsigned long long)count, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            } else {
+                __hip_atomic_store(&tile_state[tile], kStateAggregate | (unsigned long long)count, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+                int j = tile - 1, spins = 0;
+                while (j >= 0) {
+                    const unsigned long long w =
+                        __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((w >> 62) == 0) {
+                        if (++spins > kLookbackSpinLimit) {
+                            atomicOr(&ctr->flags, SCNN_FLAG_INTERNAL);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(1);
+                        continue;
+                    }
+                    base += (long long)(w & kStateValueMask);
+                    if ((w >> 62) == 2) break;
+                    --j;
+                }
+                __hip_atomic_store(&tile_state[tile], kStateInclusive | (unsigned long long)(base + count),
+                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            __syncthreads();
-            if (threadIdx.x == 0) tile_rows[tile] = (unsigned)(s_wcount[0] + s_wcount[1]);
-            continue;
+            if (tile == n_tiles - 1) ctr->n_rows = base + count;
+            s_base = base;
         }
-        const long long base = tile_rows[tile];
+        __syncthreads();
+        const long long base = s_base;
+        if (threadIdx.x < kTileRows && s_flag[threadIdx.x]) {
+            const int rank = s_rank[threadIdx.x] + (wave ? s_wcount[0] : 0);
+            s_rank[threadIdx.x] = rank;
+            const long long orow = base + rank;
+            if (orow < out_capacity) {
+                int c0, c1, c2;
+                site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
+                store_site(g, out_coords + orow * (1 + g.ndim), b, c0, c1, c2);
+            }
+        }
+        __syncthreads();
         for (int cc = 0; cc < channels; cc += 64) {
             const int cw = (channels - cc) < 64 ? (channels - cc) : 64;
-            for (int oc = cc + wave; oc < cc + cw; oc += 4) process(oc, true, cc);
-            __syncthreads();
-            if (cc == 0) {
-                if (threadIdx.x < kTileRows) {
-                    const bool f = s_flag[threadIdx.x] != 0u;
-                    const unsigned long long m = __ballot(f);
-                    s_rank[threadIdx.x] = __popcll(m & lt_mask);
-                    if (lane == 0) s_wcount[wave] = __popcll(m);
-                }
-                __syncthreads();
-                if (threadIdx.x < kTileRows && s_flag[threadIdx.x]) {
-                    const int rank = s_rank[threadIdx.x] + (wave ? s_wcount[0] : 0);
-                    s_rank[threadIdx.x] = rank;
-                    const long long orow = base + rank;
-                    if (orow < out_capacity) {
-                        int c0, c1, c2;
-                        site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
-                        store_site(g, out_coords + orow * (1 + g.ndim), b, c0, c1, c2);
-                    }
-                }
+            if (n_chunks > 1) {
+                for (int oc = cc + wave; oc < cc + cw; oc += 4) process(oc, true, cc);
                 __syncthreads();
             }
             for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
@@ -398,18 +488,13 @@ hipError_t launch_finish(const Counters* ctr, int which_rows, long long aux_imm,
 
 hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
-                               const ColState* cols, const unsigned* eqcnt, unsigned* tile_rows,
-                               unsigned* scan_block_sums, long long tiles_cap, Counters* ctr, int32_t* out_coords,
-                               float* out_feats, long long out_capacity, long long* n_rows_out, hipStream_t s) {
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 2048 ? 2048 : tiles_cap);
-    hipLaunchKernelGGL(k_select<false>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
-                       cand_start, tile_start, cand_lin, resp, cols, eqcnt, tile_rows, ctr, out_coords, out_feats,
-                       out_capacity);
-    hipError_t e = launch_exclusive_scan(tile_rows, tiles_cap, 0, &ctr->n_tiles, scan_block_sums, n_rows_out, s);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_select<true>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
-                       cand_start, tile_start, cand_lin, resp, cols, eqcnt, tile_rows, ctr, out_coords, out_feats,
-                       out_capacity);
+                               const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
+                               Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
+                               hipStream_t s) {
+    // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
+    hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu, cand_start,
+                       tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats, out_capacity);
     return hipGetLastError();
 }
 
