@@ -103,30 +103,52 @@ hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const flo
 }
 
 // ------------------------------------------------------------------ radix select
-constexpr int kSideStage = 2048;  // side-buffer entries staged in LDS per workgroup before a flush
+constexpr int kSideStage = 4096;  // side-buffer entries staged in LDS per workgroup before a flush
 
 // Rank search in a 2048-bin histogram held in LDS.  descending: find the bin holding the kk-th entry counted from
 // the top bin; else from the bottom bin.  Returns the bin and the number of entries strictly before it in that
 // order.  1 <= kk <= total must hold.  Contains __syncthreads(); s_res is two shared words.
 __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descending, unsigned* s_wave, int* s_res,
                                   int& bin_out, unsigned& before_out) {
+    // Works for any block size that is a multiple of 64 and at least 256: the first 256 threads search, every
+    // thread passes the same barriers.
+    const bool active = threadIdx.x < 256;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned local = 0;  // thread t owns bins [8t, 8t+8)
+    if (active) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) local += s_h[threadIdx.x * 8 + i];
-    unsigned total;
-    const unsigned excl = block_exclusive_scan_256(local, s_wave, total);
-    const unsigned before_threads = descending ? total - excl - local : excl;
-    if ((long long)before_threads < kk && kk <= (long long)before_threads + (long long)local) {
-        unsigned before = before_threads;
-        int bin = descending ? threadIdx.x * 8 + 7 : threadIdx.x * 8;
-        for (int i = 0; i < 7; ++i) {
-            const unsigned c = s_h[bin];
-            if (kk <= (long long)before + (long long)c) break;
-            before += c;
-            bin += descending ? -1 : 1;
+        for (int i = 0; i < 8; ++i) local += s_h[threadIdx.x * 8 + i];
+    }
+    unsigned inc = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    if (active && lane == 63) s_wave[wave] = inc;
+    __syncthreads();
+    if (active) {
+        unsigned base = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const unsigned x = s_wave[w];
+            if (w < wave) base += x;
+            total += x;
         }
-        s_res[0] = bin;
-        s_res[1] = (int)before;
+        const unsigned excl = base + inc - local;
+        const unsigned before_threads = descending ? total - excl - local : excl;
+        if ((long long)before_threads < kk && kk <= (long long)before_threads + (long long)local) {
+            unsigned before = before_threads;
+            int bin = descending ? threadIdx.x * 8 + 7 : threadIdx.x * 8;
+            for (int i = 0; i < 7; ++i) {
+                const unsigned c = s_h[bin];
+                if (kk <= (long long)before + (long long)c) break;
+                before += c;
+                bin += descending ? -1 : 1;
+            }
+            s_res[0] = bin;
+            s_res[1] = (int)before;
+        }
     }
     __syncthreads();
     bin_out = s_res[0];
@@ -137,16 +159,29 @@ __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descen
 // grid = (columns, slices).  Histogram of the top 11 key bits over the column's entries.
 __global__ __launch_bounds__(256) void k_hist0(int mode, int channels, const int* __restrict__ tile_start,
                                                const float* __restrict__ resp, unsigned* __restrict__ hist) {
+    constexpr int U = 4;  // tiles per wave and iteration
     __shared__ unsigned s_hist[kHistBins];
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
     for (int i = threadIdx.x; i < kHistBins; i += 256) s_hist[i] = 0;
     __syncthreads();
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    const int r = threadIdx.x & (kTileRows - 1);
-    for (int tile = t0 + blockIdx.y * 2 + (threadIdx.x >> 7); tile < t1; tile += 2 * gridDim.y) {
-        const unsigned key = score_key(resp[((size_t)tile * channels + oc) * kTileRows + r], mode);
-        if (key != 0u) atomicAdd(&s_hist[key >> 21], 1u);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int tile0 = t0 + (blockIdx.y * 4 + wave) * U; tile0 < t1; tile0 += 4 * U * gridDim.y) {
+        unsigned key[U][2];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tile = tile0 + u;
+            const float* seg = resp + ((size_t)(tile < t1 ? tile : t0) * channels + oc) * kTileRows;
+            const unsigned k0 = score_key(seg[lane], mode), k1 = score_key(seg[64 + lane], mode);
+            key[u][0] = tile < t1 ? k0 : 0u;
+            key[u][1] = tile < t1 ? k1 : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                if (key[u][h] != 0u) atomicAdd(&s_hist[key[u][h] >> 21], 1u);
     }
     __syncthreads();
     unsigned* gh = hist + (size_t)col * kHistBins;
@@ -206,48 +241,63 @@ __global__ __launch_bounds__(256) void k_pick0(long long k, ColState* __restrict
 }
 
 // grid = (columns, slices).  Copy the entries of the threshold bin, with their position in the column, to the
-// column's slice of the side buffer (order within the slice does not matter).
+// column's slice of the side buffer (order within the slice does not matter).  Every wave stages its hits in its
+// own piece of LDS and flushes it on its own, so the loop has no workgroup barrier.
 __global__ __launch_bounds__(256) void k_collect(int mode, int channels, const int* __restrict__ tile_start,
                                                  const float* __restrict__ resp, ColState* __restrict__ cols,
                                                  uint2* __restrict__ side) {
+    constexpr int U = 4;                 // tile pairs per wave and iteration
+    constexpr int WCAP = kSideStage / 4; // staged entries per wave
     __shared__ uint2 s_buf[kSideStage];
-    __shared__ unsigned s_n;
-    __shared__ unsigned s_base;
     const int col = blockIdx.x;
     const ColState st = cols[col];
     if (st.done) return;
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    const int r = threadIdx.x & (kTileRows - 1);
-    if (threadIdx.x == 0) s_n = 0;
-    __syncthreads();
-    auto flush = [&]() {  // called by all threads, with s_n stable
-        const unsigned n = s_n;
-        if (threadIdx.x == 0) s_base = atomicAdd(&cols[col].side_fill, n);
-        __syncthreads();
-        for (unsigned i = threadIdx.x; i < n; i += 256) side[st.side_off + s_base + i] = s_buf[i];
-        __syncthreads();
-        if (threadIdx.x == 0) s_n = 0;
-        __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    uint2* wbuf = s_buf + wave * WCAP;
+    int fill = 0;  // wave-uniform
+    auto flush = [&]() {
+        unsigned base = 0;
+        if (lane == 0) base = atomicAdd(&cols[col].side_fill, (unsigned)fill);
+        base = __shfl(base, 0, 64);
+        for (int i = lane; i < fill; i += 64) side[st.side_off + base + i] = wbuf[i];
+        fill = 0;
     };
-    for (int tile0 = t0 + blockIdx.y * 2; tile0 < t1; tile0 += 2 * gridDim.y) {
-        const int tile = tile0 + (threadIdx.x >> 7);
-        if (tile < t1) {
-            const unsigned key = score_key(resp[((size_t)tile * channels + oc) * kTileRows + r], mode);
-            if (key != 0u && (key >> 21) == st.prefix) {
-                const unsigned idx = atomicAdd(&s_n, 1u);
-                s_buf[idx] = make_uint2(key, (unsigned)(tile - t0) * kTileRows + (unsigned)r);
-            }
+    // a wave takes whole tiles (two 64-row halves), tiles wave, wave + 4, ... of the slice
+    for (int tile0 = t0 + (blockIdx.y * 4 + wave) * U; tile0 < t1; tile0 += 4 * U * gridDim.y) {
+        unsigned key[U][2];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int tile = tile0 + u;
+            const float* seg = resp + ((size_t)(tile < t1 ? tile : t0) * channels + oc) * kTileRows;
+            const unsigned k0 = score_key(seg[lane], mode), k1 = score_key(seg[64 + lane], mode);
+            key[u][0] = tile < t1 ? k0 : 0u;
+            key[u][1] = tile < t1 ? k1 : 0u;
         }
-        __syncthreads();
-        if (s_n > kSideStage - 256) flush();
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bool hit = key[u][h] != 0u && (key[u][h] >> 21) == st.prefix;
+                const unsigned long long m = __ballot(hit);
+                if (hit)
+                    wbuf[fill + __popcll(m & lt_mask)] =
+                        make_uint2(key[u][h], (unsigned)(tile0 + u - t0) * kTileRows + (unsigned)(h * 64 + lane));
+                fill += __popcll(m);
+            }
+        if (fill > WCAP - U * 128) flush();
     }
-    if (s_n > 0) flush();
+    if (fill > 0) flush();
 }
 
 // One block per column: settle the remaining 21 key bits on the side buffer, then, if the equal entries do not all
 // fit, the position below which they do.
-__global__ __launch_bounds__(256) void k_side_select(ColState* __restrict__ cols, const uint2* __restrict__ side) {
+constexpr int kSideThreads = 1024;
+
+__global__ __launch_bounds__(kSideThreads) void k_side_select(ColState* __restrict__ cols,
+                                                              const uint2* __restrict__ side) {
     __shared__ unsigned s_h[kHistBins];
     __shared__ unsigned s_wave[4];
     __shared__ int s_res[2];
@@ -257,25 +307,35 @@ __global__ __launch_bounds__(256) void k_side_select(ColState* __restrict__ cols
     const uint2* e = side + st.side_off;
     const unsigned m = st.n_eq;
     auto clear = [&]() {
-        for (int i = threadIdx.x; i < kHistBins; i += 256) s_h[i] = 0;
+        for (int i = threadIdx.x; i < kHistBins; i += kSideThreads) s_h[i] = 0;
         __syncthreads();
     };
-    // key bits [20:10]
-    clear();
-    for (unsigned i = threadIdx.x; i < m; i += 256) atomicAdd(&s_h[(e[i].x >> 10) & 0x7ffu], 1u);
-    __syncthreads();
+    // histogram of digit(entry) over the entries that pass(entry), loads issued eight at a time
+    auto histogram = [&](auto pass, auto digit) {
+        for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {
+            uint2 x[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const unsigned i = i0 + (unsigned)kSideThreads * u;
+                x[u] = i < m ? e[i] : make_uint2(0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (i0 + (unsigned)kSideThreads * u < m && pass(x[u])) atomicAdd(&s_h[digit(x[u])], 1u);
+        }
+        __syncthreads();
+    };
     int bin;
     unsigned before;
+    // key bits [20:10]
+    clear();
+    histogram([](uint2) { return true; }, [](uint2 x) { return (x.x >> 10) & 0x7ffu; });
     block_pick(s_h, st.k_rem, true, s_wave, s_res, bin, before);
     const unsigned prefix2 = (st.prefix << 11) | (unsigned)bin;
-    long long k_rem = st.k_rem - (long long)before;
+    const long long k_rem = st.k_rem - (long long)before;
     // key bits [9:0]
     clear();
-    for (unsigned i = threadIdx.x; i < m; i += 256) {
-        const unsigned key = e[i].x;
-        if ((key >> 10) == prefix2) atomicAdd(&s_h[key & 0x3ffu], 1u);
-    }
-    __syncthreads();
+    histogram([prefix2](uint2 x) { return (x.x >> 10) == prefix2; }, [](uint2 x) { return x.x & 0x3ffu; });
     block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);
     const unsigned tau = (prefix2 << 10) | (unsigned)bin;
     const unsigned n_eq = s_h[bin];
@@ -289,12 +349,8 @@ __global__ __launch_bounds__(256) void k_side_select(ColState* __restrict__ cols
         for (int pass = 0; pass < 3; ++pass) {
             const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0), bits = pass == 2 ? 10 : 11;
             clear();
-            for (unsigned i = threadIdx.x; i < m; i += 256) {
-                const uint2 x = e[i];
-                if (x.x == tau && (pass == 0 || (x.y >> (shift + bits)) == pprefix))
-                    atomicAdd(&s_h[(x.y >> shift) & ((1u << bits) - 1u)], 1u);
-            }
-            __syncthreads();
+            histogram([=](uint2 x) { return x.x == tau && (pass == 0 || (x.y >> (shift + bits)) == pprefix); },
+                      [=](uint2 x) { return (x.y >> shift) & ((1u << bits) - 1u); });
             block_pick(s_h, rank, false, s_wave, s_res, bin, before);
             pprefix = (pprefix << bits) | (unsigned)bin;
             rank -= (long long)before;
@@ -320,7 +376,7 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const
     hipLaunchKernelGGL(k_hist0, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, hist);
     hipLaunchKernelGGL(k_pick0, dim3(ncols), dim3(256), 0, s, k, cols, hist, ctr, side_cap);
     hipLaunchKernelGGL(k_collect, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, cols, side);
-    hipLaunchKernelGGL(k_side_select, dim3(ncols), dim3(256), 0, s, cols, side);
+    hipLaunchKernelGGL(k_side_select, dim3(ncols), dim3(kSideThreads), 0, s, cols, side);
     return hipGetLastError();
 }
 
@@ -332,6 +388,52 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const
 // all the same, and a wait that runs out is reported in the status bits instead of hanging.
 constexpr unsigned long long kStateAggregate = 1ull << 62, kStateInclusive = 2ull << 62, kStateValueMask = (1ull << 62) - 1;
 constexpr int kLookbackSpinLimit = 1 << 22;
+
+// Decoupled look-back, run by the first wave of the workgroup: publishes this tile's count, then inspects up to 64
+// predecessors per step.  Returns the number of surviving rows before the tile (valid in every lane).
+__device__ inline long long lookback_wave(unsigned long long* tile_state, int tile, int count, Counters* ctr) {
+    const int lane = threadIdx.x & 63;
+    if (tile == 0) {
+        if (lane == 0)
+            __hip_atomic_store(&tile_state[0], kStateInclusive | (unsigned long long)count, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        return 0;
+    }
+    if (lane == 0)
+        __hip_atomic_store(&tile_state[tile], kStateAggregate | (unsigned long long)count, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    long long base = 0;
+    int hi = tile - 1;  // nearest predecessor not yet accounted for
+    int spins = 0;
+    while (hi >= 0) {
+        const int j = hi - lane;
+        unsigned long long w = kStateAggregate;  // lanes past tile 0 count as empty aggregates
+        if (j >= 0) w = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned status = (unsigned)(w >> 62);
+        const unsigned long long empty = __ballot(status == 0), incl = __ballot(status == 2);
+        // the usable prefix of the window ends at the first inclusive word, or before the first empty one
+        const int first_incl = incl ? __ffsll((long long)incl) - 1 : 64;
+        const int first_empty = empty ? __ffsll((long long)empty) - 1 : 64;
+        const int usable = first_incl < first_empty ? first_incl + 1 : first_empty;  // lanes [0, usable)
+        long long v = lane < usable ? (long long)(w & kStateValueMask) : 0;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+        base += v;
+        if (first_incl < first_empty) break;  // reached an inclusive prefix
+        hi -= usable;
+        if (usable == 0) {
+            if (++spins > kLookbackSpinLimit) {
+                if (lane == 0) atomicOr(&ctr->flags, SCNN_FLAG_INTERNAL);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+    }
+    if (lane == 0)
+        __hip_atomic_store(&tile_state[tile], kStateInclusive | (unsigned long long)(base + count), __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    return base;
+}
 
 __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int mode, int relu,
                                                       const int* __restrict__ cand_start,
@@ -377,26 +479,38 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
         if (threadIdx.x < kTileRows) s_flag[threadIdx.x] = 0;
         __syncthreads();
 
-        // One wave handles one channel over the tile's 128 rows.
-        auto process = [&](int oc, bool stage, int cc) {
-            const float* seg = resp + ((size_t)tile * channels + oc) * kTileRows;
-            const unsigned tau = s_tau[oc], cut = s_cut[oc];
+        // A wave handles channels wave, wave + 4, ... over the tile's 128 rows, four channels per step so that
+        // eight loads are in flight.
+        auto process = [&](int oc_first, int oc_end, bool stage, int cc) {
+            for (int ob = oc_first + wave; ob < oc_end; ob += 16) {
+                float v[4][2];
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const int r = half * 64 + lane;
-                const float v = seg[r];
-                const unsigned key = score_key(v, mode);
-                bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
-                if (relu) keep = keep && (v > 0.0f);
-                if (keep) s_flag[r] = 1u;
-                if (stage) s_v[r][oc - cc] = keep ? v : 0.0f;
+                for (int j = 0; j < 4; ++j) {
+                    const int oc = ob + 4 * j;
+                    const float* seg = resp + ((size_t)tile * channels + (oc < oc_end ? oc : ob)) * kTileRows;
+                    v[j][0] = seg[lane];
+                    v[j][1] = seg[64 + lane];
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int oc = ob + 4 * j;
+                    if (oc < oc_end) {
+                        const unsigned tau = s_tau[oc], cut = s_cut[oc];
+#pragma unroll
+                        for (int half = 0; half < 2; ++half) {
+                            const int r = half * 64 + lane;
+                            const float x = v[j][half];
+                            const unsigned key = score_key(x, mode);
+                            bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
+                            if (relu) keep = keep && (x > 0.0f);
+                            if (keep) s_flag[r] = 1u;
+                            if (stage) s_v[r][oc - cc] = keep ? x : 0.0f;
+                        }
+                    }
+                }
             }
         };
-        if (n_chunks > 1) {  // row flags need every channel before the first chunk can be written
-            for (int oc = wave; oc < channels; oc += 4) process(oc, false, 0);
-        } else {
-            for (int oc = wave; oc < channels; oc += 4) process(oc, true, 0);
-        }
+        process(0, channels, n_chunks == 1, 0);  // with several chunks the row flags need every channel first
         __syncthreads();
         if (threadIdx.x < kTileRows) {
             const unsigned long long m = __ballot(s_flag[threadIdx.x] != 0u);
@@ -405,35 +519,12 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
         }
         __syncthreads();
         const int count = s_wcount[0] + s_wcount[1];
-        if (threadIdx.x == 0) {
-            long long base = 0;
-            if (tile == 0) {
-                __hip_atomic_store(&tile_state[0], kStateInclusive | (unsigned long long)count, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-            } else {
-                __hip_atomic_store(&tile_state[tile], kStateAggregate | (unsigned long long)count, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-                int j = tile - 1, spins = 0;
-                while (j >= 0) {
-                    const unsigned long long w =
-                        __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if ((w >> 62) == 0) {
-                        if (++spins > kLookbackSpinLimit) {
-                            atomicOr(&ctr->flags, SCNN_FLAG_INTERNAL);
-                            break;
-                        }
-                        __builtin_amdgcn_s_sleep(1);
-                        continue;
-                    }
-                    base += (long long)(w & kStateValueMask);
-                    if ((w >> 62) == 2) break;
-                    --j;
-                }
-                __hip_atomic_store(&tile_state[tile], kStateInclusive | (unsigned long long)(base + count),
-                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (wave == 0) {
+            const long long base = lookback_wave(tile_state, tile, count, ctr);
+            if (lane == 0) {
+                if (tile == n_tiles - 1) ctr->n_rows = base + count;
+                s_base = base;
             }
-            if (tile == n_tiles - 1) ctr->n_rows = base + count;
-            s_base = base;
         }
         __syncthreads();
         const long long base = s_base;
@@ -451,7 +542,7 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
         for (int cc = 0; cc < channels; cc += 64) {
             const int cw = (channels - cc) < 64 ? (channels - cc) : 64;
             if (n_chunks > 1) {
-                for (int oc = cc + wave; oc < cc + cw; oc += 4) process(oc, true, cc);
+                process(cc, cc + cw, true, cc);
                 __syncthreads();
             }
             for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
@@ -463,6 +554,119 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
             }
             __syncthreads();
         }
+    }
+}
+
+// The same pass for up to 64 channels, software-pipelined: a workgroup takes its next ticket and issues that
+// tile's loads into registers before it waits on the look-back and writes the current tile, so the read of one tile
+// overlaps the write of the previous one.
+__global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, int mode, int relu,
+                                                        const int* __restrict__ cand_start,
+                                                        const int* __restrict__ tile_start,
+                                                        const unsigned* __restrict__ cand_lin,
+                                                        const float* __restrict__ resp,
+                                                        const ColState* __restrict__ cols,
+                                                        unsigned long long* tile_state, Counters* ctr,
+                                                        int32_t* __restrict__ out_coords,
+                                                        float* __restrict__ out_feats, long long out_capacity) {
+    __shared__ unsigned s_tau[64];
+    __shared__ unsigned s_cut[64];
+    __shared__ unsigned s_flag[kTileRows];
+    __shared__ int s_rank[kTileRows];
+    __shared__ int s_wcount[2];
+    __shared__ float s_v[kTileRows][65];
+    __shared__ int s_ticket;
+    __shared__ long long s_base;
+
+    const int n_tiles = (int)ctr->n_tiles;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    int cur_b = -1;
+    float v[16][2];  // channel wave + 4*m, rows lane and lane + 64
+
+    auto take_ticket = [&]() {
+        __syncthreads();  // the previous ticket has been read by everybody
+        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        __syncthreads();
+        return s_ticket;
+    };
+    auto load_tile = [&](int tile) {
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int oc = wave + 4 * m;
+            const float* seg = resp + ((size_t)tile * channels + (oc < channels ? oc : wave)) * kTileRows;
+            v[m][0] = seg[lane];
+            v[m][1] = seg[64 + lane];
+        }
+    };
+    int tile = take_ticket();
+    if (tile < n_tiles) load_tile(tile);
+    while (tile < n_tiles) {
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        const unsigned pos0 = (unsigned)(tile - tile_start[b]) * kTileRows;  // position of row 0 in its column
+        if (b != cur_b) {
+            if (threadIdx.x < channels) {
+                const ColState* st = cols + (size_t)b * channels + threadIdx.x;
+                s_tau[threadIdx.x] = st->tau;
+                s_cut[threadIdx.x] = st->cut;
+            }
+            cur_b = b;
+        }
+        if (threadIdx.x < kTileRows) s_flag[threadIdx.x] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int oc = wave + 4 * m;
+            if (oc < channels) {
+                const unsigned tau = s_tau[oc], cut = s_cut[oc];
+#pragma unroll
+                for (int half = 0; half < 2; ++half) {
+                    const int r = half * 64 + lane;
+                    const float x = v[m][half];
+                    const unsigned key = score_key(x, mode);
+                    bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
+                    if (relu) keep = keep && (x > 0.0f);
+                    if (keep) s_flag[r] = 1u;
+                    s_v[r][oc] = keep ? x : 0.0f;
+                }
+            }
+        }
+        __syncthreads();
+        if (threadIdx.x < kTileRows) {
+            const unsigned long long m = __ballot(s_flag[threadIdx.x] != 0u);
+            s_rank[threadIdx.x] = __popcll(m & lt_mask);
+            if (lane == 0) s_wcount[wave] = __popcll(m);
+        }
+        const int next = take_ticket();  // also orders s_rank / s_wcount
+        if (next < n_tiles) load_tile(next);
+        const int count = s_wcount[0] + s_wcount[1];
+        if (wave == 0) {
+            const long long base = lookback_wave(tile_state, tile, count, ctr);
+            if (lane == 0) {
+                if (tile == n_tiles - 1) ctr->n_rows = base + count;
+                s_base = base;
+            }
+        }
+        __syncthreads();
+        const long long base = s_base;
+        if (threadIdx.x < kTileRows && s_flag[threadIdx.x]) {
+            const long long orow = base + s_rank[threadIdx.x] + (wave ? s_wcount[0] : 0);
+            if (orow < out_capacity) {
+                int c0, c1, c2;
+                site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
+                store_site(g, out_coords + orow * (1 + g.ndim), b, c0, c1, c2);
+            }
+        }
+        for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
+            const int r = i >> 6, c = i & 63;
+            if (c < channels && s_flag[r]) {
+                const long long orow = base + s_rank[r] + (r >= 64 ? s_wcount[0] : 0);
+                if (orow < out_capacity) out_feats[orow * channels + c] = s_v[r][c];
+            }
+        }
+        __syncthreads();  // the tile buffers are free for the next tile
+        tile = next;
     }
 }
 
@@ -492,9 +696,15 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
                                hipStream_t s) {
     // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
-    hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu, cand_start,
-                       tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats, out_capacity);
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
+    if (channels <= 64)
+        hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
+                           cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
+                           out_capacity);
+    else
+        hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
+                           cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
+                           out_capacity);
     return hipGetLastError();
 }
 
