@@ -152,7 +152,7 @@ constexpr int kPairTapChunk = 32;                 // taps looked up per pass of 
 constexpr unsigned kPairRowShift = 24;            // pair = (local output row << 24) | input row
 constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
 constexpr unsigned kPadPair = (unsigned)kTileRows << kPairRowShift;  // list padding: dummy accumulator row, input row 0
-constexpr int kStageBlocks = 216;                 // 16-pair blocks staged in LDS at a time by the contraction
+constexpr int kStageBlocks = 208;                 // 16-pair blocks staged in LDS at a time by the contraction
 
 // Pair lists of all tiles live in one global array of 16-entry blocks; a tile's blocks are contiguous, in
 // ascending (tap, output row) order.  tile_hdr[tile] = {first block, block count};
@@ -336,7 +336,7 @@ __host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out) {
     return (size_t)(kTileRows + 1) * (c_out + 1) * sizeof(double)   // accumulators + one dummy row
            + (size_t)kStageBlocks * 16 * sizeof(unsigned)            // staged pair blocks
            + (size_t)kStageBlocks * sizeof(unsigned short)           // tap / position of each staged block
-           + (size_t)kStageBlocks * sizeof(unsigned short)           // round list
+           + (size_t)kStageBlocks * sizeof(unsigned)                 // round list
            + 16;
 }
 
@@ -345,7 +345,7 @@ template <int KC, int NB, int RB>
 struct RoundRegs {
     f32x4 a[RB][KC][2];     // A operand: lane holds x[in(pair 16j + jj)][kc*32 + 8*gq .. + 8)
     f32x4 b[KC][NB][2];     // B operand: lane holds w[tap][kc*32 + 8*gq + s][16*cb + jj], s = 0..7
-    unsigned oaddr[RB][4];  // LDS byte offset of accumulator (row of result row 4*gq + v, channel jj)
+    unsigned oaddr[RB][4];  // LDS byte address of accumulator (row of result row 4*gq + v, channel jj)
 };
 
 // Work split: wave i of the workgroup takes rounds i, i + 4, ...  A wave multiplies its blocks against the whole
@@ -370,16 +370,17 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     double* s_c = (double*)smem;                                               // [129][CS]; row 128 absorbs padding
     unsigned* s_flat = (unsigned*)(s_c + (kTileRows + 1) * CS);                // [kStageBlocks][16] packed pairs
     unsigned short* s_btap = (unsigned short*)(s_flat + kStageBlocks * 16);    // [kStageBlocks]
-    unsigned short* s_round = s_btap + kStageBlocks;                           // [kStageBlocks] first block | nb << 8
-    int* s_nrounds = (int*)(s_round + kStageBlocks);
+    unsigned* s_rmeta = (unsigned*)(s_btap + kStageBlocks);  // [kStageBlocks] first block | blocks << 8 | tap << 16
+    int* s_nrounds = (int*)(s_rmeta + kStageBlocks);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int jj = lane & 15, gq = lane >> 4;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     const int n_tiles = (int)ctr->n_tiles;
-    const unsigned lane_off = (unsigned)jj * (unsigned)sizeof(double);
-    const unsigned in_max = (unsigned)(nnz_in - 1);
+    // LDS byte address of this lane's channel in accumulator row 0 (a generic pointer to LDS carries the LDS
+    // address in its low 32 bits); accumulator addresses are formed once per block, at load time
+    const unsigned lane_off = (unsigned)(size_t)s_c + (unsigned)jj * (unsigned)sizeof(double);
 
     // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
     // the input rows shared by neighbouring tiles stay in that XCD's L2.
@@ -388,6 +389,9 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
 
     for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;  // the dummy row needs no reset
+    // The stage buffer only ever holds entries written by the pair builder (or these zeros), so whatever a clamped
+    // read past the end of a tile's list finds there names a valid input row.
+    for (int i = threadIdx.x; i < kStageBlocks * 16; i += NT) s_flat[i] = 0u;
 
     for (int tile = xcd * span + slot; tile < tile_end; tile += per_xcd) {
         const uint2 hdr = tile_hdr[tile];
@@ -401,14 +405,23 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                 for (int i = threadIdx.x; i < n_blocks; i += NT) s_btap[i] = block_tap[hdr.x + s0 + i];
             }
             __syncthreads();
-            // ---- round list: a round starts at every RB-th block of a tap (and at the start of the stage)
+            // ---- round list: a round = up to RB consecutive blocks of one tap.  It starts at every RB-th block of
+            //      a tap's run (and at the start of the stage); entry = first block | blocks << 8 | tap << 16.
             if (wave == 0) {
                 int base = 0;
                 for (int i0 = 0; i0 < n_blocks; i0 += 64) {
                     const int i = i0 + lane;
-                    const bool start = i < n_blocks && (i == 0 || ((s_btap[i] >> 8) % RB) == 0);
+                    unsigned bt[RB];
+#pragma unroll
+                    for (int d = 0; d < RB; ++d) bt[d] = s_btap[(i + d) < n_blocks ? (i + d) : n_blocks - 1];
+                    const bool start = i < n_blocks && (i == 0 || ((bt[0] >> 8) % RB) == 0);
+                    int nb = 1;
+#pragma unroll
+                    for (int d = 1; d < RB; ++d)
+                        if (nb == d && i + d < n_blocks && ((bt[d] >> 8) % RB) != 0) nb = d + 1;
                     const unsigned long long m = __ballot(start);
-                    if (start) s_round[base + __popcll(m & lt_mask)] = (unsigned short)i;
+                    if (start)
+                        s_rmeta[base + __popcll(m & lt_mask)] = (unsigned)i | (unsigned)nb << 8 | (bt[0] & 0xffu) << 16;
                     base += __popcll(m);
                 }
                 if (lane == 0) *s_nrounds = base;
@@ -417,18 +430,29 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
             const int n_rounds = __builtin_amdgcn_readfirstlane(*s_nrounds);
             const int my_rounds = (n_rounds - wave + kConvWaves - 1) / kConvWaves;  // rounds wave, wave + 4, ...
             if (my_rounds > 0) {
-                // All loads of a round are unconditional so that their number is fixed: a round past the end
-                // repeats the wave's last one, a block past the round's end repeats list entries (input row
-                // clamped) and is never computed.
-                auto round_blocks = [&](int r) {
-                    const int first = s_round[r];
-                    const int next = r + 1 < n_rounds ? (int)s_round[r + 1] : n_blocks;
-                    return make_int2(first, next - first);
+                // The wave's pipeline, per round: list entry (LDS) -> pair entries of its blocks (LDS) -> operands
+                // (global) -> compute.  Each step is issued a full round before its result is needed, so that no
+                // LDS or memory round trip sits between two rounds' matrix instructions.  All reads of a round are
+                // unconditional, so that their number is fixed: a round past the end repeats the wave's last one
+                // (never computed), a block past a round's end repeats list entries and is never computed.
+                struct Entries {
+                    unsigned in[RB];  // pair jj of each block (its input row)
+                    uint4 out[RB];    // pairs 4*gq .. 4*gq + 3 of each block (their result rows)
                 };
-                auto load_round = [&](int k_round, RoundRegs<KC, NB, RB>& R) {
-                    const int r = wave + kConvWaves * (k_round < my_rounds ? k_round : my_rounds - 1);
-                    const int first = __builtin_amdgcn_readfirstlane(s_round[r]);
-                    int tt = __builtin_amdgcn_readfirstlane(s_btap[first] & 0xff);
+                auto meta_at = [&](int j) {
+                    return s_rmeta[wave + kConvWaves * (j < my_rounds ? j : my_rounds - 1)];
+                };
+                auto read_entries = [&](unsigned meta, Entries& E) {
+                    const int first = (int)(meta & 0xffu);
+#pragma unroll
+                    for (int k = 0; k < RB; ++k) {
+                        const int blk = (first + k) < kStageBlocks ? (first + k) : kStageBlocks - 1;
+                        E.in[k] = s_flat[16 * blk + jj];
+                        E.out[k] = *(const uint4*)(s_flat + 16 * blk + 4 * gq);
+                    }
+                };
+                auto load_round = [&](unsigned meta, const Entries& E, RoundRegs<KC, NB, RB>& R) {
+                    int tt = (int)((meta >> 16) & 0xffu);
                     tt = tt < taps ? tt : taps - 1;
                     const f32x4* wt = (const f32x4*)(wb + ((size_t)tt * KC * NB * 64 + lane) * 8);
 #pragma unroll
@@ -438,31 +462,20 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                             R.b[kc][cb][0] = wt[(kc * NB + cb) * 128];
                             R.b[kc][cb][1] = wt[(kc * NB + cb) * 128 + 1];
                         }
-                    unsigned e_in[RB];
-                    uint4 e_out[RB];
 #pragma unroll
                     for (int k = 0; k < RB; ++k) {
-                        const int blk = (first + k) < kStageBlocks ? (first + k) : kStageBlocks - 1;
-                        e_in[k] = s_flat[16 * blk + jj];
-                        e_out[k] = *(const uint4*)(s_flat + 16 * blk + 4 * gq);
-                    }
-#pragma unroll
-                    for (int k = 0; k < RB; ++k) {
-                        unsigned in = e_in[k] & kPairInMask;
-                        in = in < in_max ? in : in_max;
+                        const unsigned in = E.in[k] & kPairInMask;
                         const f32x4* src = (const f32x4*)(feats + (size_t)in * C_IN + 8 * gq);
 #pragma unroll
                         for (int kc = 0; kc < KC; ++kc) {
                             R.a[k][kc][0] = src[kc * 8];
                             R.a[k][kc][1] = src[kc * 8 + 1];
                         }
-                        // a stale entry past the end may name any row: keep the address inside the accumulators
-                        const unsigned r0 = e_out[k].x >> kPairRowShift, r1 = e_out[k].y >> kPairRowShift,
-                                       r2 = e_out[k].z >> kPairRowShift, r3 = e_out[k].w >> kPairRowShift;
-                        R.oaddr[k][0] = (r0 < kTileRows ? r0 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][1] = (r1 < kTileRows ? r1 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][2] = (r2 < kTileRows ? r2 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
-                        R.oaddr[k][3] = (r3 < kTileRows ? r3 : kTileRows) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        // (a stale entry past the end of the list may name any row, but such a block is not computed)
+                        R.oaddr[k][0] = (E.out[k].x >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][1] = (E.out[k].y >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][2] = (E.out[k].z >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
+                        R.oaddr[k][3] = (E.out[k].w >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
                     }
                 };
                 // A block = NB independent fp32 MFMA chains per 32 input channels (one per 16 output channels); the
@@ -470,11 +483,11 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                 // accumulators.  Padding pairs land in the dummy row.  Blocks are guarded one by one (uniform
                 // branches) rather than through per-count variants, which the compiler would merge again through
                 // scratch memory.
-                auto compute_round = [&](int k_round, const RoundRegs<KC, NB, RB>& R) {
-                    const int nb = round_blocks(wave + kConvWaves * k_round).y;  // 1 .. RB
+                auto compute_round = [&](unsigned meta, const RoundRegs<KC, NB, RB>& R) {
+                    const int nb = (int)((meta >> 8) & 0xffu);  // 1 .. RB
 #pragma unroll
                     for (int k = 0; k < RB; ++k) {
-                        if (k < nb) {
+                        if (k == 0 || k < nb) {  // (a round has at least one block)
 #pragma unroll
                             for (int kc = 0; kc < KC; ++kc) {
                                 f32x4 acc[NB];
@@ -494,36 +507,78 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
 #pragma unroll
                                     for (int v = 0; v < 4; ++v)
                                         __hip_atomic_fetch_add(
-                                            (double*)((unsigned char*)s_c + R.oaddr[k][v] + cb * 16 * sizeof(double)),
+                                            (__attribute__((address_space(3))) double*)(size_t)R.oaddr[k][v] + cb * 16,
                                             (double)acc[cb][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                             }
                         }
                     }
                 };
                 RoundRegs<KC, NB, RB> r0, r1;
-                load_round(0, r0);
-                for (int k_round = 0; k_round < my_rounds; k_round += 2) {
-                    load_round(k_round + 1, r1);
-                    compute_round(k_round, r0);
-                    load_round(k_round + 2, r0);
-                    if (k_round + 1 < my_rounds) compute_round(k_round + 1, r1);
+                Entries ent;
+                unsigned m0 = __builtin_amdgcn_readfirstlane(meta_at(0));
+                unsigned m1 = __builtin_amdgcn_readfirstlane(meta_at(1));
+                unsigned m_ahead = meta_at(2);
+                read_entries(m0, ent);
+                load_round(m0, ent, r0);
+                read_entries(m1, ent);
+                // Let these first reads land before the loop: inside it, every value read from LDS is used only
+                // after a round's worth of accumulator updates has been issued behind the read, so the wait for
+                // it (the LDS queue is in order) does not wait for those updates.
+                asm volatile("" : "+v"(m_ahead));
+#pragma unroll
+                for (int k = 0; k < RB; ++k)
+                    asm volatile("" : "+v"(ent.in[k]), "+v"(ent.out[k].x), "+v"(ent.out[k].y), "+v"(ent.out[k].z),
+                                 "+v"(ent.out[k].w));
+                for (int j = 0; j < my_rounds; j += 2) {
+                    // here: r0 = operands of round j (list entry m0), ent = pair entries of round j + 1 (m1),
+                    //       m_ahead = list entry of round j + 2
+                    load_round(m1, ent, r1);
+                    const unsigned m2 = __builtin_amdgcn_readfirstlane(m_ahead);
+                    read_entries(m2, ent);
+                    m_ahead = meta_at(j + 3);
+                    compute_round(m0, r0);
+                    if (j + 1 >= my_rounds) break;
+                    load_round(m2, ent, r0);
+                    const unsigned m3 = __builtin_amdgcn_readfirstlane(m_ahead);
+                    read_entries(m3, ent);
+                    m_ahead = meta_at(j + 4);
+                    compute_round(m1, r1);
+                    m0 = m2;
+                    m1 = m3;
                 }
             }
         }
         __syncthreads();
         // ---- epilogue: one rounding to fp32, bias on the non-zero entries, planar store; the accumulators are
-        //      reset on the way.  A thread handles four consecutive rows of one channel: one 16-byte store.
-        for (int i = threadIdx.x; i < (kTileRows / 4) * C_OUT; i += NT) {
-            const int r4 = (i & (kTileRows / 4 - 1)) * 4, oc = i / (kTileRows / 4);
-            f32x4 v;
+        //      reset on the way.  A lane takes one row, a wave one channel at a time: consecutive rows lie
+        //      CS doubles apart, i.e. 2 banks (mod 64), so the 64 reads of a wave spread over all LDS banks, and
+        //      the wave's stores form one contiguous 256-byte run of the planar tile.
+        {
+            constexpr int OCW = (C_OUT + kConvWaves - 1) / kConvWaves, H = kTileRows / 64;
+            double acc[OCW][H];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                float x = (float)s_c[(r4 + u) * CS + oc];
-                s_c[(r4 + u) * CS + oc] = 0.0;
-                if (bias && x != 0.0f) x += bias[oc];
-                v[u] = x;
+            for (int j = 0; j < OCW; ++j) {  // all reads first: one LDS latency for the lot
+                const int oc = (wave + j * kConvWaves) < C_OUT ? (wave + j * kConvWaves) : C_OUT - 1;
+#pragma unroll
+                for (int h = 0; h < H; ++h) acc[j][h] = s_c[(h * 64 + lane) * CS + oc];
             }
-            *(f32x4*)(resp + ((size_t)tile * C_OUT + oc) * kTileRows + r4) = v;
+#pragma unroll
+            for (int j = 0; j < OCW; ++j) {
+                const int oc = wave + j * kConvWaves;
+                if (C_OUT % kConvWaves == 0 || oc < C_OUT) {
+                    // (the weights stand in as a readable address when there is no bias)
+                    const float bl = (bias ? bias : wb)[oc];
+                    const float bv = bias ? bl : 0.0f;
+#pragma unroll
+                    for (int h = 0; h < H; ++h) {
+                        const int r = h * 64 + lane;
+                        s_c[r * CS + oc] = 0.0;
+                        float x = (float)acc[j][h];
+                        if (x != 0.0f) x += bv;
+                        resp[((size_t)tile * C_OUT + oc) * kTileRows + r] = x;
+                    }
+                }
+            }
         }
     }
 }
