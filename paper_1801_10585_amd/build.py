@@ -17,7 +17,10 @@ LIB = os.path.join(HERE, "libscnn.so")
 SOURCES = ["scnn_index.hip", "scnn_conv.hip", "scnn_topk.hip", "scnn_rows.hip", "scnn_api.hip"]
 # packed fp32 VALU ops are switched off on purpose (they have misbehaved on the target machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         # matrix-core results straight into VGPRs: the fp64 accumulation reads every result once, and a copy out
+         # of the accumulation registers would cost one more vector instruction per value
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def _deps_mtime() -> float:

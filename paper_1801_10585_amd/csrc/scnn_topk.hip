@@ -389,39 +389,57 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const
 constexpr unsigned long long kStateAggregate = 1ull << 62, kStateInclusive = 2ull << 62, kStateValueMask = (1ull << 62) - 1;
 constexpr int kLookbackSpinLimit = 1 << 22;
 
-// Decoupled look-back, run by the first wave of the workgroup: publishes this tile's count, then inspects up to 64
-// predecessors per step.  Returns the number of surviving rows before the tile (valid in every lane).
-__device__ inline long long lookback_wave(unsigned long long* tile_state, int tile, int count, Counters* ctr) {
+// Decoupled look-back, run by the first wave of the workgroup: publishes this tile's count, then inspects its
+// predecessors, nearest first, kLookbackSlices * 64 of them per step.  The tiles in flight advance together, so the
+// nearest tile whose inclusive sum is known usually lies about as far back as there are workgroups; reading that
+// whole stretch with one batch of loads costs one memory round trip instead of one per 64 tiles.
+// Returns the number of surviving rows before the tile (valid in every lane).
+constexpr int kLookbackSlices = 8;
+// (one thread) makes a tile's own count known to its successors
+__device__ inline void publish_count(unsigned long long* tile_state, int tile, int count) {
+    __hip_atomic_store(&tile_state[tile], (tile == 0 ? kStateInclusive : kStateAggregate) | (unsigned long long)count,
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// (first wave; the tile's count has been published) sums the counts of all predecessors
+__device__ inline long long lookback_published(unsigned long long* tile_state, int tile, int count, Counters* ctr) {
     const int lane = threadIdx.x & 63;
-    if (tile == 0) {
-        if (lane == 0)
-            __hip_atomic_store(&tile_state[0], kStateInclusive | (unsigned long long)count, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        return 0;
-    }
-    if (lane == 0)
-        __hip_atomic_store(&tile_state[tile], kStateAggregate | (unsigned long long)count, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+    if (tile == 0) return 0;
     long long base = 0;
     int hi = tile - 1;  // nearest predecessor not yet accounted for
     int spins = 0;
     while (hi >= 0) {
-        const int j = hi - lane;
-        unsigned long long w = kStateAggregate;  // lanes past tile 0 count as empty aggregates
-        if (j >= 0) w = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned status = (unsigned)(w >> 62);
-        const unsigned long long empty = __ballot(status == 0), incl = __ballot(status == 2);
-        // the usable prefix of the window ends at the first inclusive word, or before the first empty one
-        const int first_incl = incl ? __ffsll((long long)incl) - 1 : 64;
-        const int first_empty = empty ? __ffsll((long long)empty) - 1 : 64;
-        const int usable = first_incl < first_empty ? first_incl + 1 : first_empty;  // lanes [0, usable)
-        long long v = lane < usable ? (long long)(w & kStateValueMask) : 0;
+        unsigned long long w[kLookbackSlices];
+#pragma unroll
+        for (int u = 0; u < kLookbackSlices; ++u) {
+            const int j = hi - u * 64 - lane;
+            w[u] = kStateAggregate;  // positions past tile 0 count as empty aggregates
+            if (j >= 0) w[u] = __hip_atomic_load(&tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        long long v = 0;
+        int consumed = 0;
+        bool done = false;
+#pragma unroll
+        for (int u = 0; u < kLookbackSlices; ++u) {
+            const unsigned status = (unsigned)(w[u] >> 62);
+            const unsigned long long empty = __ballot(status == 0), incl = __ballot(status == 2);
+            // the usable prefix of the slice ends at the first inclusive word, or before the first empty one
+            const int first_incl = incl ? __ffsll((long long)incl) - 1 : 64;
+            const int first_empty = empty ? __ffsll((long long)empty) - 1 : 64;
+            const int usable = first_incl < first_empty ? first_incl + 1 : first_empty;  // lanes [0, usable)
+            if (lane < usable) v += (long long)(w[u] & kStateValueMask);
+            consumed += usable;
+            if (first_incl < first_empty) {
+                done = true;  // reached an inclusive prefix
+                break;
+            }
+            if (usable < 64) break;  // an unpublished tile: look again from there
+        }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
         base += v;
-        if (first_incl < first_empty) break;  // reached an inclusive prefix
-        hi -= usable;
-        if (usable == 0) {
+        if (done) break;
+        hi -= consumed;
+        if (consumed == 0) {
             if (++spins > kLookbackSpinLimit) {
                 if (lane == 0) atomicOr(&ctr->flags, SCNN_FLAG_INTERNAL);
                 break;
@@ -433,6 +451,10 @@ __device__ inline long long lookback_wave(unsigned long long* tile_state, int ti
         __hip_atomic_store(&tile_state[tile], kStateInclusive | (unsigned long long)(base + count), __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
     return base;
+}
+__device__ inline long long lookback_wave(unsigned long long* tile_state, int tile, int count, Counters* ctr) {
+    if ((threadIdx.x & 63) == 0) publish_count(tile_state, tile, count);
+    return lookback_published(tile_state, tile, count, ctr);
 }
 
 __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int mode, int relu,
@@ -557,10 +579,12 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
     }
 }
 
-// The same pass for up to 64 channels, software-pipelined: a workgroup takes its next ticket and issues that
-// tile's loads into registers before it waits on the look-back and writes the current tile, so the read of one tile
-// overlaps the write of the previous one.
-__global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, int mode, int relu,
+// The same pass for up to 64 channels, software-pipelined over three tiles.  A workgroup holds tile X (being
+// written), tile Y (loaded) and tile Z (its loads in flight).  Per step it decides which entries of Y survive and
+// publishes Y's row count, takes the ticket for Z and issues Z's loads, and only then looks back for X and writes
+// it.  A tile's count is therefore known to its successors a whole step before its own look-back, so that a
+// look-back rarely finds a predecessor unpublished, and the reads of one tile overlap the writes of another.
+__global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels, int mode, int relu,
                                                         const int* __restrict__ cand_start,
                                                         const int* __restrict__ tile_start,
                                                         const unsigned* __restrict__ cand_lin,
@@ -571,9 +595,9 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
                                                         float* __restrict__ out_feats, long long out_capacity) {
     __shared__ unsigned s_tau[64];
     __shared__ unsigned s_cut[64];
-    __shared__ unsigned s_flag[kTileRows];
-    __shared__ int s_rank[kTileRows];
-    __shared__ int s_wcount[2];
+    __shared__ unsigned s_flag[2][kTileRows];
+    __shared__ int s_rank[2][kTileRows];
+    __shared__ int s_wcount[2][2];
     __shared__ float s_v[kTileRows][65];
     __shared__ int s_ticket;
     __shared__ long long s_base;
@@ -581,8 +605,8 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
     const int n_tiles = (int)ctr->n_tiles;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool vec4 = (channels & 3) == 0 && ((size_t)out_feats & 15) == 0;  // rows are 16-byte aligned
     int cur_b = -1;
-    float v[16][2];  // channel wave + 4*m, rows lane and lane + 64
 
     auto take_ticket = [&]() {
         __syncthreads();  // the previous ticket has been read by everybody
@@ -590,22 +614,24 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
         __syncthreads();
         return s_ticket;
     };
-    auto load_tile = [&](int tile) {
+    // values of channel wave + 4*m at rows lane and lane + 64
+    auto load_tile = [&](int tile, float (&v)[16][2]) {
+        const float* seg = resp + ((size_t)tile * channels + wave) * kTileRows + lane;
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
-            const int oc = wave + 4 * m;
-            const float* seg = resp + ((size_t)tile * channels + (oc < channels ? oc : wave)) * kTileRows;
-            v[m][0] = seg[lane];
-            v[m][1] = seg[64 + lane];
+            if (wave + 4 * m < channels) {  // (uniform in the wave)
+                v[m][0] = seg[m * 4 * kTileRows];
+                v[m][1] = seg[m * 4 * kTileRows + 64];
+            }
         }
     };
-    int tile = take_ticket();
-    if (tile < n_tiles) load_tile(tile);
-    while (tile < n_tiles) {
+    // which of the thread's 32 values survive (bit 2*m + half); marks the rows that keep an entry, counts them
+    // and publishes the count
+    auto decide = [&](int tile, int slot, const float (&v)[16][2]) -> unsigned {
         const int b = sample_of_tile(tile_start, g.batch, tile);
-        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
         const unsigned pos0 = (unsigned)(tile - tile_start[b]) * kTileRows;  // position of row 0 in its column
-        if (b != cur_b) {
+        if (b != cur_b) {  // (uniform: every thread sees the same tiles)
+            __syncthreads();
             if (threadIdx.x < channels) {
                 const ColState* st = cols + (size_t)b * channels + threadIdx.x;
                 s_tau[threadIdx.x] = st->tau;
@@ -613,8 +639,9 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
             }
             cur_b = b;
         }
-        if (threadIdx.x < kTileRows) s_flag[threadIdx.x] = 0;
+        if (threadIdx.x < kTileRows) s_flag[slot][threadIdx.x] = 0;
         __syncthreads();
+        unsigned kmask = 0;
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int oc = wave + 4 * m;
@@ -627,22 +654,38 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
                     const unsigned key = score_key(x, mode);
                     bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
                     if (relu) keep = keep && (x > 0.0f);
-                    if (keep) s_flag[r] = 1u;
-                    s_v[r][oc] = keep ? x : 0.0f;
+                    if (keep) {
+                        s_flag[slot][r] = 1u;
+                        kmask |= 1u << (2 * m + half);
+                    }
                 }
             }
         }
         __syncthreads();
         if (threadIdx.x < kTileRows) {
-            const unsigned long long m = __ballot(s_flag[threadIdx.x] != 0u);
-            s_rank[threadIdx.x] = __popcll(m & lt_mask);
-            if (lane == 0) s_wcount[wave] = __popcll(m);
+            const unsigned long long m = __ballot(s_flag[slot][threadIdx.x] != 0u);
+            s_rank[slot][threadIdx.x] = __popcll(m & lt_mask);
+            if (lane == 0) s_wcount[slot][wave] = __popcll(m);
         }
-        const int next = take_ticket();  // also orders s_rank / s_wcount
-        if (next < n_tiles) load_tile(next);
-        const int count = s_wcount[0] + s_wcount[1];
+        __syncthreads();
+        if (threadIdx.x == 0) publish_count(tile_state, tile, s_wcount[slot][0] + s_wcount[slot][1]);
+        return kmask;
+    };
+    // look-back and write of a tile whose decisions are in (v, kmask) and in slot `slot`
+    auto write_tile = [&](int tile, int slot, const float (&v)[16][2], unsigned kmask) {
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int oc = wave + 4 * m;
+            if (oc < channels) {
+                s_v[lane][oc] = (kmask >> (2 * m)) & 1u ? v[m][0] : 0.0f;
+                s_v[64 + lane][oc] = (kmask >> (2 * m + 1)) & 1u ? v[m][1] : 0.0f;
+            }
+        }
+        const int count = s_wcount[slot][0] + s_wcount[slot][1];
         if (wave == 0) {
-            const long long base = lookback_wave(tile_state, tile, count, ctr);
+            const long long base = lookback_published(tile_state, tile, count, ctr);
             if (lane == 0) {
                 if (tile == n_tiles - 1) ctr->n_rows = base + count;
                 s_base = base;
@@ -650,23 +693,67 @@ __global__ __launch_bounds__(256) void k_select_write64(Geom g, int channels, in
         }
         __syncthreads();
         const long long base = s_base;
-        if (threadIdx.x < kTileRows && s_flag[threadIdx.x]) {
-            const long long orow = base + s_rank[threadIdx.x] + (wave ? s_wcount[0] : 0);
+        if (threadIdx.x < kTileRows && s_flag[slot][threadIdx.x]) {
+            const long long orow = base + s_rank[slot][threadIdx.x] + (wave ? s_wcount[slot][0] : 0);
             if (orow < out_capacity) {
                 int c0, c1, c2;
                 site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
                 store_site(g, out_coords + orow * (1 + g.ndim), b, c0, c1, c2);
             }
         }
-        for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
-            const int r = i >> 6, c = i & 63;
-            if (c < channels && s_flag[r]) {
-                const long long orow = base + s_rank[r] + (r >= 64 ? s_wcount[0] : 0);
-                if (orow < out_capacity) out_feats[orow * channels + c] = s_v[r][c];
+        if (vec4) {  // 16 bytes per thread: 16 threads cover a row of 64 channels
+            for (int i = threadIdx.x; i < kTileRows * 16; i += 256) {
+                const int r = i >> 4, c = (i & 15) * 4;
+                if (c < channels && s_flag[slot][r]) {
+                    const long long orow = base + s_rank[slot][r] + (r >= 64 ? s_wcount[slot][0] : 0);
+                    if (orow < out_capacity) {
+                        float4 q;
+                        q.x = s_v[r][c];
+                        q.y = s_v[r][c + 1];
+                        q.z = s_v[r][c + 2];
+                        q.w = s_v[r][c + 3];
+                        *(float4*)(out_feats + orow * channels + c) = q;
+                    }
+                }
+            }
+        } else {
+            for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
+                const int r = i >> 6, c = i & 63;
+                if (c < channels && s_flag[slot][r]) {
+                    const long long orow = base + s_rank[slot][r] + (r >= 64 ? s_wcount[slot][0] : 0);
+                    if (orow < out_capacity) out_feats[orow * channels + c] = s_v[r][c];
+                }
             }
         }
-        __syncthreads();  // the tile buffers are free for the next tile
-        tile = next;
+        __syncthreads();  // s_v, s_base and this slot are free again
+    };
+
+    float va[16][2], vb[16][2];
+    // prologue: X = first ticket (loaded, decided), Y = second ticket (loads in flight)
+    int tile_x = take_ticket();
+    if (tile_x >= n_tiles) return;
+    load_tile(tile_x, va);
+    int tile_y = take_ticket();
+    if (tile_y < n_tiles) load_tile(tile_y, vb);
+    unsigned kmask_x = decide(tile_x, 0, va);
+    int slot_x = 0;
+    // One step: (P, Q) hold (X, Y).  Decide Y, fetch Z into P's registers once X has moved to LDS, write X.
+    auto step = [&](float (&P)[16][2], float (&Q)[16][2]) {
+        unsigned kmask_y = 0;
+        if (tile_y < n_tiles) kmask_y = decide(tile_y, slot_x ^ 1, Q);
+        const int tile_z = take_ticket();
+        write_tile(tile_x, slot_x, P, kmask_x);
+        if (tile_z < n_tiles) load_tile(tile_z, P);
+        tile_x = tile_y;
+        tile_y = tile_z;
+        kmask_x = kmask_y;
+        slot_x ^= 1;
+    };
+    for (;;) {
+        step(va, vb);
+        if (tile_x >= n_tiles) break;
+        step(vb, va);
+        if (tile_x >= n_tiles) break;
     }
 }
 
