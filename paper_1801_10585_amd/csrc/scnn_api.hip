@@ -164,6 +164,7 @@ struct ConvWs {
     unsigned* block_sums;
     int* cand_start;
     int* tile_start;
+    int* rows16_start;
     int* tap_active;
     int* tap_coord;
     double* wp;
@@ -213,6 +214,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->block_sums = c.take<unsigned>(sb);
     w->cand_start = c.take<int>(g.batch + 1);
     w->tile_start = c.take<int>(g.batch + 1);
+    w->rows16_start = c.take<int>(g.batch + 1);
     w->tap_active = c.take<int>(g.T);
     w->tap_coord = c.take<int>(g.T);
     w->wp = c.take<double>((size_t)g.T * c_in * w->c_out_pad);
@@ -322,13 +324,14 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     timer.mark();
     SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
     SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
-    SCNN_TRY(launch_sample_info(g, ws.cand_prefix, ws.cand_cap, ws.cand_start, ws.tile_start, ws.ctr, s));
+    SCNN_TRY(launch_sample_info(g, ws.cand_prefix, ws.cand_cap, ws.cand_start, ws.tile_start, ws.rows16_start,
+                                ws.ctr, s));
     SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, s));
     timer.mark();
     if (g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0) {
         SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,
-                                   ws.cand_start, ws.tile_start, ws.ctr, ws.pairs, ws.block_tap, ws.tile_hdr,
-                                   ws.block_cap, ws.tiles_cap, s));
+                                   ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, ws.pairs, ws.block_tap,
+                                   ws.tile_hdr, ws.block_cap, ws.tiles_cap, s));
         SCNN_TRY(launch_filter_mfma_layout(g, w, c_in, c_out, ws.wb, s));
         timer.mark();
         SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,

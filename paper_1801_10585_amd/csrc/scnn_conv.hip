@@ -148,7 +148,6 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
 // ---------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPairTapChunk = 32;                 // taps looked up per pass of the pair builder
 constexpr unsigned kPairRowShift = 24;            // pair = (local output row << 24) | input row
 constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
 constexpr unsigned kPadPair = (unsigned)kTileRows << kPairRowShift;  // list padding: dummy accumulator row, input row 0
@@ -157,35 +156,35 @@ constexpr int kStageBlocks = 208;                 // 16-pair blocks staged in LD
 // Pair lists of all tiles live in one global array of 16-entry blocks; a tile's blocks are contiguous, in
 // ascending (tap, output row) order.  tile_hdr[tile] = {first block, block count};
 // block_tap[block] = tap | (index of the block within its tap) << 8.
+// A tile's space is reserved in closed form, at most ceil(rows / 16) blocks per active tap, so a tile starts at
+// (active taps) * (16-row groups of all earlier tiles); unused blocks of a reservation are simply never read.
+// One wave builds one tile (lanes = output rows lane and lane + 64) and walks the taps in order, so that it needs
+// neither barriers nor a scan; the taps are looked up kPairTapGroup at a time to overlap their loads.
+constexpr int kPairTapGroup = 4;
 __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long long* __restrict__ occ,
                                                     const unsigned* __restrict__ occ_prefix, long long nnz_in,
                                                     const int* __restrict__ tap_active,
                                                     const int* __restrict__ tap_coord,
                                                     const unsigned* __restrict__ cand_lin,
                                                     const int* __restrict__ cand_start,
-                                                    const int* __restrict__ tile_start, Counters* ctr,
+                                                    const int* __restrict__ tile_start,
+                                                    const int* __restrict__ rows16_start, Counters* ctr,
                                                     unsigned* __restrict__ pairs, unsigned short* __restrict__ block_tap,
                                                     uint2* __restrict__ tile_hdr, long long block_cap) {
-    constexpr int TPW = kPairTapChunk / 4;  // taps per wave and pass
-    __shared__ unsigned char s_nblk[kPairTapChunk];
-    __shared__ unsigned s_base;   // first global block of the current pass
-    __shared__ unsigned s_total;  // blocks of this tile so far
+    constexpr int G = kPairTapGroup;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
     const int n_tiles = (int)ctr->n_tiles;
-    __shared__ int s_active;  // taps with a non-zero weight
-    if (wave == 0) {
-        int active = 0;
-        for (int t0 = 0; t0 < g.T; t0 += 64)
-            active += __popcll(__ballot(t0 + lane < g.T && tap_active[t0 + lane < g.T ? t0 + lane : 0] != 0));
-        if (lane == 0) s_active = active;
-    }
-    __syncthreads();
+    int active = 0;  // taps with a non-zero weight
+    for (int t0 = 0; t0 < g.T; t0 += 64)
+        active += __popcll(__ballot(t0 + lane < g.T && tap_active[t0 + lane < g.T ? t0 + lane : 0] != 0));
 
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    const int waves = (int)gridDim.x * 4;
+    for (int tile = (int)blockIdx.x * 4 + wave; tile < n_tiles; tile += waves) {
         const int b = sample_of_tile(tile_start, g.batch, tile);
-        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        const int lt = tile - tile_start[b];
+        const int first = cand_start[b] + lt * kTileRows;
         int nrows = cand_start[b + 1] - first;
         if (nrows > kTileRows) nrows = kTileRows;
         int sc[2][3];  // sites of rows lane and lane + 64
@@ -194,34 +193,26 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
             sc[h][0] = sc[h][1] = sc[h][2] = 0;
             if (h * 64 + lane < nrows) site_of(g, cand_lin[first + h * 64 + lane], sc[h][0], sc[h][1], sc[h][2]);
         }
-        // A tile's blocks must be contiguous, so its space is reserved in one piece up front: at most
-        // ceil(nrows / 16) blocks per active tap.  Unused blocks of the reservation are simply never read.
-        __syncthreads();  // s_base / s_total of the previous tile consumed
-        if (threadIdx.x == 0) {
-            const unsigned want = (unsigned)s_active * (unsigned)((nrows + 15) >> 4);
-            unsigned base = atomicAdd(&ctr->pair_blocks, want);
-            if ((long long)base + want > block_cap) {  // cannot happen with the documented workspace size
+        const long long tile_base = (long long)active * (rows16_start[b] + lt * (kTileRows / 16));
+        if (tile_base + (long long)active * ((nrows + 15) >> 4) > block_cap) {
+            // cannot happen with the documented workspace size
+            if (lane == 0) {
                 atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
-                base = 0xffffffffu;
+                tile_hdr[tile] = make_uint2(0u, 0u);
             }
-            s_base = base;
-            s_total = 0;
+            continue;
         }
-        __syncthreads();
-        const unsigned tile_base = s_base;
-        for (int tc = 0; tc < g.T; tc += kPairTapChunk) {
-            const int tmax = (g.T - tc) < kPairTapChunk ? (g.T - tc) : kPairTapChunk;
-            // ---- neighbour lookup: wave handles taps wave, wave + 4, ... for rows lane and lane + 64.  All occupancy
-            //      words are requested first, then all prefixes, so that the loads overlap.
-            long long key[TPW][2];
-            unsigned long long word[TPW][2];
-            unsigned nbr[TPW][2];
+        unsigned blk = (unsigned)tile_base;  // next free block
+        for (int t0 = 0; t0 < g.T; t0 += G) {
+            // ---- neighbour lookup: all occupancy words are requested first, then all prefixes
+            long long key[G][2];
+            unsigned long long word[G][2];
+            unsigned nbr[G][2];
 #pragma unroll
-            for (int m = 0; m < TPW; ++m) {
-                const int tt = wave + m * 4;
-                const int tcl = tc + (tt < tmax ? tt : 0);
-                const bool live = tt < tmax && tap_active[tcl];
-                const int tc3 = tap_coord[tcl];  // (t0, t1, t2) packed one byte each
+            for (int m = 0; m < G; ++m) {
+                const int t = (t0 + m) < g.T ? (t0 + m) : g.T - 1;
+                const bool live = (t0 + m) < g.T && tap_active[t];
+                const int tc3 = tap_coord[t];  // (t0, t1, t2) packed one byte each
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     key[m][h] = -1;
@@ -235,7 +226,7 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
                 }
             }
 #pragma unroll
-            for (int m = 0; m < TPW; ++m)
+            for (int m = 0; m < G; ++m)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     unsigned n = 0xffffffffu;
@@ -247,60 +238,39 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
                     }
                     nbr[m][h] = n;
                 }
+            // ---- pack: each tap's present pairs in ascending output row, padded to whole blocks of 16 with
+            //      entries that point at the dummy accumulator row
 #pragma unroll
-            for (int m = 0; m < TPW; ++m) {
-                const int tt = wave + m * 4;
-                const int cnt =
-                    __popcll(__ballot(nbr[m][0] != 0xffffffffu)) + __popcll(__ballot(nbr[m][1] != 0xffffffffu));
-                if (lane == 0) s_nblk[tt] = (unsigned char)((cnt + 15) >> 4);
+            for (int m = 0; m < G; ++m) {
+                const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu),
+                                         m1 = __ballot(nbr[m][1] != 0xffffffffu);
+                const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
+                const int nblk = (cnt + 15) >> 4;
+                unsigned* pl = pairs + (size_t)blk * 16;
+                if (nbr[m][0] != 0xffffffffu)
+                    pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
+                if (nbr[m][1] != 0xffffffffu)
+                    pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
+                if (lane < 16 && cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
+                if (lane < nblk) block_tap[blk + lane] = (unsigned short)((t0 + m) | (lane << 8));
+                blk += (unsigned)nblk;
             }
-            __syncthreads();
-            // ---- pack: taps ascending, each tap's present pairs in ascending output row, padded to whole blocks
-            //      of 16 with entries that point at the dummy accumulator row
-            int blk_incl = lane < tmax ? (int)s_nblk[lane] : 0;
-#pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int t = __shfl_up(blk_incl, d, 64);
-                if (lane >= d) blk_incl += t;
-            }
-            const unsigned pass_blocks = (unsigned)__shfl(blk_incl, 63, 64);
-            const unsigned pass_base = tile_base + s_total;
-            if (tile_base != 0xffffffffu) {
-#pragma unroll
-                for (int m = 0; m < TPW; ++m) {
-                    const int tt = wave + m * 4;
-                    const int incl = __shfl(blk_incl, tt, 64);
-                    const int nblk = tt < tmax ? (int)s_nblk[tt] : 0;
-                    const unsigned blk0 = pass_base + (unsigned)(incl - nblk);
-                    unsigned* pl = pairs + (size_t)blk0 * 16;
-                    const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu),
-                                             m1 = __ballot(nbr[m][1] != 0xffffffffu);
-                    const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
-                    if (nbr[m][0] != 0xffffffffu)
-                        pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
-                    if (nbr[m][1] != 0xffffffffu)
-                        pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
-                    if (cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
-                    if (lane < nblk) block_tap[blk0 + lane] = (unsigned short)((tc + tt) | (lane << 8));
-                }
-            }
-            __syncthreads();  // every wave has read s_total and s_nblk
-            if (threadIdx.x == 0) s_total += pass_blocks;
-            __syncthreads();
         }
-        if (threadIdx.x == 0)
-            tile_hdr[tile] = make_uint2(tile_base == 0xffffffffu ? 0u : tile_base, tile_base == 0xffffffffu ? 0u : s_total);
+        if (lane == 0) tile_hdr[tile] = make_uint2((unsigned)tile_base, blk - (unsigned)tile_base);
     }
 }
 
 hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                              long long nnz_in, const int* tap_active, const int* tap_coord,
-                             const unsigned* cand_lin, const int* cand_start, const int* tile_start, Counters* ctr,
-                             unsigned* pairs, unsigned short* block_tap, uint2* tile_hdr, long long block_cap,
-                             long long tiles_cap, hipStream_t s) {
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 16 ? 256 * 16 : tiles_cap);
+                             const unsigned* cand_lin, const int* cand_start, const int* tile_start,
+                             const int* rows16_start, Counters* ctr, unsigned* pairs, unsigned short* block_tap,
+                             uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s) {
+    long long blocks = (tiles_cap + 3) / 4;  // one wave per tile
+    if (blocks < 1) blocks = 1;
+    if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_pair_build, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, tap_active,
-                       tap_coord, cand_lin, cand_start, tile_start, ctr, pairs, block_tap, tile_hdr, block_cap);
+                       tap_coord, cand_lin, cand_start, tile_start, rows16_start, ctr, pairs, block_tap, tile_hdr,
+                       block_cap);
     return hipGetLastError();
 }
 

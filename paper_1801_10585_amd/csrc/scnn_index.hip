@@ -286,10 +286,13 @@ hipError_t launch_popcount(const unsigned long long* bits, long long n_words, un
 }
 
 // Per-sample candidate ranges and tile ranges.  Each sample's candidates are
-// padded to whole tiles so that a tile never spans two samples.
+// padded to whole tiles so that a tile never spans two samples.  rows16_start[b] =
+// 16-row groups of all earlier samples (each sample rounded up), the unit in which
+// the pair lists of the matrix-core path reserve their space.
 __global__ __launch_bounds__(256) void k_sample_info(Geom g, const unsigned* __restrict__ cand_prefix,
                                                      long long cand_cap, int* __restrict__ cand_start,
-                                                     int* __restrict__ tile_start, Counters* ctr) {
+                                                     int* __restrict__ tile_start, int* __restrict__ rows16_start,
+                                                     Counters* ctr) {
     const long long n_cand = ctr->n_cand;  // written by the scan
     const bool overflow = n_cand > cand_cap;
     for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) {
@@ -299,21 +302,25 @@ __global__ __launch_bounds__(256) void k_sample_info(Geom g, const unsigned* __r
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        int acc = 0;
+        int acc = 0, acc16 = 0;
         for (int b = 0; b < g.batch; ++b) {
             tile_start[b] = acc;
-            acc += (cand_start[b + 1] - cand_start[b] + kTileRows - 1) / kTileRows;
+            rows16_start[b] = acc16;
+            const int n = cand_start[b + 1] - cand_start[b];
+            acc += (n + kTileRows - 1) / kTileRows;
+            acc16 += (n + 15) / 16;
         }
         tile_start[g.batch] = acc;
+        rows16_start[g.batch] = acc16;
         ctr->n_tiles = acc;
         if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
     }
 }
 
 hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
-                              int* tile_start, Counters* ctr, hipStream_t s) {
+                              int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
     hipLaunchKernelGGL(k_sample_info, dim3(1), dim3(256), 0, s, g, cand_prefix, cand_cap, cand_start, tile_start,
-                       ctr);
+                       rows16_start, ctr);
     return hipGetLastError();
 }
 

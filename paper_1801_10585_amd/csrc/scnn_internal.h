@@ -181,7 +181,7 @@ hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, cons
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
 hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
-                              int* tile_start, Counters* ctr, hipStream_t s);
+                              int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
                             long long n_words, unsigned* cand_lin, long long cand_cap, hipStream_t s);
 
@@ -195,9 +195,9 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
 bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
 hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                              long long nnz_in, const int* tap_active, const int* tap_coord,
-                             const unsigned* cand_lin, const int* cand_start, const int* tile_start, Counters* ctr,
-                             unsigned* pairs, unsigned short* block_tap, uint2* tile_hdr, long long block_cap,
-                             long long tiles_cap, hipStream_t s);
+                             const unsigned* cand_lin, const int* cand_start, const int* tile_start,
+                             const int* rows16_start, Counters* ctr, unsigned* pairs, unsigned short* block_tap,
+                             uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s);
 hipError_t launch_filter_mfma_layout(const Geom& g, const float* w, int c_in, int c_out, float* wb, hipStream_t s);
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,

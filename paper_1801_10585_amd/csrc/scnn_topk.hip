@@ -671,10 +671,8 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
         if (threadIdx.x == 0) publish_count(tile_state, tile, s_wcount[slot][0] + s_wcount[slot][1]);
         return kmask;
     };
-    // look-back and write of a tile whose decisions are in (v, kmask) and in slot `slot`
-    auto write_tile = [&](int tile, int slot, const float (&v)[16][2], unsigned kmask) {
-        const int b = sample_of_tile(tile_start, g.batch, tile);
-        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+    // the surviving values of a tile, from registers to the transposition buffer
+    auto stage_tile = [&](const float (&v)[16][2], unsigned kmask) {
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int oc = wave + 4 * m;
@@ -683,6 +681,11 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
                 s_v[64 + lane][oc] = (kmask >> (2 * m + 1)) & 1u ? v[m][1] : 0.0f;
             }
         }
+    };
+    // look-back and write of the staged tile, whose row flags and ranks are in slot `slot`
+    auto write_tile = [&](int tile, int slot) {
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
         const int count = s_wcount[slot][0] + s_wcount[slot][1];
         if (wave == 0) {
             const long long base = lookback_published(tile_state, tile, count, ctr);
@@ -737,13 +740,14 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     if (tile_y < n_tiles) load_tile(tile_y, vb);
     unsigned kmask_x = decide(tile_x, 0, va);
     int slot_x = 0;
-    // One step: (P, Q) hold (X, Y).  Decide Y, fetch Z into P's registers once X has moved to LDS, write X.
+    // One step: (P, Q) hold (X, Y).  Decide Y, move X to LDS, fetch Z into P's registers, write X.
     auto step = [&](float (&P)[16][2], float (&Q)[16][2]) {
         unsigned kmask_y = 0;
         if (tile_y < n_tiles) kmask_y = decide(tile_y, slot_x ^ 1, Q);
         const int tile_z = take_ticket();
-        write_tile(tile_x, slot_x, P, kmask_x);
-        if (tile_z < n_tiles) load_tile(tile_z, P);
+        stage_tile(P, kmask_x);
+        if (tile_z < n_tiles) load_tile(tile_z, P);  // in flight during the look-back and the writes
+        write_tile(tile_x, slot_x);
         tile_x = tile_y;
         tile_y = tile_z;
         kmask_x = kmask_y;
