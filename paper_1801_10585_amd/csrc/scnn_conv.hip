@@ -307,7 +307,7 @@ __host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out) {
            + (size_t)kStageBlocks * 16 * sizeof(unsigned)            // staged pair blocks
            + (size_t)kStageBlocks * sizeof(unsigned short)           // tap / position of each staged block
            + (size_t)kStageBlocks * sizeof(unsigned)                 // round list
-           + 16;
+           + (kConvWaves + 1) * sizeof(int);
 }
 
 // Operands of one round = up to RB consecutive 16-pair blocks of ONE tap, fetched one round ahead of their use.
@@ -318,7 +318,7 @@ struct RoundRegs {
     unsigned oaddr[RB][4];  // LDS byte address of accumulator (row of result row 4*gq + v, channel jj)
 };
 
-// Work split: wave i of the workgroup takes rounds i, i + 4, ...  A wave multiplies its blocks against the whole
+// Work split: each wave of the workgroup takes a contiguous share of the rounds.  A wave multiplies its blocks against the whole
 // filter tap (all C_out channels), so an input row is fetched once per pair and a tap's weights once per round;
 // the price is that two waves may add to the same accumulator, which the LDS fp64 atomic makes safe but not
 // ordered: the fp64 sum can differ in its last bits from run to run.
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     unsigned* s_flat = (unsigned*)(s_c + (kTileRows + 1) * CS);                // [kStageBlocks][16] packed pairs
     unsigned short* s_btap = (unsigned short*)(s_flat + kStageBlocks * 16);    // [kStageBlocks]
     unsigned* s_rmeta = (unsigned*)(s_btap + kStageBlocks);  // [kStageBlocks] first block | blocks << 8 | tap << 16
-    int* s_nrounds = (int*)(s_rmeta + kStageBlocks);
+    int* s_wlo = (int*)(s_rmeta + kStageBlocks);  // [kConvWaves + 1] first round of each wave; the last = all rounds
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -377,8 +377,13 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
             __syncthreads();
             // ---- round list: a round = up to RB consecutive blocks of one tap.  It starts at every RB-th block of
             //      a tap's run (and at the start of the stage); entry = first block | blocks << 8 | tap << 16.
+            //      Wave w takes the rounds that start in the w-th quarter of the stage's blocks: contiguous, and
+            //      within one round of an even share of the blocks.
             if (wave == 0) {
                 int base = 0;
+                int lo[kConvWaves];
+#pragma unroll
+                for (int w = 0; w < kConvWaves; ++w) lo[w] = 0;
                 for (int i0 = 0; i0 < n_blocks; i0 += 64) {
                     const int i = i0 + lane;
                     unsigned bt[RB];
@@ -393,12 +398,19 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                     if (start)
                         s_rmeta[base + __popcll(m & lt_mask)] = (unsigned)i | (unsigned)nb << 8 | (bt[0] & 0xffu) << 16;
                     base += __popcll(m);
+#pragma unroll
+                    for (int w = 1; w < kConvWaves; ++w)  // rounds that start before the w-th share of the blocks
+                        lo[w] += __popcll(__ballot(start && i * kConvWaves < w * n_blocks));
                 }
-                if (lane == 0) *s_nrounds = base;
+                if (lane == 0) {
+#pragma unroll
+                    for (int w = 0; w < kConvWaves; ++w) s_wlo[w] = lo[w];
+                    s_wlo[kConvWaves] = base;
+                }
             }
             __syncthreads();
-            const int n_rounds = __builtin_amdgcn_readfirstlane(*s_nrounds);
-            const int my_rounds = (n_rounds - wave + kConvWaves - 1) / kConvWaves;  // rounds wave, wave + 4, ...
+            const int r_lo = __builtin_amdgcn_readfirstlane(s_wlo[wave]);
+            const int my_rounds = __builtin_amdgcn_readfirstlane(s_wlo[wave + 1]) - r_lo;
             if (my_rounds > 0) {
                 // The wave's pipeline, per round: list entry (LDS) -> pair entries of its blocks (LDS) -> operands
                 // (global) -> compute.  Each step is issued a full round before its result is needed, so that no
@@ -409,9 +421,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                     unsigned in[RB];  // pair jj of each block (its input row)
                     uint4 out[RB];    // pairs 4*gq .. 4*gq + 3 of each block (their result rows)
                 };
-                auto meta_at = [&](int j) {
-                    return s_rmeta[wave + kConvWaves * (j < my_rounds ? j : my_rounds - 1)];
-                };
+                auto meta_at = [&](int j) { return s_rmeta[r_lo + (j < my_rounds ? j : my_rounds - 1)]; };
                 auto read_entries = [&](unsigned meta, Entries& E) {
                     const int first = (int)(meta & 0xffu);
 #pragma unroll
