@@ -318,21 +318,21 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
 
     StageTimer timer(s);
     timer.mark();
-    SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
-    SCNN_TRY(launch_filter_prep(g, w, c_in, c_out, ws.c_out_pad, ws.wp, ws.tap_active, ws.tap_coord, s));
+    const bool use_mfma =
+        g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0;
+    SCNN_TRY(launch_prepare(g, w, c_in, c_out, ws.c_out_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
+                            ws.tap_coord, workspace, ws.zero_bytes, s));
     SCNN_TRY(launch_index_build(g, in_coords, nnz_in, nullptr, nnz_in, ws.occ, ws.occ_prefix, ws.ctr, s));
     timer.mark();
     SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
     SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
-    SCNN_TRY(launch_sample_info(g, ws.cand_prefix, ws.cand_cap, ws.cand_start, ws.tile_start, ws.rows16_start,
-                                ws.ctr, s));
-    SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, s));
+    SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start, ws.tile_start,
+                              ws.rows16_start, ws.ctr, s));
     timer.mark();
-    if (g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0) {
+    if (use_mfma) {
         SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,
                                    ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, ws.pairs, ws.block_tap,
                                    ws.tile_hdr, ws.block_cap, ws.tiles_cap, s));
-        SCNN_TRY(launch_filter_mfma_layout(g, w, c_in, c_out, ws.wb, s));
         timer.mark();
         SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,
                                   ws.ctr, ws.resp, s));
@@ -348,13 +348,12 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     if (!pool) {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                      ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats,
-                                     out_capacity, s));
+                                     out_capacity, (long long*)nnz_out, 0, 1, s));
         timer.mark();
-        SCNN_TRY(launch_finish(ws.ctr, 0, 0, 1, out_capacity, (long long*)nnz_out, s));
     } else {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                      ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, ws.tmp_coords, ws.tmp_feats,
-                                     ws.cand_cap, s));
+                                     ws.cand_cap, nullptr, 0, 0, s));
         timer.mark();
         SCNN_TRY(launch_zero(ws.occ, (size_t)nw * sizeof(unsigned long long), s));
         SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1, ws.occ,
@@ -482,8 +481,7 @@ int attention_topk(int ndim, const int32_t* extent, int batch, const int32_t* co
                          ws.ctr, s));
     SCNN_TRY(launch_select_write(g, channels, topk_mode, 0, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                  ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats, out_capacity,
-                                 s));
-    SCNN_TRY(launch_finish(ws.ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
+                                 (long long*)nnz_out, rows, 0, s));
     return SCNN_OK;
 }
 

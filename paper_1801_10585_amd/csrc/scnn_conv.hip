@@ -274,32 +274,6 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
     return hipGetLastError();
 }
 
-// Weights in matrix-core operand order: wb[((t * KC + kc) * NB + cb) * 64 + lane][s] = w[t][kc*32 + 8*gq + s][cb*16 + jj]
-// (lane = 16*gq + jj), so that a lane fetches its eight B values of one (tap, kc, cb) with two 16-byte loads.
-__global__ __launch_bounds__(256) void k_filter_mfma_layout(const float* __restrict__ w, int taps, int c_in, int c_out,
-                                                            float* __restrict__ wb) {
-    const int kcn = c_in / 32, nb = c_out / 16;
-    const long long total = (long long)taps * c_in * c_out;
-    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
-         i += (long long)gridDim.x * blockDim.x) {
-        const int s = (int)(i & 7), lane = (int)((i >> 3) & 63);
-        long long r = i >> 9;
-        const int cb = (int)(r % nb);
-        r /= nb;
-        const int kc = (int)(r % kcn), t = (int)(r / kcn);
-        const int jj = lane & 15, gq = lane >> 4;
-        wb[i] = w[((size_t)t * c_in + kc * 32 + 8 * gq + s) * c_out + cb * 16 + jj];
-    }
-}
-
-hipError_t launch_filter_mfma_layout(const Geom& g, const float* w, int c_in, int c_out, float* wb, hipStream_t s) {
-    const long long total = (long long)g.T * c_in * c_out;
-    long long blocks = (total + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_filter_mfma_layout, dim3((unsigned)blocks), dim3(256), 0, s, w, g.T, c_in, c_out, wb);
-    return hipGetLastError();
-}
-
 constexpr int kConvWaves = 4;  // waves per workgroup of the contraction kernel
 
 __host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out) {

@@ -150,25 +150,47 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
     return hipGetLastError();
 }
 
-// ------------------------------------------------------------------ filter preparation
-// One block per tap: widen the tap's [C_in, C_out] slice to fp64 in a layout whose
-// out-channel stride is padded to a multiple of 16, and record whether the tap
-// has any non-zero weight (pruned taps generate no candidate sites).
-__global__ __launch_bounds__(256) void k_filter_prep(Geom g, const float* __restrict__ w, int c_in, int c_out,
-                                                     int c_out_pad, double* __restrict__ wp,
-                                                     int* __restrict__ tap_active, int* __restrict__ tap_coord) {
+// Everything that has to happen before the input is indexed, in one launch.  Block t < T prepares tap t of the
+// filter: tap_active[t] = "has a non-zero weight", tap_coord[t] = its offset, and its weights in the layout of the
+// convolution kernel that will run -- wb (matrix-core operand order:
+// wb[((t * KC + kc) * NB + cb) * 64 + lane][s] = w[t][kc*32 + 8*gq + s][cb*16 + jj], lane = 16*gq + jj, so that a
+// lane fetches its eight values of one (tap, kc, cb) with two 16-byte loads) or wp (fp64, rows padded to
+// c_out_pad; the vector kernel).  The blocks from T on clear the zero-initialised part of the workspace.
+__global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict__ w, int c_in, int c_out,
+                                                 int c_out_pad, double* __restrict__ wp, float* __restrict__ wb,
+                                                 int* __restrict__ tap_active, int* __restrict__ tap_coord,
+                                                 uint4* __restrict__ zero_p, size_t zero_n16) {
+    if ((int)blockIdx.x >= g.T) {
+        const size_t stride = (size_t)(gridDim.x - g.T) * blockDim.x;
+        for (size_t i = (size_t)(blockIdx.x - g.T) * blockDim.x + threadIdx.x; i < zero_n16; i += stride)
+            zero_p[i] = make_uint4(0, 0, 0, 0);
+        return;
+    }
     __shared__ int s_any;
     const int t = blockIdx.x;
     if (threadIdx.x == 0) s_any = 0;
     __syncthreads();
     int any = 0;
-    const int n = c_in * c_out_pad;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) {
-        const int ic = i / c_out_pad, oc = i % c_out_pad;
-        float v = 0.0f;
-        if (oc < c_out) v = w[((size_t)t * c_in + ic) * c_out + oc];
-        wp[(size_t)t * n + i] = (double)v;
-        any |= (v != 0.0f);
+    if (wb) {
+        const int kcn = c_in / 32, nb = c_out / 16, n = c_in * c_out;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const int sub = i & 7, lane = (i >> 3) & 63;
+            const int r = i >> 9, cb = r % nb, kc = r / nb;  // (kc < kcn since n = kcn * nb * 512)
+            const int jj = lane & 15, gq = lane >> 4;
+            const float v = w[((size_t)t * c_in + kc * 32 + 8 * gq + sub) * c_out + cb * 16 + jj];
+            wb[(size_t)t * n + i] = v;
+            any |= (v != 0.0f);
+        }
+        (void)kcn;
+    } else {
+        const int n = c_in * c_out_pad;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const int ic = i / c_out_pad, oc = i % c_out_pad;
+            float v = 0.0f;
+            if (oc < c_out) v = w[((size_t)t * c_in + ic) * c_out + oc];
+            wp[(size_t)t * n + i] = (double)v;
+            any |= (v != 0.0f);
+        }
     }
     if (any) s_any = 1;
     __syncthreads();
@@ -179,10 +201,13 @@ __global__ __launch_bounds__(256) void k_filter_prep(Geom g, const float* __rest
     }
 }
 
-hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
-                              int* tap_active, int* tap_coord, hipStream_t s) {
-    hipLaunchKernelGGL(k_filter_prep, dim3(g.T), dim3(256), 0, s, g, w, c_in, c_out, c_out_pad, wp, tap_active,
-                       tap_coord);
+hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp, float* wb,
+                          int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes, hipStream_t s) {
+    const size_t n16 = (zero_bytes + 15) / 16;
+    size_t zb = (n16 + 255) / 256;
+    if (zb > 2048) zb = 2048;
+    hipLaunchKernelGGL(k_prepare, dim3((unsigned)(g.T + zb)), dim3(256), 0, s, g, w, c_in, c_out, c_out_pad, wp, wb,
+                       tap_active, tap_coord, (uint4*)zero_p, n16);
     return hipGetLastError();
 }
 
@@ -285,52 +310,44 @@ hipError_t launch_popcount(const unsigned long long* bits, long long n_words, un
     return hipGetLastError();
 }
 
-// Per-sample candidate ranges and tile ranges.  Each sample's candidates are
-// padded to whole tiles so that a tile never spans two samples.  rows16_start[b] =
-// 16-row groups of all earlier samples (each sample rounded up), the unit in which
-// the pair lists of the matrix-core path reserve their space.
-__global__ __launch_bounds__(256) void k_sample_info(Geom g, const unsigned* __restrict__ cand_prefix,
-                                                     long long cand_cap, int* __restrict__ cand_start,
-                                                     int* __restrict__ tile_start, int* __restrict__ rows16_start,
-                                                     Counters* ctr) {
-    const long long n_cand = ctr->n_cand;  // written by the scan
-    const bool overflow = n_cand > cand_cap;
-    for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) {
-        int v = 0;
-        if (!overflow) v = (b == g.batch) ? (int)n_cand : (int)cand_prefix[(long long)b * g.Wps];
-        cand_start[b] = v;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int acc = 0, acc16 = 0;
-        for (int b = 0; b < g.batch; ++b) {
-            tile_start[b] = acc;
-            rows16_start[b] = acc16;
-            const int n = cand_start[b + 1] - cand_start[b];
-            acc += (n + kTileRows - 1) / kTileRows;
-            acc16 += (n + 15) / 16;
-        }
-        tile_start[g.batch] = acc;
-        rows16_start[g.batch] = acc16;
-        ctr->n_tiles = acc;
-        if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
-    }
-}
-
-hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
-                              int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
-    hipLaunchKernelGGL(k_sample_info, dim3(1), dim3(256), 0, s, g, cand_prefix, cand_cap, cand_start, tile_start,
-                       rows16_start, ctr);
-    return hipGetLastError();
-}
-
-// One thread per bitmap word: write the per-sample site index of every set bit
-// at its rank.  The list comes out sorted by (b, lin).
+// Candidate list and its per-sample ranges, in one launch.
+// Last block: per-sample candidate ranges and tile ranges.  Each sample's candidates are padded to whole tiles so
+// that a tile never spans two samples.  rows16_start[b] = 16-row groups of all earlier samples (each sample
+// rounded up), the unit in which the pair lists of the matrix-core path reserve their space.
+// Other blocks, one thread per bitmap word: write the per-sample site index of every set bit at its rank.  The
+// list comes out sorted by (b, lin).
 __global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long long* __restrict__ cand,
                                                    const unsigned* __restrict__ cand_prefix, long long n_words,
-                                                   unsigned* __restrict__ cand_lin, long long cand_cap) {
+                                                   unsigned* __restrict__ cand_lin, long long cand_cap,
+                                                   int* __restrict__ cand_start, int* __restrict__ tile_start,
+                                                   int* __restrict__ rows16_start, Counters* ctr) {
+    if (blockIdx.x == gridDim.x - 1) {
+        const long long n_cand = ctr->n_cand;  // written by the scan
+        const bool overflow = n_cand > cand_cap;
+        for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) {
+            int v = 0;
+            if (!overflow) v = (b == g.batch) ? (int)n_cand : (int)cand_prefix[(long long)b * g.Wps];
+            cand_start[b] = v;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int acc = 0, acc16 = 0;
+            for (int b = 0; b < g.batch; ++b) {
+                tile_start[b] = acc;
+                rows16_start[b] = acc16;
+                const int n = cand_start[b + 1] - cand_start[b];
+                acc += (n + kTileRows - 1) / kTileRows;
+                acc16 += (n + 15) / 16;
+            }
+            tile_start[g.batch] = acc;
+            rows16_start[g.batch] = acc16;
+            ctr->n_tiles = acc;
+            if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+        }
+        return;
+    }
     for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
-         w += (long long)gridDim.x * blockDim.x) {
+         w += (long long)(gridDim.x - 1) * blockDim.x) {
         unsigned long long bits = cand[w];
         if (!bits) continue;
         long long o = cand_prefix[w];
@@ -345,12 +362,13 @@ __global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long l
 }
 
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
-                            long long n_words, unsigned* cand_lin, long long cand_cap, hipStream_t s) {
+                            long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
+                            int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
     long long blocks = (n_words + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)blocks), dim3(256), 0, s, g, cand, cand_prefix, n_words,
-                       cand_lin, cand_cap);
+    hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)blocks + 1), dim3(256), 0, s, g, cand, cand_prefix, n_words,
+                       cand_lin, cand_cap, cand_start, tile_start, rows16_start, ctr);
     return hipGetLastError();
 }
 

@@ -48,7 +48,7 @@ struct Counters {
     long long n_pool;     // rows after pooling
     unsigned flags;       // SCNN_FLAG_*
     int any_tie;          // some column needs tie ranks
-    unsigned pair_blocks; // 16-pair blocks handed out to tiles so far (matrix-core path)
+    unsigned finished;    // workgroups of the compaction pass that have ended
     unsigned ticket;      // next tile of the compaction pass
     unsigned long long side_cursor;  // side-buffer entries handed out to columns so far
 };
@@ -175,15 +175,14 @@ namespace scnn {
 hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_imm, const long long* n_dev,
                               long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
                               hipStream_t s);
-hipError_t launch_filter_prep(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp,
-                              int* tap_active, int* tap_coord, hipStream_t s);
+hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp, float* wb,
+                          int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes, hipStream_t s);
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
-hipError_t launch_sample_info(const Geom& g, const unsigned* cand_prefix, long long cand_cap, int* cand_start,
-                              int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
-                            long long n_words, unsigned* cand_lin, long long cand_cap, hipStream_t s);
+                            long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
+                            int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 
 // scnn_conv.hip
 hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
@@ -198,7 +197,6 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
                              const unsigned* cand_lin, const int* cand_start, const int* tile_start,
                              const int* rows16_start, Counters* ctr, unsigned* pairs, unsigned short* block_tap,
                              uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s);
-hipError_t launch_filter_mfma_layout(const Geom& g, const float* w, int c_in, int c_out, float* wb, hipStream_t s);
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,
                             const uint2* tile_hdr, const Counters* ctr, float* resp, hipStream_t s);
@@ -216,7 +214,8 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
-                               hipStream_t s);
+                               long long* nnz_out /* nullable: also write the result counters */, long long aux_imm,
+                               int aux_is_cand, hipStream_t s);
 
 // scnn_rows.hip
 hipError_t launch_relu(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,

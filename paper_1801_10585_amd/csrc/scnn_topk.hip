@@ -158,9 +158,13 @@ __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descen
 
 // grid = (columns, slices).  Histogram of the top 11 key bits over the column's entries.
 __global__ __launch_bounds__(256) void k_hist0(int mode, int channels, const int* __restrict__ tile_start,
-                                               const float* __restrict__ resp, unsigned* __restrict__ hist) {
+                                               const float* __restrict__ resp, unsigned* __restrict__ hist,
+                                               long long k, ColState* __restrict__ cols, Counters* ctr,
+                                               unsigned long long side_cap) {
     constexpr int U = 4;  // tiles per wave and iteration
     __shared__ unsigned s_hist[kHistBins];
+    __shared__ unsigned s_wave[4];
+    __shared__ int s_res[2];
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
     for (int i = threadIdx.x; i < kHistBins; i += 256) s_hist[i] = 0;
@@ -189,21 +193,19 @@ __global__ __launch_bounds__(256) void k_hist0(int mode, int channels, const int
         const unsigned c = s_hist[i];
         if (c) atomicAdd(&gh[i], c);
     }
-}
-
-// One block per column: the bin of the k-th strongest entry, and a slice of the side buffer for that bin.
-__global__ __launch_bounds__(256) void k_pick0(long long k, ColState* __restrict__ cols,
-                                               const unsigned* __restrict__ hist, Counters* ctr,
-                                               unsigned long long side_cap) {
-    __shared__ unsigned s_h[kHistBins];
-    __shared__ unsigned s_wave[4];
-    __shared__ int s_res[2];
-    const int col = blockIdx.x;
-    const unsigned* gh = hist + (size_t)col * kHistBins;
+    // The block that finishes a column last goes on to pick the bin of the k-th strongest entry and a slice of the
+    // side buffer for that bin.  (cols[col].pad counts the column's finished blocks until the state is written.)
+    // The histogram is only ever touched by device-scope atomics, which are performed at the point of coherence;
+    // the barrier waits for this block's to be acknowledged, so no cache flush (fence) is needed before the count.
+    __syncthreads();
+    if (threadIdx.x == 0) s_res[0] = (atomicAdd(&cols[col].pad, 1u) == gridDim.y - 1) ? 1 : 0;
+    __syncthreads();
+    if (!s_res[0]) return;
+    unsigned* s_h = s_hist;
     unsigned local = 0;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const unsigned c = gh[threadIdx.x * 8 + i];
+        const unsigned c = __hip_atomic_load(&gh[threadIdx.x * 8 + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_h[threadIdx.x * 8 + i] = c;
         local += c;
     }
@@ -373,8 +375,8 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const
     int slices = 2048 / (ncols > 0 ? ncols : 1);
     if (slices < 1) slices = 1;
     if (slices > 64) slices = 64;
-    hipLaunchKernelGGL(k_hist0, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, hist);
-    hipLaunchKernelGGL(k_pick0, dim3(ncols), dim3(256), 0, s, k, cols, hist, ctr, side_cap);
+    hipLaunchKernelGGL(k_hist0, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, hist, k, cols,
+                       ctr, side_cap);
     hipLaunchKernelGGL(k_collect, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, cols, side);
     hipLaunchKernelGGL(k_side_select, dim3(ncols), dim3(kSideThreads), 0, s, cols, side);
     return hipGetLastError();
@@ -457,6 +459,23 @@ __device__ inline long long lookback_wave(unsigned long long* tile_state, int ti
     return lookback_published(tile_state, tile, count, ctr);
 }
 
+// The result counters, written by the last workgroup of the compaction pass to end (nnz_out may be null: a later
+// kernel writes them).  aux = second counter: the candidate count (aux_is_cand) or a host-side number.
+__device__ inline void finish_if_last(Counters* ctr, long long* nnz_out, long long aux_imm, int aux_is_cand,
+                                      long long out_capacity) {
+    if (!nnz_out) return;
+    __syncthreads();  // (waits for the workgroup's counter updates, all device-scope atomics, to be acknowledged)
+    if (threadIdx.x != 0) return;
+    if (atomicAdd(&ctr->finished, 1u) != gridDim.x - 1) return;
+    const long long rows = __hip_atomic_load(&ctr->n_rows, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned flags = __hip_atomic_load(&ctr->flags, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (rows > out_capacity) flags |= SCNN_FLAG_OUT_OVERFLOW;
+    nnz_out[0] = rows;
+    nnz_out[1] = aux_is_cand ? ctr->n_cand : aux_imm;
+    nnz_out[2] = (long long)flags;
+    nnz_out[3] = 0;
+}
+
 __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int mode, int relu,
                                                       const int* __restrict__ cand_start,
                                                       const int* __restrict__ tile_start,
@@ -465,7 +484,8 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
                                                       const ColState* __restrict__ cols,
                                                       unsigned long long* tile_state, Counters* ctr,
                                                       int32_t* __restrict__ out_coords, float* __restrict__ out_feats,
-                                                      long long out_capacity) {
+                                                      long long out_capacity, long long* __restrict__ nnz_out,
+                                                      long long aux_imm, int aux_is_cand) {
     __shared__ unsigned s_tau[1024];
     __shared__ unsigned s_cut[1024];
     __shared__ unsigned s_flag[kTileRows];
@@ -544,7 +564,8 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
         if (wave == 0) {
             const long long base = lookback_wave(tile_state, tile, count, ctr);
             if (lane == 0) {
-                if (tile == n_tiles - 1) ctr->n_rows = base + count;
+                if (tile == n_tiles - 1)
+                    __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 s_base = base;
             }
         }
@@ -577,6 +598,7 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
             __syncthreads();
         }
     }
+    finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
 }
 
 // The same pass for up to 64 channels, software-pipelined over three tiles.  A workgroup holds tile X (being
@@ -592,7 +614,9 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
                                                         const ColState* __restrict__ cols,
                                                         unsigned long long* tile_state, Counters* ctr,
                                                         int32_t* __restrict__ out_coords,
-                                                        float* __restrict__ out_feats, long long out_capacity) {
+                                                        float* __restrict__ out_feats, long long out_capacity,
+                                                        long long* __restrict__ nnz_out, long long aux_imm,
+                                                        int aux_is_cand) {
     __shared__ unsigned s_tau[64];
     __shared__ unsigned s_cut[64];
     __shared__ unsigned s_flag[2][kTileRows];
@@ -690,7 +714,8 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
         if (wave == 0) {
             const long long base = lookback_published(tile_state, tile, count, ctr);
             if (lane == 0) {
-                if (tile == n_tiles - 1) ctr->n_rows = base + count;
+                if (tile == n_tiles - 1)
+                    __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 s_base = base;
             }
         }
@@ -734,7 +759,10 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     float va[16][2], vb[16][2];
     // prologue: X = first ticket (loaded, decided), Y = second ticket (loads in flight)
     int tile_x = take_ticket();
-    if (tile_x >= n_tiles) return;
+    if (tile_x >= n_tiles) {
+        finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
+        return;
+    }
     load_tile(tile_x, va);
     int tile_y = take_ticket();
     if (tile_y < n_tiles) load_tile(tile_y, vb);
@@ -759,6 +787,7 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
         step(vb, va);
         if (tile_x >= n_tiles) break;
     }
+    finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
 }
 
 __global__ void k_finish(const Counters* __restrict__ ctr, int which_rows, long long aux_imm, int aux_is_cand,
@@ -785,17 +814,17 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
-                               hipStream_t s) {
+                               long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
     // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
     if (channels <= 64)
         hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
-                           out_capacity);
+                           out_capacity, nnz_out, aux_imm, aux_is_cand);
     else
         hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
-                           out_capacity);
+                           out_capacity, nnz_out, aux_imm, aux_is_cand);
     return hipGetLastError();
 }
 
