@@ -281,7 +281,7 @@ __host__ __device__ inline size_t conv_mfma_lds_bytes(int c_out) {
            + (size_t)kStageBlocks * 16 * sizeof(unsigned)            // staged pair blocks
            + (size_t)kStageBlocks * sizeof(unsigned short)           // tap / position of each staged block
            + (size_t)kStageBlocks * sizeof(unsigned)                 // round list
-           + (kConvWaves + 1) * sizeof(int);
+           + (kConvWaves + 1 + 2) * sizeof(int);
 }
 
 // Operands of one round = up to RB consecutive 16-pair blocks of ONE tap, fetched one round ahead of their use.
@@ -304,7 +304,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                                                                const unsigned* __restrict__ pairs,
                                                                const unsigned short* __restrict__ block_tap,
                                                                const uint2* __restrict__ tile_hdr,
-                                                               const Counters* __restrict__ ctr,
+                                                               Counters* __restrict__ ctr,
                                                                float* __restrict__ resp) {
     constexpr int C_IN = KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
     constexpr int RB = (KC * NB <= 4) ? 3 : ((KC * NB <= 8) ? 2 : 1);  // blocks per round
@@ -316,6 +316,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     unsigned short* s_btap = (unsigned short*)(s_flat + kStageBlocks * 16);    // [kStageBlocks]
     unsigned* s_rmeta = (unsigned*)(s_btap + kStageBlocks);  // [kStageBlocks] first block | blocks << 8 | tap << 16
     int* s_wlo = (int*)(s_rmeta + kStageBlocks);  // [kConvWaves + 1] first round of each wave; the last = all rounds
+    int* s_next = s_wlo + kConvWaves + 1;         // [2] the workgroup's next tile (alternating slots)
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -327,7 +328,9 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     const unsigned lane_off = (unsigned)(size_t)s_c + (unsigned)jj * (unsigned)sizeof(double);
 
     // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
-    // the input rows shared by neighbouring tiles stay in that XCD's L2.
+    // the input rows shared by neighbouring tiles stay in that XCD's L2.  Within its span a workgroup starts with
+    // the tile of its slot and then draws tiles, in ascending order, from the span's counter: tiles differ in work,
+    // and a fixed assignment would leave workgroups idle at the end.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
     const int span = (n_tiles + 7) >> 3;
     const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
@@ -337,7 +340,10 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     // read past the end of a tile's list finds there names a valid input row.
     for (int i = threadIdx.x; i < kStageBlocks * 16; i += NT) s_flat[i] = 0u;
 
-    for (int tile = xcd * span + slot; tile < tile_end; tile += per_xcd) {
+    int parity = 0;
+    for (int tile = xcd * span + slot; tile < tile_end; parity ^= 1) {
+        // (the draw is read after the barrier before the epilogue, a whole tile later)
+        if (threadIdx.x == 0) s_next[parity] = xcd * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[xcd], 1u);
         const uint2 hdr = tile_hdr[tile];
         for (unsigned s0 = 0; s0 < hdr.y; s0 += kStageBlocks) {
             const int n_blocks = (int)((hdr.y - s0) < (unsigned)kStageBlocks ? (hdr.y - s0) : (unsigned)kStageBlocks);
@@ -503,6 +509,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
             }
         }
         __syncthreads();
+        const int next_tile = s_next[parity];
         // ---- epilogue: one rounding to fp32, bias on the non-zero entries, planar store; the accumulators are
         //      reset on the way.  A lane takes one row, a wave one channel at a time: consecutive rows lie
         //      CS doubles apart, i.e. 2 banks (mod 64), so the 64 reads of a wave spread over all LDS banks, and
@@ -534,13 +541,14 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                 }
             }
         }
+        tile = next_tile;
     }
 }
 
 template <int KC, int NB>
 static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* feats, const float* wb, const float* bias,
                                      const unsigned* pairs, const unsigned short* block_tap, const uint2* tile_hdr,
-                                     const Counters* ctr, float* resp, hipStream_t s) {
+                                     Counters* ctr, float* resp, hipStream_t s) {
     const size_t lds = conv_mfma_lds_bytes(NB * 16);
     static size_t attr_lds = 0;
     if (attr_lds < lds) {
@@ -566,7 +574,7 @@ bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
 
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,
-                            const uint2* tile_hdr, const Counters* ctr, float* resp, hipStream_t s) {
+                            const uint2* tile_hdr, Counters* ctr, float* resp, hipStream_t s) {
 #define SCNN_MFMA_CASE(KC_, NB_)                                                                                  \
     if (c_in == KC_ * 32 && c_out == NB_ * 16)                                                                    \
         return launch_conv_mfma_t<KC_, NB_>(g.T, nnz_in, feats, wb, bias, pairs, block_tap, tile_hdr, ctr, resp, s);

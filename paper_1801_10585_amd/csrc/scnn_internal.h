@@ -51,6 +51,7 @@ struct Counters {
     unsigned finished;    // workgroups of the compaction pass that have ended
     unsigned ticket;      // next tile of the compaction pass
     unsigned long long side_cursor;  // side-buffer entries handed out to columns so far
+    unsigned conv_ticket[8];  // tiles handed out so far in each of the contraction kernel's eight tile spans
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
@@ -199,7 +200,7 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
                              uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s);
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,
-                            const uint2* tile_hdr, const Counters* ctr, float* resp, hipStream_t s);
+                            const uint2* tile_hdr, Counters* ctr, float* resp, hipStream_t s);
 
 // scnn_topk.hip
 hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,
