@@ -329,8 +329,8 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
 
     // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
     // the input rows shared by neighbouring tiles stay in that XCD's L2.  Within its span a workgroup starts with
-    // the tile of its slot and then draws tiles, in ascending order, from the span's counter: tiles differ in work,
-    // and a fixed assignment would leave workgroups idle at the end.
+    // the tile of its slot and then draws tiles, in ascending order, from the span's counter (then from the other
+    // spans' counters): tiles differ in work, and a fixed assignment would leave workgroups idle at the end.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
     const int span = (n_tiles + 7) >> 3;
     const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
@@ -341,9 +341,20 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     for (int i = threadIdx.x; i < kStageBlocks * 16; i += NT) s_flat[i] = 0u;
 
     int parity = 0;
-    for (int tile = xcd * span + slot; tile < tile_end; parity ^= 1) {
-        // (the draw is read after the barrier before the epilogue, a whole tile later)
-        if (threadIdx.x == 0) s_next[parity] = xcd * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[xcd], 1u);
+    for (int tile = xcd * span + slot < tile_end ? xcd * span + slot : -1; tile >= 0; parity ^= 1) {
+        // Draw the next tile (read after the barrier before the epilogue, a whole tile later): from the own span,
+        // and once that is used up from the other spans, so that no XCD ends before the others.
+        if (threadIdx.x == 0) {
+            int t = -1;
+            for (int d = 0; d < 8 && t < 0; ++d) {
+                const int x = (xcd + d) & 7;
+                const int end_x = (x + 1) * span < n_tiles ? (x + 1) * span : n_tiles;
+                if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
+                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
+                if (cand < end_x) t = cand;
+            }
+            s_next[parity] = t;
+        }
         const uint2 hdr = tile_hdr[tile];
         for (unsigned s0 = 0; s0 < hdr.y; s0 += kStageBlocks) {
             const int n_blocks = (int)((hdr.y - s0) < (unsigned)kStageBlocks ? (hdr.y - s0) : (unsigned)kStageBlocks);
