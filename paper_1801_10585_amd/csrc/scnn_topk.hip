@@ -396,7 +396,7 @@ constexpr int kLookbackSpinLimit = 1 << 22;
 // nearest tile whose inclusive sum is known usually lies about as far back as there are workgroups; reading that
 // whole stretch with one batch of loads costs one memory round trip instead of one per 64 tiles.
 // Returns the number of surviving rows before the tile (valid in every lane).
-constexpr int kLookbackSlices = 8;
+constexpr int kLookbackSlices = 6;
 // (one thread) makes a tile's own count known to its successors
 __device__ inline void publish_count(unsigned long long* tile_state, int tile, int count) {
     __hip_atomic_store(&tile_state[tile], (tile == 0 ? kStateInclusive : kStateAggregate) | (unsigned long long)count,
@@ -606,6 +606,8 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
 // publishes Y's row count, takes the ticket for Z and issues Z's loads, and only then looks back for X and writes
 // it.  A tile's count is therefore known to its successors a whole step before its own look-back, so that a
 // look-back rarely finds a predecessor unpublished, and the reads of one tile overlap the writes of another.
+// The rows of a tile that keep an entry are two 64-bit masks (rows 0..63, 64..127) in one of three rotating slots;
+// a row's rank is a popcount.  Three barriers per step.
 __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels, int mode, int relu,
                                                         const int* __restrict__ cand_start,
                                                         const int* __restrict__ tile_start,
@@ -617,27 +619,18 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
                                                         float* __restrict__ out_feats, long long out_capacity,
                                                         long long* __restrict__ nnz_out, long long aux_imm,
                                                         int aux_is_cand) {
-    __shared__ unsigned s_tau[64];
-    __shared__ unsigned s_cut[64];
-    __shared__ unsigned s_flag[2][kTileRows];
-    __shared__ int s_rank[2][kTileRows];
-    __shared__ int s_wcount[2][2];
+    __shared__ uint4 s_thr[64];  // per channel: {threshold if the position passes the cut, threshold if not, cut, -}
+    __shared__ unsigned long long s_mask[3][2];
+    __shared__ int s_rank[kTileRows];  // output row of a kept row of the tile being written, relative; -1 = dropped
     __shared__ float s_v[kTileRows][65];
     __shared__ int s_ticket;
     __shared__ long long s_base;
 
     const int n_tiles = (int)ctr->n_tiles;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
     const bool vec4 = (channels & 3) == 0 && ((size_t)out_feats & 15) == 0;  // rows are 16-byte aligned
     int cur_b = -1;
 
-    auto take_ticket = [&]() {
-        __syncthreads();  // the previous ticket has been read by everybody
-        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
-        __syncthreads();
-        return s_ticket;
-    };
     // values of channel wave + 4*m at rows lane and lane + 64
     auto load_tile = [&](int tile, float (&v)[16][2]) {
         const float* seg = resp + ((size_t)tile * channels + wave) * kTileRows + lane;
@@ -649,137 +642,158 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
             }
         }
     };
-    // which of the thread's 32 values survive (bit 2*m + half); marks the rows that keep an entry, counts them
-    // and publishes the count
-    auto decide = [&](int tile, int slot, const float (&v)[16][2]) -> unsigned {
+    // Zeroes, in the registers, the thread's values that do not survive; the rows that keep an entry are OR-ed into
+    // the slot's masks (the slot is zero on entry).  An entry survives iff its key exceeds a threshold that depends
+    // on its position only through the tie cut: key > tau, or key >= tau (tau > 0) where the position is within
+    // the cut -- the same rule as "above tau, or equal to tau, non-zero and not past the cut".
+    auto decide = [&](int tile, int slot, float (&v)[16][2]) {
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const unsigned pos0 = (unsigned)(tile - tile_start[b]) * kTileRows;  // position of row 0 in its column
-        if (b != cur_b) {  // (uniform: every thread sees the same tiles)
-            __syncthreads();
+        if (b != cur_b) {  // (uniform: every thread sees the same tiles; the thresholds' readers are past a barrier)
             if (threadIdx.x < channels) {
                 const ColState* st = cols + (size_t)b * channels + threadIdx.x;
-                s_tau[threadIdx.x] = st->tau;
-                s_cut[threadIdx.x] = st->cut;
+                const unsigned tau = st->tau;
+                s_thr[threadIdx.x] = make_uint4(tau - (tau != 0u ? 1u : 0u), tau, st->cut, 0u);
             }
             cur_b = b;
+            __syncthreads();
         }
-        if (threadIdx.x < kTileRows) s_flag[slot][threadIdx.x] = 0;
-        __syncthreads();
-        unsigned kmask = 0;
+        bool row0 = false, row1 = false;
+        const unsigned p0 = pos0 + (unsigned)lane, p1 = p0 + 64u;
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int oc = wave + 4 * m;
             if (oc < channels) {
-                const unsigned tau = s_tau[oc], cut = s_cut[oc];
+                const uint4 t = s_thr[oc];
 #pragma unroll
                 for (int half = 0; half < 2; ++half) {
-                    const int r = half * 64 + lane;
                     const float x = v[m][half];
                     const unsigned key = score_key(x, mode);
-                    bool keep = key > tau || (key == tau && key != 0u && pos0 + (unsigned)r <= cut);
+                    bool keep = key > ((half ? p1 : p0) <= t.z ? t.x : t.y);
                     if (relu) keep = keep && (x > 0.0f);
-                    if (keep) {
-                        s_flag[slot][r] = 1u;
-                        kmask |= 1u << (2 * m + half);
-                    }
+                    v[m][half] = keep ? x : 0.0f;
+                    if (half == 0) row0 |= keep; else row1 |= keep;
                 }
             }
         }
-        __syncthreads();
-        if (threadIdx.x < kTileRows) {
-            const unsigned long long m = __ballot(s_flag[slot][threadIdx.x] != 0u);
-            s_rank[slot][threadIdx.x] = __popcll(m & lt_mask);
-            if (lane == 0) s_wcount[slot][wave] = __popcll(m);
+        const unsigned long long b0 = __ballot(row0), b1 = __ballot(row1);
+        if (lane == 0) {
+            if (b0) atomicOr(&s_mask[slot][0], b0);
+            if (b1) atomicOr(&s_mask[slot][1], b1);
         }
-        __syncthreads();
-        if (threadIdx.x == 0) publish_count(tile_state, tile, s_wcount[slot][0] + s_wcount[slot][1]);
-        return kmask;
     };
-    // the surviving values of a tile, from registers to the transposition buffer
-    auto stage_tile = [&](const float (&v)[16][2], unsigned kmask) {
+    // the surviving values of a tile (the others are zero already), from registers to the transposition buffer
+    auto stage_tile = [&](const float (&v)[16][2]) {
 #pragma unroll
         for (int m = 0; m < 16; ++m) {
             const int oc = wave + 4 * m;
             if (oc < channels) {
-                s_v[lane][oc] = (kmask >> (2 * m)) & 1u ? v[m][0] : 0.0f;
-                s_v[64 + lane][oc] = (kmask >> (2 * m + 1)) & 1u ? v[m][1] : 0.0f;
+                s_v[lane][oc] = v[m][0];
+                s_v[64 + lane][oc] = v[m][1];
             }
         }
     };
-    // look-back and write of the staged tile, whose row flags and ranks are in slot `slot`
-    auto write_tile = [&](int tile, int slot) {
+    // ranks of the rows of the tile about to be written (threads 0..127, between the step's last two barriers)
+    auto rank_rows = [&](int slot) {
+        if (threadIdx.x < kTileRows) {
+            const unsigned long long m0 = s_mask[slot][0], m1 = s_mask[slot][1];
+            const unsigned long long mine = wave ? m1 : m0, below = (1ull << lane) - 1ull;
+            const int rank = (wave ? __popcll(m0) : 0) + __popcll(mine & below);
+            s_rank[threadIdx.x] = ((mine >> lane) & 1ull) ? rank : -1;
+        }
+    };
+    // write of the staged tile: rows before the tile in s_base, rows within it in s_rank
+    auto write_tile = [&](int tile) {
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
-        const int count = s_wcount[slot][0] + s_wcount[slot][1];
-        if (wave == 0) {
-            const long long base = lookback_published(tile_state, tile, count, ctr);
-            if (lane == 0) {
-                if (tile == n_tiles - 1)
-                    __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_base = base;
-            }
-        }
-        __syncthreads();
         const long long base = s_base;
-        if (threadIdx.x < kTileRows && s_flag[slot][threadIdx.x]) {
-            const long long orow = base + s_rank[slot][threadIdx.x] + (wave ? s_wcount[slot][0] : 0);
-            if (orow < out_capacity) {
+        if (threadIdx.x < kTileRows) {
+            const int rank = s_rank[threadIdx.x];
+            if (rank >= 0 && base + rank < out_capacity) {
                 int c0, c1, c2;
                 site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
-                store_site(g, out_coords + orow * (1 + g.ndim), b, c0, c1, c2);
+                store_site(g, out_coords + (base + rank) * (1 + g.ndim), b, c0, c1, c2);
             }
         }
         if (vec4) {  // 16 bytes per thread: 16 threads cover a row of 64 channels
-            for (int i = threadIdx.x; i < kTileRows * 16; i += 256) {
-                const int r = i >> 4, c = (i & 15) * 4;
-                if (c < channels && s_flag[slot][r]) {
-                    const long long orow = base + s_rank[slot][r] + (r >= 64 ? s_wcount[slot][0] : 0);
-                    if (orow < out_capacity) {
+            const int c = (threadIdx.x & 15) * 4;
+            if (c < channels) {
+#pragma unroll
+                for (int it = 0; it < kTileRows / 16; ++it) {
+                    const int r = (threadIdx.x >> 4) + 16 * it;
+                    const int rank = s_rank[r];
+                    if (rank >= 0 && base + rank < out_capacity) {
                         float4 q;
                         q.x = s_v[r][c];
                         q.y = s_v[r][c + 1];
                         q.z = s_v[r][c + 2];
                         q.w = s_v[r][c + 3];
-                        *(float4*)(out_feats + orow * channels + c) = q;
+                        *(float4*)(out_feats + (base + rank) * channels + c) = q;
                     }
                 }
             }
         } else {
             for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
                 const int r = i >> 6, c = i & 63;
-                if (c < channels && s_flag[slot][r]) {
-                    const long long orow = base + s_rank[slot][r] + (r >= 64 ? s_wcount[slot][0] : 0);
-                    if (orow < out_capacity) out_feats[orow * channels + c] = s_v[r][c];
-                }
+                const int rank = s_rank[r];
+                if (c < channels && rank >= 0 && base + rank < out_capacity)
+                    out_feats[(base + rank) * channels + c] = s_v[r][c];
             }
         }
-        __syncthreads();  // s_v, s_base and this slot are free again
     };
 
+    if (threadIdx.x < 6) s_mask[threadIdx.x >> 1][threadIdx.x & 1] = 0ull;
+    if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+    __syncthreads();
     float va[16][2], vb[16][2];
     // prologue: X = first ticket (loaded, decided), Y = second ticket (loads in flight)
-    int tile_x = take_ticket();
+    int tile_x = s_ticket;
     if (tile_x >= n_tiles) {
         finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
         return;
     }
     load_tile(tile_x, va);
-    int tile_y = take_ticket();
+    __syncthreads();  // (the ticket has been read)
+    if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+    decide(tile_x, 0, va);
+    __syncthreads();
+    int tile_y = s_ticket;
     if (tile_y < n_tiles) load_tile(tile_y, vb);
-    unsigned kmask_x = decide(tile_x, 0, va);
-    int slot_x = 0;
+    if (threadIdx.x == 0) publish_count(tile_state, tile_x, __popcll(s_mask[0][0]) + __popcll(s_mask[0][1]));
+    int slot_x = 0, slot_y = 1, slot_z = 2;
     // One step: (P, Q) hold (X, Y).  Decide Y, move X to LDS, fetch Z into P's registers, write X.
     auto step = [&](float (&P)[16][2], float (&Q)[16][2]) {
-        unsigned kmask_y = 0;
-        if (tile_y < n_tiles) kmask_y = decide(tile_y, slot_x ^ 1, Q);
-        const int tile_z = take_ticket();
-        stage_tile(P, kmask_x);
+        __syncthreads();  // the previous step's writes are done: s_v, s_base, s_rank, s_ticket and slot_z are free
+        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        if (tile_y < n_tiles) decide(tile_y, slot_y, Q);
+        stage_tile(P);
+        __syncthreads();  // Y's masks, the ticket and the staged tile are in place
+        const int tile_z = s_ticket;
         if (tile_z < n_tiles) load_tile(tile_z, P);  // in flight during the look-back and the writes
-        write_tile(tile_x, slot_x);
+        rank_rows(slot_x);
+        if (wave == 0) {
+            if (lane == 0) {
+                s_mask[slot_z][0] = 0ull;  // (last read before this step's first barrier, next used after its last)
+                s_mask[slot_z][1] = 0ull;
+                if (tile_y < n_tiles)
+                    publish_count(tile_state, tile_y, __popcll(s_mask[slot_y][0]) + __popcll(s_mask[slot_y][1]));
+            }
+            const int count = __popcll(s_mask[slot_x][0]) + __popcll(s_mask[slot_x][1]);
+            const long long base = lookback_published(tile_state, tile_x, count, ctr);
+            if (lane == 0) {
+                if (tile_x == n_tiles - 1)
+                    __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_base = base;
+            }
+        }
+        __syncthreads();  // s_base, s_rank
+        write_tile(tile_x);
         tile_x = tile_y;
         tile_y = tile_z;
-        kmask_x = kmask_y;
-        slot_x ^= 1;
+        const int t = slot_x;
+        slot_x = slot_y;
+        slot_y = slot_z;
+        slot_z = t;
     };
     for (;;) {
         step(va, vb);
