@@ -342,19 +342,6 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
 
     int parity = 0;
     for (int tile = xcd * span + slot < tile_end ? xcd * span + slot : -1; tile >= 0; parity ^= 1) {
-        // Draw the next tile (read after the barrier before the epilogue, a whole tile later): from the own span,
-        // and once that is used up from the other spans, so that no XCD ends before the others.
-        if (threadIdx.x == 0) {
-            int t = -1;
-            for (int d = 0; d < 8 && t < 0; ++d) {
-                const int x = (xcd + d) & 7;
-                const int end_x = (x + 1) * span < n_tiles ? (x + 1) * span : n_tiles;
-                if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
-                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
-                if (cand < end_x) t = cand;
-            }
-            s_next[parity] = t;
-        }
         const uint2 hdr = tile_hdr[tile];
         for (unsigned s0 = 0; s0 < hdr.y; s0 += kStageBlocks) {
             const int n_blocks = (int)((hdr.y - s0) < (unsigned)kStageBlocks ? (hdr.y - s0) : (unsigned)kStageBlocks);
@@ -518,6 +505,20 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                     m1 = m3;
                 }
             }
+        }
+        // Draw the next tile: from the own span, and once that is used up from the other spans, so that no XCD ends
+        // before the others.  The last wave does it when its share of the tile is done: it has the smallest share
+        // on average and would otherwise only wait at the barrier, which hides the atomic's round trip.
+        if (threadIdx.x == NT - 64) {
+            int t = -1;
+            for (int d = 0; d < 8 && t < 0; ++d) {
+                const int x = (xcd + d) & 7;
+                const int end_x = (x + 1) * span < n_tiles ? (x + 1) * span : n_tiles;
+                if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
+                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
+                if (cand < end_x) t = cand;
+            }
+            s_next[parity] = t;
         }
         __syncthreads();
         const int next_tile = s_next[parity];
