@@ -157,8 +157,9 @@ int scnn_set_conv_path(int path);
 
 /* Measurement support (not part of the method): when enabled on the calling
  * thread, every sparse_conv_fwd call records HIP events on its stream at the
- * boundaries of its stages (index build, candidate sites, pair lists + weight
- * layout, convolution, k-selection, compaction + write, pooling).  scnn_profile_collect waits for
+ * boundaries of its stages (workspace clear + filter preparation + index build,
+ * candidate sites, pair lists, convolution, k-selection, compaction + write,
+ * pooling).  scnn_profile_collect waits for
  * the recorded calls, adds their per-stage milliseconds into stage_ms
  * [scnn_profile_stage_count()] and the number of calls into *calls, then
  * forgets them.  Host pointers. */
