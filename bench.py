@@ -51,6 +51,10 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index (1..5); 4 is the headline")
+    ap.add_argument("--paper-runtime", type=int, default=0, metavar="R",
+                    help="instead of --config: the paper's runtime experiment (Sec. 4.1) at resolution R "
+                         "(random sites, density = rho_up = 1/R, 1 -> 8 channels, batch 1); not the headline")
+    ap.add_argument("--rho-f", type=float, default=1.0, help="filter density of --paper-runtime")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB streaming copy (for scaling rocprofv3 memory counters)")
@@ -63,13 +67,13 @@ def main():
     import numpy as np
     import torch
     import paper_1801_10585_amd as scnn
-    from workloads import make_config
+    from workloads import make_config, make_paper_runtime
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
-    wl = make_config(args.config)
+    wl = make_paper_runtime(args.paper_runtime, args.rho_f) if args.paper_runtime else make_config(args.config)
     layer = wl.layers[0]
     w = wl.filters[0]
     ndim = wl.ndim
@@ -134,7 +138,7 @@ def main():
     bytes_alg = scnn.algorithmic_bytes(ndim, nnz_in, c_in, w.shape[0], c_out, n_cand, rows_out)
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"conv_cfg{args.config}_traffic.json")
-    if os.path.exists(tpath):
+    if not args.paper_runtime and os.path.exists(tpath):
         try:
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:

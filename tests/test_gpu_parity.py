@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_1801_10585_amd as scnn
 from tests.parity import assert_rows_well_formed, check_column, column, lin_index
-from workloads import make_config, make_filter, random_sparse_sites
+from workloads import make_config, make_filter, make_paper_runtime, random_sparse_sites
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -317,6 +317,24 @@ def test_config5_r256_5x5x5_full_size_sampled_columns(rho):
         band = check_column(lin_index(rc, wl.extent), rf[:, 0], got_lin, got_val, k, scnn.ABS,
                             where=f"cfg5 rho={rho} oc={oc}")
         say(f"cfg5 rho={rho} oc={oc} kept={len(got_lin)} band={band}")
+
+
+# ------------------------------------------------------------------ the paper's runtime experiment (Sec. 4.1)
+@pytest.mark.parametrize("r", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("rho_f", [0.1, 1.0])
+def test_paper_runtime_workload_random_sites(r, rho_f):
+    """Uniformly random sites at density 1/r, one input and eight output channels, rho_up = 1/r, batch 1."""
+    wl = make_paper_runtime(r, rho_f)
+    L = wl.layers[0]
+    k = scnn.k_from_rho(L.rho_up, r ** 3)
+    assert k == r * r
+    say(f"paper runtime r={r} rho_f={rho_f} rows={wl.coords.shape[0]} k={k}")
+    cols = None if r <= 64 else [(0, oc) for oc in (0, 3, 7)]
+    for mode in (scnn.ABS, scnn.SIGNED):
+        gc, gf, band = check_conv_against_oracle(wl.extent, 1, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k,
+                                                 L.rho_up, mode, columns=cols, tag=f"{wl.name} mode={mode}")
+        assert ((gf != 0).sum(axis=0) <= k).all()
+        say(f"  mode={mode} out rows={gc.shape[0]} density={gc.shape[0] / r ** 3:.4f} band={band}")
 
 
 # ------------------------------------------------------------------ edge cases and error reporting

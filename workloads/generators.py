@@ -220,3 +220,20 @@ def make_config(index: int, seed: int | None = None, *, r: int | None = None,
     return Workload(name=cfg["name"], ndim=ndim, extent=extent, batch=bb, coords=coords,
                     feats=np.ascontiguousarray(feats), layers=list(layers), filters=filters,
                     density=float(occ.mean()), seed=seed)
+
+
+def make_paper_runtime(r: int, rho_f: float, seed: int | None = None) -> Workload:
+    """The paper's own runtime experiment (Sec. 4.1): one r^3 grid whose sites are occupied independently with
+    probability 1/r and hold random non-zero values, one input channel, eight output channels, a 3x3x3 filter whose
+    weights are kept with probability rho_f, rho_up = 1/r, batch 1."""
+    seed = BASE_SEED + 1000 + r if seed is None else seed
+    rng = np.random.default_rng(seed)
+    extent = (r, r, r)
+    coords = random_sparse_sites(rng, extent, 1, 1.0 / r)
+    feats = _uniform_open_closed(rng, (coords.shape[0], 1))
+    layer = LayerSpec(c_in=1, c_out=8, ksize=(3, 3, 3), filter_density=rho_f, sigma=0.2, rho_up=1.0 / r,
+                      relu=False, pool=False)
+    w = make_filter(rng, layer.ksize, 1, 8, rho_f, layer.sigma)
+    return Workload(name=f"paper_runtime_r{r}_rhof{rho_f:g}", ndim=3, extent=extent, batch=1, coords=coords,
+                    feats=np.ascontiguousarray(feats), layers=[layer], filters=[w],
+                    density=coords.shape[0] / float(r) ** 3, seed=seed)
