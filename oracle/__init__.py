@@ -48,6 +48,10 @@ def _load():
         L.oracle_sparse_relu.argtypes = [ctypes.c_int, i32p, i32p, f32p, ctypes.c_int64, ctypes.c_int]
         L.oracle_sparse_maxpool.restype = ctypes.c_int64
         L.oracle_sparse_maxpool.argtypes = [ctypes.c_int, i32p, i32p, f32p, ctypes.c_int64, ctypes.c_int]
+        L.oracle_sparse_conv_bwd.restype = ctypes.c_int64
+        L.oracle_sparse_conv_bwd.argtypes = [ctypes.c_int, i32p, ctypes.c_int, i32p, f32p, ctypes.c_int64,
+                                             ctypes.c_int, i32p, f32p, ctypes.c_int, i32p, f32p, ctypes.c_int64,
+                                             f32p, f32p]
         L.oracle_result_rows.restype = ctypes.c_int64
         L.oracle_result_macs.restype = ctypes.c_int64
         L.oracle_result_threads.restype = ctypes.c_int
@@ -111,6 +115,33 @@ def sparse_conv_fwd(extent: Sequence[int], batch: int, coords, feats, ksize: Seq
     if return_info:
         return out + ({"macs": int(L.oracle_result_macs()), "threads": int(L.oracle_result_threads())},)
     return out
+
+
+def sparse_conv_bwd(extent: Sequence[int], batch: int, coords, feats, ksize: Sequence[int], w, g_coords, g_feats,
+                    return_info: bool = False):
+    """Algorithm 2 with the masks of Eq. 3.  Returns (bp_data [rows, C_in], bp_filter [T, C_in, C_out])."""
+    L = _load()
+    ndim = len(extent)
+    ext, extp = _i32(extent)
+    ks, ksp = _i32(ksize)
+    c, cp = _i32(coords)
+    f, fp = _f32(feats)
+    wa, wp = _f32(w)
+    gc, gcp = _i32(g_coords)
+    gf, gfp = _f32(g_feats)
+    c_in, c_out = int(wa.shape[1]), int(wa.shape[2])
+    assert wa.shape[0] == int(np.prod(ks)) and f.shape == (c.shape[0], c_in) and c.shape[1] == 1 + ndim
+    assert gf.shape == (gc.shape[0], c_out) and gc.shape[1] == 1 + ndim
+    bp_data = np.zeros((c.shape[0], c_in), dtype=np.float32)
+    bp_filter = np.zeros(wa.shape, dtype=np.float32)
+    visits = L.oracle_sparse_conv_bwd(ndim, extp, int(batch), cp, fp, c.shape[0], c_in, ksp, wp, c_out, gcp, gfp,
+                                      gc.shape[0], bp_data.ctypes.data_as(ctypes.POINTER(ctypes.c_float)),
+                                      bp_filter.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    if visits < 0:
+        raise ValueError("oracle_sparse_conv_bwd: bad arguments")
+    if return_info:
+        return bp_data, bp_filter, {"visits": int(visits)}
+    return bp_data, bp_filter
 
 
 def attention_topk(extent: Sequence[int], batch: int, coords, resp, k: int, topk_mode: int = ABS):

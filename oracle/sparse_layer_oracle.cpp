@@ -5,7 +5,8 @@
 // "Inference, Learning and Attention Mechanisms that Exploit and Preserve
 // Sparsity in CNNs"): Algorithm 1 (direct sparse convolution with attention),
 // Sec. 3.2 (k-selection on each output channel), Sec. 3.3 (pooling: rewrite
-// keys, sort, reduce each cluster).  It shares no code with the HIP library
+// keys, sort, reduce each cluster), Algorithm 2 with Eq. 3 (back-propagation
+// to non-zero inputs and un-pruned weights only).  It shares no code with the HIP library
 // and must never be called from the product path: only the tests, the smoke
 // check and the benchmark's CPU-baseline leg use it.
 //
@@ -371,6 +372,91 @@ int64_t oracle_sparse_maxpool(int ndim, const int32_t* extent, const int32_t* co
     assemble_rows(e, gp, channels, g_result);
     g_result.macs = 0;
     return g_result.rows;
+}
+
+// Algorithm 2 (back-propagation through the convolution) with the masks of
+// Eq. 3: gradients reach only non-zero input values and non-zero (un-pruned)
+// filter weights.  `g_coords`/`g_feats` hold the gradient of the loss with
+// respect to the layer's output as sparse rows on the output grid (the same
+// grid as the input: stride 1); sites without a row, and zero entries of a
+// row, carry no gradient.  bp_data has the shape of in_feats, bp_filter the
+// shape of w; both are overwritten.  Sums are carried in double and rounded to
+// float once.  Returns the number of multiply-add pairs visited (each visit
+// feeds both outputs), or a negative value on bad arguments.
+int64_t oracle_sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords,
+                               const float* in_feats, int64_t nnz_in, int c_in, const int32_t* ksize,
+                               const float* w, int c_out, const int32_t* g_coords, const float* g_feats,
+                               int64_t g_rows, float* bp_data, float* bp_filter) {
+    if (ndim < 1 || ndim > 3 || batch < 0 || c_in <= 0 || c_out <= 0) return -1;
+    Geometry g = make_geometry(ndim, extent);
+    int64_t ks[3] = {1, 1, 1}, h[3] = {0, 0, 0};
+    int64_t taps = 1;
+    for (int a = 0; a < ndim; ++a) {
+        if (ksize[a] <= 0 || ksize[a] % 2 == 0) return -1;
+        ks[a] = ksize[a];
+        h[a] = (ksize[a] - 1) / 2;
+        taps *= ksize[a];
+    }
+    // steps 1-2: both gradient tensors start at zero
+    std::vector<double> d_data((size_t)nnz_in * c_in, 0.0);
+    std::vector<double> d_filter((size_t)taps * c_in * c_out, 0.0);
+    // step 3: tap index -> d-dimensional offset
+    std::vector<int64_t> tap_delta(taps * 3, 0);
+    for (int64_t t = 0; t < taps; ++t) {
+        int64_t rem = t;
+        for (int a = ndim - 1; a >= 0; --a) {
+            tap_delta[t * 3 + a] = rem % ks[a] - h[a];
+            rem /= ks[a];
+        }
+    }
+    for (int64_t r = 0; r < nnz_in; ++r)
+        if (in_coords[r * (1 + ndim)] < 0 || in_coords[r * (1 + ndim)] >= batch) return -1;
+    for (int64_t r = 0; r < g_rows; ++r) {
+        if (g_coords[r * (1 + ndim)] < 0 || g_coords[r * (1 + ndim)] >= batch) return -1;
+        for (int a = 0; a < ndim; ++a)
+            if (g_coords[r * (1 + ndim) + 1 + a] < 0 || g_coords[r * (1 + ndim) + 1 + a] >= g.extent[a]) return -1;
+    }
+    int64_t visits = 0;
+    std::vector<double> buffer(g.n_sites);
+    for (int b = 0; b < batch; ++b) {                      // step 4
+        for (int oc = 0; oc < c_out; ++oc) {               // step 5
+            std::fill(buffer.begin(), buffer.end(), 0.0);  // step 6: dense buffer <- gradients(b, oc)
+            for (int64_t r = 0; r < g_rows; ++r) {
+                const int32_t* c = g_coords + r * (1 + ndim);
+                if (c[0] != b) continue;
+                int64_t p[3] = {0, 0, 0};
+                for (int a = 0; a < ndim; ++a) p[a] = c[1 + a];
+                buffer[lin_of(g, p)] = (double)g_feats[r * c_out + oc];
+            }
+            for (int ic = 0; ic < c_in; ++ic) {            // step 7
+                for (int64_t r = 0; r < nnz_in; ++r) {     // step 8: {id, val} in data(b, ic)
+                    if (in_coords[r * (1 + ndim)] != b) continue;
+                    const float val = in_feats[r * c_in + ic];
+                    if (val == 0.0f) continue;
+                    int64_t q[3] = {0, 0, 0};
+                    for (int a = 0; a < ndim; ++a) q[a] = in_coords[r * (1 + ndim) + 1 + a];
+                    for (int64_t t = 0; t < taps; ++t) {   // step 9: {fid, fval} in filter(oc, ic)
+                        const float fval = w[(t * c_in + ic) * c_out + oc];
+                        if (fval == 0.0f) continue;
+                        int64_t p[3] = {0, 0, 0};          // step 10: same get_update_id as the forward pass
+                        bool inside = true;
+                        for (int a = 0; a < ndim; ++a) {
+                            p[a] = q[a] - tap_delta[t * 3 + a];
+                            if (p[a] < 0 || p[a] >= g.extent[a]) inside = false;
+                        }
+                        if (!inside) continue;
+                        const double grad = buffer[lin_of(g, p)];                 // step 11
+                        d_data[(size_t)r * c_in + ic] += grad * (double)fval;     // step 12
+                        d_filter[((size_t)t * c_in + ic) * c_out + oc] += grad * (double)val;  // step 13
+                        ++visits;
+                    }
+                }
+            }
+        }
+    }
+    for (size_t i = 0; i < d_data.size(); ++i) bp_data[i] = (float)d_data[i];
+    for (size_t i = 0; i < d_filter.size(); ++i) bp_filter[i] = (float)d_filter[i];
+    return visits;
 }
 
 int64_t oracle_result_rows() { return g_result.rows; }
