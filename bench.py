@@ -45,6 +45,67 @@ def cpu_baseline(wl, layer, w, mac_total):
                       f"({info['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
 
 
+def bench_backward(args, wl, layer, w, coords, feats, wd):
+    """Backward pass of the same layer: gradient rows with the sparsity pattern of the layer's own output (taken
+    from one untimed forward call), random values.  A step = one sparse_conv_bwd call."""
+    import numpy as np
+    import torch
+    import paper_1801_10585_amd as scnn
+    dev = coords.device
+    nnz_in, c_in = wl.feats.shape
+    c_out = w.shape[2]
+    yc, yf, _ = scnn.sparse_conv_fwd(wl.extent, wl.batch, coords, feats, layer.ksize, wd, rho_up=layer.rho_up,
+                                     relu=layer.relu, pool=False)
+    gen = torch.Generator(device="cpu").manual_seed(wl.seed)
+    g_feats = (torch.randn(yf.shape, generator=gen).to(dev) * (yf != 0)).contiguous()
+    g_coords = yc.contiguous()
+    g_rows = int(g_coords.shape[0])
+    visits = scnn.count_bwd_visits(wl.extent, wl.batch, wl.coords, wl.feats, layer.ksize, w, g_coords.cpu().numpy())
+    ws_bytes = scnn.sparse_conv_bwd_workspace(wl.extent, wl.batch, nnz_in, c_in, c_out, layer.ksize, g_rows)
+    workspace = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+    out = (torch.empty((nnz_in, c_in), dtype=torch.float32, device=dev),
+           torch.empty(w.shape, dtype=torch.float32, device=dev), torch.zeros(4, dtype=torch.int64, device=dev))
+
+    def step():
+        scnn.sparse_conv_bwd(wl.extent, wl.batch, coords, feats, layer.ksize, wd, g_coords, g_feats,
+                             workspace=workspace, out=out, sync=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    scnn.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    scnn.profile_enable(False)
+    stage_ms, calls = scnn.profile_collect()
+    assert int(out[2].cpu()[2]) == 0
+    stage = {k: v / max(calls, 1) for k, v in stage_ms.items() if k.startswith("bwd_")}
+    ms_per_step = dt / args.steps * 1e3
+    mfma = c_out % 32 == 0 and c_out <= 128 and c_in % 16 == 0 and c_in <= 64
+    peak = PEAK_MFMA_FP32_TFLOPS if mfma else PEAK_FP64_VECTOR_TFLOPS
+    # the two contractions (bp_data and bp_filter) do one multiply-add per visit each
+    dominant = "bwd_filter" if stage["bwd_filter"] >= stage["bwd_data_conv"] else "bwd_data_conv"
+    tflops = 2.0 * visits / (stage[dominant] * 1e-3) / 1e12
+    line = {
+        "metric": "effective non-zero GMAC/s of the sparse conv backward pass (two multiply-adds per visit)",
+        "value": 2.0 * visits * args.steps / dt / 1e9, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name + "_backward", "grid": list(wl.extent), "batch": wl.batch, "c_in": c_in,
+                   "c_out": c_out, "ksize": list(layer.ksize), "filter_density": layer.filter_density,
+                   "rho_up": layer.rho_up, "rows_in": int(nnz_in), "gradient_rows": g_rows, "visits": int(visits),
+                   "seed": wl.seed},
+        "roofline": {"bound": "mfma" if mfma else "alu", "kernel": dominant, "achieved": tflops, "peak": peak,
+                     "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None, "kernel_ms": stage[dominant],
+                     "flops_per_launch": 2 * int(visits)},
+        "stage_ms": stage,
+    }
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -55,6 +116,8 @@ def main():
                     help="instead of --config: the paper's runtime experiment (Sec. 4.1) at resolution R "
                          "(random sites, density = rho_up = 1/R, 1 -> 8 channels, batch 1); not the headline")
     ap.add_argument("--rho-f", type=float, default=1.0, help="filter density of --paper-runtime")
+    ap.add_argument("--backward", action="store_true",
+                    help="time the backward pass (Algorithm 2) of the same layer instead; not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB streaming copy (for scaling rocprofv3 memory counters)")
@@ -84,6 +147,8 @@ def main():
     wd = torch.from_numpy(w).to(dev)
     nnz_in, c_in = wl.feats.shape
     c_out = w.shape[2]
+    if args.backward:
+        return bench_backward(args, wl, layer, w, coords, feats, wd)
     # size the buffers from a first (untimed) run: candidate count is data dependent
     oc0, of0, n0 = scnn.sparse_conv_fwd(wl.extent, wl.batch, coords, feats, layer.ksize, wd, rho_up=layer.rho_up,
                                         relu=layer.relu, pool=layer.pool)

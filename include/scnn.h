@@ -148,6 +148,42 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
 int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Back-propagation through the convolution (Algorithm 2) with the masks of
+ * Eq. 3: gradients reach only non-zero input values and non-zero (un-pruned)
+ * filter weights, so both results have the fixed shapes of the forward
+ * operands (Sec. 3.4, first advantage).
+ *
+ *   bp_data[r, ic]       = sum over taps t, channels oc of
+ *                          w[t, ic, oc] * g[b(r), site(r) - delta_t, oc]   if in_feats[r, ic] != 0, else 0
+ *   bp_filter[t, ic, oc] = sum over input rows r of
+ *                          in_feats[r, ic] * g[b(r), site(r) - delta_t, oc] if w[t, ic, oc] != 0, else 0
+ *
+ * with the forward pass's get_update_id (an input at q seen through tap delta
+ * belongs to output site q - delta; sites outside the grid contribute
+ * nothing).  g is the gradient of the loss with respect to the convolution's
+ * output, given as sparse rows on the output grid (same extent, stride 1):
+ * g_coords int32 [g_rows, 1+ndim] strictly ascending by (b, lin), g_feats fp32
+ * [g_rows, c_out]; sites without a row and zero entries carry no gradient (the
+ * caller zeroes the entries that the forward selection / ReLU dropped).
+ * in_coords / in_feats / w are the forward operands.  bp_data fp32
+ * [nnz_in, c_in] and bp_filter fp32 [prod(ksize), c_in, c_out] are overwritten
+ * entirely.  Sums are carried in fp64 and rounded to fp32 once, except that the
+ * matrix-core kernels (C_out a multiple of 32 up to 128, C_in a multiple of 16
+ * up to 64, 16-byte aligned value arrays) first add up to 32 products (bp_data)
+ * or the at most 128 products of one tap within one 128-row tile (bp_filter) in
+ * fp32.  bp_filter adds its partial sums in a fixed order: repeated calls give
+ * identical bits.  info (device, int64[SCNN_NNZ_LEN]) receives {nnz_in, g_rows,
+ * SCNN_FLAG_* bits, 0}; with SCNN_FLAG_BAD_COORD or SCNN_FLAG_UNSORTED set the
+ * results are undefined (all accesses stay in bounds).  All array arguments are
+ * device pointers; extent and ksize are host pointers.  Asynchronous on
+ * hip_stream; scnn_set_conv_path(1) forces the vector kernels here too. */
+size_t sparse_conv_bwd_workspace(int ndim, const int32_t* extent, int batch, int64_t nnz_in, int c_in, int c_out,
+                                 const int32_t* ksize, int64_t g_rows);
+int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, int c_out,
+                    const int32_t* g_coords, const float* g_feats, int64_t g_rows, float* bp_data, float* bp_filter,
+                    int64_t* info, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Kernel choice for the convolution step of sparse_conv_fwd, process-wide:
  * 0 = by shape (matrix-core kernel when C_in is a multiple of 32 up to 128 and
  * C_out a multiple of 16 up to 64, else the vector kernel), 1 = always the
@@ -159,7 +195,9 @@ int scnn_set_conv_path(int path);
  * thread, every sparse_conv_fwd call records HIP events on its stream at the
  * boundaries of its stages (workspace clear + filter preparation + index build,
  * candidate sites, pair lists, convolution, k-selection, compaction + write,
- * pooling).  scnn_profile_collect waits for
+ * pooling), and every sparse_conv_bwd call at the boundaries of its own
+ * (filter preparation + index of the gradient rows, pair lists, adjoint
+ * convolution, bp_data write, bp_filter).  scnn_profile_collect waits for
  * the recorded calls, adds their per-stage milliseconds into stage_ms
  * [scnn_profile_stage_count()] and the number of calls into *calls, then
  * forgets them.  Host pointers. */

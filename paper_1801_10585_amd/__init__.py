@@ -21,6 +21,8 @@ from .binding import (  # noqa: F401
     profile_enable,
     load_library,
     set_conv_path,
+    sparse_conv_bwd,
+    sparse_conv_bwd_workspace,
     sparse_conv_fwd,
     sparse_conv_fwd_max_rows,
     sparse_conv_fwd_workspace,
@@ -29,4 +31,4 @@ from .binding import (  # noqa: F401
     validate_rows,
     EXPORTED_SYMBOLS,
 )
-from .metrics import count_mac_nz, algorithmic_bytes  # noqa: F401
+from .metrics import count_mac_nz, count_bwd_visits, algorithmic_bytes  # noqa: F401

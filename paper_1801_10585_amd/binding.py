@@ -21,6 +21,7 @@ EXPORTED_SYMBOLS = [
     "sparse_conv_fwd", "attention_topk_workspace", "attention_topk", "sparse_relu_workspace", "sparse_relu",
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
+    "sparse_conv_bwd_workspace", "sparse_conv_bwd",
 ]
 
 
@@ -57,6 +58,10 @@ def load_library():
     L.sparse_conv_fwd.restype = ci
     L.sparse_conv_fwd.argtypes = [ci, i32p, ci, vp, vp, i64, ci, i32p, vp, vp, ci, dbl, ci, cu, vp, vp, i64, i64, vp,
                                   vp, sz, vp]
+    L.sparse_conv_bwd_workspace.restype = sz
+    L.sparse_conv_bwd_workspace.argtypes = [ci, i32p, ci, i64, ci, ci, i32p, i64]
+    L.sparse_conv_bwd.restype = ci
+    L.sparse_conv_bwd.argtypes = [ci, i32p, ci, vp, vp, i64, ci, i32p, vp, ci, vp, vp, i64, vp, vp, vp, vp, sz, vp]
     L.attention_topk_workspace.restype = sz
     L.attention_topk_workspace.argtypes = [ci, i32p, ci, i64, ci]
     L.attention_topk.restype = ci
@@ -191,6 +196,60 @@ def sparse_conv_fwd(extent, batch, coords, feats, ksize, w, bias=None, *, rho_up
                            _stream(stream))
     _check(L, rc)
     return _finish(out_coords, out_feats, nnz, sync)
+
+
+def sparse_conv_bwd(extent, batch, coords, feats, ksize, w, g_coords, g_feats, *, workspace=None, out=None,
+                    stream=None, sync=True):
+    """Back-propagation through the convolution (Algorithm 2 with the masks of Eq. 3).
+    Returns (bp_data [rows, C_in], bp_filter [T, C_in, C_out], info int64[4])."""
+    L = load_library()
+    ndim = len(extent)
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    w = _dev(w, torch.float32, "w")
+    g_coords = _dev(g_coords, torch.int32, "g_coords")
+    g_feats = _dev(g_feats, torch.float32, "g_feats")
+    nnz_in, c_in = feats.shape
+    taps, c_in_w, c_out = w.shape
+    g_rows = g_feats.shape[0]
+    if c_in_w != c_in or coords.shape != (nnz_in, 1 + ndim):
+        raise ValueError("shape mismatch between coords, feats and w")
+    if g_feats.shape[1] != c_out or g_coords.shape != (g_rows, 1 + ndim):
+        raise ValueError("shape mismatch between g_coords, g_feats and w")
+    t = 1
+    for s in ksize:
+        t *= int(s)
+    if t != taps:
+        raise ValueError("w.shape[0] != prod(ksize)")
+    ext, ks = _i32arr(extent), _i32arr(ksize)
+    dev = feats.device
+    need = int(L.sparse_conv_bwd_workspace(ndim, ext, int(batch), nnz_in, c_in, c_out, ks, g_rows))
+    if need == 0:
+        raise ScnnError(-1, L.scnn_last_error().decode())
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+    if out is None:
+        bp_data = torch.empty((nnz_in, c_in), dtype=torch.float32, device=dev)
+        bp_filter = torch.empty((taps, c_in, c_out), dtype=torch.float32, device=dev)
+        info = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+    else:
+        bp_data, bp_filter, info = out
+    rc = L.sparse_conv_bwd(ndim, ext, int(batch), _ptr(coords), _ptr(feats), nnz_in, c_in, ks, _ptr(w), c_out,
+                           _ptr(g_coords), _ptr(g_feats), g_rows, _ptr(bp_data), _ptr(bp_filter), _ptr(info),
+                           _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(L, rc)
+    if sync:
+        info = info.cpu()
+    return bp_data, bp_filter, info
+
+
+def sparse_conv_bwd_workspace(extent, batch, nnz_in, c_in, c_out, ksize, g_rows) -> int:
+    L = load_library()
+    r = int(L.sparse_conv_bwd_workspace(len(extent), _i32arr(extent), int(batch), int(nnz_in), int(c_in), int(c_out),
+                                        _i32arr(ksize), int(g_rows)))
+    if r == 0:
+        raise ScnnError(-1, L.scnn_last_error().decode())
+    return r
 
 
 def attention_topk(extent, batch, coords, resp, k, topk_mode=ABS, *, out_capacity=None, workspace=None, stream=None,

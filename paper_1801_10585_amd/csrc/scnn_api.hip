@@ -110,9 +110,15 @@ static long long default_cand_bound(const Geom& g, long long nnz_in) {
 
 
 // ---------------------------------------------------------------- per-stage timing (measurement support)
-static const char* const kStageNames[] = {"index_build", "candidates", "conv_prepare", "conv", "topk_select", "compact_write", "pool_finish"};
-static constexpr int kStages = 7;
-struct ProfCall { hipEvent_t ev[kStages + 1]; };
+// Stages 0..6 belong to sparse_conv_fwd, stages 7..11 to sparse_conv_bwd.
+static const char* const kStageNames[] = {"index_build", "candidates", "conv_prepare", "conv", "topk_select",
+                                          "compact_write", "pool_finish", "bwd_index", "bwd_pairs", "bwd_data_conv",
+                                          "bwd_data_write", "bwd_filter"};
+static constexpr int kFwdStages = 7, kBwdStages = 5, kStages = kFwdStages + kBwdStages;
+struct ProfCall {
+    hipEvent_t ev[kFwdStages + 1];
+    int first_stage, n_stages;
+};
 static thread_local bool g_prof_on = false;
 static thread_local std::vector<ProfCall>* g_prof_calls = nullptr;   // recorded, not yet collected
 static thread_local std::vector<ProfCall>* g_prof_pool = nullptr;    // idle events for reuse
@@ -122,7 +128,7 @@ struct StageTimer {
     bool on = false;
     int next = 0;
     hipStream_t s;
-    explicit StageTimer(hipStream_t stream) : s(stream) {
+    StageTimer(hipStream_t stream, int first_stage, int n_stages) : s(stream) {
         if (!g_prof_on) return;
         if (!g_prof_calls) g_prof_calls = new std::vector<ProfCall>();
         if (!g_prof_pool) g_prof_pool = new std::vector<ProfCall>();
@@ -130,17 +136,19 @@ struct StageTimer {
             call = g_prof_pool->back();
             g_prof_pool->pop_back();
         } else {
-            for (int i = 0; i <= kStages; ++i)
+            for (int i = 0; i <= kFwdStages; ++i)
                 if (hipEventCreate(&call.ev[i]) != hipSuccess) return;
         }
+        call.first_stage = first_stage;
+        call.n_stages = n_stages;
         on = true;
     }
     void mark() {  // boundary between stage next-1 and stage next
-        if (on && next <= kStages) (void)hipEventRecord(call.ev[next++], s);
+        if (on && next <= call.n_stages) (void)hipEventRecord(call.ev[next++], s);
     }
     void done() {
         if (!on) return;
-        while (next <= kStages) (void)hipEventRecord(call.ev[next++], s);
+        while (next <= call.n_stages) (void)hipEventRecord(call.ev[next++], s);
         g_prof_calls->push_back(call);
         on = false;
     }
@@ -316,11 +324,11 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     const bool pool = (fuse & SCNN_FUSE_MAXPOOL2) != 0;
     const int relu = (fuse & SCNN_FUSE_RELU) ? 1 : 0;
 
-    StageTimer timer(s);
+    StageTimer timer(s, 0, kFwdStages);
     timer.mark();
     const bool use_mfma =
         g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0;
-    SCNN_TRY(launch_prepare(g, w, c_in, c_out, ws.c_out_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
+    SCNN_TRY(launch_prepare(g, w, c_in, c_out, 0, ws.c_out_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
                             ws.tap_coord, workspace, ws.zero_bytes, s));
     SCNN_TRY(launch_index_build(g, in_coords, nnz_in, nullptr, nnz_in, ws.occ, ws.occ_prefix, ws.ctr, s));
     timer.mark();
@@ -332,7 +340,7 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     if (use_mfma) {
         SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,
                                    ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, ws.pairs, ws.block_tap,
-                                   ws.tile_hdr, ws.block_cap, ws.tiles_cap, s));
+                                   ws.tile_hdr, ws.block_cap, ws.tiles_cap, nullptr, s));
         timer.mark();
         SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,
                                   ws.ctr, ws.resp, s));
@@ -365,6 +373,148 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     return SCNN_OK;
 }
 
+// ---------------------------------------------------------------- sparse_conv_bwd
+namespace {
+struct BwdWs {
+    Counters* ctr;
+    unsigned long long* occ;  // occupancy of the gradient rows
+    size_t zero_bytes;
+    unsigned* occ_prefix;
+    int* cand_start;
+    int* tile_start;
+    int* rows16_start;
+    int* tap_active;
+    int* tap_coord;
+    double* wp;
+    unsigned* cand_lin;
+    float* resp;
+    unsigned* pairs;
+    unsigned short* block_tap;
+    float* wb;
+    uint2* tile_hdr;
+    unsigned short* tap_first;
+    double* fpart;
+    long long block_cap, tiles_cap;
+    int c_in_pad, chunks_mfma, chunks_valu;
+    bool mfma_shape;
+    size_t total;
+};
+void carve_bwd(void* base, const Geom& g, long long nnz_in, int c_in, int c_out, long long g_rows, BwdWs* w) {
+    Carver c(base);
+    const long long nw = (long long)g.batch * g.Wps;
+    const long long n_elem = (long long)g.T * c_in * c_out;
+    w->tiles_cap = (nnz_in + kTileRows - 1) / kTileRows + g.batch;
+    w->c_in_pad = (int)round_up(c_in, 16);
+    // the adjoint convolution contracts over C_out and produces C_in channels
+    w->mfma_shape = conv_mfma_supported(g, c_out, c_in, g_rows) && bwd_filter_mfma_supported(c_in, c_out);
+    w->chunks_mfma = w->mfma_shape ? bwd_filter_chunks(g, c_in, c_out, w->tiles_cap, true) : 0;
+    w->chunks_valu = bwd_filter_chunks(g, c_in, c_out, w->tiles_cap, false);
+    w->ctr = c.take<Counters>(1);
+    w->occ = c.take<unsigned long long>(nw);
+    w->zero_bytes = c.total();
+    w->occ_prefix = c.take<unsigned>(nw);
+    w->cand_start = c.take<int>(g.batch + 1);
+    w->tile_start = c.take<int>(g.batch + 1);
+    w->rows16_start = c.take<int>(g.batch + 1);
+    w->tap_active = c.take<int>(g.T);
+    w->tap_coord = c.take<int>(g.T);
+    w->wp = c.take<double>((size_t)g.T * c_out * w->c_in_pad);
+    w->cand_lin = c.take<unsigned>(nnz_in > 0 ? nnz_in : 1);
+    w->resp = c.take<float>((size_t)w->tiles_cap * c_in * kTileRows);
+    w->block_cap = w->mfma_shape ? (long long)g.T * (nnz_in / 16 + w->tiles_cap) : 0;
+    w->pairs = c.take<unsigned>((size_t)w->block_cap * 16);
+    w->block_tap = c.take<unsigned short>((size_t)w->block_cap);
+    w->wb = c.take<float>(w->mfma_shape ? (size_t)n_elem : 0);
+    w->tile_hdr = c.take<uint2>(w->mfma_shape ? w->tiles_cap : 0);
+    w->tap_first = c.take<unsigned short>(w->mfma_shape ? (size_t)w->tiles_cap * (g.T + 1) : 0);
+    const int chunks = w->chunks_mfma > w->chunks_valu ? w->chunks_mfma : w->chunks_valu;
+    w->fpart = c.take<double>((size_t)chunks * n_elem);
+    w->total = c.total();
+}
+int check_bwd_sizes(const Geom& g, long long nnz_in, int c_in, int c_out, long long g_rows) {
+    if (nnz_in < 0 || nnz_in > kMaxIndex - (long long)g.batch * kTileRows)
+        return fail(SCNN_ECAPACITY, "nnz_in = %lld out of range", nnz_in);
+    if (g_rows < 0 || g_rows > kMaxIndex) return fail(SCNN_ECAPACITY, "g_rows = %lld out of range", g_rows);
+    if (c_in < 1 || c_out < 1) return fail(SCNN_EINVAL, "channel counts must be positive");
+    if (c_in > kMaxChannels || c_out > kMaxChannels) return fail(SCNN_ECAPACITY, "at most %d channels", kMaxChannels);
+    if ((long long)g.T * c_in * c_out > kMaxIndex) return fail(SCNN_ECAPACITY, "filter too large");
+    return SCNN_OK;
+}
+}  // namespace
+
+size_t sparse_conv_bwd_workspace(int ndim, const int32_t* extent, int batch, int64_t nnz_in, int c_in, int c_out,
+                                 const int32_t* ksize, int64_t g_rows) {
+    Geom g;
+    if (!ksize || make_geom(ndim, extent, batch, ksize, &g) != SCNN_OK) return 0;
+    if (check_bwd_sizes(g, nnz_in, c_in, c_out, g_rows) != SCNN_OK) return 0;
+    BwdWs w;
+    carve_bwd(nullptr, g, nnz_in, c_in, c_out, g_rows, &w);
+    return w.total;
+}
+
+int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, int c_out,
+                    const int32_t* g_coords, const float* g_feats, int64_t g_rows, float* bp_data, float* bp_filter,
+                    int64_t* info, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Geom g;
+    if (!ksize) return fail(SCNN_EINVAL, "ksize is null");
+    int rc = make_geom(ndim, extent, batch, ksize, &g);
+    if (rc != SCNN_OK) return rc;
+    rc = check_bwd_sizes(g, nnz_in, c_in, c_out, g_rows);
+    if (rc != SCNN_OK) return rc;
+    if (!w || !bp_filter || !info || !workspace) return fail(SCNN_EINVAL, "null pointer (w, bp_filter, info or workspace)");
+    if (nnz_in > 0 && (!in_coords || !in_feats || !bp_data)) return fail(SCNN_EINVAL, "null input arrays");
+    if (g_rows > 0 && (!g_coords || !g_feats)) return fail(SCNN_EINVAL, "null gradient arrays");
+    if (((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "workspace must be 256-byte aligned");
+    BwdWs ws;
+    carve_bwd(workspace, g, nnz_in, c_in, c_out, g_rows, &ws);
+    if (ws.total > workspace_bytes)
+        return fail(SCNN_EWORKSPACE, "workspace too small: %zu < %zu bytes", workspace_bytes, ws.total);
+    hipStream_t s = (hipStream_t)hip_stream;
+    const long long n_elem = (long long)g.T * c_in * c_out;
+    const bool use_mfma = g_conv_path != 1 && ws.mfma_shape && nnz_in > 0 && ((uintptr_t)in_feats & 15) == 0 &&
+                          ((uintptr_t)g_feats & 15) == 0;
+    const int n_chunks = use_mfma ? ws.chunks_mfma : ws.chunks_valu;
+
+    StageTimer timer(s, kFwdStages, kBwdStages);
+    timer.mark();
+    // adjoint filter (taps negated, channels transposed) in the layout of the convolution kernel that will run;
+    // the same launch clears the counters and the occupancy bitmap
+    SCNN_TRY(launch_prepare(g, w, c_out, c_in, 1, ws.c_in_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
+                            ws.tap_coord, workspace, ws.zero_bytes, s));
+    SCNN_TRY(launch_index_build(g, g_coords, g_rows, nullptr, g_rows, ws.occ, ws.occ_prefix, ws.ctr, s));
+    SCNN_TRY(launch_rows_sample_bounds(g, in_coords, nnz_in, ws.cand_start, ws.tile_start, ws.ctr, s));
+    SCNN_TRY(launch_bwd_sites(g, in_coords, nnz_in, ws.cand_start, ws.cand_lin, ws.rows16_start, ws.ctr, s));
+    timer.mark();
+    if (use_mfma) {
+        SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, g_rows, ws.tap_active, ws.tap_coord, ws.cand_lin,
+                                   ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, ws.pairs, ws.block_tap,
+                                   ws.tile_hdr, ws.block_cap, ws.tiles_cap, ws.tap_first, s));
+        timer.mark();
+        SCNN_TRY(launch_conv_mfma(g, g_rows, g_feats, c_out, ws.wb, c_in, nullptr, ws.pairs, ws.block_tap,
+                                  ws.tile_hdr, ws.ctr, ws.resp, s));
+    } else {
+        timer.mark();
+        SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, g_rows, g_feats, c_out, ws.wp, c_in, ws.c_in_pad, nullptr,
+                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+    }
+    timer.mark();
+    SCNN_TRY(launch_bwd_data_write(g, ws.resp, in_feats, c_in, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
+                                   bp_data, s));
+    timer.mark();
+    if (use_mfma)
+        SCNN_TRY(launch_bwd_filter_mfma(g, in_feats, c_in, g_feats, c_out, ws.pairs, ws.tap_first, ws.tile_hdr,
+                                        ws.cand_start, ws.tile_start, ws.ctr, n_chunks, ws.fpart, s));
+    else
+        SCNN_TRY(launch_bwd_filter_valu(g, ws.occ, ws.occ_prefix, g_rows, g_feats, c_out, in_feats, c_in,
+                                        ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, n_chunks,
+                                        ws.fpart, s));
+    SCNN_TRY(launch_bwd_filter_finish(ws.fpart, n_chunks, n_elem, w, bp_filter, ws.ctr, nnz_in, g_rows,
+                                      (long long*)info, s));
+    timer.done();
+    return SCNN_OK;
+}
+
 int scnn_set_conv_path(int path) {
     if (path != 0 && path != 1) return fail(SCNN_EINVAL, "conv path must be 0 (auto) or 1 (vector kernel)");
     g_conv_path = path;
@@ -392,11 +542,11 @@ int scnn_profile_collect(double* stage_ms, int64_t* calls) {
     *calls = 0;
     if (!g_prof_calls) return SCNN_OK;
     for (ProfCall& c : *g_prof_calls) {
-        SCNN_TRY(hipEventSynchronize(c.ev[kStages]));
-        for (int i = 0; i < kStages; ++i) {
+        SCNN_TRY(hipEventSynchronize(c.ev[c.n_stages]));
+        for (int i = 0; i < c.n_stages; ++i) {
             float ms = 0.0f;
             SCNN_TRY(hipEventElapsedTime(&ms, c.ev[i], c.ev[i + 1]));
-            stage_ms[i] += (double)ms;
+            stage_ms[c.first_stage + i] += (double)ms;
         }
         ++*calls;
         g_prof_pool->push_back(c);

@@ -1,0 +1,390 @@
+// Back-propagation through the convolution (Algorithm 2, with the masks of Eq. 3).
+//
+// The paper walks the same loop nest as the forward pass and issues two atomic
+// adds per multiply (one into bp_data, one into bp_filter).  Here both outputs
+// are formed without value atomics:
+//
+//   bp_data[q, ic]      = sum over taps t, channels oc of  w[t, ic, oc] * g[q - delta_t, oc]     (x[q, ic] != 0)
+//   bp_filter[t, ic, oc] = sum over input rows q of         x[q, ic]    * g[q - delta_t, oc]     (w[t, ic, oc] != 0)
+//
+// bp_data is the forward convolution of the gradient rows with the adjoint
+// filter (taps negated, channels transposed), evaluated at the input's own
+// sites only: the forward kernels are reused with the input rows as the list
+// of output sites (gather form, fixed summation order in the vector kernel).
+// bp_filter is a reduction over (input row, gradient row) pairs per tap: every
+// workgroup (vector kernel) or wave (matrix-core kernel) sums a share of the
+// tiles into a private partial filter in fp64 and stores it; a last kernel
+// adds the partials in a fixed order, applies the mask and rounds to fp32 once.
+#include "scnn_internal.h"
+
+namespace scnn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kBwdTapChunk = 32;  // taps whose neighbour rows are staged in LDS at a time (vector kernel)
+
+// ------------------------------------------------------------------ input rows as the list of output sites
+// cand_lin[r] = site index of input row r; rows16_start[b] = 16-row groups of all earlier samples (the unit in
+// which the pair lists reserve their space).  Rows outside the grid or out of order are reported.
+__global__ __launch_bounds__(256) void k_bwd_sites(Geom g, const int32_t* __restrict__ coords, long long rows,
+                                                   const int* __restrict__ cand_start,
+                                                   unsigned* __restrict__ cand_lin, int* __restrict__ rows16_start,
+                                                   Counters* ctr) {
+    const int stride = 1 + g.ndim;
+    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < rows;
+         r += (long long)gridDim.x * blockDim.x) {
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        unsigned lin = 0;
+        if (site_in_grid(g, b, c0, c1, c2)) {
+            lin = (unsigned)lin_of(g, c0, c1, c2);
+            if (r > 0) {
+                int pb, p0, p1, p2;
+                load_site(g, coords + (r - 1) * stride, pb, p0, p1, p2);
+                if (site_in_grid(g, pb, p0, p1, p2) &&
+                    (long long)pb * g.Npad + lin_of(g, p0, p1, p2) >= (long long)b * g.Npad + lin)
+                    atomicOr(&ctr->flags, SCNN_FLAG_UNSORTED);
+            }
+        } else {
+            atomicOr(&ctr->flags, SCNN_FLAG_BAD_COORD);
+        }
+        cand_lin[r] = lin;
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        int acc16 = 0;
+        for (int b = 0; b < g.batch; ++b) {
+            rows16_start[b] = acc16;
+            acc16 += (cand_start[b + 1] - cand_start[b] + 15) / 16;
+        }
+        rows16_start[g.batch] = acc16;
+    }
+}
+
+hipError_t launch_bwd_sites(const Geom& g, const int32_t* coords, long long rows, const int* cand_start,
+                            unsigned* cand_lin, int* rows16_start, Counters* ctr, hipStream_t s) {
+    long long blocks = (rows + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_bwd_sites, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, rows, cand_start, cand_lin,
+                       rows16_start, ctr);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bp_data: planar tiles -> rows, masked by x != 0
+// resp[tile][ic][row] holds the adjoint convolution at the input rows of the tile (Eq. 3, first line: the
+// gradient reaches non-zero input values only).  Through LDS so that both sides coalesce.
+__global__ __launch_bounds__(256) void k_bwd_data_write(Geom g, const float* __restrict__ resp,
+                                                        const float* __restrict__ x, int c_in,
+                                                        const int* __restrict__ cand_start,
+                                                        const int* __restrict__ tile_start,
+                                                        const Counters* __restrict__ ctr,
+                                                        float* __restrict__ bp_data) {
+    __shared__ float s_t[kTileRows][65];
+    const int n_tiles = (int)ctr->n_tiles;
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        int nrows = cand_start[b + 1] - first;
+        if (nrows > kTileRows) nrows = kTileRows;
+        for (int cc = 0; cc < c_in; cc += 64) {
+            const int cw = (c_in - cc) < 64 ? (c_in - cc) : 64;
+            __syncthreads();
+            for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
+                const int c = i >> 7, r = i & 127;
+                if (c < cw) s_t[r][c] = resp[((size_t)tile * c_in + cc + c) * kTileRows + r];
+            }
+            __syncthreads();
+            for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
+                const int r = i >> 6, c = i & 63;
+                if (r < nrows && c < cw) {
+                    const size_t at = (size_t)(first + r) * c_in + cc + c;
+                    bp_data[at] = (x[at] != 0.0f) ? s_t[r][c] : 0.0f;
+                }
+            }
+        }
+    }
+}
+
+hipError_t launch_bwd_data_write(const Geom& g, const float* resp, const float* x, int c_in, const int* cand_start,
+                                 const int* tile_start, const Counters* ctr, long long tiles_cap, float* bp_data,
+                                 hipStream_t s) {
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 4096 ? 4096 : tiles_cap);
+    hipLaunchKernelGGL(k_bwd_data_write, dim3((unsigned)blocks), dim3(256), 0, s, g, resp, x, c_in, cand_start,
+                       tile_start, ctr, bp_data);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bp_filter, vector kernel (any shape)
+// Work item = (block of 256 consecutive filter elements in [t][ic][oc] order, share of the tiles).  A thread owns
+// one element and walks the rows of its tiles: row q contributes x[q, ic] * g[q - delta_t, oc] when the gradient
+// has a row at q - delta_t.  The neighbour rows of a tile are looked up once per tap and shared through LDS.
+// fp64 throughout; the partial sum of the share is stored (no atomics), zero included.
+__global__ __launch_bounds__(256) void k_bwd_filter_valu(Geom g, const unsigned long long* __restrict__ occ,
+                                                         const unsigned* __restrict__ occ_prefix, long long g_rows,
+                                                         const float* __restrict__ gf, int c_out,
+                                                         const float* __restrict__ x, int c_in,
+                                                         const int* __restrict__ tap_active /* adjoint tap order */,
+                                                         const unsigned* __restrict__ cand_lin,
+                                                         const int* __restrict__ cand_start,
+                                                         const int* __restrict__ tile_start,
+                                                         const Counters* __restrict__ ctr, int n_eb, int n_chunks,
+                                                         double* __restrict__ fpart) {
+    __shared__ int s_nbr[kTileRows][kBwdTapChunk + 1];
+    __shared__ int s_site[kTileRows][3];
+    const int n_tiles = (int)ctr->n_tiles;
+    const int cc = c_in * c_out;
+    const long long n_elem = (long long)g.T * cc;
+    const int eb = (int)(blockIdx.x % (unsigned)n_eb), chunk = (int)(blockIdx.x / (unsigned)n_eb);
+    const long long e = (long long)eb * 256 + threadIdx.x;
+    const bool valid = e < n_elem;
+    const int t_e = valid ? (int)(e / cc) : -1;
+    const int ic = valid ? (int)((e % cc) / c_out) : 0, oc = valid ? (int)(e % c_out) : 0;
+    const int t_lo = (int)(((long long)eb * 256) / cc);
+    long long e_hi = (long long)eb * 256 + 255;
+    if (e_hi > n_elem - 1) e_hi = n_elem - 1;
+    const int t_hi = (int)(e_hi / cc);
+    double acc = 0.0;
+
+    for (int tile = chunk; tile < n_tiles; tile += n_chunks) {
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        int nrows = cand_start[b + 1] - first;
+        if (nrows > kTileRows) nrows = kTileRows;
+        __syncthreads();  // readers of s_site / s_nbr of the previous tile are done
+        if (threadIdx.x < kTileRows) {
+            int c0 = 0, c1 = 0, c2 = 0;
+            if (threadIdx.x < nrows) site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
+            s_site[threadIdx.x][0] = c0;
+            s_site[threadIdx.x][1] = c1;
+            s_site[threadIdx.x][2] = c2;
+        }
+        for (int tc = t_lo; tc <= t_hi; tc += kBwdTapChunk) {
+            __syncthreads();
+            for (int i = threadIdx.x; i < kTileRows * kBwdTapChunk; i += 256) {
+                const int tt = i & (kBwdTapChunk - 1), r = i >> 5;
+                const int t = tc + tt;
+                int n = -1;
+                // a tap whose weights are all zero is masked out of bp_filter anyway
+                if (t <= t_hi && r < nrows && tap_active[g.T - 1 - t]) {
+                    const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
+                    n = lookup_row(g, occ, occ_prefix, g_rows, b, s_site[r][0] - (t0 - g.H[0]),
+                                   s_site[r][1] - (t1 - g.H[1]), s_site[r][2] - (t2 - g.H[2]));
+                }
+                s_nbr[r][tt] = n;
+            }
+            __syncthreads();
+            if (valid && t_e >= tc && t_e < tc + kBwdTapChunk) {
+                const int tt = t_e - tc;
+                for (int r = 0; r < nrows; ++r) {
+                    const int n = s_nbr[r][tt];
+                    if (n < 0) continue;
+                    acc = fma((double)x[(size_t)(first + r) * c_in + ic], (double)gf[(size_t)n * c_out + oc], acc);
+                }
+            }
+        }
+    }
+    if (valid) fpart[(size_t)chunk * n_elem + e] = acc;
+}
+
+hipError_t launch_bwd_filter_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                                  long long g_rows, const float* gf, int c_out, const float* x, int c_in,
+                                  const int* tap_active, const unsigned* cand_lin, const int* cand_start,
+                                  const int* tile_start, const Counters* ctr, int n_chunks, double* fpart,
+                                  hipStream_t s) {
+    const long long n_elem = (long long)g.T * c_in * c_out;
+    const int n_eb = (int)((n_elem + 255) / 256);
+    hipLaunchKernelGGL(k_bwd_filter_valu, dim3((unsigned)((long long)n_eb * n_chunks)), dim3(256), 0, s, g, occ,
+                       occ_prefix, g_rows, gf, c_out, x, c_in, tap_active, cand_lin, cand_start, tile_start, ctr,
+                       n_eb, n_chunks, fpart);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bp_filter, matrix-core kernel
+// Uses the pair lists of the adjoint convolution: per tile of 128 input rows and per adjoint tap t', blocks of 16
+// (local input row, gradient row) pairs.  For one tap the filter gradient is the contraction
+//     D[ic][oc] += sum over pairs  x[q(pair)][ic] * g[p(pair)][oc],
+// i.e. a [C_in x pairs] . [pairs x C_out] product whose long dimension is the pair list: the pairs are the K
+// dimension of v_mfma_f32_16x16x4_f32, four per instruction.  A wave owns one (tap, 16*MT input channels,
+// 16*NT output channels) slab and a share of the tiles; it keeps the slab in registers for its whole life:
+// fp32 matrix-core sums over the (at most 128) pairs of one tile, added to an fp64 copy after each tile.
+// Lane (jj = lane & 15, gq = lane >> 4) feeds pair 4*gq + j of a block in step j (the order of the pairs inside a
+// sum is free), input channels jj*MT + i and output channels jj*NT + i of the slab, so that its operands are one
+// 8- or 16-byte load per pair.
+template <int MT, int NT>
+__global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int c_out, const float* __restrict__ x,
+                                                         const float* __restrict__ gf,
+                                                         const unsigned* __restrict__ pairs,
+                                                         const unsigned short* __restrict__ tap_first,
+                                                         const uint2* __restrict__ tile_hdr,
+                                                         const int* __restrict__ cand_start,
+                                                         const int* __restrict__ tile_start, int batch,
+                                                         const Counters* __restrict__ ctr, int n_chunks,
+                                                         double* __restrict__ fpart) {
+    const int lane = threadIdx.x & 63;
+    const int jj = lane & 15, gq = lane >> 4;
+    const int n_icb = c_in / (16 * MT), n_ocb = c_out / (16 * NT);
+    const int slabs = taps * n_icb * n_ocb;
+    const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int chunk = __builtin_amdgcn_readfirstlane((int)(item / slabs));
+    if (chunk >= n_chunks) return;
+    const int slab = __builtin_amdgcn_readfirstlane((int)(item % slabs));
+    const int ta = slab / (n_icb * n_ocb);  // adjoint tap
+    const int icb = (slab / n_ocb) % n_icb, ocb = slab % n_ocb;
+    const int n_tiles = (int)ctr->n_tiles;
+    const float* __restrict__ xl = x + icb * 16 * MT + jj * MT;
+    const float* __restrict__ gl = gf + ocb * 16 * NT + jj * NT;
+
+    double acc64[MT][NT][4];
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int c = 0; c < NT; ++c)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc64[a][c][v] = 0.0;
+
+    for (int tile = chunk; tile < n_tiles; tile += n_chunks) {
+        const uint2 hdr = tile_hdr[tile];
+        const unsigned short* tf = tap_first + (size_t)tile * (taps + 1) + ta;
+        const unsigned b0 = hdr.x + tf[0], b1 = hdr.x + tf[1];
+        if (b0 >= b1 || hdr.y == 0) continue;
+        const int b = sample_of_tile(tile_start, batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        f32x4 acc[MT][NT];
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int c = 0; c < NT; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+        uint4 ent = *(const uint4*)(pairs + (size_t)b0 * 16 + gq * 4);
+        for (unsigned blk = b0; blk < b1; ++blk) {
+            const unsigned en[4] = {ent.x, ent.y, ent.z, ent.w};
+            if (blk + 1 < b1) ent = *(const uint4*)(pairs + (size_t)(blk + 1) * 16 + gq * 4);
+            float av[4][MT], bv[4][NT];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const unsigned row = en[j] >> kPairRowShift, in = en[j] & kPairInMask;
+                const bool live = row < (unsigned)kTileRows;  // list padding points at row 128
+                const float* xp = xl + (size_t)(first + (live ? row : 0u)) * c_in;
+                const float* gp = gl + (size_t)in * c_out;
+                if constexpr (MT == 1) {
+                    av[j][0] = live ? xp[0] : 0.0f;
+                } else {
+                    const float2 t2 = *(const float2*)xp;
+                    av[j][0] = live ? t2.x : 0.0f;
+                    av[j][1] = live ? t2.y : 0.0f;
+                }
+                if constexpr (NT == 2) {
+                    const float2 t2 = *(const float2*)gp;
+                    bv[j][0] = t2.x;
+                    bv[j][1] = t2.y;
+                } else {
+                    const float4 t4 = *(const float4*)gp;
+                    bv[j][0] = t4.x;
+                    bv[j][1] = t4.y;
+                    bv[j][2] = t4.z;
+                    bv[j][3] = t4.w;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int a = 0; a < MT; ++a)
+#pragma unroll
+                    for (int c = 0; c < NT; ++c)
+                        acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j][a], bv[j][c], acc[a][c], 0, 0, 0);
+        }
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int c = 0; c < NT; ++c)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc64[a][c][v] += (double)acc[a][c][v];
+    }
+    // result element (a, c, v) of this lane: input channel (4*gq + v)*MT + a, output channel jj*NT + c of the slab
+    const int t = taps - 1 - ta;  // tap of the filter itself
+    double* out = fpart + ((size_t)chunk * taps + t) * c_in * c_out;
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ic = icb * 16 * MT + (4 * gq + v) * MT + a;
+#pragma unroll
+            for (int c = 0; c < NT; ++c) out[(size_t)ic * c_out + ocb * 16 * NT + jj * NT + c] = acc64[a][c][v];
+        }
+}
+
+bool bwd_filter_mfma_supported(int c_in, int c_out) { return c_in % 16 == 0 && c_out % 32 == 0; }
+
+// waves per share of the tiles
+static int bwd_filter_slabs(const Geom& g, int c_in, int c_out) {
+    const int mt = (c_in % 32 == 0) ? 2 : 1, nt = (c_out % 64 == 0) ? 4 : 2;
+    return g.T * (c_in / (16 * mt)) * (c_out / (16 * nt));
+}
+
+int bwd_filter_chunks(const Geom& g, int c_in, int c_out, long long tiles_cap, bool mfma) {
+    long long chunks;
+    if (mfma) {
+        const int slabs = bwd_filter_slabs(g, c_in, c_out);
+        chunks = (256 * 12 + slabs - 1) / slabs;  // about twelve waves per compute unit
+        if (chunks > 256) chunks = 256;
+    } else {
+        const long long n_eb = ((long long)g.T * c_in * c_out + 255) / 256;
+        chunks = (4096 + n_eb - 1) / n_eb;
+        if (chunks > 512) chunks = 512;
+    }
+    if (chunks > tiles_cap) chunks = tiles_cap;
+    if (chunks < 1) chunks = 1;
+    return (int)chunks;
+}
+
+hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const float* gf, int c_out,
+                                  const unsigned* pairs, const unsigned short* tap_first, const uint2* tile_hdr,
+                                  const int* cand_start, const int* tile_start, const Counters* ctr, int n_chunks,
+                                  double* fpart, hipStream_t s) {
+    const long long waves = (long long)bwd_filter_slabs(g, c_in, c_out) * n_chunks;
+    const unsigned blocks = (unsigned)((waves + 3) / 4);
+#define SCNN_BWD_CASE(MT_, NT_)                                                                                   \
+    hipLaunchKernelGGL((k_bwd_filter_mfma<MT_, NT_>), dim3(blocks), dim3(256), 0, s, g.T, c_in, c_out, x, gf, pairs, \
+                       tap_first, tile_hdr, cand_start, tile_start, g.batch, ctr, n_chunks, fpart)
+    if (c_in % 32 == 0) {
+        if (c_out % 64 == 0) SCNN_BWD_CASE(2, 4); else SCNN_BWD_CASE(2, 2);
+    } else {
+        if (c_out % 64 == 0) SCNN_BWD_CASE(1, 4); else SCNN_BWD_CASE(1, 2);
+    }
+#undef SCNN_BWD_CASE
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ bp_filter: add the partials, mask, round
+// Eq. 3, second line: a weight that is exactly zero (pruned) receives no gradient.
+__global__ __launch_bounds__(256) void k_bwd_filter_finish(const double* __restrict__ fpart, int n_chunks,
+                                                           long long n_elem, const float* __restrict__ w,
+                                                           float* __restrict__ bp_filter) {
+    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= n_elem) return;
+    double sum = 0.0;
+    if (w[e] != 0.0f)
+        for (int c = 0; c < n_chunks; ++c) sum += fpart[(size_t)c * n_elem + e];
+    bp_filter[e] = (float)sum;
+}
+
+// also the place where the call's status words are written: {input rows, gradient rows, flags, 0}
+__global__ void k_bwd_status(const Counters* __restrict__ ctr, long long nnz_in, long long g_rows,
+                             long long* __restrict__ info) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) {
+        info[0] = nnz_in;
+        info[1] = g_rows;
+        info[2] = (long long)ctr->flags;
+        info[3] = 0;
+    }
+}
+
+hipError_t launch_bwd_filter_finish(const double* fpart, int n_chunks, long long n_elem, const float* w,
+                                    float* bp_filter, const Counters* ctr, long long nnz_in, long long g_rows,
+                                    long long* info, hipStream_t s) {
+    hipLaunchKernelGGL(k_bwd_filter_finish, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, fpart, n_chunks,
+                       n_elem, w, bp_filter);
+    hipLaunchKernelGGL(k_bwd_status, dim3(1), dim3(64), 0, s, ctr, nnz_in, g_rows, info);
+    return hipGetLastError();
+}
+
+}  // namespace scnn

@@ -148,8 +148,6 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
 // ---------------------------------------------------------------------------
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr unsigned kPairRowShift = 24;            // pair = (local output row << 24) | input row
-constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
 constexpr unsigned kPadPair = (unsigned)kTileRows << kPairRowShift;  // list padding: dummy accumulator row, input row 0
 constexpr int kStageBlocks = 208;                 // 16-pair blocks staged in LDS at a time by the contraction
 
@@ -170,7 +168,8 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
                                                     const int* __restrict__ tile_start,
                                                     const int* __restrict__ rows16_start, Counters* ctr,
                                                     unsigned* __restrict__ pairs, unsigned short* __restrict__ block_tap,
-                                                    uint2* __restrict__ tile_hdr, long long block_cap) {
+                                                    uint2* __restrict__ tile_hdr, long long block_cap,
+                                                    unsigned short* __restrict__ tap_first) {
     constexpr int G = kPairTapGroup;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -200,6 +199,8 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
                 atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
                 tile_hdr[tile] = make_uint2(0u, 0u);
             }
+            if (tap_first)
+                for (int t = lane; t <= g.T; t += 64) tap_first[(size_t)tile * (g.T + 1) + t] = 0;
             continue;
         }
         unsigned blk = (unsigned)tile_base;  // next free block
@@ -253,10 +254,16 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
                     pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
                 if (lane < 16 && cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
                 if (lane < nblk) block_tap[blk + lane] = (unsigned short)((t0 + m) | (lane << 8));
+                // optional: where each tap's blocks start within the tile (entry T = the tile's block count)
+                if (tap_first && lane == 0 && t0 + m < g.T)
+                    tap_first[(size_t)tile * (g.T + 1) + t0 + m] = (unsigned short)(blk - (unsigned)tile_base);
                 blk += (unsigned)nblk;
             }
         }
-        if (lane == 0) tile_hdr[tile] = make_uint2((unsigned)tile_base, blk - (unsigned)tile_base);
+        if (lane == 0) {
+            tile_hdr[tile] = make_uint2((unsigned)tile_base, blk - (unsigned)tile_base);
+            if (tap_first) tap_first[(size_t)tile * (g.T + 1) + g.T] = (unsigned short)(blk - (unsigned)tile_base);
+        }
     }
 }
 
@@ -264,13 +271,14 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
                              long long nnz_in, const int* tap_active, const int* tap_coord,
                              const unsigned* cand_lin, const int* cand_start, const int* tile_start,
                              const int* rows16_start, Counters* ctr, unsigned* pairs, unsigned short* block_tap,
-                             uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s) {
+                             uint2* tile_hdr, long long block_cap, long long tiles_cap, unsigned short* tap_first,
+                             hipStream_t s) {
     long long blocks = (tiles_cap + 3) / 4;  // one wave per tile
     if (blocks < 1) blocks = 1;
     if (blocks > 256 * 8) blocks = 256 * 8;
     hipLaunchKernelGGL(k_pair_build, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, tap_active,
                        tap_coord, cand_lin, cand_start, tile_start, rows16_start, ctr, pairs, block_tap, tile_hdr,
-                       block_cap);
+                       block_cap, tap_first);
     return hipGetLastError();
 }
 

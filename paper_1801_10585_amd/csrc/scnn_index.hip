@@ -156,7 +156,15 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
 // wb[((t * KC + kc) * NB + cb) * 64 + lane][s] = w[t][kc*32 + 8*gq + s][cb*16 + jj], lane = 16*gq + jj, so that a
 // lane fetches its eight values of one (tap, kc, cb) with two 16-byte loads) or wp (fp64, rows padded to
 // c_out_pad; the vector kernel).  The blocks from T on clear the zero-initialised part of the workspace.
-__global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict__ w, int c_in, int c_out,
+// With `adjoint` set the filter is read as the one of the adjoint convolution (back-propagation to the data):
+// `w` is then stored [T][c_out][c_in] and tap t of the adjoint is tap T-1-t of `w` (offset negated), i.e.
+// element (t, ic, oc) = w[T-1-t][oc][ic].
+__device__ inline float filter_at(const float* __restrict__ w, int T, int c_in, int c_out, int adjoint, int t, int ic,
+                                  int oc) {
+    return adjoint ? w[((size_t)(T - 1 - t) * c_out + oc) * c_in + ic] : w[((size_t)t * c_in + ic) * c_out + oc];
+}
+
+__global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict__ w, int c_in, int c_out, int adjoint,
                                                  int c_out_pad, double* __restrict__ wp, float* __restrict__ wb,
                                                  int* __restrict__ tap_active, int* __restrict__ tap_coord,
                                                  uint4* __restrict__ zero_p, size_t zero_n16) {
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
             const int sub = i & 7, lane = (i >> 3) & 63;
             const int r = i >> 9, cb = r % nb, kc = r / nb;  // (kc < kcn since n = kcn * nb * 512)
             const int jj = lane & 15, gq = lane >> 4;
-            const float v = w[((size_t)t * c_in + kc * 32 + 8 * gq + sub) * c_out + cb * 16 + jj];
+            const float v = filter_at(w, g.T, c_in, c_out, adjoint, t, kc * 32 + 8 * gq + sub, cb * 16 + jj);
             wb[(size_t)t * n + i] = v;
             any |= (v != 0.0f);
         }
@@ -187,7 +195,7 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
         for (int i = threadIdx.x; i < n; i += blockDim.x) {
             const int ic = i / c_out_pad, oc = i % c_out_pad;
             float v = 0.0f;
-            if (oc < c_out) v = w[((size_t)t * c_in + ic) * c_out + oc];
+            if (oc < c_out) v = filter_at(w, g.T, c_in, c_out, adjoint, t, ic, oc);
             wp[(size_t)t * n + i] = (double)v;
             any |= (v != 0.0f);
         }
@@ -201,13 +209,14 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
     }
 }
 
-hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp, float* wb,
-                          int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes, hipStream_t s) {
+hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int adjoint, int c_out_pad, double* wp,
+                          float* wb, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
+                          hipStream_t s) {
     const size_t n16 = (zero_bytes + 15) / 16;
     size_t zb = (n16 + 255) / 256;
     if (zb > 2048) zb = 2048;
-    hipLaunchKernelGGL(k_prepare, dim3((unsigned)(g.T + zb)), dim3(256), 0, s, g, w, c_in, c_out, c_out_pad, wp, wb,
-                       tap_active, tap_coord, (uint4*)zero_p, n16);
+    hipLaunchKernelGGL(k_prepare, dim3((unsigned)(g.T + zb)), dim3(256), 0, s, g, w, c_in, c_out, adjoint, c_out_pad, wp,
+                       wb, tap_active, tap_coord, (uint4*)zero_p, n16);
     return hipGetLastError();
 }
 

@@ -11,6 +11,9 @@ namespace scnn {
 constexpr int kTileRows = 128;    // candidate sites per response tile
 constexpr int kHistBins = 2048;   // bins per radix-select pass (11-bit digits)
 constexpr int kScanChunk = 2048;  // elements per block in the device scan
+// matrix-core pair lists: pair = (local row of the tile << 24) | row of the other operand
+constexpr unsigned kPairRowShift = 24;
+constexpr unsigned kPairInMask = (1u << kPairRowShift) - 1u;
 
 // Grid geometry, passed by value to kernels.
 struct Geom {
@@ -176,8 +179,9 @@ namespace scnn {
 hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_imm, const long long* n_dev,
                               long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
                               hipStream_t s);
-hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int c_out_pad, double* wp, float* wb,
-                          int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes, hipStream_t s);
+hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int adjoint, int c_out_pad, double* wp,
+                          float* wb, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
+                          hipStream_t s);
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
@@ -197,10 +201,33 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
                              long long nnz_in, const int* tap_active, const int* tap_coord,
                              const unsigned* cand_lin, const int* cand_start, const int* tile_start,
                              const int* rows16_start, Counters* ctr, unsigned* pairs, unsigned short* block_tap,
-                             uint2* tile_hdr, long long block_cap, long long tiles_cap, hipStream_t s);
+                             uint2* tile_hdr, long long block_cap, long long tiles_cap,
+                             unsigned short* tap_first /* nullable: [tiles][T + 1] first block of each tap */,
+                             hipStream_t s);
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,
                             const uint2* tile_hdr, Counters* ctr, float* resp, hipStream_t s);
+
+// scnn_bwd.hip
+hipError_t launch_bwd_sites(const Geom& g, const int32_t* coords, long long rows, const int* cand_start,
+                            unsigned* cand_lin, int* rows16_start, Counters* ctr, hipStream_t s);
+hipError_t launch_bwd_data_write(const Geom& g, const float* resp, const float* x, int c_in, const int* cand_start,
+                                 const int* tile_start, const Counters* ctr, long long tiles_cap, float* bp_data,
+                                 hipStream_t s);
+bool bwd_filter_mfma_supported(int c_in, int c_out);
+int bwd_filter_chunks(const Geom& g, int c_in, int c_out, long long tiles_cap, bool mfma);
+hipError_t launch_bwd_filter_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                                  long long g_rows, const float* gf, int c_out, const float* x, int c_in,
+                                  const int* tap_active, const unsigned* cand_lin, const int* cand_start,
+                                  const int* tile_start, const Counters* ctr, int n_chunks, double* fpart,
+                                  hipStream_t s);
+hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const float* gf, int c_out,
+                                  const unsigned* pairs, const unsigned short* tap_first, const uint2* tile_hdr,
+                                  const int* cand_start, const int* tile_start, const Counters* ctr, int n_chunks,
+                                  double* fpart, hipStream_t s);
+hipError_t launch_bwd_filter_finish(const double* fpart, int n_chunks, long long n_elem, const float* w,
+                                    float* bp_filter, const Counters* ctr, long long nnz_in, long long g_rows,
+                                    long long* info, hipStream_t s);
 
 // scnn_topk.hip
 hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,

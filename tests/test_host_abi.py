@@ -90,6 +90,27 @@ def test_mac_count_matches_oracle_loop_count():
     assert macs == info["macs"]
 
 
+def test_backward_visit_count_matches_oracle_loop_counter():
+    import numpy as np
+    import oracle
+    from workloads import make_filter, random_sparse_sites
+    rng = np.random.default_rng(0)
+    for extent, batch, ci, co, ks in [((9, 7), 2, 3, 4, (3, 5)), ((6, 7, 5), 2, 2, 3, (3, 3, 3))]:
+        c = random_sparse_sites(rng, extent, batch, 0.3)
+        f = rng.normal(size=(c.shape[0], ci)).astype(np.float32)
+        f *= rng.random(f.shape) > 0.3
+        w = make_filter(rng, ks, ci, co, 0.5, 0.3)
+        # the oracle's loop visits every in-grid site of its dense gradient buffer; with a gradient row on every
+        # site the two counts must agree, and thinning the gradient rows can only lower the count of rows met
+        full = random_sparse_sites(rng, extent, batch, 1.1)
+        _, _, info = oracle.sparse_conv_bwd(extent, batch, c, f, ks, w, full, np.ones((full.shape[0], co), np.float32),
+                                            return_info=True)
+        assert scnn.count_bwd_visits(extent, batch, c, f, ks, w, full) == info["visits"]
+        assert scnn.count_bwd_visits(extent, batch, c, f, ks, w, full) == scnn.count_mac_nz(extent, c, f, ks, w)
+        thin = random_sparse_sites(rng, extent, batch, 0.4)
+        assert 0 < scnn.count_bwd_visits(extent, batch, c, f, ks, w, thin) < info["visits"]
+
+
 def test_operators_refuse_cpu_tensors():
     import torch
     c = torch.zeros((1, 4), dtype=torch.int32)
