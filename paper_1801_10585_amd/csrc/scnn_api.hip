@@ -406,7 +406,7 @@ void carve_bwd(void* base, const Geom& g, long long nnz_in, int c_in, int c_out,
     w->tiles_cap = (nnz_in + kTileRows - 1) / kTileRows + g.batch;
     w->c_in_pad = (int)round_up(c_in, 16);
     // the adjoint convolution contracts over C_out and produces C_in channels
-    w->mfma_shape = conv_mfma_supported(g, c_out, c_in, g_rows) && bwd_filter_mfma_supported(c_in, c_out);
+    w->mfma_shape = conv_mfma_supported(g, c_out, c_in, g_rows) && bwd_filter_mfma_supported(c_in, c_out, g_rows);
     w->chunks_mfma = w->mfma_shape ? bwd_filter_chunks(g, c_in, c_out, w->tiles_cap, true) : 0;
     w->chunks_valu = bwd_filter_chunks(g, c_in, c_out, w->tiles_cap, false);
     w->ctr = c.take<Counters>(1);

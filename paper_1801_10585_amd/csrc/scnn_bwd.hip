@@ -89,17 +89,15 @@ __global__ __launch_bounds__(256) void k_bwd_data_write(Geom g, const float* __r
         for (int cc = 0; cc < c_in; cc += 64) {
             const int cw = (c_in - cc) < 64 ? (c_in - cc) : 64;
             __syncthreads();
-            for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
+            for (int i = threadIdx.x; i < kTileRows * cw; i += 256) {
                 const int c = i >> 7, r = i & 127;
-                if (c < cw) s_t[r][c] = resp[((size_t)tile * c_in + cc + c) * kTileRows + r];
+                s_t[r][c] = resp[((size_t)tile * c_in + cc + c) * kTileRows + r];
             }
             __syncthreads();
-            for (int i = threadIdx.x; i < kTileRows * 64; i += 256) {
-                const int r = i >> 6, c = i & 63;
-                if (r < nrows && c < cw) {
-                    const size_t at = (size_t)(first + r) * c_in + cc + c;
-                    bp_data[at] = (x[at] != 0.0f) ? s_t[r][c] : 0.0f;
-                }
+            for (int i = threadIdx.x; i < nrows * cw; i += 256) {
+                const int r = i / cw, c = i - r * cw;
+                const size_t at = (size_t)(first + r) * c_in + cc + c;
+                bp_data[at] = (x[at] != 0.0f) ? s_t[r][c] : 0.0f;
             }
         }
     }
@@ -205,11 +203,73 @@ hipError_t launch_bwd_filter_valu(const Geom& g, const unsigned long long* occ, 
 //     D[ic][oc] += sum over pairs  x[q(pair)][ic] * g[p(pair)][oc],
 // i.e. a [C_in x pairs] . [pairs x C_out] product whose long dimension is the pair list: the pairs are the K
 // dimension of v_mfma_f32_16x16x4_f32, four per instruction.  A wave owns one (tap, 16*MT input channels,
-// 16*NT output channels) slab and a share of the tiles; it keeps the slab in registers for its whole life:
-// fp32 matrix-core sums over the (at most 128) pairs of one tile, added to an fp64 copy after each tile.
+// 16*NT output channels) slab and a contiguous share of the tiles; it keeps the slab in registers for its whole
+// life: fp32 matrix-core sums over the (at most 128) pairs of one tile, added to an fp64 copy after each tile.
 // Lane (jj = lane & 15, gq = lane >> 4) feeds pair 4*gq + j of a block in step j (the order of the pairs inside a
 // sum is free), input channels jj*MT + i and output channels jj*NT + i of the slab, so that its operands are one
-// 8- or 16-byte load per pair.
+// 8- or 16-byte load per pair at a 32-bit offset from a wave-uniform base: three vector instructions of address
+// arithmetic per pair.  Only the last block of a tap can hold list padding (local row 128), so only that block
+// pays for masking.
+//
+// All slabs of one share of the tiles run on the same XCD (workgroup i runs on XCD i % 8), so that the share's
+// input rows and gradient rows are fetched into that XCD's L2 once for all taps.
+template <int MT, int NT>
+struct BwdOperands {
+    float av[4][MT], bv[4][NT];
+};
+
+template <int MT, int NT, bool MASKED>
+__device__ __forceinline__ void bwd_filter_load(const uint4 ent, const char* __restrict__ xt,
+                                                const char* __restrict__ gl, unsigned cin4, unsigned cout4,
+                                                unsigned xlane, unsigned glane, BwdOperands<MT, NT>& o) {
+    const unsigned en[4] = {ent.x, ent.y, ent.z, ent.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const unsigned row = en[j] >> kPairRowShift;
+        // the 24-bit multiply reads the low 24 bits of its operands: the gradient row of the pair, as it is
+        const unsigned goff = __umul24(en[j], cout4) + glane;
+        unsigned xoff = __umul24(row, cin4) + xlane;
+        bool live = true;
+        if constexpr (MASKED) {
+            live = row < (unsigned)kTileRows;
+            xoff = live ? xoff : xlane;
+        }
+        if constexpr (MT == 1) {
+            o.av[j][0] = *(const float*)(xt + xoff);
+        } else {
+            const float2 t2 = *(const float2*)(xt + xoff);
+            o.av[j][0] = t2.x;
+            o.av[j][1] = t2.y;
+        }
+        if constexpr (MASKED) {
+#pragma unroll
+            for (int a = 0; a < MT; ++a) o.av[j][a] = live ? o.av[j][a] : 0.0f;
+        }
+        if constexpr (NT == 2) {
+            const float2 t2 = *(const float2*)(gl + goff);
+            o.bv[j][0] = t2.x;
+            o.bv[j][1] = t2.y;
+        } else {
+            const float4 t4 = *(const float4*)(gl + goff);
+            o.bv[j][0] = t4.x;
+            o.bv[j][1] = t4.y;
+            o.bv[j][2] = t4.z;
+            o.bv[j][3] = t4.w;
+        }
+    }
+}
+
+template <int MT, int NT>
+__device__ __forceinline__ void bwd_filter_mma(const BwdOperands<MT, NT>& o, f32x4 (&acc)[MT][NT]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int c = 0; c < NT; ++c)
+                acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(o.av[j][a], o.bv[j][c], acc[a][c], 0, 0, 0);
+}
+
 template <int MT, int NT>
 __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int c_out, const float* __restrict__ x,
                                                          const float* __restrict__ gf,
@@ -219,20 +279,25 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
                                                          const int* __restrict__ cand_start,
                                                          const int* __restrict__ tile_start, int batch,
                                                          const Counters* __restrict__ ctr, int n_chunks,
+                                                         int groups /* workgroups per share */,
                                                          double* __restrict__ fpart) {
     const int lane = threadIdx.x & 63;
     const int jj = lane & 15, gq = lane >> 4;
     const int n_icb = c_in / (16 * MT), n_ocb = c_out / (16 * NT);
     const int slabs = taps * n_icb * n_ocb;
-    const long long item = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int chunk = __builtin_amdgcn_readfirstlane((int)(item / slabs));
-    if (chunk >= n_chunks) return;
-    const int slab = __builtin_amdgcn_readfirstlane((int)(item % slabs));
+    const int xcd = blockIdx.x & 7, j_in_xcd = blockIdx.x >> 3;
+    const int chunk = (j_in_xcd / groups) * 8 + xcd;
+    const int slab = __builtin_amdgcn_readfirstlane((j_in_xcd % groups) * 4 + (int)(threadIdx.x >> 6));
+    if (chunk >= n_chunks || slab >= slabs) return;
     const int ta = slab / (n_icb * n_ocb);  // adjoint tap
     const int icb = (slab / n_ocb) % n_icb, ocb = slab % n_ocb;
     const int n_tiles = (int)ctr->n_tiles;
-    const float* __restrict__ xl = x + icb * 16 * MT + jj * MT;
-    const float* __restrict__ gl = gf + ocb * 16 * NT + jj * NT;
+    // contiguous share of the tiles
+    const int tile_lo = (int)((long long)chunk * n_tiles / n_chunks);
+    const int tile_hi = (int)((long long)(chunk + 1) * n_tiles / n_chunks);
+    const unsigned cin4 = (unsigned)c_in * 4u, cout4 = (unsigned)c_out * 4u;
+    const unsigned xlane = (unsigned)(icb * 16 * MT + jj * MT) * 4u, glane = (unsigned)(ocb * 16 * NT + jj * NT) * 4u;
+    const char* __restrict__ gl = (const char*)gf;
 
     double acc64[MT][NT][4];
 #pragma unroll
@@ -242,55 +307,60 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
 #pragma unroll
             for (int v = 0; v < 4; ++v) acc64[a][c][v] = 0.0;
 
-    for (int tile = chunk; tile < n_tiles; tile += n_chunks) {
-        const uint2 hdr = tile_hdr[tile];
-        const unsigned short* tf = tap_first + (size_t)tile * (taps + 1) + ta;
-        const unsigned b0 = hdr.x + tf[0], b1 = hdr.x + tf[1];
-        if (b0 >= b1 || hdr.y == 0) continue;
-        const int b = sample_of_tile(tile_start, batch, tile);
+    int b = tile_lo < tile_hi ? sample_of_tile(tile_start, batch, tile_lo) : 0;
+    int b_end = tile_start[b + 1];  // first tile of the next sample
+    // block range of this tap in a tile; fetched one tile ahead of its use
+    unsigned nb0 = 0, nb1 = 0;
+    if (tile_lo < tile_hi) {
+        const unsigned short* tf = tap_first + (size_t)tile_lo * (taps + 1) + ta;
+        const unsigned h = tile_hdr[tile_lo].x;
+        nb0 = h + tf[0];
+        nb1 = h + tf[1];
+    }
+    for (int tile = tile_lo; tile < tile_hi; ++tile) {
+        const unsigned b0 = nb0, b1 = nb1;
+        if (tile + 1 < tile_hi) {
+            const unsigned short* tf = tap_first + (size_t)(tile + 1) * (taps + 1) + ta;
+            const unsigned h = tile_hdr[tile + 1].x;
+            nb0 = h + tf[0];
+            nb1 = h + tf[1];
+        }
+        while (tile >= b_end) {  // next sample (samples without rows have no tiles)
+            ++b;
+            b_end = tile_start[b + 1];
+        }
+        if (b0 >= b1) continue;
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        const char* __restrict__ xt = (const char*)(x + (size_t)first * c_in);
         f32x4 acc[MT][NT];
 #pragma unroll
         for (int a = 0; a < MT; ++a)
 #pragma unroll
             for (int c = 0; c < NT; ++c) acc[a][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-        uint4 ent = *(const uint4*)(pairs + (size_t)b0 * 16 + gq * 4);
-        for (unsigned blk = b0; blk < b1; ++blk) {
-            const unsigned en[4] = {ent.x, ent.y, ent.z, ent.w};
-            if (blk + 1 < b1) ent = *(const uint4*)(pairs + (size_t)(blk + 1) * 16 + gq * 4);
-            float av[4][MT], bv[4][NT];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const unsigned row = en[j] >> kPairRowShift, in = en[j] & kPairInMask;
-                const bool live = row < (unsigned)kTileRows;  // list padding points at row 128
-                const float* xp = xl + (size_t)(first + (live ? row : 0u)) * c_in;
-                const float* gp = gl + (size_t)in * c_out;
-                if constexpr (MT == 1) {
-                    av[j][0] = live ? xp[0] : 0.0f;
-                } else {
-                    const float2 t2 = *(const float2*)xp;
-                    av[j][0] = live ? t2.x : 0.0f;
-                    av[j][1] = live ? t2.y : 0.0f;
-                }
-                if constexpr (NT == 2) {
-                    const float2 t2 = *(const float2*)gp;
-                    bv[j][0] = t2.x;
-                    bv[j][1] = t2.y;
-                } else {
-                    const float4 t4 = *(const float4*)gp;
-                    bv[j][0] = t4.x;
-                    bv[j][1] = t4.y;
-                    bv[j][2] = t4.z;
-                    bv[j][3] = t4.w;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-#pragma unroll
-                for (int a = 0; a < MT; ++a)
-#pragma unroll
-                    for (int c = 0; c < NT; ++c)
-                        acc[a][c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[j][a], bv[j][c], acc[a][c], 0, 0, 0);
+        // operands one block ahead of their use (two register sets that swap roles, so that nothing is copied),
+        // pair entries two blocks ahead
+        const unsigned* pl = pairs + (size_t)b0 * 16 + gq * 4;
+        const unsigned nblk = b1 - b0;
+        BwdOperands<MT, NT> opa, opb;
+        uint4 ent_next = *(const uint4*)pl;
+        unsigned issued = 0, done = 0;
+        auto issue = [&](BwdOperands<MT, NT>& dst) {
+            const uint4 e = ent_next;
+            if (issued + 1 < nblk) ent_next = *(const uint4*)(pl + (size_t)(issued + 1) * 16);
+            if (issued + 1 < nblk)
+                bwd_filter_load<MT, NT, false>(e, xt, gl, cin4, cout4, xlane, glane, dst);
+            else
+                bwd_filter_load<MT, NT, true>(e, xt, gl, cin4, cout4, xlane, glane, dst);
+            ++issued;
+        };
+        issue(opa);
+        for (;;) {
+            if (issued < nblk) issue(opb);
+            bwd_filter_mma<MT, NT>(opa, acc);
+            if (++done == nblk) break;
+            if (issued < nblk) issue(opa);
+            bwd_filter_mma<MT, NT>(opb, acc);
+            if (++done == nblk) break;
         }
 #pragma unroll
         for (int a = 0; a < MT; ++a)
@@ -312,7 +382,10 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
         }
 }
 
-bool bwd_filter_mfma_supported(int c_in, int c_out) { return c_in % 16 == 0 && c_out % 32 == 0; }
+// The gradient values are addressed with 32-bit byte offsets.
+bool bwd_filter_mfma_supported(int c_in, int c_out, long long g_rows) {
+    return c_in % 16 == 0 && c_out % 32 == 0 && g_rows * c_out * 4 < (1ll << 32);
+}
 
 // waves per share of the tiles
 static int bwd_filter_slabs(const Geom& g, int c_in, int c_out) {
@@ -324,7 +397,9 @@ int bwd_filter_chunks(const Geom& g, int c_in, int c_out, long long tiles_cap, b
     long long chunks;
     if (mfma) {
         const int slabs = bwd_filter_slabs(g, c_in, c_out);
-        chunks = (256 * 12 + slabs - 1) / slabs;  // about twelve waves per compute unit
+        // all waves resident at once (two per SIMD), the same number of shares on every XCD
+        chunks = (256 * 8) / ((slabs + 3) / 4 * 4) / 8 * 8;
+        if (chunks < 8) chunks = 8;
         if (chunks > 256) chunks = 256;
     } else {
         const long long n_eb = ((long long)g.T * c_in * c_out + 255) / 256;
@@ -340,11 +415,11 @@ hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const
                                   const unsigned* pairs, const unsigned short* tap_first, const uint2* tile_hdr,
                                   const int* cand_start, const int* tile_start, const Counters* ctr, int n_chunks,
                                   double* fpart, hipStream_t s) {
-    const long long waves = (long long)bwd_filter_slabs(g, c_in, c_out) * n_chunks;
-    const unsigned blocks = (unsigned)((waves + 3) / 4);
+    const int groups = (bwd_filter_slabs(g, c_in, c_out) + 3) / 4;
+    const unsigned blocks = (unsigned)(8 * groups * ((n_chunks + 7) / 8));
 #define SCNN_BWD_CASE(MT_, NT_)                                                                                   \
     hipLaunchKernelGGL((k_bwd_filter_mfma<MT_, NT_>), dim3(blocks), dim3(256), 0, s, g.T, c_in, c_out, x, gf, pairs, \
-                       tap_first, tile_hdr, cand_start, tile_start, g.batch, ctr, n_chunks, fpart)
+                       tap_first, tile_hdr, cand_start, tile_start, g.batch, ctr, n_chunks, groups, fpart)
     if (c_in % 32 == 0) {
         if (c_out % 64 == 0) SCNN_BWD_CASE(2, 4); else SCNN_BWD_CASE(2, 2);
     } else {
@@ -359,12 +434,20 @@ hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const
 __global__ __launch_bounds__(256) void k_bwd_filter_finish(const double* __restrict__ fpart, int n_chunks,
                                                            long long n_elem, const float* __restrict__ w,
                                                            float* __restrict__ bp_filter) {
-    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (e >= n_elem) return;
+    // 64 elements per workgroup; four threads per element each add a quarter of the partials (ascending), then
+    // the quarters are added in ascending order: the order of the additions never depends on timing
+    __shared__ double s_q[4][64];
+    const int el = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const long long e = (long long)blockIdx.x * 64 + el;
     double sum = 0.0;
-    if (w[e] != 0.0f)
-        for (int c = 0; c < n_chunks; ++c) sum += fpart[(size_t)c * n_elem + e];
-    bp_filter[e] = (float)sum;
+    const bool live = e < n_elem && w[e] != 0.0f;
+    if (live) {
+        const int c0 = (int)((long long)q * n_chunks / 4), c1 = (int)((long long)(q + 1) * n_chunks / 4);
+        for (int c = c0; c < c1; ++c) sum += fpart[(size_t)c * n_elem + e];
+    }
+    s_q[q][el] = sum;
+    __syncthreads();
+    if (q == 0 && e < n_elem) bp_filter[e] = (float)(((s_q[0][el] + s_q[1][el]) + s_q[2][el]) + s_q[3][el]);
 }
 
 // also the place where the call's status words are written: {input rows, gradient rows, flags, 0}
@@ -381,7 +464,7 @@ __global__ void k_bwd_status(const Counters* __restrict__ ctr, long long nnz_in,
 hipError_t launch_bwd_filter_finish(const double* fpart, int n_chunks, long long n_elem, const float* w,
                                     float* bp_filter, const Counters* ctr, long long nnz_in, long long g_rows,
                                     long long* info, hipStream_t s) {
-    hipLaunchKernelGGL(k_bwd_filter_finish, dim3((unsigned)((n_elem + 255) / 256)), dim3(256), 0, s, fpart, n_chunks,
+    hipLaunchKernelGGL(k_bwd_filter_finish, dim3((unsigned)((n_elem + 63) / 64)), dim3(256), 0, s, fpart, n_chunks,
                        n_elem, w, bp_filter);
     hipLaunchKernelGGL(k_bwd_status, dim3(1), dim3(64), 0, s, ctr, nnz_in, g_rows, info);
     return hipGetLastError();

@@ -214,7 +214,7 @@ hipError_t launch_bwd_sites(const Geom& g, const int32_t* coords, long long rows
 hipError_t launch_bwd_data_write(const Geom& g, const float* resp, const float* x, int c_in, const int* cand_start,
                                  const int* tile_start, const Counters* ctr, long long tiles_cap, float* bp_data,
                                  hipStream_t s);
-bool bwd_filter_mfma_supported(int c_in, int c_out);
+bool bwd_filter_mfma_supported(int c_in, int c_out, long long g_rows);
 int bwd_filter_chunks(const Geom& g, int c_in, int c_out, long long tiles_cap, bool mfma);
 hipError_t launch_bwd_filter_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                                   long long g_rows, const float* gf, int c_out, const float* x, int c_in,
