@@ -229,7 +229,7 @@ def main():
                 "frac_of_8TBs": bytes_alg["alg"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
                 "whole_layer_roofline_frac": max(bytes_alg["alg"] / (PEAK_HBM_GBS * 1e9),
                                                  2.0 * mac_nz / (PEAK_MFMA_FP32_TFLOPS * 1e12)) / (ms_per_step * 1e-3)},
-        "stage_ms": {k: v / max(calls, 1) for k, v in stage_ms.items()},
+        "stage_ms": {k: v / max(calls, 1) for k, v in stage_ms.items() if not k.startswith("bwd_")},
         "ms_per_step_without_events": dt_plain / args.steps * 1e3,
     }
     if not args.no_cpu_baseline:

@@ -118,24 +118,39 @@ __global__ __launch_bounds__(256) void k_index_build(Geom g, const int32_t* __re
                                                      unsigned* __restrict__ occ_prefix, Counters* ctr) {
     const long long n = n_dev ? *n_dev : n_imm;
     const int stride = 1 + g.ndim;
-    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < n;
-         r += (long long)gridDim.x * blockDim.x) {
-        int b, c0, c1, c2;
-        load_site(g, coords + r * stride, b, c0, c1, c2);
-        if (!site_in_grid(g, b, c0, c1, c2)) {
-            atomicOr(&ctr->flags, SCNN_FLAG_BAD_COORD);
-            continue;
+    const int lane = threadIdx.x & 63;
+    for (long long base = (long long)blockIdx.x * blockDim.x; base < n; base += (long long)gridDim.x * blockDim.x) {
+        const long long r = base + threadIdx.x;
+        long long key = -1;
+        if (r < n) {
+            int b, c0, c1, c2;
+            load_site(g, coords + r * stride, b, c0, c1, c2);
+            if (site_in_grid(g, b, c0, c1, c2)) {
+                key = (long long)b * g.Npad + lin_of(g, c0, c1, c2);
+                long long prev_key = -1;
+                if (r > 0) {
+                    int pb, p0, p1, p2;
+                    load_site(g, coords + (r - 1) * stride, pb, p0, p1, p2);
+                    if (site_in_grid(g, pb, p0, p1, p2)) prev_key = (long long)pb * g.Npad + lin_of(g, p0, p1, p2);
+                }
+                if (prev_key >= key) atomicOr(&ctr->flags, SCNN_FLAG_UNSORTED);
+                if ((prev_key >> 6) != (key >> 6)) occ_prefix[key >> 6] = (unsigned)r;
+            } else {
+                atomicOr(&ctr->flags, SCNN_FLAG_BAD_COORD);
+            }
         }
-        const long long key = (long long)b * g.Npad + lin_of(g, c0, c1, c2);
-        long long prev_key = -1;
-        if (r > 0) {
-            int pb, p0, p1, p2;
-            load_site(g, coords + (r - 1) * stride, pb, p0, p1, p2);
-            if (site_in_grid(g, pb, p0, p1, p2)) prev_key = (long long)pb * g.Npad + lin_of(g, p0, p1, p2);
+        // Sorted rows of one bitmap word sit in adjacent lanes: OR their bits together inside the wave and let the
+        // first lane of each run issue the one atomic (a run may continue in the next wave, hence still atomic).
+        const long long word = key >= 0 ? (key >> 6) : (long long)(-1 - lane);
+        unsigned long long bits = key >= 0 ? (1ull << (key & 63)) : 0ull;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const long long ow = __shfl_down(word, d, 64);
+            const unsigned long long ob = __shfl_down(bits, d, 64);
+            if (lane + d < 64 && ow == word) bits |= ob;
         }
-        if (prev_key >= key) atomicOr(&ctr->flags, SCNN_FLAG_UNSORTED);
-        atomicOr(&occ[key >> 6], 1ull << (key & 63));
-        if ((prev_key >> 6) != (key >> 6)) occ_prefix[key >> 6] = (unsigned)r;
+        const long long pw = __shfl_up(word, 1, 64);
+        if (key >= 0 && (lane == 0 || pw != word)) atomicOr(&occ[word], bits);
     }
 }
 
