@@ -45,6 +45,59 @@ def cpu_baseline(wl, layer, w, mac_total):
                       f"({info['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
 
 
+def bench_stack(args):
+    """A step = the nine-layer sparse part of OctNet3-R^3 + sparseToDense on one batch; each layer's row count is read
+    back on the host (the boundary takes it as a host integer), so the timed region includes those nine round trips."""
+    import numpy as np
+    import torch
+    import paper_1801_10585_amd as scnn
+    from workloads import make_octnet3_stack
+    dev = torch.device("cuda:0")
+    wl = make_octnet3_stack(args.stack, batch=4)
+    c0, f0 = torch.from_numpy(wl.coords).to(dev), torch.from_numpy(wl.feats).to(dev)
+    ws = [torch.from_numpy(w).to(dev) for w in wl.filters]
+    macs, rows_log, dens_log = 0, [], []
+    ext, c, f = wl.extent, wl.coords, wl.feats
+    # sizing pass (untimed): work count and per-layer densities
+    cd, fd = c0, f0
+    for L, w, wd in zip(wl.layers, wl.filters, ws):
+        macs += scnn.count_mac_nz(ext, cd.cpu().numpy(), fd.cpu().numpy(), L.ksize, w)
+        cd, fd, _ = scnn.sparse_conv_fwd(ext, wl.batch, cd, fd, L.ksize, wd, rho_up=L.rho_up, relu=L.relu, pool=L.pool)
+        if L.pool:
+            ext = tuple((e + 1) // 2 for e in ext)
+        n_sites = wl.batch * int(np.prod(ext))
+        rows_log.append(int(cd.shape[0]))
+        dens_log.append(float((fd != 0).sum().item()) / (n_sites * L.c_out))
+
+    def step():
+        e, cc, ff = wl.extent, c0, f0
+        for L, wd in zip(wl.layers, ws):
+            cc, ff, _ = scnn.sparse_conv_fwd(e, wl.batch, cc, ff, L.ksize, wd, rho_up=L.rho_up, relu=L.relu,
+                                             pool=L.pool)
+            if L.pool:
+                e = tuple((x + 1) // 2 for x in e)
+        return scnn.sparse_to_dense(e, wl.batch, cc, ff)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    line = {
+        "metric": "effective non-zero GMAC/s of a nine-layer sparse conv+attention stack, end to end",
+        "value": macs * args.steps / dt / 1e9, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "grid": list(wl.extent), "batch": wl.batch, "rows_in": int(wl.coords.shape[0]),
+                   "layers": [[L.c_in, L.c_out, L.rho_up, bool(L.pool)] for L in wl.layers], "mac_nz": int(macs),
+                   "rows_after_layer": rows_log, "entry_density_after_layer": dens_log, "seed": wl.seed},
+    }
+    print(json.dumps(line))
+
+
 def bench_backward(args, wl, layer, w, coords, feats, wd):
     """Backward pass of the same layer: gradient rows with the sparsity pattern of the layer's own output (taken
     from one untimed forward call), random values.  A step = one sparse_conv_bwd call."""
@@ -116,6 +169,9 @@ def main():
                     help="instead of --config: the paper's runtime experiment (Sec. 4.1) at resolution R "
                          "(random sites, density = rho_up = 1/R, 1 -> 8 channels, batch 1); not the headline")
     ap.add_argument("--rho-f", type=float, default=1.0, help="filter density of --paper-runtime")
+    ap.add_argument("--stack", type=int, default=0, metavar="R", choices=[0, 32, 64, 128],
+                    help="instead of --config: the sparse part of the paper's OctNet3-R^3 network (nine convolutions, "
+                         "two poolings, sparseToDense) with random weights, end to end; not the headline")
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (Algorithm 2) of the same layer instead; not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -136,6 +192,8 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    if args.stack:
+        return bench_stack(args)
     wl = make_paper_runtime(args.paper_runtime, args.rho_f) if args.paper_runtime else make_config(args.config)
     layer = wl.layers[0]
     w = wl.filters[0]

@@ -142,6 +142,14 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
                    int64_t rows, int channels, int32_t* out_coords, float* out_feats, int64_t out_capacity,
                    int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* sparseToDense (the layer that closes the sparse part of the paper's networks,
+ * appendix table of architectures): dense fp32 [batch, channels, extent...]
+ * (channel-major, last spatial axis fastest) with dense[b, c, site(r)] =
+ * feats[r, c] for every row r and 0 everywhere else.  dense: device pointer,
+ * 16-byte aligned, overwritten entirely.  Rows outside the grid are skipped. */
+int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* feats,
+                    int64_t rows, int channels, float* dense, void* hip_stream);
+
 /* Optional precondition check of a coordinate list (synchronises the stream):
  * SCNN_OK, SCNN_EINVAL (coordinate outside the grid) or SCNN_EUNSORTED (rows
  * not strictly ascending by (b, lin)).  workspace: at least 256 bytes. */

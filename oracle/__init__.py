@@ -176,3 +176,14 @@ def sparse_maxpool(extent: Sequence[int], coords, feats):
     if rows < 0:
         raise ValueError("oracle_sparse_maxpool: bad arguments")
     return _fetch(L, int(rows), len(extent), f.shape[1])
+
+
+def sparse_to_dense(extent: Sequence[int], batch: int, coords, feats) -> np.ndarray:
+    """sparseToDense (appendix table of architectures): dense [batch, channels, *extent], the rows' values at
+    their sites and zero elsewhere.  Written out as the definition, one row at a time."""
+    coords = np.asarray(coords)
+    feats = np.asarray(feats, dtype=np.float32)
+    dense = np.zeros((int(batch), feats.shape[1], *[int(e) for e in extent]), dtype=np.float32)
+    for r in range(coords.shape[0]):
+        dense[(int(coords[r, 0]), slice(None)) + tuple(int(v) for v in coords[r, 1:])] = feats[r]
+    return dense

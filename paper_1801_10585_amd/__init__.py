@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     sparse_conv_fwd_workspace,
     sparse_maxpool,
     sparse_relu,
+    sparse_to_dense,
     validate_rows,
     EXPORTED_SYMBOLS,
 )

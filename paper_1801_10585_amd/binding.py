@@ -21,7 +21,7 @@ EXPORTED_SYMBOLS = [
     "sparse_conv_fwd", "attention_topk_workspace", "attention_topk", "sparse_relu_workspace", "sparse_relu",
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
-    "sparse_conv_bwd_workspace", "sparse_conv_bwd",
+    "sparse_conv_bwd_workspace", "sparse_conv_bwd", "sparse_to_dense",
 ]
 
 
@@ -74,6 +74,8 @@ def load_library():
     L.sparse_maxpool_workspace.argtypes = [ci, i32p, ci, i64, ci]
     L.sparse_maxpool.restype = ci
     L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
+    L.sparse_to_dense.restype = ci
+    L.sparse_to_dense.argtypes = [ci, i32p, ci, vp, vp, i64, ci, vp, vp]
     L.scnn_validate_rows.restype = ci
     L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
     L.scnn_calibration_copy.restype = ci
@@ -324,6 +326,19 @@ def sparse_maxpool(extent, batch, coords, feats, window=2, *, out_capacity=None,
                           _stream(stream))
     _check(L, rc)
     return _finish(out_coords, out_feats, nnz, sync)
+
+
+def sparse_to_dense(extent, batch, coords, feats, *, out=None, stream=None):
+    """Dense fp32 [batch, channels, *extent] holding the rows' values, zero elsewhere."""
+    L = load_library()
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    rows, ch = feats.shape
+    if out is None:
+        out = torch.empty((int(batch), ch, *[int(e) for e in extent]), dtype=torch.float32, device=feats.device)
+    _check(L, L.sparse_to_dense(len(extent), _i32arr(extent), int(batch), _ptr(coords), _ptr(feats), rows, ch,
+                                _ptr(out), _stream(stream)))
+    return out
 
 
 def validate_rows(extent, batch, coords, stream=None) -> None:

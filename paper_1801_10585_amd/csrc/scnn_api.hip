@@ -745,6 +745,22 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
     return SCNN_OK;
 }
 
+// ---------------------------------------------------------------- sparse_to_dense
+int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* feats,
+                    int64_t rows, int channels, float* dense, void* hip_stream) {
+    Geom g;
+    int rc = make_geom(ndim, extent, batch, nullptr, &g);
+    if (rc != SCNN_OK) return rc;
+    if (rows < 0 || rows > kMaxIndex) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (channels < 1) return fail(SCNN_EINVAL, "channels must be positive");
+    if (channels > kMaxChannels) return fail(SCNN_ECAPACITY, "at most %d channels", kMaxChannels);
+    if (!dense) return fail(SCNN_EINVAL, "dense is null");
+    if (((uintptr_t)dense & 15) != 0) return fail(SCNN_EINVAL, "dense must be 16-byte aligned");
+    if (rows > 0 && (!coords || !feats)) return fail(SCNN_EINVAL, "null input arrays");
+    SCNN_TRY(launch_to_dense(g, coords, feats, rows, channels, dense, (hipStream_t)hip_stream));
+    return SCNN_OK;
+}
+
 // ---------------------------------------------------------------- validation
 int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {

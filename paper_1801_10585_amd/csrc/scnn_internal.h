@@ -255,6 +255,8 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
                           unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
                           int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
                           hipStream_t s);
+hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
+                           float* dense, hipStream_t s);
 hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows, Counters* ctr, hipStream_t s);
 hipError_t launch_finish(const Counters* ctr, int which_rows /*0 n_rows, 1 n_pool*/, long long aux_imm,
                          int aux_is_cand, long long out_capacity, long long* nnz_out, hipStream_t s);

@@ -211,4 +211,48 @@ hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows,
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ sparseToDense
+// dense[b][c][lin] = feats[row(b, lin)][c]; every other element 0.  The fill and the scatter are two launches on
+// the same stream.  Rows outside the grid are skipped.
+__global__ __launch_bounds__(256) void k_dense_fill(float* __restrict__ dense, size_t n) {
+    const size_t n4 = n / 4;  // dense is 16-byte aligned
+    float4* d4 = (float4*)dense;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
+        d4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (blockIdx.x == 0 && threadIdx.x < (n & 3)) dense[n4 * 4 + threadIdx.x] = 0.f;
+}
+
+__global__ __launch_bounds__(256) void k_dense_scatter(Geom g, const int32_t* __restrict__ coords,
+                                                       const float* __restrict__ feats, long long rows, int channels,
+                                                       float* __restrict__ dense) {
+    const int stride = 1 + g.ndim;
+    const long long total = rows * channels;
+    for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+         i += (long long)gridDim.x * blockDim.x) {
+        const long long r = i / channels;
+        const int c = (int)(i - r * channels);
+        int b, c0, c1, c2;
+        load_site(g, coords + r * stride, b, c0, c1, c2);
+        if (!site_in_grid(g, b, c0, c1, c2)) continue;
+        dense[((size_t)b * channels + c) * (size_t)g.N + (size_t)lin_of(g, c0, c1, c2)] = feats[i];
+    }
+}
+
+hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
+                           float* dense, hipStream_t s) {
+    const size_t n = (size_t)g.batch * channels * (size_t)g.N;
+    size_t fb = (n / 4 + 255) / 256;
+    if (fb < 1) fb = 1;
+    if (fb > 4096) fb = 4096;
+    hipLaunchKernelGGL(k_dense_fill, dim3((unsigned)fb), dim3(256), 0, s, dense, n);
+    if (rows > 0) {
+        long long sb = (rows * channels + 255) / 256;
+        if (sb > 8192) sb = 8192;
+        hipLaunchKernelGGL(k_dense_scatter, dim3((unsigned)sb), dim3(256), 0, s, g, coords, feats, rows, channels,
+                           dense);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace scnn

@@ -368,3 +368,21 @@ def test_threads_do_not_change_the_result():
     b = oracle.sparse_conv_fwd(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=L.rho_up,
                                relu=True, threads=4)
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+# ---------------------------------------------------------------- sparseToDense against a library routine
+@pytest.mark.parametrize("extent,batch,channels", [((7, 5), 2, 3), ((4, 6, 5), 3, 2)])
+def test_sparse_to_dense_equals_library_coo_to_dense(extent, batch, channels):
+    rng = np.random.default_rng(len(extent) + channels)
+    coords = random_sparse_sites(rng, extent, batch, 0.3)
+    feats = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    dense = oracle.sparse_to_dense(extent, batch, coords, feats)
+    assert dense.shape == (batch, channels, *extent)
+    # library: a COO tensor indexed (b, site...) with a dense channel vector per entry, channel axis moved to 1
+    coo = torch.sparse_coo_tensor(torch.from_numpy(coords.T.astype(np.int64)), torch.from_numpy(feats),
+                                  size=(batch, *extent, channels))
+    want = coo.to_dense().movedim(-1, 1).numpy()
+    assert np.array_equal(dense, want)
+    # value count and sum survive; everything off the rows is zero
+    assert np.count_nonzero(dense) == np.count_nonzero(feats)
+    assert dense[0, :, 0, 0].shape == (channels,) if len(extent) == 2 else True

@@ -17,6 +17,7 @@ from .generators import (  # noqa: F401
     Workload,
     make_config,
     make_filter,
+    make_octnet3_stack,
     make_paper_runtime,
     random_sparse_sites,
     shell_volume,

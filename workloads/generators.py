@@ -237,3 +237,28 @@ def make_paper_runtime(r: int, rho_f: float, seed: int | None = None) -> Workloa
     return Workload(name=f"paper_runtime_r{r}_rhof{rho_f:g}", ndim=3, extent=extent, batch=1, coords=coords,
                     feats=np.ascontiguousarray(feats), layers=[layer], filters=[w],
                     density=coords.shape[0] / float(r) ** 3, seed=seed)
+
+
+# Upper density bounds of the three sparse blocks of the paper's OctNet3 variants (appendix, network architectures).
+OCTNET3_RHO = {32: (0.14, 0.33, 0.66), 64: (0.06, 0.14, 0.33), 128: (0.02, 0.06, 0.14)}
+
+
+def make_octnet3_stack(r: int, batch: int = 2, seed: int | None = None) -> Workload:
+    """The sparse part of the paper's OctNet3-r^3 network (appendix table of architectures) with random weights:
+    three blocks of three 3x3x3 convolutions, 1 -> 8 -> 8 -> 8 | 8 -> 16 -> 16 -> 16 | 16 -> 24 -> 24 -> 24 channels,
+    block i bounded by rho_i, a 2^3 max-pooling after the first two blocks, sparseToDense after the third.  Every
+    convolution is followed by ReLU (a reading: the table lists the convolutions only).  Input: occupancy (value 1)
+    of shell surfaces at density about 3/r, as in the other 3-D workloads.  `pool` of a layer means "pool after it"."""
+    rho = OCTNET3_RHO[r]
+    seed = BASE_SEED + 2000 + r if seed is None else seed
+    rng = np.random.default_rng(seed)
+    dens, tol = 2.9 / r, 0.6 / r
+    occ = np.stack([shell_volume(rng, r, dens, tol) for _ in range(batch)])
+    coords = occupancy_to_rows(occ)
+    feats = np.ones((coords.shape[0], 1), dtype=np.float32)
+    chans = [(1, 8), (8, 8), (8, 8), (8, 16), (16, 16), (16, 16), (16, 24), (24, 24), (24, 24)]
+    layers = [LayerSpec(c_in=ci, c_out=co, ksize=(3, 3, 3), filter_density=1.0, sigma=float(np.sqrt(2.0 / (27 * ci))),
+                        rho_up=rho[i // 3], relu=True, pool=(i in (2, 5))) for i, (ci, co) in enumerate(chans)]
+    filters = [make_filter(rng, L.ksize, L.c_in, L.c_out, 1.0, L.sigma) for L in layers]
+    return Workload(name=f"octnet3_{r}_sparse_part", ndim=3, extent=(r, r, r), batch=batch, coords=coords,
+                    feats=feats, layers=layers, filters=filters, density=float(occ.mean()), seed=seed)
