@@ -150,6 +150,32 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
 int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* feats,
                     int64_t rows, int channels, float* dense, void* hip_stream);
 
+/* Adaptive density regularisation (Sec. 3.5, Eq. 4).  The density of a layer's
+ * output, rho = (non-zero entries of out_feats[0 .. rows)) / (n_sites_total *
+ * channels) with n_sites_total = batch * prod(extent), sets the bias of the L2
+ * regulariser sum (w + b)^2:
+ *     b = o + b1 * (rho - rho_up)   if rho > rho_up,    b = -b2 * (rho_up - rho)   otherwise.
+ * result (device, double[4]) = {rho, b, lambda * sum over un-pruned weights of
+ * (w + b)^2, non-zero entries}; grad_w (device, fp32 [n_w], nullable) =
+ * 2 * lambda * (w + b) on un-pruned weights and 0 on pruned ones (exact 0.0f:
+ * Eq. 3 gives a removed weight no gradient).  rows_dev (nullable, device): the
+ * row count is read from there (capped by rows) so that the call can follow
+ * sparse_conv_fwd without a host read.  Sums in fp64 in a fixed order.
+ * workspace: density_regulariser_workspace() bytes, 256-byte aligned. */
+size_t density_regulariser_workspace(void);
+int density_regulariser(const float* out_feats, int64_t rows, const int64_t* rows_dev, int channels, int64_t n_sites_total,
+                        double rho_up, double o, double b1, double b2, double lambda, const float* w, int64_t n_w,
+                        float* grad_w, double* result, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* One-warning-shot pruning (Sec. 3.6), called once per epoch: a non-zero weight
+ * with |w| < eps that already carried a warning from the previous call is set
+ * to exactly 0 (and stays 0 under sparse_conv_bwd); one that is small for the
+ * first time only receives the warning; any other weight loses its warning.
+ * w (device, fp32 [n_w]) and warned (device, one byte per weight, 0/1; all 0
+ * before the first epoch) are updated in place.  counts (device, int64[2]) =
+ * {weights removed by this call, non-zero weights left}. */
+int prune_weights(float* w, unsigned char* warned, int64_t n_w, float eps, int64_t* counts, void* hip_stream);
+
 /* Optional precondition check of a coordinate list (synchronises the stream):
  * SCNN_OK, SCNN_EINVAL (coordinate outside the grid) or SCNN_EUNSORTED (rows
  * not strictly ascending by (b, lin)).  workspace: at least 256 bytes. */

@@ -187,3 +187,41 @@ def sparse_to_dense(extent: Sequence[int], batch: int, coords, feats) -> np.ndar
     for r in range(coords.shape[0]):
         dense[(int(coords[r, 0]), slice(None)) + tuple(int(v) for v in coords[r, 1:])] = feats[r]
     return dense
+
+
+def density_regulariser(out_feats, n_sites_total: int, rho_up: float, o: float, b1: float, b2: float, lam: float, w):
+    """Adaptive density regularisation (Sec. 3.5, Eq. 4), in double.  Returns (rho, b, R, grad) with
+    R = lam * sum over un-pruned weights of (w + b)^2 and grad = dR/dw on those weights, 0 on pruned ones."""
+    out_feats = np.asarray(out_feats)
+    w64 = np.asarray(w, dtype=np.float64)
+    entries = int(np.count_nonzero(out_feats))
+    rho = entries / (float(n_sites_total) * out_feats.shape[1])
+    if rho > rho_up:
+        b = o + b1 * (rho - rho_up)      # exceeds the available resources
+    else:
+        b = -b2 * (rho_up - rho)         # not using all resources
+    alive = w64 != 0.0
+    reg = 0.0
+    grad = np.zeros_like(w64)
+    for i in np.flatnonzero(alive.ravel()):
+        t = w64.ravel()[i] + b
+        reg += t * t
+        grad.ravel()[i] = 2.0 * lam * t
+    return rho, b, lam * reg, grad
+
+
+def prune_weights(w, warned, eps: float):
+    """One-warning-shot pruning (Sec. 3.6) of one epoch's end.  Returns (new w, new warned, removed, left)."""
+    w = np.array(w, dtype=np.float32, copy=True)
+    warned = np.array(warned, dtype=np.uint8, copy=True)
+    removed = 0
+    for i in range(w.size):
+        wi = w.flat[i]
+        small = wi != 0.0 and abs(wi) < np.float32(eps)
+        if small and warned.flat[i]:
+            w.flat[i] = 0.0        # second time in a row: remove
+            warned.flat[i] = 0
+            removed += 1
+        else:
+            warned.flat[i] = 1 if small else 0
+    return w, warned, removed, int(np.count_nonzero(w))

@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     ScnnError,
     attention_topk,
     calibration_copy,
+    density_regulariser,
+    prune_weights,
     k_from_rho,
     library_path,
     profile_collect,

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
     "sparse_conv_bwd_workspace", "sparse_conv_bwd", "sparse_to_dense",
+    "density_regulariser_workspace", "density_regulariser", "prune_weights",
 ]
 
 
@@ -76,6 +77,12 @@ def load_library():
     L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
     L.sparse_to_dense.restype = ci
     L.sparse_to_dense.argtypes = [ci, i32p, ci, vp, vp, i64, ci, vp, vp]
+    L.density_regulariser_workspace.restype = sz
+    L.density_regulariser_workspace.argtypes = []
+    L.density_regulariser.restype = ci
+    L.density_regulariser.argtypes = [vp, i64, vp, ci, i64, dbl, dbl, dbl, dbl, dbl, vp, i64, vp, vp, vp, sz, vp]
+    L.prune_weights.restype = ci
+    L.prune_weights.argtypes = [vp, vp, i64, ctypes.c_float, vp, vp]
     L.scnn_validate_rows.restype = ci
     L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
     L.scnn_calibration_copy.restype = ci
@@ -339,6 +346,36 @@ def sparse_to_dense(extent, batch, coords, feats, *, out=None, stream=None):
     _check(L, L.sparse_to_dense(len(extent), _i32arr(extent), int(batch), _ptr(coords), _ptr(feats), rows, ch,
                                 _ptr(out), _stream(stream)))
     return out
+
+
+def density_regulariser(out_feats, n_sites_total, rho_up, o, b1, b2, lam, w, *, rows_dev=None, want_grad=True,
+                        stream=None):
+    """Eq. 4.  Returns (result double[4] = {rho, b, lambda * sum (w + b)^2, entries} on the device, grad_w or None)."""
+    L = load_library()
+    out_feats = _dev(out_feats, torch.float32, "out_feats")
+    w = _dev(w, torch.float32, "w")
+    rows, ch = out_feats.shape
+    dev = w.device
+    grad = torch.empty_like(w) if want_grad else None
+    result = torch.zeros(4, dtype=torch.float64, device=dev)
+    need = int(L.density_regulariser_workspace())
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    _check(L, L.density_regulariser(_ptr(out_feats), rows, _ptr(rows_dev), ch, int(n_sites_total), float(rho_up),
+                                    float(o), float(b1), float(b2), float(lam), _ptr(w), w.numel(), _ptr(grad),
+                                    _ptr(result), _ptr(ws), need, _stream(stream)))
+    return result, grad
+
+
+def prune_weights(w, warned, eps, *, stream=None):
+    """One-warning-shot pruning, in place on w (fp32) and warned (uint8).  Returns counts int64[2] on the device."""
+    L = load_library()
+    if not (w.is_cuda and warned.is_cuda and w.dtype == torch.float32 and warned.dtype == torch.uint8):
+        raise ValueError("w must be a float32 and warned a uint8 GPU tensor")
+    if not (w.is_contiguous() and warned.is_contiguous()) or w.numel() != warned.numel():
+        raise ValueError("w and warned must be contiguous and of equal size")
+    counts = torch.zeros(2, dtype=torch.int64, device=w.device)
+    _check(L, L.prune_weights(_ptr(w), _ptr(warned), w.numel(), float(eps), _ptr(counts), _stream(stream)))
+    return counts
 
 
 def validate_rows(extent, batch, coords, stream=None) -> None:

@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscnn.so")
-SOURCES = ["scnn_index.hip", "scnn_conv.hip", "scnn_topk.hip", "scnn_rows.hip", "scnn_bwd.hip", "scnn_api.hip"]
+SOURCES = ["scnn_index.hip", "scnn_conv.hip", "scnn_topk.hip", "scnn_rows.hip", "scnn_bwd.hip", "scnn_train.hip", "scnn_api.hip"]
 # packed fp32 VALU ops are switched off on purpose (they have misbehaved on the target machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",
@@ -47,7 +47,7 @@ def _compile(src: str, force: bool) -> str:
     return obj
 
 
-def build(force: bool = True, jobs: int = 6) -> str:
+def build(force: bool = True, jobs: int = 7) -> str:
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))

@@ -761,6 +761,38 @@ int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* c
     return SCNN_OK;
 }
 
+// ---------------------------------------------------------------- regulariser and pruning
+size_t density_regulariser_workspace(void) { return 256 + 256 * sizeof(double); }
+
+int density_regulariser(const float* out_feats, int64_t rows, const int64_t* rows_dev, int channels, int64_t n_sites_total,
+                        double rho_up, double o, double b1, double b2, double lambda, const float* w, int64_t n_w,
+                        float* grad_w, double* result, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (rows < 0 || rows > kMaxIndex) return fail(SCNN_ECAPACITY, "rows out of range");
+    if (channels < 1 || channels > kMaxChannels) return fail(SCNN_EINVAL, "bad channel count");
+    if (n_sites_total < 1) return fail(SCNN_EINVAL, "n_sites_total must be positive");
+    if (!(rho_up >= 0.0 && rho_up <= 1.0)) return fail(SCNN_EINVAL, "rho_up = %g not in [0, 1]", rho_up);
+    if (!(o >= 0.0) || !(b1 >= 0.0) || !(b2 >= 0.0)) return fail(SCNN_EINVAL, "o, b1, b2 must be >= 0");
+    if (n_w < 0 || n_w > kMaxIndex) return fail(SCNN_ECAPACITY, "n_w out of range");
+    if (!result || !workspace || (n_w > 0 && !w)) return fail(SCNN_EINVAL, "null pointer");
+    if (rows > 0 && !out_feats) return fail(SCNN_EINVAL, "null out_feats");
+    if (((uintptr_t)workspace & 255) != 0 || workspace_bytes < density_regulariser_workspace())
+        return fail(SCNN_EWORKSPACE, "workspace too small or misaligned");
+    unsigned long long* count = (unsigned long long*)workspace;
+    double* partial = (double*)((char*)workspace + 256);
+    SCNN_TRY(launch_density_regulariser(out_feats, rows, (const long long*)rows_dev, rows, channels,
+                                        (double)n_sites_total * channels, rho_up, o, b1, b2, lambda, w, n_w, grad_w,
+                                        count, partial, result, (hipStream_t)hip_stream));
+    return SCNN_OK;
+}
+
+int prune_weights(float* w, unsigned char* warned, int64_t n_w, float eps, int64_t* counts, void* hip_stream) {
+    if (n_w < 0 || n_w > kMaxIndex) return fail(SCNN_ECAPACITY, "n_w out of range");
+    if (!(eps >= 0.0f)) return fail(SCNN_EINVAL, "eps must be >= 0");
+    if (!counts || (n_w > 0 && (!w || !warned))) return fail(SCNN_EINVAL, "null pointer");
+    SCNN_TRY(launch_prune(w, warned, n_w, eps, (unsigned long long*)counts, (hipStream_t)hip_stream));
+    return SCNN_OK;
+}
+
 // ---------------------------------------------------------------- validation
 int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t* coords, int64_t rows,
                        void* workspace, size_t workspace_bytes, void* hip_stream) {

@@ -367,7 +367,7 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
 #pragma unroll
             for (int c = 0; c < NT; ++c)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) acc64[a][c][v] += (double)acc[a][c][v];
+                for (int v = 0; v < 4; ++v) acc64[a][c][v] = fma((double)acc[a][c][v], 1.0, acc64[a][c][v]);  // full-rate form of the add
     }
     // result element (a, c, v) of this lane: input channel (4*gq + v)*MT + a, output channel jj*NT + c of the slab
     const int t = taps - 1 - ta;  // tap of the filter itself

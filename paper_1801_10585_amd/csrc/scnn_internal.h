@@ -229,6 +229,14 @@ hipError_t launch_bwd_filter_finish(const double* fpart, int n_chunks, long long
                                     float* bp_filter, const Counters* ctr, long long nnz_in, long long g_rows,
                                     long long* info, hipStream_t s);
 
+// scnn_train.hip
+hipError_t launch_density_regulariser(const float* feats, long long rows_imm, const long long* rows_dev,
+                                      long long rows_cap, int channels, double n_total, double rho_up, double o,
+                                      double b1, double b2, double lambda, const float* w, long long n_w, float* grad,
+                                      unsigned long long* count, double* partial, double* out, hipStream_t s);
+hipError_t launch_prune(float* w, unsigned char* warned, long long n, float eps, unsigned long long* counts,
+                        hipStream_t s);
+
 // scnn_topk.hip
 hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long long rows, int* cand_start,
                                      int* tile_start, Counters* ctr, hipStream_t s);
