@@ -118,6 +118,21 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                     int64_t out_capacity, int64_t cand_capacity, int64_t* nnz_out, void* workspace,
                     size_t workspace_bytes, void* hip_stream);
 
+/* sparse_conv_fwd for a layer that follows another one on the same stream
+ * without a host read in between: the number of input rows is taken on the
+ * device from nnz_in_dev[0] (for instance the previous call's nnz_out), clamped
+ * to in_capacity, the row capacity of in_coords / in_feats that also sizes the
+ * workspace (sparse_conv_fwd_workspace with nnz_in = in_capacity).  Rows past
+ * the device count are never read.  Everything else as sparse_conv_fwd.  A
+ * chain of such calls contains no allocation, host synchronisation or memset
+ * node, so it can be captured in a HIP graph (per-stage timing must be off). */
+int sparse_conv_fwd_chained(int ndim, const int32_t* extent, int batch, const int32_t* in_coords,
+                            const float* in_feats, int64_t in_capacity, const int64_t* nnz_in_dev, int c_in,
+                            const int32_t* ksize, const float* w, const float* bias, int c_out, double rho_up,
+                            int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats, int64_t out_capacity,
+                            int64_t cand_capacity, int64_t* nnz_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream);
+
 /* The attention step alone (Sec. 3.2; Alg. 1 steps 13, 15-17): k-selection per
  * (sample, channel) over the non-zero entries of a site-major response matrix
  * resp[rows, channels] whose rows are given by `coords`.  k is the integer
@@ -146,9 +161,11 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
  * appendix table of architectures): dense fp32 [batch, channels, extent...]
  * (channel-major, last spatial axis fastest) with dense[b, c, site(r)] =
  * feats[r, c] for every row r and 0 everywhere else.  dense: device pointer,
- * 16-byte aligned, overwritten entirely.  Rows outside the grid are skipped. */
+ * 16-byte aligned, overwritten entirely.  Rows outside the grid are skipped.
+ * rows_dev (nullable, device): the row count is read from there, capped by
+ * rows, so that the call can end a chain without a host read. */
 int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* feats,
-                    int64_t rows, int channels, float* dense, void* hip_stream);
+                    int64_t rows, const int64_t* rows_dev, int channels, float* dense, void* hip_stream);
 
 /* Adaptive density regularisation (Sec. 3.5, Eq. 4).  The density of a layer's
  * output, rho = (non-zero entries of out_feats[0 .. rows)) / (n_sites_total *

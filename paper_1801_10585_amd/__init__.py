@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     FLAG_OUT_OVERFLOW,
     FLAG_UNSORTED,
     ScnnError,
+    ChainedLayer,
     attention_topk,
     calibration_copy,
     density_regulariser,

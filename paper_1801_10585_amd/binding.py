@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "sparse_maxpool_workspace", "sparse_maxpool", "scnn_validate_rows", "scnn_profile_enable",
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
     "sparse_conv_bwd_workspace", "sparse_conv_bwd", "sparse_to_dense",
-    "density_regulariser_workspace", "density_regulariser", "prune_weights",
+    "density_regulariser_workspace", "density_regulariser", "prune_weights", "sparse_conv_fwd_chained",
 ]
 
 
@@ -76,7 +76,10 @@ def load_library():
     L.sparse_maxpool.restype = ci
     L.sparse_maxpool.argtypes = [ci, i32p, ci, ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
     L.sparse_to_dense.restype = ci
-    L.sparse_to_dense.argtypes = [ci, i32p, ci, vp, vp, i64, ci, vp, vp]
+    L.sparse_to_dense.argtypes = [ci, i32p, ci, vp, vp, i64, vp, ci, vp, vp]
+    L.sparse_conv_fwd_chained.restype = ci
+    L.sparse_conv_fwd_chained.argtypes = [ci, i32p, ci, vp, vp, i64, vp, ci, i32p, vp, vp, ci, dbl, ci, cu, vp, vp, i64,
+                                          i64, vp, vp, sz, vp]
     L.density_regulariser_workspace.restype = sz
     L.density_regulariser_workspace.argtypes = []
     L.density_regulariser.restype = ci
@@ -261,6 +264,54 @@ def sparse_conv_bwd_workspace(extent, batch, nnz_in, c_in, c_out, ksize, g_rows)
     return r
 
 
+class ChainedLayer:
+    """One layer of a chain that runs without host reads: buffers sized once from capacities, the input row count
+    taken on the device.  `in_capacity` bounds the rows of the input arrays."""
+
+    def __init__(self, extent, batch, in_capacity, c_in, ksize, w, *, bias=None, rho_up=1.0, topk_mode=ABS,
+                 relu=False, pool=False):
+        L = load_library()
+        self.extent, self.batch, self.ksize = tuple(int(e) for e in extent), int(batch), tuple(int(k) for k in ksize)
+        self.ndim = len(self.extent)
+        self.w = _dev(w, torch.float32, "w")
+        self.bias = None if bias is None else _dev(bias, torch.float32, "bias")
+        self.c_in, self.c_out = int(c_in), int(self.w.shape[2])
+        self.in_capacity = max(1, int(in_capacity))
+        self.rho_up, self.topk_mode = float(rho_up), int(topk_mode)
+        self.fuse = (FUSE_RELU if relu else 0) | (FUSE_MAXPOOL2 if pool else 0)
+        ext, ks = _i32arr(self.extent), _i32arr(self.ksize)
+        self.cand_capacity = int(L.sparse_conv_fwd_max_rows(self.ndim, ext, self.batch, self.in_capacity, ks))
+        need = int(L.sparse_conv_fwd_workspace(self.ndim, ext, self.batch, self.in_capacity, self.c_in, self.c_out, ks,
+                                               self.fuse, self.cand_capacity))
+        if need == 0:
+            raise ScnnError(-1, L.scnn_last_error().decode())
+        dev = self.w.device
+        self.out_extent = tuple((e + 1) // 2 for e in self.extent) if pool else self.extent
+        n_out = self.batch
+        for e in self.out_extent:
+            n_out *= e
+        self.out_capacity = min(self.cand_capacity, n_out)
+        self.workspace = torch.empty(need, dtype=torch.uint8, device=dev)
+        self.out_coords = torch.empty((self.out_capacity, 1 + self.ndim), dtype=torch.int32, device=dev)
+        self.out_feats = torch.empty((self.out_capacity, self.c_out), dtype=torch.float32, device=dev)
+        self.nnz = torch.zeros(NNZ_LEN, dtype=torch.int64, device=dev)
+
+    def __call__(self, coords, feats, nnz_in_dev, stream=None):
+        """Enqueue the layer; returns (out_coords, out_feats, nnz) -- full-capacity buffers, the count stays on the
+        device in nnz[0]."""
+        L = load_library()
+        if coords.shape[0] > self.in_capacity or feats.shape != (coords.shape[0], self.c_in):
+            raise ValueError("input arrays do not fit this layer")
+        rc = L.sparse_conv_fwd_chained(self.ndim, _i32arr(self.extent), self.batch, _ptr(coords), _ptr(feats),
+                                       coords.shape[0], _ptr(nnz_in_dev), self.c_in, _i32arr(self.ksize), _ptr(self.w),
+                                       _ptr(self.bias), self.c_out, self.rho_up, self.topk_mode, self.fuse,
+                                       _ptr(self.out_coords), _ptr(self.out_feats), self.out_capacity,
+                                       self.cand_capacity, _ptr(self.nnz), _ptr(self.workspace),
+                                       self.workspace.numel(), _stream(stream))
+        _check(L, rc)
+        return self.out_coords, self.out_feats, self.nnz
+
+
 def attention_topk(extent, batch, coords, resp, k, topk_mode=ABS, *, out_capacity=None, workspace=None, stream=None,
                    sync=True):
     L = load_library()
@@ -335,7 +386,7 @@ def sparse_maxpool(extent, batch, coords, feats, window=2, *, out_capacity=None,
     return _finish(out_coords, out_feats, nnz, sync)
 
 
-def sparse_to_dense(extent, batch, coords, feats, *, out=None, stream=None):
+def sparse_to_dense(extent, batch, coords, feats, *, rows_dev=None, out=None, stream=None):
     """Dense fp32 [batch, channels, *extent] holding the rows' values, zero elsewhere."""
     L = load_library()
     coords = _dev(coords, torch.int32, "coords")
@@ -343,8 +394,8 @@ def sparse_to_dense(extent, batch, coords, feats, *, out=None, stream=None):
     rows, ch = feats.shape
     if out is None:
         out = torch.empty((int(batch), ch, *[int(e) for e in extent]), dtype=torch.float32, device=feats.device)
-    _check(L, L.sparse_to_dense(len(extent), _i32arr(extent), int(batch), _ptr(coords), _ptr(feats), rows, ch,
-                                _ptr(out), _stream(stream)))
+    _check(L, L.sparse_to_dense(len(extent), _i32arr(extent), int(batch), _ptr(coords), _ptr(feats), rows,
+                                _ptr(rows_dev), ch, _ptr(out), _stream(stream)))
     return out
 
 

@@ -293,11 +293,11 @@ size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int
     return w.total;
 }
 
-int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
-                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, const float* bias, int c_out,
-                    double rho_up, int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats,
-                    int64_t out_capacity, int64_t cand_capacity, int64_t* nnz_out, void* workspace,
-                    size_t workspace_bytes, void* hip_stream) {
+static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                         int64_t nnz_in, const int64_t* nnz_in_dev, int c_in, const int32_t* ksize, const float* w,
+                         const float* bias, int c_out, double rho_up, int topk_mode, unsigned fuse,
+                         int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t cand_capacity,
+                         int64_t* nnz_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
     Geom g;
     if (!ksize) return fail(SCNN_EINVAL, "ksize is null");
     int rc = make_geom(ndim, extent, batch, ksize, &g);
@@ -330,7 +330,10 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
         g_conv_path != 1 && conv_mfma_supported(g, c_in, c_out, nnz_in) && ((uintptr_t)in_feats & 15) == 0;
     SCNN_TRY(launch_prepare(g, w, c_in, c_out, 0, ws.c_out_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
                             ws.tap_coord, workspace, ws.zero_bytes, s));
-    SCNN_TRY(launch_index_build(g, in_coords, nnz_in, nullptr, nnz_in, ws.occ, ws.occ_prefix, ws.ctr, s));
+    // with a device-resident count, nnz_in is only the capacity of the input arrays: rows past the true count are
+    // never indexed, so no look-up can return them
+    SCNN_TRY(launch_index_build(g, in_coords, nnz_in, (const long long*)nnz_in_dev, nnz_in, ws.occ, ws.occ_prefix,
+                                ws.ctr, s));
     timer.mark();
     SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
     SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
@@ -347,7 +350,8 @@ int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     } else {
         timer.mark();
         SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
-                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
+                                  ws.resp, s));
     }
     timer.mark();
     SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
@@ -496,7 +500,8 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     } else {
         timer.mark();
         SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, g_rows, g_feats, c_out, ws.wp, c_in, ws.c_in_pad, nullptr,
-                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, s));
+                                  ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
+                                  ws.resp, s));
     }
     timer.mark();
     SCNN_TRY(launch_bwd_data_write(g, ws.resp, in_feats, c_in, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
@@ -513,6 +518,28 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                                       (long long*)info, s));
     timer.done();
     return SCNN_OK;
+}
+
+int sparse_conv_fwd(int ndim, const int32_t* extent, int batch, const int32_t* in_coords, const float* in_feats,
+                    int64_t nnz_in, int c_in, const int32_t* ksize, const float* w, const float* bias, int c_out,
+                    double rho_up, int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats,
+                    int64_t out_capacity, int64_t cand_capacity, int64_t* nnz_out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    return conv_fwd_impl(ndim, extent, batch, in_coords, in_feats, nnz_in, nullptr, c_in, ksize, w, bias, c_out, rho_up,
+                         topk_mode, fuse, out_coords, out_feats, out_capacity, cand_capacity, nnz_out, workspace,
+                         workspace_bytes, hip_stream);
+}
+
+int sparse_conv_fwd_chained(int ndim, const int32_t* extent, int batch, const int32_t* in_coords,
+                            const float* in_feats, int64_t in_capacity, const int64_t* nnz_in_dev, int c_in,
+                            const int32_t* ksize, const float* w, const float* bias, int c_out, double rho_up,
+                            int topk_mode, unsigned fuse, int32_t* out_coords, float* out_feats, int64_t out_capacity,
+                            int64_t cand_capacity, int64_t* nnz_out, void* workspace, size_t workspace_bytes,
+                            void* hip_stream) {
+    if (!nnz_in_dev) return fail(SCNN_EINVAL, "nnz_in_dev is null");
+    return conv_fwd_impl(ndim, extent, batch, in_coords, in_feats, in_capacity, nnz_in_dev, c_in, ksize, w, bias, c_out,
+                         rho_up, topk_mode, fuse, out_coords, out_feats, out_capacity, cand_capacity, nnz_out,
+                         workspace, workspace_bytes, hip_stream);
 }
 
 int scnn_set_conv_path(int path) {
@@ -747,7 +774,7 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
 
 // ---------------------------------------------------------------- sparse_to_dense
 int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* coords, const float* feats,
-                    int64_t rows, int channels, float* dense, void* hip_stream) {
+                    int64_t rows, const int64_t* rows_dev, int channels, float* dense, void* hip_stream) {
     Geom g;
     int rc = make_geom(ndim, extent, batch, nullptr, &g);
     if (rc != SCNN_OK) return rc;
@@ -757,7 +784,7 @@ int sparse_to_dense(int ndim, const int32_t* extent, int batch, const int32_t* c
     if (!dense) return fail(SCNN_EINVAL, "dense is null");
     if (((uintptr_t)dense & 15) != 0) return fail(SCNN_EINVAL, "dense must be 16-byte aligned");
     if (rows > 0 && (!coords || !feats)) return fail(SCNN_EINVAL, "null input arrays");
-    SCNN_TRY(launch_to_dense(g, coords, feats, rows, channels, dense, (hipStream_t)hip_stream));
+    SCNN_TRY(launch_to_dense(g, coords, feats, rows, (const long long*)rows_dev, channels, dense, (hipStream_t)hip_stream));
     return SCNN_OK;
 }
 

@@ -25,9 +25,11 @@ namespace scnn {
 constexpr int kTapChunk = 32;  // taps whose neighbour rows are staged in LDS at a time
 constexpr int kOcBlock = 16;   // output channels accumulated per thread
 
-// Generic vector kernel: any C_in, C_out, any filter sparsity.
-// Work item = (tile, block of 32 output channels); thread = (row, 16 channels).
-__global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long long* __restrict__ occ,
+// Streaming form of the vector kernel, for layers with many more work items than workgroup slots: little shared
+// memory and few registers, so that 32 waves per compute unit hide each other's memory latency; a thread walks its
+// taps and input channels one load at a time.  Work item = (tile, block of 32 output channels); thread = (row, 16
+// channels).  Runs only when the layer has more than `min_items` work items (a device-side count).
+__global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned long long* __restrict__ occ,
                                                    const unsigned* __restrict__ occ_prefix, long long nnz_in,
                                                    const float* __restrict__ feats, int c_in,
                                                    const double* __restrict__ wp, int c_out, int c_out_pad,
@@ -36,13 +38,15 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                                                    const unsigned* __restrict__ cand_lin,
                                                    const int* __restrict__ cand_start,
                                                    const int* __restrict__ tile_start,
-                                                   const Counters* __restrict__ ctr, float* __restrict__ resp) {
+                                                   const Counters* __restrict__ ctr, long long min_items,
+                                                          float* __restrict__ resp) {
     __shared__ int s_nbr[kTileRows][kTapChunk + 1];
     __shared__ int s_site[kTileRows][3];
 
     const int n_tiles = (int)ctr->n_tiles;
     const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
     const long long n_items = (long long)n_tiles * n_chunks;
+    if (n_items <= min_items) return;  // the latency-oriented kernel takes small layers
     const int row = threadIdx.x & (kTileRows - 1);
     const int half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);  // which 16-channel block of the chunk
 
@@ -113,13 +117,244 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
     }
 }
 
+// Response tiles of a layer without input rows (candidate sites cannot exist either; kept for completeness).
+__global__ __launch_bounds__(256) void k_conv_valu_empty(int c_out, const Counters* __restrict__ ctr,
+                                                         float* __restrict__ resp) {
+    const size_t n = (size_t)ctr->n_tiles * c_out * kTileRows;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x)
+        resp[i] = 0.0f;
+}
+
+// Latency-oriented form of the vector kernel, for layers with at most `max_items` work items (about one per
+// workgroup slot of the chip: the regime of the paper's own narrow networks on small grids).
+// Work item = (tile, block of 32 output channels); thread = (row, 16 channels).  When the block has only 16
+// channels (C_out <= 16, or the last block), the second half of the workgroup would idle: it then takes every
+// other tap of the same 16 channels instead and the two partial sums are added through LDS (even taps + odd taps,
+// a fixed order).
+// What bounds a small layer is memory latency, not arithmetic, so nothing in the inner loop waits on global memory:
+// the neighbour rows of a chunk of taps are looked up with all bitmap and prefix loads of a batch in flight at once,
+// and the neighbours' values are gathered into LDS cooperatively (CH channels of TG taps at a time, every load
+// independent of every other), together with the group's weights, before the multiply-add phase reads both from
+// there.
+constexpr int kLookupBatch = 8;
+template <int CH /* input channels per gather: the largest of 8, 4, 2, 1 that divides C_in */>
+__global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long long* __restrict__ occ,
+                                                   const unsigned* __restrict__ occ_prefix, long long nnz_in,
+                                                   const float* __restrict__ feats, int c_in,
+                                                   const double* __restrict__ wp, int c_out, int c_out_pad,
+                                                   const float* __restrict__ bias,
+                                                   const int* __restrict__ tap_active,
+                                                   const unsigned* __restrict__ cand_lin,
+                                                   const int* __restrict__ cand_start,
+                                                   const int* __restrict__ tile_start,
+                                                   const Counters* __restrict__ ctr, long long max_items,
+                                                   float* __restrict__ resp) {
+    constexpr int TG = (64 / CH) < kTapChunk ? (64 / CH) : kTapChunk;  // taps per gather
+    constexpr int XS = TG * CH + 4;                                     // row stride of the gathered values
+    __shared__ int s_nbr[kTileRows][kTapChunk + 1];
+    __shared__ int s_site[kTileRows][3];
+    __shared__ __align__(16) float s_x[kTileRows][XS];
+    __shared__ __align__(16) double s_w[2][TG * CH][kOcBlock];  // the group's weights, per 16-channel block
+    // partial sums of the second half when it shares the taps; reuses the gather buffer after the last group
+    static_assert(sizeof(float) * XS >= sizeof(double) * (kOcBlock + 1), "gather rows hold a row of partial sums");
+    double (*s_acc)[kOcBlock + 1] = reinterpret_cast<double (*)[kOcBlock + 1]>(&s_x[0][0]);
+
+    const int n_tiles = (int)ctr->n_tiles;
+    const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
+    const long long n_items = (long long)n_tiles * n_chunks;
+    if (n_items > max_items) return;  // the streaming kernel takes large layers
+    const int row = threadIdx.x & (kTileRows - 1);
+    const int half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);  // which 16-channel block of the chunk
+    const long long occ_words = (long long)g.batch * g.Wps;
+
+    for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int tile = (int)(item / n_chunks);
+        const int chunk = (int)(item - (long long)tile * n_chunks);
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+        int nrows = cand_start[b + 1] - first;
+        if (nrows > kTileRows) nrows = kTileRows;
+        // the chunk's second 16-channel block does not exist: both halves work on the first one, taps interleaved
+        const bool split = chunk * 2 * kOcBlock + kOcBlock >= c_out_pad;
+        const int oc0 = chunk * 2 * kOcBlock + (split ? 0 : half * kOcBlock);
+
+        __syncthreads();  // previous item's readers of the shared arrays are done
+        if (threadIdx.x < kTileRows) {
+            int c0 = 0, c1 = 0, c2 = 0;
+            if (threadIdx.x < nrows) site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
+            s_site[threadIdx.x][0] = c0;
+            s_site[threadIdx.x][1] = c1;
+            s_site[threadIdx.x][2] = c2;
+        }
+
+        double acc[kOcBlock];
+#pragma unroll
+        for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
+
+        for (int tc = 0; tc < g.T; tc += kTapChunk) {
+            const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
+            __syncthreads();
+            // ---- neighbour rows of (row, tap): element i = tap-in-chunk * 128 + row.  No branch between the loads:
+            //      an absent neighbour reads word 0 and is discarded afterwards.
+            for (int i0 = threadIdx.x; i0 < kTileRows * tmax; i0 += 256 * kLookupBatch) {
+                long long key[kLookupBatch];
+                unsigned long long word[kLookupBatch];
+                unsigned pre[kLookupBatch];
+#pragma unroll
+                for (int m = 0; m < kLookupBatch; ++m) {
+                    const int i = i0 + m * 256;
+                    const int r = i & (kTileRows - 1), tt = i >> 7;
+                    const int t = (tt < tmax) ? tc + tt : tc;
+                    const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
+                    const int q0 = s_site[r][0] + t0 - g.H[0], q1 = s_site[r][1] + t1 - g.H[1],
+                              q2 = s_site[r][2] + t2 - g.H[2];
+                    const bool ok = tt < tmax && r < nrows && tap_active[t] != 0 && site_in_grid(g, b, q0, q1, q2);
+                    key[m] = ok ? (long long)b * g.Npad + lin_of(g, q0, q1, q2) : -1;
+                }
+#pragma unroll
+                for (int m = 0; m < kLookupBatch; ++m) {
+                    long long wi = key[m] >> 6;
+                    wi = (wi >= 0 && wi < occ_words) ? wi : 0;
+                    word[m] = occ[wi];
+                    pre[m] = occ_prefix[wi];
+                }
+#pragma unroll
+                for (int m = 0; m < kLookupBatch; ++m) {
+                    const int i = i0 + m * 256;
+                    if (i < kTileRows * tmax) {
+                        int n = -1;
+                        const int bit = (int)(key[m] & 63);
+                        if (key[m] >= 0 && ((word[m] >> bit) & 1ull)) {
+                            const long long rr = (long long)pre[m] + __popcll(word[m] & ((1ull << bit) - 1ull));
+                            if (rr < nnz_in) n = (int)rr;  // only an unsorted input can trip this guard
+                        }
+                        s_nbr[i & (kTileRows - 1)][i >> 7] = n;
+                    }
+                }
+            }
+            for (int ic0 = 0; ic0 < c_in; ic0 += CH) {
+                for (int tg0 = 0; tg0 < tmax; tg0 += TG) {
+                    const int tg_n = (tmax - tg0) < TG ? (tmax - tg0) : TG;
+                    __syncthreads();  // s_nbr complete; the previous group's readers of s_x are done
+                    // ---- gather CH channels of every present neighbour of the group
+                    constexpr int GB = (kTileRows * TG) / 256;  // (row, tap) pairs per thread
+                    float xv[GB][CH];
+#pragma unroll
+                    for (int m = 0; m < GB; ++m) {
+                        const int e = threadIdx.x + m * 256;
+                        const int r = e & (kTileRows - 1), tg = e >> 7;
+                        int n = (tg < tg_n) ? s_nbr[r][tg0 + tg] : -1;
+                        const float* __restrict__ xp = feats + (size_t)(n < 0 ? 0 : n) * c_in + ic0;
+                        if constexpr (CH == 8) {
+                            const float4 u = *(const float4*)xp, v = *(const float4*)(xp + 4);
+                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                            xv[m][4] = v.x; xv[m][5] = v.y; xv[m][6] = v.z; xv[m][7] = v.w;
+                        } else if constexpr (CH == 4) {
+                            const float4 u = *(const float4*)xp;
+                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                        } else if constexpr (CH == 2) {
+                            const float2 u = *(const float2*)xp;
+                            xv[m][0] = u.x; xv[m][1] = u.y;
+                        } else {
+                            xv[m][0] = xp[0];
+                        }
+                    }
+#pragma unroll
+                    for (int m = 0; m < GB; ++m) {
+                        const int e = threadIdx.x + m * 256;
+                        const int r = e & (kTileRows - 1), tg = e >> 7;
+#pragma unroll
+                        for (int j = 0; j < CH; ++j) s_x[r][tg * CH + j] = xv[m][j];
+                    }
+                    // the group's weights: s_w[hb][tg * CH + j][o] = w[tap tg][ic0 + j][16 * hb + o of the chunk]
+                    for (int e = threadIdx.x; e < 2 * TG * CH * kOcBlock; e += 256) {
+                        const int o = e & (kOcBlock - 1), tj = (e >> 4) % (TG * CH), hb = e / (TG * CH * kOcBlock);
+                        const int tg = tj / CH, j = tj - tg * CH;
+                        const int oc = chunk * 2 * kOcBlock + hb * kOcBlock + o;
+                        double v = 0.0;
+                        if (tg < tg_n && oc < c_out_pad)
+                            v = wp[((size_t)(tc + tg0 + tg) * c_in + ic0 + j) * c_out_pad + oc];
+                        s_w[hb][tj][o] = v;
+                    }
+                    __syncthreads();
+                    // ---- multiply-add: values and weights from LDS (the weights are a broadcast read)
+                    if (oc0 < c_out_pad && row < nrows) {
+                        const int hb = split ? 0 : half;
+                        for (int tg = split ? half : 0; tg < tg_n; tg += split ? 2 : 1) {
+                            if (s_nbr[row][tg0 + tg] < 0) continue;
+#pragma unroll
+                            for (int j = 0; j < CH; ++j) {
+                                const double xd = (double)s_x[row][tg * CH + j];
+                                const double* wr = &s_w[hb][tg * CH + j][0];
+#pragma unroll
+                                for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        if (split) {  // even taps (first half) + odd taps (second half)
+            __syncthreads();  // the last group's values have been read
+            if (half == 1) {
+#pragma unroll
+                for (int o = 0; o < kOcBlock; ++o) s_acc[row][o] = acc[o];
+            }
+            __syncthreads();
+            if (half == 0) {
+#pragma unroll
+                for (int o = 0; o < kOcBlock; ++o) acc[o] += s_acc[row][o];
+            }
+        }
+        if (oc0 < c_out_pad && (!split || half == 0)) {
+#pragma unroll
+            for (int o = 0; o < kOcBlock; ++o) {
+                const int oc = oc0 + o;
+                if (oc < c_out) {
+                    float v = (row < nrows) ? (float)acc[o] : 0.0f;
+                    if (bias && v != 0.0f) v += bias[oc];
+                    resp[((size_t)tile * c_out + oc) * kTileRows + row] = v;
+                }
+            }
+        }
+    }
+}
+
+// Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
+constexpr long long kValuLatencyItems = 2048;
+
 hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                             long long nnz_in, const float* feats, int c_in, const double* wp, int c_out,
                             int c_out_pad, const float* bias, const int* tap_active, const unsigned* cand_lin,
-                            const int* cand_start, const int* tile_start, const Counters* ctr, float* resp,
-                            hipStream_t s) {
-    hipLaunchKernelGGL(k_conv_valu, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, wp,
-                       c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr, resp);
+                            const int* cand_start, const int* tile_start, const Counters* ctr, long long tiles_cap,
+                            float* resp, hipStream_t s) {
+    if (nnz_in <= 0) {  // no input row: every response tile is zero (the gather would have no row to point at)
+        hipLaunchKernelGGL(k_conv_valu_empty, dim3(256 * 8), dim3(256), 0, s, c_out, ctr, resp);
+        return hipGetLastError();
+    }
+    // Which kernel runs is decided by the number of work items, which only the device knows.  The host knows an
+    // upper bound (tiles_cap): when that is small the latency-oriented kernel is launched alone; otherwise both
+    // are launched and the one whose regime it is not returns at once (a few microseconds).
+    const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
+    if (tiles_cap * n_chunks > kValuLatencyItems)
+        hipLaunchKernelGGL(k_conv_valu_stream, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in,
+                           wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,
+                           kValuLatencyItems, resp);
+    // vector loads of CH channels need the row start aligned to them
+    const int align_ch = (int)((((uintptr_t)feats) & 15) == 0 ? 8 : ((((uintptr_t)feats) & 7) == 0 ? 2 : 1));
+    int ch = 1;
+    if (c_in % 8 == 0 && align_ch >= 8) ch = 8;
+    else if (c_in % 4 == 0 && align_ch >= 8) ch = 4;
+    else if (c_in % 2 == 0 && align_ch >= 2) ch = 2;
+#define SCNN_VALU_CASE(CH_)                                                                                        \
+    hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, wp, \
+                       c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr, kValuLatencyItems,  \
+                       resp)
+    if (ch == 8) SCNN_VALU_CASE(8);
+    else if (ch == 4) SCNN_VALU_CASE(4);
+    else if (ch == 2) SCNN_VALU_CASE(2);
+    else SCNN_VALU_CASE(1);
+#undef SCNN_VALU_CASE
     return hipGetLastError();
 }
 

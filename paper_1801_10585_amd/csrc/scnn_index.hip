@@ -113,10 +113,12 @@ hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n
 // records its own index as that word's prefix.  Rows outside the grid are
 // skipped and reported; a row not strictly above its predecessor is reported.
 __global__ __launch_bounds__(256) void k_index_build(Geom g, const int32_t* __restrict__ coords, long long n_imm,
-                                                     const long long* __restrict__ n_dev,
+                                                     const long long* __restrict__ n_dev, long long n_cap,
                                                      unsigned long long* __restrict__ occ,
                                                      unsigned* __restrict__ occ_prefix, Counters* ctr) {
-    const long long n = n_dev ? *n_dev : n_imm;
+    long long n = n_dev ? *n_dev : n_imm;
+    if (n > n_cap) n = n_cap;  // a device-resident count never reaches past the arrays
+    if (n < 0) n = 0;
     const int stride = 1 + g.ndim;
     const int lane = threadIdx.x & 63;
     for (long long base = (long long)blockIdx.x * blockDim.x; base < n; base += (long long)gridDim.x * blockDim.x) {
@@ -160,7 +162,7 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
     long long blocks = (n_cap + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_index_build, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, n_imm, n_dev, occ,
+    hipLaunchKernelGGL(k_index_build, dim3((unsigned)blocks), dim3(256), 0, s, g, coords, n_imm, n_dev, n_cap, occ,
                        occ_prefix, ctr);
     return hipGetLastError();
 }

@@ -193,8 +193,8 @@ hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const
 hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                             long long nnz_in, const float* feats, int c_in, const double* wp, int c_out,
                             int c_out_pad, const float* bias, const int* tap_active, const unsigned* cand_lin,
-                            const int* cand_start, const int* tile_start, const Counters* ctr, float* resp,
-                            hipStream_t s);
+                            const int* cand_start, const int* tile_start, const Counters* ctr, long long tiles_cap,
+                            float* resp, hipStream_t s);
 
 bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
 hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
@@ -263,8 +263,8 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
                           unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
                           int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
                           hipStream_t s);
-hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
-                           float* dense, hipStream_t s);
+hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows,
+                           const long long* rows_dev, int channels, float* dense, hipStream_t s);
 hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows, Counters* ctr, hipStream_t s);
 hipError_t launch_finish(const Counters* ctr, int which_rows /*0 n_rows, 1 n_pool*/, long long aux_imm,
                          int aux_is_cand, long long out_capacity, long long* nnz_out, hipStream_t s);

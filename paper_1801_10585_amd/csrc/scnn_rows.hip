@@ -224,9 +224,12 @@ __global__ __launch_bounds__(256) void k_dense_fill(float* __restrict__ dense, s
 }
 
 __global__ __launch_bounds__(256) void k_dense_scatter(Geom g, const int32_t* __restrict__ coords,
-                                                       const float* __restrict__ feats, long long rows, int channels,
+                                                       const float* __restrict__ feats, long long rows_cap,
+                                                       const long long* __restrict__ rows_dev, int channels,
                                                        float* __restrict__ dense) {
     const int stride = 1 + g.ndim;
+    long long rows = rows_dev ? *rows_dev : rows_cap;
+    if (rows > rows_cap) rows = rows_cap;
     const long long total = rows * channels;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
@@ -239,8 +242,8 @@ __global__ __launch_bounds__(256) void k_dense_scatter(Geom g, const int32_t* __
     }
 }
 
-hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,
-                           float* dense, hipStream_t s) {
+hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows,
+                           const long long* rows_dev, int channels, float* dense, hipStream_t s) {
     const size_t n = (size_t)g.batch * channels * (size_t)g.N;
     size_t fb = (n / 4 + 255) / 256;
     if (fb < 1) fb = 1;
@@ -249,8 +252,8 @@ hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* fe
     if (rows > 0) {
         long long sb = (rows * channels + 255) / 256;
         if (sb > 8192) sb = 8192;
-        hipLaunchKernelGGL(k_dense_scatter, dim3((unsigned)sb), dim3(256), 0, s, g, coords, feats, rows, channels,
-                           dense);
+        hipLaunchKernelGGL(k_dense_scatter, dim3((unsigned)sb), dim3(256), 0, s, g, coords, feats, rows, rows_dev,
+                           channels, dense);
     }
     return hipGetLastError();
 }

@@ -73,3 +73,91 @@ def test_sparse_to_dense_is_exact(extent, batch, channels):
     out = torch.full((batch, channels, *extent), 7.0, dtype=torch.float32, device="cuda:0")
     scnn.sparse_to_dense(extent, batch, dev(coords[:0]), dev(feats[:0]), out=out)
     assert not host(out).any()
+
+
+def _eager_chain(wl):
+    ext, c, f = wl.extent, dev(wl.coords), dev(wl.feats)
+    for L, w in zip(wl.layers, wl.filters):
+        c, f, n = scnn.sparse_conv_fwd(ext, wl.batch, c, f, L.ksize, dev(w), rho_up=L.rho_up, relu=L.relu, pool=L.pool)
+        if L.pool:
+            ext = pooled_extent(ext)
+    return ext, host(c), host(f), host(scnn.sparse_to_dense(ext, wl.batch, c, f))
+
+
+def _build_chain(wl):
+    layers, ext, cap = [], wl.extent, wl.coords.shape[0]
+    for L, w in zip(wl.layers, wl.filters):
+        lay = scnn.ChainedLayer(ext, wl.batch, cap, L.c_in, L.ksize, dev(w), rho_up=L.rho_up, relu=L.relu, pool=L.pool)
+        layers.append(lay)
+        ext, cap = lay.out_extent, lay.out_capacity
+    dense = torch.empty((wl.batch, wl.layers[-1].c_out, *ext), dtype=torch.float32, device="cuda:0")
+    return layers, ext, dense
+
+
+def _run_chain(layers, ext, dense, c, f, n_dev, batch):
+    for lay in layers:
+        c, f, nnz = lay(c, f, n_dev)
+        n_dev = nnz[:1]
+    scnn.sparse_to_dense(ext, batch, c, f, rows_dev=n_dev, out=dense)
+    return c, f, nnz
+
+
+@pytest.mark.parametrize("r", [32, 64])
+def test_chain_without_host_reads_equals_the_call_by_call_chain(r):
+    """The same nine layers enqueued back to back with device-resident row counts (buffers at their capacities):
+    these channel widths run the vector kernels, whose sums have a fixed order, so the results must be identical."""
+    wl = make_octnet3_stack(r)
+    ext_e, c_e, f_e, dense_e = _eager_chain(wl)
+    layers, ext, dense = _build_chain(wl)
+    assert ext == ext_e
+    n0 = torch.tensor([wl.coords.shape[0]], dtype=torch.int64, device="cuda:0")
+    c, f, nnz = _run_chain(layers, ext, dense, dev(wl.coords), dev(wl.feats), n0, wl.batch)
+    nnz = host(nnz)
+    assert int(nnz[2]) == 0 and int(nnz[0]) == c_e.shape[0]
+    assert np.array_equal(host(c)[:c_e.shape[0]], c_e) and np.array_equal(host(f)[:c_e.shape[0]], f_e)
+    assert np.array_equal(host(dense), dense_e)
+    say(f"octnet3-{r} chained: {int(nnz[0])} final rows, identical to the call-by-call chain")
+
+
+def test_chain_captured_in_a_graph_replays_correctly():
+    """The chain contains no allocation, host synchronisation or memset, so it can be captured; every replay is
+    checked against the eager result, with eager work and synchronisations between the replays and a changed input
+    before the last one."""
+    wl = make_octnet3_stack(32)
+    _, c_e, f_e, dense_e = _eager_chain(wl)
+    layers, ext, dense = _build_chain(wl)
+    cap = wl.coords.shape[0]
+    cin, fin = dev(wl.coords).clone(), dev(wl.feats).clone()
+    n0 = torch.tensor([cap], dtype=torch.int64, device="cuda:0")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture
+        _run_chain(layers, ext, dense, cin, fin, n0, wl.batch)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        _run_chain(layers, ext, dense, cin, fin, n0, wl.batch)
+    for rep in range(3):
+        dense.fill_(-1.0)                               # eager work between replays
+        scnn.sparse_relu(3, dev(wl.coords), dev(np.ones((cap, 2), np.float32)))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(host(dense), dense_e), f"replay {rep}"
+        assert int(host(layers[-1].nnz)[0]) == c_e.shape[0]
+    # a different input through the same graph: half of the rows (device-resident count), same buffers
+    half = cap // 2
+    n0.fill_(half)
+    graph.replay()
+    torch.cuda.synchronize()
+    wl2_c, wl2_f = wl.coords[:half], wl.feats[:half]
+    ext2, c2 = wl.extent, None
+    cc, ff = dev(wl2_c), dev(wl2_f)
+    for L, w in zip(wl.layers, wl.filters):
+        cc, ff, _ = scnn.sparse_conv_fwd(ext2, wl.batch, cc, ff, L.ksize, dev(w), rho_up=L.rho_up, relu=L.relu,
+                                         pool=L.pool)
+        if L.pool:
+            ext2 = pooled_extent(ext2)
+    want = host(scnn.sparse_to_dense(ext2, wl.batch, cc, ff))
+    assert np.array_equal(host(dense), want), "replay with a new device-resident row count"
