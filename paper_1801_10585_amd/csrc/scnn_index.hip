@@ -98,8 +98,42 @@ __global__ __launch_bounds__(256) void k_scan_add(unsigned* __restrict__ vals, l
         if (base + i < n) vals[base + i] += add;
 }
 
+// The whole scan in one workgroup, for short arrays (small grids): one launch instead of three.
+__global__ __launch_bounds__(256) void k_scan_small(unsigned* __restrict__ vals, long long n_imm,
+                                                    const long long* __restrict__ n_dev,
+                                                    long long* __restrict__ total_out) {
+    __shared__ unsigned s_wave[4];
+    const long long n = n_dev ? *n_dev : n_imm;
+    unsigned carry = 0;
+    for (long long start = 0; start < n; start += kScanChunk) {
+        const long long base = start + (long long)threadIdx.x * 8;
+        unsigned v[8];
+        unsigned sum = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            v[i] = (base + i < n) ? vals[base + i] : 0u;
+            sum += v[i];
+        }
+        unsigned total;
+        unsigned excl = carry + block_exclusive_scan_256(sum, s_wave, total);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (base + i < n) vals[base + i] = excl;
+            excl += v[i];
+        }
+        carry += total;
+    }
+    if (threadIdx.x == 0 && total_out) *total_out = (long long)carry;
+}
+
+constexpr long long kScanSmall = 16 * kScanChunk;  // up to this many elements one workgroup scans alone
+
 hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n_imm, const long long* n_dev,
                                  unsigned* block_sums, long long* total, hipStream_t s) {
+    if (capacity <= kScanSmall) {
+        hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(256), 0, s, vals, n_imm, n_dev, total);
+        return hipGetLastError();
+    }
     long long blocks = (capacity + kScanChunk - 1) / kScanChunk;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_scan_local, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums);
@@ -145,14 +179,8 @@ __global__ __launch_bounds__(256) void k_index_build(Geom g, const int32_t* __re
         // first lane of each run issue the one atomic (a run may continue in the next wave, hence still atomic).
         const long long word = key >= 0 ? (key >> 6) : (long long)(-1 - lane);
         unsigned long long bits = key >= 0 ? (1ull << (key & 63)) : 0ull;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const long long ow = __shfl_down(word, d, 64);
-            const unsigned long long ob = __shfl_down(bits, d, 64);
-            if (lane + d < 64 && ow == word) bits |= ob;
-        }
-        const long long pw = __shfl_up(word, 1, 64);
-        if (key >= 0 && (lane == 0 || pw != word)) atomicOr(&occ[word], bits);
+        const bool first = wave_or_runs(word, bits);
+        if (key >= 0 && first) atomicOr(&occ[word], bits);
     }
 }
 
@@ -239,21 +267,28 @@ hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, in
 
 // ------------------------------------------------------------------ candidate sites
 // Candidate sites = occupied sites dilated by the filter's non-zero taps: an input at q reaches p = q - delta,
-// i.e. p is a candidate iff some active tap has an occupied site at p + delta.  One thread produces one 64-bit
-// word of the candidate bitmap by OR-ing shifted windows of the occupancy bitmap (no atomics).  A word is cut
+// i.e. p is a candidate iff some active tap has an occupied site at p + delta.  Sixteen lanes produce one 64-bit
+// word of the candidate bitmap by OR-ing shifted windows of the occupancy bitmap (no atomics): each lane takes some
+// of the (delta_0, delta_1) lines and the lanes combine with shuffles.  A word is cut
 // into the runs it shares with grid lines (last axis); for a run and a (delta_0, delta_1) pair the source bits
 // of all delta_2 lie in one window of at most three occupancy words.
 __device__ inline unsigned long long funnel64(unsigned long long lo, unsigned long long hi, int s) {
     return s ? ((lo >> s) | (hi << (64 - s))) : lo;
 }
 
+// LANES lanes share one bitmap word, one (delta_0, delta_1) line at a time each: 16 on small grids, where one lane
+// per word would leave most of the chip idle behind a chain of dependent loads, 1 on large grids.
+template <int kDilateLanes>
 __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long long* __restrict__ occ,
                                                      const int* __restrict__ tap_active,
                                                      unsigned long long* __restrict__ cand,
                                                      unsigned* __restrict__ cand_count) {
     const long long n_words = (long long)g.batch * g.Wps;
-    for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
-         w += (long long)gridDim.x * blockDim.x) {
+    const int sub = threadIdx.x & (kDilateLanes - 1);
+    const long long groups = (long long)gridDim.x * (blockDim.x / kDilateLanes);
+    const int n_lines = g.K[0] * g.K[1];
+    for (long long w = (long long)blockIdx.x * (blockDim.x / kDilateLanes) + threadIdx.x / kDilateLanes; w < n_words;
+         w += groups) {
         const int b = (int)(w / g.Wps);
         const long long p_first = (w - (long long)b * g.Wps) * 64;  // lin of bit 0
         long long remaining = g.N - p_first;                         // bits of this word that are sites
@@ -269,35 +304,32 @@ __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long
             int len = g.E[2] - c2;
             if (len > remaining) len = (int)remaining;
             unsigned long long run = 0;
-            for (int t0 = 0; t0 < g.K[0]; ++t0) {
-                const int q0 = c0 + t0 - g.H[0];
-                if ((unsigned)q0 >= (unsigned)g.E[0]) continue;
-                for (int t1 = 0; t1 < g.K[1]; ++t1) {
-                    const int q1 = c1 + t1 - g.H[1];
-                    if ((unsigned)q1 >= (unsigned)g.E[1]) continue;
-                    // window of occupancy bits [s - H2, s + len + H2) of line (q0, q1), s = site (q0, q1, c2)
-                    const long long s = sample_bit0 + ((long long)q0 * g.E[1] + q1) * g.E[2] + c2;
-                    const long long wb = (s - g.H[2]) >> 6;  // arithmetic shift: floor also for negatives
-                    unsigned long long win[3];
+            for (int l = sub; l < n_lines; l += kDilateLanes) {
+                const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+                const int q0 = c0 + t0 - g.H[0], q1 = c1 + t1 - g.H[1];
+                if ((unsigned)q0 >= (unsigned)g.E[0] || (unsigned)q1 >= (unsigned)g.E[1]) continue;
+                // window of occupancy bits [s - H2, s + len + H2) of line (q0, q1), s = site (q0, q1, c2)
+                const long long s = sample_bit0 + ((long long)q0 * g.E[1] + q1) * g.E[2] + c2;
+                const long long wb = (s - g.H[2]) >> 6;  // arithmetic shift: floor also for negatives
+                unsigned long long win[3];
 #pragma unroll
-                    for (int i = 0; i < 3; ++i) {
-                        const long long wi = wb + i;
-                        win[i] = (wi >= word_lo && wi < word_hi) ? occ[wi] : 0ull;
-                    }
-                    const int* act = tap_active + (t0 * g.K[1] + t1) * g.K[2];
-                    for (int t2 = 0; t2 < g.K[2]; ++t2) {
-                        if (!act[t2]) continue;
-                        const int d2 = t2 - g.H[2];
-                        // source z = c2 + i + d2 must stay on the line: i in [lo, hi)
-                        int lo = -d2 - c2, hi = g.E[2] - d2 - c2;
-                        if (lo < 0) lo = 0;
-                        if (hi > len) hi = len;
-                        if (lo >= hi) continue;
-                        const int o = (int)(s + d2 - wb * 64);  // 0 <= o < 128 for H2 <= 32
-                        unsigned long long bits = o < 64 ? funnel64(win[0], win[1], o) : funnel64(win[1], win[2], o - 64);
-                        unsigned long long m = (hi - lo) >= 64 ? ~0ull : (((1ull << (hi - lo)) - 1ull) << lo);
-                        run |= bits & m;
-                    }
+                for (int i = 0; i < 3; ++i) {
+                    const long long wi = wb + i;
+                    win[i] = (wi >= word_lo && wi < word_hi) ? occ[wi] : 0ull;
+                }
+                const int* act = tap_active + l * g.K[2];
+                for (int t2 = 0; t2 < g.K[2]; ++t2) {
+                    if (!act[t2]) continue;
+                    const int d2 = t2 - g.H[2];
+                    // source z = c2 + i + d2 must stay on the line: i in [lo, hi)
+                    int lo = -d2 - c2, hi = g.E[2] - d2 - c2;
+                    if (lo < 0) lo = 0;
+                    if (hi > len) hi = len;
+                    if (lo >= hi) continue;
+                    const int o = (int)(s + d2 - wb * 64);  // 0 <= o < 128 for H2 <= 32
+                    unsigned long long bits = o < 64 ? funnel64(win[0], win[1], o) : funnel64(win[1], win[2], o - 64);
+                    unsigned long long m = (hi - lo) >= 64 ? ~0ull : (((1ull << (hi - lo)) - 1ull) << lo);
+                    run |= bits & m;
                 }
             }
             out |= run << bit;
@@ -306,18 +338,31 @@ __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long
             c2 = 0;
             if (++c1 == g.E[1]) { c1 = 0; ++c0; }
         }
-        cand[w] = out;
-        cand_count[w] = (unsigned)__popcll(out);
+        // OR of the lanes' lines
+        if constexpr (kDilateLanes > 1) {
+#pragma unroll
+            for (int d = 1; d < kDilateLanes; d <<= 1) out |= __shfl_xor(out, d, kDilateLanes);
+        }
+        if (sub == 0) {
+            cand[w] = out;
+            cand_count[w] = (unsigned)__popcll(out);
+        }
     }
 }
 
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s) {
     const long long n_words = (long long)g.batch * g.Wps;
-    long long blocks = (n_words + 255) / 256;
+    const int lanes = n_words <= 32768 ? 16 : 1;  // below about half a wave per SIMD at one lane per word
+    long long blocks = (n_words * lanes + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 8192) blocks = 8192;
-    hipLaunchKernelGGL(k_cand_dilate, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active, cand, cand_count);
+    if (lanes == 16)
+        hipLaunchKernelGGL(k_cand_dilate<16>, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active, cand,
+                           cand_count);
+    else
+        hipLaunchKernelGGL(k_cand_dilate<1>, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active, cand,
+                           cand_count);
     return hipGetLastError();
 }
 

@@ -128,6 +128,22 @@ __device__ inline int lookup_row(const Geom& g, const unsigned long long* __rest
     return row < nnz_in ? (int)row : -1;  // only an unsorted input can trip this guard
 }
 
+// Bits destined for a bitmap, one (word index, bits) per lane, where lanes that address the same word sit next to
+// each other (rows sorted by site): OR the bits of each run of equal words into its first lane and report whether
+// this lane is such a first lane.  Lanes with nothing to contribute pass a word index no other lane uses (negative).
+// Every lane of the wave must call it.
+__device__ inline bool wave_or_runs(long long word, unsigned long long& bits) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const long long ow = __shfl_down(word, d, 64);
+        const unsigned long long ob = __shfl_down(bits, d, 64);
+        if (lane + d < 64 && ow == word) bits |= ob;
+    }
+    const long long pw = __shfl_up(word, 1, 64);
+    return lane == 0 || pw != word;
+}
+
 // Exclusive scan across a 256-thread block; `total` receives the block sum.
 // Contains __syncthreads(): every thread of the block must call it.
 __device__ inline unsigned block_exclusive_scan_256(unsigned v, unsigned* s_wave /*[4], shared*/, unsigned& total) {

@@ -79,18 +79,25 @@ __global__ __launch_bounds__(256) void k_pool_mark(Geom g, Geom gp, const int32_
                                                    unsigned long long* __restrict__ pbits) {
     const long long n = n_dev ? *n_dev : n_imm;
     const int stride = 1 + g.ndim;
-    for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < n;
-         r += (long long)gridDim.x * blockDim.x) {
-        int b, c0, c1, c2;
-        load_site(g, coords + r * stride, b, c0, c1, c2);
-        if (!site_in_grid(g, b, c0, c1, c2)) continue;
-        if (!rows_have_entries) {  // a row of zeros holds no entry and creates no output site
-            bool any = false;
-            for (int c = 0; c < channels; ++c) any |= feats[r * channels + c] != 0.0f;
-            if (!any) continue;
+    const int lane = threadIdx.x & 63;
+    for (long long base = (long long)blockIdx.x * blockDim.x; base < n; base += (long long)gridDim.x * blockDim.x) {
+        const long long r = base + threadIdx.x;
+        long long key = -1;
+        if (r < n) {
+            int b, c0, c1, c2;
+            load_site(g, coords + r * stride, b, c0, c1, c2);
+            bool any = site_in_grid(g, b, c0, c1, c2);
+            if (any && !rows_have_entries) {  // a row of zeros holds no entry and creates no output site
+                any = false;
+                for (int c = 0; c < channels; ++c) any |= feats[r * channels + c] != 0.0f;
+            }
+            if (any) key = (long long)b * gp.Npad + lin_of(gp, c0 >> 1, c1 >> 1, c2 >> 1);
         }
-        const long long key = (long long)b * gp.Npad + lin_of(gp, c0 >> 1, c1 >> 1, c2 >> 1);
-        atomicOr(&pbits[key >> 6], 1ull << (key & 63));
+        // neighbouring rows fall into the same output word: one atomic per run of equal words
+        const long long word = key >= 0 ? (key >> 6) : (long long)(-1 - lane);
+        unsigned long long bits = key >= 0 ? (1ull << (key & 63)) : 0ull;
+        const bool first = wave_or_runs(word, bits);
+        if (key >= 0 && first) atomicOr(&pbits[word], bits);
     }
 }
 
