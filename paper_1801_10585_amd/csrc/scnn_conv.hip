@@ -232,63 +232,84 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                     }
                 }
             }
-            for (int ic0 = 0; ic0 < c_in; ic0 += CH) {
-                for (int tg0 = 0; tg0 < tmax; tg0 += TG) {
-                    const int tg_n = (tmax - tg0) < TG ? (tmax - tg0) : TG;
-                    __syncthreads();  // s_nbr complete; the previous group's readers of s_x are done
-                    // ---- gather CH channels of every present neighbour of the group
-                    constexpr int GB = (kTileRows * TG) / 256;  // (row, tap) pairs per thread
-                    float xv[GB][CH];
+            // ---- rounds = (block of CH input channels) x (group of TG taps).  The global loads of round q + 1 (the
+            //      neighbours' values and the group's weights) are in flight while round q multiplies.
+            constexpr int GB = (kTileRows * TG) / 256;                   // (row, tap) pairs a thread gathers
+            constexpr int WB = (2 * TG * CH * kOcBlock + 255) / 256;     // weights a thread stages
+            const int n_tg = (tmax + TG - 1) / TG;
+            const int n_rounds = (c_in / CH) * n_tg;
+            float xv[GB][CH];
+            double wv[WB];
+            auto fetch = [&](int q) {
+                const int ic0 = (q / n_tg) * CH, tg0 = (q % n_tg) * TG;
+                const int tg_n = (tmax - tg0) < TG ? (tmax - tg0) : TG;
 #pragma unroll
-                    for (int m = 0; m < GB; ++m) {
-                        const int e = threadIdx.x + m * 256;
-                        const int r = e & (kTileRows - 1), tg = e >> 7;
-                        int n = (tg < tg_n) ? s_nbr[r][tg0 + tg] : -1;
-                        const float* __restrict__ xp = feats + (size_t)(n < 0 ? 0 : n) * c_in + ic0;
-                        if constexpr (CH == 8) {
-                            const float4 u = *(const float4*)xp, v = *(const float4*)(xp + 4);
-                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
-                            xv[m][4] = v.x; xv[m][5] = v.y; xv[m][6] = v.z; xv[m][7] = v.w;
-                        } else if constexpr (CH == 4) {
-                            const float4 u = *(const float4*)xp;
-                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
-                        } else if constexpr (CH == 2) {
-                            const float2 u = *(const float2*)xp;
-                            xv[m][0] = u.x; xv[m][1] = u.y;
-                        } else {
-                            xv[m][0] = xp[0];
-                        }
+                for (int m = 0; m < GB; ++m) {
+                    const int e = threadIdx.x + m * 256;
+                    const int r = e & (kTileRows - 1), tg = e >> 7;
+                    const int n = (tg < tg_n) ? s_nbr[r][tg0 + tg] : -1;
+                    const float* __restrict__ xp = feats + (size_t)(n < 0 ? 0 : n) * c_in + ic0;
+                    if constexpr (CH == 8) {
+                        const float4 u = *(const float4*)xp, v = *(const float4*)(xp + 4);
+                        xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                        xv[m][4] = v.x; xv[m][5] = v.y; xv[m][6] = v.z; xv[m][7] = v.w;
+                    } else if constexpr (CH == 4) {
+                        const float4 u = *(const float4*)xp;
+                        xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                    } else if constexpr (CH == 2) {
+                        const float2 u = *(const float2*)xp;
+                        xv[m][0] = u.x; xv[m][1] = u.y;
+                    } else {
+                        xv[m][0] = xp[0];
                     }
+                }
+                // the group's weights: element e = (hb, tg * CH + j, o) <- w[tap tg][ic0 + j][16 * hb + o of the chunk]
 #pragma unroll
-                    for (int m = 0; m < GB; ++m) {
-                        const int e = threadIdx.x + m * 256;
-                        const int r = e & (kTileRows - 1), tg = e >> 7;
+                for (int m = 0; m < WB; ++m) {
+                    const int e = threadIdx.x + m * 256;
+                    const int o = e & (kOcBlock - 1), tj = (e >> 4) % (TG * CH), hb = e / (TG * CH * kOcBlock);
+                    const int tg = tj / CH, j = tj - tg * CH;
+                    const int oc = chunk * 2 * kOcBlock + hb * kOcBlock + o;
+                    const bool ok = e < 2 * TG * CH * kOcBlock && tg < tg_n && oc < c_out_pad;
+                    const size_t at = ok ? ((size_t)(tc + tg0 + tg) * c_in + ic0 + j) * c_out_pad + oc : 0;
+                    const double v = wp[at];
+                    wv[m] = ok ? v : 0.0;
+                }
+            };
+            auto commit = [&]() {
 #pragma unroll
-                        for (int j = 0; j < CH; ++j) s_x[r][tg * CH + j] = xv[m][j];
-                    }
-                    // the group's weights: s_w[hb][tg * CH + j][o] = w[tap tg][ic0 + j][16 * hb + o of the chunk]
-                    for (int e = threadIdx.x; e < 2 * TG * CH * kOcBlock; e += 256) {
-                        const int o = e & (kOcBlock - 1), tj = (e >> 4) % (TG * CH), hb = e / (TG * CH * kOcBlock);
-                        const int tg = tj / CH, j = tj - tg * CH;
-                        const int oc = chunk * 2 * kOcBlock + hb * kOcBlock + o;
-                        double v = 0.0;
-                        if (tg < tg_n && oc < c_out_pad)
-                            v = wp[((size_t)(tc + tg0 + tg) * c_in + ic0 + j) * c_out_pad + oc];
-                        s_w[hb][tj][o] = v;
-                    }
-                    __syncthreads();
-                    // ---- multiply-add: values and weights from LDS (the weights are a broadcast read)
-                    if (oc0 < c_out_pad && row < nrows) {
-                        const int hb = split ? 0 : half;
-                        for (int tg = split ? half : 0; tg < tg_n; tg += split ? 2 : 1) {
-                            if (s_nbr[row][tg0 + tg] < 0) continue;
+                for (int m = 0; m < GB; ++m) {
+                    const int e = threadIdx.x + m * 256;
+                    const int r = e & (kTileRows - 1), tg = e >> 7;
 #pragma unroll
-                            for (int j = 0; j < CH; ++j) {
-                                const double xd = (double)s_x[row][tg * CH + j];
-                                const double* wr = &s_w[hb][tg * CH + j][0];
+                    for (int j = 0; j < CH; ++j) s_x[r][tg * CH + j] = xv[m][j];
+                }
 #pragma unroll
-                                for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
-                            }
+                for (int m = 0; m < WB; ++m) {
+                    const int e = threadIdx.x + m * 256;
+                    if (e < 2 * TG * CH * kOcBlock) (&s_w[0][0][0])[e] = wv[m];
+                }
+            };
+            __syncthreads();  // s_nbr complete
+            fetch(0);
+            for (int q = 0; q < n_rounds; ++q) {
+                const int tg0 = (q % n_tg) * TG;
+                const int tg_n = (tmax - tg0) < TG ? (tmax - tg0) : TG;
+                __syncthreads();  // the previous round's readers of s_x / s_w are done
+                commit();
+                __syncthreads();
+                if (q + 1 < n_rounds) fetch(q + 1);
+                // ---- multiply-add: values and weights from LDS (the weights are a broadcast read)
+                if (oc0 < c_out_pad && row < nrows) {
+                    const int hb = split ? 0 : half;
+                    for (int tg = split ? half : 0; tg < tg_n; tg += split ? 2 : 1) {
+                        if (s_nbr[row][tg0 + tg] < 0) continue;
+#pragma unroll
+                        for (int j = 0; j < CH; ++j) {
+                            const double xd = (double)s_x[row][tg * CH + j];
+                            const double* wr = &s_w[hb][tg * CH + j][0];
+#pragma unroll
+                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
                         }
                     }
                 }
