@@ -26,22 +26,28 @@ constexpr int kTapChunk = 32;  // taps whose neighbour rows are staged in LDS at
 constexpr int kOcBlock = 16;   // output channels accumulated per thread
 
 // Streaming form of the vector kernel, for layers with many more work items than workgroup slots: little shared
-// memory and few registers, so that 32 waves per compute unit hide each other's memory latency; a thread walks its
-// taps and input channels one load at a time.  Work item = (tile, block of 32 output channels); thread = (row, 16
-// channels).  Runs only when the layer has more than `min_items` work items (a device-side count).
+// memory and moderate registers, so that many waves per compute unit hide each other's memory latency.  A thread
+// walks its taps; per tap it fetches CH input channels with one vector load and takes the weights through scalar
+// loads.  The neighbour look-ups of a tap chunk are issued four at a time with no branch between the loads.
+// Work item = (tile, block of 32 output channels); thread = (row, 16 channels).  When the block holds only 16
+// channels the second half of the workgroup takes every other tap (partial sums added through LDS, fixed order).
+// Runs only when the layer has more than `min_items` work items (a device-side count).
+template <int CH /* the largest of 8, 4, 2, 1 that divides C_in and suits the alignment of the values */>
 __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned long long* __restrict__ occ,
-                                                   const unsigned* __restrict__ occ_prefix, long long nnz_in,
-                                                   const float* __restrict__ feats, int c_in,
-                                                   const double* __restrict__ wp, int c_out, int c_out_pad,
-                                                   const float* __restrict__ bias,
-                                                   const int* __restrict__ tap_active,
-                                                   const unsigned* __restrict__ cand_lin,
-                                                   const int* __restrict__ cand_start,
-                                                   const int* __restrict__ tile_start,
-                                                   const Counters* __restrict__ ctr, long long min_items,
+                                                          const unsigned* __restrict__ occ_prefix, long long nnz_in,
+                                                          const float* __restrict__ feats, int c_in,
+                                                          const double* __restrict__ wp, int c_out, int c_out_pad,
+                                                          const float* __restrict__ bias,
+                                                          const int* __restrict__ tap_active,
+                                                          const unsigned* __restrict__ cand_lin,
+                                                          const int* __restrict__ cand_start,
+                                                          const int* __restrict__ tile_start,
+                                                          const Counters* __restrict__ ctr, long long min_items,
                                                           float* __restrict__ resp) {
-    __shared__ int s_nbr[kTileRows][kTapChunk + 1];
+    // s_nbr doubles as the buffer of the second half's partial sums (16 doubles per row fit in 33 ints)
+    __shared__ __align__(8) int s_nbr[kTileRows][kTapChunk + 2];
     __shared__ int s_site[kTileRows][3];
+    static_assert(sizeof(int) * (kTapChunk + 2) >= sizeof(double) * (kOcBlock + 1), "a row of partial sums fits");
 
     const int n_tiles = (int)ctr->n_tiles;
     const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
@@ -57,8 +63,8 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
         int nrows = cand_start[b + 1] - first;
         if (nrows > kTileRows) nrows = kTileRows;
-        const int oc0 = chunk * 2 * kOcBlock + half * kOcBlock;
-        const bool oc_valid = oc0 < c_out_pad;
+        const bool split = chunk * 2 * kOcBlock + kOcBlock >= c_out_pad;
+        const int oc0 = chunk * 2 * kOcBlock + (split ? 0 : half * kOcBlock);
 
         __syncthreads();  // previous item's readers of s_site / s_nbr are done
         if (threadIdx.x < kTileRows) {
@@ -74,36 +80,70 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
         for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
 
         for (int tc = 0; tc < g.T; tc += kTapChunk) {
+            const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
             __syncthreads();
-            for (int i = threadIdx.x; i < kTileRows * kTapChunk; i += 256) {
-                const int tt = i & (kTapChunk - 1), r = i >> 5;
-                const int t = tc + tt;
-                int n = -1;
-                if (t < g.T && r < nrows && tap_active[t]) {
-                    const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
-                    n = lookup_row(g, occ, occ_prefix, nnz_in, b, s_site[r][0] + t0 - g.H[0],
-                                   s_site[r][1] + t1 - g.H[1], s_site[r][2] + t2 - g.H[2]);
+            // element i = line segment * 128 + row: the chunk's taps are cut into runs that share (t0, t1); a run's
+            // neighbours are adjacent sites and are resolved from one pair of bitmap words
+            {
+                const int l_first = tc / g.K[2];
+                const int n_seg = (tc + tmax - 1) / g.K[2] - l_first + 1;
+                for (int i = threadIdx.x; i < kTileRows * n_seg; i += 256) {
+                    const int r = i & (kTileRows - 1), l = l_first + (i >> 7);
+                    const int ta = tc > l * g.K[2] ? tc : l * g.K[2];
+                    const int tb = (tc + tmax) < (l + 1) * g.K[2] ? (tc + tmax) : (l + 1) * g.K[2];
+                    const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+                    int* dst = &s_nbr[r][ta - tc];
+                    lookup_line(g, occ, occ_prefix, nnz_in, r < nrows, b, s_site[r][0], s_site[r][1], s_site[r][2], t0,
+                                t1, ta - l * g.K[2], tb - ta, tap_active + ta, [&](int k, int n) { dst[k] = n; });
                 }
-                s_nbr[r][tt] = n;
             }
             __syncthreads();
-            if (oc_valid && row < nrows) {
-                const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
-                for (int tt = 0; tt < tmax; ++tt) {
+            if (oc0 < c_out_pad && row < nrows) {
+                for (int tt = split ? half : 0; tt < tmax; tt += split ? 2 : 1) {
                     const int n = s_nbr[row][tt];
                     if (n < 0) continue;
                     const float* __restrict__ x = feats + (size_t)n * c_in;
                     const double* __restrict__ wt = wp + ((size_t)(tc + tt) * c_in) * c_out_pad + oc0;
-                    for (int ic = 0; ic < c_in; ++ic) {
-                        const double xv = (double)x[ic];
-                        const double* __restrict__ wr = wt + (size_t)ic * c_out_pad;
+                    for (int ic0 = 0; ic0 < c_in; ic0 += CH) {
+                        float xv[CH];
+                        if constexpr (CH == 8) {
+                            const float4 u = *(const float4*)(x + ic0), v = *(const float4*)(x + ic0 + 4);
+                            xv[0] = u.x; xv[1] = u.y; xv[2] = u.z; xv[3] = u.w;
+                            xv[4] = v.x; xv[5] = v.y; xv[6] = v.z; xv[7] = v.w;
+                        } else if constexpr (CH == 4) {
+                            const float4 u = *(const float4*)(x + ic0);
+                            xv[0] = u.x; xv[1] = u.y; xv[2] = u.z; xv[3] = u.w;
+                        } else if constexpr (CH == 2) {
+                            const float2 u = *(const float2*)(x + ic0);
+                            xv[0] = u.x; xv[1] = u.y;
+                        } else {
+                            xv[0] = x[ic0];
+                        }
 #pragma unroll
-                        for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xv, wr[o], acc[o]);
+                        for (int j = 0; j < CH; ++j) {
+                            const double xd = (double)xv[j];
+                            const double* __restrict__ wr = wt + (size_t)(ic0 + j) * c_out_pad;
+#pragma unroll
+                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                        }
                     }
                 }
             }
         }
-        if (oc_valid) {
+        if (split) {  // even taps (first half) + odd taps (second half)
+            double* s_acc = reinterpret_cast<double*>(&s_nbr[row][0]);
+            __syncthreads();  // the last chunk's neighbour rows have been read
+            if (half == 1) {
+#pragma unroll
+                for (int o = 0; o < kOcBlock; ++o) s_acc[o] = acc[o];
+            }
+            __syncthreads();
+            if (half == 0) {
+#pragma unroll
+                for (int o = 0; o < kOcBlock; ++o) acc[o] += s_acc[o];
+            }
+        }
+        if (oc0 < c_out_pad && (!split || half == 0)) {
 #pragma unroll
             for (int o = 0; o < kOcBlock; ++o) {
                 const int oc = oc0 + o;
@@ -136,7 +176,6 @@ __global__ __launch_bounds__(256) void k_conv_valu_empty(int c_out, const Counte
 // and the neighbours' values are gathered into LDS cooperatively (CH channels of TG taps at a time, every load
 // independent of every other), together with the group's weights, before the multiply-add phase reads both from
 // there.
-constexpr int kLookupBatch = 8;
 template <int CH /* input channels per gather: the largest of 8, 4, 2, 1 that divides C_in */>
 __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long long* __restrict__ occ,
                                                    const unsigned* __restrict__ occ_prefix, long long nnz_in,
@@ -165,7 +204,6 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
     if (n_items > max_items) return;  // the streaming kernel takes large layers
     const int row = threadIdx.x & (kTileRows - 1);
     const int half = __builtin_amdgcn_readfirstlane(threadIdx.x >> 7);  // which 16-channel block of the chunk
-    const long long occ_words = (long long)g.batch * g.Wps;
 
     for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
         const int tile = (int)(item / n_chunks);
@@ -194,42 +232,19 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
         for (int tc = 0; tc < g.T; tc += kTapChunk) {
             const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
             __syncthreads();
-            // ---- neighbour rows of (row, tap): element i = tap-in-chunk * 128 + row.  No branch between the loads:
-            //      an absent neighbour reads word 0 and is discarded afterwards.
-            for (int i0 = threadIdx.x; i0 < kTileRows * tmax; i0 += 256 * kLookupBatch) {
-                long long key[kLookupBatch];
-                unsigned long long word[kLookupBatch];
-                unsigned pre[kLookupBatch];
-#pragma unroll
-                for (int m = 0; m < kLookupBatch; ++m) {
-                    const int i = i0 + m * 256;
-                    const int r = i & (kTileRows - 1), tt = i >> 7;
-                    const int t = (tt < tmax) ? tc + tt : tc;
-                    const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
-                    const int q0 = s_site[r][0] + t0 - g.H[0], q1 = s_site[r][1] + t1 - g.H[1],
-                              q2 = s_site[r][2] + t2 - g.H[2];
-                    const bool ok = tt < tmax && r < nrows && tap_active[t] != 0 && site_in_grid(g, b, q0, q1, q2);
-                    key[m] = ok ? (long long)b * g.Npad + lin_of(g, q0, q1, q2) : -1;
-                }
-#pragma unroll
-                for (int m = 0; m < kLookupBatch; ++m) {
-                    long long wi = key[m] >> 6;
-                    wi = (wi >= 0 && wi < occ_words) ? wi : 0;
-                    word[m] = occ[wi];
-                    pre[m] = occ_prefix[wi];
-                }
-#pragma unroll
-                for (int m = 0; m < kLookupBatch; ++m) {
-                    const int i = i0 + m * 256;
-                    if (i < kTileRows * tmax) {
-                        int n = -1;
-                        const int bit = (int)(key[m] & 63);
-                        if (key[m] >= 0 && ((word[m] >> bit) & 1ull)) {
-                            const long long rr = (long long)pre[m] + __popcll(word[m] & ((1ull << bit) - 1ull));
-                            if (rr < nnz_in) n = (int)rr;  // only an unsorted input can trip this guard
-                        }
-                        s_nbr[i & (kTileRows - 1)][i >> 7] = n;
-                    }
+            // ---- neighbour rows of (row, tap): element i = line segment * 128 + row; the chunk's taps are cut into
+            //      runs that share (t0, t1), whose neighbours are resolved from one pair of bitmap words
+            {
+                const int l_first = tc / g.K[2];
+                const int n_seg = (tc + tmax - 1) / g.K[2] - l_first + 1;
+                for (int i = threadIdx.x; i < kTileRows * n_seg; i += 256) {
+                    const int r = i & (kTileRows - 1), l = l_first + (i >> 7);
+                    const int ta = tc > l * g.K[2] ? tc : l * g.K[2];
+                    const int tb = (tc + tmax) < (l + 1) * g.K[2] ? (tc + tmax) : (l + 1) * g.K[2];
+                    const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+                    int* dst = &s_nbr[r][ta - tc];
+                    lookup_line(g, occ, occ_prefix, nnz_in, r < nrows, b, s_site[r][0], s_site[r][1], s_site[r][2], t0,
+                                t1, ta - l * g.K[2], tb - ta, tap_active + ta, [&](int k, int n) { dst[k] = n; });
                 }
             }
             // ---- rounds = (block of CH input channels) x (group of TG taps).  The global loads of round q + 1 (the
@@ -356,21 +371,24 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
     // Which kernel runs is decided by the number of work items, which only the device knows.  The host knows an
     // upper bound (tiles_cap): when that is small the latency-oriented kernel is launched alone; otherwise both
     // are launched and the one whose regime it is not returns at once (a few microseconds).
-    const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
-    if (tiles_cap * n_chunks > kValuLatencyItems)
-        hipLaunchKernelGGL(k_conv_valu_stream, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in,
-                           wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,
-                           kValuLatencyItems, resp);
-    // vector loads of CH channels need the row start aligned to them
+    // Vector loads of CH channels need the row start aligned to them.
     const int align_ch = (int)((((uintptr_t)feats) & 15) == 0 ? 8 : ((((uintptr_t)feats) & 7) == 0 ? 2 : 1));
     int ch = 1;
     if (c_in % 8 == 0 && align_ch >= 8) ch = 8;
     else if (c_in % 4 == 0 && align_ch >= 8) ch = 4;
     else if (c_in % 2 == 0 && align_ch >= 2) ch = 2;
-#define SCNN_VALU_CASE(CH_)                                                                                        \
-    hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, wp, \
-                       c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr, kValuLatencyItems,  \
-                       resp)
+    const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
+    const bool both = tiles_cap * n_chunks > kValuLatencyItems;
+#define SCNN_VALU_CASE(CH_)                                                                                          \
+    do {                                                                                                             \
+        if (both)                                                                                                    \
+            hipLaunchKernelGGL(k_conv_valu_stream<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in,  \
+                               feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, \
+                               ctr, kValuLatencyItems, resp);                                                        \
+        hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, \
+                           wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,            \
+                           kValuLatencyItems, resp);                                                                 \
+    } while (0)
     if (ch == 8) SCNN_VALU_CASE(8);
     else if (ch == 4) SCNN_VALU_CASE(4);
     else if (ch == 2) SCNN_VALU_CASE(2);

@@ -128,6 +128,47 @@ __device__ inline int lookup_row(const Geom& g, const unsigned long long* __rest
     return row < nnz_in ? (int)row : -1;  // only an unsorted input can trip this guard
 }
 
+// Neighbour rows of one site along one filter line: the taps (t0, t1, t2_lo .. t2_lo + count - 1), count <= 32, look
+// at the sites (c0 + t0 - H0, c1 + t1 - H1, c2 + t2 - H2), which are adjacent along the last axis and therefore sit
+// in at most two adjacent 64-bit words of the occupancy bitmap.  Both words and their prefixes are loaded once and
+// every tap of the line is resolved from them: emit(k, row) is called for k = 0 .. count-1 with the neighbour's row
+// or -1.  `live` = false (a padding lane) emits -1 everywhere without touching memory contents that matter.
+// 32-bit arithmetic throughout: site indices and bitmap word indices fit 31 bits.
+template <typename Emit>
+__device__ inline void lookup_line(const Geom& g, const unsigned long long* __restrict__ occ,
+                                   const unsigned* __restrict__ occ_prefix, long long nnz_in, bool live, int b, int c0,
+                                   int c1, int c2, int t0, int t1, int t2_lo, int count,
+                                   const int* __restrict__ tap_active_line /* [t2_lo + k] */, Emit&& emit) {
+    const int q0 = c0 + t0 - g.H[0], q1 = c1 + t1 - g.H[1];
+    const bool line_ok = live && (unsigned)b < (unsigned)g.batch && (unsigned)q0 < (unsigned)g.E[0] &&
+                         (unsigned)q1 < (unsigned)g.E[1];
+    const int q2s = c2 + t2_lo - g.H[2];               // site of tap k is q2s + k
+    const int k_lo = q2s < 0 ? -q2s : 0;               // first tap whose site is on the line
+    const unsigned line_bit0 = (unsigned)((q0 * g.E[1] + q1) * g.E[2]);  // site index of (q0, q1, 0), if line_ok
+    const unsigned first_bit = line_ok ? line_bit0 + (unsigned)(q2s + k_lo) : 0u;
+    const unsigned w_rel = first_bit >> 6;             // word of the sample holding the first looked-at site
+    const unsigned w0 = (unsigned)b * (unsigned)g.Wps + w_rel;
+    const unsigned w_last = (unsigned)g.batch * (unsigned)g.Wps - 1u;
+    const unsigned wa = line_ok ? (w0 < w_last ? w0 : w_last) : 0u, wb = wa < w_last ? wa + 1u : wa;
+    const unsigned long long word_a = occ[wa], word_b = occ[wb];
+    const unsigned pre_a = occ_prefix[wa], pre_b = occ_prefix[wb];
+    for (int k = 0; k < count; ++k) {
+        int n = -1;
+        const int q2 = q2s + k;
+        if (line_ok && (unsigned)q2 < (unsigned)g.E[2] && tap_active_line[k] != 0) {
+            const unsigned bitpos = line_bit0 + (unsigned)q2;
+            const bool second = (bitpos >> 6) != w_rel;
+            const unsigned long long word = second ? word_b : word_a;
+            const unsigned bit = bitpos & 63u;
+            if ((word >> bit) & 1ull) {
+                const long long rr = (long long)(second ? pre_b : pre_a) + __popcll(word & ((1ull << bit) - 1ull));
+                if (rr < nnz_in) n = (int)rr;  // only an unsorted input can trip this guard
+            }
+        }
+        emit(k, n);
+    }
+}
+
 // Bits destined for a bitmap, one (word index, bits) per lane, where lanes that address the same word sit next to
 // each other (rows sorted by site): OR the bits of each run of equal words into its first lane and report whether
 // this lane is such a first lane.  Lanes with nothing to contribute pass a word index no other lane uses (negative).
