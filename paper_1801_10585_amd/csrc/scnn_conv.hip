@@ -478,61 +478,56 @@ __global__ __launch_bounds__(256) void k_pair_build(Geom g, const unsigned long 
             continue;
         }
         unsigned blk = (unsigned)tile_base;  // next free block
-        for (int t0 = 0; t0 < g.T; t0 += G) {
-            // ---- neighbour lookup: all occupancy words are requested first, then all prefixes
-            long long key[G][2];
-            unsigned long long word[G][2];
-            unsigned nbr[G][2];
+        // Taps are walked in order as segments of up to G taps of one filter line (t0, t1): the neighbours of a
+        // segment are adjacent sites, resolved from one pair of bitmap words per row.  Two segments per step keep
+        // sixteen loads in flight per lane.
+        const int n_sub = (g.K[2] + G - 1) / G;
+        const int n_seg = g.K[0] * g.K[1] * n_sub;
+        for (int sg0 = 0; sg0 < n_seg; sg0 += 2) {
+            unsigned nbr[2][G][2];
+            int seg_tap[2], seg_cnt[2];
 #pragma unroll
-            for (int m = 0; m < G; ++m) {
-                const int t = (t0 + m) < g.T ? (t0 + m) : g.T - 1;
-                const bool live = (t0 + m) < g.T && tap_active[t];
-                const int tc3 = tap_coord[t];  // (t0, t1, t2) packed one byte each
+            for (int u = 0; u < 2; ++u) {
+                const int sg = sg0 + u < n_seg ? sg0 + u : n_seg - 1;
+                const int line = sg / n_sub, t2_lo = (sg - line * n_sub) * G;
+                const int t0l = line / g.K[1], t1l = line - t0l * g.K[1];
+                int cnt = g.K[2] - t2_lo;
+                if (cnt > G) cnt = G;
+                if (sg0 + u >= n_seg) cnt = 0;
+                seg_tap[u] = line * g.K[2] + t2_lo;
+                seg_cnt[u] = cnt;
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
-                    key[m][h] = -1;
-                    word[m][h] = 0;
-                    const int q0 = sc[h][0] + (tc3 & 255) - g.H[0], q1 = sc[h][1] + ((tc3 >> 8) & 255) - g.H[1],
-                              q2 = sc[h][2] + (tc3 >> 16) - g.H[2];
-                    if (live && h * 64 + lane < nrows && site_in_grid(g, b, q0, q1, q2)) {
-                        key[m][h] = (long long)b * g.Npad + lin_of(g, q0, q1, q2);
-                        word[m][h] = occ[key[m][h] >> 6];
-                    }
+#pragma unroll
+                    for (int k = 0; k < G; ++k) nbr[u][k][h] = 0xffffffffu;
+                    lookup_line(g, occ, occ_prefix, nnz_in, cnt > 0 && h * 64 + lane < nrows, b, sc[h][0], sc[h][1],
+                                sc[h][2], t0l, t1l, t2_lo, cnt, tap_active + seg_tap[u],
+                                [&](int k, int n) { nbr[u][k][h] = (unsigned)n; });
                 }
             }
-#pragma unroll
-            for (int m = 0; m < G; ++m)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    unsigned n = 0xffffffffu;
-                    const int bit = (int)(key[m][h] & 63);
-                    if (key[m][h] >= 0 && ((word[m][h] >> bit) & 1ull)) {
-                        const long long row = (long long)occ_prefix[key[m][h] >> 6] +
-                                              __popcll(word[m][h] & ((1ull << bit) - 1ull));
-                        if (row < nnz_in) n = (unsigned)row;
-                    }
-                    nbr[m][h] = n;
-                }
             // ---- pack: each tap's present pairs in ascending output row, padded to whole blocks of 16 with
             //      entries that point at the dummy accumulator row
 #pragma unroll
-            for (int m = 0; m < G; ++m) {
-                const unsigned long long m0 = __ballot(nbr[m][0] != 0xffffffffu),
-                                         m1 = __ballot(nbr[m][1] != 0xffffffffu);
-                const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
-                const int nblk = (cnt + 15) >> 4;
-                unsigned* pl = pairs + (size_t)blk * 16;
-                if (nbr[m][0] != 0xffffffffu)
-                    pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[m][0];
-                if (nbr[m][1] != 0xffffffffu)
-                    pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[m][1];
-                if (lane < 16 && cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
-                if (lane < nblk) block_tap[blk + lane] = (unsigned short)((t0 + m) | (lane << 8));
-                // optional: where each tap's blocks start within the tile (entry T = the tile's block count)
-                if (tap_first && lane == 0 && t0 + m < g.T)
-                    tap_first[(size_t)tile * (g.T + 1) + t0 + m] = (unsigned short)(blk - (unsigned)tile_base);
-                blk += (unsigned)nblk;
-            }
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int m = 0; m < G; ++m) {
+                    if (m >= seg_cnt[u]) continue;
+                    const int t = seg_tap[u] + m;
+                    const unsigned long long m0 = __ballot(nbr[u][m][0] != 0xffffffffu),
+                                             m1 = __ballot(nbr[u][m][1] != 0xffffffffu);
+                    const int c0 = __popcll(m0), cnt = c0 + __popcll(m1);
+                    const int nblk = (cnt + 15) >> 4;
+                    unsigned* pl = pairs + (size_t)blk * 16;
+                    if (nbr[u][m][0] != 0xffffffffu)
+                        pl[__popcll(m0 & lt_mask)] = ((unsigned)lane << kPairRowShift) | nbr[u][m][0];
+                    if (nbr[u][m][1] != 0xffffffffu)
+                        pl[c0 + __popcll(m1 & lt_mask)] = ((unsigned)(64 + lane) << kPairRowShift) | nbr[u][m][1];
+                    if (lane < 16 && cnt + lane < nblk * 16) pl[cnt + lane] = kPadPair;
+                    if (lane < nblk) block_tap[blk + lane] = (unsigned short)(t | (lane << 8));
+                    // optional: where each tap's blocks start within the tile (entry T = the tile's block count)
+                    if (tap_first && lane == 0) tap_first[(size_t)tile * (g.T + 1) + t] = (unsigned short)(blk - (unsigned)tile_base);
+                    blk += (unsigned)nblk;
+                }
         }
         if (lane == 0) {
             tile_hdr[tile] = make_uint2((unsigned)tile_base, blk - (unsigned)tile_base);
