@@ -119,12 +119,27 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
                         } else {
                             xv[0] = x[ic0];
                         }
+                        // two channels' weights (64 scalar registers) in flight at a time: more would spill
 #pragma unroll
-                        for (int j = 0; j < CH; ++j) {
-                            const double xd = (double)xv[j];
-                            const double* __restrict__ wr = wt + (size_t)(ic0 + j) * c_out_pad;
+                        for (int j2 = 0; j2 < CH; j2 += 2) {
+                            const double* __restrict__ wr = wt + (size_t)(ic0 + j2) * c_out_pad;
+                            double wa[kOcBlock], wb[kOcBlock];
 #pragma unroll
-                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                            for (int o = 0; o < kOcBlock; ++o) wa[o] = wr[o];
+                            if constexpr (CH > 1) {
+#pragma unroll
+                                for (int o = 0; o < kOcBlock; ++o) wb[o] = wr[c_out_pad + o];
+                            }
+                            const double xa = (double)xv[j2];
+#pragma unroll
+                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xa, wa[o], acc[o]);
+                            if constexpr (CH > 1) {
+                                const double xb = (double)xv[j2 + 1];
+#pragma unroll
+                                for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xb, wb[o], acc[o]);
+                            }
+                            // keeps the compiler from hoisting the next pair's scalar loads above this point
+                            asm volatile("" ::: "memory");
                         }
                     }
                 }
