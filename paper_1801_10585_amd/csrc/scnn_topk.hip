@@ -824,6 +824,130 @@ hipError_t launch_finish(const Counters* ctr, int which_rows, long long aux_imm,
     return hipGetLastError();
 }
 
+// The same pass for narrow layers (at most 16 channels, the widths of the paper's own networks): a tile of 128 rows
+// holds too little data to pay for a ticket, a look-back and three barriers, so a workgroup takes kNarrowTiles
+// consecutive tiles per ticket (a "super-tile", one status word in tile_state) and a thread owns whole rows: it reads
+// a row's channels from the planar tile (coalesced across the wave), decides them, and writes the row itself.
+constexpr int kNarrowTiles = 8;  // tiles per ticket; 4 rows per thread
+template <int CMAX>
+__global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int channels, int mode, int relu,
+                                                                const int* __restrict__ cand_start,
+                                                                const int* __restrict__ tile_start,
+                                                                const unsigned* __restrict__ cand_lin,
+                                                                const float* __restrict__ resp,
+                                                                const ColState* __restrict__ cols,
+                                                                unsigned long long* tile_state, Counters* ctr,
+                                                                int32_t* __restrict__ out_coords,
+                                                                float* __restrict__ out_feats, long long out_capacity,
+                                                                long long* __restrict__ nnz_out, long long aux_imm,
+                                                                int aux_is_cand) {
+    constexpr int RPT = kNarrowTiles * kTileRows / 256;  // rows per thread
+    __shared__ int s_cnt[RPT * 4];                       // kept rows of each (row group, wave)
+    __shared__ int s_ticket;
+    __shared__ long long s_base;
+    const int n_tiles = (int)ctr->n_tiles;
+    // tiles per ticket: as many as keep about a thousand tickets in the launch, so that a small layer still spreads
+    // over the chip (1, 2, 4 or kNarrowTiles)
+    int tps = 1;
+    while (tps < kNarrowTiles && n_tiles > 1024 * tps) tps *= 2;
+    const int n_super = (n_tiles + tps - 1) / tps;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool vec4 = (channels & 3) == 0 && ((size_t)out_feats & 15) == 0;
+
+    for (;;) {
+        __syncthreads();  // the previous super-tile's readers of s_ticket / s_base / s_cnt are done
+        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        __syncthreads();
+        const int st = s_ticket;
+        if (st >= n_super) break;
+        float v[RPT][CMAX];
+        bool keep_row[RPT];
+        int row_b[RPT], row_first[RPT];
+        // row q of the thread: tile st * tps + (q * 256 + threadIdx.x) / 128, local row (.. & 127); the 64
+        // rows of a wave always lie in one tile
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            const int e = q * 256 + threadIdx.x;
+            const int tile = st * tps + (e >> 7), r = e & (kTileRows - 1);
+            keep_row[q] = false;
+            row_b[q] = 0;
+            row_first[q] = -1;
+            if ((e >> 7) < tps && tile < n_tiles) {  // (uniform in the wave)
+                const int b = sample_of_tile(tile_start, g.batch, tile);
+                const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
+                int nrows = cand_start[b + 1] - first;
+                if (nrows > kTileRows) nrows = kTileRows;
+                const unsigned pos = (unsigned)(tile - tile_start[b]) * kTileRows + (unsigned)r;
+                row_b[q] = b;
+                if (r < nrows) row_first[q] = first + r;
+                const float* seg = resp + (size_t)tile * channels * kTileRows + r;
+#pragma unroll
+                for (int c = 0; c < CMAX; ++c)
+                    if (c < channels) v[q][c] = seg[(size_t)c * kTileRows];
+                bool any = false;
+#pragma unroll
+                for (int c = 0; c < CMAX; ++c) {
+                    if (c < channels) {
+                        const ColState* cs = cols + (size_t)b * channels + c;
+                        const unsigned tau = cs->tau, cut = cs->cut;
+                        const float x = v[q][c];
+                        const unsigned key = score_key(x, mode);
+                        bool keep = key > (pos <= cut ? tau - (tau != 0u ? 1u : 0u) : tau);
+                        if (relu) keep = keep && (x > 0.0f);
+                        keep = keep && r < nrows;
+                        v[q][c] = keep ? x : 0.0f;
+                        any |= keep;
+                    }
+                }
+                keep_row[q] = any;
+            }
+        }
+        unsigned long long ball[RPT];
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            ball[q] = __ballot(keep_row[q]);
+            if (lane == 0) s_cnt[q * 4 + wave] = __popcll(ball[q]);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            int total = 0;
+#pragma unroll
+            for (int i = 0; i < RPT * 4; ++i) total += s_cnt[i];
+            const long long base = lookback_wave(tile_state, st, total, ctr);
+            if (lane == 0) {
+                if (st == n_super - 1)
+                    __hip_atomic_store(&ctr->n_rows, base + total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                s_base = base;
+            }
+        }
+        __syncthreads();
+        const long long base = s_base;
+#pragma unroll
+        for (int q = 0; q < RPT; ++q) {
+            int before = 0;  // kept rows of the super-tile before this wave's group (groups ascend with q, then wave)
+            for (int i = 0; i < q * 4 + wave; ++i) before += s_cnt[i];
+            const long long o = base + before + __popcll(ball[q] & lt_mask);
+            if (keep_row[q] && o < out_capacity) {
+                int c0, c1, c2;
+                site_of(g, cand_lin[row_first[q]], c0, c1, c2);
+                store_site(g, out_coords + o * (1 + g.ndim), row_b[q], c0, c1, c2);
+                float* dst = out_feats + o * channels;
+                if (vec4) {
+#pragma unroll
+                    for (int c = 0; c < CMAX; c += 4)
+                        if (c < channels) *(float4*)(dst + c) = make_float4(v[q][c], v[q][c + 1], v[q][c + 2], v[q][c + 3]);
+                } else {
+#pragma unroll
+                    for (int c = 0; c < CMAX; ++c)
+                        if (c < channels) dst[c] = v[q][c];
+                }
+            }
+        }
+    }
+    finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
+}
+
 hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
@@ -831,7 +955,14 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
     // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
-    if (channels <= 64)
+#define SCNN_NARROW_CASE(CMAX_)                                                                                   \
+    hipLaunchKernelGGL(k_select_write_narrow<CMAX_>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu, \
+                       cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,          \
+                       out_capacity, nnz_out, aux_imm, aux_is_cand)
+    if (channels <= 4) SCNN_NARROW_CASE(4);
+    else if (channels <= 8) SCNN_NARROW_CASE(8);
+    else if (channels <= 16) SCNN_NARROW_CASE(16);
+    else if (channels <= 64)
         hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
                            out_capacity, nnz_out, aux_imm, aux_is_cand);
@@ -839,6 +970,7 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
         hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
                            out_capacity, nnz_out, aux_imm, aux_is_cand);
+#undef SCNN_NARROW_CASE
     return hipGetLastError();
 }
 
