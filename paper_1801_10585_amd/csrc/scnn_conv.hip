@@ -372,7 +372,7 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
 }
 
 // Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
-constexpr long long kValuLatencyItems = 2048;
+constexpr long long kValuLatencyItems = 1024;
 
 hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                             long long nnz_in, const float* feats, int c_in, const double* wp, int c_out,
