@@ -828,8 +828,7 @@ hipError_t launch_finish(const Counters* ctr, int which_rows, long long aux_imm,
 // holds too little data to pay for a ticket, a look-back and three barriers, so a workgroup takes kNarrowTiles
 // consecutive tiles per ticket (a "super-tile", one status word in tile_state) and a thread owns whole rows: it reads
 // a row's channels from the planar tile (coalesced across the wave), decides them, and writes the row itself.
-constexpr int kNarrowTiles = 8;  // tiles per ticket; 4 rows per thread
-template <int CMAX>
+template <int CMAX, int kNarrowTiles /* tiles per ticket at most: rows per thread = kNarrowTiles / 2 */>
 __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int channels, int mode, int relu,
                                                                 const int* __restrict__ cand_start,
                                                                 const int* __restrict__ tile_start,
@@ -955,13 +954,14 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
     // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
-#define SCNN_NARROW_CASE(CMAX_)                                                                                   \
-    hipLaunchKernelGGL(k_select_write_narrow<CMAX_>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu, \
-                       cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,          \
+#define SCNN_NARROW_CASE(CMAX_, NT_)                                                                              \
+    hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, \
+                       relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,     \
                        out_capacity, nnz_out, aux_imm, aux_is_cand)
-    if (channels <= 4) SCNN_NARROW_CASE(4);
-    else if (channels <= 8) SCNN_NARROW_CASE(8);
-    else if (channels <= 16) SCNN_NARROW_CASE(16);
+    if (channels <= 4) SCNN_NARROW_CASE(4, 8);
+    else if (channels <= 8) SCNN_NARROW_CASE(8, 8);
+    else if (channels <= 16) SCNN_NARROW_CASE(16, 8);
+    else if (channels <= 32) SCNN_NARROW_CASE(32, 4);
     else if (channels <= 64)
         hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
