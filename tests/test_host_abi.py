@@ -75,6 +75,49 @@ def test_host_argument_checks():
     assert L.sparse_conv_fwd_max_rows(3, big, 1, 10, ks3) == -2
 
 
+def test_host_argument_checks_of_the_widening_entry_points():
+    L = scnn.load_library()
+    ext3, ks3 = _i32([8, 8, 8]), _i32([3, 3, 3])
+    fake = ctypes.c_void_p(256)
+    f64 = ctypes.c_double
+    # backward pass
+    assert L.sparse_conv_bwd_workspace(3, ext3, 2, 10, 4, 4, ks3, 20) > 0
+    assert L.sparse_conv_bwd_workspace(3, ext3, 2, 10, 0, 4, ks3, 20) == 0
+    assert L.sparse_conv_bwd_workspace(3, ext3, 2, 10, 4, 4, _i32([3, 4, 3]), 20) == 0
+    rc = L.sparse_conv_bwd(3, ext3, 2, fake, fake, 10, 4, ks3, fake, 4, fake, fake, 20, fake, fake, fake, fake, 16, None)
+    assert rc == -3 and b"workspace" in L.scnn_last_error()
+    rc = L.sparse_conv_bwd(3, ext3, 2, fake, fake, 10, 4, ks3, None, 4, fake, fake, 20, fake, fake, fake, fake, 1 << 30,
+                           None)
+    assert rc == -1
+    rc = L.sparse_conv_bwd(3, ext3, 2, fake, fake, 10, 4, ks3, fake, 4, None, fake, 20, fake, fake, fake, fake, 1 << 30,
+                           None)
+    assert rc == -1 and b"gradient" in L.scnn_last_error()
+    # chained forward: the device-resident count is mandatory
+    rc = L.sparse_conv_fwd_chained(3, ext3, 2, fake, fake, 10, None, 4, ks3, fake, None, 4, 0.5, 0, 0, fake, fake, 10, 0,
+                                   fake, fake, 1 << 30, None)
+    assert rc == -1 and b"nnz_in_dev" in L.scnn_last_error()
+    rc = L.sparse_conv_fwd_chained(3, ext3, 2, fake, fake, 10, fake, 4, ks3, fake, None, 4, 1.5, 0, 0, fake, fake, 10, 0,
+                                   fake, fake, 1 << 30, None)
+    assert rc == -1 and b"rho_up" in L.scnn_last_error()
+    # sparseToDense
+    assert L.sparse_to_dense(3, ext3, 2, fake, fake, 10, None, 0, fake, None) == -1
+    assert L.sparse_to_dense(3, ext3, 2, fake, fake, 10, None, 4, ctypes.c_void_p(260), None) == -1
+    assert b"aligned" in L.scnn_last_error()
+    assert L.sparse_to_dense(3, ext3, 2, fake, fake, 10, None, 4, None, None) == -1
+    # regulariser and pruning
+    assert L.density_regulariser_workspace() >= 256
+    args = [fake, 10, None, 4, 1000]
+    tail = [fake, 100, fake, fake, fake, ctypes.c_size_t(1 << 20), None]
+    assert L.density_regulariser(*args, f64(1.5), f64(0.1), f64(1.0), f64(1.0), f64(1e-3), *tail) == -1
+    assert L.density_regulariser(*args, f64(0.5), f64(-0.1), f64(1.0), f64(1.0), f64(1e-3), *tail) == -1
+    assert L.density_regulariser(fake, 10, None, 4, 0, f64(0.5), f64(0.1), f64(1.0), f64(1.0), f64(1e-3), *tail) == -1
+    assert L.density_regulariser(*args, f64(0.5), f64(0.1), f64(1.0), f64(1.0), f64(1e-3), fake, 100, fake, fake, fake,
+                                 ctypes.c_size_t(8), None) == -3
+    assert L.prune_weights(fake, fake, 10, ctypes.c_float(-1.0), fake, None) == -1
+    assert L.prune_weights(None, fake, 10, ctypes.c_float(0.1), fake, None) == -1
+    assert L.prune_weights(fake, fake, 10, ctypes.c_float(0.1), None, None) == -1
+
+
 def test_mac_count_matches_oracle_loop_count():
     from workloads import make_config
     wl = make_config(2, r=16, batch=2)
