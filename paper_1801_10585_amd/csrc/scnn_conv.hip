@@ -28,7 +28,8 @@ constexpr int kOcBlock = 16;   // output channels accumulated per thread
 // Streaming form of the vector kernel, for layers with many more work items than workgroup slots: little shared
 // memory and moderate registers, so that many waves per compute unit hide each other's memory latency.  A thread
 // walks its taps; per tap it fetches CH input channels with one vector load and takes the weights through scalar
-// loads.  The neighbour look-ups of a tap chunk are issued four at a time with no branch between the loads.
+// loads, two channels' worth at a time.  Neighbour rows are looked up per filter line (adjacent sites share one
+// pair of bitmap words).
 // Work item = (tile, block of 32 output channels); thread = (row, 16 channels).  When the block holds only 16
 // channels the second half of the workgroup takes every other tap (partial sums added through LDS, fixed order).
 // Runs only when the layer has more than `min_items` work items (a device-side count).
@@ -187,10 +188,10 @@ __global__ __launch_bounds__(256) void k_conv_valu_empty(int c_out, const Counte
 // other tap of the same 16 channels instead and the two partial sums are added through LDS (even taps + odd taps,
 // a fixed order).
 // What bounds a small layer is memory latency, not arithmetic, so nothing in the inner loop waits on global memory:
-// the neighbour rows of a chunk of taps are looked up with all bitmap and prefix loads of a batch in flight at once,
-// and the neighbours' values are gathered into LDS cooperatively (CH channels of TG taps at a time, every load
-// independent of every other), together with the group's weights, before the multiply-add phase reads both from
-// there.
+// the neighbour rows of a chunk of taps are looked up per filter line (adjacent sites share one pair of bitmap
+// words), and the neighbours' values are gathered into LDS cooperatively (CH channels of TG taps at a time, every
+// load independent of every other), together with the group's weights, one round ahead of the multiply-add phase
+// that reads both from there.
 template <int CH /* input channels per gather: the largest of 8, 4, 2, 1 that divides C_in */>
 __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long long* __restrict__ occ,
                                                    const unsigned* __restrict__ occ_prefix, long long nnz_in,
