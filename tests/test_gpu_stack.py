@@ -161,3 +161,33 @@ def test_chain_captured_in_a_graph_replays_correctly():
             ext2 = pooled_extent(ext2)
     want = host(scnn.sparse_to_dense(ext2, wl.batch, cc, ff))
     assert np.array_equal(host(dense), want), "replay with a new device-resident row count"
+
+
+def test_chained_layer_ignores_rows_past_the_device_count_on_the_matrix_core_path():
+    """Wide channels (matrix-core kernels) through the chained entry point, with input arrays twice as long as the
+    device-resident row count says and garbage behind it: the result must be the plain call's."""
+    from workloads import make_config
+    wl = make_config(4, r=48, batch=2)
+    L = wl.layers[0]
+    rows = wl.coords.shape[0]
+    rng = np.random.default_rng(5)
+    pad_c = np.full((rows, 4), 7, dtype=np.int32)                    # same site over and over: never indexed
+    pad_f = rng.normal(size=(rows, L.c_in)).astype(np.float32)
+    cin, fin = dev(np.concatenate([wl.coords, pad_c])), dev(np.concatenate([wl.feats, pad_f]))
+    lay = scnn.ChainedLayer(wl.extent, wl.batch, 2 * rows, L.c_in, L.ksize, dev(wl.filters[0]), rho_up=L.rho_up,
+                            relu=True)
+    n_dev = torch.tensor([rows], dtype=torch.int64, device="cuda:0")
+    oc, of, nnz = lay(cin, fin, n_dev)
+    nnz = host(nnz)
+    assert int(nnz[2]) == 0
+    rc, rf, rn = scnn.sparse_conv_fwd(wl.extent, wl.batch, dev(wl.coords), dev(wl.feats), L.ksize, dev(wl.filters[0]),
+                                      rho_up=L.rho_up, relu=True)
+    n = int(nnz[0])
+    assert n == rc.shape[0] and int(nnz[1]) == int(rn[1])
+    assert np.array_equal(host(oc)[:n], host(rc))
+    # the matrix-core kernel adds its fp64 partial sums in no fixed order: values agree to the last bits only
+    assert np.allclose(host(of)[:n], host(rf), rtol=1e-6, atol=1e-7)
+    # a count larger than the arrays is clamped to their capacity (here: the garbage rows then take part, flagged)
+    n_dev.fill_(10 * rows)
+    _, _, nnz2 = lay(cin, fin, n_dev)
+    assert int(host(nnz2)[2]) & (scnn.FLAG_UNSORTED | scnn.FLAG_BAD_COORD)
