@@ -158,25 +158,43 @@ __global__ __launch_bounds__(256) void k_bwd_filter_valu(Geom g, const unsigned 
         }
         for (int tc = t_lo; tc <= t_hi; tc += kBwdTapChunk) {
             __syncthreads();
-            for (int i = threadIdx.x; i < kTileRows * kBwdTapChunk; i += 256) {
-                const int tt = i & (kBwdTapChunk - 1), r = i >> 5;
-                const int t = tc + tt;
-                int n = -1;
-                // a tap whose weights are all zero is masked out of bp_filter anyway
-                if (t <= t_hi && r < nrows && tap_active[g.T - 1 - t]) {
-                    const int t2 = t % g.K[2], t1 = (t / g.K[2]) % g.K[1], t0 = t / (g.K[2] * g.K[1]);
-                    n = lookup_row(g, occ, occ_prefix, g_rows, b, s_site[r][0] - (t0 - g.H[0]),
-                                   s_site[r][1] - (t1 - g.H[1]), s_site[r][2] - (t2 - g.H[2]));
+            // The gradient row of (row, tap t) sits at site - delta_t = site + delta of the mirrored tap T-1-t, so the
+            // look-ups run over the mirrored (adjoint) tap indices, per filter line: the taps of a line look at
+            // adjacent sites and share one pair of bitmap words.  tap_active is in adjoint order already.
+            {
+                const int t_last = (tc + kBwdTapChunk - 1) < t_hi ? (tc + kBwdTapChunk - 1) : t_hi;
+                const int a_lo = g.T - 1 - t_last, a_hi = g.T - 1 - tc;  // adjoint taps [a_lo, a_hi]
+                const int l_first = a_lo / g.K[2];
+                const int n_seg = a_hi / g.K[2] - l_first + 1;
+                for (int i = threadIdx.x; i < kTileRows * n_seg; i += 256) {
+                    const int r = i & (kTileRows - 1), l = l_first + (i >> 7);
+                    const int aa = a_lo > l * g.K[2] ? a_lo : l * g.K[2];
+                    const int ab = (a_hi + 1) < (l + 1) * g.K[2] ? (a_hi + 1) : (l + 1) * g.K[2];
+                    const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+                    int* dst = &s_nbr[r][0];
+                    lookup_line(g, occ, occ_prefix, g_rows, r < nrows, b, s_site[r][0], s_site[r][1], s_site[r][2], t0,
+                                t1, aa - l * g.K[2], ab - aa, tap_active + aa,
+                                [&](int k, int n) { dst[g.T - 1 - (aa + k) - tc] = n; });
                 }
-                s_nbr[r][tt] = n;
             }
             __syncthreads();
             if (valid && t_e >= tc && t_e < tc + kBwdTapChunk) {
                 const int tt = t_e - tc;
-                for (int r = 0; r < nrows; ++r) {
-                    const int n = s_nbr[r][tt];
-                    if (n < 0) continue;
-                    acc = fma((double)x[(size_t)(first + r) * c_in + ic], (double)gf[(size_t)n * c_out + oc], acc);
+                // eight rows at a time, their loads independent of one another; the sum keeps the row order
+                for (int r0 = 0; r0 < nrows; r0 += 8) {
+                    float xv[8], gv[8];
+                    bool on[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const int r = r0 + u;
+                        const int n = r < nrows ? s_nbr[r][tt] : -1;
+                        on[u] = n >= 0;
+                        xv[u] = x[(size_t)(first + (r < nrows ? r : 0)) * c_in + ic];
+                        gv[u] = on[u] ? gf[(size_t)n * c_out + oc] : 0.0f;  // (no gradient row: nothing is read)
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (on[u]) acc = fma((double)xv[u], (double)gv[u], acc);
                 }
             }
         }
