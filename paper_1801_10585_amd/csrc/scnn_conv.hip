@@ -293,6 +293,9 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                     } else {
                         xv[m][0] = xp[0];
                     }
+                    // a site without this neighbour multiplies zeros: the multiply-add phase has no per-row branch
+#pragma unroll
+                    for (int j = 0; j < CH; ++j) xv[m][j] = n < 0 ? 0.0f : xv[m][j];
                 }
                 // the group's weights: element e = (hb, tg * CH + j, o) <- w[tap tg][ic0 + j][16 * hb + o of the chunk]
 #pragma unroll
@@ -330,17 +333,58 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                 commit();
                 __syncthreads();
                 if (q + 1 < n_rounds) fetch(q + 1);
-                // ---- multiply-add: values and weights from LDS (the weights are a broadcast read)
-                if (oc0 < c_out_pad && row < nrows) {
+                // ---- multiply-add: values and weights from LDS (the weights are a broadcast read).  A tap is skipped
+                //      when no row of the wave has that neighbour; the weights of input channel j + 1 are read while
+                //      channel j multiplies (the fences keep the compiler from sinking the reads to their uses).
+                if (oc0 < c_out_pad) {
                     const int hb = split ? 0 : half;
+                    unsigned live = 0;
+#pragma unroll
+                    for (int tg = 0; tg < TG; ++tg) {
+                        const bool has = tg < tg_n && s_nbr[row][tg0 + tg] >= 0;
+                        if (__ballot(has) != 0ull) live |= 1u << tg;
+                    }
+                    auto read_w = [&](double (&dst)[kOcBlock], int tj) {
+                        const double2* p = reinterpret_cast<const double2*>(&s_w[hb][tj][0]);
+#pragma unroll
+                        for (int o = 0; o < kOcBlock / 2; ++o) {
+                            const double2 v = p[o];
+                            dst[2 * o] = v.x;
+                            dst[2 * o + 1] = v.y;
+                        }
+                    };
+                    auto mul_add = [&](float x, const double (&wr)[kOcBlock]) {
+                        const double xd = (double)x;
+#pragma unroll
+                        for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                    };
                     for (int tg = split ? half : 0; tg < tg_n; tg += split ? 2 : 1) {
-                        if (s_nbr[row][tg0 + tg] < 0) continue;
+                        if (!((live >> tg) & 1u)) continue;
+                        float xf[CH];
+                        if constexpr (CH >= 4) {
 #pragma unroll
-                        for (int j = 0; j < CH; ++j) {
-                            const double xd = (double)s_x[row][tg * CH + j];
-                            const double* wr = &s_w[hb][tg * CH + j][0];
+                            for (int j = 0; j < CH; j += 4) {
+                                const float4 u = *reinterpret_cast<const float4*>(&s_x[row][tg * CH + j]);
+                                xf[j] = u.x; xf[j + 1] = u.y; xf[j + 2] = u.z; xf[j + 3] = u.w;
+                            }
+                        } else {
 #pragma unroll
-                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                            for (int j = 0; j < CH; ++j) xf[j] = s_x[row][tg * CH + j];
+                        }
+                        double wa[kOcBlock], wb[kOcBlock];
+                        read_w(wa, tg * CH);
+#pragma unroll
+                        for (int j = 0; j < CH; j += 2) {
+                            if (j + 1 < CH) read_w(wb, tg * CH + j + 1);
+                            __builtin_amdgcn_sched_barrier(0);
+                            mul_add(xf[j], wa);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (j + 1 < CH) {
+                                if (j + 2 < CH) read_w(wa, tg * CH + j + 2);
+                                __builtin_amdgcn_sched_barrier(0);
+                                mul_add(xf[j + 1], wb);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
                         }
                     }
                 }
@@ -372,8 +416,237 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
     }
 }
 
+// The same kernel shape for the smallest layers (at most a few hundred tiles: the deep, pooled layers of the paper's
+// networks), where 128-row work items would leave most of the chip idle.  Work item = (quarter of a tile = 32 rows,
+// block of 32 output channels).  The four waves of the workgroup share the taps (wave w takes taps w, w + 4, ...);
+// the two halves of a wave take the two 16-channel blocks, or, when there is only one, every other input channel.
+// A round covers all taps of the chunk for CH input channels, so that a 3^d filter over 24 channels takes three
+// rounds; the eight partial sums per output are added through LDS in a fixed order.
+template <int CH /* 8, 4 or 2 */>
+__global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned long long* __restrict__ occ,
+                                                         const unsigned* __restrict__ occ_prefix, long long nnz_in,
+                                                         const float* __restrict__ feats, int c_in,
+                                                         const double* __restrict__ wp, int c_out, int c_out_pad,
+                                                         const float* __restrict__ bias,
+                                                         const int* __restrict__ tap_active,
+                                                         const unsigned* __restrict__ cand_lin,
+                                                         const int* __restrict__ cand_start,
+                                                         const int* __restrict__ tile_start,
+                                                         const Counters* __restrict__ ctr, float* __restrict__ resp) {
+    constexpr int R = 32;                    // rows per work item
+    constexpr int Q = kTileRows / R;         // work items per tile and channel block
+    constexpr int XS = kTapChunk * CH + 4;   // row stride of the gathered values
+    constexpr int GB = (R * kTapChunk) / 256;                     // (row, tap) pairs a thread gathers per round
+    constexpr int WB = (2 * kTapChunk * CH * kOcBlock) / 256;     // weights a thread stages per round
+    __shared__ int s_nbr[R][kTapChunk + 1];
+    __shared__ int s_site[R][3];
+    __shared__ __align__(16) float s_x[R][XS];
+    // the round's weights, per 16-channel block; after the last round the same memory holds the partial sums of
+    // the eight (wave, half) pairs
+    constexpr int kWElems = 2 * kTapChunk * CH * kOcBlock, kRedElems = 8 * R * (kOcBlock + 1);
+    __shared__ __align__(16) double s_wr[kWElems > kRedElems ? kWElems : kRedElems];
+    double (*s_w)[kTapChunk * CH][kOcBlock] = reinterpret_cast<double (*)[kTapChunk * CH][kOcBlock]>(&s_wr[0]);
+    double (*s_red)[R][kOcBlock + 1] = reinterpret_cast<double (*)[R][kOcBlock + 1]>(&s_wr[0]);
+
+    const int n_tiles = (int)ctr->n_tiles;
+    const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
+    const long long n_items = (long long)n_tiles * n_chunks * Q;
+    const int row = threadIdx.x & (R - 1);
+    const int sl = threadIdx.x >> 5;          // (wave, half of the wave)
+    const int lh = sl & 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    for (long long item = blockIdx.x; item < n_items; item += gridDim.x) {
+        const int quarter = (int)(item % Q);
+        const long long tc_item = item / Q;
+        const int tile = (int)(tc_item / n_chunks);
+        const int chunk = (int)(tc_item - (long long)tile * n_chunks);
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows + quarter * R;
+        int nrows = cand_start[b + 1] - first;
+        if (nrows > R) nrows = R;
+        if (nrows < 0) nrows = 0;
+        // the chunk's second 16-channel block does not exist: the halves of a wave share the input channels
+        const bool split = chunk * 2 * kOcBlock + kOcBlock >= c_out_pad;
+        const int hb = split ? 0 : lh;
+
+        double acc[kOcBlock];
+#pragma unroll
+        for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
+
+        __syncthreads();  // previous item's readers of the shared arrays are done
+        if (nrows > 0) {  // (uniform) a quarter without rows only writes its zeros
+            if (threadIdx.x < R) {
+                int c0 = 0, c1 = 0, c2 = 0;
+                if (threadIdx.x < nrows) site_of(g, cand_lin[first + threadIdx.x], c0, c1, c2);
+                s_site[threadIdx.x][0] = c0;
+                s_site[threadIdx.x][1] = c1;
+                s_site[threadIdx.x][2] = c2;
+            }
+            for (int tc = 0; tc < g.T; tc += kTapChunk) {
+                const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
+                const int n_rounds = c_in / CH;
+                float xv[GB][CH];
+                double wv[WB];
+                // the round's weights: element e = (block hb, tap tg, channel j, o) <- w[tc + tg][ic0 + j][16 hb + o]
+                auto fetch_w = [&](int q) {
+                    const int ic0 = q * CH;
+#pragma unroll
+                    for (int m = 0; m < WB; ++m) {
+                        const int e = threadIdx.x + m * 256;
+                        const int o = e & (kOcBlock - 1), tj = (e >> 4) % (kTapChunk * CH);
+                        const int hbw = e / (kTapChunk * CH * kOcBlock);
+                        const int tg = tj / CH, j = tj - tg * CH;
+                        const int oc = chunk * 2 * kOcBlock + hbw * kOcBlock + o;
+                        const bool ok = tg < tmax && oc < c_out_pad;
+                        const size_t at = ok ? ((size_t)(tc + tg) * c_in + ic0 + j) * c_out_pad + oc : 0;
+                        const double v = wp[at];
+                        wv[m] = ok ? v : 0.0;
+                    }
+                };
+                // the neighbours' values; a site without the neighbour multiplies zeros
+                auto fetch_x = [&](int q) {
+                    const int ic0 = q * CH;
+#pragma unroll
+                    for (int m = 0; m < GB; ++m) {
+                        const int e = threadIdx.x + m * 256;
+                        const int r = e & (R - 1), tg = e >> 5;
+                        const int n = (tg < tmax) ? s_nbr[r][tg] : -1;
+                        const float* __restrict__ xp = feats + (size_t)(n < 0 ? 0 : n) * c_in + ic0;
+                        if constexpr (CH == 8) {
+                            const float4 u = *(const float4*)xp, v = *(const float4*)(xp + 4);
+                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                            xv[m][4] = v.x; xv[m][5] = v.y; xv[m][6] = v.z; xv[m][7] = v.w;
+                        } else if constexpr (CH == 4) {
+                            const float4 u = *(const float4*)xp;
+                            xv[m][0] = u.x; xv[m][1] = u.y; xv[m][2] = u.z; xv[m][3] = u.w;
+                        } else {
+                            const float2 u = *(const float2*)xp;
+                            xv[m][0] = u.x; xv[m][1] = u.y;
+                        }
+#pragma unroll
+                        for (int j = 0; j < CH; ++j) xv[m][j] = n < 0 ? 0.0f : xv[m][j];
+                    }
+                };
+                auto commit = [&]() {
+#pragma unroll
+                    for (int m = 0; m < GB; ++m) {
+                        const int e = threadIdx.x + m * 256;
+                        const int r = e & (R - 1), tg = e >> 5;
+#pragma unroll
+                        for (int j = 0; j < CH; ++j) s_x[r][tg * CH + j] = xv[m][j];
+                    }
+#pragma unroll
+                    for (int m = 0; m < WB; ++m) (&s_w[0][0][0])[threadIdx.x + m * 256] = wv[m];
+                };
+                fetch_w(0);  // does not depend on the neighbours: in flight during the look-ups
+                __syncthreads();  // s_site written; the previous chunk's readers of s_nbr are done
+                {
+                    const int l_first = tc / g.K[2];
+                    const int n_seg = (tc + tmax - 1) / g.K[2] - l_first + 1;
+                    for (int i = threadIdx.x; i < R * n_seg; i += 256) {
+                        const int r = i & (R - 1), l = l_first + (i >> 5);
+                        const int ta = tc > l * g.K[2] ? tc : l * g.K[2];
+                        const int tb = (tc + tmax) < (l + 1) * g.K[2] ? (tc + tmax) : (l + 1) * g.K[2];
+                        const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+                        int* dst = &s_nbr[r][ta - tc];
+                        lookup_line(g, occ, occ_prefix, nnz_in, r < nrows, b, s_site[r][0], s_site[r][1], s_site[r][2],
+                                    t0, t1, ta - l * g.K[2], tb - ta, tap_active + ta,
+                                    [&](int k, int n) { dst[k] = n; });
+                    }
+                }
+                __syncthreads();  // s_nbr complete
+                fetch_x(0);
+                // taps of the chunk that some row of this wave has
+                unsigned live = 0;
+                for (int tg = wave; tg < tmax; tg += 4)
+                    if (__ballot(s_nbr[row][tg] >= 0) != 0ull) live |= 1u << tg;
+                for (int q = 0; q < n_rounds; ++q) {
+                    __syncthreads();  // the previous round's readers of s_x / s_w are done
+                    commit();
+                    __syncthreads();
+                    if (q + 1 < n_rounds) {
+                        fetch_w(q + 1);
+                        fetch_x(q + 1);
+                    }
+                    // ---- multiply-add, weights of the next input channel read while this one multiplies
+                    auto read_w = [&](double (&dst)[kOcBlock], int tj) {
+                        const double2* p = reinterpret_cast<const double2*>(&s_w[hb][tj][0]);
+#pragma unroll
+                        for (int o = 0; o < kOcBlock / 2; ++o) {
+                            const double2 v = p[o];
+                            dst[2 * o] = v.x;
+                            dst[2 * o + 1] = v.y;
+                        }
+                    };
+                    auto mul_add = [&](float x, const double (&wr)[kOcBlock]) {
+                        const double xd = (double)x;
+#pragma unroll
+                        for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xd, wr[o], acc[o]);
+                    };
+                    // channel of step i: every channel, or every other one starting at this half's
+                    const int jmul = split ? 2 : 1, jadd = split ? lh : 0;
+                    const int n_steps = split ? CH / 2 : CH;
+                    for (int tg = wave; tg < tmax; tg += 4) {
+                        if (!((live >> tg) & 1u)) continue;
+                        double wa[kOcBlock], wb[kOcBlock];
+                        const float* xr = &s_x[row][tg * CH + jadd];
+                        read_w(wa, tg * CH + jadd);
+                        for (int i = 0; i < n_steps; i += 2) {
+                            const float xa = xr[i * jmul];
+                            float xb = 0.0f;
+                            if (i + 1 < n_steps) {
+                                xb = xr[(i + 1) * jmul];
+                                read_w(wb, tg * CH + (i + 1) * jmul + jadd);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                            mul_add(xa, wa);
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (i + 1 < n_steps) {
+                                if (i + 2 < n_steps) read_w(wa, tg * CH + (i + 2) * jmul + jadd);
+                                __builtin_amdgcn_sched_barrier(0);
+                                mul_add(xb, wb);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        // ---- the eight partial sums of an output, added in a fixed order (wave 0 .. 3, first half then second)
+        __syncthreads();  // the last round's weights have been read
+#pragma unroll
+        for (int o = 0; o < kOcBlock; ++o) s_red[sl][row][o] = acc[o];
+        __syncthreads();
+        {
+            const int per = split ? 2 : 4;  // channels per thread: 16 or 32 channels over 8 thread groups
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (i >= per) break;
+                const int c = sl * per + i;               // channel within the chunk
+                const int hbo = c >> 4, o = c & (kOcBlock - 1);
+                const int oc = chunk * 2 * kOcBlock + c;
+                if (oc >= c_out) continue;
+                double sum = 0.0;
+                if (split) {
+#pragma unroll
+                    for (int k = 0; k < 8; ++k) sum += s_red[k][row][o];
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) sum += s_red[2 * k + hbo][row][o];
+                }
+                float v = (row < nrows) ? (float)sum : 0.0f;
+                if (bias && v != 0.0f) v += bias[oc];
+                resp[((size_t)tile * c_out + oc) * kTileRows + quarter * R + row] = v;
+            }
+        }
+    }
+}
+
 // Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
 constexpr long long kValuLatencyItems = 1024;
+// Layers whose workspace holds at most this many work items (a bound the host knows) run the 32-row form.
+constexpr long long kValuSmallItems = 256;
 
 hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                             long long nnz_in, const float* feats, int c_in, const double* wp, int c_out,
@@ -395,6 +668,17 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
     else if (c_in % 2 == 0 && align_ch >= 2) ch = 2;
     const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
     const bool both = tiles_cap * n_chunks > kValuLatencyItems;
+    if (tiles_cap * n_chunks <= kValuSmallItems && ch >= 2) {  // cannot hold more than a few hundred tiles
+        const int blocks = (int)(tiles_cap * n_chunks * (kTileRows / 32));
+#define SCNN_VALU_SMALL(CH_)                                                                                         \
+    hipLaunchKernelGGL(k_conv_valu_small<CH_>, dim3(blocks), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats,     \
+                       c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr, resp)
+        if (ch == 8) SCNN_VALU_SMALL(8);
+        else if (ch == 4) SCNN_VALU_SMALL(4);
+        else SCNN_VALU_SMALL(2);
+#undef SCNN_VALU_SMALL
+        return hipGetLastError();
+    }
 #define SCNN_VALU_CASE(CH_)                                                                                          \
     do {                                                                                                             \
         if (both)                                                                                                    \

@@ -368,10 +368,110 @@ __global__ __launch_bounds__(kSideThreads) void k_side_select(ColState* __restri
     }
 }
 
+// The whole selection of a column in one workgroup, for columns that fit its registers (grids of at most 32768
+// sites per sample: the paper's networks from the second resolution level on).  The same digit passes as above,
+// 11 + 11 + 10 key bits and, when the equal entries do not all fit, 11 + 4 position bits, over keys read once;
+// no global histogram, no side buffer and one launch instead of three (what such a layer costs is launches).
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallPerThread = 32;
+constexpr long long kSmallColumn = (long long)kSmallThreads * kSmallPerThread;  // entries of a column at most
+
+__global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int channels,
+                                                                const int* __restrict__ tile_start,
+                                                                const float* __restrict__ resp, long long k,
+                                                                ColState* __restrict__ cols) {
+    __shared__ unsigned s_h[kHistBins];
+    __shared__ unsigned s_wave[4];
+    __shared__ int s_res[2];
+    __shared__ unsigned s_total;
+    const int col = blockIdx.x;
+    const int b = col / channels, oc = col - b * channels;
+    const int t0 = tile_start[b], t1 = tile_start[b + 1];
+    const unsigned n = (unsigned)(t1 - t0) * kTileRows;  // positions of the column (<= kSmallColumn, see the launcher)
+    if (threadIdx.x == 0) s_total = 0;
+    // entry u of the thread sits at position u * 1024 + thread: a wave reads 64 consecutive rows of one tile
+    unsigned key[kSmallPerThread];
+    unsigned mine = 0;
+#pragma unroll
+    for (int u = 0; u < kSmallPerThread; ++u) {
+        const unsigned i = (unsigned)u * kSmallThreads + threadIdx.x;
+        key[u] = 0u;
+        if (i < n)
+            key[u] = score_key(resp[((size_t)(t0 + (int)(i >> 7)) * channels + oc) * kTileRows + (i & 127u)], mode);
+        mine += key[u] != 0u ? 1u : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) mine += __shfl_xor(mine, d, 64);
+    if ((threadIdx.x & 63) == 0 && mine) atomicAdd(&s_total, mine);
+    // histogram of digit(key, position) over the entries that pass(key, position)
+    auto histogram = [&](auto pass, auto digit) {
+        for (int i = threadIdx.x; i < kHistBins; i += kSmallThreads) s_h[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kSmallPerThread; ++u) {
+            const unsigned i = (unsigned)u * kSmallThreads + threadIdx.x;
+            if (key[u] != 0u && pass(key[u], i)) atomicAdd(&s_h[digit(key[u], i)], 1u);
+        }
+        __syncthreads();
+    };
+    histogram([](unsigned, unsigned) { return true; }, [](unsigned x, unsigned) { return x >> 21; });
+    ColState st;
+    st.prefix = 0; st.tau = 0; st.k_rem = k; st.n_eq = 0; st.q = 0; st.n_nz = s_total; st.done = 1; st.cut = 0xffffffffu;
+    st.side_off = 0; st.side_fill = 0; st.pad = 0;
+    if (k <= 0) st.tau = 0xffffffffu;  // no key is stronger: nothing survives
+    if (k <= 0 || (long long)st.n_nz <= k) {  // or fewer entries than k: all survive (tau = 0)
+        if (threadIdx.x == 0) cols[col] = st;
+        return;
+    }
+    int bin;
+    unsigned before;
+    block_pick(s_h, k, true, s_wave, s_res, bin, before);  // key bits [31:21]
+    const unsigned prefix1 = (unsigned)bin;
+    long long k_rem = k - (long long)before;
+    histogram([prefix1](unsigned x, unsigned) { return (x >> 21) == prefix1; },
+              [](unsigned x, unsigned) { return (x >> 10) & 0x7ffu; });
+    block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);  // key bits [20:10]
+    const unsigned prefix2 = (prefix1 << 11) | (unsigned)bin;
+    k_rem -= (long long)before;
+    histogram([prefix2](unsigned x, unsigned) { return (x >> 10) == prefix2; },
+              [](unsigned x, unsigned) { return x & 0x3ffu; });
+    block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);  // key bits [9:0]
+    const unsigned tau = (prefix2 << 10) | (unsigned)bin;
+    const unsigned n_eq = s_h[bin];
+    const unsigned q = (unsigned)(k_rem - (long long)before);  // 1 <= q <= n_eq
+    __syncthreads();
+    unsigned cut = 0xffffffffu;
+    if (q < n_eq) {  // q-th smallest position among the entries equal to tau (positions have 15 bits)
+        histogram([tau](unsigned x, unsigned) { return x == tau; }, [](unsigned, unsigned i) { return i >> 4; });
+        block_pick(s_h, (long long)q, false, s_wave, s_res, bin, before);
+        const unsigned phi = (unsigned)bin;
+        const long long rank = (long long)q - (long long)before;
+        histogram([tau, phi](unsigned x, unsigned i) { return x == tau && (i >> 4) == phi; },
+                  [](unsigned, unsigned i) { return i & 15u; });
+        block_pick(s_h, rank, false, s_wave, s_res, bin, before);
+        cut = (phi << 4) | (unsigned)bin;
+    }
+    if (threadIdx.x == 0) {
+        st.prefix = prefix2 >> 11;
+        st.tau = tau;
+        st.k_rem = k_rem;
+        st.n_eq = n_eq;
+        st.q = q;
+        st.cut = cut;
+        cols[col] = st;
+    }
+}
+
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
                        const float* resp, ColState* cols, unsigned* hist, uint2* side, unsigned long long side_cap,
                        Counters* ctr, hipStream_t s) {
     const int ncols = g.batch * channels;
+    if (ncols > 0 && (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kSmallColumn) {
+        hipLaunchKernelGGL(k_select_small, dim3(ncols), dim3(kSmallThreads), 0, s, mode, channels, tile_start, resp, k,
+                           cols);
+        return hipGetLastError();
+    }
     int slices = 2048 / (ncols > 0 ? ncols : 1);
     if (slices < 1) slices = 1;
     if (slices > 64) slices = 64;
@@ -459,6 +559,14 @@ __device__ inline long long lookback_wave(unsigned long long* tile_state, int ti
     return lookback_published(tile_state, tile, count, ctr);
 }
 
+// (one thread) The next `n` tiles of the compaction pass's queue.  Read-modify-writes of one address are served one
+// at a time, about 13 ns each on this chip (a plain load of the counter is no cheaper), so a pass over a few
+// thousand tiles can be bound by its tickets alone, and a thousand workgroups asking at once wait 13 us for theirs.
+// Hence: several tiles per ticket in the narrow kernel, whose tiles are small, and no ticket that is known to come
+// back empty: a launch with at least as many workgroups as tickets takes one ticket per workgroup (`once`), and a
+// workgroup that has seen the queue empty does not ask again.
+__device__ inline unsigned take_ticket(Counters* ctr, unsigned n) { return atomicAdd(&ctr->ticket, n); }
+
 // The result counters, written by the last workgroup of the compaction pass to end (nnz_out may be null: a later
 // kernel writes them).  aux = second counter: the candidate count (aux_is_cand) or a host-side number.
 __device__ inline void finish_if_last(Counters* ctr, long long* nnz_out, long long aux_imm, int aux_is_cand,
@@ -503,7 +611,7 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
 
     for (;;) {
         __syncthreads();  // s_ticket and the tile buffers of the previous round are no longer read
-        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        if (threadIdx.x == 0) s_ticket = (int)take_ticket(ctr, 1u);
         __syncthreads();
         const int tile = s_ticket;
         if (tile >= n_tiles) break;
@@ -742,8 +850,16 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
         }
     };
 
+    // (thread 0) the next tile of this workgroup; a launch with a workgroup per tile asks once
+    const bool once = (long long)gridDim.x >= n_tiles;
+    bool asked = false;
+    auto next_tile = [&]() -> int {
+        const int t = (once && asked) ? n_tiles : (int)take_ticket(ctr, 1u);
+        asked = true;
+        return t;  // (at or past n_tiles: no tile)
+    };
     if (threadIdx.x < 6) s_mask[threadIdx.x >> 1][threadIdx.x & 1] = 0ull;
-    if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+    if (threadIdx.x == 0) s_ticket = next_tile();
     __syncthreads();
     float va[16][2], vb[16][2];
     // prologue: X = first ticket (loaded, decided), Y = second ticket (loads in flight)
@@ -754,7 +870,7 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     }
     load_tile(tile_x, va);
     __syncthreads();  // (the ticket has been read)
-    if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+    if (threadIdx.x == 0) s_ticket = next_tile();
     decide(tile_x, 0, va);
     __syncthreads();
     int tile_y = s_ticket;
@@ -764,7 +880,7 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     // One step: (P, Q) hold (X, Y).  Decide Y, move X to LDS, fetch Z into P's registers, write X.
     auto step = [&](float (&P)[16][2], float (&Q)[16][2]) {
         __syncthreads();  // the previous step's writes are done: s_v, s_base, s_rank, s_ticket and slot_z are free
-        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        if (threadIdx.x == 0) s_ticket = tile_y < n_tiles ? next_tile() : n_tiles;
         if (tile_y < n_tiles) decide(tile_y, slot_y, Q);
         stage_tile(P);
         __syncthreads();  // Y's masks, the ticket and the staged tile are in place
@@ -839,16 +955,12 @@ __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int chan
                                                                 int32_t* __restrict__ out_coords,
                                                                 float* __restrict__ out_feats, long long out_capacity,
                                                                 long long* __restrict__ nnz_out, long long aux_imm,
-                                                                int aux_is_cand) {
+                                                                int aux_is_cand, int tps /* tiles per ticket */) {
     constexpr int RPT = kNarrowTiles * kTileRows / 256;  // rows per thread
     __shared__ int s_cnt[RPT * 4];                       // kept rows of each (row group, wave)
     __shared__ int s_ticket;
     __shared__ long long s_base;
     const int n_tiles = (int)ctr->n_tiles;
-    // tiles per ticket: as many as keep about a thousand tickets in the launch, so that a small layer still spreads
-    // over the chip (1, 2, 4 or kNarrowTiles)
-    int tps = 1;
-    while (tps < kNarrowTiles && n_tiles > 1024 * tps) tps *= 2;
     const int n_super = (n_tiles + tps - 1) / tps;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
@@ -856,10 +968,11 @@ __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int chan
 
     for (;;) {
         __syncthreads();  // the previous super-tile's readers of s_ticket / s_base / s_cnt are done
-        if (threadIdx.x == 0) s_ticket = (int)atomicAdd(&ctr->ticket, 1u);
+        if (threadIdx.x == 0) s_ticket = (int)take_ticket(ctr, 1u);
         __syncthreads();
         const int st = s_ticket;
         if (st >= n_super) break;
+        const bool once = (int)gridDim.x >= n_super;  // one ticket per workgroup covers the layer: do not ask again
         float v[RPT][CMAX];
         bool keep_row[RPT];
         int row_b[RPT], row_first[RPT];
@@ -943,6 +1056,7 @@ __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int chan
                 }
             }
         }
+        if (once) break;
     }
     finish_if_last(ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
 }
@@ -954,10 +1068,18 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
     // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
+    // Narrow layers: a ticket covers 1, 2, 4 .. NT_ tiles, the fewest that leave at most one ticket per CU (a small
+    // layer is bound by the tickets, taken one at a time, and every workgroup launched takes at least one).
 #define SCNN_NARROW_CASE(CMAX_, NT_)                                                                              \
-    hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, \
-                       relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,     \
-                       out_capacity, nnz_out, aux_imm, aux_is_cand)
+    do {                                                                                                          \
+        int tps = 1;                                                                                              \
+        while (tps < NT_ && tiles_cap > 256ll * tps) tps *= 2;                                                    \
+        long long nb = (tiles_cap + tps - 1) / tps;                                                               \
+        nb = nb < 1 ? 1 : (nb > 256 * 4 ? 256 * 4 : nb);                                                          \
+        hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)nb), dim3(256), 0, s, g, channels, \
+                           mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, \
+                           out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);                          \
+    } while (0)
     if (channels <= 4) SCNN_NARROW_CASE(4, 8);
     else if (channels <= 8) SCNN_NARROW_CASE(8, 8);
     else if (channels <= 16) SCNN_NARROW_CASE(16, 8);
