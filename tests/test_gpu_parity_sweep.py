@@ -1,0 +1,82 @@
+"""GPU parity over a seeded sweep of small layer shapes, chosen to cross the points at which the library changes
+kernels: channel counts around the 16- and 32-channel blocks of the vector convolution, odd and even C_in (vector
+width of the gathers), row counts around the 32- and 128-row work items, filters with more than 32 taps, grids on both
+sides of the single-workgroup selection (32768 sites per sample), item counts on both sides of the small / latency /
+streaming forms of the vector convolution, a sample without rows.  Every case goes through the same band-rule
+comparison with the oracle as the fixed cases (un-fused layer on sampled columns, fused variants, standalone
+operators)."""
+import numpy as np
+import pytest
+
+import paper_1801_10585_amd as scnn
+from tests.test_gpu_parity import _sampled_columns, check_conv_against_oracle, say
+from workloads import make_filter, random_sparse_sites
+
+pytestmark = pytest.mark.gpu
+
+KSIZES_3D = [(3, 3, 3), (1, 3, 3), (3, 1, 1), (5, 5, 5), (3, 5, 1), (1, 1, 1)]
+KSIZES_2D = [(3, 3), (5, 3), (7, 7), (1, 5)]
+C_IN = [1, 2, 3, 4, 6, 8, 12, 16, 24]
+C_OUT = [1, 3, 8, 15, 16, 17, 24, 31, 32, 33, 40]
+
+
+def _case(seed):
+    rng = np.random.default_rng(1000 + seed)
+    if seed % 4 == 3:
+        extent = tuple(int(x) for x in rng.integers(6, 40, size=2))
+        ksize = KSIZES_2D[int(rng.integers(len(KSIZES_2D)))]
+    else:
+        extent = tuple(int(x) for x in rng.integers(4, 18, size=3))
+        ksize = KSIZES_3D[int(rng.integers(len(KSIZES_3D)))]
+    batch = int(rng.integers(1, 4))
+    c_in = C_IN[int(rng.integers(len(C_IN)))]
+    c_out = C_OUT[int(rng.integers(len(C_OUT)))]
+    density = float(rng.choice([0.03, 0.1, 0.3, 0.6]))
+    fdens = float(rng.choice([0.3, 0.7, 1.0]))
+    return rng, extent, batch, c_in, c_out, ksize, density, fdens
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_random_small_layers(seed):
+    rng, extent, batch, c_in, c_out, ksize, density, fdens = _case(seed)
+    coords = random_sparse_sites(rng, extent, batch, density)
+    if batch > 1 and seed % 5 == 0:  # one sample without rows
+        coords = np.ascontiguousarray(coords[coords[:, 0] != batch // 2])
+    feats = rng.normal(size=(coords.shape[0], c_in)).astype(np.float32)
+    feats *= rng.random(feats.shape) < 0.9
+    feats = np.ascontiguousarray(feats.astype(np.float32))
+    w = make_filter(rng, ksize, c_in, c_out, fdens, 0.4)
+    bias = rng.normal(size=c_out).astype(np.float32) if seed % 3 == 0 else None
+    n = int(np.prod(extent))
+    mode = scnn.ABS if seed % 2 == 0 else scnn.SIGNED
+    for rho in (0.05, 0.4):
+        k = scnn.k_from_rho(rho, n)
+        say(f"sweep seed={seed} extent={extent} B={batch} {c_in}->{c_out} ksize={ksize} rows={coords.shape[0]} "
+            f"fdens={fdens} rho={rho} k={k} mode={mode}")
+        check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, rho, mode,
+                                  columns=_sampled_columns(rng, batch, c_out, 5), tag=f"sweep {seed} rho={rho}")
+
+
+# item counts (tiles x 32-channel blocks) on both sides of the vector convolution's three forms, and grids on both
+# sides of the single-workgroup selection
+REGIMES = [
+    # extent, batch, c_in, c_out, density
+    ((30, 30, 30), 1, 4, 8, 0.04),     # 27000 sites: about 200 tiles -> 32-row items
+    ((36, 36, 36), 1, 8, 16, 0.03),    # 46656 sites: about 360 tiles -> 128-row items, generic selection
+    ((32, 32, 32), 2, 2, 40, 0.05),    # up to 514 tiles x 2 channel blocks: the device-side count picks the form
+    ((48, 48, 48), 2, 6, 12, 0.08),    # most of 221184 sites are candidates: over 1024 tiles -> streaming form
+]
+
+
+@pytest.mark.parametrize("case", REGIMES)
+def test_vector_convolution_regimes(case):
+    extent, batch, c_in, c_out, density = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 32)
+    coords = random_sparse_sites(rng, extent, batch, density)
+    feats = np.ascontiguousarray(rng.normal(size=(coords.shape[0], c_in)).astype(np.float32))
+    w = make_filter(rng, (3, 3, 3), c_in, c_out, 0.8, 0.3)
+    n = int(np.prod(extent))
+    k = scnn.k_from_rho(0.1, n)
+    say(f"regime extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} k={k}")
+    check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, None, k, 0.1, scnn.ABS,
+                              columns=_sampled_columns(rng, batch, c_out, 4), tag=f"regime {extent}")
