@@ -181,6 +181,8 @@ __global__ __launch_bounds__(256) void k_conv_valu_empty(int c_out, const Counte
         resp[i] = 0.0f;
 }
 
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
 // Latency-oriented form of the vector kernel, for layers with at most `max_items` work items (about one per
 // workgroup slot of the chip: the regime of the paper's own narrow networks on small grids).
 // Work item = (tile, block of 32 output channels); thread = (row, 16 channels).  When the block has only 16
@@ -244,6 +246,15 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
         double acc[kOcBlock];
 #pragma unroll
         for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
+        // matrix-core form (CH >= 4): wave w owns rows 32 w .. 32 w + 31 as two 16-row groups, times the chunk's
+        // 16-channel blocks; lane (m, kq) holds output channel m of rows kq, 4 + kq, 8 + kq, 12 + kq of a group
+        f64x4 macc[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) macc[a][c] = f64x4{0.0, 0.0, 0.0, 0.0};
+        const int mi = threadIdx.x & 15, kq = (threadIdx.x >> 4) & 3;
+        const int wrow = (threadIdx.x >> 6) * 32;  // first row of the wave
 
         for (int tc = 0; tc < g.T; tc += kTapChunk) {
             const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
@@ -333,6 +344,34 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                 commit();
                 __syncthreads();
                 if (q + 1 < n_rounds) fetch(q + 1);
+                if constexpr (CH >= 4) {
+                    // ---- multiply-add on the matrix cores in fp64: per tap and four input channels, the wave's 32
+                    //      rows' values (A, 16 x 4 per row group; zeros where a row lacks the neighbour) times the
+                    //      weights (B, 4 x 16 per channel block)
+                    unsigned live = 0;
+#pragma unroll
+                    for (int tg = 0; tg < TG; ++tg) {
+                        const bool has = tg < tg_n && s_nbr[wrow + (threadIdx.x & 31)][tg0 + tg] >= 0;
+                        if (__ballot(has) != 0ull) live |= 1u << tg;
+                    }
+                    for (int tg = 0; tg < tg_n; ++tg) {
+                        if (!((live >> tg) & 1u)) continue;
+#pragma unroll
+                        for (int jb = 0; jb < CH / 4; ++jb) {
+                            const int tj = tg * CH + jb * 4 + kq;
+                            const double a0 = (double)s_x[wrow + mi][tj], a1 = (double)s_x[wrow + 16 + mi][tj];
+                            const double b0 = s_w[0][tj][mi];
+                            macc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, macc[0][0], 0, 0, 0);
+                            macc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, macc[1][0], 0, 0, 0);
+                            if (!split) {
+                                const double b1 = s_w[1][tj][mi];
+                                macc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, macc[0][1], 0, 0, 0);
+                                macc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, macc[1][1], 0, 0, 0);
+                            }
+                        }
+                    }
+                    continue;
+                }
                 // ---- multiply-add: values and weights from LDS (the weights are a broadcast read).  A tap is skipped
                 //      when no row of the wave has that neighbour; the weights of input channel j + 1 are read while
                 //      channel j multiplies (the fences keep the compiler from sinking the reads to their uses).
@@ -389,6 +428,31 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
                     }
                 }
             }
+        }
+        if constexpr (CH >= 4) {
+            // ---- results to LDS (over the gather buffer), so that a thread can write a row's channels as below
+            static_assert(XS >= 2 * kOcBlock + 1, "a gather row holds a row of results");
+            __syncthreads();  // the last round's values have been read
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        s_x[wrow + a * 16 + 4 * v + kq][c * kOcBlock + mi] = (float)macc[a][c][v];
+            __syncthreads();
+            if (oc0 < c_out_pad && (!split || half == 0)) {
+#pragma unroll
+                for (int o = 0; o < kOcBlock; ++o) {
+                    const int oc = oc0 + o;
+                    if (oc < c_out) {
+                        float v = (row < nrows) ? s_x[row][(split ? 0 : half) * kOcBlock + o] : 0.0f;
+                        if (bias && v != 0.0f) v += bias[oc];
+                        resp[((size_t)tile * c_out + oc) * kTileRows + row] = v;
+                    }
+                }
+            }
+            continue;
         }
         if (split) {  // even taps (first half) + odd taps (second half)
             __syncthreads();  // the last group's values have been read
@@ -473,6 +537,14 @@ __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned 
         double acc[kOcBlock];
 #pragma unroll
         for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
+        // matrix-core form (CH >= 4): [16-row group][16-channel block]; lane (m, kq) holds output channel m of rows
+        // kq, 4 + kq, 8 + kq, 12 + kq (the fp64 instruction's result layout)
+        f64x4 macc[2][2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) macc[a][c] = f64x4{0.0, 0.0, 0.0, 0.0};
+        const int mi = threadIdx.x & 15, kq = (threadIdx.x >> 4) & 3;
 
         __syncthreads();  // previous item's readers of the shared arrays are done
         if (nrows > 0) {  // (uniform) a quarter without rows only writes its zeros
@@ -569,6 +641,29 @@ __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned 
                         fetch_w(q + 1);
                         fetch_x(q + 1);
                     }
+                    if constexpr (CH >= 4) {
+                        // ---- multiply-add on the matrix cores in fp64: per tap and four input channels, the 32
+                        //      rows' values (A, 16 x 4 per row group; zeros where a row lacks the neighbour) times
+                        //      the weights (B, 4 x 16 per channel block).  Two 8-byte operand reads feed 1024
+                        //      multiply-adds, where the vector form reads 128 bytes of weights per lane for 16.
+                        for (int tg = wave; tg < tmax; tg += 4) {
+                            if (!((live >> tg) & 1u)) continue;
+#pragma unroll
+                            for (int jb = 0; jb < CH / 4; ++jb) {
+                                const int tj = tg * CH + jb * 4 + kq;
+                                const double a0 = (double)s_x[mi][tj], a1 = (double)s_x[16 + mi][tj];
+                                const double b0 = s_w[0][tj][mi];
+                                macc[0][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b0, macc[0][0], 0, 0, 0);
+                                macc[1][0] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b0, macc[1][0], 0, 0, 0);
+                                if (!split) {
+                                    const double b1 = s_w[1][tj][mi];
+                                    macc[0][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a0, b1, macc[0][1], 0, 0, 0);
+                                    macc[1][1] = __builtin_amdgcn_mfma_f64_16x16x4f64(a1, b1, macc[1][1], 0, 0, 0);
+                                }
+                            }
+                        }
+                        continue;
+                    }
                     // ---- multiply-add, weights of the next input channel read while this one multiplies
                     auto read_w = [&](double (&dst)[kOcBlock], int tj) {
                         const double2* p = reinterpret_cast<const double2*>(&s_w[hb][tj][0]);
@@ -613,8 +708,35 @@ __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned 
                 }
             }
         }
-        // ---- the eight partial sums of an output, added in a fixed order (wave 0 .. 3, first half then second)
         __syncthreads();  // the last round's weights have been read
+        if constexpr (CH >= 4) {
+            // ---- the four waves' partial sums (one per tap slice), added in the order of the waves
+            double (*s_rm)[R][2 * kOcBlock + 1] = reinterpret_cast<double (*)[R][2 * kOcBlock + 1]>(&s_wr[0]);
+            static_assert(4 * R * (2 * kOcBlock + 1) <= kRedElems, "the partial sums fit");
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int c = 0; c < 2; ++c)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) s_rm[wave][a * 16 + 4 * v + kq][c * kOcBlock + mi] = macc[a][c][v];
+            __syncthreads();
+            const int per = split ? 2 : 4;  // channels per thread: 16 or 32 channels over 8 thread groups
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (i >= per) break;
+                const int c = sl * per + i;  // channel within the chunk
+                const int oc = chunk * 2 * kOcBlock + c;
+                if (oc >= c_out) continue;
+                double sum = 0.0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) sum += s_rm[k][row][c];
+                float v = (row < nrows) ? (float)sum : 0.0f;
+                if (bias && v != 0.0f) v += bias[oc];
+                resp[((size_t)tile * c_out + oc) * kTileRows + quarter * R + row] = v;
+            }
+            continue;
+        }
+        // ---- the eight partial sums of an output, added in a fixed order (wave 0 .. 3, first half then second)
 #pragma unroll
         for (int o = 0; o < kOcBlock; ++o) s_red[sl][row][o] = acc[o];
         __syncthreads();
