@@ -336,9 +336,14 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
                                 ws.ctr, s));
     timer.mark();
     SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
-    SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
-    SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start, ws.tile_start,
-                              ws.rows16_start, ws.ctr, s));
+    if (nw <= kEmitSmallWords) {
+        SCNN_TRY(launch_cand_emit_small(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start,
+                                        ws.tile_start, ws.rows16_start, ws.ctr, s));
+    } else {
+        SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
+        SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start,
+                                  ws.tile_start, ws.rows16_start, ws.ctr, s));
+    }
     timer.mark();
     if (use_mfma) {
         SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,

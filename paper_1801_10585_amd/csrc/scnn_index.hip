@@ -432,6 +432,78 @@ __global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long l
     }
 }
 
+// The same for short bitmaps (at most kEmitSmallWords words), without a scan launch before it: a block sums the counts
+// of the words before its own (a few thousand numbers out of L2) and scans its 256 words itself; the last block scans
+// the whole array once to find the per-sample ranges.  `cand_count` holds the words' candidate counts, unscanned.
+__global__ __launch_bounds__(256) void k_cand_emit_small(Geom g, const unsigned long long* __restrict__ cand,
+                                                         const unsigned* __restrict__ cand_count, int n_words,
+                                                         unsigned* __restrict__ cand_lin, long long cand_cap,
+                                                         int* __restrict__ cand_start, int* __restrict__ tile_start,
+                                                         int* __restrict__ rows16_start, Counters* ctr) {
+    __shared__ unsigned s_wave[4];
+    if (blockIdx.x == gridDim.x - 1) {
+        // exclusive scan in chunks of 2048 words; a sample starts at every Wps-th word
+        unsigned carry = 0;
+        for (int start = 0; start < n_words; start += kScanChunk) {
+            const int base = start + threadIdx.x * 8;
+            unsigned v[8], sum = 0;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v[i] = (base + i < n_words) ? cand_count[base + i] : 0u;
+                sum += v[i];
+            }
+            unsigned total;
+            unsigned excl = carry + block_exclusive_scan_256(sum, s_wave, total);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int w = base + i;
+                if (w < n_words && w % (int)g.Wps == 0) cand_start[w / (int)g.Wps] = (int)excl;
+                excl += v[i];
+            }
+            carry += total;
+        }
+        const long long n_cand = (long long)carry;
+        const bool overflow = n_cand > cand_cap;
+        __syncthreads();  // cand_start[0 .. batch) written
+        if (overflow)
+            for (int b = threadIdx.x; b < g.batch; b += blockDim.x) cand_start[b] = 0;
+        if (threadIdx.x == 0) cand_start[g.batch] = overflow ? 0 : (int)n_cand;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int acc = 0, acc16 = 0;
+            for (int b = 0; b < g.batch; ++b) {
+                tile_start[b] = acc;
+                rows16_start[b] = acc16;
+                const int n = cand_start[b + 1] - cand_start[b];
+                acc += (n + kTileRows - 1) / kTileRows;
+                acc16 += (n + 15) / 16;
+            }
+            tile_start[g.batch] = acc;
+            rows16_start[g.batch] = acc16;
+            ctr->n_cand = n_cand;
+            ctr->n_tiles = acc;
+            if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+        }
+        return;
+    }
+    const int w0 = blockIdx.x * 256;
+    unsigned below = 0;
+    for (int i = threadIdx.x; i < w0; i += 256) below += cand_count[i];
+    unsigned before_block;
+    (void)block_exclusive_scan_256(below, s_wave, before_block);  // (the total is what is wanted)
+    const int w = w0 + threadIdx.x;
+    unsigned long long bits = w < n_words ? cand[w] : 0ull;
+    unsigned block_total;
+    long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
+    const unsigned base = w < n_words ? (unsigned)((w % g.Wps) * 64) : 0u;
+    while (bits) {
+        const int bit = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        if (o < cand_cap) cand_lin[o] = base + (unsigned)bit;
+        ++o;
+    }
+}
+
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
                             long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
                             int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
@@ -439,6 +511,15 @@ hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const
     if (blocks < 1) blocks = 1;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(k_cand_emit, dim3((unsigned)blocks + 1), dim3(256), 0, s, g, cand, cand_prefix, n_words,
+                       cand_lin, cand_cap, cand_start, tile_start, rows16_start, ctr);
+    return hipGetLastError();
+}
+
+hipError_t launch_cand_emit_small(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
+                                  long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
+                                  int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
+    const unsigned blocks = (unsigned)((n_words + 255) / 256);
+    hipLaunchKernelGGL(k_cand_emit_small, dim3(blocks + 1), dim3(256), 0, s, g, cand, cand_count, (int)n_words,
                        cand_lin, cand_cap, cand_start, tile_start, rows16_start, ctr);
     return hipGetLastError();
 }

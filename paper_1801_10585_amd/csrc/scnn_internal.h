@@ -242,6 +242,11 @@ hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, in
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
+// bitmaps of at most this many words: the emit kernels find their offsets themselves, no scan launch
+constexpr long long kEmitSmallWords = 8192;
+hipError_t launch_cand_emit_small(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
+                                  long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
+                                  int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
                             long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
                             int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);

@@ -117,6 +117,31 @@ __global__ __launch_bounds__(256) void k_pool_emit(const unsigned long long* __r
     }
 }
 
+// The same for short bitmaps (at most kEmitSmallWords words), without the popcount and scan launches before it: a
+// block sums the popcounts of the words before its own and scans its 256 words itself; the block that holds the last
+// word also knows the total.
+__global__ __launch_bounds__(256) void k_pool_emit_small(const unsigned long long* __restrict__ pbits, int n_words,
+                                                         long long* __restrict__ pool_key, long long pool_cap,
+                                                         Counters* ctr) {
+    __shared__ unsigned s_wave[4];
+    const int w0 = blockIdx.x * 256;
+    unsigned below = 0;
+    for (int i = threadIdx.x; i < w0; i += 256) below += (unsigned)__popcll(pbits[i]);
+    unsigned before_block;
+    (void)block_exclusive_scan_256(below, s_wave, before_block);
+    const int w = w0 + threadIdx.x;
+    unsigned long long bits = w < n_words ? pbits[w] : 0ull;
+    unsigned block_total;
+    long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) ctr->n_pool = (long long)before_block + block_total;
+    while (bits) {
+        const int bit = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        if (o < pool_cap) pool_key[o] = (long long)w * 64 + bit;
+        ++o;
+    }
+}
+
 __global__ __launch_bounds__(256) void k_pool_gather(Geom g, Geom gp, const unsigned long long* __restrict__ occ,
                                                      const unsigned* __restrict__ occ_prefix, long long n_imm,
                                                      const long long* __restrict__ n_dev,
@@ -170,14 +195,19 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
     hipLaunchKernelGGL(k_pool_mark, dim3((unsigned)blocks), dim3(256), 0, s, g, gp, coords, feats, channels,
                        rows_have_entries, n_imm, n_dev, pbits);
     const long long n_words = (long long)gp.batch * gp.Wps;
-    e = launch_popcount(pbits, n_words, pprefix, s);
-    if (e != hipSuccess) return e;
-    e = launch_exclusive_scan(pprefix, n_words, n_words, nullptr, scan_block_sums, &ctr->n_pool, s);
-    if (e != hipSuccess) return e;
-    blocks = (n_words + 255) / 256;
-    if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_pool_emit, dim3((unsigned)blocks), dim3(256), 0, s, pbits, pprefix, n_words, pool_key,
-                       pool_cap);
+    if (n_words <= kEmitSmallWords) {
+        hipLaunchKernelGGL(k_pool_emit_small, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, pbits,
+                           (int)n_words, pool_key, pool_cap, ctr);
+    } else {
+        e = launch_popcount(pbits, n_words, pprefix, s);
+        if (e != hipSuccess) return e;
+        e = launch_exclusive_scan(pprefix, n_words, n_words, nullptr, scan_block_sums, &ctr->n_pool, s);
+        if (e != hipSuccess) return e;
+        blocks = (n_words + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(k_pool_emit, dim3((unsigned)blocks), dim3(256), 0, s, pbits, pprefix, n_words, pool_key,
+                           pool_cap);
+    }
     blocks = (pool_cap * channels + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 16384) blocks = 16384;
