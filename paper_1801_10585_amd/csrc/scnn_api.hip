@@ -161,6 +161,7 @@ struct ConvWs {
     unsigned long long* occ;
     unsigned long long* cand;
     unsigned long long* pbits;
+    unsigned long long* occ_sel;
     unsigned* hist;
     ColState* cols;
     unsigned long long* tile_state;
@@ -209,6 +210,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->occ = c.take<unsigned long long>(nw);
     w->cand = c.take<unsigned long long>(nw);
     w->pbits = c.take<unsigned long long>(pool ? nwp : 0);
+    w->occ_sel = c.take<unsigned long long>(pool ? nw : 0);  // occupancy of the selected rows, for the pooling
     w->hist = c.take<unsigned>(ncols * kHistBins);
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
@@ -372,10 +374,9 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
                                      ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, ws.tmp_coords, ws.tmp_feats,
                                      ws.cand_cap, nullptr, 0, 0, s));
         timer.mark();
-        SCNN_TRY(launch_zero(ws.occ, (size_t)nw * sizeof(unsigned long long), s));
-        SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1, ws.occ,
-                                ws.occ_prefix, ws.pbits, ws.pprefix, ws.block_sums, ws.pool_key, ws.pool_cap,
-                                out_coords, out_feats, out_capacity, ws.ctr, s));
+        SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1,
+                                ws.occ_sel, ws.occ_prefix, ws.pbits, ws.pprefix, ws.block_sums, ws.pool_key,
+                                ws.pool_cap, out_coords, out_feats, out_capacity, ws.ctr, s));
         SCNN_TRY(launch_finish(ws.ctr, 1, 0, 1, out_capacity, (long long*)nnz_out, s));
     }
     timer.done();
