@@ -126,7 +126,8 @@ __global__ __launch_bounds__(256) void k_scan_small(unsigned* __restrict__ vals,
     if (threadIdx.x == 0 && total_out) *total_out = (long long)carry;
 }
 
-constexpr long long kScanSmall = 16 * kScanChunk;  // up to this many elements one workgroup scans alone
+// up to this many elements one workgroup scans alone: it takes about 2 us per chunk of 2048, three launches 13 us
+constexpr long long kScanSmall = 4 * kScanChunk;
 
 hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n_imm, const long long* n_dev,
                                  unsigned* block_sums, long long* total, hipStream_t s) {
