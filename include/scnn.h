@@ -236,10 +236,13 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                     int64_t* info, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Kernel choice for the convolution step of sparse_conv_fwd, process-wide:
- * 0 = by shape (matrix-core kernel when C_in is a multiple of 32 up to 128 and
- * C_out a multiple of 16 up to 64, else the vector kernel), 1 = always the
- * vector kernel.  Both compute the same sums to the same rounding rule; the
- * switch exists so that tests and measurements can reach either. */
+ * 0 = by shape and size (matrix-core kernel when C_in is a multiple of 32 up to
+ * 128, or 16 on a large layer with C_out >= 32, and C_out a multiple of 16 up
+ * to 64; else the vector kernel), 1 = always the vector kernel, 2 = the
+ * matrix-core kernel whenever the shape allows it, whatever the size.  All
+ * compute the same sums to the same rounding rule; the switch exists so that
+ * tests and measurements can reach each.  The setting enters the workspace
+ * size: query the workspace under the setting the call will run with. */
 int scnn_set_conv_path(int path);
 
 /* Measurement support (not part of the method): when enabled on the calling

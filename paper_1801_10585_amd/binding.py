@@ -455,7 +455,8 @@ def profile_collect():
 
 
 def set_conv_path(path: int) -> None:
-    """0 = choose the convolution kernel by shape, 1 = always the vector kernel."""
+    """0 = choose the convolution kernel by shape and size, 1 = always the vector kernel, 2 = the matrix-core kernel
+    whenever the shape allows it."""
     L = load_library()
     _check(L, L.scnn_set_conv_path(int(path)))
 

@@ -995,7 +995,10 @@ struct RoundRegs {
 // filter tap (all C_out channels), so an input row is fetched once per pair and a tap's weights once per round;
 // the price is that two waves may add to the same accumulator, which the LDS fp64 atomic makes safe but not
 // ordered: the fp64 sum can differ in its last bits from run to run.
-template <int KC /* C_in / 32 */, int NB /* C_out / 16 */>
+// HALF: C_in = 16 (KC = 1): a lane's K slot gq stands for the four channels 4 gq .. 4 gq + 3 instead of eight, so a
+// block takes four matrix instructions per 16 output channels and the second halves of the operands stay unused
+// (the filter is prepared in the same 8-floats-per-lane layout, upper four zero).
+template <int KC /* C_in / 32 */, int NB /* C_out / 16 */, int HALF = 0>
 __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long long nnz_in,
                                                                const float* __restrict__ feats,
                                                                const float* __restrict__ wb,
@@ -1005,7 +1008,8 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                                                                const uint2* __restrict__ tile_hdr,
                                                                Counters* __restrict__ ctr,
                                                                float* __restrict__ resp) {
-    constexpr int C_IN = KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
+    static_assert(!HALF || KC == 1, "the half chunk stands alone");
+    constexpr int C_IN = HALF ? 16 : KC * 32, C_OUT = NB * 16, CS = C_OUT + 1 /* padded accumulator row */;
     constexpr int RB = (KC * NB <= 4) ? 3 : ((KC * NB <= 8) ? 2 : 1);  // blocks per round
     constexpr int NT = kConvWaves * 64;
     static_assert(kStageBlocks % 4 == 0 && kStageBlocks <= 256, "stage size");
@@ -1117,16 +1121,16 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
 #pragma unroll
                         for (int cb = 0; cb < NB; ++cb) {
                             R.b[kc][cb][0] = wt[(kc * NB + cb) * 128];
-                            R.b[kc][cb][1] = wt[(kc * NB + cb) * 128 + 1];
+                            if constexpr (!HALF) R.b[kc][cb][1] = wt[(kc * NB + cb) * 128 + 1];
                         }
 #pragma unroll
                     for (int k = 0; k < RB; ++k) {
                         const unsigned in = E.in[k] & kPairInMask;
-                        const f32x4* src = (const f32x4*)(feats + (size_t)in * C_IN + 8 * gq);
+                        const f32x4* src = (const f32x4*)(feats + (size_t)in * C_IN + (HALF ? 4 : 8) * gq);
 #pragma unroll
                         for (int kc = 0; kc < KC; ++kc) {
                             R.a[k][kc][0] = src[kc * 8];
-                            R.a[k][kc][1] = src[kc * 8 + 1];
+                            if constexpr (!HALF) R.a[k][kc][1] = src[kc * 8 + 1];
                         }
                         // (a stale entry past the end of the list may name any row, but such a block is not computed)
                         R.oaddr[k][0] = (E.out[k].x >> kPairRowShift) * (unsigned)(CS * sizeof(double)) + lane_off;
@@ -1154,9 +1158,11 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
 #pragma unroll
                                     for (int s = 0; s < 4; ++s)
                                         c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][0][s], R.b[kc][cb][0][s], c, 0, 0, 0);
+                                    if constexpr (!HALF) {
 #pragma unroll
-                                    for (int s = 0; s < 4; ++s)
-                                        c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][cb][1][s], c, 0, 0, 0);
+                                        for (int s = 0; s < 4; ++s)
+                                            c = __builtin_amdgcn_mfma_f32_16x16x4f32(R.a[k][kc][1][s], R.b[kc][cb][1][s], c, 0, 0, 0);
+                                    }
                                     acc[cb] = c;
                                 }
 #pragma unroll
@@ -1256,14 +1262,14 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     }
 }
 
-template <int KC, int NB>
+template <int KC, int NB, int HALF = 0>
 static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* feats, const float* wb, const float* bias,
                                      const unsigned* pairs, const unsigned short* block_tap, const uint2* tile_hdr,
                                      Counters* ctr, float* resp, hipStream_t s) {
     const size_t lds = conv_mfma_lds_bytes(NB * 16);
     static size_t attr_lds = 0;
     if (attr_lds < lds) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<KC, NB>,
+        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<KC, NB, HALF>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_lds = lds;
@@ -1272,14 +1278,15 @@ static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* fe
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;    // 16 waves per CU
     const int grid = 256 * per_cu;  // a multiple of 8 (one span of tiles per XCD)
-    hipLaunchKernelGGL((k_conv_mfma<KC, NB>), dim3(grid), dim3(kConvWaves * 64), lds, s, taps, nnz_in, feats, wb, bias,
+    hipLaunchKernelGGL((k_conv_mfma<KC, NB, HALF>), dim3(grid), dim3(kConvWaves * 64), lds, s, taps, nnz_in, feats, wb,
+                       bias,
                        pairs, block_tap, tile_hdr, ctr, resp);
     return hipGetLastError();
 }
 
 bool conv_mfma_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
     if (g.T > 255) return false;  // block_tap holds the tap in one byte
-    return c_in % 32 == 0 && c_in <= 128 && c_out % 16 == 0 && c_out <= 64 && nnz_in > 0 &&
+    return ((c_in % 32 == 0 && c_in <= 128) || c_in == 16) && c_out % 16 == 0 && c_out <= 64 && nnz_in > 0 &&
            nnz_in < (1ll << kPairRowShift);
 }
 
@@ -1294,6 +1301,11 @@ hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats,
     SCNN_MFMA_CASE(3, 1) SCNN_MFMA_CASE(3, 2) SCNN_MFMA_CASE(3, 3) SCNN_MFMA_CASE(3, 4)
     SCNN_MFMA_CASE(4, 1) SCNN_MFMA_CASE(4, 2) SCNN_MFMA_CASE(4, 3) SCNN_MFMA_CASE(4, 4)
 #undef SCNN_MFMA_CASE
+#define SCNN_MFMA_HALF(NB_)                                                                                       \
+    if (c_in == 16 && c_out == NB_ * 16)                                                                          \
+        return launch_conv_mfma_t<1, NB_, 1>(g.T, nnz_in, feats, wb, bias, pairs, block_tap, tile_hdr, ctr, resp, s);
+    SCNN_MFMA_HALF(1) SCNN_MFMA_HALF(2) SCNN_MFMA_HALF(3) SCNN_MFMA_HALF(4)
+#undef SCNN_MFMA_HALF
     return hipErrorInvalidValue;
 }
 

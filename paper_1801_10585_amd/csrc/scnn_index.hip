@@ -226,16 +226,19 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
     __syncthreads();
     int any = 0;
     if (wb) {
-        const int kcn = c_in / 32, nb = c_out / 16, n = c_in * c_out;
+        // C_in = 16 is laid out like one 32-channel chunk: a lane's first four values are channels 4 gq .. 4 gq + 3,
+        // its other four are zero
+        const bool half = c_in == 16;
+        const int nb = c_out / 16, n = (half ? 32 : c_in) * c_out;
         for (int i = threadIdx.x; i < n; i += blockDim.x) {
             const int sub = i & 7, lane = (i >> 3) & 63;
-            const int r = i >> 9, cb = r % nb, kc = r / nb;  // (kc < kcn since n = kcn * nb * 512)
+            const int r = i >> 9, cb = r % nb, kc = r / nb;  // (kc < C_in / 32 since n = (C_in / 32) * nb * 512)
             const int jj = lane & 15, gq = lane >> 4;
-            const float v = filter_at(w, g.T, c_in, c_out, adjoint, t, kc * 32 + 8 * gq + sub, cb * 16 + jj);
+            const int ic = half ? (sub < 4 ? 4 * gq + sub : -1) : kc * 32 + 8 * gq + sub;
+            const float v = ic >= 0 ? filter_at(w, g.T, c_in, c_out, adjoint, t, ic, cb * 16 + jj) : 0.0f;
             wb[(size_t)t * n + i] = v;
             any |= (v != 0.0f);
         }
-        (void)kcn;
     } else {
         const int n = c_in * c_out_pad;
         for (int i = threadIdx.x; i < n; i += blockDim.x) {

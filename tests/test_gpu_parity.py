@@ -223,11 +223,15 @@ MFMA_CASES = [
     ((18, 18, 18), 2, 32, 32, (5, 5, 5), 0.03, 0.3),
     ((40, 40), 3, 96, 32, (3, 3), 0.15, 0.8),
     ((12, 12, 12), 1, 128, 64, (1, 3, 3), 0.2, 1.0),
+    # sixteen input channels: the half-chunk form of the matrix-core kernel
+    ((16, 16, 16), 2, 16, 16, (3, 3, 3), 0.08, 1.0),
+    ((20, 20, 20), 1, 16, 64, (3, 3, 3), 0.05, 0.6),
+    ((30, 30), 2, 16, 48, (3, 3), 0.2, 1.0),
 ]
 
 
 @pytest.mark.parametrize("case", MFMA_CASES)
-@pytest.mark.parametrize("path", [0, 1])
+@pytest.mark.parametrize("path", [0, 1, 2])
 def test_layer_wide_channels_both_kernels(case, path):
     extent, batch, c_in, c_out, ksize, density, fdens = case
     rng = np.random.default_rng(abs(hash(case)) % 2 ** 32)
