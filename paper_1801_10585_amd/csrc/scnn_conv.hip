@@ -766,7 +766,7 @@ __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned 
 }
 
 // Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
-constexpr long long kValuLatencyItems = 1280;  // five per CU
+constexpr long long kValuLatencyItems = 1024;
 // Layers whose workspace holds at most this many work items (a bound the host knows) run the 32-row form.
 constexpr long long kValuSmallItems = 256;
 

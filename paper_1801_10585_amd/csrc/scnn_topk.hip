@@ -321,9 +321,21 @@ __global__ __launch_bounds__(kSideThreads) void k_side_select(ColState* __restri
                 const unsigned i = i0 + (unsigned)kSideThreads * u;
                 x[u] = i < m ? e[i] : make_uint2(0u, 0u);
             }
+            // Data with long runs of equal scores (unit input values) sends most lanes of a wave to one bin, and LDS
+            // serves the atomics of a wave on one word one after the other: the lanes that share the first active
+            // lane's bin add once, through that lane; the others add on their own.
 #pragma unroll
-            for (int u = 0; u < 8; ++u)
-                if (i0 + (unsigned)kSideThreads * u < m && pass(x[u])) atomicAdd(&s_h[digit(x[u])], 1u);
+            for (int u = 0; u < 8; ++u) {
+                const bool valid = i0 + (unsigned)kSideThreads * u < m && pass(x[u]);
+                const unsigned bin = valid ? digit(x[u]) : 0u;
+                const unsigned long long act = __ballot(valid);
+                if (act == 0ull) continue;  // (uniform)
+                const int first = __ffsll((long long)act) - 1;
+                const unsigned b0 = __shfl(bin, first, 64);
+                const unsigned long long same = __ballot(valid && bin == b0);
+                if ((int)(threadIdx.x & 63) == first) atomicAdd(&s_h[b0], (unsigned)__popcll(same));
+                else if (valid && bin != b0) atomicAdd(&s_h[bin], 1u);
+            }
         }
         __syncthreads();
     };
