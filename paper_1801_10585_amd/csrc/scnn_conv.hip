@@ -32,8 +32,11 @@ constexpr int kOcBlock = 16;   // output channels accumulated per thread
 // pair of bitmap words).
 // Work item = (tile, block of 32 output channels); thread = (row, 16 channels).  When the block holds only 16
 // channels the second half of the workgroup takes every other tap (partial sums added through LDS, fixed order).
+// OCB = 8: layers of at most 8 output channels (the first block of the paper's networks, on its largest grid) keep
+// 8 accumulators per thread instead of 16 half-idle ones; on such layers the kernel is bound by FMA issue.
 // Runs only when the layer has more than `min_items` work items (a device-side count).
-template <int CH /* the largest of 8, 4, 2, 1 that divides C_in and suits the alignment of the values */>
+template <int CH /* the largest of 8, 4, 2, 1 that divides C_in and suits the alignment of the values */,
+          int OCB /* output channels per thread: 16, or 8 for layers of at most 8 channels (then always split) */>
 __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned long long* __restrict__ occ,
                                                           const unsigned* __restrict__ occ_prefix, long long nnz_in,
                                                           const float* __restrict__ feats, int c_in,
@@ -76,9 +79,9 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
             s_site[threadIdx.x][2] = c2;
         }
 
-        double acc[kOcBlock];
+        double acc[OCB];
 #pragma unroll
-        for (int o = 0; o < kOcBlock; ++o) acc[o] = 0.0;
+        for (int o = 0; o < OCB; ++o) acc[o] = 0.0;
 
         for (int tc = 0; tc < g.T; tc += kTapChunk) {
             const int tmax = (g.T - tc) < kTapChunk ? (g.T - tc) : kTapChunk;
@@ -124,20 +127,20 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
 #pragma unroll
                         for (int j2 = 0; j2 < CH; j2 += 2) {
                             const double* __restrict__ wr = wt + (size_t)(ic0 + j2) * c_out_pad;
-                            double wa[kOcBlock], wb[kOcBlock];
+                            double wa[OCB], wb[OCB];
 #pragma unroll
-                            for (int o = 0; o < kOcBlock; ++o) wa[o] = wr[o];
+                            for (int o = 0; o < OCB; ++o) wa[o] = wr[o];
                             if constexpr (CH > 1) {
 #pragma unroll
-                                for (int o = 0; o < kOcBlock; ++o) wb[o] = wr[c_out_pad + o];
+                                for (int o = 0; o < OCB; ++o) wb[o] = wr[c_out_pad + o];
                             }
                             const double xa = (double)xv[j2];
 #pragma unroll
-                            for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xa, wa[o], acc[o]);
+                            for (int o = 0; o < OCB; ++o) acc[o] = fma(xa, wa[o], acc[o]);
                             if constexpr (CH > 1) {
                                 const double xb = (double)xv[j2 + 1];
 #pragma unroll
-                                for (int o = 0; o < kOcBlock; ++o) acc[o] = fma(xb, wb[o], acc[o]);
+                                for (int o = 0; o < OCB; ++o) acc[o] = fma(xb, wb[o], acc[o]);
                             }
                             // keeps the compiler from hoisting the next pair's scalar loads above this point
                             asm volatile("" ::: "memory");
@@ -151,17 +154,17 @@ __global__ __launch_bounds__(256) void k_conv_valu_stream(Geom g, const unsigned
             __syncthreads();  // the last chunk's neighbour rows have been read
             if (half == 1) {
 #pragma unroll
-                for (int o = 0; o < kOcBlock; ++o) s_acc[o] = acc[o];
+                for (int o = 0; o < OCB; ++o) s_acc[o] = acc[o];
             }
             __syncthreads();
             if (half == 0) {
 #pragma unroll
-                for (int o = 0; o < kOcBlock; ++o) acc[o] += s_acc[o];
+                for (int o = 0; o < OCB; ++o) acc[o] += s_acc[o];
             }
         }
         if (oc0 < c_out_pad && (!split || half == 0)) {
 #pragma unroll
-            for (int o = 0; o < kOcBlock; ++o) {
+            for (int o = 0; o < OCB; ++o) {
                 const int oc = oc0 + o;
                 if (oc < c_out) {
                     float v = (row < nrows) ? (float)acc[o] : 0.0f;
@@ -803,10 +806,14 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
     }
 #define SCNN_VALU_CASE(CH_)                                                                                          \
     do {                                                                                                             \
-        if (both)                                                                                                    \
-            hipLaunchKernelGGL(k_conv_valu_stream<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in,  \
-                               feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, \
-                               ctr, kValuLatencyItems, resp);                                                        \
+        if (both && c_out <= 8)                                                                                      \
+            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 8>), dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix,     \
+                               nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start,    \
+                               tile_start, ctr, kValuLatencyItems, resp);                                            \
+        else if (both)                                                                                               \
+            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 16>), dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix,    \
+                               nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start,    \
+                               tile_start, ctr, kValuLatencyItems, resp);                                            \
         hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, \
                            wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,            \
                            kValuLatencyItems, resp);                                                                 \
