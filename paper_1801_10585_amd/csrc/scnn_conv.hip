@@ -197,6 +197,10 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 // words), and the neighbours' values are gathered into LDS cooperatively (CH channels of TG taps at a time, every
 // load independent of every other), together with the group's weights, one round ahead of the multiply-add phase
 // that reads both from there.
+// With CH >= 4 the multiply-add phase runs on the fp64 matrix cores instead (v_mfma_f64_16x16x4_f64, same fp64
+// products and sums): wave w then owns rows 32 w .. 32 w + 31 and all of the chunk's channels, and the results go
+// through LDS to the (row, 16 channels) threads that write them.  Reading a (tap, channel)'s 16 weights as an LDS
+// broadcast per lane, as the thread-per-row form does, costs the LDS four times the cycles the FMAs take.
 template <int CH /* input channels per gather: the largest of 8, 4, 2, 1 that divides C_in */>
 __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long long* __restrict__ occ,
                                                    const unsigned* __restrict__ occ_prefix, long long nnz_in,
@@ -486,9 +490,11 @@ __global__ __launch_bounds__(256) void k_conv_valu(Geom g, const unsigned long l
 // The same kernel shape for the smallest layers (at most a few hundred tiles: the deep, pooled layers of the paper's
 // networks), where 128-row work items would leave most of the chip idle.  Work item = (quarter of a tile = 32 rows,
 // block of 32 output channels).  The four waves of the workgroup share the taps (wave w takes taps w, w + 4, ...);
-// the two halves of a wave take the two 16-channel blocks, or, when there is only one, every other input channel.
 // A round covers all taps of the chunk for CH input channels, so that a 3^d filter over 24 channels takes three
-// rounds; the eight partial sums per output are added through LDS in a fixed order.
+// rounds.  CH >= 4: a wave multiplies its taps for all 32 rows and channels on the fp64 matrix cores
+// (v_mfma_f64_16x16x4_f64) and the four waves' partial sums are added through LDS in the order of the waves.
+// CH = 2: the two halves of a wave take the two 16-channel blocks, or, when there is only one, every other input
+// channel, with fp64 FMAs; the eight partial sums per output are added through LDS in a fixed order.
 template <int CH /* 8, 4 or 2 */>
 __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned long long* __restrict__ occ,
                                                          const unsigned* __restrict__ occ_prefix, long long nnz_in,
