@@ -65,6 +65,11 @@ REGIMES = [
     ((36, 36, 36), 1, 8, 16, 0.03),    # 46656 sites: about 360 tiles -> 128-row items, generic selection
     ((32, 32, 32), 2, 2, 40, 0.05),    # up to 514 tiles x 2 channel blocks: the device-side count picks the form
     ((48, 48, 48), 2, 6, 12, 0.08),    # most of 221184 sites are candidates: over 1024 tiles -> streaming form
+    ((48, 48, 48), 2, 8, 8, 0.08),     # the same with at most 8 output channels: 8 accumulators per thread
+    ((64, 64, 128), 1, 2, 4, 0.003),   # exactly 8192 bitmap words: the emit kernels still find their own offsets
+    ((64, 64, 136), 1, 2, 4, 0.003),   # more than 8192 words: scan launches
+    ((33, 32, 32), 2, 4, 8, 0.05),     # just over 32768 sites per sample: three-launch selection
+    ((176, 176, 176), 1, 2, 4, 0.0004),  # pooled grid 88^3: more than 8192 words in the pooling's bitmap
 ]
 
 
