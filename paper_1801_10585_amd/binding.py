@@ -266,7 +266,9 @@ def sparse_conv_bwd_workspace(extent, batch, nnz_in, c_in, c_out, ksize, g_rows)
 
 class ChainedLayer:
     """One layer of a chain that runs without host reads: buffers sized once from capacities, the input row count
-    taken on the device.  `in_capacity` bounds the rows of the input arrays."""
+    taken on the device.  `in_capacity` bounds the rows of the input arrays.  Run a chain once eagerly before
+    capturing it in a HIP graph: the first launch of a matrix-core kernel sets that kernel's shared-memory attribute,
+    which is not a stream operation."""
 
     def __init__(self, extent, batch, in_capacity, c_in, ksize, w, *, bias=None, rho_up=1.0, topk_mode=ABS,
                  relu=False, pool=False):
