@@ -254,7 +254,10 @@ int scnn_set_conv_path(int path);
  * convolution, bp_data write, bp_filter).  scnn_profile_collect waits for
  * the recorded calls, adds their per-stage milliseconds into stage_ms
  * [scnn_profile_stage_count()] and the number of calls into *calls, then
- * forgets them.  Host pointers. */
+ * forgets them.  on = 1: every boundary; on = 2: only the two events around
+ * the convolution stage of sparse_conv_fwd (the other stages read 0), for
+ * timing the dominant kernel inside a throughput measurement at the least
+ * cost; on = 0: none.  Host pointers. */
 int scnn_profile_enable(int on);
 int scnn_profile_stage_count(void);
 const char* scnn_profile_stage_name(int stage);

@@ -441,9 +441,10 @@ def validate_rows(extent, batch, coords, stream=None) -> None:
     _check(L, rc)
 
 
-def profile_enable(on: bool) -> None:
-    """Per-stage HIP-event timing of sparse_conv_fwd calls made from this thread."""
-    _check(load_library(), load_library().scnn_profile_enable(1 if on else 0))
+def profile_enable(on) -> None:
+    """Per-stage HIP-event timing of sparse_conv_fwd calls made from this thread: False / 0 = off, True / 1 = every
+    stage, 2 = only the convolution stage (two events per call)."""
+    _check(load_library(), load_library().scnn_profile_enable(int(on)))
 
 
 def profile_collect():

@@ -128,14 +128,16 @@ static constexpr int kFwdStages = 7, kBwdStages = 5, kStages = kFwdStages + kBwd
 struct ProfCall {
     hipEvent_t ev[kFwdStages + 1];
     int first_stage, n_stages;
+    unsigned recorded;  // bit i: ev[i] was recorded in this call
 };
-static thread_local bool g_prof_on = false;
+static constexpr int kConvStage = 3;  // "conv": the only stage timed in mode 2
+static thread_local int g_prof_on = 0;  // 0 off, 1 every stage boundary, 2 only the convolution stage's two
 static thread_local std::vector<ProfCall>* g_prof_calls = nullptr;   // recorded, not yet collected
 static thread_local std::vector<ProfCall>* g_prof_pool = nullptr;    // idle events for reuse
 
 struct StageTimer {
     ProfCall call;
-    bool on = false;
+    bool on = false, only_conv = false;
     int next = 0;
     hipStream_t s;
     StageTimer(hipStream_t stream, int first_stage, int n_stages) : s(stream) {
@@ -151,14 +153,22 @@ struct StageTimer {
         }
         call.first_stage = first_stage;
         call.n_stages = n_stages;
+        call.recorded = 0;
+        only_conv = g_prof_on == 2 && first_stage == 0;
         on = true;
     }
     void mark() {  // boundary between stage next-1 and stage next
-        if (on && next <= call.n_stages) (void)hipEventRecord(call.ev[next++], s);
+        if (on && next <= call.n_stages) {
+            if (!only_conv || next == kConvStage || next == kConvStage + 1) {
+                (void)hipEventRecord(call.ev[next], s);
+                call.recorded |= 1u << next;
+            }
+            ++next;
+        }
     }
     void done() {
         if (!on) return;
-        while (next <= call.n_stages) (void)hipEventRecord(call.ev[next++], s);
+        while (next <= call.n_stages) mark();
         g_prof_calls->push_back(call);
         on = false;
     }
@@ -572,7 +582,8 @@ int scnn_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_st
 }
 
 int scnn_profile_enable(int on) {
-    g_prof_on = on != 0;
+    if (on < 0 || on > 2) return fail(SCNN_EINVAL, "profile mode must be 0, 1 or 2");
+    g_prof_on = on;
     return SCNN_OK;
 }
 
@@ -586,8 +597,13 @@ int scnn_profile_collect(double* stage_ms, int64_t* calls) {
     *calls = 0;
     if (!g_prof_calls) return SCNN_OK;
     for (ProfCall& c : *g_prof_calls) {
-        SCNN_TRY(hipEventSynchronize(c.ev[c.n_stages]));
+        for (int i = c.n_stages; i >= 0; --i)
+            if (c.recorded >> i & 1u) {
+                SCNN_TRY(hipEventSynchronize(c.ev[i]));  // the call's last recorded event
+                break;
+            }
         for (int i = 0; i < c.n_stages; ++i) {
+            if ((c.recorded >> i & 3u) != 3u) continue;  // a stage needs both of its boundaries
             float ms = 0.0f;
             SCNN_TRY(hipEventElapsedTime(&ms, c.ev[i], c.ev[i + 1]));
             stage_ms[c.first_stage + i] += (double)ms;
