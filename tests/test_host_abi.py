@@ -118,6 +118,16 @@ def test_host_argument_checks_of_the_widening_entry_points():
     assert L.prune_weights(fake, fake, 10, ctypes.c_float(0.1), None, None) == -1
 
 
+def test_measurement_switches_reject_unknown_modes():
+    L = scnn.load_library()
+    assert L.scnn_profile_enable(3) == -1 and b"profile mode" in L.scnn_last_error()
+    assert L.scnn_profile_enable(2) == 0 and L.scnn_profile_enable(0) == 0
+    assert L.scnn_set_conv_path(3) == -1 and b"conv path" in L.scnn_last_error()
+    assert L.scnn_set_conv_path(2) == 0 and L.scnn_set_conv_path(0) == 0
+    names = [L.scnn_profile_stage_name(i).decode() for i in range(L.scnn_profile_stage_count())]
+    assert names[3] == "conv" and len(set(names)) == len(names)
+
+
 def test_mac_count_matches_oracle_loop_count():
     from workloads import make_config
     wl = make_config(2, r=16, batch=2)
