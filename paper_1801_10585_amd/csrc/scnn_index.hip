@@ -129,6 +129,28 @@ __global__ __launch_bounds__(256) void k_scan_small(unsigned* __restrict__ vals,
 // up to this many elements one workgroup scans alone: it takes about 2 us per chunk of 2048, three launches 13 us
 constexpr long long kScanSmall = 4 * kScanChunk;
 
+// Second and last step of the scan of up to kScanTwoStep chunks: a block adds up the sums of the chunks before its
+// own by itself (a few thousand numbers at most) instead of waiting for a launch that scans them.
+constexpr long long kScanTwoStep = 4096;
+__global__ __launch_bounds__(256) void k_scan_add_own(unsigned* __restrict__ vals, long long n_imm,
+                                                      const long long* __restrict__ n_dev,
+                                                      const unsigned* __restrict__ block_sums,
+                                                      long long* __restrict__ total_out) {
+    __shared__ unsigned s_wave[4];
+    const long long n = n_dev ? *n_dev : n_imm;
+    unsigned below = 0;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += 256) below += block_sums[i];
+    unsigned add;
+    (void)block_exclusive_scan_256(below, s_wave, add);  // (the total is what is wanted)
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0 && total_out)
+        *total_out = (long long)add + (long long)block_sums[blockIdx.x];
+    if (add == 0) return;
+    const long long base = (long long)blockIdx.x * kScanChunk + (long long)threadIdx.x * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        if (base + i < n) vals[base + i] += add;
+}
+
 hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n_imm, const long long* n_dev,
                                  unsigned* block_sums, long long* total, hipStream_t s) {
     if (capacity <= kScanSmall) {
@@ -138,6 +160,11 @@ hipError_t launch_exclusive_scan(unsigned* vals, long long capacity, long long n
     long long blocks = (capacity + kScanChunk - 1) / kScanChunk;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_scan_local, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums);
+    if (blocks <= kScanTwoStep) {
+        hipLaunchKernelGGL(k_scan_add_own, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums,
+                           total);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(k_scan_top, dim3(1), dim3(256), 0, s, block_sums, blocks, total);
     hipLaunchKernelGGL(k_scan_add, dim3((unsigned)blocks), dim3(256), 0, s, vals, n_imm, n_dev, block_sums);
     return hipGetLastError();
