@@ -1078,8 +1078,9 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
                                long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
-    // at most as many workgroups as can be resident at once (4 per CU by LDS), so that every ticket holder runs
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
+    // no more workgroups than can be resident at once (4 per CU by LDS), so that every ticket holder runs; three per
+    // CU measured best for the wide kernels (cfg 4: 103 us against 107 with four and 110 with two)
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
     // Narrow layers: a ticket covers 1, 2, 4 .. NT_ tiles, the fewest that leave at most one ticket per CU (a small
     // layer is bound by the tickets, taken one at a time, and every workgroup launched takes at least one).
 #define SCNN_NARROW_CASE(CMAX_, NT_)                                                                              \
