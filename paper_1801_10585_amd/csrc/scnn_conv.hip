@@ -774,6 +774,12 @@ __global__ __launch_bounds__(256) void k_conv_valu_small(Geom g, const unsigned 
     }
 }
 
+// Workgroups of the streaming kernel.  About six are resident per CU; a grid of 8 per CU ran a third of them in a
+// second, badly filled round (128^3 stack 2.05 ms, paper runtime shape r = 256: convolution 155 us), 6 per CU fits
+// exactly (2.02 ms, 137 us), and 32 per CU, about one work item per workgroup on these layers, balances best
+// (1.99 ms, 123 us; 64 and 128 per CU the same).
+constexpr int kStreamBlocks = 256 * 32;
+
 // Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
 constexpr long long kValuLatencyItems = 1024;
 // Layers whose workspace holds at most this many work items (a bound the host knows) run the 32-row form.
@@ -813,13 +819,13 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
 #define SCNN_VALU_CASE(CH_)                                                                                          \
     do {                                                                                                             \
         if (both && c_out <= 8)                                                                                      \
-            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 8>), dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix,     \
-                               nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start,    \
-                               tile_start, ctr, kValuLatencyItems, resp);                                            \
+            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 8>), dim3(kStreamBlocks), dim3(256), 0, s, g, occ,           \
+                               occ_prefix, nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin,    \
+                               cand_start, tile_start, ctr, kValuLatencyItems, resp);                                \
         else if (both)                                                                                               \
-            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 16>), dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix,    \
-                               nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start,    \
-                               tile_start, ctr, kValuLatencyItems, resp);                                            \
+            hipLaunchKernelGGL((k_conv_valu_stream<CH_, 16>), dim3(kStreamBlocks), dim3(256), 0, s, g, occ,          \
+                               occ_prefix, nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin,    \
+                               cand_start, tile_start, ctr, kValuLatencyItems, resp);                                \
         hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, \
                            wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,            \
                            kValuLatencyItems, resp);                                                                 \
