@@ -1088,7 +1088,7 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
         int tps = 1;                                                                                              \
         while (tps < NT_ && tiles_cap > 256ll * tps) tps *= 2;                                                    \
         long long nb = (tiles_cap + tps - 1) / tps;                                                               \
-        nb = nb < 1 ? 1 : (nb > 256 * 4 ? 256 * 4 : nb);                                                          \
+        nb = nb < 1 ? 1 : (nb > 256 * 3 ? 256 * 3 : nb);                                                          \
         hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)nb), dim3(256), 0, s, g, channels, \
                            mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, \
                            out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);                          \
