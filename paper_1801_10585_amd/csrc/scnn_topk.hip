@@ -1081,12 +1081,13 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
     // no more workgroups than can be resident at once (4 per CU by LDS), so that every ticket holder runs; three per
     // CU measured best for the wide kernels (cfg 4: 103 us against 107 with four and 110 with two)
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
-    // Narrow layers: a ticket covers 1, 2, 4 .. NT_ tiles, the fewest that leave at most one ticket per CU (a small
-    // layer is bound by the tickets, taken one at a time, and every workgroup launched takes at least one).
+    // Narrow layers: a ticket covers 1, 2, 4 .. NT_ tiles, the fewest that leave at most two tickets per CU (a small
+    // layer is bound by the tickets, taken one at a time, and every workgroup launched takes at least one; one per
+    // CU and four per CU both measured slower on the paper's networks).
 #define SCNN_NARROW_CASE(CMAX_, NT_)                                                                              \
     do {                                                                                                          \
         int tps = 1;                                                                                              \
-        while (tps < NT_ && tiles_cap > 256ll * tps) tps *= 2;                                                    \
+        while (tps < NT_ && tiles_cap > 512ll * tps) tps *= 2;                                                    \
         long long nb = (tiles_cap + tps - 1) / tps;                                                               \
         nb = nb < 1 ? 1 : (nb > 256 * 3 ? 256 * 3 : nb);                                                          \
         hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)nb), dim3(256), 0, s, g, channels, \
