@@ -81,6 +81,8 @@ __global__ __launch_bounds__(256) void k_bwd_data_write(Geom g, const float* __r
                                                         float* __restrict__ bp_data) {
     __shared__ float s_t[kTileRows][65];
     const int n_tiles = (int)ctr->n_tiles;
+    // rows of x and bp_data start on 16-byte boundaries
+    const bool vec4 = (c_in & 3) == 0 && ((((size_t)x) | ((size_t)bp_data)) & 15) == 0;
     for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
@@ -94,10 +96,25 @@ __global__ __launch_bounds__(256) void k_bwd_data_write(Geom g, const float* __r
                 s_t[r][c] = resp[((size_t)tile * c_in + cc + c) * kTileRows + r];
             }
             __syncthreads();
-            for (int i = threadIdx.x; i < nrows * cw; i += 256) {
-                const int r = i / cw, c = i - r * cw;
-                const size_t at = (size_t)(first + r) * c_in + cc + c;
-                bp_data[at] = (x[at] != 0.0f) ? s_t[r][c] : 0.0f;
+            if (vec4) {  // four channels per thread: 16-byte loads of x and stores of bp_data
+                const int q = cw >> 2;
+                for (int i = threadIdx.x; i < nrows * q; i += 256) {
+                    const int r = i / q, c = (i - r * q) * 4;
+                    const size_t at = (size_t)(first + r) * c_in + cc + c;
+                    const float4 xv = *reinterpret_cast<const float4*>(x + at);
+                    float4 o;
+                    o.x = xv.x != 0.0f ? s_t[r][c] : 0.0f;
+                    o.y = xv.y != 0.0f ? s_t[r][c + 1] : 0.0f;
+                    o.z = xv.z != 0.0f ? s_t[r][c + 2] : 0.0f;
+                    o.w = xv.w != 0.0f ? s_t[r][c + 3] : 0.0f;
+                    *reinterpret_cast<float4*>(bp_data + at) = o;
+                }
+            } else {
+                for (int i = threadIdx.x; i < nrows * cw; i += 256) {
+                    const int r = i / cw, c = i - r * cw;
+                    const size_t at = (size_t)(first + r) * c_in + cc + c;
+                    bp_data[at] = (x[at] != 0.0f) ? s_t[r][c] : 0.0f;
+                }
             }
         }
     }
