@@ -154,6 +154,41 @@ __global__ __launch_bounds__(256) void k_pool_gather(Geom g, Geom gp, const unsi
     long long n_out = ctr->n_pool;
     if (n_out > pool_cap) n_out = pool_cap;
     if (n_out > out_capacity) n_out = out_capacity;
+    // four channels per thread where the rows allow 16-byte accesses: a quarter of the child look-ups
+    if ((channels & 3) == 0 && ((((size_t)feats) | ((size_t)out_feats)) & 15) == 0) {
+        const int q = channels >> 2;
+        const long long total4 = n_out * q;
+        for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total4;
+             i += (long long)gridDim.x * blockDim.x) {
+            const long long o = i / q;
+            const int c = (int)(i - o * q) * 4;
+            const long long key = pool_key[o];
+            const int b = (int)(key / gp.Npad);
+            int p0, p1, p2;
+            site_of(gp, key - (long long)b * gp.Npad, p0, p1, p2);
+            float best[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            bool present[4] = {false, false, false, false};
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                const int row = lookup_row(g, occ, occ_prefix, n_in, b, 2 * p0 + (d >> 2), 2 * p1 + ((d >> 1) & 1),
+                                           2 * p2 + (d & 1));
+                if (row < 0) continue;
+                const float4 v4 = *reinterpret_cast<const float4*>(feats + (size_t)row * channels + c);
+                const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (v[j] == 0.0f) continue;
+                    best[j] = present[j] ? fmaxf(best[j], v[j]) : v[j];
+                    present[j] = true;
+                }
+            }
+            *reinterpret_cast<float4*>(out_feats + o * channels + c) =
+                make_float4(present[0] ? best[0] : 0.0f, present[1] ? best[1] : 0.0f, present[2] ? best[2] : 0.0f,
+                            present[3] ? best[3] : 0.0f);
+            if (c == 0) store_site(gp, out_coords + o * (1 + gp.ndim), b, p0, p1, p2);
+        }
+        return;
+    }
     const long long total = n_out * channels;
     for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total;
          i += (long long)gridDim.x * blockDim.x) {
