@@ -149,6 +149,22 @@ int sparse_relu(int ndim, const int32_t* coords, const float* feats, int64_t row
                 int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t* nnz_out, void* workspace,
                 size_t workspace_bytes, void* hip_stream);
 
+/* sparse_relu for callers that cannot allocate device memory or hold a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation.  Same kernels and same results as sparse_relu; the scratch
+ * (counters, one flag and one offset per row, scan sums: about 8 MiB) is a
+ * device array inside the library image, held by every GPU the library runs on
+ * until the process ends.  At most sparse_relu_static_max_rows() (2^20) rows:
+ * more returns SCNN_ECAPACITY and does nothing.  The call allocates and frees
+ * nothing, issues no memset node and does not synchronise.  All calls on one
+ * GPU share that GPU's array: calls that overlap on one GPU (different streams
+ * or host threads) race -- serialise them.  Inputs and outputs are the caller's
+ * device arrays as for sparse_relu. */
+int64_t sparse_relu_static_max_rows(void);
+int sparse_relu_static(int ndim, const int32_t* coords, const float* feats, int64_t rows, int channels,
+                       int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t* nnz_out,
+                       void* hip_stream);
+
 /* Sparse max-pooling (Sec. 3.3): output site = floor(p / window), output extent
  * = ceil(extent / window), maximum over the present entries of each cluster,
  * per channel.  window == stride; only window = 2 is implemented. */

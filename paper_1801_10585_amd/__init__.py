@@ -31,6 +31,8 @@ from .binding import (  # noqa: F401
     sparse_conv_fwd_workspace,
     sparse_maxpool,
     sparse_relu,
+    sparse_relu_static,
+    sparse_relu_static_max_rows,
     sparse_to_dense,
     validate_rows,
     EXPORTED_SYMBOLS,

@@ -23,6 +23,7 @@ EXPORTED_SYMBOLS = [
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
     "sparse_conv_bwd_workspace", "sparse_conv_bwd", "sparse_to_dense",
     "density_regulariser_workspace", "density_regulariser", "prune_weights", "sparse_conv_fwd_chained",
+    "sparse_relu_static_max_rows", "sparse_relu_static",
 ]
 
 
@@ -71,6 +72,10 @@ def load_library():
     L.sparse_relu_workspace.argtypes = [i64, ci]
     L.sparse_relu.restype = ci
     L.sparse_relu.argtypes = [ci, vp, vp, i64, ci, vp, vp, i64, vp, vp, sz, vp]
+    L.sparse_relu_static_max_rows.restype = i64
+    L.sparse_relu_static_max_rows.argtypes = []
+    L.sparse_relu_static.restype = ci
+    L.sparse_relu_static.argtypes = [ci, vp, vp, i64, ci, vp, vp, i64, vp, vp]
     L.sparse_maxpool_workspace.restype = sz
     L.sparse_maxpool_workspace.argtypes = [ci, i32p, ci, i64, ci]
     L.sparse_maxpool.restype = ci
@@ -360,6 +365,21 @@ def sparse_relu(ndim, coords, feats, *, out_capacity=None, workspace=None, strea
                        int(out_capacity), _ptr(nnz), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(L, rc)
     return _finish(out_coords, out_feats, nnz, sync)
+
+
+def sparse_relu_static_max_rows() -> int:
+    return int(load_library().sparse_relu_static_max_rows())
+
+
+def sparse_relu_static(ndim, coords, feats, out_coords, out_feats, nnz, *, stream=None):
+    """sparse_relu on the library's own scratch array: every buffer is the caller's, nothing is allocated here."""
+    L = load_library()
+    coords = _dev(coords, torch.int32, "coords")
+    feats = _dev(feats, torch.float32, "feats")
+    rows, ch = feats.shape
+    rc = L.sparse_relu_static(int(ndim), _ptr(coords), _ptr(feats), rows, ch, _ptr(out_coords), _ptr(out_feats),
+                              int(out_feats.shape[0]), _ptr(nnz), _stream(stream))
+    _check(L, rc)
 
 
 def sparse_maxpool(extent, batch, coords, feats, window=2, *, out_capacity=None, workspace=None, stream=None,

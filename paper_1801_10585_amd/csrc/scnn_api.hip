@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "scnn_internal.h"
@@ -730,6 +731,79 @@ int sparse_relu(int ndim, const int32_t* coords, const float* feats, int64_t row
     g.ndim = ndim;
     hipStream_t s = (hipStream_t)hip_stream;
     SCNN_TRY(launch_zero(workspace, zero_bytes, s));
+    SCNN_TRY(launch_relu(g, coords, feats, rows, channels, flags, offs, block_sums, out_coords, out_feats,
+                         out_capacity, ctr, s));
+    SCNN_TRY(launch_finish(ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
+    return SCNN_OK;
+}
+
+// ---------------------------------------------------------------- sparse_relu without a workspace
+// The same kernels as sparse_relu; the counters, row flags, row offsets and scan sums live in a device array
+// that is part of the library image instead of a caller's workspace.  Each GPU holds its own copy of the array at
+// its own address: the address is looked up once per device, with that device current, and only that address
+// (never the array's name) is handed to kernels.
+namespace {
+constexpr long long kStaticReluMaxRows = 1ll << 20;
+constexpr size_t kStaticReluBytes = 256                                                      // Counters
+                                    + 2 * (size_t)kStaticReluMaxRows * sizeof(unsigned)      // flags, offsets
+                                    + (((size_t)kStaticReluMaxRows / kScanChunk + 2) * sizeof(unsigned) + 255) / 256 * 256;
+constexpr int kMaxDevices = 64;
+}  // namespace
+static __device__ __align__(256) unsigned char scratch[kStaticReluBytes];
+namespace {
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+int static_scratch(void** out) {
+    int dev = -1;
+    SCNN_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(SCNN_ECAPACITY, "device ordinal %d not supported (at most %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        SCNN_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p || ((uintptr_t)p & 255) != 0) return fail(SCNN_EHIP, "static scratch array has no usable device address");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return SCNN_OK;
+}
+}  // namespace
+
+int64_t sparse_relu_static_max_rows(void) { return kStaticReluMaxRows; }
+
+int sparse_relu_static(int ndim, const int32_t* coords, const float* feats, int64_t rows, int channels,
+                       int32_t* out_coords, float* out_feats, int64_t out_capacity, int64_t* nnz_out,
+                       void* hip_stream) {
+    if (ndim != 2 && ndim != 3) return fail(SCNN_EINVAL, "ndim must be 2 or 3 (got %d)", ndim);
+    if (rows < 0) return fail(SCNN_EINVAL, "rows < 0");
+    if (rows > kStaticReluMaxRows)
+        return fail(SCNN_ECAPACITY, "sparse_relu_static takes at most %lld rows (got %lld): use sparse_relu with a workspace",
+                    kStaticReluMaxRows, (long long)rows);
+    if (channels < 1) return fail(SCNN_EINVAL, "channels must be positive");
+    if (channels > kMaxChannels) return fail(SCNN_ECAPACITY, "at most %d channels", kMaxChannels);
+    if (!nnz_out) return fail(SCNN_EINVAL, "nnz_out is null");
+    if (rows > 0 && (!coords || !feats)) return fail(SCNN_EINVAL, "null input arrays");
+    if (out_capacity < 0 || out_capacity > kMaxIndex) return fail(SCNN_EINVAL, "bad out_capacity");
+    if (out_capacity > 0 && (!out_coords || !out_feats)) return fail(SCNN_EINVAL, "null output arrays");
+    void* base = nullptr;
+    int rc = static_scratch(&base);
+    if (rc != SCNN_OK) return rc;
+    Carver c(base);
+    Counters* ctr = c.take<Counters>(1);
+    const size_t zero_bytes = c.total();
+    unsigned* flags = c.take<unsigned>(kStaticReluMaxRows);
+    unsigned* offs = c.take<unsigned>(kStaticReluMaxRows);
+    unsigned* block_sums = c.take<unsigned>(scan_blocks(kStaticReluMaxRows));
+    if (c.total() > kStaticReluBytes) return fail(SCNN_EWORKSPACE, "static scratch layout exceeds the array");
+    Geom g;
+    memset(&g, 0, sizeof(g));
+    g.ndim = ndim;
+    hipStream_t s = (hipStream_t)hip_stream;
+    // the array keeps the previous call's contents: the counters start from zero through a fill kernel (no memset
+    // node, so the call can be captured); flags and offsets of rows [0, rows) are rewritten before they are read
+    SCNN_TRY(launch_zero(base, zero_bytes, s));
     SCNN_TRY(launch_relu(g, coords, feats, rows, channels, flags, offs, block_sums, out_coords, out_feats,
                          out_capacity, ctr, s));
     SCNN_TRY(launch_finish(ctr, 0, rows, 0, out_capacity, (long long*)nnz_out, s));
