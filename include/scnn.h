@@ -238,8 +238,13 @@ int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t
  * matrix-core kernels (C_out a multiple of 32 up to 128, C_in a multiple of 16
  * up to 64, 16-byte aligned value arrays) first add up to 32 products (bp_data)
  * or the at most 128 products of one tap within one 128-row tile (bp_filter) in
- * fp32.  bp_filter adds its partial sums in a fixed order: repeated calls give
- * identical bits.  info (device, int64[SCNN_NNZ_LEN]) receives {nnz_in, g_rows,
+ * fp32.  Error bound of the matrix-core kernels: with A the sum of the
+ * magnitudes of the products behind an element, |result - exact| <=
+ * 1e-5 |exact| + 1e-6 + c A with c = 2e-8 for bp_data and 1e-7 for bp_filter
+ * (a third of, resp. 1.7 times, the fp32 unit roundoff 2^-24: the fp32 chains
+ * leave an error proportional to A, not to the cancelling result); the vector
+ * kernels meet 1e-5 |exact| + 1e-6 alone.  bp_filter adds its partial sums in
+ * a fixed order: repeated calls give identical bits.  info (device, int64[SCNN_NNZ_LEN]) receives {nnz_in, g_rows,
  * SCNN_FLAG_* bits, 0}; with SCNN_FLAG_BAD_COORD or SCNN_FLAG_UNSORTED set the
  * results are undefined (all accesses stay in bounds).  All array arguments are
  * device pointers; extent and ksize are host pointers.  Asynchronous on

@@ -33,6 +33,18 @@ def gpu_conv(extent, batch, coords, feats, ksize, w, bias=None, **kw):
     return host(c), host(f), n
 
 
+def oracle_responses(extent, coords, feats, ksize, w, bias, b, ocs, threads=16):
+    """Every response of sample b on the output channels `ocs`, before the selection: the oracle's rows (sample index
+    0) and values [rows, len(ocs)]; a row is listed when any of these channels is non-zero there."""
+    sel = coords[:, 0] == b
+    cb = coords[sel].copy()
+    cb[:, 0] = 0
+    ocs = list(ocs)
+    return oracle.sparse_conv_fwd(extent, 1, cb, feats[sel], ksize, np.ascontiguousarray(w[:, :, ocs]),
+                                  None if bias is None else np.ascontiguousarray(bias[ocs]), resp_only=True,
+                                  threads=threads)
+
+
 def _close_column(got, want, where):
     """Same coordinate set, values within the layer's tolerance."""
     (gl, gv), (wl_, wv) = got, want
@@ -66,30 +78,33 @@ def check_conv_against_oracle(extent, batch, coords, feats, ksize, w, bias, k, r
     if columns is None:
         columns = [(b, oc) for b in range(batch) for oc in range(c_out)]
     band_total = 0
-    for (b, oc) in columns:
-        sel = coords[:, 0] == b
-        cb = coords[sel].copy()
-        cb[:, 0] = 0
-        rc, rf = oracle.sparse_conv_fwd(extent, 1, cb, feats[sel], ksize, w[:, :, oc:oc + 1],
-                                        None if bias is None else bias[oc:oc + 1], resp_only=True)
-        all_lin, all_val = lin_index(rc, extent), rf[:, 0]
-        got_lin, got_val = column(gc, gf, extent, b, oc)
-        where = f"{tag} (b={b}, oc={oc})"
-        band = check_column(all_lin, all_val, got_lin, got_val, k, mode, where=where)
-        band_total += band
-        assert len(got_lin) <= k
-        if band or (np.abs(all_val) <= ATOL).any():
-            continue
-        kc, kf = oracle.attention_topk(extent, 1, rc, rf, k, mode)     # the oracle's own selection
-        rco, rfo = oracle.sparse_relu(extent, kc, kf)
-        for (relu, pool), (fc, ff) in fused.items():
-            ec, ef = (rco, rfo) if relu else (kc, kf)
-            ext_o = extent
-            if pool:
-                ec, ef = oracle.sparse_maxpool(extent, ec, ef)
-                ext_o = ext_p
-            _close_column(column(fc, ff, ext_o, b, oc), (lin_index(ec, ext_o), ef[:, 0]),
-                          f"{where} relu={relu} pool={pool}")
+    for b in sorted({b for (b, _) in columns}):
+        ocs = sorted(oc for (bb, oc) in columns if bb == b)
+        # the oracle's responses of this sample, all wanted channels in one (threaded) run
+        rc_all, rf_all = oracle_responses(extent, coords, feats, ksize, w, bias, b, ocs)
+        lin_all = lin_index(rc_all, extent)
+        for j, oc in enumerate(ocs):
+            nz = rf_all[:, j] != 0
+            rc, rf = np.ascontiguousarray(rc_all[nz]), np.ascontiguousarray(rf_all[nz, j:j + 1])
+            all_lin, all_val = lin_all[nz], rf[:, 0]
+            got_lin, got_val = column(gc, gf, extent, b, oc)
+            where = f"{tag} (b={b}, oc={oc})"
+            band = check_column(all_lin, all_val, got_lin, got_val, k, mode, where=where)
+            band_total += band
+            assert len(got_lin) <= k
+            # (the k-th entry itself always lies in the band: more than one entry there makes the selection ambiguous)
+            if band > 1 or (np.abs(all_val) <= ATOL).any():
+                continue
+            kc, kf = oracle.attention_topk(extent, 1, rc, rf, k, mode)     # the oracle's own selection
+            rco, rfo = oracle.sparse_relu(extent, kc, kf)
+            for (relu, pool), (fc, ff) in fused.items():
+                ec, ef = (rco, rfo) if relu else (kc, kf)
+                ext_o = extent
+                if pool:
+                    ec, ef = oracle.sparse_maxpool(extent, ec, ef)
+                    ext_o = ext_p
+                _close_column(column(fc, ff, ext_o, b, oc), (lin_index(ec, ext_o), ef[:, 0]),
+                              f"{where} relu={relu} pool={pool}")
     # fused variants against the library's own standalone operators (no oracle involved): bit-exact
     dgc, dgf = dev(gc), dev(gf)
     rcs, rfs, _ = scnn.sparse_relu(len(extent), dgc, dgf)
@@ -316,7 +331,7 @@ def test_config3_two_layers_full_size():
     k1 = scnn.k_from_rho(L1.rho_up, 64 ** 3)
     say(f"cfg3 layer 1 rows={wl.coords.shape[0]} k={k1}")
     check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L1.ksize, wl.filters[0], None, k1, L1.rho_up,
-                              scnn.ABS, columns=_sampled_columns(rng, wl.batch, L1.c_out, 12), tag="cfg3-L1")
+                              scnn.ABS, tag="cfg3-L1")
     # layer 2 takes the ORACLE's layer-1 output (conv + attention + ReLU + pool) as the input of both sides
     c1, f1 = oracle.sparse_conv_fwd(wl.extent, wl.batch, wl.coords, wl.feats, L1.ksize, wl.filters[0], k=k1,
                                     relu=True, pool=True, threads=16)
@@ -324,7 +339,7 @@ def test_config3_two_layers_full_size():
     k2 = scnn.k_from_rho(L2.rho_up, 32 ** 3)
     say(f"cfg3 layer 2 rows={c1.shape[0]} k={k2}")
     check_conv_against_oracle(ext2, wl.batch, c1, f1, L2.ksize, wl.filters[1], None, k2, L2.rho_up, scnn.ABS,
-                              columns=_sampled_columns(rng, wl.batch, L2.c_out, 12), tag="cfg3-L2")
+                              tag="cfg3-L2")
     # the library's own two-layer chain: well-formed, within the density bound, and close to the oracle's chain
     g1c, g1f, _ = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L1.ksize, wl.filters[0], rho_up=L1.rho_up,
                            relu=True, pool=True)
@@ -338,38 +353,50 @@ def test_config3_two_layers_full_size():
     assert abs(g1c.shape[0] - c1.shape[0]) <= 0.001 * c1.shape[0]
 
 
-def test_config4_r128_dense_filter_full_size_sampled_columns():
+def test_config4_r128_dense_filter_full_size_every_column():
     wl = make_config(4)
     L = wl.layers[0]
-    rng = np.random.default_rng(4)
     k = scnn.k_from_rho(L.rho_up, 128 ** 3)
     say(f"cfg4 rows={wl.coords.shape[0]} k={k}")
     gc, gf, band = check_conv_against_oracle(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], None, k,
-                                             L.rho_up, scnn.ABS, columns=_sampled_columns(rng, wl.batch, L.c_out, 10),
-                                             tag="cfg4")
+                                             L.rho_up, scnn.ABS, tag="cfg4")
     say(f"cfg4 out rows={gc.shape[0]} band entries={band}")
     for b in range(wl.batch):
         assert ((gf[gc[:, 0] == b] != 0).sum(axis=0) <= k).all()
 
 
+_CFG5 = {}
+
+
+def _cfg5_oracle_responses():
+    """The oracle's responses of cfg 5 on all 64 channels, computed once for the three rho_up values."""
+    if not _CFG5:
+        wl = make_config(5)
+        L = wl.layers[0]
+        say(f"cfg5 oracle: rows={wl.coords.shape[0]} (threaded, all {L.c_out} channels)")
+        rc, rf = oracle_responses(wl.extent, wl.coords, wl.feats, L.ksize, wl.filters[0], None, 0, range(L.c_out))
+        _CFG5.update(wl=wl, lin=lin_index(rc, wl.extent), resp=rf)
+    return _CFG5["wl"], _CFG5["lin"], _CFG5["resp"]
+
+
 @pytest.mark.parametrize("rho", [0.02, 0.05, 0.10])
-def test_config5_r256_5x5x5_full_size_sampled_columns(rho):
-    wl = make_config(5)
+def test_config5_r256_5x5x5_full_size_every_column(rho):
+    wl, all_lin, all_resp = _cfg5_oracle_responses()
     L = wl.layers[0]
-    rng = np.random.default_rng(5)
     k = scnn.k_from_rho(rho, 256 ** 3)
     say(f"cfg5 rows={wl.coords.shape[0]} rho={rho} k={k}")
     gc, gf, n = gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=rho)
     assert int(n[2]) == 0
     assert_rows_well_formed(gc, gf, wl.extent, wl.batch)
     assert ((gf != 0).sum(axis=0) <= k).all()
-    for (b, oc) in _sampled_columns(rng, 1, L.c_out, 3):
-        rc, rf = oracle.sparse_conv_fwd(wl.extent, 1, wl.coords, wl.feats, L.ksize, wl.filters[0][:, :, oc:oc + 1],
-                                        resp_only=True)
-        got_lin, got_val = column(gc, gf, wl.extent, b, oc)
-        band = check_column(lin_index(rc, wl.extent), rf[:, 0], got_lin, got_val, k, scnn.ABS,
-                            where=f"cfg5 rho={rho} oc={oc}")
-        say(f"cfg5 rho={rho} oc={oc} kept={len(got_lin)} band={band}")
+    got_lin_all = lin_index(gc, wl.extent)
+    band_total = 0
+    for oc in range(L.c_out):
+        nz = all_resp[:, oc] != 0
+        gnz = gf[:, oc] != 0
+        band_total += check_column(all_lin[nz], all_resp[nz, oc], got_lin_all[gnz], gf[gnz, oc], k, scnn.ABS,
+                                   where=f"cfg5 rho={rho} oc={oc}")
+    say(f"cfg5 rho={rho} out rows={gc.shape[0]} band entries={band_total}")
 
 
 # ------------------------------------------------------------------ the paper's runtime experiment (Sec. 4.1)
