@@ -204,6 +204,9 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (Algorithm 2) of the same layer instead; not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--conv-path", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="convolution kernel family (scnn_set_conv_path): 0 the library's choice (the headline), "
+                         "1 vector kernels, 2 matrix cores wherever possible, 3 the pair-list matrix-core kernel")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB streaming copy (for scaling rocprofv3 memory counters)")
     args = ap.parse_args()
@@ -221,6 +224,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     dev = torch.device("cuda:0")
+    scnn.set_conv_path(args.conv_path)
     if args.stack:
         return bench_stack(args)
     wl = make_paper_runtime(args.paper_runtime, args.rho_f) if args.paper_runtime else make_config(args.config)
@@ -304,12 +308,11 @@ def main():
             traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
-    # (the library's own rule: matrix-core kernel for C_in % 32 == 0, or C_in == 16 on a large layer with C_out >= 32)
-    mfma_shape = (c_in % 32 == 0 and c_in <= 128) or (c_in == 16 and c_out >= 32 and n_cand / 128 + wl.batch > 1280)
-    conv_kernel = "k_conv_mfma" if (mfma_shape and c_out % 16 == 0 and c_out <= 64) else "k_conv_valu"
+    conv_kernel = scnn.last_conv_kernel()   # what the library launched, by its own rule
+    on_matrix_cores = conv_kernel in ("k_conv_quad", "k_conv_mfma")
     # the matrix-core kernel is priced against the fp32 MFMA peak, the vector kernel (fp64 FMA) against the fp64
     # vector peak
-    conv_peak = PEAK_MFMA_FP32_TFLOPS if conv_kernel == "k_conv_mfma" else PEAK_FP64_VECTOR_TFLOPS
+    conv_peak = PEAK_MFMA_FP32_TFLOPS if on_matrix_cores else PEAK_FP64_VECTOR_TFLOPS
     line = {
         "metric": "effective non-zero GMAC/s of sparse conv+attention; % of HBM roofline",
         "value": gmacs, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -319,7 +322,7 @@ def main():
                    "ksize": list(layer.ksize), "filter_density": layer.filter_density, "rho_up": layer.rho_up,
                    "relu": layer.relu, "pool": layer.pool, "rows_in": int(nnz_in), "candidate_sites": n_cand,
                    "rows_out": rows_out, "mac_nz": int(mac_nz), "input_density": wl.density, "seed": wl.seed},
-        "roofline": {"bound": "mfma" if conv_kernel == "k_conv_mfma" else "alu", "kernel": conv_kernel,
+        "roofline": {"bound": "mfma" if on_matrix_cores else "alu", "kernel": conv_kernel,
                      "achieved": conv_tflops, "peak": conv_peak, "unit": "TFLOP/s", "frac": conv_tflops / conv_peak,
                      "traffic": traffic,
                      "kernel_ms": conv_ms, "flops_per_launch": 2 * int(mac_nz)},

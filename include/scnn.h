@@ -93,13 +93,14 @@ size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int
  *                   w[tap(delta), ic, oc] * in[b, p + delta, ic]
  * (stride 1, zero "same" padding: an input at q updates p = q - delta, updates
  * leaving the grid are dropped -- Alg. 1 steps 5-9).  Inputs, weights and
- * responses are fp32; each response is summed in fp64 (the matrix-core kernel
- * sums 32 products at a time in fp32 first) and rounded to fp32 once.  The
- * vector kernel adds in a fixed order and is reproducible bit for bit; the
- * matrix-core kernel adds the per-tap partial sums to its fp64 accumulators
- * with LDS atomics in no fixed order, so a run can differ from another in the
- * last bits of the fp64 sum, which survives the rounding to fp32 for about one
- * response in 10^8.  Responses that are exactly 0 are
+ * responses are fp32; each response is summed in fp64 (the matrix-core kernels
+ * sum the at most 32 products of one tap and 32-channel chunk in fp32 first)
+ * and rounded to fp32 once.  The vector kernels and the quad matrix-core kernel
+ * add in an order fixed by the data alone and are reproducible bit for bit; the
+ * pair-list matrix-core kernel (C_in = 96 or 128 only, unless forced) adds its
+ * per-tap partial sums with LDS atomics in no fixed order, so a run can differ
+ * from another in the last bits of the fp64 sum, which survives the rounding
+ * to fp32 for about one response in 10^8.  Responses that are exactly 0 are
  * not entries (step 13).  bias (nullable, device, [c_out]) is added to the
  * entries (step 14); an entry whose biased value is exactly 0 stops being one.
  * Per (sample b, output channel oc) only the k = scnn_k_from_rho(rho_up, N)
@@ -256,14 +257,24 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
                     const int32_t* g_coords, const float* g_feats, int64_t g_rows, float* bp_data, float* bp_filter,
                     int64_t* info, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* Kernel choice for the convolution step of sparse_conv_fwd, process-wide:
- * 0 = by shape and size (matrix-core kernel when C_in is a multiple of 32 up to
- * 128, or 16 on a large layer with C_out >= 32, and C_out a multiple of 16 up
- * to 64; else the vector kernel), 1 = always the vector kernel, 2 = the
- * matrix-core kernel whenever the shape allows it, whatever the size.  All
- * compute the same sums to the same rounding rule; the switch exists so that
- * tests and measurements can reach each.  The setting enters the workspace
- * size: query the workspace under the setting the call will run with. */
+/* Kernel choice for the convolution step of sparse_conv_fwd (and, for 1, of
+ * sparse_conv_bwd), for the calling thread:
+ * 0 = by shape and size: the quad matrix-core kernel (C_in in {8, 16, 24, 32,
+ *     40, 48, 64}, up to 64 output channels, at most 32 taps, 16-byte aligned
+ *     in_feats; with C_in < 32 only on large layers with C_out >= 32), the
+ *     pair-list matrix-core kernel for C_in = 96 or 128 (C_out a multiple of 16
+ *     up to 64), else the vector kernels;
+ * 1 = always the vector kernels;
+ * 2 = a matrix-core kernel whenever one takes the shape, whatever the size;
+ * 3 = the pair-list matrix-core kernel where it takes the shape (C_in = 16 or
+ *     a multiple of 32 up to 128, C_out a multiple of 16 up to 64).
+ * All compute the same sums to the same rounding rule; the switch exists so
+ * that tests and measurements can reach each.  The setting enters the
+ * workspace size: query the workspace under the setting the call will run with.
+ * scnn_last_conv_kernel() names the kernel family the calling thread's last
+ * sparse_conv_fwd call launched ("k_conv_quad", "k_conv_mfma", "k_conv_valu";
+ * "" before the first call). */
+const char* scnn_last_conv_kernel(void);
 int scnn_set_conv_path(int path);
 
 /* Measurement support (not part of the method): when enabled on the calling

@@ -24,6 +24,7 @@ from .binding import (  # noqa: F401
     profile_enable,
     load_library,
     set_conv_path,
+    last_conv_kernel,
     sparse_conv_bwd,
     sparse_conv_bwd_workspace,
     sparse_conv_fwd,

@@ -23,7 +23,7 @@ EXPORTED_SYMBOLS = [
     "scnn_profile_stage_count", "scnn_set_conv_path", "scnn_calibration_copy", "scnn_profile_stage_name", "scnn_profile_collect",
     "sparse_conv_bwd_workspace", "sparse_conv_bwd", "sparse_to_dense",
     "density_regulariser_workspace", "density_regulariser", "prune_weights", "sparse_conv_fwd_chained",
-    "sparse_relu_static_max_rows", "sparse_relu_static",
+    "sparse_relu_static_max_rows", "sparse_relu_static", "scnn_last_conv_kernel",
 ]
 
 
@@ -95,6 +95,8 @@ def load_library():
     L.scnn_validate_rows.argtypes = [ci, i32p, ci, vp, i64, vp, sz, vp]
     L.scnn_calibration_copy.restype = ci
     L.scnn_calibration_copy.argtypes = [vp, vp, sz, vp]
+    L.scnn_last_conv_kernel.restype = ctypes.c_char_p
+    L.scnn_last_conv_kernel.argtypes = []
     L.scnn_set_conv_path.restype = ci
     L.scnn_set_conv_path.argtypes = [ci]
     L.scnn_profile_enable.restype = ci
@@ -478,10 +480,15 @@ def profile_collect():
 
 
 def set_conv_path(path: int) -> None:
-    """0 = choose the convolution kernel by shape and size, 1 = always the vector kernel, 2 = the matrix-core kernel
-    whenever the shape allows it."""
+    """0 = choose the convolution kernel by shape and size, 1 = always the vector kernels, 2 = a matrix-core kernel
+    whenever one takes the shape, 3 = the pair-list matrix-core kernel where it takes the shape."""
     L = load_library()
     _check(L, L.scnn_set_conv_path(int(path)))
+
+
+def last_conv_kernel() -> str:
+    """Kernel family launched by this thread's last sparse_conv_fwd call."""
+    return load_library().scnn_last_conv_kernel().decode()
 
 
 def calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

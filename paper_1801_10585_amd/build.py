@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscnn.so")
-SOURCES = ["scnn_index.hip", "scnn_conv.hip", "scnn_topk.hip", "scnn_rows.hip", "scnn_bwd.hip", "scnn_train.hip", "scnn_api.hip"]
+SOURCES = ["scnn_index.hip", "scnn_conv.hip", "scnn_conv_quad.hip", "scnn_topk.hip", "scnn_rows.hip", "scnn_bwd.hip", "scnn_train.hip", "scnn_api.hip"]
 # packed fp32 VALU ops are switched off on purpose (they have misbehaved on the target machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument",

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument checks, workspace layout, launch sequences.
 // Nothing here touches values; every step of the layer runs in the kernels.
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -12,16 +13,27 @@
 namespace scnn {
 
 static thread_local char g_err[256] = "";
-static int g_conv_path = 0;  // 0 = choose by shape and size, 1 = always the vector kernel, 2 = matrix cores if possible
+// Kernel family of the convolution step, per calling thread:
+// 0 = by shape and size, 1 = always the vector kernels, 2 = matrix cores wherever a matrix-core kernel takes the shape,
+// 3 = the pair-list matrix-core kernel where it takes the shape (else the vector kernels).
+static thread_local int g_conv_path = 0;
+static thread_local const char* g_last_conv_kernel = "";
 
-// Whether the forward convolution of this shape runs on the fp32 matrix cores.  With sixteen input channels the
-// pair lists pay only on large layers with at least 32 output channels (cfg 3 layer 1: 0.22 -> 0.15 ms including
-// the lists; the 16 -> 16 layers of the paper's networks are faster on the vector kernels).
-static bool conv_uses_mfma(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
-    if (g_conv_path == 1 || !conv_mfma_supported(g, c_in, c_out, nnz_in)) return false;
-    if (g_conv_path == 2) return true;
-    if (c_in == 16) return c_out >= 32 && tiles_cap > 1280;
-    return true;
+enum class ConvKernel { kValu, kPair, kQuad };
+
+// Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
+// 64 output channels with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With sixteen
+// input channels the matrix cores pay only on large layers with at least 32 output channels; narrower layers are
+// faster on the vector kernels.
+static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
+    if (g_conv_path == 1) return ConvKernel::kValu;
+    const bool pair_ok = conv_mfma_supported(g, c_in, c_out, nnz_in);
+    if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
+    const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
+    if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
+    if (pair_ok && (c_in >= 32 || (c_in == 16 && c_out >= 32 && tiles_cap > 1280))) return ConvKernel::kPair;
+    (void)quad_ok;
+    return ConvKernel::kValu;
 }
 
 static int fail(int code, const char* fmt, ...) {
@@ -41,6 +53,21 @@ static int fail_hip(hipError_t e, const char* what) {
         hipError_t e__ = (expr);                               \
         if (e__ != hipSuccess) return fail_hip(e__, #expr);    \
     } while (0)
+
+// Compute units of the current device, asked once per device.
+static int device_cus(int* cus) {
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    SCNN_TRY(hipGetDevice(&dev));
+    int n = (dev >= 0 && dev < 64) ? cache[dev].load(std::memory_order_relaxed) : 0;
+    if (n <= 0) {
+        SCNN_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
+        if (n < 1) n = 1;
+        if (dev >= 0 && dev < 64) cache[dev].store(n, std::memory_order_relaxed);
+    }
+    *cus = n;
+    return SCNN_OK;
+}
 
 static constexpr long long kMaxIndex = 0x7fffffffLL;  // rows, candidates and sites use 31-bit indices
 static constexpr int kMaxChannels = 1024;
@@ -205,8 +232,10 @@ struct ConvWs {
     unsigned* pairs;
     unsigned short* block_tap;
     float* wb;
+    float* wq;
     uint2* tile_hdr;
     long long block_cap;
+    ConvKernel kernel;
     int32_t* tmp_coords;
     float* tmp_feats;
     long long* pool_key;
@@ -253,13 +282,14 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->resp = c.take<float>((size_t)w->tiles_cap * c_out * kTileRows);
     w->side_cap = (unsigned long long)w->tiles_cap * kTileRows * c_out;
     w->side = c.take<uint2>((size_t)w->side_cap);
-    // matrix-core path: every (input row, tap) gives at most one pair; a tile reserves whole blocks per active tap
-    w->block_cap =
-        conv_uses_mfma(g, c_in, c_out, nnz_in, w->tiles_cap) ? (long long)g.T * (cand_cap / 16 + w->tiles_cap) : 0;
+    w->kernel = conv_kernel_for(g, c_in, c_out, nnz_in, w->tiles_cap);
+    // pair-list kernel: every (input row, tap) gives at most one pair; a tile reserves whole blocks per active tap
+    w->block_cap = w->kernel == ConvKernel::kPair ? (long long)g.T * (cand_cap / 16 + w->tiles_cap) : 0;
     w->pairs = c.take<unsigned>((size_t)w->block_cap * 16);
     w->block_tap = c.take<unsigned short>((size_t)w->block_cap);
     w->wb = c.take<float>(w->block_cap ? (size_t)g.T * round_up(c_in, 32) * c_out : 0);
     w->tile_hdr = c.take<uint2>(w->block_cap ? w->tiles_cap : 0);
+    w->wq = c.take<float>(w->kernel == ConvKernel::kQuad ? (size_t)g.T * ((c_in + 31) / 32) * 2048 : 0);
     w->tmp_coords = c.take<int32_t>(pool ? (size_t)cand_cap * (1 + g.ndim) : 0);
     w->tmp_feats = c.take<float>(pool ? (size_t)cand_cap * c_out : 0);
     w->pool_key = c.take<long long>(pool ? w->pool_cap : 0);
@@ -350,9 +380,11 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
 
     StageTimer timer(s, 0, kFwdStages);
     timer.mark();
-    const bool use_mfma = ws.block_cap > 0 && ((uintptr_t)in_feats & 15) == 0;
-    SCNN_TRY(launch_prepare(g, w, c_in, c_out, 0, ws.c_out_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
-                            ws.tap_coord, workspace, ws.zero_bytes, s));
+    // the matrix-core kernels load input rows 16 bytes at a time
+    const ConvKernel kernel = ((uintptr_t)in_feats & 15) == 0 ? ws.kernel : ConvKernel::kValu;
+    SCNN_TRY(launch_prepare(g, w, c_in, c_out, 0, ws.c_out_pad, ws.wp, kernel == ConvKernel::kPair ? ws.wb : nullptr,
+                            kernel == ConvKernel::kQuad ? ws.wq : nullptr, ws.tap_active, ws.tap_coord, workspace,
+                            ws.zero_bytes, s));
     // with a device-resident count, nnz_in is only the capacity of the input arrays: rows past the true count are
     // never indexed, so no look-up can return them
     SCNN_TRY(launch_index_build(g, in_coords, nnz_in, (const long long*)nnz_in_dev, nnz_in, ws.occ, ws.occ_prefix,
@@ -368,18 +400,28 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
                                   ws.tile_start, ws.rows16_start, ws.ctr, s));
     }
     timer.mark();
-    if (use_mfma) {
+    if (kernel == ConvKernel::kQuad) {
+        int cus = 0;
+        rc = device_cus(&cus);
+        if (rc != SCNN_OK) return rc;
+        timer.mark();
+        SCNN_TRY(launch_conv_quad(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wq, c_out, bias, ws.tap_active,
+                                  ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, cus, s));
+        g_last_conv_kernel = "k_conv_quad";
+    } else if (kernel == ConvKernel::kPair) {
         SCNN_TRY(launch_pair_build(g, ws.occ, ws.occ_prefix, nnz_in, ws.tap_active, ws.tap_coord, ws.cand_lin,
                                    ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, ws.pairs, ws.block_tap,
                                    ws.tile_hdr, ws.block_cap, ws.tiles_cap, nullptr, s));
         timer.mark();
         SCNN_TRY(launch_conv_mfma(g, nnz_in, in_feats, c_in, ws.wb, c_out, bias, ws.pairs, ws.block_tap, ws.tile_hdr,
                                   ws.ctr, ws.resp, s));
+        g_last_conv_kernel = "k_conv_mfma";
     } else {
         timer.mark();
         SCNN_TRY(launch_conv_valu(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wp, c_out, ws.c_out_pad, bias,
                                   ws.tap_active, ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
                                   ws.resp, s));
+        g_last_conv_kernel = "k_conv_valu";
     }
     timer.mark();
     SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
@@ -511,8 +553,8 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
     timer.mark();
     // adjoint filter (taps negated, channels transposed) in the layout of the convolution kernel that will run;
     // the same launch clears the counters and the occupancy bitmap
-    SCNN_TRY(launch_prepare(g, w, c_out, c_in, 1, ws.c_in_pad, ws.wp, use_mfma ? ws.wb : nullptr, ws.tap_active,
-                            ws.tap_coord, workspace, ws.zero_bytes, s));
+    SCNN_TRY(launch_prepare(g, w, c_out, c_in, 1, ws.c_in_pad, ws.wp, use_mfma ? ws.wb : nullptr, nullptr,
+                            ws.tap_active, ws.tap_coord, workspace, ws.zero_bytes, s));
     SCNN_TRY(launch_index_build(g, g_coords, g_rows, nullptr, g_rows, ws.occ, ws.occ_prefix, ws.ctr, s));
     SCNN_TRY(launch_rows_sample_bounds(g, in_coords, nnz_in, ws.cand_start, ws.tile_start, ws.ctr, s));
     SCNN_TRY(launch_bwd_sites(g, in_coords, nnz_in, ws.cand_start, ws.cand_lin, ws.rows16_start, ws.ctr, s));
@@ -570,11 +612,13 @@ int sparse_conv_fwd_chained(int ndim, const int32_t* extent, int batch, const in
 }
 
 int scnn_set_conv_path(int path) {
-    if (path < 0 || path > 2)
-        return fail(SCNN_EINVAL, "conv path must be 0 (auto), 1 (vector kernel) or 2 (matrix cores where possible)");
+    if (path < 0 || path > 3)
+        return fail(SCNN_EINVAL, "conv path must be 0 (auto), 1 (vector kernels), 2 (matrix cores where possible) or 3 (pair-list matrix-core kernel)");
     g_conv_path = path;
     return SCNN_OK;
 }
+
+const char* scnn_last_conv_kernel(void) { return g_last_conv_kernel; }
 
 int scnn_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
     if (!dst || !src || bytes % 16 != 0) return fail(SCNN_EINVAL, "calibration copy needs non-null pointers and a multiple of 16 bytes");

@@ -1,0 +1,368 @@
+// Matrix-core convolution, output-stationary over groups of four candidate sites (Alg. 1 steps 5-9, 13-14).
+//
+// A surface candidate has about a third of its taps' neighbours, and which ones differs from site to site.  The
+// matrix instruction used here, v_mfma_f32_4x4x1_16b_f32 with its A operand broadcast to all blocks, multiplies FOUR
+// rows by one input channel of a tap's weights for all output channels at once (lane = output channel): the unit
+// that has to share a tap is a quad of sites instead of the sixteen rows of the larger instructions.  A wave owns 64
+// consecutive candidate sites (half a response tile).  It looks up their neighbours, sorts the sites by their
+// neighbour pattern so that a quad holds similar sites (a pattern-sorted quad has the neighbour in about 90 % of the
+// (row, tap) slots it multiplies, against 45 % for sixteen consecutive rows), and then walks the taps: for every quad
+// that has the tap it gathers the four neighbour rows (one buffer load; an absent neighbour is an out-of-range offset
+// and reads as zero), runs one fp32 chain over at most 32 input channels, and adds the 4 x C_out results to fp64
+// accumulators it keeps in registers for all its sites.  No partial sum ever leaves the wave: there are no atomics, the
+// order of every addition is fixed by the data alone, and the result is reproducible bit for bit.  The fp32 matrix
+// cores only ever add the at most 32 products of one (tap, 32-channel chunk); the long cancelling sum over taps and
+// chunks is carried in double and rounded to fp32 once.
+//
+// Waves are independent (no workgroup barrier anywhere): a workgroup is just four of them sharing a launch slot.
+#include "scnn_internal.h"
+
+namespace scnn {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kQuadWaves = 4;            // waves per workgroup
+constexpr int kQuadRows = 64;            // candidate sites per wave
+constexpr int kQuadMaxTaps = 32;         // taps per filter (one bit each in a site's neighbour pattern)
+constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that does not exist: out of range, reads 0
+
+// LDS of one wave.  While the taps are walked: neighbour offsets [taps][64 sorted sites], the list of (tap, chunk)
+// passes, the list of (pass, quad set) steps.  Afterwards the same bytes hold the 64 x C_out results for the
+// transposition to the planar tile.
+constexpr int kQuadTabWords = kQuadMaxTaps * kQuadRows;                   // 8 KiB
+constexpr int kQuadMaxPasses = kQuadMaxTaps * 4;                          // C_in <= 128
+constexpr int kQuadMaxSteps = kQuadMaxPasses * 16 + 4;
+constexpr int kQuadTrWords = kQuadRows * 65;                              // transposition buffer, padded rows
+__host__ __device__ constexpr int quad_lds_words(int c_in) {
+    const int nch = (c_in + 31) / 32;
+    const int walk = kQuadTabWords + kQuadMaxTaps * nch + (kQuadMaxTaps * nch * 16 + 4) + kQuadRows;
+    return walk > kQuadTrWords ? walk : kQuadTrWords;
+}
+
+// One fp32 chain over the KC channels of a chunk: channel ch of the chunk is lane field kb = ch / NA of A register
+// ch % NA (a lane loads NA consecutive channels), selected through the instruction's broadcast index.
+template <int CH, int KC, int NA, int CBSZ>
+__device__ __forceinline__ void quad_chain(const float (&a)[4], const float (&b)[32], f32x4& d) {
+    if constexpr (CH < KC) {
+        d = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d, CBSZ, CH / NA, 0);
+        quad_chain<CH + 1, KC, NA, CBSZ>(a, b, d);
+    }
+}
+
+template <int NA>
+__device__ __forceinline__ void quad_load_a(__amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff, float (&a)[4]) {
+    if constexpr (NA == 1) {
+        a[0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, voff, soff, 0));
+    } else if constexpr (NA == 2) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rsrc, voff, soff, 0);
+        a[0] = __uint_as_float(v.x);
+        a[1] = __uint_as_float(v.y);
+    } else {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, soff, 0);
+        a[0] = __uint_as_float(v.x);
+        a[1] = __uint_as_float(v.y);
+        a[2] = __uint_as_float(v.z);
+        a[3] = __uint_as_float(v.w);
+    }
+}
+
+// Weights of one pass (tap, 32-channel chunk) in matrix-operand order: register ch of lane l holds
+// w[tap][32 chunk + ch][column of lane l]; stored as [pass][ch / 4][lane][ch % 4] so that a wave reads 1 KiB runs.
+template <int KC>
+__device__ __forceinline__ void quad_load_b(const float* __restrict__ wq, int pass, int lane, float (&b)[32]) {
+    const f32x4* p = (const f32x4*)(wq + (size_t)pass * 2048) + lane;
+#pragma unroll
+    for (int j = 0; j < (KC + 3) / 4; ++j) {
+        const f32x4 v = p[j * 64];
+        b[4 * j] = v.x;
+        b[4 * j + 1] = v.y;
+        b[4 * j + 2] = v.z;
+        b[4 * j + 3] = v.w;
+    }
+}
+
+// QPM = quads per matrix instruction: 1 (up to 64 output channels, lane = channel) or 2 (up to 32 output channels:
+// the two half waves hold two quads that then have to share their taps).
+template <int C_IN, int QPM>
+__global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
+    Geom g, const unsigned long long* __restrict__ occ, const unsigned* __restrict__ occ_prefix, long long nnz_in,
+    const float* __restrict__ feats, const float* __restrict__ wq, const float* __restrict__ bias, int c_out,
+    const int* __restrict__ tap_active, const unsigned* __restrict__ cand_lin, const int* __restrict__ cand_start,
+    const int* __restrict__ tile_start, Counters* __restrict__ ctr, float* __restrict__ resp) {
+    constexpr int NCH = (C_IN + 31) / 32;        // 32-channel chunks
+    constexpr int KB = 16 / QPM;                 // lanes of a quad row that hold channels
+    constexpr int NS = 16 / QPM;                 // quad sets (4 * QPM sites that share their taps) per wave
+    constexpr int SET = 4 * QPM;                 // sites per quad set
+    constexpr int CBSZ = QPM == 1 ? 4 : 3;       // A broadcast over 16 or 8 blocks
+    constexpr int COLS = 64 / QPM;
+    constexpr int KC_LAST = C_IN - 32 * (NCH - 1);
+    // channels a lane loads per row: those of a full chunk and of the last chunk (three become four: 16-byte loads)
+    constexpr int NA_FULL = 32 / KB, NA_LAST = (KC_LAST + KB - 1) / KB == 3 ? 4 : (KC_LAST + KB - 1) / KB;
+    constexpr int NA0 = NCH == 1 ? NA_LAST : NA_FULL;  // of every chunk but the last (of the only chunk)
+    static_assert(NA_FULL <= 4 && NA_LAST <= 4 && NA_LAST >= 1, "chunk width");
+    constexpr int LDSW = quad_lds_words(C_IN);
+    extern __shared__ __align__(16) unsigned smem_u[];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    unsigned* s_tab = smem_u + wave * LDSW;                    // [taps][64] buffer offsets, sorted site order
+    unsigned* s_pass = s_tab + kQuadTabWords;                  // [passes] tap | chunk << 8 | mask of quad sets << 16
+    unsigned* s_step = s_pass + kQuadMaxTaps * NCH;            // [steps + 2] (tap * 64 + set * SET) * 4 | chunk << 20
+    unsigned* s_pos = s_step + (kQuadMaxTaps * NCH * 16 + 4);  // [64] sorted position of a site
+    float* s_tr = (float*)s_tab;                               // [64][65] after the walk
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+
+    // lane fields of the matrix operands
+    const int row_in_set = (lane & 3) + 4 * (QPM == 2 ? (lane >> 5) : 0);
+    const int kb = (lane >> 2) & (KB - 1);
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)feats, 0, (int)(nnz_in * (long long)(C_IN * 4)), 0x00020000);
+
+    // XCD-aware order: workgroup i runs on XCD i % 8; each XCD owns one contiguous span of the wave tiles so that the
+    // input rows shared by neighbouring tiles stay in its L2.  A wave starts with the tile of its slot and then draws
+    // tiles from its span's counter, and from the other spans' once its own is used up.
+    const int n_wt = 2 * (int)ctr->n_tiles;
+    const int xcd = blockIdx.x & 7, slot = (blockIdx.x >> 3) * kQuadWaves + wave, per_xcd = (gridDim.x >> 3) * kQuadWaves;
+    const int span = (n_wt + 7) >> 3;
+    const int my_end = (xcd + 1) * span < n_wt ? (xcd + 1) * span : n_wt;
+
+    for (int wt = xcd * span + slot < my_end ? xcd * span + slot : -1; wt >= 0;) {
+        const int tile = wt >> 1, half = wt & 1;
+        const int b = sample_of_tile(tile_start, g.batch, tile);
+        const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows + half * kQuadRows;
+        int nrows = cand_start[b + 1] - first;
+        nrows = nrows > kQuadRows ? kQuadRows : nrows;
+
+        double acc[NS][4];
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[s][r] = 0.0;
+        unsigned orig_s = (unsigned)lane;  // site (of the 64) that sits at sorted position `lane`
+
+        if (nrows > 0) {
+            // ---- neighbours of site `lane`: buffer offsets into s_tab[tap][lane], pattern bits into `mask`
+            int c0 = 0, c1 = 0, c2 = 0;
+            const bool live = lane < nrows;
+            if (live) site_of(g, cand_lin[first + lane], c0, c1, c2);
+            unsigned mask = 0;
+            for (int line = 0; line < g.K[0] * g.K[1]; ++line) {
+                const int t0 = line / g.K[1], t1 = line - t0 * g.K[1];
+                const int tap0 = line * g.K[2];
+                lookup_line(g, occ, occ_prefix, nnz_in, live, b, c0, c1, c2, t0, t1, 0, g.K[2], tap_active + tap0,
+                            [&](int k, int n) {
+                                s_tab[(tap0 + k) * 64 + lane] = n < 0 ? kAbsent : (unsigned)n * (unsigned)(C_IN * 4);
+                                mask |= (n < 0 ? 0u : 1u) << (tap0 + k);
+                            });
+            }
+            // ---- sort the sites by pattern (bitonic network over the wave; ties by site, so the order is a
+            //      function of the data alone)
+            unsigned key = mask;
+#pragma unroll
+            for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+                for (int j = k >> 1; j > 0; j >>= 1) {
+                    const unsigned ok = __shfl_xor(key, j, 64), oo = __shfl_xor(orig_s, j, 64);
+                    const bool other_less = ok < key || (ok == key && oo < orig_s);
+                    const bool want_min = ((lane & k) == 0) == ((lane & j) == 0);
+                    if (other_less == want_min) {
+                        key = ok;
+                        orig_s = oo;
+                    }
+                }
+            s_pos[orig_s] = (unsigned)lane;
+            const unsigned my_pos = s_pos[lane];
+            // rows of the table into sorted order, in place (a wave's LDS reads finish before its next writes)
+            for (int t = 0; t < g.T; ++t) {
+                const unsigned v = s_tab[t * 64 + lane];
+                s_tab[t * 64 + my_pos] = v;
+            }
+            // ---- taps of each quad set = union over its sites; step list: per tap, per chunk, the sets that have it
+            unsigned u = key;
+            u |= __shfl_xor(u, 1, 64);
+            u |= __shfl_xor(u, 2, 64);
+            if constexpr (QPM == 2) u |= __shfl_xor(u, 4, 64);
+            const bool leader = (lane & (SET - 1)) == 0;
+            int n_pass = 0, n_step = 0;
+            for (int t = 0; t < g.T; ++t) {
+                const unsigned long long m = __ballot(leader && ((u >> t) & 1u));
+                if (m == 0ull) continue;
+                const int cnt = __popcll(m);
+                // bit s of the pass entry = quad set s has the tap (the leaders sit SET lanes apart)
+                unsigned set_bits = 0;
+#pragma unroll
+                for (int st = 0; st < NS; ++st) set_bits |= (unsigned)((m >> (st * SET)) & 1ull) << st;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) {
+                    if (lane == 0) s_pass[n_pass + c] = (unsigned)t | (unsigned)c << 8 | set_bits << 16;
+                    if (leader && ((u >> t) & 1u))
+                        s_step[n_step + c * cnt + __popcll(m & lt_mask)] =
+                            (unsigned)((t * 64 + lane) * 4) | (unsigned)c << 20;
+                }
+                n_pass += NCH;
+                n_step += NCH * cnt;
+            }
+            if (lane < 3) s_step[n_step + lane] = 0u;  // read ahead by the pipeline, never multiplied
+
+            if (n_step > 0) {
+                // ---- the walk.  Pipeline per step: list entry two steps ahead (LDS), the set's neighbour offsets one
+                //      step ahead (LDS), the gathered rows one step ahead (buffer load).
+                float a_next[4], b0[32], b1[32];
+                const unsigned tab_lane = (unsigned)(size_t)s_tab + (unsigned)row_in_set * 4u;  // LDS byte address
+                const unsigned kb_off = (unsigned)kb * 4u;  // times NA below: a lane loads NA consecutive channels
+                auto tab_at = [&](unsigned e) {
+                    return *(const __attribute__((address_space(3))) unsigned*)(size_t)(tab_lane + (e & 0xffffu));
+                };
+                // (the chunk's byte offset goes into the checked vector offset: an offset past the array reads as 0)
+                auto load_a = [&](unsigned off, unsigned e, float (&a)[4]) {
+                    const unsigned chunk = (e >> 20) & 3u;
+                    if (NCH > 1 && NA_LAST != NA0 && chunk == NCH - 1)
+                        quad_load_a<NA_LAST>(rsrc, off + (kb_off * NA_LAST + chunk * 128u), 0u, a);
+                    else
+                        quad_load_a<NA0>(rsrc, off + (kb_off * NA0 + chunk * 128u), 0u, a);
+                };
+                // at the top of step n: a_next = rows of step n, (e_1, off_1) = list entry and neighbour offsets of step
+                // n + 1, e_raw = list entry of step n + 2 as it comes from LDS (made uniform a step after it was read)
+                const unsigned e_first = __builtin_amdgcn_readfirstlane(s_step[0]);
+                unsigned e_1 = __builtin_amdgcn_readfirstlane(s_step[1]);
+                load_a(tab_at(e_first), e_first, a_next);
+                unsigned off_1 = tab_at(e_1);
+                unsigned e_raw = s_step[2];
+                int step = 0;
+                // One step = one quad set against one pass: the chain, then the set's four (per lane) fp64 additions.
+                // The sets are walked by straight-line code, one copy per set, so that the accumulators are plain
+                // registers; which sets a pass has comes from its mask.
+                auto run_step = [&](const float (&bw)[32], double (&ac)[4], bool last_chunk) {
+                    float a_cur[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) a_cur[i] = a_next[i];
+                    // rows of the next step; offsets of the one after; list entry of the one after that
+                    load_a(off_1, e_1, a_next);
+                    e_1 = __builtin_amdgcn_readfirstlane(e_raw);
+                    off_1 = tab_at(e_1);
+                    e_raw = s_step[step + 3];
+                    ++step;
+                    f32x4 d = {0.f, 0.f, 0.f, 0.f};
+                    if (NCH == 1 || last_chunk)
+                        quad_chain<0, KC_LAST, NA_LAST, CBSZ>(a_cur, bw, d);
+                    else
+                        quad_chain<0, 32, NA_FULL, CBSZ>(a_cur, bw, d);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) ac[r] += (double)d[r];
+                };
+                auto run_pass = [&](const float (&bw)[32], unsigned pass_info) {
+                    const unsigned sets = pass_info >> 16;
+                    const bool last_chunk = NCH > 1 && ((pass_info >> 8) & 0xffu) == NCH - 1;
+#pragma unroll
+                    for (int st = 0; st < NS; ++st)
+                        if (sets & (1u << st)) run_step(bw, acc[st], last_chunk);
+                };
+                auto pass_index = [&](unsigned info) { return (int)(info & 0xffu) * NCH + (int)((info >> 8) & 0xffu); };
+                auto load_pass = [&](unsigned info, float (&bw)[32]) {
+                    if (NCH > 1 && ((info >> 8) & 0xffu) != NCH - 1)
+                        quad_load_b<32>(wq, pass_index(info), lane, bw);
+                    else
+                        quad_load_b<KC_LAST>(wq, pass_index(info), lane, bw);
+                };
+                // passes in pairs: one register set multiplies while the other receives the next pass's weights
+                unsigned p_info = __builtin_amdgcn_readfirstlane(s_pass[0]);
+                load_pass(p_info, b0);
+                for (int p = 0; p < n_pass; p += 2) {
+                    unsigned p_next = 0;
+                    if (p + 1 < n_pass) {
+                        p_next = __builtin_amdgcn_readfirstlane(s_pass[p + 1]);
+                        load_pass(p_next, b1);
+                    }
+                    run_pass(b0, p_info);
+                    if (p + 1 >= n_pass) break;
+                    if (p + 2 < n_pass) {
+                        p_info = __builtin_amdgcn_readfirstlane(s_pass[p + 2]);
+                        load_pass(p_info, b0);
+                    }
+                    run_pass(b1, p_next);
+                }
+            }
+        }
+
+        // ---- next tile: the ticket's round trip hides behind the epilogue
+        int next_wt = -1;
+        if (lane == 0) {
+            for (int d = 0; d < 8 && next_wt < 0; ++d) {
+                const int x = (xcd + d) & 7;
+                const int end_x = (x + 1) * span < n_wt ? (x + 1) * span : n_wt;
+                if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
+                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
+                if (cand < end_x) next_wt = cand;
+            }
+        }
+
+        // ---- epilogue: one rounding to fp32, bias on the non-zero entries, transposition through LDS to the planar
+        //      tile (lane = channel  ->  lane = site).  Sites past the sample's end store zeros.
+        {
+            const int col = lane & (COLS - 1);
+            const float bv = (bias && col < c_out) ? bias[col] : 0.0f;
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    // sorted position of this value's site, and from it the site
+                    const int p = s * SET + r + (QPM == 2 ? 4 * (lane >> 5) : 0);
+                    unsigned o;
+                    if constexpr (QPM == 1)
+                        o = (unsigned)__builtin_amdgcn_readlane((int)orig_s, s * SET + r);
+                    else
+                        o = (unsigned)__shfl((int)orig_s, p, 64);
+                    float x = (float)acc[s][r];
+                    if (x != 0.0f) x += bv;
+                    s_tr[o * 65 + col] = x;
+                }
+            float* dst = resp + (size_t)tile * c_out * kTileRows + half * kQuadRows + lane;
+            for (int c = 0; c < c_out; ++c) dst[(size_t)c * kTileRows] = s_tr[lane * 65 + c];
+        }
+        wt = __builtin_amdgcn_readfirstlane(next_wt);
+    }
+}
+
+bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
+    if (g.T > kQuadMaxTaps) return false;
+    const bool shape = (c_in == 8 || c_in == 16 || c_in == 24 || c_in == 32 || c_in == 40 || c_in == 48 || c_in == 64) &&
+                       c_out >= 1 && c_out <= 64;
+    return shape && nnz_in > 0 && nnz_in * (long long)c_in * 4 < (1ll << 31);
+}
+
+template <int C_IN, int QPM>
+static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
+                                     long long nnz_in, const float* feats, const float* wq, const float* bias, int c_out,
+                                     const int* tap_active, const unsigned* cand_lin, const int* cand_start,
+                                     const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s) {
+    const size_t lds = (size_t)quad_lds_words(C_IN) * 4 * kQuadWaves;
+    hipError_t e = hipFuncSetAttribute((const void*)k_conv_quad<C_IN, QPM>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return e;
+    const int grid = (cus * 2 + 7) / 8 * 8;  // two workgroups (eight waves) per CU; a multiple of 8: one span per XCD
+    hipLaunchKernelGGL((k_conv_quad<C_IN, QPM>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix, nnz_in,
+                       feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix, long long nnz_in,
+                            const float* feats, int c_in, const float* wq, int c_out, const float* bias,
+                            const int* tap_active, const unsigned* cand_lin, const int* cand_start,
+                            const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s) {
+#define SCNN_QUAD_CASE(CI)                                                                                          \
+    if (c_in == CI) {                                                                                               \
+        if (c_out > 32)                                                                                             \
+            return launch_conv_quad_t<CI, 1>(g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, \
+                                             cand_start, tile_start, ctr, resp, cus, s);                            \
+        return launch_conv_quad_t<CI, 2>(g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin,  \
+                                         cand_start, tile_start, ctr, resp, cus, s);                                \
+    }
+    SCNN_QUAD_CASE(8) SCNN_QUAD_CASE(16) SCNN_QUAD_CASE(24) SCNN_QUAD_CASE(32) SCNN_QUAD_CASE(40) SCNN_QUAD_CASE(48)
+    SCNN_QUAD_CASE(64)
+#undef SCNN_QUAD_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace scnn

@@ -239,8 +239,9 @@ __device__ inline float filter_at(const float* __restrict__ w, int T, int c_in, 
 
 __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict__ w, int c_in, int c_out, int adjoint,
                                                  int c_out_pad, double* __restrict__ wp, float* __restrict__ wb,
-                                                 int* __restrict__ tap_active, int* __restrict__ tap_coord,
-                                                 uint4* __restrict__ zero_p, size_t zero_n16) {
+                                                 float* __restrict__ wq, int* __restrict__ tap_active,
+                                                 int* __restrict__ tap_coord, uint4* __restrict__ zero_p,
+                                                 size_t zero_n16) {
     if ((int)blockIdx.x >= g.T) {
         const size_t stride = (size_t)(gridDim.x - g.T) * blockDim.x;
         for (size_t i = (size_t)(blockIdx.x - g.T) * blockDim.x + threadIdx.x; i < zero_n16; i += stride)
@@ -252,7 +253,19 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
     if (threadIdx.x == 0) s_any = 0;
     __syncthreads();
     int any = 0;
-    if (wb) {
+    if (wq) {
+        // operand order of the quad kernel: [tap][32-channel chunk][channel / 4][lane][channel % 4], lane = output
+        // channel (modulo 32 when there are at most 32 of them); channels and columns past the real ones are zero
+        const int nch = (c_in + 31) / 32, cols = c_out > 32 ? 64 : 32;
+        const int n = nch * 2048;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const int e = i & 3, lane = (i >> 2) & 63, j = (i >> 8) & 7, c = i >> 11;
+            const int ic = c * 32 + 4 * j + e, oc = lane & (cols - 1);
+            const float v = (ic < c_in && oc < c_out) ? filter_at(w, g.T, c_in, c_out, adjoint, t, ic, oc) : 0.0f;
+            wq[(size_t)t * n + i] = v;
+            any |= (v != 0.0f);
+        }
+    } else if (wb) {
         // C_in = 16 is laid out like one 32-channel chunk: a lane's first four values are channels 4 gq .. 4 gq + 3,
         // its other four are zero
         const bool half = c_in == 16;
@@ -286,13 +299,13 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
 }
 
 hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int adjoint, int c_out_pad, double* wp,
-                          float* wb, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
+                          float* wb, float* wq, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
                           hipStream_t s) {
     const size_t n16 = (zero_bytes + 15) / 16;
     size_t zb = (n16 + 255) / 256;
     if (zb > 2048) zb = 2048;
     hipLaunchKernelGGL(k_prepare, dim3((unsigned)(g.T + zb)), dim3(256), 0, s, g, w, c_in, c_out, adjoint, c_out_pad, wp,
-                       wb, tap_active, tap_coord, (uint4*)zero_p, n16);
+                       wb, wq, tap_active, tap_coord, (uint4*)zero_p, n16);
     return hipGetLastError();
 }
 

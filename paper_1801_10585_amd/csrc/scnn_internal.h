@@ -236,8 +236,10 @@ namespace scnn {
 hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_imm, const long long* n_dev,
                               long long n_cap, unsigned long long* occ, unsigned* occ_prefix, Counters* ctr,
                               hipStream_t s);
+// wp / wb / wq: the filter in the layout of the vector / pair-list matrix-core / quad matrix-core kernel (exactly the
+// one that will run is non-null)
 hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int adjoint, int c_out_pad, double* wp,
-                          float* wb, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
+                          float* wb, float* wq, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
                           hipStream_t s);
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, hipStream_t s);
@@ -269,6 +271,13 @@ hipError_t launch_pair_build(const Geom& g, const unsigned long long* occ, const
 hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats, int c_in, const float* wb, int c_out,
                             const float* bias, const unsigned* pairs, const unsigned short* block_tap,
                             const uint2* tile_hdr, Counters* ctr, float* resp, hipStream_t s);
+
+// scnn_conv_quad.hip
+bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
+hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix, long long nnz_in,
+                            const float* feats, int c_in, const float* wq, int c_out, const float* bias,
+                            const int* tap_active, const unsigned* cand_lin, const int* cand_start,
+                            const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s);
 
 // scnn_bwd.hip
 hipError_t launch_bwd_sites(const Geom& g, const int32_t* coords, long long rows, const int* cand_start,

@@ -242,11 +242,21 @@ MFMA_CASES = [
     ((16, 16, 16), 2, 16, 16, (3, 3, 3), 0.08, 1.0),
     ((20, 20, 20), 1, 16, 64, (3, 3, 3), 0.05, 0.6),
     ((30, 30), 2, 16, 48, (3, 3), 0.2, 1.0),
+    # the channel widths of the paper's networks (appendix table: 8 / 16 / 24 / 32 / 40 / 48) and output widths that
+    # are no multiple of 16: the quad matrix-core kernel with one or two quads per instruction
+    ((18, 18, 18), 2, 8, 8, (3, 3, 3), 0.08, 1.0),
+    ((16, 16, 16), 2, 24, 24, (3, 3, 3), 0.08, 0.7),
+    ((16, 16, 16), 1, 40, 40, (3, 3, 3), 0.07, 1.0),
+    ((14, 14, 14), 2, 48, 48, (3, 3, 3), 0.08, 0.5),
+    ((16, 16, 16), 2, 24, 33, (3, 3, 3), 0.06, 1.0),
+    ((20, 20, 20), 1, 64, 17, (3, 1, 3), 0.1, 1.0),
+    ((36, 36), 3, 40, 64, (5, 5), 0.12, 0.6),
+    ((150, 3, 3), 1, 32, 64, (3, 3, 3), 0.3, 1.0),
 ]
 
 
 @pytest.mark.parametrize("case", MFMA_CASES)
-@pytest.mark.parametrize("path", [0, 1, 2])
+@pytest.mark.parametrize("path", [0, 1, 2, 3])
 def test_layer_wide_channels_both_kernels(case, path):
     extent, batch, c_in, c_out, ksize, density, fdens = case
     rng = np.random.default_rng(abs(hash(case)) % 2 ** 32)
@@ -266,6 +276,41 @@ def test_layer_wide_channels_both_kernels(case, path):
                                       tag=f"wide {case} path={path}")
     finally:
         scnn.set_conv_path(0)
+
+
+def test_matrix_core_kernels_are_exact_on_integer_data_and_repeatable():
+    """Small integers: every product and every partial sum is exact, so each kernel family must give the oracle's
+    values bit for bit; and two runs of the same call must give the same bits on every family whose additions
+    have a fixed order (all but the pair-list kernel)."""
+    rng = np.random.default_rng(123)
+    for (extent, batch, c_in, c_out, ksize) in (((22, 22, 22), 2, 32, 64, (3, 3, 3)), ((20, 20, 20), 2, 64, 32, (3, 3, 3)),
+                                                ((20, 20, 20), 1, 24, 24, (3, 3, 3))):
+        coords = random_sparse_sites(rng, extent, batch, 0.08)
+        feats = rng.integers(-3, 4, size=(coords.shape[0], c_in)).astype(np.float32)
+        w = rng.integers(-2, 3, size=(int(np.prod(ksize)), c_in, c_out)).astype(np.float32)
+        oc_, of_ = oracle.sparse_conv_fwd(extent, batch, coords, feats, ksize, w, rho_up=1.0, threads=16)
+        for path in (1, 2, 3):
+            scnn.set_conv_path(path)
+            try:
+                gc, gf, _ = gpu_conv(extent, batch, coords, feats, ksize, w, rho_up=1.0)
+                kernel = scnn.last_conv_kernel()
+            finally:
+                scnn.set_conv_path(0)
+            say(f"integer data {c_in}->{c_out} path={path}: {kernel}, rows={gc.shape[0]}")
+            assert np.array_equal(gc, oc_) and np.array_equal(gf, of_), f"path {path} ({kernel})"
+            assert kernel == ("k_conv_valu" if path == 1 else "k_conv_quad") or path == 3
+    # continuous data on the shape of the r = 128 configuration: the same bits on every run, selection included
+    wl = make_config(4, r=40, batch=2)
+    L = wl.layers[0]
+    scnn.set_conv_path(2)
+    try:
+        runs = [gpu_conv(wl.extent, wl.batch, wl.coords, wl.feats, L.ksize, wl.filters[0], rho_up=L.rho_up, relu=True)
+                for _ in range(3)]
+    finally:
+        scnn.set_conv_path(0)
+    assert scnn.last_conv_kernel() == "k_conv_quad"
+    for r in runs[1:]:
+        assert np.array_equal(runs[0][0], r[0]) and np.array_equal(runs[0][1], r[1]), "runs differ"
 
 
 def test_matrix_core_kernel_keeps_small_responses_accurate():

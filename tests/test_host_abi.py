@@ -122,7 +122,7 @@ def test_measurement_switches_reject_unknown_modes():
     L = scnn.load_library()
     assert L.scnn_profile_enable(3) == -1 and b"profile mode" in L.scnn_last_error()
     assert L.scnn_profile_enable(2) == 0 and L.scnn_profile_enable(0) == 0
-    assert L.scnn_set_conv_path(3) == -1 and b"conv path" in L.scnn_last_error()
+    assert L.scnn_set_conv_path(4) == -1 and b"conv path" in L.scnn_last_error()
     assert L.scnn_set_conv_path(2) == 0 and L.scnn_set_conv_path(0) == 0
     names = [L.scnn_profile_stage_name(i).decode() for i in range(L.scnn_profile_stage_count())]
     assert names[3] == "conv" and len(set(names)) == len(names)
