@@ -2,6 +2,7 @@
 // Nothing here touches values; every step of the layer runs in the kernels.
 #include <atomic>
 #include <cmath>
+#include <cstddef>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -788,7 +789,7 @@ int sparse_relu(int ndim, const int32_t* coords, const float* feats, int64_t row
 // (never the array's name) is handed to kernels.
 namespace {
 constexpr long long kStaticReluMaxRows = 1ll << 20;
-constexpr size_t kStaticReluBytes = 256                                                      // Counters
+constexpr size_t kStaticReluBytes = (sizeof(Counters) + 255) / 256 * 256                     // Counters
                                     + 2 * (size_t)kStaticReluMaxRows * sizeof(unsigned)      // flags, offsets
                                     + (((size_t)kStaticReluMaxRows / kScanChunk + 2) * sizeof(unsigned) + 255) / 256 * 256;
 constexpr int kMaxDevices = 64;
@@ -983,10 +984,12 @@ int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t
     if (workspace_bytes < 256 || ((uintptr_t)workspace & 255) != 0) return fail(SCNN_EWORKSPACE, "need 256 aligned bytes");
     hipStream_t s = (hipStream_t)hip_stream;
     Counters* ctr = (Counters*)workspace;
+    // (the check only touches the status bits, which sit in the first 256 bytes of the counters)
+    static_assert(offsetof(Counters, flags) + sizeof(unsigned) <= 256, "status bits within the documented workspace");
     SCNN_TRY(launch_zero(workspace, 256, s));
     SCNN_TRY(launch_validate(g, coords, rows, ctr, s));
-    Counters host;
-    SCNN_TRY(hipMemcpyAsync(&host, ctr, sizeof(host), hipMemcpyDeviceToHost, s));
+    struct { unsigned flags; } host;
+    SCNN_TRY(hipMemcpyAsync(&host.flags, &ctr->flags, sizeof(unsigned), hipMemcpyDeviceToHost, s));
     SCNN_TRY(hipStreamSynchronize(s));
     if (host.flags & SCNN_FLAG_BAD_COORD) return fail(SCNN_EINVAL, "a coordinate lies outside the grid");
     if (host.flags & SCNN_FLAG_UNSORTED) return fail(SCNN_EUNSORTED, "rows are not strictly ascending by (b, lin)");

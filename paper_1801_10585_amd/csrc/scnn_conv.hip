@@ -1239,7 +1239,7 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
                 const int x = (xcd + d) & 7;
                 const int end_x = (x + 1) * span < n_tiles ? (x + 1) * span : n_tiles;
                 if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
-                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
+                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x * kTicketStride], 1u);
                 if (cand < end_x) t = cand;
             }
             s_next[parity] = t;

@@ -26,6 +26,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kQuadWaves = 4;            // waves per workgroup
 constexpr int kQuadRows = 64;            // candidate sites per wave
 constexpr int kQuadMaxTaps = 32;         // taps per filter (one bit each in a site's neighbour pattern)
+constexpr int kLineBatch = 9;            // filter lines whose bitmap words are fetched together
 constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that does not exist: out of range, reads 0
 
 // LDS of one wave.  While the taps are walked: neighbour offsets [taps][64 sorted sites], the list of (tap, chunk)
@@ -41,13 +42,18 @@ __host__ __device__ constexpr int quad_lds_words(int c_in) {
     return walk > kQuadTrWords ? walk : kQuadTrWords;
 }
 
-// One fp32 chain over the KC channels of a chunk: channel ch of the chunk is lane field kb = ch / NA of A register
-// ch % NA (a lane loads NA consecutive channels), selected through the instruction's broadcast index.
+// The fp32 products of one step: channel ch of the chunk is lane field kb = ch / NA of A register ch % NA (a lane
+// loads NA consecutive channels), selected through the instruction's broadcast index.  Even and odd channels go to
+// two accumulators, i.e. two independent chains of matrix instructions issued alternately: an instruction of a chain
+// then never waits for the result of the one before it (its predecessor in the chain is two issue slots away).
 template <int CH, int KC, int NA, int CBSZ>
-__device__ __forceinline__ void quad_chain(const float (&a)[4], const float (&b)[32], f32x4& d) {
+__device__ __forceinline__ void quad_chain(const float (&a)[4], const float (&b)[32], f32x4& d0, f32x4& d1) {
     if constexpr (CH < KC) {
-        d = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d, CBSZ, CH / NA, 0);
-        quad_chain<CH + 1, KC, NA, CBSZ>(a, b, d);
+        if constexpr (CH % 2 == 0)
+            d0 = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d0, CBSZ, CH / NA, 0);
+        else
+            d1 = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d1, CBSZ, CH / NA, 0);
+        quad_chain<CH + 1, KC, NA, CBSZ>(a, b, d0, d1);
     }
 }
 
@@ -120,6 +126,9 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc((void*)feats, 0, (int)(nnz_in * (long long)(C_IN * 4)), 0x00020000);
 
+    // taps with a non-zero weight, one bit each
+    const unsigned act_mask = (unsigned)__ballot(lane < g.T && tap_active[lane < g.T ? lane : 0] != 0);
+
     // XCD-aware order: workgroup i runs on XCD i % 8; each XCD owns one contiguous span of the wave tiles so that the
     // input rows shared by neighbouring tiles stay in its L2.  A wave starts with the tile of its slot and then draws
     // tiles from its span's counter, and from the other spans' once its own is used up.
@@ -128,6 +137,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
     const int span = (n_wt + 7) >> 3;
     const int my_end = (xcd + 1) * span < n_wt ? (xcd + 1) * span : n_wt;
 
+    bool own_done = xcd * span + per_xcd >= my_end;  // nothing to draw beyond the first tiles
     for (int wt = xcd * span + slot < my_end ? xcd * span + slot : -1; wt >= 0;) {
         const int tile = wt >> 1, half = wt & 1;
         const int b = sample_of_tile(tile_start, g.batch, tile);
@@ -140,26 +150,73 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
         for (int s = 0; s < NS; ++s)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[s][r] = 0.0;
-        unsigned orig_s = (unsigned)lane;  // site (of the 64) that sits at sorted position `lane`
+        unsigned my_pos = (unsigned)lane;  // sorted position of site `lane` (of the wave's 64)
 
         if (nrows > 0) {
-            // ---- neighbours of site `lane`: buffer offsets into s_tab[tap][lane], pattern bits into `mask`
+            // ---- neighbours of site `lane`: buffer offsets into s_tab[tap][lane], pattern bits into `mask`.
+            //      The taps of one filter line (t0, t1, .) look at adjacent sites, which sit in at most two adjacent
+            //      words of the occupancy bitmap: both words and their row prefixes are fetched for kLineBatch lines
+            //      at a time, all loads in flight together, and the lines' taps are resolved from them afterwards.
             int c0 = 0, c1 = 0, c2 = 0;
             const bool live = lane < nrows;
             if (live) site_of(g, cand_lin[first + lane], c0, c1, c2);
             unsigned mask = 0;
-            for (int line = 0; line < g.K[0] * g.K[1]; ++line) {
-                const int t0 = line / g.K[1], t1 = line - t0 * g.K[1];
-                const int tap0 = line * g.K[2];
-                lookup_line(g, occ, occ_prefix, nnz_in, live, b, c0, c1, c2, t0, t1, 0, g.K[2], tap_active + tap0,
-                            [&](int k, int n) {
-                                s_tab[(tap0 + k) * 64 + lane] = n < 0 ? kAbsent : (unsigned)n * (unsigned)(C_IN * 4);
-                                mask |= (n < 0 ? 0u : 1u) << (tap0 + k);
-                            });
+            // LDS address of s_tab[0][lane], made opaque per tile: the addresses of the table's rows must not be
+            // computed once for the whole kernel and kept in registers
+            unsigned tab_w = (unsigned)(size_t)s_tab + (unsigned)lane * 4u;
+            asm volatile("" : "+v"(tab_w));
+            const int n_lines = g.K[0] * g.K[1];
+            const unsigned w_last = (unsigned)g.batch * (unsigned)g.Wps - 1u;
+            const int q2s = c2 - g.H[2];                       // site of tap k of a line is q2s + k
+            const int k_lo = q2s < 0 ? -q2s : 0;               // first tap whose site is on the line
+            for (int line0 = 0; line0 < n_lines; line0 += kLineBatch) {
+                unsigned long long word_a[kLineBatch], word_b[kLineBatch];
+                unsigned pre_a[kLineBatch], pre_b[kLineBatch], bit0[kLineBatch], w_rel[kLineBatch];
+                bool ok[kLineBatch];
+#pragma unroll
+                for (int i = 0; i < kLineBatch; ++i) {
+                    const int line = line0 + i < n_lines ? line0 + i : n_lines - 1;
+                    const int t0 = line / g.K[1], t1 = line - t0 * g.K[1];
+                    const int q0 = c0 + t0 - g.H[0], q1 = c1 + t1 - g.H[1];
+                    ok[i] = live && line0 + i < n_lines && (unsigned)q0 < (unsigned)g.E[0] && (unsigned)q1 < (unsigned)g.E[1];
+                    bit0[i] = (unsigned)((q0 * g.E[1] + q1) * g.E[2]);  // site index of (q0, q1, 0), if ok
+                    const unsigned first_bit = ok[i] ? bit0[i] + (unsigned)(q2s + k_lo) : 0u;
+                    w_rel[i] = first_bit >> 6;
+                    const unsigned w0 = (unsigned)b * (unsigned)g.Wps + w_rel[i];
+                    const unsigned wa = ok[i] ? (w0 < w_last ? w0 : w_last) : 0u, wb = wa < w_last ? wa + 1u : wa;
+                    word_a[i] = occ[wa];
+                    word_b[i] = occ[wb];
+                    pre_a[i] = occ_prefix[wa];
+                    pre_b[i] = occ_prefix[wb];
+                }
+#pragma unroll
+                for (int i = 0; i < kLineBatch; ++i) {
+                    if (line0 + i >= n_lines) break;
+                    const int tap0 = (line0 + i) * g.K[2];
+                    for (int k = 0; k < g.K[2]; ++k) {
+                        unsigned off = kAbsent;
+                        const int q2 = q2s + k;
+                        if (ok[i] && (unsigned)q2 < (unsigned)g.E[2] && ((act_mask >> (tap0 + k)) & 1u)) {
+                            const unsigned bitpos = bit0[i] + (unsigned)q2;
+                            const bool second = (bitpos >> 6) != w_rel[i];
+                            const unsigned long long word = second ? word_b[i] : word_a[i];
+                            const unsigned bit = bitpos & 63u;
+                            if ((word >> bit) & 1ull) {
+                                const long long rr =
+                                    (long long)(second ? pre_b[i] : pre_a[i]) + __popcll(word & ((1ull << bit) - 1ull));
+                                if (rr < nnz_in) {  // (only an unsorted input can fail this)
+                                    off = (unsigned)rr * (unsigned)(C_IN * 4);
+                                    mask |= 1u << (tap0 + k);
+                                }
+                            }
+                        }
+                        *(__attribute__((address_space(3))) unsigned*)(size_t)(tab_w + (unsigned)(tap0 + k) * 256u) = off;
+                    }
+                }
             }
             // ---- sort the sites by pattern (bitonic network over the wave; ties by site, so the order is a
             //      function of the data alone)
-            unsigned key = mask;
+            unsigned key = mask, orig_s = (unsigned)lane;  // orig_s: the site that sits at sorted position `lane`
 #pragma unroll
             for (int k = 2; k <= 64; k <<= 1)
 #pragma unroll
@@ -173,7 +230,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
                     }
                 }
             s_pos[orig_s] = (unsigned)lane;
-            const unsigned my_pos = s_pos[lane];
+            my_pos = s_pos[lane];
             // rows of the table into sorted order, in place (a wave's LDS reads finish before its next writes)
             for (int t = 0; t < g.T; ++t) {
                 const unsigned v = s_tab[t * 64 + lane];
@@ -191,9 +248,19 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
                 if (m == 0ull) continue;
                 const int cnt = __popcll(m);
                 // bit s of the pass entry = quad set s has the tap (the leaders sit SET lanes apart)
-                unsigned set_bits = 0;
-#pragma unroll
-                for (int st = 0; st < NS; ++st) set_bits |= (unsigned)((m >> (st * SET)) & 1ull) << st;
+                // the leaders' bits, SET lanes apart, moved next to each other: bit st = set st has the tap
+                unsigned long long x = m;
+                if constexpr (QPM == 1) {
+                    x = (x | x >> 3) & 0x0303030303030303ull;
+                    x = (x | x >> 6) & 0x000f000f000f000full;
+                    x = (x | x >> 12) & 0x000000ff000000ffull;
+                    x = (x | x >> 24) & 0xffffull;
+                } else {
+                    x = (x | x >> 7) & 0x0003000300030003ull;
+                    x = (x | x >> 14) & 0x0000000f0000000full;
+                    x = (x | x >> 28) & 0xffull;
+                }
+                const unsigned set_bits = (unsigned)x;
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     if (lane == 0) s_pass[n_pass + c] = (unsigned)t | (unsigned)c << 8 | set_bits << 16;
@@ -244,13 +311,13 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
                     off_1 = tab_at(e_1);
                     e_raw = s_step[step + 3];
                     ++step;
-                    f32x4 d = {0.f, 0.f, 0.f, 0.f};
+                    f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
                     if (NCH == 1 || last_chunk)
-                        quad_chain<0, KC_LAST, NA_LAST, CBSZ>(a_cur, bw, d);
+                        quad_chain<0, KC_LAST, NA_LAST, CBSZ>(a_cur, bw, d0, d1);
                     else
-                        quad_chain<0, 32, NA_FULL, CBSZ>(a_cur, bw, d);
+                        quad_chain<0, 32, NA_FULL, CBSZ>(a_cur, bw, d0, d1);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) ac[r] += (double)d[r];
+                    for (int r = 0; r < 4; ++r) ac[r] += (double)(d0[r] + d1[r]);
                 };
                 auto run_pass = [&](const float (&bw)[32], unsigned pass_info) {
                     const unsigned sets = pass_info >> 16;
@@ -286,42 +353,66 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
             }
         }
 
-        // ---- next tile: the ticket's round trip hides behind the epilogue
-        int next_wt = -1;
-        if (lane == 0) {
-            for (int d = 0; d < 8 && next_wt < 0; ++d) {
-                const int x = (xcd + d) & 7;
-                const int end_x = (x + 1) * span < n_wt ? (x + 1) * span : n_wt;
-                if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
-                const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x], 1u);
-                if (cand < end_x) next_wt = cand;
-            }
-        }
+        // ---- next tile: ask the own span's counter now and look at the answer after the epilogue, which hides the
+        //      round trip.  (Lane 0 asks; the counters sit on separate cache lines.)
+        unsigned ticket = 0;
+        if (!own_done && lane == 0) ticket = atomicAdd(&ctr->conv_ticket[xcd * kTicketStride], 1u);
 
         // ---- epilogue: one rounding to fp32, bias on the non-zero entries, transposition through LDS to the planar
-        //      tile (lane = channel  ->  lane = site).  Sites past the sample's end store zeros.
+        //      tile: a lane holds its channel's values of all sorted positions and writes them in that order (fixed
+        //      offsets); then lane = site reads the row of its sorted position.  Sites past the sample's end store 0.
         {
             const int col = lane & (COLS - 1);
-            const float bv = (bias && col < c_out) ? bias[col] : 0.0f;
+            float* tr_w = s_tr + col + (QPM == 2 ? 4 * 65 * (lane >> 5) : 0);
+            if (bias) {
+                const float bv = col < c_out ? bias[col] : 0.0f;
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
+                for (int st = 0; st < NS; ++st)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    // sorted position of this value's site, and from it the site
-                    const int p = s * SET + r + (QPM == 2 ? 4 * (lane >> 5) : 0);
-                    unsigned o;
-                    if constexpr (QPM == 1)
-                        o = (unsigned)__builtin_amdgcn_readlane((int)orig_s, s * SET + r);
-                    else
-                        o = (unsigned)__shfl((int)orig_s, p, 64);
-                    float x = (float)acc[s][r];
-                    if (x != 0.0f) x += bv;
-                    s_tr[o * 65 + col] = x;
-                }
+                    for (int r = 0; r < 4; ++r) {
+                        float x = (float)acc[st][r];
+                        if (x != 0.0f) x += bv;
+                        tr_w[(st * SET + r) * 65] = x;
+                    }
+            } else {
+#pragma unroll
+                for (int st = 0; st < NS; ++st)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) tr_w[(st * SET + r) * 65] = (float)acc[st][r];
+            }
+            const float* tr_r = s_tr + my_pos * 65;
             float* dst = resp + (size_t)tile * c_out * kTileRows + half * kQuadRows + lane;
-            for (int c = 0; c < c_out; ++c) dst[(size_t)c * kTileRows] = s_tr[lane * 65 + c];
+            int c = 0;
+            for (; c + 8 <= c_out; c += 8) {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = tr_r[c + i];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(v[i], dst + (size_t)(c + i) * kTileRows);
+            }
+            for (; c < c_out; ++c) __builtin_nontemporal_store(tr_r[c], dst + (size_t)c * kTileRows);
         }
-        wt = __builtin_amdgcn_readfirstlane(next_wt);
+        int next_wt = -1;
+        if (!own_done) {
+            const int cand = xcd * span + per_xcd + (int)__builtin_amdgcn_readfirstlane(ticket);
+            if (cand < my_end) next_wt = cand; else own_done = true;
+        }
+        if (own_done) {
+            // the own span is used up: help the next spans, so that no XCD ends long before the others (tiles differ
+            // in work).  Only the next two are tried: a wave that finds nothing there retires.
+            int got = -1;
+            if (lane == 0) {
+                for (int d = 1; d <= 2 && got < 0; ++d) {
+                    const int x = (xcd + d) & 7;
+                    const int end_x = (x + 1) * span < n_wt ? (x + 1) * span : n_wt;
+                    if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
+                    const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x * kTicketStride], 1u);
+                    if (cand < end_x) got = cand;
+                }
+            }
+            next_wt = __builtin_amdgcn_readfirstlane(got);
+        }
+        wt = next_wt;
     }
 }
 

@@ -43,6 +43,8 @@ struct ColState {
     unsigned long long side_off;  // first side-buffer entry of the column
 };
 
+constexpr int kTicketStride = 32;  // 32-bit words between two ticket counters
+
 // Device-resident counters produced on the way.
 struct Counters {
     long long n_cand;     // candidate sites
@@ -54,7 +56,9 @@ struct Counters {
     unsigned finished;    // workgroups of the compaction pass that have ended
     unsigned ticket;      // next tile of the compaction pass
     unsigned long long side_cursor;  // side-buffer entries handed out to columns so far
-    unsigned conv_ticket[8];  // tiles handed out so far in each of the contraction kernel's eight tile spans
+    // tiles handed out so far in each of the contraction kernels' eight tile spans; one counter per 128-byte line:
+    // read-modify-writes on one line are served one after the other, whichever word they address
+    unsigned conv_ticket[8 * kTicketStride];
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
