@@ -15,6 +15,8 @@
 // chunks is carried in double and rounded to fp32 once.
 //
 // Waves are independent (no workgroup barrier anywhere): a workgroup is just four of them sharing a launch slot.
+#include <type_traits>
+
 #include "scnn_internal.h"
 
 namespace scnn {
@@ -35,11 +37,16 @@ constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that 
 constexpr int kQuadTabWords = kQuadMaxTaps * kQuadRows;                   // 8 KiB
 constexpr int kQuadMaxPasses = kQuadMaxTaps * 4;                          // C_in <= 128
 constexpr int kQuadMaxSteps = kQuadMaxPasses * 16 + 4;
-constexpr int kQuadTrWords = kQuadRows * 65;                              // transposition buffer, padded rows
+constexpr int kQuadTrWords = kQuadRows * 33;                              // transposition buffer: half the columns, padded rows
 __host__ __device__ constexpr int quad_lds_words(int c_in) {
     const int nch = (c_in + 31) / 32;
     const int walk = kQuadTabWords + kQuadMaxTaps * nch + (kQuadMaxTaps * nch * 16 + 4) + kQuadRows;
     return walk > kQuadTrWords ? walk : kQuadTrWords;
+}
+// Waves per SIMD the kernel is built for: its registers are the accumulators (64 sites x 64 channels, 4 or 8 bytes
+// each) plus two sets of weights.
+__host__ __device__ constexpr int quad_waves_per_simd(int c_in, int qpm, int acc64) {
+    return ((qpm == 1 && acc64) || c_in == 40 || c_in == 48) ? 2 : 3;  // (two chunk widths cost registers too)
 }
 
 // The fp32 products of one step: channel ch of the chunk is lane field kb = ch / NA of A register ch % NA (a lane
@@ -91,8 +98,10 @@ __device__ __forceinline__ void quad_load_b(const float* __restrict__ wq, int pa
 
 // QPM = quads per matrix instruction: 1 (up to 64 output channels, lane = channel) or 2 (up to 32 output channels:
 // the two half waves hold two quads that then have to share their taps).
-template <int C_IN, int QPM>
-__global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
+// ACC64: the sums over taps and chunks are carried in fp64 (else fp32: for filters of few taps, where the additions
+// across taps contribute less rounding error than the fp32 chains themselves).
+template <int C_IN, int QPM, int ACC64>
+__global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC64)) void k_conv_quad(
     Geom g, const unsigned long long* __restrict__ occ, const unsigned* __restrict__ occ_prefix, long long nnz_in,
     const float* __restrict__ feats, const float* __restrict__ wq, const float* __restrict__ bias, int c_out,
     const int* __restrict__ tap_active, const unsigned* __restrict__ cand_lin, const int* __restrict__ cand_start,
@@ -109,6 +118,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
     constexpr int NA0 = NCH == 1 ? NA_LAST : NA_FULL;  // of every chunk but the last (of the only chunk)
     static_assert(NA_FULL <= 4 && NA_LAST <= 4 && NA_LAST >= 1, "chunk width");
     constexpr int LDSW = quad_lds_words(C_IN);
+    typedef typename std::conditional<ACC64 != 0, double, float>::type acc_t;
     extern __shared__ __align__(16) unsigned smem_u[];
 
     const int lane = threadIdx.x & 63;
@@ -117,7 +127,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
     unsigned* s_pass = s_tab + kQuadTabWords;                  // [passes] tap | chunk << 8 | mask of quad sets << 16
     unsigned* s_step = s_pass + kQuadMaxTaps * NCH;            // [steps + 2] (tap * 64 + set * SET) * 4 | chunk << 20
     unsigned* s_pos = s_step + (kQuadMaxTaps * NCH * 16 + 4);  // [64] sorted position of a site
-    float* s_tr = (float*)s_tab;                               // [64][65] after the walk
+    float* s_tr = (float*)s_tab;                               // [64][COLS / 2 + 1] after the walk
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
     // lane fields of the matrix operands
@@ -145,11 +155,11 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
         int nrows = cand_start[b + 1] - first;
         nrows = nrows > kQuadRows ? kQuadRows : nrows;
 
-        double acc[NS][4];
+        acc_t acc[NS][4];
 #pragma unroll
         for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[s][r] = 0.0;
+            for (int r = 0; r < 4; ++r) acc[s][r] = (acc_t)0;
         unsigned my_pos = (unsigned)lane;  // sorted position of site `lane` (of the wave's 64)
 
         if (nrows > 0) {
@@ -301,7 +311,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
                 // One step = one quad set against one pass: the chain, then the set's four (per lane) fp64 additions.
                 // The sets are walked by straight-line code, one copy per set, so that the accumulators are plain
                 // registers; which sets a pass has comes from its mask.
-                auto run_step = [&](const float (&bw)[32], double (&ac)[4], bool last_chunk) {
+                auto run_step = [&](const float (&bw)[32], acc_t (&ac)[4], bool last_chunk) {
                     float a_cur[4];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) a_cur[i] = a_next[i];
@@ -317,7 +327,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
                     else
                         quad_chain<0, 32, NA_FULL, CBSZ>(a_cur, bw, d0, d1);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) ac[r] += (double)(d0[r] + d1[r]);
+                    for (int r = 0; r < 4; ++r) ac[r] += (acc_t)(d0[r] + d1[r]);
                 };
                 auto run_pass = [&](const float (&bw)[32], unsigned pass_info) {
                     const unsigned sets = pass_info >> 16;
@@ -361,36 +371,44 @@ __global__ __launch_bounds__(kQuadWaves * 64, 2) void k_conv_quad(
         // ---- epilogue: one rounding to fp32, bias on the non-zero entries, transposition through LDS to the planar
         //      tile: a lane holds its channel's values of all sorted positions and writes them in that order (fixed
         //      offsets); then lane = site reads the row of its sorted position.  Sites past the sample's end store 0.
+        //      The buffer holds half of the columns at a time.
         {
-            const int col = lane & (COLS - 1);
-            float* tr_w = s_tr + col + (QPM == 2 ? 4 * 65 * (lane >> 5) : 0);
-            if (bias) {
-                const float bv = col < c_out ? bias[col] : 0.0f;
-#pragma unroll
-                for (int st = 0; st < NS; ++st)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float x = (float)acc[st][r];
-                        if (x != 0.0f) x += bv;
-                        tr_w[(st * SET + r) * 65] = x;
-                    }
-            } else {
-#pragma unroll
-                for (int st = 0; st < NS; ++st)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) tr_w[(st * SET + r) * 65] = (float)acc[st][r];
-            }
-            const float* tr_r = s_tr + my_pos * 65;
+            constexpr int HC = COLS / 2;                         // columns per half
+            const int col = lane & (COLS - 1), colh = col & (HC - 1);
+            const float bv = (bias && col < c_out) ? bias[col] : 0.0f;
+            float* tr_w = s_tr + colh + (QPM == 2 ? 4 * (HC + 1) * (lane >> 5) : 0);
+            const float* tr_r = s_tr + my_pos * (HC + 1);
             float* dst = resp + (size_t)tile * c_out * kTileRows + half * kQuadRows + lane;
-            int c = 0;
-            for (; c + 8 <= c_out; c += 8) {
-                float v[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = tr_r[c + i];
+            for (int h = 0; h < 2; ++h) {
+                if ((col >= HC) == (h == 1)) {
+                    if (bias) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(v[i], dst + (size_t)(c + i) * kTileRows);
+                        for (int st = 0; st < NS; ++st)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                float x = (float)acc[st][r];
+                                if (x != 0.0f) x += bv;
+                                tr_w[(st * SET + r) * (HC + 1)] = x;
+                            }
+                    } else {
+#pragma unroll
+                        for (int st = 0; st < NS; ++st)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) tr_w[(st * SET + r) * (HC + 1)] = (float)acc[st][r];
+                    }
+                }
+                const int c_end = c_out < (h + 1) * HC ? c_out : (h + 1) * HC;
+                int c = h * HC;
+                for (; c + 8 <= c_end; c += 8) {
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = tr_r[c - h * HC + i];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(v[i], dst + (size_t)(c + i) * kTileRows);
+                }
+                for (; c < c_end; ++c) __builtin_nontemporal_store(tr_r[c - h * HC], dst + (size_t)c * kTileRows);
             }
-            for (; c < c_out; ++c) __builtin_nontemporal_store(tr_r[c], dst + (size_t)c * kTileRows);
         }
         int next_wt = -1;
         if (!own_done) {
@@ -423,18 +441,19 @@ bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
     return shape && nnz_in > 0 && nnz_in * (long long)c_in * 4 < (1ll << 31);
 }
 
-template <int C_IN, int QPM>
+template <int C_IN, int QPM, int ACC64>
 static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                                      long long nnz_in, const float* feats, const float* wq, const float* bias, int c_out,
                                      const int* tap_active, const unsigned* cand_lin, const int* cand_start,
                                      const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s) {
     const size_t lds = (size_t)quad_lds_words(C_IN) * 4 * kQuadWaves;
-    hipError_t e = hipFuncSetAttribute((const void*)k_conv_quad<C_IN, QPM>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
+    hipError_t e = hipFuncSetAttribute((const void*)k_conv_quad<C_IN, QPM, ACC64>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const int grid = (cus * 2 + 7) / 8 * 8;  // two workgroups (eight waves) per CU; a multiple of 8: one span per XCD
-    hipLaunchKernelGGL((k_conv_quad<C_IN, QPM>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix, nnz_in,
-                       feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp);
+    // one workgroup (four waves) per SIMD wave slot of every CU; a multiple of 8: one span of tiles per XCD
+    const int grid = (cus * quad_waves_per_simd(C_IN, QPM, ACC64) + 7) / 8 * 8;
+    hipLaunchKernelGGL((k_conv_quad<C_IN, QPM, ACC64>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix,
+                       nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp);
     return hipGetLastError();
 }
 
@@ -442,17 +461,20 @@ hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const 
                             const float* feats, int c_in, const float* wq, int c_out, const float* bias,
                             const int* tap_active, const unsigned* cand_lin, const int* cand_start,
                             const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s) {
-#define SCNN_QUAD_CASE(CI)                                                                                          \
-    if (c_in == CI) {                                                                                               \
-        if (c_out > 32)                                                                                             \
-            return launch_conv_quad_t<CI, 1>(g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, \
-                                             cand_start, tile_start, ctr, resp, cus, s);                            \
-        return launch_conv_quad_t<CI, 2>(g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin,  \
-                                         cand_start, tile_start, ctr, resp, cus, s);                                \
+    // fp32 sums over taps for filters of at most 32 (tap, chunk) passes (a 3x3x3 filter over up to 32 channels),
+    // fp64 sums beyond
+    const bool acc64 = (long long)g.T * ((c_in + 31) / 32) > 32;
+#define SCNN_QUAD_ARGS g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp, cus, s
+#define SCNN_QUAD_CASE(CI)                                                          \
+    if (c_in == CI) {                                                               \
+        if (c_out > 32)                                                             \
+            return acc64 ? launch_conv_quad_t<CI, 1, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 1, 0>(SCNN_QUAD_ARGS); \
+        return acc64 ? launch_conv_quad_t<CI, 2, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 2, 0>(SCNN_QUAD_ARGS);     \
     }
     SCNN_QUAD_CASE(8) SCNN_QUAD_CASE(16) SCNN_QUAD_CASE(24) SCNN_QUAD_CASE(32) SCNN_QUAD_CASE(40) SCNN_QUAD_CASE(48)
     SCNN_QUAD_CASE(64)
 #undef SCNN_QUAD_CASE
+#undef SCNN_QUAD_ARGS
     return hipErrorInvalidValue;
 }
 
