@@ -32,8 +32,8 @@ static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long 
     if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
     const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
+    if (quad_ok && c_in >= 32) return ConvKernel::kQuad;
     if (pair_ok && (c_in >= 32 || (c_in == 16 && c_out >= 32 && tiles_cap > 1280))) return ConvKernel::kPair;
-    (void)quad_ok;
     return ConvKernel::kValu;
 }
 

@@ -28,6 +28,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kQuadWaves = 4;            // waves per workgroup
 constexpr int kQuadRows = 64;            // candidate sites per wave
 constexpr int kQuadMaxTaps = 32;         // taps per filter (one bit each in a site's neighbour pattern)
+constexpr bool kQuadSingleChain = false;
 constexpr int kLineBatch = 9;            // filter lines whose bitmap words are fetched together
 constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that does not exist: out of range, reads 0
 
@@ -56,7 +57,7 @@ __host__ __device__ constexpr int quad_waves_per_simd(int c_in, int qpm, int acc
 template <int CH, int KC, int NA, int CBSZ>
 __device__ __forceinline__ void quad_chain(const float (&a)[4], const float (&b)[32], f32x4& d0, f32x4& d1) {
     if constexpr (CH < KC) {
-        if constexpr (CH % 2 == 0)
+        if constexpr (CH % 2 == 0 || kQuadSingleChain)
             d0 = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d0, CBSZ, CH / NA, 0);
         else
             d1 = __builtin_amdgcn_mfma_f32_4x4x1f32(a[CH % NA], b[CH], d1, CBSZ, CH / NA, 0);
@@ -199,27 +200,31 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
                     pre_a[i] = occ_prefix[wa];
                     pre_b[i] = occ_prefix[wb];
                 }
+                // A line's taps sit next to each other in the bitmap: bit k of `win` = site of tap k occupied, valid
+                // (on the line, tap active).  The row of a present tap = rows before the window + present taps below it.
 #pragma unroll
                 for (int i = 0; i < kLineBatch; ++i) {
                     if (line0 + i >= n_lines) break;
                     const int tap0 = (line0 + i) * g.K[2];
+                    const unsigned first_bit = bit0[i] + (unsigned)(q2s + k_lo);
+                    const unsigned p = first_bit & 63u;   // position of the window's first site in word_a
+                    unsigned long long both = word_a[i] >> p;
+                    if (p) both |= word_b[i] << (64u - p);
+                    // taps on the line: k_lo <= k < min(K2, E2 - q2s); and active
+                    const int k_hi = g.E[2] - q2s < g.K[2] ? g.E[2] - q2s : g.K[2];
+                    unsigned valid = (k_hi >= 32 ? ~0u : ((1u << (k_hi > 0 ? k_hi : 0)) - 1u)) & ~((1u << k_lo) - 1u);
+                    valid &= act_mask >> tap0;
+                    const unsigned raw = (unsigned)both << k_lo;      // occupancy of the sites the taps look at
+                    const unsigned win = ok[i] ? raw & valid : 0u;    // ... where the tap counts
+                    mask |= win << tap0;
+                    // rows before the window in word_a; taps from bit s_k on lie in word_b, whose own prefix counts
+                    // from its first bit (every occupied site is a row, whether or not its tap counts)
+                    const unsigned s_k = 64u - p + (unsigned)k_lo;
+                    const unsigned base_a = pre_a[i] + (unsigned)__popcll(word_a[i] & ((1ull << p) - 1ull));
+                    const unsigned base_b = pre_b[i] - (unsigned)__popc(s_k >= 32u ? raw : raw & ((1u << s_k) - 1u));
                     for (int k = 0; k < g.K[2]; ++k) {
-                        unsigned off = kAbsent;
-                        const int q2 = q2s + k;
-                        if (ok[i] && (unsigned)q2 < (unsigned)g.E[2] && ((act_mask >> (tap0 + k)) & 1u)) {
-                            const unsigned bitpos = bit0[i] + (unsigned)q2;
-                            const bool second = (bitpos >> 6) != w_rel[i];
-                            const unsigned long long word = second ? word_b[i] : word_a[i];
-                            const unsigned bit = bitpos & 63u;
-                            if ((word >> bit) & 1ull) {
-                                const long long rr =
-                                    (long long)(second ? pre_b[i] : pre_a[i]) + __popcll(word & ((1ull << bit) - 1ull));
-                                if (rr < nnz_in) {  // (only an unsorted input can fail this)
-                                    off = (unsigned)rr * (unsigned)(C_IN * 4);
-                                    mask |= 1u << (tap0 + k);
-                                }
-                            }
-                        }
+                        const unsigned row = ((unsigned)k < s_k ? base_a : base_b) + (unsigned)__popc(raw & ((1u << k) - 1u));
+                        const unsigned off = ((win >> k) & 1u) ? row * (unsigned)(C_IN * 4) : kAbsent;
                         *(__attribute__((address_space(3))) unsigned*)(size_t)(tab_w + (unsigned)(tap0 + k) * 256u) = off;
                     }
                 }
@@ -405,9 +410,9 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
 #pragma unroll
                     for (int i = 0; i < 8; ++i) v[i] = tr_r[c - h * HC + i];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) __builtin_nontemporal_store(v[i], dst + (size_t)(c + i) * kTileRows);
+                    for (int i = 0; i < 8; ++i) dst[(size_t)(c + i) * kTileRows] = v[i];
                 }
-                for (; c < c_end; ++c) __builtin_nontemporal_store(tr_r[c - h * HC], dst + (size_t)c * kTileRows);
+                for (; c < c_end; ++c) dst[(size_t)c * kTileRows] = tr_r[c - h * HC];
             }
         }
         int next_wt = -1;
