@@ -28,7 +28,10 @@
  *       rows beyond out_capacity are not written)
  *   [1] number of candidate output sites examined (conv) / input rows (others)
  *   [2] status bits, see SCNN_FLAG_*; 0 = fine
- *   [3] reserved
+ *   [3] notes, not errors: 1 = the attention step found some column's k-th
+ *       strongest response outside the bracket it had estimated from a sample
+ *       of the column and settled that column from the whole column instead
+ *       (same result, more time); else 0
  * The caller reads them after its own synchronisation.
  *
  * Return value: SCNN_OK or a negative SCNN_E* code; scnn_last_error() gives a

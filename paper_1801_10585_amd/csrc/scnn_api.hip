@@ -211,11 +211,14 @@ struct ConvWs {
     unsigned long long* cand;
     unsigned long long* pbits;
     unsigned long long* occ_sel;
-    unsigned* hist;
     ColState* cols;
     unsigned long long* tile_state;
     size_t zero_bytes;
     // not zeroed
+    uint4* part;
+    unsigned long long* row_keep;
+    unsigned long long* row_plane;
+    long long* tile_base;
     unsigned* occ_prefix;
     unsigned* cand_prefix;
     unsigned* pprefix;
@@ -262,10 +265,15 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cand = c.take<unsigned long long>(nw);
     w->pbits = c.take<unsigned long long>(pool ? nwp : 0);
     w->occ_sel = c.take<unsigned long long>(pool ? nw : 0);  // occupancy of the selected rows, for the pooling
-    w->hist = c.take<unsigned>(ncols * kHistBins);
+    // rows known to survive are marked during the selection when the streaming compaction kernel can use them
+    const bool marks = !topk_small_columns(g) && c_out > 32 && c_out <= 64;
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
+    w->part = c.take<uint4>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
+    w->row_keep = c.take<unsigned long long>(marks ? 2 * w->tiles_cap : 0);
+    w->row_plane = c.take<unsigned long long>(marks ? 2 * w->tiles_cap * kMarkPlanes : 0);
+    w->tile_base = c.take<long long>(marks ? w->tiles_cap : 0);
     w->occ_prefix = c.take<unsigned>(nw);
     w->cand_prefix = c.take<unsigned>(nw);
     w->pprefix = c.take<unsigned>(pool ? nwp : 0);
@@ -425,18 +433,20 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
         g_last_conv_kernel = "k_conv_valu";
     }
     timer.mark();
-    SCNN_TRY(launch_topk(g, c_out, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
-                         ws.ctr, s));
+    const bool marks = !topk_small_columns(g) && c_out > 32 && c_out <= 64 && k > 0;
+    SCNN_TRY(launch_topk(g, c_out, k, topk_mode, relu, ws.tile_start, ws.resp, ws.cols, ws.side, ws.part,
+                         marks ? ws.row_keep : nullptr, marks ? ws.row_plane : nullptr, marks ? ws.tile_base : nullptr,
+                         ws.tiles_cap, ws.ctr, s));
     timer.mark();
     if (!pool) {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                      ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats,
-                                     out_capacity, (long long*)nnz_out, 0, 1, s));
+                                     out_capacity, (long long*)nnz_out, 0, 1, marks ? ws.tile_base : nullptr, s));
         timer.mark();
     } else {
         SCNN_TRY(launch_select_write(g, c_out, topk_mode, relu, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                      ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, ws.tmp_coords, ws.tmp_feats,
-                                     ws.cand_cap, nullptr, 0, 0, s));
+                                     ws.cand_cap, nullptr, 0, 0, marks ? ws.tile_base : nullptr, s));
         timer.mark();
         SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1,
                                 ws.occ_sel, ws.occ_prefix, ws.pbits, ws.pprefix, ws.block_sums, ws.pool_key,
@@ -665,10 +675,14 @@ int scnn_profile_collect(double* stage_ms, int64_t* calls) {
 namespace {
 struct TopkWs {
     Counters* ctr;
-    unsigned* hist;
     ColState* cols;
     unsigned long long* tile_state;
     size_t zero_bytes;
+    uint4* part;
+    unsigned long long* row_keep;
+    unsigned long long* row_plane;
+    long long* tile_base;
+    bool marks;
     unsigned* block_sums;
     int* cand_start;
     int* tile_start;
@@ -684,10 +698,14 @@ void carve_topk(void* base, const Geom& g, long long rows, int channels, TopkWs*
     const long long ncols = (long long)g.batch * channels;
     w->tiles_cap = (rows + kTileRows - 1) / kTileRows + g.batch;
     w->ctr = c.take<Counters>(1);
-    w->hist = c.take<unsigned>(ncols * kHistBins);
+    w->marks = !topk_small_columns(g) && channels > 32 && channels <= 64;
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
+    w->part = c.take<uint4>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
+    w->row_keep = c.take<unsigned long long>(w->marks ? 2 * w->tiles_cap : 0);
+    w->row_plane = c.take<unsigned long long>(w->marks ? 2 * w->tiles_cap * kMarkPlanes : 0);
+    w->tile_base = c.take<long long>(w->marks ? w->tiles_cap : 0);
     w->block_sums = c.take<unsigned>(scan_blocks(w->tiles_cap));
     w->cand_start = c.take<int>(g.batch + 1);
     w->tile_start = c.take<int>(g.batch + 1);
@@ -733,11 +751,13 @@ int attention_topk(int ndim, const int32_t* extent, int batch, const int32_t* co
     SCNN_TRY(launch_rows_sample_bounds(g, coords, rows, ws.cand_start, ws.tile_start, ws.ctr, s));
     SCNN_TRY(launch_rows_to_planar(g, coords, resp, channels, ws.cand_start, ws.tile_start, ws.ctr, ws.tiles_cap,
                                    ws.cand_lin, ws.resp, s));
-    SCNN_TRY(launch_topk(g, channels, k, topk_mode, ws.tile_start, ws.resp, ws.cols, ws.hist, ws.side, ws.side_cap,
-                         ws.ctr, s));
+    const bool marks = ws.marks && k > 0;
+    SCNN_TRY(launch_topk(g, channels, k, topk_mode, 0, ws.tile_start, ws.resp, ws.cols, ws.side, ws.part,
+                         marks ? ws.row_keep : nullptr, marks ? ws.row_plane : nullptr, marks ? ws.tile_base : nullptr,
+                         ws.tiles_cap, ws.ctr, s));
     SCNN_TRY(launch_select_write(g, channels, topk_mode, 0, ws.cand_start, ws.tile_start, ws.cand_lin, ws.resp,
                                  ws.cols, ws.tile_state, ws.tiles_cap, ws.ctr, out_coords, out_feats, out_capacity,
-                                 (long long*)nnz_out, rows, 0, s));
+                                 (long long*)nnz_out, rows, 0, marks ? ws.tile_base : nullptr, s));
     return SCNN_OK;
 }
 

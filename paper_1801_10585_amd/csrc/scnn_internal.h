@@ -30,16 +30,15 @@ struct Geom {
 
 // One per (sample, channel) column of the response matrix.
 struct ColState {
-    unsigned prefix;    // radix prefix found so far (high bits of the threshold key)
-    unsigned tau;       // final threshold key
-    long long k_rem;    // entries still to take from the current bin
+    unsigned tau;       // threshold key: the k-th strongest key of the column
+    unsigned cut;       // entries equal to tau survive up to this position in the column (0xffffffff: all of them)
     unsigned n_eq;      // entries whose key equals tau
     unsigned q;         // how many of those survive (lowest lin first)
+    unsigned tau_lo;    // bracket expected to hold tau, from a sample of the column: keys in [tau_lo, tau_hi] go to the
+    unsigned tau_hi;    //   side buffer, keys above tau_hi are only counted
     unsigned n_nz;      // non-zero entries in the column
-    int done;           // 1 = selection settled (bypass or k == 0), later passes skip the column
-    unsigned cut;       // equal entries survive up to this position in the column (0xffffffff: all of them)
-    unsigned side_fill; // side-buffer entries written so far
-    unsigned pad;
+    unsigned n_above;   // entries above the bracket
+    int done;           // 1 = tau and cut are final
     unsigned long long side_off;  // first side-buffer entry of the column
 };
 
@@ -55,7 +54,8 @@ struct Counters {
     int any_tie;          // some column needs tie ranks
     unsigned finished;    // workgroups of the compaction pass that have ended
     unsigned ticket;      // next tile of the compaction pass
-    unsigned long long side_cursor;  // side-buffer entries handed out to columns so far
+    unsigned bracket_failed;  // some column's threshold lay outside its sampled bracket
+    unsigned cols_done;       // columns whose selection has ended
     // tiles handed out so far in each of the contraction kernels' eight tile spans; one counter per 128-byte line:
     // read-modify-writes on one line are served one after the other, whichever word they address
     unsigned conv_ticket[8 * kTicketStride];
@@ -318,15 +318,25 @@ hipError_t launch_rows_sample_bounds(const Geom& g, const int32_t* coords, long 
 hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const float* feats, int channels,
                                  const int* cand_start, const int* tile_start, const Counters* ctr,
                                  long long tiles_cap, unsigned* cand_lin, float* resp, hipStream_t s);
-hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
-                       const float* resp, ColState* cols, unsigned* hist, uint2* side, unsigned long long side_cap,
-                       Counters* ctr, hipStream_t s);
+// Columns short enough for the one-workgroup selection (no sampled bracket, no marked rows).
+bool topk_small_columns(const Geom& g);
+// Row marks (all three nullable): row_keep, two 64-bit words per tile; row_plane, kMarkPlanes times as much;
+// tile_base, one word per tile.  When given, the columns are not small and k > 0, tile_base[t] becomes the output row
+// at which tile t starts, unless ctr->bracket_failed is set; launch_select_write must then be given tile_base.
+constexpr int kTopkPartWords = 256;  // slices of a column at most
+constexpr int kMarkPlanes = 64;  // one per channel where marks are used (up to 64 channels)
+hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int relu, const int* tile_start,
+                       const float* resp, ColState* cols, uint2* side,
+                       uint4* part /* kTopkPartWords entries per column */, unsigned long long* row_keep,
+                       unsigned long long* row_plane, long long* tile_base, long long tiles_cap, Counters* ctr,
+                       hipStream_t s);
 hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
                                long long* nnz_out /* nullable: also write the result counters */, long long aux_imm,
-                               int aux_is_cand, hipStream_t s);
+                               int aux_is_cand, const long long* tile_base /* nullable: from launch_topk */,
+                               hipStream_t s);
 
 // scnn_rows.hip
 hipError_t launch_relu(const Geom& g, const int32_t* coords, const float* feats, long long rows, int channels,

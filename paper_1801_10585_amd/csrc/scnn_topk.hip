@@ -15,6 +15,8 @@
 // equal entries (a second, ascending radix select on the side buffer) is the
 // cut.  The response matrix is read three times in all: histogram, collection,
 // and the final mask + compaction + write.
+#include <type_traits>
+
 #include "scnn_internal.h"
 
 namespace scnn {
@@ -103,7 +105,6 @@ hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const flo
 }
 
 // ------------------------------------------------------------------ radix select
-constexpr int kSideStage = 4096;  // side-buffer entries staged in LDS per workgroup before a flush
 
 // Rank search in a 2048-bin histogram held in LDS.  descending: find the bin holding the kk-th entry counted from
 // the top bin; else from the bottom bin.  Returns the bin and the number of entries strictly before it in that
@@ -156,214 +157,409 @@ __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descen
     __syncthreads();
 }
 
-// grid = (columns, slices).  Histogram of the top 11 key bits over the column's entries.
-__global__ __launch_bounds__(256) void k_hist0(int mode, int channels, const int* __restrict__ tile_start,
-                                               const float* __restrict__ resp, unsigned* __restrict__ hist,
-                                               long long k, ColState* __restrict__ cols, Counters* ctr,
-                                               unsigned long long side_cap) {
-    constexpr int U = 4;  // tiles per wave and iteration
-    __shared__ unsigned s_hist[kHistBins];
+// First launch: a bracket [tau_lo, tau_hi] around the k-th strongest key of every column, from a sample of the
+// column.  One workgroup per column reads every S-th tile of it (at most kBracketTiles tiles, whole tiles: 512
+// contiguous bytes per channel), keeps the keys in registers and looks up, by two radix digits (22 key bits), the
+// sample's keys at the ranks  r -+ delta,  r = k * (sample slots / column slots)  being where the k-th strongest
+// entry of the column is expected in the sample (empty slots rank last, as key 0).  delta = 8 standard deviations
+// of a uniformly drawn sample's rank plus half a percent of the sample: tiles are pieces of space, not independent
+// draws, hence the margin.  Nothing depends on the bracket being right: the second launch counts what lies above it
+// and the third one checks that the k-th entry fell inside, and settles the column from the response matrix itself
+// when it did not.
+constexpr int kBracketThreads = 1024;
+constexpr int kBracketPerThread = 16;
+constexpr int kBracketTiles = kBracketThreads * kBracketPerThread / kTileRows;  // 128
+
+__global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int channels,
+                                                             const int* __restrict__ tile_start,
+                                                             const float* __restrict__ resp, long long k,
+                                                             ColState* __restrict__ cols) {
+    __shared__ unsigned s_h[kHistBins], s_h2[kHistBins];
     __shared__ unsigned s_wave[4];
     __shared__ int s_res[2];
+    __shared__ unsigned s_total;
+    __shared__ unsigned s_range[2];
+    auto clamp_add = [](unsigned a, unsigned c) { return a + c < a ? 0xffffffffu : a + c; };
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
-    for (int i = threadIdx.x; i < kHistBins; i += 256) s_hist[i] = 0;
-    __syncthreads();
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int tile0 = t0 + (blockIdx.y * 4 + wave) * U; tile0 < t1; tile0 += 4 * U * gridDim.y) {
-        unsigned key[U][2];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int tile = tile0 + u;
-            const float* seg = resp + ((size_t)(tile < t1 ? tile : t0) * channels + oc) * kTileRows;
-            const unsigned k0 = score_key(seg[lane], mode), k1 = score_key(seg[64 + lane], mode);
-            key[u][0] = tile < t1 ? k0 : 0u;
-            key[u][1] = tile < t1 ? k1 : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-                if (key[u][h] != 0u) atomicAdd(&s_hist[key[u][h] >> 21], 1u);
-    }
-    __syncthreads();
-    unsigned* gh = hist + (size_t)col * kHistBins;
-    for (int i = threadIdx.x; i < kHistBins; i += 256) {
-        const unsigned c = s_hist[i];
-        if (c) atomicAdd(&gh[i], c);
-    }
-    // The block that finishes a column last goes on to pick the bin of the k-th strongest entry and a slice of the
-    // side buffer for that bin.  (cols[col].pad counts the column's finished blocks until the state is written.)
-    // The histogram is only ever touched by device-scope atomics, which are performed at the point of coherence;
-    // the barrier waits for this block's to be acknowledged, so no cache flush (fence) is needed before the count.
-    __syncthreads();
-    if (threadIdx.x == 0) s_res[0] = (atomicAdd(&cols[col].pad, 1u) == gridDim.y - 1) ? 1 : 0;
-    __syncthreads();
-    if (!s_res[0]) return;
-    unsigned* s_h = s_hist;
-    unsigned local = 0;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const unsigned c = __hip_atomic_load(&gh[threadIdx.x * 8 + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_h[threadIdx.x * 8 + i] = c;
-        local += c;
-    }
-    unsigned total;
-    (void)block_exclusive_scan_256(local, s_wave, total);
+    const int T = t1 - t0;
     ColState st;
-    st.prefix = 0; st.tau = 0; st.k_rem = k; st.n_eq = 0; st.q = 0; st.n_nz = total; st.done = 0; st.cut = 0xffffffffu;
-    st.side_off = 0; st.side_fill = 0; st.pad = 0;
-    if (k <= 0) {
+    st.tau = 0; st.cut = 0xffffffffu; st.n_eq = 0; st.q = 0; st.tau_lo = 1u; st.tau_hi = 0u; st.n_nz = 0; st.n_above = 0;
+    st.done = 0;
+    st.side_off = ((unsigned long long)t0 * channels + (unsigned long long)oc * T) * kTileRows;
+    if (k <= 0 || T == 0) {
         st.done = 1;
-        st.tau = 0xffffffffu;  // no key is stronger: nothing survives
-    } else if ((long long)total <= k) {
-        st.done = 1;           // fewer entries than k: all survive (tau = 0, every non-zero key is above it)
-    }
-    if (st.done) {
+        if (k <= 0) st.tau = 0xffffffffu;  // no key is stronger: nothing survives
         if (threadIdx.x == 0) cols[col] = st;
         return;
     }
-    int bin;
-    unsigned before;
-    block_pick(s_h, k, true, s_wave, s_res, bin, before);
+    const int S = (T + kBracketTiles - 1) / kBracketTiles;  // every S-th tile
+    const int ns_tiles = (T + S - 1) / S;
+    const unsigned m_s = (unsigned)ns_tiles * kTileRows;
     if (threadIdx.x == 0) {
-        st.prefix = (unsigned)bin;
-        st.k_rem = k - (long long)before;
-        st.n_eq = s_h[bin];  // for now: entries in the bin = entries the side buffer will hold
-        const unsigned long long off = atomicAdd(&ctr->side_cursor, (unsigned long long)st.n_eq);
-        if (off + st.n_eq > side_cap) {  // cannot happen with the documented workspace size
-            atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
-            st.done = 1;
-            st.tau = 0xffffffffu;
-        }
-        st.side_off = off;
-        cols[col] = st;
+        s_total = 0;
+        s_range[0] = 0xffffffffu;
+        s_range[1] = 0u;
     }
+    unsigned key[kBracketPerThread];
+    unsigned mine = 0;
+#pragma unroll
+    for (int u = 0; u < kBracketPerThread; ++u) {
+        const unsigned i = (unsigned)u * kBracketThreads + threadIdx.x;
+        key[u] = 0u;
+        if (i < m_s)
+            key[u] = score_key(resp[((size_t)(t0 + (int)(i >> 7) * S) * channels + oc) * kTileRows + (i & 127u)], mode);
+        mine += key[u] != 0u ? 1u : 0u;
+    }
+    // the sample's entries, and the range of their keys
+    unsigned kmin = 0xffffffffu, kmax = 0u;
+#pragma unroll
+    for (int u = 0; u < kBracketPerThread; ++u) {
+        if (key[u] != 0u) {
+            kmin = key[u] < kmin ? key[u] : kmin;
+            kmax = key[u] > kmax ? key[u] : kmax;
+        }
+    }
+    __syncthreads();  // (s_total and the range words are set up)
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        mine += __shfl_xor(mine, d, 64);
+        const unsigned a = __shfl_xor(kmin, d, 64), c = __shfl_xor(kmax, d, 64);
+        kmin = a < kmin ? a : kmin;
+        kmax = c > kmax ? c : kmax;
+    }
+    if ((threadIdx.x & 63) == 0 && mine) {
+        atomicAdd(&s_total, mine);
+        atomicMin(&s_range[0], kmin);
+        atomicMax(&s_range[1], kmax);
+    }
+    __syncthreads();
+    const long long nz = (long long)s_total;
+    kmin = s_range[0];
+    kmax = s_range[1];
+    const double r = (double)k * (double)m_s / ((double)T * kTileRows);
+    const double frac = r / (double)m_s;
+    double delta = 0.0;  // (a sample of every tile is the column: the ranks are exact)
+    if (S > 1) delta = 8.0 * sqrt(r * (frac < 1.0 ? 1.0 - frac : 0.0)) + 0.005 * (double)m_s + 16.0;
+    const double r_up = floor(r - delta), r_dn = ceil(r + delta);
+    // The sample's keys at ranks r_up and r_dn (1 = strongest), cut down to two digits of 11 bits.  The digits are
+    // taken from key - kmin: the leading bits of the keys themselves are the same for most of a column (sign, high
+    // exponent bits), and a histogram whose entries fall into a dozen bins is a queue at those LDS words.  Past the
+    // sample's entries on the strong side nothing is above the bracket; past them on the weak side every entry is in
+    // it or above it.
+    const bool want_up = r_up >= 1.0 && (long long)r_up <= nz, want_dn = r_dn >= 1.0 && r_dn <= (double)nz;  // (uniform)
+    long long rank_up = want_up ? (long long)r_up : 1, rank_dn = want_dn ? (long long)r_dn : 1;
+    const unsigned span = nz > 0 ? kmax - kmin : 0u;
+    const int nb = span ? 32 - __clz(span) : 1;  // bits of key - kmin
+    const int sh1 = nb > 11 ? nb - 11 : 0;       // first digit: bits [sh1, nb)
+    const int sh2 = sh1 > 11 ? sh1 - 11 : 0;     // second digit: bits [sh2, sh1)
+    const unsigned mask2 = (1u << (sh1 - sh2)) - 1u;
+    for (int i = threadIdx.x; i < kHistBins; i += kBracketThreads) s_h[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kBracketPerThread; ++u)
+        if (key[u] != 0u) atomicAdd(&s_h[(key[u] - kmin) >> sh1], 1u);
+    __syncthreads();
+    int bin_up = 0, bin_dn = 0;
+    unsigned before = 0;
+    if (nz > 0) {
+        block_pick(s_h, rank_up, true, s_wave, s_res, bin_up, before);
+        rank_up -= (long long)before;
+        block_pick(s_h, rank_dn, true, s_wave, s_res, bin_dn, before);
+        rank_dn -= (long long)before;
+    }
+    int sub_up = 0, sub_dn = 0;
+    if (sh1 > 0) {  // (uniform)
+        for (int i = threadIdx.x; i < kHistBins; i += kBracketThreads) {
+            s_h[i] = 0;
+            s_h2[i] = 0;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kBracketPerThread; ++u) {
+            if (key[u] == 0u) continue;
+            const unsigned d = key[u] - kmin;
+            if ((int)(d >> sh1) == bin_up) atomicAdd(&s_h[(d >> sh2) & mask2], 1u);
+            if ((int)(d >> sh1) == bin_dn) atomicAdd(&s_h2[(d >> sh2) & mask2], 1u);
+        }
+        __syncthreads();
+        if (nz > 0) {
+            block_pick(s_h, rank_up, true, s_wave, s_res, sub_up, before);
+            block_pick(s_h2, rank_dn, true, s_wave, s_res, sub_dn, before);
+        }
+    }
+    st.tau_hi = 0xffffffffu;  // rank < 1: nothing is above
+    if (r_up >= 1.0)  // (the upper end of the two-digit bin)
+        st.tau_hi =
+            want_up ? clamp_add(kmin, ((unsigned)bin_up << sh1) | ((unsigned)sub_up << sh2) | ((1u << sh2) - 1u)) : 0u;
+    if (want_dn) {
+        const unsigned lo = kmin + (((unsigned)bin_dn << sh1) | ((unsigned)sub_dn << sh2));
+        st.tau_lo = lo ? lo : 1u;
+    }
+    if (threadIdx.x == 0) cols[col] = st;
 }
 
-// grid = (columns, slices).  Copy the entries of the threshold bin, with their position in the column, to the
-// column's slice of the side buffer (order within the slice does not matter).  Every wave stages its hits in its
-// own piece of LDS and flushes it on its own, so the loop has no workgroup barrier.
-__global__ __launch_bounds__(256) void k_collect(int mode, int channels, const int* __restrict__ tile_start,
-                                                 const float* __restrict__ resp, ColState* __restrict__ cols,
-                                                 uint2* __restrict__ side) {
-    constexpr int U = 4;                 // tile pairs per wave and iteration
-    constexpr int WCAP = kSideStage / 4; // staged entries per wave
-    __shared__ uint2 s_buf[kSideStage];
-    const int col = blockIdx.x;
+// Second launch, grid = (sample x group of kClassifyWaves channels, slices); a wave per channel, the waves of a
+// workgroup on the same tiles (adjacent channels of a tile are adjacent in memory).  Counts the column's entries and
+// those above the bracket, copies the entries inside it (value and position in the column) to the side buffer, and,
+// when row_plane is given, records which rows hold an entry above the bracket -- those survive whatever the exact
+// threshold turns out to be -- in the channel's own plane of row marks, two 64-bit words per tile, which
+// k_combine_marks merges.  Nothing here is shared between waves: a slice of a column is a run of consecutive tiles
+// and owns a run of the column's side-buffer entries long enough for all of them, so there is no counter to
+// reserve from and no barrier.  (Marks kept in one shared plane cost 40 us of device-scope atomics on the r = 128
+// layer, and reserving side-buffer space from a counter per column about as much again.)  The loop is bound by
+// instruction issue, hence the float compares on ballots, the counts in scalar registers and the marks gathered
+// with v_writelane.
+// With the score s(x) = |x| or x: the value t such that, for an entry x (non-zero, not a NaN),
+// score_key(x) > key  <=>  s(x) > t  and  score_key(x) >= key  <=>  s(x) >= t:  the float whose key `key` is, or, for the
+// keys below every float's (signed order: 0 .. 0x007fffff), minus infinity.  Key 0xffffffff gives a NaN: no score
+// compares above it.
+__device__ inline float score_bound(unsigned key, int mode) {
+    if (mode == SCNN_TOPK_ABS) return __uint_as_float(key);  // (keys are the bit patterns of |x|; key 0 is 0.0)
+    if (key >= 0x80000000u) return __uint_as_float(key & 0x7fffffffu);
+    return key <= 0x007fffffu ? -INFINITY : __uint_as_float(~key);
+}
+
+// v with lane `lane` (uniform) replaced by the uniform value x
+__device__ inline unsigned write_lane(unsigned v, unsigned x, int lane) {
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(x), "i"(lane));  // (lane: a constant once the loops are unrolled)
+    return v;
+}
+
+constexpr int kClassifyWaves = 8;
+constexpr int kClassifyTiles = 4;
+constexpr int kClassifySlicesMax = 256;  // (the third launch scans a column's slices with its first 256 threads)
+
+// Tiles per slice when a column of T tiles is cut into `slices` runs of whole iterations.
+__host__ __device__ inline int classify_slice_tiles(int T, int slices) {
+    const int per = (T + slices - 1) / slices;
+    return (per + kClassifyTiles - 1) / kClassifyTiles * kClassifyTiles;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int channels,
+                                                                  const int* __restrict__ tile_start,
+                                                                  const float* __restrict__ resp,
+                                                                  const ColState* __restrict__ cols,
+                                                                  uint2* __restrict__ side, uint4* __restrict__ part,
+                                                                  unsigned long long* __restrict__ row_plane,
+                                                                  long long plane_words) {
+    constexpr int U = kClassifyTiles;  // tiles per iteration
+    constexpr int WCAP = 768;          // staged entries per wave (a flush leaves room for an iteration's worth)
+    __shared__ uint2 s_buf[kClassifyWaves * WCAP];
+    const int groups = (channels + kClassifyWaves - 1) / kClassifyWaves;
+    const int b = blockIdx.x / groups;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // (uniform, and known to be)
+    const int oc = (blockIdx.x - b * groups) * kClassifyWaves + wave;
+    if (oc >= channels) return;  // (the last group may be short)
+    const int col = b * channels + oc;
     const ColState st = cols[col];
     if (st.done) return;
-    const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const float s_lo = score_bound(st.tau_lo, MODE), s_hi = score_bound(st.tau_hi, MODE);
+    const unsigned long long relu_off = relu ? 0ull : ~0ull;
     uint2* wbuf = s_buf + wave * WCAP;
-    int fill = 0;  // wave-uniform
+    int fill = 0;                    // wave-uniform
+    unsigned n_nz = 0, n_above = 0;  // wave-uniform
+    // slice y of the column: tiles [first, last), and a run of the column's side-buffer entries that could hold every
+    // one of their entries
+    const int L = classify_slice_tiles(t1 - t0, (int)gridDim.y);
+    const int first = t0 + (int)blockIdx.y * L;
+    const int last = first + L < t1 ? first + L : t1;
+    uint2* run = side + st.side_off + (unsigned long long)blockIdx.y * L * kTileRows;
+    unsigned written = 0;  // wave-uniform
     auto flush = [&]() {
-        unsigned base = 0;
-        if (lane == 0) base = atomicAdd(&cols[col].side_fill, (unsigned)fill);
-        base = __shfl(base, 0, 64);
-        for (int i = lane; i < fill; i += 64) side[st.side_off + base + i] = wbuf[i];
+        for (int i = lane; i < fill; i += 64) run[written + i] = wbuf[i];
+        written += (unsigned)fill;
         fill = 0;
     };
-    // a wave takes whole tiles (two 64-row halves), tiles wave, wave + 4, ... of the slice
-    for (int tile0 = t0 + (blockIdx.y * 4 + wave) * U; tile0 < t1; tile0 += 4 * U * gridDim.y) {
-        unsigned key[U][2];
+    unsigned long long* plane = row_plane ? row_plane + (size_t)oc * plane_words : nullptr;
+    // the values of tiles tile0 .. tile0 + U - 1 at rows lane and lane + 64 (a tile past the slice: the slice's first)
+    auto load = [&](int tile0, float (&v)[U][2]) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int tile = tile0 + u;
-            const float* seg = resp + ((size_t)(tile < t1 ? tile : t0) * channels + oc) * kTileRows;
-            const unsigned k0 = score_key(seg[lane], mode), k1 = score_key(seg[64 + lane], mode);
-            key[u][0] = tile < t1 ? k0 : 0u;
-            key[u][1] = tile < t1 ? k1 : 0u;
+            const float* seg = resp + ((size_t)(tile < last ? tile : first) * channels + oc) * kTileRows;
+            v[u][0] = seg[lane];
+            v[u][1] = seg[64 + lane];
         }
+    };
+    // one iteration: the tiles tile0 .. tile0 + U - 1, whose values are in v; FULL: all of them are in the slice
+    auto process = [&](int tile0, const float (&v)[U][2], auto full) {
+        constexpr bool FULL = decltype(full)::value;
+        unsigned mark_lo = 0, mark_hi = 0;  // lane j: the marks of tile j / 2, rows (j & 1) * 64 ..
 #pragma unroll
-        for (int u = 0; u < U; ++u)
+        for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const bool hit = key[u][h] != 0u && (key[u][h] >> 21) == st.prefix;
-                const unsigned long long m = __ballot(hit);
-                if (hit)
-                    wbuf[fill + __popcll(m & lt_mask)] =
-                        make_uint2(key[u][h], (unsigned)(tile0 + u - t0) * kTileRows + (unsigned)(h * 64 + lane));
+                const float x = (FULL || tile0 + u < last) ? v[u][h] : 0.0f;
+                const float sc = MODE == SCNN_TOPK_ABS ? fabsf(x) : x;
+                // (ballots of single compares: the compare writes the mask; the masks are combined as scalars)
+                const unsigned long long nz = __ballot(x != 0.0f);
+                const unsigned long long above = __ballot(sc > s_hi) & nz;
+                const unsigned long long m = __ballot(sc >= s_lo) & nz & ~above;  // inside the bracket
+                const bool hit = x != 0.0f && sc >= s_lo && !(sc > s_hi);
+                n_nz += (unsigned)__popcll(nz);
+                n_above += (unsigned)__popcll(above);
+                if (plane) {
+                    const unsigned long long sure = above & (__ballot(x > 0.0f) | relu_off);
+                    mark_lo = write_lane(mark_lo, (unsigned)sure, u * 2 + h);
+                    mark_hi = write_lane(mark_hi, (unsigned)(sure >> 32), u * 2 + h);
+                }
+                if (hit) {  // the value itself is staged; its key is taken when the entry is read
+                    const unsigned rank =
+                        __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
+                    wbuf[fill + (int)rank] = make_uint2(__float_as_uint(x), (unsigned)(tile0 + u - t0) * kTileRows +
+                                                                                 (unsigned)(h * 64 + lane));
+                }
                 fill += __popcll(m);
             }
-        if (fill > WCAP - U * 128) flush();
+        }
+        if (plane && lane < 2 * U && (FULL || tile0 + (lane >> 1) < last))
+            plane[2 * (size_t)tile0 + lane] = ((unsigned long long)mark_hi << 32) | mark_lo;
+    };
+    auto process_any = [&](int tile0, const float (&v)[U][2]) {
+        if (tile0 + U <= last) process(tile0, v, std::true_type{});
+        else process(tile0, v, std::false_type{});
+    };
+    // Two register sets in turn, so that an iteration's loads are in flight during the whole of the one before it.
+    // The staging buffer is emptied, when an iteration could overfill it, before the next loads are issued, never
+    // between an iteration's loads and their use, and the next loads are issued whether or not there is a next
+    // iteration: the compiler counts outstanding loads along every path, and behind a loop of stores, or a branch
+    // that may have skipped the loads, it waits for all of them.
+    auto make_room = [&]() {
+        if (fill > WCAP - U * kTileRows) flush();
+    };
+    float va[U][2], vb[U][2];
+    if (first < last) load(first, va);
+    for (int tile0 = first; tile0 < last; tile0 += 2 * U) {
+        make_room();
+        load(tile0 + U, vb);  // (always: past the slice it reads the slice's first tile again, and nobody looks)
+        process_any(tile0, va);
+        if (tile0 + U >= last) break;
+        make_room();
+        load(tile0 + 2 * U, va);
+        process_any(tile0 + U, vb);
     }
     if (fill > 0) flush();
+    if (lane == 0) part[(size_t)col * gridDim.y + blockIdx.y] = make_uint4(n_nz, n_above, written, 0u);
 }
 
-// One block per column: settle the remaining 21 key bits on the side buffer, then, if the equal entries do not all
-// fit, the position below which they do.
+// Third launch, one workgroup per column: the exact k-th strongest key tau, the number of entries equal to it and,
+// if those do not all fit, the position up to which they do -- by radix select over the column's side-buffer
+// entries when the bracket held the k-th entry (the rule), over the column itself when it did not.
 constexpr int kSideThreads = 1024;
 
-__global__ __launch_bounds__(kSideThreads) void k_side_select(ColState* __restrict__ cols,
-                                                              const uint2* __restrict__ side) {
-    __shared__ unsigned s_h[kHistBins];
-    __shared__ unsigned s_wave[4];
-    __shared__ int s_res[2];
-    const int col = blockIdx.x;
-    ColState st = cols[col];
-    if (st.done) return;
-    const uint2* e = side + st.side_off;
-    const unsigned m = st.n_eq;
+struct SideEntries {  // entry i of a column's side-buffer entries, which lie in one run per slice
+    const uint2* e;         // the column's first run
+    const unsigned* start;  // (LDS) start[s] = entries in the runs before run s; start[slices] = all of them
+    int slices;
+    unsigned run_pitch;     // entries from one run to the next
+    int mode;
+    // {key, position}; the buffer holds the value's bits
+    __device__ uint2 operator()(unsigned i) const {
+        int lo = 0, hi = slices - 1;  // last run that starts at or before i
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (start[mid] <= i) lo = mid; else hi = mid - 1;
+        }
+        const uint2 x = e[(size_t)lo * run_pitch + (i - start[lo])];
+        return make_uint2(score_key(__uint_as_float(x.x), mode), x.y);
+    }
+};
+struct ColumnEntries {  // slot i of a column of the response matrix (key 0: not an entry)
+    const float* col;   // the column's values in its first tile
+    size_t tile_pitch;  // floats from one tile to the next
+    int mode;
+    __device__ uint2 operator()(unsigned i) const {
+        return make_uint2(score_key(col[(size_t)(i >> 7) * tile_pitch + (i & 127u)], mode), i);
+    }
+};
+
+// tau = the kk-th strongest key among m entries {key, position} whose keys lie in [key_lo, key_hi] (key 0: not an
+// entry); n_eq entries equal it, the q of lowest position survive: those at positions <= cut.  1 <= kk <= number of
+// entries.  The digits of the radix select, 11 bits at most, are taken from key - key_lo, most significant first, so
+// that a narrow bracket is settled in two passes.  Up to kSettleCached entries per thread are held in registers
+// between the passes.  (whole workgroup)
+constexpr int kSettleCached = 16;
+
+// held: the entries threadIdx.x + 1024 * u of the column, if cached (m <= kSettleCached * 1024), loaded by the caller.
+template <class Entries>
+__device__ inline void settle_column(const Entries& entry, unsigned m, const uint2 (&held)[kSettleCached], bool cached,
+                                     unsigned key_lo, unsigned key_hi, long long kk, unsigned* s_h, unsigned* s_wave,
+                                     int* s_res, unsigned& tau, unsigned& n_eq, unsigned& q, unsigned& cut) {
     auto clear = [&]() {
         for (int i = threadIdx.x; i < kHistBins; i += kSideThreads) s_h[i] = 0;
         __syncthreads();
     };
-    // histogram of digit(entry) over the entries that pass(entry), loads issued eight at a time
+    // Data with long runs of equal scores (unit input values) sends most lanes of a wave to one bin, and LDS serves
+    // the atomics of a wave on one word one after the other: the lanes that share the first active lane's bin add
+    // once, through that lane; the others add on their own.
+    auto add = [&](bool valid, unsigned bin) {
+        const unsigned long long act = __ballot(valid);
+        if (act == 0ull) return;  // (uniform)
+        const int first = __ffsll((long long)act) - 1;
+        const unsigned b0 = __shfl(valid ? bin : 0u, first, 64);
+        const unsigned long long same = __ballot(valid && bin == b0);
+        if ((int)(threadIdx.x & 63) == first) atomicAdd(&s_h[b0], (unsigned)__popcll(same));
+        else if (valid && bin != b0) atomicAdd(&s_h[bin], 1u);
+    };
+    // histogram of digit(entry) over the entries that pass(entry)
     auto histogram = [&](auto pass, auto digit) {
-        for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {
-            uint2 x[8];
+        clear();
+        if (cached) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const unsigned i = i0 + (unsigned)kSideThreads * u;
-                x[u] = i < m ? e[i] : make_uint2(0u, 0u);
+            for (int u = 0; u < kSettleCached; ++u) {
+                const bool valid = held[u].x != 0u && pass(held[u]);
+                add(valid, valid ? digit(held[u]) : 0u);
             }
-            // Data with long runs of equal scores (unit input values) sends most lanes of a wave to one bin, and LDS
-            // serves the atomics of a wave on one word one after the other: the lanes that share the first active
-            // lane's bin add once, through that lane; the others add on their own.
+        } else {
+            for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // loads issued eight at a time
+                uint2 x[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const bool valid = i0 + (unsigned)kSideThreads * u < m && pass(x[u]);
-                const unsigned bin = valid ? digit(x[u]) : 0u;
-                const unsigned long long act = __ballot(valid);
-                if (act == 0ull) continue;  // (uniform)
-                const int first = __ffsll((long long)act) - 1;
-                const unsigned b0 = __shfl(bin, first, 64);
-                const unsigned long long same = __ballot(valid && bin == b0);
-                if ((int)(threadIdx.x & 63) == first) atomicAdd(&s_h[b0], (unsigned)__popcll(same));
-                else if (valid && bin != b0) atomicAdd(&s_h[bin], 1u);
+                for (int u = 0; u < 8; ++u) {
+                    const unsigned i = i0 + (unsigned)kSideThreads * u;
+                    x[u] = i < m ? entry(i) : make_uint2(0u, 0u);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const bool valid = x[u].x != 0u && pass(x[u]);
+                    add(valid, valid ? digit(x[u]) : 0u);
+                }
             }
         }
         __syncthreads();
     };
-    int bin;
-    unsigned before;
-    // key bits [20:10]
-    clear();
-    histogram([](uint2) { return true; }, [](uint2 x) { return (x.x >> 10) & 0x7ffu; });
-    block_pick(s_h, st.k_rem, true, s_wave, s_res, bin, before);
-    const unsigned prefix2 = (st.prefix << 11) | (unsigned)bin;
-    const long long k_rem = st.k_rem - (long long)before;
-    // key bits [9:0]
-    clear();
-    histogram([prefix2](uint2 x) { return (x.x >> 10) == prefix2; }, [](uint2 x) { return x.x & 0x3ffu; });
-    block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);
-    const unsigned tau = (prefix2 << 10) | (unsigned)bin;
-    const unsigned n_eq = s_h[bin];
-    const unsigned q = (unsigned)(k_rem - (long long)before);  // 1 <= q <= n_eq
+    int bin = 0;
+    unsigned before = 0;
+    const unsigned span = key_hi - key_lo;
+    int nb = span ? 32 - __clz(span) : 1;  // bits of key - key_lo still open
+    unsigned prefix = 0;                   // the bits above them
+    while (nb > 0) {
+        const int w = nb < 11 ? nb : 11, shift = nb - w;
+        const int above = nb;  // (captured by value)
+        histogram([=](uint2 x) { return (unsigned)((unsigned long long)(x.x - key_lo) >> above) == prefix; },
+                  [=](uint2 x) { return ((x.x - key_lo) >> shift) & ((1u << w) - 1u); });
+        block_pick(s_h, kk, true, s_wave, s_res, bin, before);
+        kk -= (long long)before;
+        prefix = (prefix << w) | (unsigned)bin;
+        nb = shift;
+    }
+    tau = key_lo + prefix;
+    n_eq = s_h[bin];
+    q = (unsigned)kk;  // 1 <= q <= n_eq
     __syncthreads();
-    unsigned cut = 0xffffffffu;
+    cut = 0xffffffffu;
     if (q < n_eq) {
         // q-th smallest position among the entries equal to tau: ascending radix select on the position
+        const unsigned t = tau;
         unsigned pprefix = 0;
         long long rank = q;
         for (int pass = 0; pass < 3; ++pass) {
             const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0), bits = pass == 2 ? 10 : 11;
-            clear();
-            histogram([=](uint2 x) { return x.x == tau && (pass == 0 || (x.y >> (shift + bits)) == pprefix); },
+            histogram([=](uint2 x) { return x.x == t && (pass == 0 || (x.y >> (shift + bits)) == pprefix); },
                       [=](uint2 x) { return (x.y >> shift) & ((1u << bits) - 1u); });
             block_pick(s_h, rank, false, s_wave, s_res, bin, before);
             pprefix = (pprefix << bits) | (unsigned)bin;
@@ -371,13 +567,193 @@ __global__ __launch_bounds__(kSideThreads) void k_side_select(ColState* __restri
         }
         cut = pprefix;
     }
-    if (threadIdx.x == 0) {
-        st.tau = tau;
-        st.n_eq = n_eq;
-        st.q = q;
-        st.cut = cut;
-        cols[col] = st;
+}
+
+__global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int channels, long long k,
+                                                         const int* __restrict__ tile_start,
+                                                         const float* __restrict__ resp, ColState* __restrict__ cols,
+                                                         const uint2* __restrict__ side,
+                                                         const uint4* __restrict__ part, int slices,
+                                                         unsigned long long* row_keep,
+                                                         long long* __restrict__ tile_base, Counters* ctr) {
+    __shared__ unsigned s_h[kHistBins];
+    __shared__ unsigned s_wave[4];
+    __shared__ int s_res[2];
+    __shared__ uint4 s_part[4];
+    __shared__ unsigned s_start[kClassifySlicesMax + 1];
+    const int col = blockIdx.x;
+    const int b = col / channels, oc = col - b * channels;
+    const int t0 = tile_start[b], t1 = tile_start[b + 1];
+    ColState st = cols[col];
+    // the slices' counts: entries, entries above the bracket, entries in the side buffer's runs (read along with the
+    // column's state; unused, and possibly stale, where the column is settled already)
+    uint4 my_part = make_uint4(0u, 0u, 0u, 0u);
+    if ((int)threadIdx.x < slices) my_part = part[(size_t)col * slices + threadIdx.x];
+    if (!st.done) {
+        unsigned mine = my_part.z, sum_nz = my_part.x, sum_above = my_part.y;
+        unsigned inc = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned t = __shfl_up(inc, d, 64);
+            if ((int)(threadIdx.x & 63) >= d) inc += t;
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            sum_nz += __shfl_xor(sum_nz, d, 64);
+            sum_above += __shfl_xor(sum_above, d, 64);
+        }
+        if (threadIdx.x < 256 && (threadIdx.x & 63) == 63) {
+            s_part[threadIdx.x >> 6] = make_uint4(sum_nz, sum_above, inc, 0u);
+        }
+        __syncthreads();
+        unsigned before = 0;
+        st.n_nz = 0;
+        st.n_above = 0;
+        unsigned m = 0;
+        for (int w = 0; w < 4; ++w) {
+            const uint4 p = s_part[w];
+            if (w < (int)(threadIdx.x >> 6)) before += p.z;
+            st.n_nz += p.x;
+            st.n_above += p.y;
+            m += p.z;
+        }
+        if ((int)threadIdx.x < slices) s_start[threadIdx.x] = before + inc - mine;
+        if (threadIdx.x == 0) s_start[slices] = m;
+        __syncthreads();
+        const int T = t1 - t0;
+        const float* col0 = resp + ((size_t)t0 * channels + oc) * kTileRows;
+        const size_t pitch = (size_t)channels * kTileRows;
+        const SideEntries e{side + st.side_off, s_start, slices, (unsigned)classify_slice_tiles(T, slices) * kTileRows,
+                            mode};
+        // the side buffer's entries of the column, in registers if they are few enough (the rule)
+        const bool cached = m <= (unsigned)kSettleCached * kSideThreads;  // (uniform)
+        uint2 kept[kSettleCached];
+        if (cached) {
+#pragma unroll
+            for (int u = 0; u < kSettleCached; ++u) {
+                const unsigned i = threadIdx.x + (unsigned)kSideThreads * u;
+                kept[u] = i < m ? e(i) : make_uint2(0u, 0u);
+            }
+        }
+        bool held;  // the side buffer decides the column
+        if ((long long)st.n_nz <= k) {
+            // fewer entries than k: all survive (tau = 0, every non-zero key is above it); the rows are all marked if
+            // no entry lay below the bracket
+            st.tau = 0;
+            held = st.n_above + m == st.n_nz;
+        } else {
+            const long long k_rem = k - (long long)st.n_above;
+            held = k_rem >= 1 && k_rem <= (long long)m;
+            if (held)
+                settle_column(e, m, kept, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq, st.q,
+                              st.cut);
+            else
+                settle_column(ColumnEntries{col0, pitch, mode}, (unsigned)(t1 - t0) * kTileRows, kept, false, 0u,
+                              0xffffffffu, k, s_h, s_wave, s_res, st.tau, st.n_eq, st.q, st.cut);
+        }
+        if (threadIdx.x == 0) {
+            st.done = 1;
+            cols[col] = st;
+            if (!held) atomicOr(&ctr->bracket_failed, 1u);  // the rows marked so far cannot be relied on
+        }
+        if (row_keep && held) {
+            // the bracket's entries that survive keep their rows too
+            auto survives = [&](uint2 x) { return x.x > st.tau || (x.x == st.tau && x.x != 0u && x.y <= st.cut); };
+            auto word_of = [&](uint2 x) { return row_keep + 2 * (size_t)(t0 + (int)(x.y >> 7)) + ((x.y >> 6) & 1u); };
+            auto mark = [&](uint2 x, unsigned long long have) {
+                const unsigned long long bit = 1ull << (x.y & 63u);
+                if (have & bit) return;
+                if (relu && !(col0[(size_t)(x.y >> 7) * pitch + (x.y & 127u)] > 0.0f)) return;
+                atomicOr(word_of(x), bit);
+            };
+            if (cached) {
+                unsigned long long have[kSettleCached];
+#pragma unroll
+                for (int u = 0; u < kSettleCached; ++u) {
+                    have[u] = ~0ull;
+                    if (survives(kept[u]))
+                        have[u] = __hip_atomic_load(word_of(kept[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int u = 0; u < kSettleCached; ++u) mark(kept[u], have[u]);
+            } else {
+                for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // eight entries in flight per thread
+                    uint2 x[8];
+                    unsigned long long have[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const unsigned i = i0 + (unsigned)kSideThreads * u;
+                        x[u] = i < m ? e(i) : make_uint2(0u, 0u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        have[u] = ~0ull;
+                        if (survives(x[u]))
+                            have[u] = __hip_atomic_load(word_of(x[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) mark(x[u], have[u]);
+                }
+            }
+        }
     }
+    if (!tile_base) return;
+    // The workgroup that ends last turns the marked rows into the output row at which every tile starts.  The marks
+    // are only ever touched by device-scope atomics, which are performed at the point of coherence; the barrier waits
+    // for this workgroup's to be acknowledged, so no cache write-back (a fence, tens of microseconds here) is needed
+    // before the count.
+    __syncthreads();
+    if (threadIdx.x == 0) s_res[0] = (atomicAdd(&ctr->cols_done, 1u) == gridDim.x - 1) ? 1 : 0;
+    __syncthreads();
+    if (!s_res[0]) return;
+    if (__hip_atomic_load(&ctr->bracket_failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) return;
+    const int n_tiles = (int)ctr->n_tiles;
+    const int per = (n_tiles + kSideThreads - 1) / kSideThreads;  // consecutive tiles per thread
+    const int first = threadIdx.x * per;
+    auto rows_of = [&](int t) -> unsigned {
+        return (unsigned)(__popcll(__hip_atomic_load(&row_keep[2 * (size_t)t], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) +
+                          __popcll(__hip_atomic_load(&row_keep[2 * (size_t)t + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+    };
+    constexpr int kKept = 8;  // counts held in registers between the two sweeps
+    unsigned cnt[kKept];
+    unsigned local = 0;
+#pragma unroll
+    for (int j = 0; j < kKept; ++j) {
+        const int t = first + j;
+        cnt[j] = (j < per && t < n_tiles) ? rows_of(t) : 0u;
+        local += cnt[j];
+    }
+    for (int t = first + kKept; t < first + per && t < n_tiles; ++t) local += rows_of(t);
+    // exclusive scan over the 1024 threads (64-bit sums through s_h)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long inc = local;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const unsigned long long t = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += t;
+    }
+    unsigned long long* s_tot = (unsigned long long*)s_h;
+    __syncthreads();
+    if (lane == 63) s_tot[wave] = inc;
+    __syncthreads();
+    unsigned long long base = 0, total = 0;
+    for (int w = 0; w < kSideThreads / 64; ++w) {
+        const unsigned long long x = s_tot[w];
+        if (w < wave) base += x;
+        total += x;
+    }
+    long long run = (long long)(base + inc - local);
+#pragma unroll
+    for (int j = 0; j < kKept; ++j) {
+        const int t = first + j;
+        if (j < per && t < n_tiles) tile_base[t] = run;
+        run += cnt[j];
+    }
+    for (int t = first + kKept; t < first + per && t < n_tiles; ++t) {
+        tile_base[t] = run;
+        run += rows_of(t);
+    }
+    if (threadIdx.x == 0) ctr->n_rows = (long long)total;
 }
 
 // The whole selection of a column in one workgroup, for columns that fit its registers (grids of at most 32768
@@ -429,8 +805,8 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     };
     histogram([](unsigned, unsigned) { return true; }, [](unsigned x, unsigned) { return x >> 21; });
     ColState st;
-    st.prefix = 0; st.tau = 0; st.k_rem = k; st.n_eq = 0; st.q = 0; st.n_nz = s_total; st.done = 1; st.cut = 0xffffffffu;
-    st.side_off = 0; st.side_fill = 0; st.pad = 0;
+    st.tau = 0; st.cut = 0xffffffffu; st.n_eq = 0; st.q = 0; st.tau_lo = 0; st.tau_hi = 0; st.n_nz = s_total;
+    st.n_above = 0; st.done = 1; st.side_off = 0;
     if (k <= 0) st.tau = 0xffffffffu;  // no key is stronger: nothing survives
     if (k <= 0 || (long long)st.n_nz <= k) {  // or fewer entries than k: all survive (tau = 0)
         if (threadIdx.x == 0) cols[col] = st;
@@ -465,9 +841,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
         cut = (phi << 4) | (unsigned)bin;
     }
     if (threadIdx.x == 0) {
-        st.prefix = prefix2 >> 11;
         st.tau = tau;
-        st.k_rem = k_rem;
         st.n_eq = n_eq;
         st.q = q;
         st.cut = cut;
@@ -475,22 +849,62 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     }
 }
 
-hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, const int* tile_start,
-                       const float* resp, ColState* cols, unsigned* hist, uint2* side, unsigned long long side_cap,
-                       Counters* ctr, hipStream_t s) {
+bool topk_small_columns(const Geom& g) {
+    return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kSmallColumn;
+}
+
+// row_keep[w] = the channels' marks for word w (two words per tile) taken together.  A wave takes 64 consecutive
+// words; its loads of a plane are one 512-byte piece, eight planes in flight at a time.
+__global__ __launch_bounds__(64) void k_combine_marks(int planes, const unsigned long long* __restrict__ row_plane,
+                                                      long long plane_words, const Counters* __restrict__ ctr,
+                                                      unsigned long long* __restrict__ row_keep) {
+    const long long words = 2 * ctr->n_tiles;
+    for (long long w = (long long)blockIdx.x * 64 + threadIdx.x; w < words; w += (long long)gridDim.x * 64) {
+        unsigned long long m = 0;
+        int p = 0;
+        for (; p + 8 <= planes; p += 8) {
+            unsigned long long x[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[j] = row_plane[(size_t)(p + j) * plane_words + w];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) m |= x[j];
+        }
+        for (; p < planes; ++p) m |= row_plane[(size_t)p * plane_words + w];
+        row_keep[w] = m;
+    }
+}
+
+hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int relu, const int* tile_start,
+                       const float* resp, ColState* cols, uint2* side, uint4* part, unsigned long long* row_keep,
+                       unsigned long long* row_plane, long long* tile_base, long long tiles_cap, Counters* ctr,
+                       hipStream_t s) {
     const int ncols = g.batch * channels;
-    if (ncols > 0 && (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kSmallColumn) {
+    if (ncols <= 0) return hipSuccess;
+    if (topk_small_columns(g)) {
         hipLaunchKernelGGL(k_select_small, dim3(ncols), dim3(kSmallThreads), 0, s, mode, channels, tile_start, resp, k,
                            cols);
         return hipGetLastError();
     }
-    int slices = 4096 / (ncols > 0 ? ncols : 1);  // (cfg 4, 256 columns: 16 slices; 8 or 32 were 6 % slower)
+    const int groups = g.batch * ((channels + kClassifyWaves - 1) / kClassifyWaves);
+    int slices = 2048 / groups;
     if (slices < 1) slices = 1;
-    if (slices > 64) slices = 64;
-    hipLaunchKernelGGL(k_hist0, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, hist, k, cols,
-                       ctr, side_cap);
-    hipLaunchKernelGGL(k_collect, dim3(ncols, slices), dim3(256), 0, s, mode, channels, tile_start, resp, cols, side);
-    hipLaunchKernelGGL(k_side_select, dim3(ncols), dim3(kSideThreads), 0, s, cols, side);
+    if (slices > kClassifySlicesMax) slices = kClassifySlicesMax;
+    const bool marks = row_keep && row_plane && tile_base && k > 0;
+    hipLaunchKernelGGL(k_bracket, dim3(ncols), dim3(kBracketThreads), 0, s, mode, channels, tile_start, resp, k, cols);
+    if (mode == SCNN_TOPK_ABS)
+        hipLaunchKernelGGL(k_classify<SCNN_TOPK_ABS>, dim3(groups, slices), dim3(kClassifyWaves * 64), 0, s, relu,
+                           channels, tile_start, resp, cols, side, part, marks ? row_plane : nullptr, 2 * tiles_cap);
+    else
+        hipLaunchKernelGGL(k_classify<SCNN_TOPK_SIGNED>, dim3(groups, slices), dim3(kClassifyWaves * 64), 0, s, relu,
+                           channels, tile_start, resp, cols, side, part, marks ? row_plane : nullptr, 2 * tiles_cap);
+    if (marks) {
+        long long cb = (2 * tiles_cap + 63) / 64;
+        cb = cb < 1 ? 1 : (cb > 2048 ? 2048 : cb);
+        hipLaunchKernelGGL(k_combine_marks, dim3((unsigned)cb), dim3(64), 0, s, channels, row_plane, 2 * tiles_cap, ctr,
+                           row_keep);
+    }
+    hipLaunchKernelGGL(k_settle, dim3(ncols), dim3(kSideThreads), 0, s, mode, relu, channels, k, tile_start, resp, cols,
+                       side, part, slices, marks ? row_keep : nullptr, marks ? tile_base : nullptr, ctr);
     return hipGetLastError();
 }
 
@@ -593,7 +1007,7 @@ __device__ inline void finish_if_last(Counters* ctr, long long* nnz_out, long lo
     nnz_out[0] = rows;
     nnz_out[1] = aux_is_cand ? ctr->n_cand : aux_imm;
     nnz_out[2] = (long long)flags;
-    nnz_out[3] = 0;
+    nnz_out[3] = (long long)__hip_atomic_load(&ctr->bracket_failed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int mode, int relu,
@@ -728,6 +1142,11 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
 // look-back rarely finds a predecessor unpublished, and the reads of one tile overlap the writes of another.
 // The rows of a tile that keep an entry are two 64-bit masks (rows 0..63, 64..127) in one of three rotating slots;
 // a row's rank is a popcount.  Three barriers per step.
+// STREAM: the output row at which every tile starts is known (tile_base, from the rows marked during the
+// selection): tiles are dealt out by workgroup index, nothing is published or looked back at, and no tile waits for
+// another.  The selection can find, late, that its marks are not to be relied on (ctr->bracket_failed); the stream
+// kernel then leaves at once and the look-back kernel, launched behind it, does the work; otherwise that one leaves.
+template <bool STREAM>
 __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels, int mode, int relu,
                                                         const int* __restrict__ cand_start,
                                                         const int* __restrict__ tile_start,
@@ -738,7 +1157,8 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
                                                         int32_t* __restrict__ out_coords,
                                                         float* __restrict__ out_feats, long long out_capacity,
                                                         long long* __restrict__ nnz_out, long long aux_imm,
-                                                        int aux_is_cand) {
+                                                        int aux_is_cand, const long long* __restrict__ tile_base) {
+    if (STREAM ? ctr->bracket_failed != 0u : (tile_base != nullptr && ctr->bracket_failed == 0u)) return;
     __shared__ uint4 s_thr[64];  // per channel: {threshold if the position passes the cut, threshold if not, cut, -}
     __shared__ unsigned long long s_mask[3][2];
     __shared__ int s_rank[kTileRows];  // output row of a kept row of the tile being written, relative; -1 = dropped
@@ -865,7 +1285,13 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     // (thread 0) the next tile of this workgroup; a launch with a workgroup per tile asks once
     const bool once = (long long)gridDim.x >= n_tiles;
     bool asked = false;
+    int dealt = (int)blockIdx.x;  // (STREAM) the next tile of this workgroup
     auto next_tile = [&]() -> int {
+        if (STREAM) {
+            const int t = dealt < n_tiles ? dealt : n_tiles;
+            dealt = t + (int)gridDim.x;
+            return t;
+        }
         const int t = (once && asked) ? n_tiles : (int)take_ticket(ctr, 1u);
         asked = true;
         return t;  // (at or past n_tiles: no tile)
@@ -887,7 +1313,8 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
     __syncthreads();
     int tile_y = s_ticket;
     if (tile_y < n_tiles) load_tile(tile_y, vb);
-    if (threadIdx.x == 0) publish_count(tile_state, tile_x, __popcll(s_mask[0][0]) + __popcll(s_mask[0][1]));
+    if (!STREAM && threadIdx.x == 0)
+        publish_count(tile_state, tile_x, __popcll(s_mask[0][0]) + __popcll(s_mask[0][1]));
     int slot_x = 0, slot_y = 1, slot_z = 2;
     // One step: (P, Q) hold (X, Y).  Decide Y, move X to LDS, fetch Z into P's registers, write X.
     auto step = [&](float (&P)[16][2], float (&Q)[16][2]) {
@@ -903,15 +1330,19 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
             if (lane == 0) {
                 s_mask[slot_z][0] = 0ull;  // (last read before this step's first barrier, next used after its last)
                 s_mask[slot_z][1] = 0ull;
-                if (tile_y < n_tiles)
+                if (!STREAM && tile_y < n_tiles)
                     publish_count(tile_state, tile_y, __popcll(s_mask[slot_y][0]) + __popcll(s_mask[slot_y][1]));
             }
-            const int count = __popcll(s_mask[slot_x][0]) + __popcll(s_mask[slot_x][1]);
-            const long long base = lookback_published(tile_state, tile_x, count, ctr);
-            if (lane == 0) {
-                if (tile_x == n_tiles - 1)
-                    __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                s_base = base;
+            if (STREAM) {
+                if (lane == 0) s_base = tile_base[tile_x];
+            } else {
+                const int count = __popcll(s_mask[slot_x][0]) + __popcll(s_mask[slot_x][1]);
+                const long long base = lookback_published(tile_state, tile_x, count, ctr);
+                if (lane == 0) {
+                    if (tile_x == n_tiles - 1)
+                        __hip_atomic_store(&ctr->n_rows, base + count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    s_base = base;
+                }
             }
         }
         __syncthreads();  // s_base, s_rank
@@ -941,7 +1372,7 @@ __global__ void k_finish(const Counters* __restrict__ ctr, int which_rows, long 
         nnz_out[0] = rows;
         nnz_out[1] = aux_is_cand ? ctr->n_cand : aux_imm;
         nnz_out[2] = (long long)flags;
-        nnz_out[3] = 0;
+        nnz_out[3] = (long long)ctr->bracket_failed;
     }
 }
 
@@ -1077,7 +1508,8 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                const int* tile_start, const unsigned* cand_lin, const float* resp,
                                const ColState* cols, unsigned long long* tile_state, long long tiles_cap,
                                Counters* ctr, int32_t* out_coords, float* out_feats, long long out_capacity,
-                               long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
+                               long long* nnz_out, long long aux_imm, int aux_is_cand, const long long* tile_base,
+                               hipStream_t s) {
     // no more workgroups than can be resident at once (4 per CU by LDS), so that every ticket holder runs; three per
     // CU measured best for the wide kernels (cfg 4: 103 us against 107 with four and 110 with two)
     long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
@@ -1098,10 +1530,17 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
     else if (channels <= 8) SCNN_NARROW_CASE(8, 8);
     else if (channels <= 16) SCNN_NARROW_CASE(16, 8);
     else if (channels <= 32) SCNN_NARROW_CASE(32, 4);
-    else if (channels <= 64)
-        hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
+    else if (channels <= 64) {
+        if (tile_base) {
+            const long long sb = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
+            hipLaunchKernelGGL(k_select_write64<true>, dim3((unsigned)sb), dim3(256), 0, s, g, channels, mode, relu,
+                               cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
+                               out_capacity, nnz_out, aux_imm, aux_is_cand, tile_base);
+        }
+        hipLaunchKernelGGL(k_select_write64<false>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
-                           out_capacity, nnz_out, aux_imm, aux_is_cand);
+                           out_capacity, nnz_out, aux_imm, aux_is_cand, tile_base);
+    }
     else
         hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,

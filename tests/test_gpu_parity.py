@@ -139,7 +139,7 @@ def _random_rows(rng, extent, batch, density, channels, levels=None, fill=0.7):
 
 @pytest.mark.parametrize("extent,batch,channels,density", [
     ((9, 11), 1, 1, 0.5), ((16, 16), 3, 5, 0.4), ((12, 10, 9), 2, 64, 0.3), ((20, 20, 20), 4, 70, 0.12),
-    ((33, 17, 5), 2, 130, 0.2), ((40, 40, 40), 2, 16, 0.1)])
+    ((33, 17, 5), 2, 130, 0.2), ((40, 40, 40), 2, 16, 0.1), ((48, 48, 32), 2, 40, 0.3), ((64, 64, 12), 1, 64, 0.9)])
 @pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
 def test_attention_topk_bit_exact_with_heavy_ties(extent, batch, channels, density, mode):
     rng = np.random.default_rng(abs(hash((extent, batch, channels, mode))) % 2 ** 32)
@@ -153,6 +153,38 @@ def test_attention_topk_bit_exact_with_heavy_ties(extent, batch, channels, densi
             assert int(n[2]) == 0
             assert np.array_equal(host(gc), oc_), (k, levels)
             assert np.array_equal(host(gf), of_), (k, levels)
+
+
+@pytest.mark.parametrize("channels", [16, 40])
+@pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
+def test_attention_topk_is_exact_when_the_sampled_bracket_misses(channels, mode):
+    """Long columns are settled from a bracket estimated on every S-th tile of 128 rows (S = ceil(tiles / 128)).
+    Here exactly those tiles hold the strong responses, so the estimate is far off in every column: the selection must
+    notice (result counter 3) and still return the oracle's rows bit for bit."""
+    extent, batch = (64, 64, 16), 2
+    rng = np.random.default_rng(77 + channels + mode)
+    coords = random_sparse_sites(rng, extent, batch, 0.6)
+    resp = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    for b in range(batch):
+        rows = np.nonzero(coords[:, 0] == b)[0]
+        tiles = -(-len(rows) // 128)
+        assert tiles > 2 * 128  # S = 3
+        S = -(-tiles // 128)
+        strong = (np.arange(len(rows)) // 128) % S == 0
+        resp[rows[strong]] += np.float32(100.0)
+    for k in (len(coords) // batch // 10, len(coords) // batch // 2):
+        say(f"attention_topk bracket miss C={channels} mode={mode} k={k}")
+        gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+        oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+        assert int(n[2]) == 0 and int(n[3]) == 1
+        assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+    # and the usual case: the estimate holds
+    resp = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    k = len(coords) // batch // 3
+    gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+    oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+    assert int(n[2]) == 0 and int(n[3]) == 0
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
 
 
 def test_attention_topk_empty_and_single_sample_cases():
