@@ -215,7 +215,7 @@ struct ConvWs {
     unsigned long long* tile_state;
     size_t zero_bytes;
     // not zeroed
-    uint4* part;
+    uint2* part;
     unsigned long long* row_keep;
     unsigned long long* row_plane;
     long long* tile_base;
@@ -270,7 +270,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
-    w->part = c.take<uint4>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
+    w->part = c.take<uint2>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
     w->row_keep = c.take<unsigned long long>(marks ? 2 * w->tiles_cap : 0);
     w->row_plane = c.take<unsigned long long>(marks ? 2 * w->tiles_cap * kMarkPlanes : 0);
     w->tile_base = c.take<long long>(marks ? w->tiles_cap : 0);
@@ -678,7 +678,7 @@ struct TopkWs {
     ColState* cols;
     unsigned long long* tile_state;
     size_t zero_bytes;
-    uint4* part;
+    uint2* part;
     unsigned long long* row_keep;
     unsigned long long* row_plane;
     long long* tile_base;
@@ -702,7 +702,7 @@ void carve_topk(void* base, const Geom& g, long long rows, int channels, TopkWs*
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
-    w->part = c.take<uint4>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
+    w->part = c.take<uint2>(topk_small_columns(g) ? 0 : ncols * kTopkPartWords);
     w->row_keep = c.take<unsigned long long>(w->marks ? 2 * w->tiles_cap : 0);
     w->row_plane = c.take<unsigned long long>(w->marks ? 2 * w->tiles_cap * kMarkPlanes : 0);
     w->tile_base = c.take<long long>(w->marks ? w->tiles_cap : 0);

@@ -38,6 +38,7 @@ struct ColState {
     unsigned tau_hi;    //   side buffer, keys above tau_hi are only counted
     unsigned n_nz;      // non-zero entries in the column
     unsigned n_above;   // entries above the bracket
+    unsigned side_fill; // side-buffer entries written so far
     int done;           // 1 = tau and cut are final
     unsigned long long side_off;  // first side-buffer entry of the column
 };
@@ -327,7 +328,7 @@ constexpr int kTopkPartWords = 256;  // slices of a column at most
 constexpr int kMarkPlanes = 64;  // one per channel where marks are used (up to 64 channels)
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int relu, const int* tile_start,
                        const float* resp, ColState* cols, uint2* side,
-                       uint4* part /* kTopkPartWords entries per column */, unsigned long long* row_keep,
+                       uint2* part /* kTopkPartWords entries per column */, unsigned long long* row_keep,
                        unsigned long long* row_plane, long long* tile_base, long long tiles_cap, Counters* ctr,
                        hipStream_t s);
 hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, const int* cand_start,

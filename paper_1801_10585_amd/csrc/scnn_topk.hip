@@ -163,9 +163,10 @@ __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descen
 // sample's keys at the ranks  r -+ delta,  r = k * (sample slots / column slots)  being where the k-th strongest
 // entry of the column is expected in the sample (empty slots rank last, as key 0).  delta = 8 standard deviations
 // of a uniformly drawn sample's rank plus half a percent of the sample: tiles are pieces of space, not independent
-// draws, hence the margin.  Nothing depends on the bracket being right: the second launch counts what lies above it
-// and the third one checks that the k-th entry fell inside, and settles the column from the response matrix itself
-// when it did not.
+// draws, hence the margin (6 deviations plus a quarter percent missed on three layers of the 128^3 network and on
+// the r = 128 layer).  Nothing depends on the bracket being right: the second launch counts what lies above it and
+// the third one checks that the k-th entry fell inside, and settles the column from the response matrix itself when
+// it did not.
 constexpr int kBracketThreads = 1024;
 constexpr int kBracketPerThread = 16;
 constexpr int kBracketTiles = kBracketThreads * kBracketPerThread / kTileRows;  // 128
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int chann
     const int T = t1 - t0;
     ColState st;
     st.tau = 0; st.cut = 0xffffffffu; st.n_eq = 0; st.q = 0; st.tau_lo = 1u; st.tau_hi = 0u; st.n_nz = 0; st.n_above = 0;
-    st.done = 0;
+    st.side_fill = 0; st.done = 0;
     st.side_off = ((unsigned long long)t0 * channels + (unsigned long long)oc * T) * kTileRows;
     if (k <= 0 || T == 0) {
         st.done = 1;
@@ -305,10 +306,9 @@ __global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int chann
 // those above the bracket, copies the entries inside it (value and position in the column) to the side buffer, and,
 // when row_plane is given, records which rows hold an entry above the bracket -- those survive whatever the exact
 // threshold turns out to be -- in the channel's own plane of row marks, two 64-bit words per tile, which
-// k_combine_marks merges.  Nothing here is shared between waves: a slice of a column is a run of consecutive tiles
-// and owns a run of the column's side-buffer entries long enough for all of them, so there is no counter to
-// reserve from and no barrier.  (Marks kept in one shared plane cost 40 us of device-scope atomics on the r = 128
-// layer, and reserving side-buffer space from a counter per column about as much again.)  The loop is bound by
+// k_combine_marks merges.  Waves share nothing but the cursor of their column's side-buffer entries and never wait
+// for one another.  (Marks kept in one shared plane cost 40 us of device-scope atomics on the r = 128 layer, whose
+// every tile half would be updated by every channel.)  The loop is bound by
 // instruction issue, hence the float compares on ballots, the counts in scalar registers and the marks gathered
 // with v_writelane.
 // With the score s(x) = |x| or x: the value t such that, for an entry x (non-zero, not a NaN),
@@ -341,8 +341,8 @@ template <int MODE>
 __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int channels,
                                                                   const int* __restrict__ tile_start,
                                                                   const float* __restrict__ resp,
-                                                                  const ColState* __restrict__ cols,
-                                                                  uint2* __restrict__ side, uint4* __restrict__ part,
+                                                                  ColState* __restrict__ cols,
+                                                                  uint2* __restrict__ side, uint2* __restrict__ part,
                                                                   unsigned long long* __restrict__ row_plane,
                                                                   long long plane_words) {
     constexpr int U = kClassifyTiles;  // tiles per iteration
@@ -363,16 +363,18 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
     uint2* wbuf = s_buf + wave * WCAP;
     int fill = 0;                    // wave-uniform
     unsigned n_nz = 0, n_above = 0;  // wave-uniform
-    // slice y of the column: tiles [first, last), and a run of the column's side-buffer entries that could hold every
-    // one of their entries
+    // slice y of the column: tiles [first, last)
     const int L = classify_slice_tiles(t1 - t0, (int)gridDim.y);
     const int first = t0 + (int)blockIdx.y * L;
     const int last = first + L < t1 ? first + L : t1;
-    uint2* run = side + st.side_off + (unsigned long long)blockIdx.y * L * kTileRows;
-    unsigned written = 0;  // wave-uniform
+    // a flush reserves its piece of the column's side-buffer entries from the column's cursor: one returning atomic
+    // per wave and flush, a few thousand a layer, which is what keeps the column's entries in one run
+    uint2* run = side + st.side_off;
     auto flush = [&]() {
-        for (int i = lane; i < fill; i += 64) run[written + i] = wbuf[i];
-        written += (unsigned)fill;
+        unsigned base = 0;
+        if (lane == 0) base = atomicAdd(&cols[col].side_fill, (unsigned)fill);
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (int i = lane; i < fill; i += 64) run[base + i] = wbuf[i];
         fill = 0;
     };
     unsigned long long* plane = row_plane ? row_plane + (size_t)oc * plane_words : nullptr;
@@ -444,7 +446,7 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
         process_any(tile0 + U, vb);
     }
     if (fill > 0) flush();
-    if (lane == 0) part[(size_t)col * gridDim.y + blockIdx.y] = make_uint4(n_nz, n_above, written, 0u);
+    if (lane == 0) part[(size_t)col * gridDim.y + blockIdx.y] = make_uint2(n_nz, n_above);
 }
 
 // Third launch, one workgroup per column: the exact k-th strongest key tau, the number of entries equal to it and,
@@ -452,20 +454,11 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
 // entries when the bracket held the k-th entry (the rule), over the column itself when it did not.
 constexpr int kSideThreads = 1024;
 
-struct SideEntries {  // entry i of a column's side-buffer entries, which lie in one run per slice
-    const uint2* e;         // the column's first run
-    const unsigned* start;  // (LDS) start[s] = entries in the runs before run s; start[slices] = all of them
-    int slices;
-    unsigned run_pitch;     // entries from one run to the next
+struct SideEntries {  // entry i of a column's side-buffer entries: {key, position}; the buffer holds the value's bits
+    const uint2* e;
     int mode;
-    // {key, position}; the buffer holds the value's bits
     __device__ uint2 operator()(unsigned i) const {
-        int lo = 0, hi = slices - 1;  // last run that starts at or before i
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (start[mid] <= i) lo = mid; else hi = mid - 1;
-        }
-        const uint2 x = e[(size_t)lo * run_pitch + (i - start[lo])];
+        const uint2 x = e[i];
         return make_uint2(score_key(__uint_as_float(x.x), mode), x.y);
     }
 };
@@ -483,7 +476,7 @@ struct ColumnEntries {  // slot i of a column of the response matrix (key 0: not
 // entries.  The digits of the radix select, 11 bits at most, are taken from key - key_lo, most significant first, so
 // that a narrow bracket is settled in two passes.  Up to kSettleCached entries per thread are held in registers
 // between the passes.  (whole workgroup)
-constexpr int kSettleCached = 16;
+constexpr int kSettleCached = 20;
 
 // held: the entries threadIdx.x + 1024 * u of the column, if cached (m <= kSettleCached * 1024), loaded by the caller.
 template <class Entries>
@@ -573,58 +566,36 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                                                          const int* __restrict__ tile_start,
                                                          const float* __restrict__ resp, ColState* __restrict__ cols,
                                                          const uint2* __restrict__ side,
-                                                         const uint4* __restrict__ part, int slices,
+                                                         const uint2* __restrict__ part, int slices,
                                                          unsigned long long* row_keep,
                                                          long long* __restrict__ tile_base, Counters* ctr) {
     __shared__ unsigned s_h[kHistBins];
     __shared__ unsigned s_wave[4];
     __shared__ int s_res[2];
-    __shared__ uint4 s_part[4];
-    __shared__ unsigned s_start[kClassifySlicesMax + 1];
+    __shared__ uint2 s_part[4];
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
     ColState st = cols[col];
-    // the slices' counts: entries, entries above the bracket, entries in the side buffer's runs (read along with the
-    // column's state; unused, and possibly stale, where the column is settled already)
-    uint4 my_part = make_uint4(0u, 0u, 0u, 0u);
+    // the slices' counts of entries and of entries above the bracket (read along with the column's state; unused, and
+    // possibly stale, where the column is settled already)
+    uint2 my_part = make_uint2(0u, 0u);
     if ((int)threadIdx.x < slices) my_part = part[(size_t)col * slices + threadIdx.x];
     if (!st.done) {
-        unsigned mine = my_part.z, sum_nz = my_part.x, sum_above = my_part.y;
-        unsigned inc = mine;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned t = __shfl_up(inc, d, 64);
-            if ((int)(threadIdx.x & 63) >= d) inc += t;
-        }
+        unsigned sum_nz = my_part.x, sum_above = my_part.y;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) {
             sum_nz += __shfl_xor(sum_nz, d, 64);
             sum_above += __shfl_xor(sum_above, d, 64);
         }
-        if (threadIdx.x < 256 && (threadIdx.x & 63) == 63) {
-            s_part[threadIdx.x >> 6] = make_uint4(sum_nz, sum_above, inc, 0u);
-        }
+        if (threadIdx.x < 256 && (threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = make_uint2(sum_nz, sum_above);
         __syncthreads();
-        unsigned before = 0;
-        st.n_nz = 0;
-        st.n_above = 0;
-        unsigned m = 0;
-        for (int w = 0; w < 4; ++w) {
-            const uint4 p = s_part[w];
-            if (w < (int)(threadIdx.x >> 6)) before += p.z;
-            st.n_nz += p.x;
-            st.n_above += p.y;
-            m += p.z;
-        }
-        if ((int)threadIdx.x < slices) s_start[threadIdx.x] = before + inc - mine;
-        if (threadIdx.x == 0) s_start[slices] = m;
-        __syncthreads();
-        const int T = t1 - t0;
+        st.n_nz = s_part[0].x + s_part[1].x + s_part[2].x + s_part[3].x;
+        st.n_above = s_part[0].y + s_part[1].y + s_part[2].y + s_part[3].y;
+        const unsigned m = st.side_fill;
         const float* col0 = resp + ((size_t)t0 * channels + oc) * kTileRows;
         const size_t pitch = (size_t)channels * kTileRows;
-        const SideEntries e{side + st.side_off, s_start, slices, (unsigned)classify_slice_tiles(T, slices) * kTileRows,
-                            mode};
+        const SideEntries e{side + st.side_off, mode};
         // the side buffer's entries of the column, in registers if they are few enough (the rule)
         const bool cached = m <= (unsigned)kSettleCached * kSideThreads;  // (uniform)
         uint2 kept[kSettleCached];
@@ -667,15 +638,19 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                 atomicOr(word_of(x), bit);
             };
             if (cached) {
-                unsigned long long have[kSettleCached];
 #pragma unroll
-                for (int u = 0; u < kSettleCached; ++u) {
-                    have[u] = ~0ull;
-                    if (survives(kept[u]))
-                        have[u] = __hip_atomic_load(word_of(kept[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int u0 = 0; u0 < kSettleCached; u0 += 8) {  // eight words in flight per thread
+                    unsigned long long have[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        have[u] = ~0ull;
+                        if (u0 + u < kSettleCached && survives(kept[u0 + u]))
+                            have[u] = __hip_atomic_load(word_of(kept[u0 + u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (u0 + u < kSettleCached) mark(kept[u0 + u], have[u]);
                 }
-#pragma unroll
-                for (int u = 0; u < kSettleCached; ++u) mark(kept[u], have[u]);
             } else {
                 for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // eight entries in flight per thread
                     uint2 x[8];
@@ -806,7 +781,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     histogram([](unsigned, unsigned) { return true; }, [](unsigned x, unsigned) { return x >> 21; });
     ColState st;
     st.tau = 0; st.cut = 0xffffffffu; st.n_eq = 0; st.q = 0; st.tau_lo = 0; st.tau_hi = 0; st.n_nz = s_total;
-    st.n_above = 0; st.done = 1; st.side_off = 0;
+    st.n_above = 0; st.side_fill = 0; st.done = 1; st.side_off = 0;
     if (k <= 0) st.tau = 0xffffffffu;  // no key is stronger: nothing survives
     if (k <= 0 || (long long)st.n_nz <= k) {  // or fewer entries than k: all survive (tau = 0)
         if (threadIdx.x == 0) cols[col] = st;
@@ -875,7 +850,7 @@ __global__ __launch_bounds__(64) void k_combine_marks(int planes, const unsigned
 }
 
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int relu, const int* tile_start,
-                       const float* resp, ColState* cols, uint2* side, uint4* part, unsigned long long* row_keep,
+                       const float* resp, ColState* cols, uint2* side, uint2* part, unsigned long long* row_keep,
                        unsigned long long* row_plane, long long* tile_base, long long tiles_cap, Counters* ctr,
                        hipStream_t s) {
     const int ncols = g.batch * channels;
