@@ -25,24 +25,49 @@ PEAK_FP64_VECTOR_TFLOPS = 78.6
 
 
 def cpu_baseline(wl, layer, w, mac_total):
-    """The oracle, as it stands, on a bounded sample of the same workload: sample 0, all output channels."""
+    """The oracle, as it stands, on the host cores: the whole batch on all the cores the box gives us, and sample 0
+    on one thread (the whole batch on one thread would take over a minute)."""
     import numpy as np
     import oracle
-    sel = wl.coords[:, 0] == 0
-    coords = wl.coords[sel].copy()
-    feats = wl.feats[sel]
-    n_oc = w.shape[2]
-    ws = np.ascontiguousarray(w[:, :, :n_oc])
-    threads = min(16, os.cpu_count() or 1)
     k = oracle.k_from_rho(layer.rho_up, int(np.prod(wl.extent)))
-    t0 = time.perf_counter()
-    _, _, info = oracle.sparse_conv_fwd(wl.extent, 1, coords, feats, layer.ksize, ws, k=k, relu=layer.relu,
-                                        pool=layer.pool, threads=threads, return_info=True)
-    dt = time.perf_counter() - t0
-    return {"value": info["macs"] / dt / 1e9, "unit": "GMAC/s (non-zero MACs)", "cores": info["threads"],
-            "kind": "oracle", "seconds": dt,
-            "sample": f"sample 0 of {wl.batch}, output channels 0..{n_oc - 1} of {w.shape[2]} "
-                      f"({info['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
+    ws = np.ascontiguousarray(w)
+
+    def run(batch, coords, feats, threads):
+        t0 = time.perf_counter()
+        _, _, info = oracle.sparse_conv_fwd(wl.extent, batch, coords, feats, layer.ksize, ws, k=k, relu=layer.relu,
+                                            pool=layer.pool, threads=threads, return_info=True)
+        return time.perf_counter() - t0, info
+
+    threads = min(16, os.cpu_count() or 1)
+    dt, info = run(wl.batch, wl.coords, wl.feats, threads)
+    multi = {"value": info["macs"] / dt / 1e9, "unit": "GMAC/s (non-zero MACs)", "cores": info["threads"],
+             "kind": "oracle", "seconds": dt,
+             "sample": f"the whole batch of {wl.batch} samples, all {w.shape[2]} output channels "
+                       f"({info['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
+    sel = wl.coords[:, 0] == 0
+    dt1, info1 = run(1, wl.coords[sel].copy(), wl.feats[sel], 1)
+    single = {"value": info1["macs"] / dt1 / 1e9, "unit": "GMAC/s (non-zero MACs)", "cores": info1["threads"],
+              "kind": "oracle", "seconds": dt1,
+              "sample": f"sample 0 of {wl.batch}, all {w.shape[2]} output channels "
+                        f"({info1['macs'] / 1e9:.3f} of {mac_total / 1e9:.3f} GMAC), full layer incl. selection + ReLU"}
+    return multi, single
+
+
+def copy_ceiling(scnn, torch, dev):
+    """GB/s (read + write) of a plain 1 GiB device-to-device copy kernel: what streaming reaches on this machine."""
+    src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    scnn.calibration_copy(dst, src)
+    best = 0.0
+    for _ in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        scnn.calibration_copy(dst, src)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
 
 
 def bench_stack(args):
@@ -171,6 +196,17 @@ def bench_backward(args, wl, layer, w, coords, feats, wd):
     # the two contractions (bp_data and bp_filter) do one multiply-add per visit each
     dominant = "bwd_filter" if stage["bwd_filter"] >= stage["bwd_data_conv"] else "bwd_data_conv"
     tflops = 2.0 * visits / (stage[dominant] * 1e-3) / 1e12
+    # HBM bytes of the dominant kernel per launch, from the committed counter runs of this command (see main())
+    traffic, traffic_source = None, None
+    tpath = os.path.join(ROOT, "profiles", f"bwd_cfg{args.config}_traffic.json")
+    if not args.paper_runtime and os.path.exists(tpath):
+        try:
+            rec = json.load(open(tpath)).get(dominant)
+            if rec:
+                traffic = rec.get("hbm_bytes_per_launch")
+                traffic_source = "profiles/" + os.path.basename(tpath) + ": " + rec.get("source", "")
+        except Exception:
+            traffic = None
     line = {
         "metric": "effective non-zero GMAC/s of the sparse conv backward pass (two multiply-adds per visit)",
         "value": 2.0 * visits * args.steps / dt / 1e9, "unit": "GMAC/s", "n_gpus": 1, "steps": args.steps,
@@ -181,7 +217,8 @@ def bench_backward(args, wl, layer, w, coords, feats, wd):
                    "rho_up": layer.rho_up, "rows_in": int(nnz_in), "gradient_rows": g_rows, "visits": int(visits),
                    "seed": wl.seed},
         "roofline": {"bound": "mfma" if mfma else "alu", "kernel": dominant, "achieved": tflops, "peak": peak,
-                     "unit": "TFLOP/s", "frac": tflops / peak, "traffic": None, "kernel_ms": stage[dominant],
+                     "unit": "TFLOP/s", "frac": tflops / peak, "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel_ms": stage[dominant],
                      "flops_per_launch": 2 * int(visits)},
         "stage_ms": stage,
     }
@@ -204,11 +241,13 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="time the backward pass (Algorithm 2) of the same layer instead; not the headline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rho-up", type=float, default=None, help="override the configuration's rho_up (not the headline)")
+    ap.add_argument("--layer", type=int, default=1,
+                    help="which layer of a multi-layer configuration to time (1-based; its input is produced by the "
+                         "library from the layers before it, untimed); not the headline")
     ap.add_argument("--conv-path", type=int, default=0, choices=[0, 1, 2, 3],
                     help="convolution kernel family (scnn_set_conv_path): 0 the library's choice (the headline), "
                          "1 vector kernels, 2 matrix cores wherever possible, 3 the pair-list matrix-core kernel")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run one 1 GiB streaming copy (for scaling rocprofv3 memory counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the layer shards by sample with no exchange; "
@@ -228,7 +267,25 @@ def main():
     if args.stack:
         return bench_stack(args)
     wl = make_paper_runtime(args.paper_runtime, args.rho_f) if args.paper_runtime else make_config(args.config)
+    if not 1 <= args.layer <= len(wl.layers):
+        print(f"bench.py: configuration {args.config} has {len(wl.layers)} layer(s)", file=sys.stderr)
+        sys.exit(2)
+    if args.layer > 1:
+        # the timed layer's input: the output of the layers before it (and their pooling), computed here, untimed
+        import dataclasses
+        cc, ff, ext = torch.from_numpy(wl.coords).to(dev), torch.from_numpy(wl.feats).to(dev), wl.extent
+        for L, wprev in zip(wl.layers[:args.layer - 1], wl.filters):
+            cc, ff, _ = scnn.sparse_conv_fwd(ext, wl.batch, cc, ff, L.ksize, torch.from_numpy(wprev).to(dev),
+                                             rho_up=L.rho_up, relu=L.relu, pool=L.pool)
+            if L.pool:
+                ext = tuple((e + 1) // 2 for e in ext)
+        wl = dataclasses.replace(wl, name=f"{wl.name}_layer{args.layer}", extent=ext, coords=cc.cpu().numpy(),
+                                 feats=ff.cpu().numpy(), layers=wl.layers[args.layer - 1:],
+                                 filters=wl.filters[args.layer - 1:])
     layer = wl.layers[0]
+    if args.rho_up is not None:
+        import dataclasses
+        layer = dataclasses.replace(layer, rho_up=args.rho_up)
     w = wl.filters[0]
     ndim = wl.ndim
     mac_nz = scnn.count_mac_nz(wl.extent, wl.coords, wl.feats, layer.ksize, w)
@@ -238,6 +295,7 @@ def main():
     wd = torch.from_numpy(w).to(dev)
     nnz_in, c_in = wl.feats.shape
     c_out = w.shape[2]
+    copy_gbs = copy_ceiling(scnn, torch, dev)  # (also the known-size copy that scales the profiler's byte counters)
     if args.backward:
         return bench_backward(args, wl, layer, w, coords, feats, wd)
     # size the buffers from a first (untimed) run: candidate count is data dependent
@@ -258,18 +316,19 @@ def main():
                              relu=layer.relu, pool=layer.pool, out_capacity=cand_cap, cand_capacity=cand_cap,
                              workspace=workspace, out=out, sync=False)
 
-    if args.calibrate_copy:
-        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        scnn.calibration_copy(dst, src)
-        torch.cuda.synchronize()
-        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # timed region: the library records two HIP events per call on the launch stream, around the convolution
-    # kernel (the dominant one, whose duration the roofline object needs from this very region)
-    scnn.profile_enable(2)
+    # untimed: the same number of calls with the timed region's event mode, so that the library's events exist before
+    # the clock starts (creating them costs about 10 us each)
+    scnn.profile_enable(3)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    scnn.profile_collect()
+    # timed region: on every fourth call the library records two HIP events on the launch stream, around the
+    # convolution kernel (the dominant one, whose duration the roofline object needs from this very region)
+    scnn.profile_enable(3)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -301,14 +360,20 @@ def main():
     conv_ms = conv_only["conv"] / max(conv_calls, 1)
     conv_tflops = 2.0 * mac_nz / (conv_ms * 1e-3) / 1e12
     bytes_alg = scnn.algorithmic_bytes(ndim, nnz_in, c_in, w.shape[0], c_out, n_cand, rows_out)
-    traffic = None
+    conv_kernel = scnn.last_conv_kernel()   # what the library launched, by its own rule
+    # HBM bytes of the dominant kernel per launch: hardware counters cannot be read from inside this process, so the
+    # figure is the one committed from two counter runs of this same command under the profiler (and only used if it
+    # was taken for the kernel that ran here)
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"conv_cfg{args.config}_traffic.json")
-    if not args.paper_runtime and os.path.exists(tpath):
+    if not args.paper_runtime and args.layer == 1 and os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            rec = json.load(open(tpath))
+            if rec.get("kernel", "").startswith(conv_kernel):
+                traffic = rec.get("hbm_bytes_per_launch")
+                traffic_source = "profiles/" + os.path.basename(tpath) + ": " + rec.get("source", "")
         except Exception:
             traffic = None
-    conv_kernel = scnn.last_conv_kernel()   # what the library launched, by its own rule
     on_matrix_cores = conv_kernel in ("k_conv_quad", "k_conv_mfma")
     # the matrix-core kernel is priced against the fp32 MFMA peak, the vector kernel (fp64 FMA) against the fp64
     # vector peak
@@ -324,10 +389,15 @@ def main():
                    "rows_out": rows_out, "mac_nz": int(mac_nz), "input_density": wl.density, "seed": wl.seed},
         "roofline": {"bound": "mfma" if on_matrix_cores else "alu", "kernel": conv_kernel,
                      "achieved": conv_tflops, "peak": conv_peak, "unit": "TFLOP/s", "frac": conv_tflops / conv_peak,
-                     "traffic": traffic,
-                     "kernel_ms": conv_ms, "flops_per_launch": 2 * int(mac_nz)},
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "kernel_ms": conv_ms, "kernel_launches_timed": conv_calls, "flops_per_launch": 2 * int(mac_nz),
+                     # the whole layer against its own bound: max(algorithmic bytes / 8 TB/s, flops / fp32 MFMA peak)
+                     # over the step time
+                     "layer_frac": max(bytes_alg["alg"] / (PEAK_HBM_GBS * 1e9),
+                                       2.0 * mac_nz / (PEAK_MFMA_FP32_TFLOPS * 1e12)) / (ms_per_step * 1e-3)},
         "hbm": {"algorithmic_bytes": bytes_alg["alg"], "achieved_GBs": bytes_alg["alg"] / (ms_per_step * 1e-3) / 1e9,
                 "frac_of_8TBs": bytes_alg["alg"] / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "copy_kernel_GBs": copy_gbs,
                 "whole_layer_roofline_frac": max(bytes_alg["alg"] / (PEAK_HBM_GBS * 1e9),
                                                  2.0 * mac_nz / (PEAK_MFMA_FP32_TFLOPS * 1e12)) / (ms_per_step * 1e-3)},
         "stage_ms": {k: v / max(calls, 1) for k, v in stage_ms.items() if not k.startswith("bwd_")},
@@ -335,7 +405,7 @@ def main():
         "ms_per_step_without_events": dt_plain / args.steps * 1e3,
     }
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl, layer, w, mac_nz)
+        line["cpu_baseline"], line["cpu_baseline_1thread"] = cpu_baseline(wl, layer, w, mac_nz)
     print(json.dumps(line))
 
 

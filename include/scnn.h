@@ -96,15 +96,19 @@ size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int
  *                   w[tap(delta), ic, oc] * in[b, p + delta, ic]
  * (stride 1, zero "same" padding: an input at q updates p = q - delta, updates
  * leaving the grid are dropped -- Alg. 1 steps 5-9).  Inputs, weights and
- * responses are fp32; each response is summed in fp64 (the matrix-core kernels
- * sum the at most 32 products of one tap and 32-channel chunk in fp32 first)
- * and rounded to fp32 once.  The vector kernels and the quad matrix-core kernel
- * add in an order fixed by the data alone and are reproducible bit for bit; the
- * pair-list matrix-core kernel (C_in = 96 or 128 only, unless forced) adds its
- * per-tap partial sums with LDS atomics in no fixed order, so a run can differ
- * from another in the last bits of the fp64 sum, which survives the rounding
- * to fp32 for about one response in 10^8.  Responses that are exactly 0 are
- * not entries (step 13).  bias (nullable, device, [c_out]) is added to the
+ * responses are fp32.  The vector kernels sum each response in fp64 and round
+ * to fp32 once.  The matrix-core kernels first add the at most 32 products of
+ * one tap and 32-channel chunk in fp32; the quad kernel then adds these partial
+ * sums in fp32 where a response has at most 32 of them (filters of up to 32
+ * taps on up to 32 input channels, 16 taps on 64: the r = 128 layer's 27 x 1),
+ * in fp64 otherwise; the pair-list kernel always adds them in fp64.  All stay
+ * within 1e-5 relative + 1e-6 absolute of the exact sum on the workloads this
+ * library is tested on.  The vector kernels and the quad kernel add in an order
+ * fixed by the data alone and are reproducible bit for bit; the pair-list
+ * kernel adds its per-tap partial sums with LDS atomics in no fixed order, so a
+ * run can differ from another in the last bits of the fp64 sum, which survives
+ * the rounding to fp32 for about one response in 10^8.  Responses that are
+ * exactly 0 are not entries (step 13).  bias (nullable, device, [c_out]) is added to the
  * entries (step 14); an entry whose biased value is exactly 0 stops being one.
  * Per (sample b, output channel oc) only the k = scnn_k_from_rho(rho_up, N)
  * entries with the largest score survive (step 15; score = |v| or v by
@@ -262,13 +266,15 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
 
 /* Kernel choice for the convolution step of sparse_conv_fwd (and, for 1, of
  * sparse_conv_bwd), for the calling thread:
- * 0 = by shape and size: the quad matrix-core kernel (C_in in {8, 16, 24, 32,
- *     40, 48, 64}, up to 64 output channels, at most 32 taps, 16-byte aligned
- *     in_feats; with C_in < 32 only on large layers with C_out >= 32), the
- *     pair-list matrix-core kernel for C_in = 96 or 128 (C_out a multiple of 16
- *     up to 64), else the vector kernels;
+ * 0 = by shape and size: the quad matrix-core kernel where C_in is 32, 40, 48
+ *     or 64, C_out at most 64, the filter has at most 32 taps and in_feats is
+ *     16-byte aligned; else the pair-list matrix-core kernel where C_in is a
+ *     multiple of 32 up to 128 (any number of taps), or 16 on large layers
+ *     with C_out >= 32, and C_out a multiple of 16 up to 64; else the vector
+ *     kernels;
  * 1 = always the vector kernels;
- * 2 = a matrix-core kernel whenever one takes the shape, whatever the size;
+ * 2 = a matrix-core kernel whenever one takes the shape, whatever the size:
+ *     the quad kernel also for C_in = 8, 16 and 24;
  * 3 = the pair-list matrix-core kernel where it takes the shape (C_in = 16 or
  *     a multiple of 32 up to 128, C_out a multiple of 16 up to 64).
  * All compute the same sums to the same rounding rule; the switch exists so
@@ -291,8 +297,11 @@ int scnn_set_conv_path(int path);
  * [scnn_profile_stage_count()] and the number of calls into *calls, then
  * forgets them.  on = 1: every boundary; on = 2: only the two events around
  * the convolution stage of sparse_conv_fwd (the other stages read 0), for
- * timing the dominant kernel inside a throughput measurement at the least
- * cost; on = 0: none.  Host pointers. */
+ * timing the dominant kernel inside a throughput measurement at little
+ * cost; on = 3: those two events on every fourth sparse_conv_fwd call after
+ * this one, the first included (the events of a call cost about 0.01 ms of
+ * stream time; *calls then counts the calls that were timed); on = 0: none.
+ * Host pointers. */
 int scnn_profile_enable(int on);
 int scnn_profile_stage_count(void);
 const char* scnn_profile_stage_name(int stage);

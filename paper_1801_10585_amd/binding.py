@@ -465,7 +465,7 @@ def validate_rows(extent, batch, coords, stream=None) -> None:
 
 def profile_enable(on) -> None:
     """Per-stage HIP-event timing of sparse_conv_fwd calls made from this thread: False / 0 = off, True / 1 = every
-    stage, 2 = only the convolution stage (two events per call)."""
+    stage, 2 = only the convolution stage (two events per call), 3 = the same on every fourth call."""
     _check(load_library(), load_library().scnn_profile_enable(int(on)))
 
 

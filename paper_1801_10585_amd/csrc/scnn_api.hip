@@ -55,21 +55,6 @@ static int fail_hip(hipError_t e, const char* what) {
         if (e__ != hipSuccess) return fail_hip(e__, #expr);    \
     } while (0)
 
-// Compute units of the current device, asked once per device.
-static int device_cus(int* cus) {
-    static std::atomic<int> cache[64];
-    int dev = 0;
-    SCNN_TRY(hipGetDevice(&dev));
-    int n = (dev >= 0 && dev < 64) ? cache[dev].load(std::memory_order_relaxed) : 0;
-    if (n <= 0) {
-        SCNN_TRY(hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev));
-        if (n < 1) n = 1;
-        if (dev >= 0 && dev < 64) cache[dev].store(n, std::memory_order_relaxed);
-    }
-    *cus = n;
-    return SCNN_OK;
-}
-
 static constexpr long long kMaxIndex = 0x7fffffffLL;  // rows, candidates and sites use 31-bit indices
 static constexpr int kMaxChannels = 1024;
 
@@ -160,7 +145,9 @@ struct ProfCall {
     unsigned recorded;  // bit i: ev[i] was recorded in this call
 };
 static constexpr int kConvStage = 3;  // "conv": the only stage timed in mode 2
-static thread_local int g_prof_on = 0;  // 0 off, 1 every stage boundary, 2 only the convolution stage's two
+static thread_local int g_prof_on = 0;  // 0 off, 1 every stage boundary, 2 only the convolution stage's two,
+                                        // 3 the same on every fourth forward call
+static thread_local unsigned g_prof_tick = 0;
 static thread_local std::vector<ProfCall>* g_prof_calls = nullptr;   // recorded, not yet collected
 static thread_local std::vector<ProfCall>* g_prof_pool = nullptr;    // idle events for reuse
 
@@ -171,6 +158,7 @@ struct StageTimer {
     hipStream_t s;
     StageTimer(hipStream_t stream, int first_stage, int n_stages) : s(stream) {
         if (!g_prof_on) return;
+        if (g_prof_on == 3 && (first_stage != 0 || (g_prof_tick++ & 3u) != 0)) return;
         if (!g_prof_calls) g_prof_calls = new std::vector<ProfCall>();
         if (!g_prof_pool) g_prof_pool = new std::vector<ProfCall>();
         if (!g_prof_pool->empty()) {
@@ -183,7 +171,7 @@ struct StageTimer {
         call.first_stage = first_stage;
         call.n_stages = n_stages;
         call.recorded = 0;
-        only_conv = g_prof_on == 2 && first_stage == 0;
+        only_conv = g_prof_on >= 2 && first_stage == 0;
         on = true;
     }
     void mark() {  // boundary between stage next-1 and stage next
@@ -410,9 +398,7 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
     }
     timer.mark();
     if (kernel == ConvKernel::kQuad) {
-        int cus = 0;
-        rc = device_cus(&cus);
-        if (rc != SCNN_OK) return rc;
+        const int cus = device_cu_count();
         timer.mark();
         SCNN_TRY(launch_conv_quad(g, ws.occ, ws.occ_prefix, nnz_in, in_feats, c_in, ws.wq, c_out, bias, ws.tap_active,
                                   ws.cand_lin, ws.cand_start, ws.tile_start, ws.ctr, ws.resp, cus, s));
@@ -638,8 +624,9 @@ int scnn_calibration_copy(void* dst, const void* src, size_t bytes, void* hip_st
 }
 
 int scnn_profile_enable(int on) {
-    if (on < 0 || on > 2) return fail(SCNN_EINVAL, "profile mode must be 0, 1 or 2");
+    if (on < 0 || on > 3) return fail(SCNN_EINVAL, "profile mode must be 0, 1, 2 or 3");
     g_prof_on = on;
+    g_prof_tick = 0;
     return SCNN_OK;
 }
 

@@ -1286,17 +1286,15 @@ static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* fe
                                      const unsigned* pairs, const unsigned short* block_tap, const uint2* tile_hdr,
                                      Counters* ctr, float* resp, hipStream_t s) {
     const size_t lds = conv_mfma_lds_bytes(NB * 16);
-    static size_t attr_lds = 0;
-    if (attr_lds < lds) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<KC, NB, HALF>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_lds = lds;
-    }
+    // (set on every launch: the attribute belongs to the current device's copy of the kernel, and a flag remembering
+    // that it was set would have to be kept per device and guarded between threads for the sake of a microsecond)
+    hipError_t e = hipFuncSetAttribute((const void*)k_conv_mfma<KC, NB, HALF>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
     int per_cu = (int)((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;    // 16 waves per CU
-    const int grid = 256 * per_cu;  // a multiple of 8 (one span of tiles per XCD)
+    const int grid = (device_cu_count() * per_cu + 7) / 8 * 8;  // a multiple of 8 (one span of tiles per XCD)
     hipLaunchKernelGGL((k_conv_mfma<KC, NB, HALF>), dim3(grid), dim3(kConvWaves * 64), lds, s, taps, nnz_in, feats, wb,
                        bias,
                        pairs, block_tap, tile_hdr, ctr, resp);

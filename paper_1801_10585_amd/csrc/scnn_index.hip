@@ -10,9 +10,24 @@
 // non-zero at) are the occupied sites dilated by the filter's non-zero taps;
 // they are marked in a second bitmap, counted per word, scanned, and written
 // out as a sorted list of per-sample site indices.
+#include <atomic>
+
 #include "scnn_internal.h"
 
 namespace scnn {
+
+int device_cu_count() {
+    static std::atomic<int> cache[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    int n = (dev >= 0 && dev < 64) ? cache[dev].load(std::memory_order_relaxed) : 0;
+    if (n <= 0) {
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) return 256;
+        if (dev >= 0 && dev < 64) cache[dev].store(n, std::memory_order_relaxed);
+    }
+    return n;
+}
+
 
 // ------------------------------------------------------------------ zero fill
 __global__ void k_zero(uint4* __restrict__ p, size_t n16) {

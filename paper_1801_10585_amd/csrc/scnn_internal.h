@@ -64,6 +64,12 @@ struct Counters {
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
 
+// Compute units of the current device (asked once per device; 256, the part the launch shapes were tuned on, if the
+// runtime will not say).  The persistent kernels size their grids from it.  The XCD-aware tile orders assume that
+// workgroup i runs on XCD i % 8, which is how an 8-XCD part deals out workgroups; on another partitioning they are
+// still correct, the spans just stop matching the L2s.
+int device_cu_count();
+
 __device__ inline long long lin_of(const Geom& g, int c0, int c1, int c2) {
     // unused leading axes have extent 1 and coordinate 0
     return ((long long)c0 * g.E[1] + c1) * g.E[2] + c2;

@@ -1499,7 +1499,8 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
                                hipStream_t s) {
     // no more workgroups than can be resident at once (4 per CU by LDS), so that every ticket holder runs; three per
     // CU measured best for the wide kernels (cfg 4: 103 us against 107 with four and 110 with two)
-    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 3 ? 256 * 3 : tiles_cap);
+    const long long cus = device_cu_count();
+    long long blocks = tiles_cap < 1 ? 1 : (tiles_cap > cus * 3 ? cus * 3 : tiles_cap);
     // Narrow layers: a ticket covers 1, 2, 4 .. NT_ tiles, the fewest that leave at most two tickets per CU (a small
     // layer is bound by the tickets, taken one at a time, and every workgroup launched takes at least one; one per
     // CU and four per CU both measured slower on the paper's networks).
@@ -1508,7 +1509,7 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
         int tps = 1;                                                                                              \
         while (tps < NT_ && tiles_cap > 512ll * tps) tps *= 2;                                                    \
         long long nb = (tiles_cap + tps - 1) / tps;                                                               \
-        nb = nb < 1 ? 1 : (nb > 256 * 3 ? 256 * 3 : nb);                                                          \
+        nb = nb < 1 ? 1 : (nb > cus * 3 ? cus * 3 : nb);                                                          \
         hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)nb), dim3(256), 0, s, g, channels, \
                            mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, \
                            out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);                          \
@@ -1519,7 +1520,7 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
     else if (channels <= 32) SCNN_NARROW_CASE(32, 4);
     else if (channels <= 64) {
         if (tile_base) {
-            const long long sb = tiles_cap < 1 ? 1 : (tiles_cap > 256 * 4 ? 256 * 4 : tiles_cap);
+            const long long sb = tiles_cap < 1 ? 1 : (tiles_cap > cus * 4 ? cus * 4 : tiles_cap);
             hipLaunchKernelGGL(k_select_write64<true>, dim3((unsigned)sb), dim3(256), 0, s, g, channels, mode, relu,
                                cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
                                out_capacity, nnz_out, aux_imm, aux_is_cand, tile_base);

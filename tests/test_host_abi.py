@@ -120,7 +120,7 @@ def test_host_argument_checks_of_the_widening_entry_points():
 
 def test_measurement_switches_reject_unknown_modes():
     L = scnn.load_library()
-    assert L.scnn_profile_enable(3) == -1 and b"profile mode" in L.scnn_last_error()
+    assert L.scnn_profile_enable(4) == -1 and b"profile mode" in L.scnn_last_error()
     assert L.scnn_profile_enable(2) == 0 and L.scnn_profile_enable(0) == 0
     assert L.scnn_set_conv_path(4) == -1 and b"conv path" in L.scnn_last_error()
     assert L.scnn_set_conv_path(2) == 0 and L.scnn_set_conv_path(0) == 0
