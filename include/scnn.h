@@ -38,8 +38,11 @@
  * host string for the calling thread's last failure.  No exception crosses
  * this boundary.  Preconditions that are not checked on the host (sorted,
  * unique, in-range coordinates; finite values) are reported through the
- * status bits where the kernels can see them cheaply; rows with out-of-range
- * coordinates are skipped, never dereferenced.
+ * status bits where the kernels can see them cheaply.  With
+ * SCNN_FLAG_BAD_COORD or SCNN_FLAG_UNSORTED set the results of the call are
+ * undefined (a row with an out-of-range coordinate is never used as an
+ * address, but the rows that share its 64-site bitmap word are then looked up
+ * one row off); every access stays inside the caller's arrays.
  */
 #ifndef SCNN_H_
 #define SCNN_H_
