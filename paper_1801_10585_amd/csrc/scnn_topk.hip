@@ -1131,9 +1131,8 @@ __global__ __launch_bounds__(256) void k_select_write(Geom g, int channels, int 
 // a row's rank is a popcount.  Three barriers per step.
 // STREAM: the output row at which every tile starts is known (tile_base, from the rows marked during the
 // selection): tiles are dealt out by workgroup index, nothing is published or looked back at, and no tile waits for
-// another.  The selection can find, late, that its marks are not to be relied on (ctr->bracket_failed); the stream
-// kernel then leaves at once and the look-back kernel, launched behind it, does the work; otherwise that one leaves.
-template <bool STREAM>
+// another.  The selection can find, late, that its marks are not to be relied on (ctr->bracket_failed): the kernel
+// then works by look-back although it was given tile_base (the choice is uniform over the launch).
 __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels, int mode, int relu,
                                                         const int* __restrict__ cand_start,
                                                         const int* __restrict__ tile_start,
@@ -1145,7 +1144,7 @@ __global__ __launch_bounds__(256, 4) void k_select_write64(Geom g, int channels,
                                                         float* __restrict__ out_feats, long long out_capacity,
                                                         long long* __restrict__ nnz_out, long long aux_imm,
                                                         int aux_is_cand, const long long* __restrict__ tile_base) {
-    if (STREAM ? ctr->bracket_failed != 0u : (tile_base != nullptr && ctr->bracket_failed == 0u)) return;
+    const bool STREAM = tile_base != nullptr && ctr->bracket_failed == 0u;
     __shared__ uint4 s_thr[64];  // per channel: {threshold if the position passes the cut, threshold if not, cut, -}
     __shared__ unsigned long long s_mask[3][2];
     __shared__ int s_rank[kTileRows];  // output row of a kept row of the tile being written, relative; -1 = dropped
@@ -1519,17 +1518,13 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
     else if (channels <= 16) SCNN_NARROW_CASE(16, 8);
     else if (channels <= 32) SCNN_NARROW_CASE(32, 4);
     else if (channels <= 64) {
-        if (tile_base) {
-            const long long sb = tiles_cap < 1 ? 1 : (tiles_cap > cus * 4 ? cus * 4 : tiles_cap);
-            hipLaunchKernelGGL(k_select_write64<true>, dim3((unsigned)sb), dim3(256), 0, s, g, channels, mode, relu,
-                               cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
-                               out_capacity, nnz_out, aux_imm, aux_is_cand, tile_base);
-        }
-        hipLaunchKernelGGL(k_select_write64<false>, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
+        // (streaming: four workgroups per CU; by look-back three measured best, and four cost it 5 %, which only the
+        // rare launch that was given tile_base and cannot use it pays)
+        if (tile_base) blocks = tiles_cap < 1 ? 1 : (tiles_cap > cus * 4 ? cus * 4 : tiles_cap);
+        hipLaunchKernelGGL(k_select_write64, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
                            out_capacity, nnz_out, aux_imm, aux_is_cand, tile_base);
-    }
-    else
+    } else
         hipLaunchKernelGGL(k_select_write, dim3((unsigned)blocks), dim3(256), 0, s, g, channels, mode, relu,
                            cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, out_feats,
                            out_capacity, nnz_out, aux_imm, aux_is_cand);
