@@ -88,3 +88,40 @@ def test_vector_convolution_regimes(case):
     say(f"regime extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} k={k}")
     check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, None, k, 0.1, scnn.ABS,
                               columns=_sampled_columns(rng, batch, c_out, 4), tag=f"regime {extent}")
+
+
+# Long columns (more than 32768 sites per sample): the selection brackets the k-th key from every S-th tile of 128
+# rows, S = ceil(tiles / 128); the compaction streams for 33..64 channels and looks back otherwise; the settling pass
+# holds up to 20480 bracket entries of a column in registers.  Row counts on both sides of S = 1 / 2, channel counts
+# on both sides of 33 and 64, and few distinct values, which put far more than 20480 equal scores into the bracket.
+SELECTION_REGIMES = [
+    # rows per sample, channels, levels (None: normal values)
+    (128 * 128, 40, None), (128 * 128 + 1, 40, None), (129 * 128, 33, 40), (300 * 128 + 77, 32, None),
+    (300 * 128 + 77, 64, 2), (300 * 128 + 77, 65, None), (40000, 48, 2), (40000, 8, 2),
+]
+
+
+@pytest.mark.parametrize("case", SELECTION_REGIMES)
+@pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
+def test_selection_regimes_bit_exact(case, mode):
+    import oracle
+    from tests.test_gpu_parity import dev, host
+    rows_per_sample, channels, levels = case
+    extent, batch = (64, 64, 16), 2
+    rng = np.random.default_rng(abs(hash((case, mode))) % 2 ** 32)
+    full = random_sparse_sites(rng, extent, batch, 0.8)
+    keep = np.concatenate([np.nonzero(full[:, 0] == b)[0][:rows_per_sample] for b in range(batch)])
+    coords = np.ascontiguousarray(full[keep])
+    assert (np.bincount(coords[:, 0], minlength=batch) == rows_per_sample).all()
+    if levels:
+        resp = rng.integers(-levels, levels + 1, size=(coords.shape[0], channels)).astype(np.float32) * 0.25
+    else:
+        resp = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    resp = np.ascontiguousarray(resp * (rng.random(resp.shape) < 0.9), dtype=np.float32)
+    for k in (1, rows_per_sample // 20, rows_per_sample // 2, rows_per_sample):
+        say(f"selection regime rows={rows_per_sample} C={channels} levels={levels} mode={mode} k={k}")
+        gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+        oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+        assert int(n[2]) == 0
+        assert np.array_equal(host(gc), oc_), (case, k)
+        assert np.array_equal(host(gf), of_), (case, k)
