@@ -125,3 +125,67 @@ def test_selection_regimes_bit_exact(case, mode):
         assert int(n[2]) == 0
         assert np.array_equal(host(gc), oc_), (case, k)
         assert np.array_equal(host(gf), of_), (case, k)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_selection_random_long_columns(seed):
+    """Samples of very different sizes in one batch (one of them may be empty or tiny), channels that are all zero
+    or hold a single entry, k above and below the samples' entry counts: attention_topk bit for bit."""
+    import oracle
+    from tests.test_gpu_parity import dev, host
+    rng = np.random.default_rng(5000 + seed)
+    extent = [(64, 64, 16), (40, 40, 40), (256, 300)][seed % 3]
+    batch = int(rng.integers(2, 5))
+    channels = int(rng.choice([1, 5, 16, 33, 40, 64, 70]))
+    full = random_sparse_sites(rng, extent, batch, 0.7)
+    keep = []
+    for b in range(batch):
+        rows = np.nonzero(full[:, 0] == b)[0]
+        frac = float(rng.choice([0.0, 0.001, 0.3, 1.0]))
+        keep.append(rows[: int(len(rows) * frac)])
+    coords = np.ascontiguousarray(full[np.concatenate(keep)])
+    levels = [None, 3, 1][seed % 3]
+    if levels:
+        resp = rng.integers(-levels, levels + 1, size=(coords.shape[0], channels)).astype(np.float32)
+    else:
+        resp = rng.standard_cauchy(size=(coords.shape[0], channels)).astype(np.float32)  # heavy tails: wide key range
+    resp *= rng.random(resp.shape) < float(rng.choice([0.05, 0.5, 1.0]))
+    if channels > 2:
+        resp[:, 0] = 0.0                      # a channel without entries
+        resp[:, 1] = 0.0
+        if len(resp):
+            resp[len(resp) // 2, 1] = 2.5     # a channel with one entry
+    resp = np.ascontiguousarray(resp, dtype=np.float32)
+    n_max = int(np.bincount(coords[:, 0], minlength=batch).max()) if len(coords) else 0
+    mode = scnn.ABS if seed % 2 == 0 else scnn.SIGNED
+    for k in sorted({0, 1, max(1, n_max // 50), max(1, n_max // 3), n_max, n_max + 5}):
+        say(f"selection random seed={seed} extent={extent} B={batch} C={channels} rows={len(coords)} k={k} mode={mode}")
+        gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+        oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+        assert int(n[2]) == 0
+        assert np.array_equal(host(gc), oc_), (seed, k)
+        assert np.array_equal(host(gf), of_), (seed, k)
+
+
+# Whole layers whose columns are long and whose channel counts take the row-marking selection with the streaming
+# compaction (33..64 output channels), with the quad, the pair-list and the vector convolution in front of it.
+WIDE_LONG = [
+    ((40, 40, 40), 2, 32, 40, 0.08), ((36, 36, 36), 1, 16, 64, 0.10), ((48, 40, 36), 2, 8, 33, 0.06),
+    ((40, 40, 40), 1, 64, 48, 0.05),
+]
+
+
+@pytest.mark.parametrize("case", WIDE_LONG)
+def test_wide_layers_with_long_columns(case):
+    extent, batch, c_in, c_out, density = case
+    rng = np.random.default_rng(abs(hash(case)) % 2 ** 32)
+    coords = random_sparse_sites(rng, extent, batch, density)
+    feats = np.ascontiguousarray(rng.normal(size=(coords.shape[0], c_in)).astype(np.float32))
+    w = make_filter(rng, (3, 3, 3), c_in, c_out, 0.9, 0.3)
+    bias = rng.normal(size=c_out).astype(np.float32) * 0.1
+    n = int(np.prod(extent))
+    for rho in (0.02, 0.3):
+        k = scnn.k_from_rho(rho, n)
+        say(f"wide/long extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} rho={rho} k={k}")
+        check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, bias, k, rho, scnn.ABS,
+                                  columns=_sampled_columns(rng, batch, c_out, 6), tag=f"wide/long {extent} rho={rho}")
