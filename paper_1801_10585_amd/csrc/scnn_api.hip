@@ -32,8 +32,11 @@ static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long 
     if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
     const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
-    if (quad_ok && c_in >= 32) return ConvKernel::kQuad;
-    if (pair_ok && (c_in >= 32 || (c_in == 16 && c_out >= 32 && tiles_cap > 1280))) return ConvKernel::kPair;
+    // sixteen input channels pay for the matrix-core kernels' look-ups and lists only on large layers with at least
+    // 32 output channels; below that, and with fewer input channels, the vector kernels are faster
+    const bool wide = c_in >= 32 || (c_in == 16 && c_out >= 32 && tiles_cap > 1280);
+    if (quad_ok && wide) return ConvKernel::kQuad;
+    if (pair_ok && wide) return ConvKernel::kPair;
     return ConvKernel::kValu;
 }
 
