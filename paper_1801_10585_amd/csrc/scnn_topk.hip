@@ -486,15 +486,20 @@ struct ColumnEntries {  // slot i of a column of the response matrix (key 0: not
 // tau = the kk-th strongest key among m entries {key, position} whose keys lie in [key_lo, key_hi] (key 0: not an
 // entry); n_eq entries equal it, the q of lowest position survive: those at positions <= cut.  1 <= kk <= number of
 // entries.  The digits of the radix select, 11 bits at most, are taken from key - key_lo, most significant first, so
-// that a narrow bracket is settled in two passes.  Up to kSettleCached entries per thread are held in registers
-// between the passes.  (whole workgroup)
+// that a narrow bracket is settled in two passes.  Between the passes up to kSettleCached entries per thread are held
+// in registers and kSettleLds more per workgroup in LDS (brackets that hold long runs of equal scores run to 30 000
+// entries on the paper's first layers).  (whole workgroup)
 constexpr int kSettleCached = 20;
+constexpr unsigned kSettleRegs = (unsigned)kSettleCached * 1024u;  // entries held in registers at most
+constexpr unsigned kSettleLds = 12288;                             // entries held in LDS behind them
 
-// held: the entries threadIdx.x + 1024 * u of the column, if cached (m <= kSettleCached * 1024), loaded by the caller.
+// held: the entries threadIdx.x + 1024 * u of the column, more: the entries from kSettleRegs on, if cached
+// (m <= kSettleRegs + kSettleLds); both loaded by the caller.
 template <class Entries>
-__device__ inline void settle_column(const Entries& entry, unsigned m, const uint2 (&held)[kSettleCached], bool cached,
-                                     unsigned key_lo, unsigned key_hi, long long kk, unsigned* s_h, unsigned* s_wave,
-                                     int* s_res, unsigned& tau, unsigned& n_eq, unsigned& q, unsigned& cut) {
+__device__ inline void settle_column(const Entries& entry, unsigned m, const uint2 (&held)[kSettleCached],
+                                     const uint2* more, bool cached, unsigned key_lo, unsigned key_hi, long long kk,
+                                     unsigned* s_h, unsigned* s_wave, int* s_res, unsigned& tau, unsigned& n_eq,
+                                     unsigned& q, unsigned& cut) {
     auto clear = [&]() {
         for (int i = threadIdx.x; i < kHistBins; i += kSideThreads) s_h[i] = 0;
         __syncthreads();
@@ -519,6 +524,15 @@ __device__ inline void settle_column(const Entries& entry, unsigned m, const uin
             for (int u = 0; u < kSettleCached; ++u) {
                 const bool valid = held[u].x != 0u && pass(held[u]);
                 add(valid, valid ? digit(held[u]) : 0u);
+            }
+            if (m > kSettleRegs) {  // (uniform; whole waves take part in every round: add() uses ballots)
+                const unsigned n_more = m - kSettleRegs;
+                for (unsigned j0 = 0; j0 < n_more; j0 += kSideThreads) {
+                    const unsigned j = j0 + threadIdx.x;
+                    const uint2 x = j < n_more ? more[j] : make_uint2(0u, 0u);
+                    const bool valid = x.x != 0u && pass(x);
+                    add(valid, valid ? digit(x) : 0u);
+                }
             }
         } else {
             for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // loads issued eight at a time
@@ -585,6 +599,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
     __shared__ unsigned s_wave[4];
     __shared__ int s_res[2];
     __shared__ uint2 s_part[4];
+    __shared__ uint2 s_more[kSettleLds];
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
@@ -609,7 +624,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
         const size_t pitch = (size_t)channels * kTileRows;
         const SideEntries e{side + st.side_off, mode};
         // the side buffer's entries of the column, in registers if they are few enough (the rule)
-        const bool cached = m <= (unsigned)kSettleCached * kSideThreads;  // (uniform)
+        const bool cached = m <= kSettleRegs + kSettleLds;  // (uniform)
         uint2 kept[kSettleCached];
         if (cached) {
 #pragma unroll
@@ -617,6 +632,8 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                 const unsigned i = threadIdx.x + (unsigned)kSideThreads * u;
                 kept[u] = i < m ? e(i) : make_uint2(0u, 0u);
             }
+            for (unsigned i = kSettleRegs + threadIdx.x; i < m; i += kSideThreads) s_more[i - kSettleRegs] = e(i);
+            __syncthreads();
         }
         bool held;  // the side buffer decides the column
         if ((long long)st.n_nz <= k) {
@@ -628,10 +645,10 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
             const long long k_rem = k - (long long)st.n_above;
             held = k_rem >= 1 && k_rem <= (long long)m;
             if (held)
-                settle_column(e, m, kept, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq, st.q,
-                              st.cut);
+                settle_column(e, m, kept, s_more, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq,
+                              st.q, st.cut);
             else
-                settle_column(ColumnEntries{col0, pitch, mode}, (unsigned)(t1 - t0) * kTileRows, kept, false, 0u,
+                settle_column(ColumnEntries{col0, pitch, mode}, (unsigned)(t1 - t0) * kTileRows, kept, s_more, false, 0u,
                               0xffffffffu, k, s_h, s_wave, s_res, st.tau, st.n_eq, st.q, st.cut);
         }
         if (threadIdx.x == 0) {
@@ -662,6 +679,10 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
                         if (u0 + u < kSettleCached) mark(kept[u0 + u], have[u]);
+                }
+                for (unsigned i = kSettleRegs + threadIdx.x; i < m; i += kSideThreads) {
+                    const uint2 x = s_more[i - kSettleRegs];
+                    if (survives(x)) mark(x, __hip_atomic_load(word_of(x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 }
             } else {
                 for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // eight entries in flight per thread
