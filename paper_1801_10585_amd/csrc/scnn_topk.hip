@@ -119,7 +119,8 @@ hipError_t launch_rows_to_planar(const Geom& g, const int32_t* coords, const flo
 
 // Rank search in a 2048-bin histogram held in LDS.  descending: find the bin holding the kk-th entry counted from
 // the top bin; else from the bottom bin.  Returns the bin and the number of entries strictly before it in that
-// order.  1 <= kk <= total must hold.  Contains __syncthreads(); s_res is two shared words.
+// order.  1 <= kk <= total must hold.  Contains two __syncthreads(); s_res is two shared words that the next call
+// must not share (callers alternate between two pairs): the result is read after the last barrier.
 __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descending, unsigned* s_wave, int* s_res,
                                   int& bin_out, unsigned& before_out) {
     // Works for any block size that is a multiple of 64 and at least 256: the first 256 threads search, every
@@ -165,7 +166,6 @@ __device__ inline void block_pick(const unsigned* s_h, long long kk, bool descen
     __syncthreads();
     bin_out = s_res[0];
     before_out = (unsigned)s_res[1];
-    __syncthreads();
 }
 
 // First launch: a bracket [tau_lo, tau_hi] around the k-th strongest key of every column, from a sample of the
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int chann
                                                              ColState* __restrict__ cols) {
     __shared__ unsigned s_h[kHistBins], s_h2[kHistBins];
     __shared__ unsigned s_wave[4];
-    __shared__ int s_res[2];
+    __shared__ int s_res[4];
     __shared__ unsigned s_total;
     __shared__ unsigned s_range[2];
     auto clamp_add = [](unsigned a, unsigned c) { return a + c < a ? 0xffffffffu : a + c; };
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int chann
     if (nz > 0) {
         block_pick(s_h, rank_up, true, s_wave, s_res, bin_up, before);
         rank_up -= (long long)before;
-        block_pick(s_h, rank_dn, true, s_wave, s_res, bin_dn, before);
+        block_pick(s_h, rank_dn, true, s_wave, s_res + 2, bin_dn, before);
         rank_dn -= (long long)before;
     }
     int sub_up = 0, sub_dn = 0;
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(kBracketThreads) void k_bracket(int mode, int chann
         __syncthreads();
         if (nz > 0) {
             block_pick(s_h, rank_up, true, s_wave, s_res, sub_up, before);
-            block_pick(s_h2, rank_dn, true, s_wave, s_res, sub_dn, before);
+            block_pick(s_h2, rank_dn, true, s_wave, s_res + 2, sub_dn, before);
         }
     }
     st.tau_hi = 0xffffffffu;  // rank < 1: nothing is above
@@ -551,7 +551,7 @@ __device__ inline void settle_column(const Entries& entry, unsigned m, const uin
         }
         __syncthreads();
     };
-    int bin = 0;
+    int bin = 0, picks = 0;
     unsigned before = 0;
     const unsigned span = key_hi - key_lo;
     int nb = span ? 32 - __clz(span) : 1;  // bits of key - key_lo still open
@@ -561,7 +561,7 @@ __device__ inline void settle_column(const Entries& entry, unsigned m, const uin
         const int above = nb;  // (captured by value)
         histogram([=](uint2 x) { return (unsigned)((unsigned long long)(x.x - key_lo) >> above) == prefix; },
                   [=](uint2 x) { return ((x.x - key_lo) >> shift) & ((1u << w) - 1u); });
-        block_pick(s_h, kk, true, s_wave, s_res, bin, before);
+        block_pick(s_h, kk, true, s_wave, s_res + 2 * (picks++ & 1), bin, before);
         kk -= (long long)before;
         prefix = (prefix << w) | (unsigned)bin;
         nb = shift;
@@ -580,7 +580,7 @@ __device__ inline void settle_column(const Entries& entry, unsigned m, const uin
             const int shift = pass == 0 ? 21 : (pass == 1 ? 10 : 0), bits = pass == 2 ? 10 : 11;
             histogram([=](uint2 x) { return x.x == t && (pass == 0 || (x.y >> (shift + bits)) == pprefix); },
                       [=](uint2 x) { return (x.y >> shift) & ((1u << bits) - 1u); });
-            block_pick(s_h, rank, false, s_wave, s_res, bin, before);
+            block_pick(s_h, rank, false, s_wave, s_res + 2 * (picks++ & 1), bin, before);
             pprefix = (pprefix << bits) | (unsigned)bin;
             rank -= (long long)before;
         }
@@ -597,7 +597,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                                                          long long* __restrict__ tile_base, Counters* ctr) {
     __shared__ unsigned s_h[kHistBins];
     __shared__ unsigned s_wave[4];
-    __shared__ int s_res[2];
+    __shared__ int s_res[4];
     __shared__ uint2 s_part[4];
     __shared__ uint2 s_more[kSettleLds];
     const int col = blockIdx.x;
@@ -778,7 +778,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
                                                                 ColState* __restrict__ cols) {
     __shared__ unsigned s_h[kHistBins];
     __shared__ unsigned s_wave[4];
-    __shared__ int s_res[2];
+    __shared__ int s_res[4];
     __shared__ unsigned s_total;
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
@@ -827,7 +827,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     long long k_rem = k - (long long)before;
     histogram([prefix1](unsigned x, unsigned) { return (x >> 21) == prefix1; },
               [](unsigned x, unsigned) { return (x >> 10) & 0x7ffu; });
-    block_pick(s_h, k_rem, true, s_wave, s_res, bin, before);  // key bits [20:10]
+    block_pick(s_h, k_rem, true, s_wave, s_res + 2, bin, before);  // key bits [20:10]
     const unsigned prefix2 = (prefix1 << 11) | (unsigned)bin;
     k_rem -= (long long)before;
     histogram([prefix2](unsigned x, unsigned) { return (x >> 10) == prefix2; },
@@ -840,7 +840,7 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     unsigned cut = 0xffffffffu;
     if (q < n_eq) {  // q-th smallest position among the entries equal to tau (positions have 15 bits)
         histogram([tau](unsigned x, unsigned) { return x == tau; }, [](unsigned, unsigned i) { return i >> 4; });
-        block_pick(s_h, (long long)q, false, s_wave, s_res, bin, before);
+        block_pick(s_h, (long long)q, false, s_wave, s_res + 2, bin, before);
         const unsigned phi = (unsigned)bin;
         const long long rank = (long long)q - (long long)before;
         histogram([tau, phi](unsigned x, unsigned i) { return x == tau && (i >> 4) == phi; },
