@@ -23,18 +23,19 @@ static thread_local const char* g_last_conv_kernel = "";
 enum class ConvKernel { kValu, kPair, kQuad };
 
 // Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
-// 64 output channels with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With sixteen
-// input channels the matrix cores pay only on large layers with at least 32 output channels; narrower layers are
-// faster on the vector kernels.
+// 64 output channels with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With 16 or
+// 24 input channels the matrix cores pay only on layers of more than 1024 tiles with at least 24 output channels;
+// narrower and smaller layers are faster on the vector kernels.
 static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
     if (g_conv_path == 1) return ConvKernel::kValu;
     const bool pair_ok = conv_mfma_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
     const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
-    // sixteen input channels pay for the matrix-core kernels' look-ups and lists only on large layers with at least
-    // 32 output channels; below that, and with fewer input channels, the vector kernels are faster
-    const bool wide = c_in >= 32 || (c_in == 16 && c_out >= 32 && tiles_cap > 1280);
+    // 16 and 24 input channels pay for the matrix-core kernels' look-ups and lists only with at least 24 output
+    // channels (two quads then share a matrix instruction whatever the count) on layers of more than 1024 tiles;
+    // below that, and with fewer input channels, the vector kernels are faster
+    const bool wide = c_in >= 32 || ((c_in == 16 || c_in == 24) && c_out >= 24 && tiles_cap > 1024);
     if (quad_ok && wide) return ConvKernel::kQuad;
     if (pair_ok && wide) return ConvKernel::kPair;
     return ConvKernel::kValu;
@@ -269,6 +270,8 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cand_prefix = c.take<unsigned>(nw);
     w->pprefix = c.take<unsigned>(pool ? nwp : 0);
     long long sb = scan_blocks(nw);
+    // per-chunk candidate counts (chunks of 16 words up to 32768 words, of 256 beyond)
+    if (nw <= kEmitMidWords && (nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256) > sb) sb = nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256;
     if (scan_blocks(w->tiles_cap) > sb) sb = scan_blocks(w->tiles_cap);
     if (scan_blocks(nwp) > sb) sb = scan_blocks(nwp);
     w->block_sums = c.take<unsigned>(sb);
@@ -390,10 +393,14 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
     SCNN_TRY(launch_index_build(g, in_coords, nnz_in, (const long long*)nnz_in_dev, nnz_in, ws.occ, ws.occ_prefix,
                                 ws.ctr, s));
     timer.mark();
-    SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, s));
+    const bool emit_mid = nw > kEmitSmallWords && nw <= kEmitMidWords;
+    SCNN_TRY(launch_cand_dilate(g, ws.occ, ws.tap_active, ws.cand, ws.cand_prefix, emit_mid ? ws.block_sums : nullptr, s));
     if (nw <= kEmitSmallWords) {
         SCNN_TRY(launch_cand_emit_small(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start,
                                         ws.tile_start, ws.rows16_start, ws.ctr, s));
+    } else if (emit_mid) {
+        SCNN_TRY(launch_cand_emit_mid(g, ws.cand, ws.cand_prefix, ws.block_sums, nw, ws.cand_lin, ws.cand_cap,
+                                      ws.cand_start, ws.tile_start, ws.rows16_start, ws.ctr, s));
     } else {
         SCNN_TRY(launch_exclusive_scan(ws.cand_prefix, nw, nw, nullptr, ws.block_sums, &ws.ctr->n_cand, s));
         SCNN_TRY(launch_cand_emit(g, ws.cand, ws.cand_prefix, nw, ws.cand_lin, ws.cand_cap, ws.cand_start,

@@ -338,6 +338,67 @@ __device__ inline unsigned long long funnel64(unsigned long long lo, unsigned lo
 // LANES lanes share one bitmap word, one (delta_0, delta_1) line at a time each: 16 on small grids, where one lane
 // per word would leave most of the chip idle behind a chain of dependent loads, 1 on large grids.
 template <int kDilateLanes>
+__device__ __forceinline__ unsigned long long dilate_word(const Geom& g, const unsigned long long* __restrict__ occ,
+                                                          const int* __restrict__ tap_active, long long w, int sub) {
+    const int n_lines = g.K[0] * g.K[1];
+    const int b = (int)(w / g.Wps);
+    const long long p_first = (w - (long long)b * g.Wps) * 64;  // lin of bit 0
+    long long remaining = g.N - p_first;                         // bits of this word that are sites
+    if (remaining > 64) remaining = 64;
+    unsigned long long out = 0;
+    const long long sample_bit0 = (long long)b * g.Npad;
+    const long long word_lo = (long long)b * g.Wps, word_hi = word_lo + g.Wps;  // this sample's words
+    long long line = p_first / g.E[2];
+    int c2 = (int)(p_first - line * g.E[2]);
+    int c1 = (int)(line % g.E[1]), c0 = (int)(line / g.E[1]);
+    int bit = 0;
+    while (remaining > 0) {
+        int len = g.E[2] - c2;
+        if (len > remaining) len = (int)remaining;
+        unsigned long long run = 0;
+        for (int l = sub; l < n_lines; l += kDilateLanes) {
+            const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
+            const int q0 = c0 + t0 - g.H[0], q1 = c1 + t1 - g.H[1];
+            if ((unsigned)q0 >= (unsigned)g.E[0] || (unsigned)q1 >= (unsigned)g.E[1]) continue;
+            // window of occupancy bits [s - H2, s + len + H2) of line (q0, q1), s = site (q0, q1, c2)
+            const long long s = sample_bit0 + ((long long)q0 * g.E[1] + q1) * g.E[2] + c2;
+            const long long wb = (s - g.H[2]) >> 6;  // arithmetic shift: floor also for negatives
+            unsigned long long win[3];
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const long long wi = wb + i;
+                win[i] = (wi >= word_lo && wi < word_hi) ? occ[wi] : 0ull;
+            }
+            const int* act = tap_active + l * g.K[2];
+            for (int t2 = 0; t2 < g.K[2]; ++t2) {
+                if (!act[t2]) continue;
+                const int d2 = t2 - g.H[2];
+                // source z = c2 + i + d2 must stay on the line: i in [lo, hi)
+                int lo = -d2 - c2, hi = g.E[2] - d2 - c2;
+                if (lo < 0) lo = 0;
+                if (hi > len) hi = len;
+                if (lo >= hi) continue;
+                const int o = (int)(s + d2 - wb * 64);  // 0 <= o < 128 for H2 <= 32
+                unsigned long long bits = o < 64 ? funnel64(win[0], win[1], o) : funnel64(win[1], win[2], o - 64);
+                unsigned long long m = (hi - lo) >= 64 ? ~0ull : (((1ull << (hi - lo)) - 1ull) << lo);
+                run |= bits & m;
+            }
+        }
+        out |= run << bit;
+        bit += len;
+        remaining -= len;
+        c2 = 0;
+        if (++c1 == g.E[1]) { c1 = 0; ++c0; }
+    }
+    // OR of the lanes' lines
+    if constexpr (kDilateLanes > 1) {
+#pragma unroll
+        for (int d = 1; d < kDilateLanes; d <<= 1) out |= __shfl_xor(out, d, kDilateLanes);
+    }
+    return out;
+}
+
+template <int kDilateLanes>
 __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long long* __restrict__ occ,
                                                      const int* __restrict__ tap_active,
                                                      unsigned long long* __restrict__ cand,
@@ -345,63 +406,9 @@ __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long
     const long long n_words = (long long)g.batch * g.Wps;
     const int sub = threadIdx.x & (kDilateLanes - 1);
     const long long groups = (long long)gridDim.x * (blockDim.x / kDilateLanes);
-    const int n_lines = g.K[0] * g.K[1];
     for (long long w = (long long)blockIdx.x * (blockDim.x / kDilateLanes) + threadIdx.x / kDilateLanes; w < n_words;
          w += groups) {
-        const int b = (int)(w / g.Wps);
-        const long long p_first = (w - (long long)b * g.Wps) * 64;  // lin of bit 0
-        long long remaining = g.N - p_first;                         // bits of this word that are sites
-        if (remaining > 64) remaining = 64;
-        unsigned long long out = 0;
-        const long long sample_bit0 = (long long)b * g.Npad;
-        const long long word_lo = (long long)b * g.Wps, word_hi = word_lo + g.Wps;  // this sample's words
-        long long line = p_first / g.E[2];
-        int c2 = (int)(p_first - line * g.E[2]);
-        int c1 = (int)(line % g.E[1]), c0 = (int)(line / g.E[1]);
-        int bit = 0;
-        while (remaining > 0) {
-            int len = g.E[2] - c2;
-            if (len > remaining) len = (int)remaining;
-            unsigned long long run = 0;
-            for (int l = sub; l < n_lines; l += kDilateLanes) {
-                const int t0 = l / g.K[1], t1 = l - t0 * g.K[1];
-                const int q0 = c0 + t0 - g.H[0], q1 = c1 + t1 - g.H[1];
-                if ((unsigned)q0 >= (unsigned)g.E[0] || (unsigned)q1 >= (unsigned)g.E[1]) continue;
-                // window of occupancy bits [s - H2, s + len + H2) of line (q0, q1), s = site (q0, q1, c2)
-                const long long s = sample_bit0 + ((long long)q0 * g.E[1] + q1) * g.E[2] + c2;
-                const long long wb = (s - g.H[2]) >> 6;  // arithmetic shift: floor also for negatives
-                unsigned long long win[3];
-#pragma unroll
-                for (int i = 0; i < 3; ++i) {
-                    const long long wi = wb + i;
-                    win[i] = (wi >= word_lo && wi < word_hi) ? occ[wi] : 0ull;
-                }
-                const int* act = tap_active + l * g.K[2];
-                for (int t2 = 0; t2 < g.K[2]; ++t2) {
-                    if (!act[t2]) continue;
-                    const int d2 = t2 - g.H[2];
-                    // source z = c2 + i + d2 must stay on the line: i in [lo, hi)
-                    int lo = -d2 - c2, hi = g.E[2] - d2 - c2;
-                    if (lo < 0) lo = 0;
-                    if (hi > len) hi = len;
-                    if (lo >= hi) continue;
-                    const int o = (int)(s + d2 - wb * 64);  // 0 <= o < 128 for H2 <= 32
-                    unsigned long long bits = o < 64 ? funnel64(win[0], win[1], o) : funnel64(win[1], win[2], o - 64);
-                    unsigned long long m = (hi - lo) >= 64 ? ~0ull : (((1ull << (hi - lo)) - 1ull) << lo);
-                    run |= bits & m;
-                }
-            }
-            out |= run << bit;
-            bit += len;
-            remaining -= len;
-            c2 = 0;
-            if (++c1 == g.E[1]) { c1 = 0; ++c0; }
-        }
-        // OR of the lanes' lines
-        if constexpr (kDilateLanes > 1) {
-#pragma unroll
-            for (int d = 1; d < kDilateLanes; d <<= 1) out |= __shfl_xor(out, d, kDilateLanes);
-        }
+        const unsigned long long out = dilate_word<kDilateLanes>(g, occ, tap_active, w, sub);
         if (sub == 0) {
             cand[w] = out;
             cand_count[w] = (unsigned)__popcll(out);
@@ -409,10 +416,56 @@ __global__ __launch_bounds__(256) void k_cand_dilate(Geom g, const unsigned long
     }
 }
 
+// The same for bitmaps of up to kEmitMidWords words: a workgroup takes chunks of 256 / LANES consecutive words and also
+// leaves each chunk's candidate count, from which k_cand_emit_mid finds its place in the candidate list without a
+// scan launch in between.
+template <int kDilateLanes>
+__global__ __launch_bounds__(256) void k_cand_dilate_chunks(Geom g, const unsigned long long* __restrict__ occ,
+                                                            const int* __restrict__ tap_active,
+                                                            unsigned long long* __restrict__ cand,
+                                                            unsigned* __restrict__ cand_count,
+                                                            unsigned* __restrict__ chunk_sums) {
+    constexpr int kChunk = 256 / kDilateLanes;
+    __shared__ unsigned s_wave[4];
+    const long long n_words = (long long)g.batch * g.Wps;
+    const long long n_chunks = (n_words + kChunk - 1) / kChunk;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = threadIdx.x & (kDilateLanes - 1);
+    for (long long c = blockIdx.x; c < n_chunks; c += gridDim.x) {
+        const long long w = c * kChunk + threadIdx.x / kDilateLanes;
+        unsigned n = 0;
+        if (w < n_words) {
+            const unsigned long long out = dilate_word<kDilateLanes>(g, occ, tap_active, w, sub);
+            if (sub == 0) {
+                n = (unsigned)__popcll(out);
+                cand[w] = out;
+                cand_count[w] = n;
+            }
+        }
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) n += __shfl_xor(n, d, 64);
+        if (lane == 0) s_wave[wave] = n;
+        __syncthreads();
+        if (threadIdx.x == 0) chunk_sums[c] = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+        __syncthreads();
+    }
+}
+
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
-                              unsigned long long* cand, unsigned* cand_count, hipStream_t s) {
+                              unsigned long long* cand, unsigned* cand_count, unsigned* chunk_sums, hipStream_t s) {
     const long long n_words = (long long)g.batch * g.Wps;
     const int lanes = n_words <= 32768 ? 16 : 1;  // below about half a wave per SIMD at one lane per word
+    if (chunk_sums) {  // (the caller passes them for kEmitSmallWords < n_words <= kEmitMidWords)
+        long long blocks = (n_words * lanes + 255) / 256;
+        if (blocks > 8192) blocks = 8192;
+        if (lanes == 16)
+            hipLaunchKernelGGL(k_cand_dilate_chunks<16>, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active,
+                               cand, cand_count, chunk_sums);
+        else
+            hipLaunchKernelGGL(k_cand_dilate_chunks<1>, dim3((unsigned)blocks), dim3(256), 0, s, g, occ, tap_active,
+                               cand, cand_count, chunk_sums);
+        return hipGetLastError();
+    }
     long long blocks = (n_words * lanes + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 8192) blocks = 8192;
@@ -561,6 +614,89 @@ __global__ __launch_bounds__(256) void k_cand_emit_small(Geom g, const unsigned 
         if (o < cand_cap) cand_lin[o] = base + (unsigned)bit;
         ++o;
     }
+}
+
+// The same for bitmaps of up to kEmitMidWords words, after k_cand_dilate_chunks: a block owns 256 words, adds up the
+// counts of the chunks (of 1 << chunk_shift words: 256 or 16) before them, a few thousand numbers out of L2, and scans
+// its own words.  The last
+// block finds the per-sample ranges from the chunk counts by itself, so that no block waits for another.
+// `cand_count` holds the words' candidate counts, unscanned.
+__global__ __launch_bounds__(256) void k_cand_emit_mid(Geom g, const unsigned long long* __restrict__ cand,
+                                                       const unsigned* __restrict__ cand_count,
+                                                       const unsigned* __restrict__ chunk_sums, int chunk_shift,
+                                                       long long n_words, unsigned* __restrict__ cand_lin,
+                                                       long long cand_cap,
+                                                       int* __restrict__ cand_start, int* __restrict__ tile_start,
+                                                       int* __restrict__ rows16_start, Counters* ctr) {
+    __shared__ unsigned s_wave[4];
+    __shared__ unsigned long long s_total;
+    if (blockIdx.x == gridDim.x - 1) {
+        // candidates before sample b = chunks wholly before its first word + the words of the chunk it starts in
+        for (int b = threadIdx.x >> 6; b <= g.batch; b += 4) {
+            const long long w_b = (long long)b * g.Wps;  // (= n_words for b = batch)
+            const int c_b = (int)(w_b >> chunk_shift);
+            unsigned long long sum = 0;
+            for (int i = threadIdx.x & 63; i < c_b; i += 64) sum += chunk_sums[i];
+            for (long long w = ((long long)c_b << chunk_shift) + (threadIdx.x & 63); w < w_b; w += 64)
+                sum += cand_count[w];
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+            if ((threadIdx.x & 63) == 0) {
+                if (b == g.batch) s_total = sum;
+                // (a total beyond the capacity is far below 2^31: at most 2^31 sites per call)
+                cand_start[b] = (int)sum;
+            }
+        }
+        __syncthreads();
+        const long long n_cand = (long long)s_total;
+        const bool overflow = n_cand > cand_cap;
+        if (overflow)
+            for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) cand_start[b] = 0;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int acc = 0, acc16 = 0;
+            for (int b = 0; b < g.batch; ++b) {
+                tile_start[b] = acc;
+                rows16_start[b] = acc16;
+                const int n = cand_start[b + 1] - cand_start[b];
+                acc += (n + kTileRows - 1) / kTileRows;
+                acc16 += (n + 15) / 16;
+            }
+            tile_start[g.batch] = acc;
+            rows16_start[g.batch] = acc16;
+            ctr->n_cand = n_cand;
+            ctr->n_tiles = acc;
+            if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
+        }
+        return;
+    }
+    const int c = blockIdx.x;  // words [256 c, 256 c + 256): whole chunks (a chunk has 256 or 16 words)
+    const int chunks_below = (int)(((long long)c << 8) >> chunk_shift);
+    unsigned below = 0;
+    for (int i = threadIdx.x; i < chunks_below; i += 256) below += chunk_sums[i];
+    unsigned before_block;
+    (void)block_exclusive_scan_256(below, s_wave, before_block);  // (the total is what is wanted)
+    const long long w = (long long)c * 256 + threadIdx.x;
+    unsigned long long bits = w < n_words ? cand[w] : 0ull;
+    unsigned block_total;
+    long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
+    const unsigned base = w < n_words ? (unsigned)((w % g.Wps) * 64) : 0u;
+    while (bits) {
+        const int bit = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        if (o < cand_cap) cand_lin[o] = base + (unsigned)bit;
+        ++o;
+    }
+}
+
+hipError_t launch_cand_emit_mid(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
+                                const unsigned* chunk_sums, long long n_words, unsigned* cand_lin, long long cand_cap,
+                                int* cand_start, int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
+    const unsigned blocks = (unsigned)((n_words + 255) / 256);
+    const int chunk_shift = n_words <= 32768 ? 4 : 8;  // as launch_cand_dilate chooses its lanes per word
+    hipLaunchKernelGGL(k_cand_emit_mid, dim3(blocks + 1), dim3(256), 0, s, g, cand, cand_count, chunk_sums,
+                       chunk_shift, n_words, cand_lin, cand_cap, cand_start, tile_start, rows16_start, ctr);
+    return hipGetLastError();
 }
 
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,

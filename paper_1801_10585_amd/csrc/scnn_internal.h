@@ -252,14 +252,21 @@ hipError_t launch_index_build(const Geom& g, const int32_t* coords, long long n_
 hipError_t launch_prepare(const Geom& g, const float* w, int c_in, int c_out, int adjoint, int c_out_pad, double* wp,
                           float* wb, float* wq, int* tap_active, int* tap_coord, void* zero_p, size_t zero_bytes,
                           hipStream_t s);
+// chunk_sums: null, or (for more than kEmitSmallWords and at most kEmitMidWords words) counters that receive the
+// candidate counts of chunks of 16 words (up to 32768 words) or 256 words (beyond), for launch_cand_emit_mid
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
-                              unsigned long long* cand, unsigned* cand_count, hipStream_t s);
+                              unsigned long long* cand, unsigned* cand_count, unsigned* chunk_sums, hipStream_t s);
 hipError_t launch_popcount(const unsigned long long* bits, long long n_words, unsigned* out, hipStream_t s);
 // bitmaps of at most this many words: the emit kernels find their offsets themselves, no scan launch
 constexpr long long kEmitSmallWords = 8192;
 hipError_t launch_cand_emit_small(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
                                   long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
                                   int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
+// up to this many words the candidate list is emitted from per-chunk counts (8192 chunks of 256 words), no scan launch
+constexpr long long kEmitMidWords = 8192 * 256;
+hipError_t launch_cand_emit_mid(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
+                                const unsigned* chunk_sums, long long n_words, unsigned* cand_lin, long long cand_cap,
+                                int* cand_start, int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 hipError_t launch_cand_emit(const Geom& g, const unsigned long long* cand, const unsigned* cand_prefix,
                             long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
                             int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);

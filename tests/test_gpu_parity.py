@@ -510,6 +510,25 @@ def test_empty_input_and_zero_k():
     assert gc.shape[0] == 0 and int(n[1]) == 0
 
 
+@pytest.mark.parametrize("extent", [(64, 64, 136), (128, 128, 130)])
+def test_candidate_overflow_on_large_bitmaps(extent):
+    """Bitmaps of more than 8192 words (and of more than 32768): the candidate list is placed from per-chunk counts;
+    a capacity below the candidate count is flagged and leaves an empty output, the exact capacity works."""
+    rng = np.random.default_rng(extent[2])
+    coords = random_sparse_sites(rng, extent, 1, 0.002)
+    feats = rng.normal(size=(coords.shape[0], 2)).astype(np.float32)
+    w = rng.normal(size=(27, 2, 3)).astype(np.float32)
+    full_c, full_f, n = gpu_conv(extent, 1, coords, feats, (3, 3, 3), w, rho_up=1.0)
+    n_cand = int(n[1])
+    assert n_cand > 0 and int(n[0]) > 0
+    c, f, nn = scnn.sparse_conv_fwd(extent, 1, dev(coords), dev(feats), (3, 3, 3), dev(w), rho_up=1.0,
+                                    cand_capacity=n_cand - 1, sync=False)
+    nn = nn.cpu()
+    assert int(nn[2]) & scnn.FLAG_CAND_OVERFLOW and int(nn[0]) == 0 and int(nn[1]) == n_cand
+    c, f, nn = gpu_conv(extent, 1, coords, feats, (3, 3, 3), w, rho_up=1.0, cand_capacity=n_cand)
+    assert np.array_equal(c, full_c) and np.array_equal(f, full_f)
+
+
 def test_capacity_flags_and_validation():
     extent = (10, 10, 10)
     rng = np.random.default_rng(2)

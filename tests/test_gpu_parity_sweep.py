@@ -67,7 +67,9 @@ REGIMES = [
     ((48, 48, 48), 2, 6, 12, 0.08),    # most of 221184 sites are candidates: over 1024 tiles -> streaming form
     ((48, 48, 48), 2, 8, 8, 0.08),     # the same with at most 8 output channels: 8 accumulators per thread
     ((64, 64, 128), 1, 2, 4, 0.003),   # exactly 8192 bitmap words: the emit kernels still find their own offsets
-    ((64, 64, 136), 1, 2, 4, 0.003),   # more than 8192 words: scan launches
+    ((64, 64, 136), 1, 2, 4, 0.003),   # more than 8192 words: candidate list from per-chunk counts (16-word chunks)
+    ((100, 90, 61), 2, 2, 4, 0.002),   # ... 8579 words per sample: a sample starts inside a chunk
+    ((150, 130, 111), 2, 2, 4, 0.0005),  # ... over 32768 words: 256-word chunks, 33821 words per sample
     ((33, 32, 32), 2, 4, 8, 0.05),     # just over 32768 sites per sample: three-launch selection
     ((176, 176, 176), 1, 2, 4, 0.0004),  # pooled grid 88^3: more than 8192 words in the pooling's bitmap
     ((9, 8, 7), 37, 4, 24, 0.2),       # many small samples, some of them empty
