@@ -274,6 +274,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     if (nw <= kEmitMidWords && (nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256) > sb) sb = nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256;
     if (scan_blocks(w->tiles_cap) > sb) sb = scan_blocks(w->tiles_cap);
     if (scan_blocks(nwp) > sb) sb = scan_blocks(nwp);
+    if (nwp <= kEmitMidWords && (nwp + 255) / 256 > sb) sb = (nwp + 255) / 256;  // (the pooling's chunk counts)
     w->block_sums = c.take<unsigned>(sb);
     w->cand_start = c.take<int>(g.batch + 1);
     w->tile_start = c.take<int>(g.batch + 1);
@@ -898,7 +899,9 @@ void carve_pool(void* base, const Geom& g, const Geom& gp, long long rows, PoolW
     w->zero_bytes = c.total();
     w->occ_prefix = c.take<unsigned>(nw);
     w->pprefix = c.take<unsigned>(nwp);
-    w->block_sums = c.take<unsigned>(scan_blocks(nwp));
+    // (up to kEmitMidWords words the pooling keeps a count per chunk of 256 words instead of the scan's sums)
+    w->block_sums = c.take<unsigned>(nwp <= kEmitMidWords && (nwp + 255) / 256 > scan_blocks(nwp) ? (nwp + 255) / 256
+                                                                                                  : scan_blocks(nwp));
     w->pool_key = c.take<long long>(w->pool_cap);
     w->total = c.total();
 }

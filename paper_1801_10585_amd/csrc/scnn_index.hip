@@ -600,7 +600,13 @@ __global__ __launch_bounds__(256) void k_cand_emit_small(Geom g, const unsigned 
     }
     const int w0 = blockIdx.x * 256;
     unsigned below = 0;
-    for (int i = threadIdx.x; i < w0; i += 256) below += cand_count[i];
+    for (int i0 = threadIdx.x; i0 < w0; i0 += 256 * 8) {  // eight loads in flight per thread
+        unsigned x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = i0 + 256 * u < w0 ? cand_count[i0 + 256 * u] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) below += x[u];
+    }
     unsigned before_block;
     (void)block_exclusive_scan_256(below, s_wave, before_block);  // (the total is what is wanted)
     const int w = w0 + threadIdx.x;
@@ -673,7 +679,13 @@ __global__ __launch_bounds__(256) void k_cand_emit_mid(Geom g, const unsigned lo
     const int c = blockIdx.x;  // words [256 c, 256 c + 256): whole chunks (a chunk has 256 or 16 words)
     const int chunks_below = (int)(((long long)c << 8) >> chunk_shift);
     unsigned below = 0;
-    for (int i = threadIdx.x; i < chunks_below; i += 256) below += chunk_sums[i];
+    for (int i0 = threadIdx.x; i0 < chunks_below; i0 += 256 * 8) {  // eight loads in flight per thread
+        unsigned x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = i0 + 256 * u < chunks_below ? chunk_sums[i0 + 256 * u] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) below += x[u];
+    }
     unsigned before_block;
     (void)block_exclusive_scan_256(below, s_wave, before_block);  // (the total is what is wanted)
     const long long w = (long long)c * 256 + threadIdx.x;

@@ -126,7 +126,13 @@ __global__ __launch_bounds__(256) void k_pool_emit_small(const unsigned long lon
     __shared__ unsigned s_wave[4];
     const int w0 = blockIdx.x * 256;
     unsigned below = 0;
-    for (int i = threadIdx.x; i < w0; i += 256) below += (unsigned)__popcll(pbits[i]);
+    for (int i0 = threadIdx.x; i0 < w0; i0 += 256 * 8) {  // eight loads in flight per thread
+        unsigned long long x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = i0 + 256 * u < w0 ? pbits[i0 + 256 * u] : 0ull;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) below += (unsigned)__popcll(x[u]);
+    }
     unsigned before_block;
     (void)block_exclusive_scan_256(below, s_wave, before_block);
     const int w = w0 + threadIdx.x;
@@ -138,6 +144,49 @@ __global__ __launch_bounds__(256) void k_pool_emit_small(const unsigned long lon
         const int bit = __ffsll((long long)bits) - 1;
         bits &= bits - 1;
         if (o < pool_cap) pool_key[o] = (long long)w * 64 + bit;
+        ++o;
+    }
+}
+
+// Bitmaps of up to kEmitMidWords words, two launches instead of four: the candidate counts of chunks of 256 words, then
+// blocks that add up the counts of the chunks before their own (one round of loads) and scan their own 256 words.
+__global__ __launch_bounds__(256) void k_pool_count_chunks(const unsigned long long* __restrict__ pbits,
+                                                           long long n_words, unsigned* __restrict__ chunk_sums) {
+    __shared__ unsigned s_wave[4];
+    const long long w = (long long)blockIdx.x * 256 + threadIdx.x;
+    unsigned n = w < n_words ? (unsigned)__popcll(pbits[w]) : 0u;
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) n += __shfl_xor(n, d, 64);
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = n;
+    __syncthreads();
+    if (threadIdx.x == 0) chunk_sums[blockIdx.x] = s_wave[0] + s_wave[1] + s_wave[2] + s_wave[3];
+}
+
+__global__ __launch_bounds__(256) void k_pool_emit_mid(const unsigned long long* __restrict__ pbits,
+                                                       const unsigned* __restrict__ chunk_sums, long long n_words,
+                                                       long long* __restrict__ pool_key, long long pool_cap,
+                                                       Counters* ctr) {
+    __shared__ unsigned s_wave[4];
+    const int c = blockIdx.x;
+    unsigned below = 0;
+    for (int i0 = threadIdx.x; i0 < c; i0 += 256 * 8) {  // eight loads in flight per thread
+        unsigned x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = i0 + 256 * u < c ? chunk_sums[i0 + 256 * u] : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) below += x[u];
+    }
+    unsigned before_block;
+    (void)block_exclusive_scan_256(below, s_wave, before_block);
+    const long long w = (long long)c * 256 + threadIdx.x;
+    unsigned long long bits = w < n_words ? pbits[w] : 0ull;
+    unsigned block_total;
+    long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) ctr->n_pool = (long long)before_block + block_total;
+    while (bits) {
+        const int bit = __ffsll((long long)bits) - 1;
+        bits &= bits - 1;
+        if (o < pool_cap) pool_key[o] = w * 64 + bit;
         ++o;
     }
 }
@@ -233,6 +282,11 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
     if (n_words <= kEmitSmallWords) {
         hipLaunchKernelGGL(k_pool_emit_small, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, pbits,
                            (int)n_words, pool_key, pool_cap, ctr);
+    } else if (n_words <= kEmitMidWords) {  // (scan_block_sums holds at least a counter per 256 words then)
+        const unsigned chunks = (unsigned)((n_words + 255) / 256);
+        hipLaunchKernelGGL(k_pool_count_chunks, dim3(chunks), dim3(256), 0, s, pbits, n_words, scan_block_sums);
+        hipLaunchKernelGGL(k_pool_emit_mid, dim3(chunks), dim3(256), 0, s, pbits, scan_block_sums, n_words, pool_key,
+                           pool_cap, ctr);
     } else {
         e = launch_popcount(pbits, n_words, pprefix, s);
         if (e != hipSuccess) return e;

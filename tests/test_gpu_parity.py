@@ -221,6 +221,19 @@ def test_relu_and_maxpool_bit_exact(extent, batch, channels):
     assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
 
 
+@pytest.mark.parametrize("extent,batch,density", [((176, 176, 176), 1, 0.001), ((64, 64, 64), 5, 0.004),
+                                                  ((262, 258, 260), 1, 0.0005)])
+def test_maxpool_on_large_grids(extent, batch, density):
+    """Pooled bitmaps of more than 8192 words (the emit kernel still counts the words before its own by itself, up to
+    32768 words) and of more than 32768 (popcount and scan launches), several samples, odd extents."""
+    rng = np.random.default_rng(extent[0] + batch)
+    coords, feats = _random_rows(rng, extent, batch, density, 4)
+    say(f"maxpool extent={extent} B={batch} rows={coords.shape[0]}")
+    gc, gf, n = scnn.sparse_maxpool(extent, batch, dev(coords), dev(feats))
+    oc_, of_ = oracle.sparse_maxpool(extent, coords, feats)
+    assert np.array_equal(host(gc), oc_) and np.array_equal(host(gf), of_)
+
+
 def test_relu_and_pool_on_empty_input():
     c = np.zeros((0, 3), np.int32)
     f = np.zeros((0, 2), np.float32)
