@@ -270,8 +270,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cand_prefix = c.take<unsigned>(nw);
     w->pprefix = c.take<unsigned>(pool ? nwp : 0);
     long long sb = scan_blocks(nw);
-    // per-chunk candidate counts (chunks of 16 words up to 32768 words, of 256 beyond)
-    if (nw <= kEmitMidWords && (nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256) > sb) sb = nw <= 32768 ? (nw + 15) / 16 : (nw + 255) / 256;
+    if (nw <= kEmitMidWords && cand_chunk_count(nw) > sb) sb = cand_chunk_count(nw);  // per-chunk candidate counts
     if (scan_blocks(w->tiles_cap) > sb) sb = scan_blocks(w->tiles_cap);
     if (scan_blocks(nwp) > sb) sb = scan_blocks(nwp);
     if (nwp <= kEmitMidWords && (nwp + 255) / 256 > sb) sb = (nwp + 255) / 256;  // (the pooling's chunk counts)

@@ -264,6 +264,14 @@ hipError_t launch_cand_emit_small(const Geom& g, const unsigned long long* cand,
                                   int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 // up to this many words the candidate list is emitted from per-chunk counts (8192 chunks of 256 words), no scan launch
 constexpr long long kEmitMidWords = 8192 * 256;
+// Lanes that share a bitmap word in the candidate dilation: 16 on small grids, where one lane per word would leave
+// most of the chip idle behind a chain of dependent loads (below about half a wave per SIMD), 1 on large grids.  A
+// chunk, whose candidates the dilation counts, is what one workgroup of 256 threads covers per step: 16 or 256 words.
+inline int cand_dilate_lanes(long long n_words) { return n_words <= 32768 ? 16 : 1; }
+inline int cand_chunk_shift(long long n_words) { return cand_dilate_lanes(n_words) == 16 ? 4 : 8; }
+inline long long cand_chunk_count(long long n_words) {
+    return (n_words + (1ll << cand_chunk_shift(n_words)) - 1) >> cand_chunk_shift(n_words);
+}
 hipError_t launch_cand_emit_mid(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
                                 const unsigned* chunk_sums, long long n_words, unsigned* cand_lin, long long cand_cap,
                                 int* cand_start, int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
