@@ -23,7 +23,7 @@ static thread_local const char* g_last_conv_kernel = "";
 enum class ConvKernel { kValu, kPair, kQuad };
 
 // Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
-// 64 output channels with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With 16 or
+// 128 output channels (a launch per 64) with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With 16 or
 // 24 input channels the matrix cores pay only on layers of more than 1024 tiles with at least 24 output channels;
 // narrower and smaller layers are faster on the vector kernels.
 static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
@@ -292,7 +292,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->block_tap = c.take<unsigned short>((size_t)w->block_cap);
     w->wb = c.take<float>(w->block_cap ? (size_t)g.T * round_up(c_in, 32) * c_out : 0);
     w->tile_hdr = c.take<uint2>(w->block_cap ? w->tiles_cap : 0);
-    w->wq = c.take<float>(w->kernel == ConvKernel::kQuad ? (size_t)g.T * ((c_in + 31) / 32) * 2048 : 0);
+    w->wq = c.take<float>(w->kernel == ConvKernel::kQuad ? quad_groups(c_out) * quad_filter_floats(g.T, c_in) : 0);
     w->tmp_coords = c.take<int32_t>(pool ? (size_t)cand_cap * (1 + g.ndim) : 0);
     w->tmp_feats = c.take<float>(pool ? (size_t)cand_cap * c_out : 0);
     w->pool_key = c.take<long long>(pool ? w->pool_cap : 0);

@@ -105,8 +105,11 @@ template <int C_IN, int QPM, int ACC64>
 __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC64)) void k_conv_quad(
     Geom g, const unsigned long long* __restrict__ occ, const unsigned* __restrict__ occ_prefix, long long nnz_in,
     const float* __restrict__ feats, const float* __restrict__ wq, const float* __restrict__ bias, int c_out,
-    const int* __restrict__ tap_active, const unsigned* __restrict__ cand_lin, const int* __restrict__ cand_start,
-    const int* __restrict__ tile_start, Counters* __restrict__ ctr, float* __restrict__ resp) {
+    int col0, int c_out_all, const int* __restrict__ tap_active, const unsigned* __restrict__ cand_lin,
+    const int* __restrict__ cand_start, const int* __restrict__ tile_start, Counters* __restrict__ ctr,
+    float* __restrict__ resp) {
+    // c_out: the output channels of this launch (at most 64), col0 .. col0 + c_out - 1 of the layer's c_out_all; wq
+    // and bias point at this group's; the group col0 / 64 has its own tile counters
     constexpr int NCH = (C_IN + 31) / 32;        // 32-channel chunks
     constexpr int KB = 16 / QPM;                 // lanes of a quad row that hold channels
     constexpr int NS = 16 / QPM;                 // quad sets (4 * QPM sites that share their taps) per wave
@@ -147,6 +150,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
     const int xcd = blockIdx.x & 7, slot = (blockIdx.x >> 3) * kQuadWaves + wave, per_xcd = (gridDim.x >> 3) * kQuadWaves;
     const int span = (n_wt + 7) >> 3;
     const int my_end = (xcd + 1) * span < n_wt ? (xcd + 1) * span : n_wt;
+    unsigned* tickets = ctr->conv_ticket + (col0 >> 6) * 8 * kTicketStride;
 
     bool own_done = xcd * span + per_xcd >= my_end;  // nothing to draw beyond the first tiles
     for (int wt = xcd * span + slot < my_end ? xcd * span + slot : -1; wt >= 0;) {
@@ -371,7 +375,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
         // ---- next tile: ask the own span's counter now and look at the answer after the epilogue, which hides the
         //      round trip.  (Lane 0 asks; the counters sit on separate cache lines.)
         unsigned ticket = 0;
-        if (!own_done && lane == 0) ticket = atomicAdd(&ctr->conv_ticket[xcd * kTicketStride], 1u);
+        if (!own_done && lane == 0) ticket = atomicAdd(&tickets[xcd * kTicketStride], 1u);
 
         // ---- epilogue: one rounding to fp32, bias on the non-zero entries, transposition through LDS to the planar
         //      tile: a lane holds its channel's values of all sorted positions and writes them in that order (fixed
@@ -383,7 +387,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
             const float bv = (bias && col < c_out) ? bias[col] : 0.0f;
             float* tr_w = s_tr + colh + (QPM == 2 ? 4 * (HC + 1) * (lane >> 5) : 0);
             const float* tr_r = s_tr + my_pos * (HC + 1);
-            float* dst = resp + (size_t)tile * c_out * kTileRows + half * kQuadRows + lane;
+            float* dst = resp + ((size_t)tile * c_out_all + col0) * kTileRows + half * kQuadRows + lane;
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if ((col >= HC) == (h == 1)) {
@@ -429,7 +433,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
                     const int x = (xcd + d) & 7;
                     const int end_x = (x + 1) * span < n_wt ? (x + 1) * span : n_wt;
                     if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
-                    const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x * kTicketStride], 1u);
+                    const int cand = x * span + per_xcd + (int)atomicAdd(&tickets[x * kTicketStride], 1u);
                     if (cand < end_x) got = cand;
                 }
             }
@@ -442,15 +446,16 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
 bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
     if (g.T > kQuadMaxTaps) return false;
     const bool shape = (c_in == 8 || c_in == 16 || c_in == 24 || c_in == 32 || c_in == 40 || c_in == 48 || c_in == 64) &&
-                       c_out >= 1 && c_out <= 64;
+                       c_out >= 1 && c_out <= kQuadMaxCout;
     return shape && nnz_in > 0 && nnz_in * (long long)c_in * 4 < (1ll << 31);
 }
 
 template <int C_IN, int QPM, int ACC64>
 static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix,
                                      long long nnz_in, const float* feats, const float* wq, const float* bias, int c_out,
-                                     const int* tap_active, const unsigned* cand_lin, const int* cand_start,
-                                     const int* tile_start, Counters* ctr, float* resp, int cus, hipStream_t s) {
+                                     int col0, int c_out_all, const int* tap_active, const unsigned* cand_lin,
+                                     const int* cand_start, const int* tile_start, Counters* ctr, float* resp, int cus,
+                                     hipStream_t s) {
     const size_t lds = (size_t)quad_lds_words(C_IN) * 4 * kQuadWaves;
     hipError_t e = hipFuncSetAttribute((const void*)k_conv_quad<C_IN, QPM, ACC64>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -458,7 +463,8 @@ static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* oc
     // one workgroup (four waves) per SIMD wave slot of every CU; a multiple of 8: one span of tiles per XCD
     const int grid = (cus * quad_waves_per_simd(C_IN, QPM, ACC64) + 7) / 8 * 8;
     hipLaunchKernelGGL((k_conv_quad<C_IN, QPM, ACC64>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix,
-                       nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp);
+                       nnz_in, feats, wq, bias, c_out, col0, c_out_all, tap_active, cand_lin, cand_start, tile_start, ctr,
+                       resp);
     return hipGetLastError();
 }
 
@@ -469,18 +475,28 @@ hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const 
     // fp32 sums over taps for filters of at most 32 (tap, chunk) passes (a 3x3x3 filter over up to 32 channels),
     // fp64 sums beyond
     const bool acc64 = (long long)g.T * ((c_in + 31) / 32) > 32;
-#define SCNN_QUAD_ARGS g, occ, occ_prefix, nnz_in, feats, wq, bias, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp, cus, s
-#define SCNN_QUAD_CASE(CI)                                                          \
-    if (c_in == CI) {                                                               \
-        if (c_out > 32)                                                             \
-            return acc64 ? launch_conv_quad_t<CI, 1, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 1, 0>(SCNN_QUAD_ARGS); \
-        return acc64 ? launch_conv_quad_t<CI, 2, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 2, 0>(SCNN_QUAD_ARGS);     \
+    // more than 64 output channels: one launch per group of 64 (a wave's accumulators hold 64 sites x 64 channels);
+    // every group repeats the look-ups and the sort, which the wider layers' matrix work outweighs
+    for (int col0 = 0; col0 < c_out; col0 += 64) {
+        const int cg = c_out - col0 < 64 ? c_out - col0 : 64;
+        const float* wq_g = wq + (size_t)(col0 >> 6) * quad_filter_floats(g.T, c_in);
+        const float* bias_g = bias ? bias + col0 : nullptr;
+        hipError_t e = hipErrorInvalidValue;
+#define SCNN_QUAD_ARGS g, occ, occ_prefix, nnz_in, feats, wq_g, bias_g, cg, col0, c_out, tap_active, cand_lin, cand_start, tile_start, ctr, resp, cus, s
+#define SCNN_QUAD_CASE(CI)                                                                                            \
+    if (c_in == CI) {                                                                                                 \
+        if (cg > 32)                                                                                                  \
+            e = acc64 ? launch_conv_quad_t<CI, 1, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 1, 0>(SCNN_QUAD_ARGS);  \
+        else                                                                                                          \
+            e = acc64 ? launch_conv_quad_t<CI, 2, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 2, 0>(SCNN_QUAD_ARGS);  \
     }
-    SCNN_QUAD_CASE(8) SCNN_QUAD_CASE(16) SCNN_QUAD_CASE(24) SCNN_QUAD_CASE(32) SCNN_QUAD_CASE(40) SCNN_QUAD_CASE(48)
-    SCNN_QUAD_CASE(64)
+        SCNN_QUAD_CASE(8) SCNN_QUAD_CASE(16) SCNN_QUAD_CASE(24) SCNN_QUAD_CASE(32) SCNN_QUAD_CASE(40) SCNN_QUAD_CASE(48)
+        SCNN_QUAD_CASE(64)
 #undef SCNN_QUAD_CASE
 #undef SCNN_QUAD_ARGS
-    return hipErrorInvalidValue;
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace scnn

@@ -271,14 +271,20 @@ __global__ __launch_bounds__(256) void k_prepare(Geom g, const float* __restrict
     if (wq) {
         // operand order of the quad kernel: [tap][32-channel chunk][channel / 4][lane][channel % 4], lane = output
         // channel (modulo 32 when there are at most 32 of them); channels and columns past the real ones are zero
-        const int nch = (c_in + 31) / 32, cols = c_out > 32 ? 64 : 32;
+        // With more than 64 output channels: one such filter per group of 64, one after the other.
+        const int nch = (c_in + 31) / 32;
         const int n = nch * 2048;
-        for (int i = threadIdx.x; i < n; i += blockDim.x) {
-            const int e = i & 3, lane = (i >> 2) & 63, j = (i >> 8) & 7, c = i >> 11;
-            const int ic = c * 32 + 4 * j + e, oc = lane & (cols - 1);
-            const float v = (ic < c_in && oc < c_out) ? filter_at(w, g.T, c_in, c_out, adjoint, t, ic, oc) : 0.0f;
-            wq[(size_t)t * n + i] = v;
-            any |= (v != 0.0f);
+        for (int col0 = 0; col0 < c_out; col0 += 64) {
+            const int cg = c_out - col0 < 64 ? c_out - col0 : 64, cols = cg > 32 ? 64 : 32;
+            float* wq_g = wq + (size_t)(col0 >> 6) * quad_filter_floats(g.T, c_in);
+            for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                const int e = i & 3, lane = (i >> 2) & 63, j = (i >> 8) & 7, c = i >> 11;
+                const int ic = c * 32 + 4 * j + e, oc = lane & (cols - 1);
+                const float v =
+                    (ic < c_in && oc < cg) ? filter_at(w, g.T, c_in, c_out, adjoint, t, ic, col0 + oc) : 0.0f;
+                wq_g[(size_t)t * n + i] = v;
+                any |= (v != 0.0f);
+            }
         }
     } else if (wb) {
         // C_in = 16 is laid out like one 32-channel chunk: a lane's first four values are channels 4 gq .. 4 gq + 3,

@@ -59,7 +59,8 @@ struct Counters {
     unsigned cols_done;       // columns whose selection has ended
     // tiles handed out so far in each of the contraction kernels' eight tile spans; one counter per 128-byte line:
     // read-modify-writes on one line are served one after the other, whichever word they address
-    unsigned conv_ticket[8 * kTicketStride];
+    // (two sets: the quad kernel runs once per group of 64 output channels, up to two groups)
+    unsigned conv_ticket[2 * 8 * kTicketStride];
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
@@ -299,6 +300,10 @@ hipError_t launch_conv_mfma(const Geom& g, long long nnz_in, const float* feats,
                             const uint2* tile_hdr, Counters* ctr, float* resp, hipStream_t s);
 
 // scnn_conv_quad.hip
+constexpr int kQuadMaxCout = 128;  // two groups of 64 output channels, one launch each
+// floats of the quad kernel's filter per group of 64 output channels: [tap][32-channel chunk][2048]
+__host__ __device__ inline size_t quad_filter_floats(int taps, int c_in) { return (size_t)taps * ((c_in + 31) / 32) * 2048; }
+inline int quad_groups(int c_out) { return (c_out + 63) / 64; }
 bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in);
 hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const unsigned* occ_prefix, long long nnz_in,
                             const float* feats, int c_in, const float* wq, int c_out, const float* bias,

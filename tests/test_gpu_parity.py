@@ -297,6 +297,12 @@ MFMA_CASES = [
     ((20, 20, 20), 1, 64, 17, (3, 1, 3), 0.1, 1.0),
     ((36, 36), 3, 40, 64, (5, 5), 0.12, 0.6),
     ((150, 3, 3), 1, 32, 64, (3, 3, 3), 0.3, 1.0),
+    # more than 64 output channels: the quad kernel runs once per group of 64 (a full and a partial group, partial
+    # groups of at most and of more than 32 channels)
+    ((16, 16, 16), 2, 32, 128, (3, 3, 3), 0.07, 1.0),
+    ((16, 16, 16), 1, 24, 96, (3, 3, 3), 0.08, 0.7),
+    ((14, 14, 14), 2, 64, 80, (3, 3, 3), 0.08, 1.0),
+    ((30, 30), 2, 16, 100, (3, 3), 0.2, 1.0),
 ]
 
 
@@ -310,7 +316,7 @@ def test_layer_wide_channels_both_kernels(case, path):
     feats *= rng.random(feats.shape) < 0.9
     feats = np.ascontiguousarray(feats.astype(np.float32))
     w = make_filter(rng, ksize, c_in, c_out, fdens, 0.2)
-    bias = rng.normal(size=c_out).astype(np.float32) if c_out == 32 else None
+    bias = rng.normal(size=c_out).astype(np.float32) if c_out in (32, 96) else None
     n = int(np.prod(extent))
     scnn.set_conv_path(path)
     try:
@@ -329,7 +335,7 @@ def test_matrix_core_kernels_are_exact_on_integer_data_and_repeatable():
     have a fixed order (all but the pair-list kernel)."""
     rng = np.random.default_rng(123)
     for (extent, batch, c_in, c_out, ksize) in (((22, 22, 22), 2, 32, 64, (3, 3, 3)), ((20, 20, 20), 2, 64, 32, (3, 3, 3)),
-                                                ((20, 20, 20), 1, 24, 24, (3, 3, 3))):
+                                                ((20, 20, 20), 1, 24, 24, (3, 3, 3)), ((18, 18, 18), 2, 32, 100, (3, 3, 3))):
         coords = random_sparse_sites(rng, extent, batch, 0.08)
         feats = rng.integers(-3, 4, size=(coords.shape[0], c_in)).astype(np.float32)
         w = rng.integers(-2, 3, size=(int(np.prod(ksize)), c_in, c_out)).astype(np.float32)
