@@ -258,7 +258,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->pbits = c.take<unsigned long long>(pool ? nwp : 0);
     w->occ_sel = c.take<unsigned long long>(pool ? nw : 0);  // occupancy of the selected rows, for the pooling
     // rows known to survive are marked during the selection when the streaming compaction kernel can use them
-    const bool marks = !topk_small_columns(g) && c_out > 32 && c_out <= 64;
+    const bool marks = !topk_small_columns(g) && c_out > kMarkMinChannels && c_out <= kMarkPlanes;
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();
@@ -429,7 +429,7 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
         g_last_conv_kernel = "k_conv_valu";
     }
     timer.mark();
-    const bool marks = !topk_small_columns(g) && c_out > 32 && c_out <= 64 && k > 0;
+    const bool marks = !topk_small_columns(g) && c_out > kMarkMinChannels && c_out <= kMarkPlanes && k > 0;
     SCNN_TRY(launch_topk(g, c_out, k, topk_mode, relu, ws.tile_start, ws.resp, ws.cols, ws.side, ws.part,
                          marks ? ws.row_keep : nullptr, marks ? ws.row_plane : nullptr, marks ? ws.tile_base : nullptr,
                          ws.tiles_cap, ws.ctr, s));
@@ -695,7 +695,7 @@ void carve_topk(void* base, const Geom& g, long long rows, int channels, TopkWs*
     const long long ncols = (long long)g.batch * channels;
     w->tiles_cap = (rows + kTileRows - 1) / kTileRows + g.batch;
     w->ctr = c.take<Counters>(1);
-    w->marks = !topk_small_columns(g) && channels > 32 && channels <= 64;
+    w->marks = !topk_small_columns(g) && channels > kMarkMinChannels && channels <= kMarkPlanes;
     w->cols = c.take<ColState>(ncols);
     w->tile_state = c.take<unsigned long long>(w->tiles_cap);
     w->zero_bytes = c.total();

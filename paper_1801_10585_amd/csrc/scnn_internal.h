@@ -352,6 +352,9 @@ bool topk_small_columns(const Geom& g);
 // at which tile t starts, unless ctr->bracket_failed is set; launch_select_write must then be given tile_base.
 constexpr int kTopkPartWords = 256;  // slices of a column at most
 constexpr int kMarkPlanes = 64;  // one per channel where marks are used (up to 64 channels)
+// Marks pay from 17 channels on: with fewer, few rows are marked by some channel's strong response and nearly every
+// surviving entry of a bracket costs the settling pass an atomic.
+constexpr int kMarkMinChannels = 16;
 hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int relu, const int* tile_start,
                        const float* resp, ColState* cols, uint2* side,
                        uint2* part /* kTopkPartWords entries per column */, unsigned long long* row_keep,

@@ -1537,7 +1537,7 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
     if (channels <= 4) SCNN_NARROW_CASE(4, 8);
     else if (channels <= 8) SCNN_NARROW_CASE(8, 8);
     else if (channels <= 16) SCNN_NARROW_CASE(16, 8);
-    else if (channels <= 32) SCNN_NARROW_CASE(32, 4);
+    else if (channels <= 32 && !tile_base) SCNN_NARROW_CASE(32, 4);  // (with tile_base: the streaming kernel below)
     else if (channels <= 64) {
         // (streaming: four workgroups per CU; by look-back three measured best, and four cost it 5 %, which only the
         // rare launch that was given tile_base and cannot use it pays)

@@ -93,13 +93,14 @@ def test_vector_convolution_regimes(case):
 
 
 # Long columns (more than 32768 sites per sample): the selection brackets the k-th key from every S-th tile of 128
-# rows, S = ceil(tiles / 128); the compaction streams for 33..64 channels and looks back otherwise; the settling pass
+# rows, S = ceil(tiles / 128); the compaction streams for 17..64 channels and looks back otherwise; the settling pass
 # holds up to 20480 bracket entries of a column in registers.  Row counts on both sides of S = 1 / 2, channel counts
-# on both sides of 33 and 64, and few distinct values, which put far more than 20480 equal scores into the bracket.
+# on both sides of 17, 33 and 64, and few distinct values, which put far more than 20480 equal scores into the bracket.
 SELECTION_REGIMES = [
     # rows per sample, channels, levels (None: normal values)
     (128 * 128, 40, None), (128 * 128 + 1, 40, None), (129 * 128, 33, 40), (300 * 128 + 77, 32, None),
     (300 * 128 + 77, 64, 2), (300 * 128 + 77, 65, None), (40000, 48, 2), (40000, 8, 2),
+    (129 * 128, 16, None), (40000, 17, 2), (129 * 128 + 5, 24, 3),
 ]
 
 
@@ -170,10 +171,10 @@ def test_selection_random_long_columns(seed):
 
 
 # Whole layers whose columns are long and whose channel counts take the row-marking selection with the streaming
-# compaction (33..64 output channels), with the quad, the pair-list and the vector convolution in front of it.
+# compaction (17..64 output channels), with the quad, the pair-list and the vector convolution in front of it.
 WIDE_LONG = [
     ((40, 40, 40), 2, 32, 40, 0.08), ((36, 36, 36), 1, 16, 64, 0.10), ((48, 40, 36), 2, 8, 33, 0.06),
-    ((40, 40, 40), 1, 64, 48, 0.05),
+    ((40, 40, 40), 1, 64, 48, 0.05), ((40, 40, 40), 2, 8, 17, 0.08), ((36, 40, 44), 1, 24, 24, 0.10),
 ]
 
 
