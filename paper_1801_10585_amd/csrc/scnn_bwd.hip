@@ -50,13 +50,9 @@ __global__ __launch_bounds__(256) void k_bwd_sites(Geom g, const int32_t* __rest
         }
         cand_lin[r] = lin;
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
-        int acc16 = 0;
-        for (int b = 0; b < g.batch; ++b) {
-            rows16_start[b] = acc16;
-            acc16 += (cand_start[b + 1] - cand_start[b] + 15) / 16;
-        }
-        rows16_start[g.batch] = acc16;
+    if (blockIdx.x == 0) {  // (whole block)
+        __shared__ unsigned s_wave[4];
+        (void)sample_ranges_256(g.batch, cand_start, nullptr, rows16_start, s_wave);
     }
 }
 

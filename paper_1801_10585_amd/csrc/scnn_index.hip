@@ -510,6 +510,7 @@ __global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long l
                                                    unsigned* __restrict__ cand_lin, long long cand_cap,
                                                    int* __restrict__ cand_start, int* __restrict__ tile_start,
                                                    int* __restrict__ rows16_start, Counters* ctr) {
+    __shared__ unsigned s_wave[4];
     if (blockIdx.x == gridDim.x - 1) {
         const long long n_cand = ctr->n_cand;  // written by the scan
         const bool overflow = n_cand > cand_cap;
@@ -519,18 +520,9 @@ __global__ __launch_bounds__(256) void k_cand_emit(Geom g, const unsigned long l
             cand_start[b] = v;
         }
         __syncthreads();
+        const int n_tiles_all = sample_ranges_256(g.batch, cand_start, tile_start, rows16_start, s_wave);
         if (threadIdx.x == 0) {
-            int acc = 0, acc16 = 0;
-            for (int b = 0; b < g.batch; ++b) {
-                tile_start[b] = acc;
-                rows16_start[b] = acc16;
-                const int n = cand_start[b + 1] - cand_start[b];
-                acc += (n + kTileRows - 1) / kTileRows;
-                acc16 += (n + 15) / 16;
-            }
-            tile_start[g.batch] = acc;
-            rows16_start[g.batch] = acc16;
-            ctr->n_tiles = acc;
+            ctr->n_tiles = n_tiles_all;
             if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
         }
         return;
@@ -587,19 +579,10 @@ __global__ __launch_bounds__(256) void k_cand_emit_small(Geom g, const unsigned 
             for (int b = threadIdx.x; b < g.batch; b += blockDim.x) cand_start[b] = 0;
         if (threadIdx.x == 0) cand_start[g.batch] = overflow ? 0 : (int)n_cand;
         __syncthreads();
+        const int n_tiles_all = sample_ranges_256(g.batch, cand_start, tile_start, rows16_start, s_wave);
         if (threadIdx.x == 0) {
-            int acc = 0, acc16 = 0;
-            for (int b = 0; b < g.batch; ++b) {
-                tile_start[b] = acc;
-                rows16_start[b] = acc16;
-                const int n = cand_start[b + 1] - cand_start[b];
-                acc += (n + kTileRows - 1) / kTileRows;
-                acc16 += (n + 15) / 16;
-            }
-            tile_start[g.batch] = acc;
-            rows16_start[g.batch] = acc16;
             ctr->n_cand = n_cand;
-            ctr->n_tiles = acc;
+            ctr->n_tiles = n_tiles_all;
             if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
         }
         return;
@@ -642,22 +625,38 @@ __global__ __launch_bounds__(256) void k_cand_emit_mid(Geom g, const unsigned lo
                                                        int* __restrict__ rows16_start, Counters* ctr) {
     __shared__ unsigned s_wave[4];
     __shared__ unsigned long long s_total;
+    __shared__ unsigned s_pref[kEmitMidChunks + 1];  // (last block) candidates in the chunks before chunk i
     if (blockIdx.x == gridDim.x - 1) {
+        // exclusive scan of the chunk counts: a thread takes `per` consecutive chunks
+        const int n_chunks = (int)((n_words + (1ll << chunk_shift) - 1) >> chunk_shift);  // (<= kEmitMidChunks)
+        const int per = (n_chunks + 255) / 256, i_lo = (int)threadIdx.x * per;
+        unsigned local = 0;
+        for (int i = i_lo; i < i_lo + per && i < n_chunks; ++i) local += chunk_sums[i];
+        unsigned total;
+        unsigned run = block_exclusive_scan_256(local, s_wave, total);
+        for (int i = i_lo; i < i_lo + per && i < n_chunks; ++i) {
+            s_pref[i] = run;
+            run += chunk_sums[i];
+        }
+        if (threadIdx.x == 0) {
+            s_pref[n_chunks] = total;
+            s_total = total;
+        }
+        __syncthreads();
         // candidates before sample b = chunks wholly before its first word + the words of the chunk it starts in
-        for (int b = threadIdx.x >> 6; b <= g.batch; b += 4) {
+        for (int b = threadIdx.x; b <= g.batch; b += 256) {
             const long long w_b = (long long)b * g.Wps;  // (= n_words for b = batch)
             const int c_b = (int)(w_b >> chunk_shift);
-            unsigned long long sum = 0;
-            for (int i = threadIdx.x & 63; i < c_b; i += 64) sum += chunk_sums[i];
-            for (long long w = ((long long)c_b << chunk_shift) + (threadIdx.x & 63); w < w_b; w += 64)
-                sum += cand_count[w];
+            unsigned sum = s_pref[c_b];
+            for (long long w0 = (long long)c_b << chunk_shift; w0 < w_b; w0 += 8) {  // eight loads in flight
+                unsigned x[8];
 #pragma unroll
-            for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
-            if ((threadIdx.x & 63) == 0) {
-                if (b == g.batch) s_total = sum;
-                // (a total beyond the capacity is far below 2^31: at most 2^31 sites per call)
-                cand_start[b] = (int)sum;
+                for (int u = 0; u < 8; ++u) x[u] = w0 + u < w_b ? cand_count[w0 + u] : 0u;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) sum += x[u];
             }
+            // (a total beyond the capacity is far below 2^31: at most 2^31 sites per call)
+            cand_start[b] = (int)sum;
         }
         __syncthreads();
         const long long n_cand = (long long)s_total;
@@ -665,19 +664,10 @@ __global__ __launch_bounds__(256) void k_cand_emit_mid(Geom g, const unsigned lo
         if (overflow)
             for (int b = threadIdx.x; b <= g.batch; b += blockDim.x) cand_start[b] = 0;
         __syncthreads();
+        const int n_tiles_all = sample_ranges_256(g.batch, cand_start, tile_start, rows16_start, s_wave);
         if (threadIdx.x == 0) {
-            int acc = 0, acc16 = 0;
-            for (int b = 0; b < g.batch; ++b) {
-                tile_start[b] = acc;
-                rows16_start[b] = acc16;
-                const int n = cand_start[b + 1] - cand_start[b];
-                acc += (n + kTileRows - 1) / kTileRows;
-                acc16 += (n + 15) / 16;
-            }
-            tile_start[g.batch] = acc;
-            rows16_start[g.batch] = acc16;
             ctr->n_cand = n_cand;
-            ctr->n_tiles = acc;
+            ctr->n_tiles = n_tiles_all;
             if (overflow) atomicOr(&ctr->flags, SCNN_FLAG_CAND_OVERFLOW);
         }
         return;

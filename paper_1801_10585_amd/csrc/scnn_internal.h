@@ -221,6 +221,35 @@ __device__ inline unsigned block_exclusive_scan_256(unsigned v, unsigned* s_wave
     return base + inc - v;
 }
 
+// Per-sample tile ranges and 16-row group ranges from the per-sample candidate ranges (cand_start[0 .. batch], in
+// global memory and visible to the block): tile_start[b] = tiles of all earlier samples, each sample rounded up to
+// whole tiles; rows16_start likewise in groups of 16 rows.  Either output may be null.  Returns the number of tiles.
+// A scan over the samples, 256 at a time, so that batches of thousands of small samples cost a few rounds rather
+// than one thread's walk over all of them.  Contains __syncthreads(): whole block of 256 threads.
+__device__ inline int sample_ranges_256(int batch, const int* cand_start, int* tile_start, int* rows16_start,
+                                        unsigned* s_wave /*[4], shared*/) {
+    unsigned carry_t = 0, carry_r = 0;
+    for (int b0 = 0; b0 < batch; b0 += 256) {
+        const int b = b0 + (int)threadIdx.x;
+        const int n = b < batch ? cand_start[b + 1] - cand_start[b] : 0;
+        const unsigned t = (unsigned)((n + kTileRows - 1) / kTileRows), r = (unsigned)((n + 15) / 16);
+        unsigned tot_t, tot_r;
+        const unsigned et = block_exclusive_scan_256(t, s_wave, tot_t);
+        const unsigned er = block_exclusive_scan_256(r, s_wave, tot_r);
+        if (b < batch) {
+            if (tile_start) tile_start[b] = (int)(carry_t + et);
+            if (rows16_start) rows16_start[b] = (int)(carry_r + er);
+        }
+        carry_t += tot_t;
+        carry_r += tot_r;
+    }
+    if (threadIdx.x == 0) {
+        if (tile_start) tile_start[batch] = (int)carry_t;
+        if (rows16_start) rows16_start[batch] = (int)carry_r;
+    }
+    return (int)carry_t;
+}
+
 // ---- host-side launchers (one per kernel family), all asynchronous on `s` ----
 struct ScanBufs {
     unsigned* block_sums;  // ceil(capacity / kScanChunk) + 1 entries
@@ -264,7 +293,8 @@ hipError_t launch_cand_emit_small(const Geom& g, const unsigned long long* cand,
                                   long long n_words, unsigned* cand_lin, long long cand_cap, int* cand_start,
                                   int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s);
 // up to this many words the candidate list is emitted from per-chunk counts (8192 chunks of 256 words), no scan launch
-constexpr long long kEmitMidWords = 8192 * 256;
+constexpr int kEmitMidChunks = 8192;
+constexpr long long kEmitMidWords = (long long)kEmitMidChunks * 256;
 // Lanes that share a bitmap word in the candidate dilation: 16 on small grids, where one lane per word would leave
 // most of the chip idle behind a chain of dependent loads (below about half a wave per SIMD), 1 on large grids.  A
 // chunk, whose candidates the dilation counts, is what one workgroup of 256 threads covers per step: 16 or 256 words.

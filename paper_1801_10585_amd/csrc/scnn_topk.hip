@@ -47,14 +47,10 @@ __global__ __launch_bounds__(256) void k_rows_sample_bounds(Geom g, const int32_
         cand_start[b] = (int)lo;
     }
     __syncthreads();
+    __shared__ unsigned s_wave[4];
+    const int n_tiles = sample_ranges_256(g.batch, cand_start, tile_start, nullptr, s_wave);
     if (threadIdx.x == 0) {
-        int acc = 0;
-        for (int b = 0; b < g.batch; ++b) {
-            tile_start[b] = acc;
-            acc += (cand_start[b + 1] - cand_start[b] + kTileRows - 1) / kTileRows;
-        }
-        tile_start[g.batch] = acc;
-        ctr->n_tiles = acc;
+        ctr->n_tiles = n_tiles;
         ctr->n_cand = rows;
     }
 }
@@ -857,6 +853,89 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
     }
 }
 
+// The same for columns of at most 1024 positions (eight tiles: 2-D grids up to 32 x 32, 3-D up to 10^3), one WAVE
+// per column and no shared memory: batches of thousands of such samples (a batch of small images) have thousands
+// of columns, and a workgroup of 1024 threads with five passes over a 2048-bin histogram costs each of them about
+// 10 us.  The k-th strongest key is found bit by bit, from the top: with the bits above already fixed, the keys
+// that have the next bit set are counted (a ballot per register); the tie cut is the position of the q-th equal key
+// in position order.
+constexpr int kTinyPerLane = 16;
+constexpr long long kTinyColumn = 64 * kTinyPerLane;  // positions of a column at most
+
+__global__ __launch_bounds__(256) void k_select_tiny(int mode, int channels, int ncols,
+                                                     const int* __restrict__ tile_start,
+                                                     const float* __restrict__ resp, long long k,
+                                                     ColState* __restrict__ cols) {
+    const int lane = threadIdx.x & 63;
+    const int col = (int)blockIdx.x * 4 + (int)(threadIdx.x >> 6);
+    if (col >= ncols) return;  // (whole waves)
+    const int b = col / channels, oc = col - b * channels;
+    const int t0 = tile_start[b], t1 = tile_start[b + 1];
+    const unsigned n = (unsigned)(t1 - t0) * kTileRows;  // positions of the column (<= kTinyColumn, see the launcher)
+    // key u of the lane sits at position u * 64 + lane
+    unsigned key[kTinyPerLane];
+    unsigned n_nz = 0;
+#pragma unroll
+    for (int u = 0; u < kTinyPerLane; ++u) {
+        const unsigned i = (unsigned)u * 64u + (unsigned)lane;
+        key[u] = 0u;
+        if (i < n)
+            key[u] = score_key(resp[((size_t)(t0 + (int)(i >> 7)) * channels + oc) * kTileRows + (i & 127u)], mode);
+        n_nz += (unsigned)__popcll(__ballot(key[u] != 0u));
+    }
+    ColState st;
+    st.tau = 0; st.cut = 0xffffffffu; st.n_eq = 0; st.q = 0; st.tau_lo = 0; st.tau_hi = 0; st.n_nz = n_nz;
+    st.n_above = 0; st.side_fill = 0; st.done = 1; st.side_off = 0;
+    if (k <= 0) st.tau = 0xffffffffu;  // no key is stronger: nothing survives
+    if (k <= 0 || (long long)n_nz <= k) {  // or fewer entries than k: all survive (tau = 0)
+        if (lane == 0) cols[col] = st;
+        return;
+    }
+    // 1 <= k < n_nz: the k-th strongest key is non-zero
+    unsigned prefix = 0, k_rem = (unsigned)k;
+    for (int bit = 31; bit >= 0; --bit) {
+        const unsigned want = (prefix >> bit) | 1u;  // the bits from `bit` up of a key with this bit set
+        unsigned cnt = 0;
+#pragma unroll
+        for (int u = 0; u < kTinyPerLane; ++u) cnt += (unsigned)__popcll(__ballot((key[u] >> bit) == want));
+        if (cnt >= k_rem) prefix |= 1u << bit;  // the k-th strongest has the bit
+        else k_rem -= cnt;                      // it lies below the cnt keys that have it
+    }
+    const unsigned tau = prefix;
+    unsigned n_eq = 0;
+#pragma unroll
+    for (int u = 0; u < kTinyPerLane; ++u) n_eq += (unsigned)__popcll(__ballot(key[u] == tau));
+    const unsigned q = k_rem;  // 1 <= q <= n_eq: the entries equal to tau that survive, those of lowest position
+    unsigned cut = 0xffffffffu;
+    if (q < n_eq) {
+        unsigned left = q;
+#pragma unroll
+        for (int u = 0; u < kTinyPerLane; ++u) {
+            const unsigned long long m = __ballot(key[u] == tau);
+            const unsigned c = (unsigned)__popcll(m);
+            if (left >= 1u && left <= c) {  // (uniform) the q-th equal key is in this register: the lane of rank `left`
+                const unsigned long long hit =
+                    __ballot(key[u] == tau && (unsigned)__popcll(m & ((1ull << lane) - 1ull)) + 1u == left);
+                cut = (unsigned)u * 64u + (unsigned)(__ffsll((long long)hit) - 1);
+                left = 0u;
+            } else if (left > c) {
+                left -= c;
+            }
+        }
+    }
+    if (lane == 0) {
+        st.tau = tau;
+        st.n_eq = n_eq;
+        st.q = q;
+        st.cut = cut;
+        cols[col] = st;
+    }
+}
+
+static bool topk_tiny_columns(const Geom& g) {
+    return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kTinyColumn;
+}
+
 bool topk_small_columns(const Geom& g) {
     return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kSmallColumn;
 }
@@ -888,6 +967,11 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int r
                        hipStream_t s) {
     const int ncols = g.batch * channels;
     if (ncols <= 0) return hipSuccess;
+    if (topk_tiny_columns(g)) {
+        hipLaunchKernelGGL(k_select_tiny, dim3((unsigned)((ncols + 3) / 4)), dim3(256), 0, s, mode, channels, ncols,
+                           tile_start, resp, k, cols);
+        return hipGetLastError();
+    }
     if (topk_small_columns(g)) {
         hipLaunchKernelGGL(k_select_small, dim3(ncols), dim3(kSmallThreads), 0, s, mode, channels, tile_start, resp, k,
                            cols);

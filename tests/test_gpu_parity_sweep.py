@@ -73,6 +73,8 @@ REGIMES = [
     ((33, 32, 32), 2, 4, 8, 0.05),     # just over 32768 sites per sample: three-launch selection
     ((176, 176, 176), 1, 2, 4, 0.0004),  # pooled grid 88^3: more than 8192 words in the pooling's bitmap
     ((9, 8, 7), 37, 4, 24, 0.2),       # many small samples, some of them empty
+    ((28, 28), 300, 1, 8, 0.19),       # a batch of small images: per-sample ranges by a scan over the samples
+    ((28, 28), 1100, 1, 3, 0.1),       # ... more than 8192 bitmap words of 13-word samples (a sample starts inside a chunk)
 ]
 
 
@@ -84,11 +86,12 @@ def test_vector_convolution_regimes(case):
     if batch > 8:  # every fifth sample without rows
         coords = np.ascontiguousarray(coords[coords[:, 0] % 5 != 2])
     feats = np.ascontiguousarray(rng.normal(size=(coords.shape[0], c_in)).astype(np.float32))
-    w = make_filter(rng, (3, 3, 3), c_in, c_out, 0.8, 0.3)
+    ksize = (3,) * len(extent)
+    w = make_filter(rng, ksize, c_in, c_out, 0.8, 0.3)
     n = int(np.prod(extent))
     k = scnn.k_from_rho(0.1, n)
     say(f"regime extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} k={k}")
-    check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, None, k, 0.1, scnn.ABS,
+    check_conv_against_oracle(extent, batch, coords, feats, ksize, w, None, k, 0.1, scnn.ABS,
                               columns=_sampled_columns(rng, batch, c_out, 4), tag=f"regime {extent}")
 
 
