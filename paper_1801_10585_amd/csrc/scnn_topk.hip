@@ -858,10 +858,13 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
 // of columns, and a workgroup of 1024 threads with five passes over a 2048-bin histogram costs each of them about
 // 10 us.  The k-th strongest key is found bit by bit, from the top: with the bits above already fixed, the keys
 // that have the next bit set are counted (a ballot per register); the tie cut is the position of the q-th equal key
-// in position order.
-constexpr int kTinyPerLane = 16;
-constexpr long long kTinyColumn = 64 * kTinyPerLane;  // positions of a column at most
+// in position order.  kTinyPerLane = 64 (columns of up to 4096 positions: 16^3 grids) is used when there are more
+// than a thousand columns; with few columns a workgroup per column is as fast.
+constexpr long long kTinyColumn = 64 * 16;   // positions of a column at most, 16 keys per lane
+constexpr long long kTinyColumn64 = 64 * 64;  // ... 64 keys per lane
+constexpr int kTinyManyColumns = 1024;
 
+template <int kTinyPerLane>
 __global__ __launch_bounds__(256) void k_select_tiny(int mode, int channels, int ncols,
                                                      const int* __restrict__ tile_start,
                                                      const float* __restrict__ resp, long long k,
@@ -871,7 +874,7 @@ __global__ __launch_bounds__(256) void k_select_tiny(int mode, int channels, int
     if (col >= ncols) return;  // (whole waves)
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
-    const unsigned n = (unsigned)(t1 - t0) * kTileRows;  // positions of the column (<= kTinyColumn, see the launcher)
+    const unsigned n = (unsigned)(t1 - t0) * kTileRows;  // positions of the column (<= 64 kTinyPerLane, see the launcher)
     // key u of the lane sits at position u * 64 + lane
     unsigned key[kTinyPerLane];
     unsigned n_nz = 0;
@@ -932,9 +935,7 @@ __global__ __launch_bounds__(256) void k_select_tiny(int mode, int channels, int
     }
 }
 
-static bool topk_tiny_columns(const Geom& g) {
-    return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kTinyColumn;
-}
+static long long column_positions(const Geom& g) { return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows; }
 
 bool topk_small_columns(const Geom& g) {
     return (long long)((g.N + kTileRows - 1) / kTileRows) * kTileRows <= kSmallColumn;
@@ -967,8 +968,13 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int r
                        hipStream_t s) {
     const int ncols = g.batch * channels;
     if (ncols <= 0) return hipSuccess;
-    if (topk_tiny_columns(g)) {
-        hipLaunchKernelGGL(k_select_tiny, dim3((unsigned)((ncols + 3) / 4)), dim3(256), 0, s, mode, channels, ncols,
+    if (column_positions(g) <= kTinyColumn) {
+        hipLaunchKernelGGL(k_select_tiny<16>, dim3((unsigned)((ncols + 3) / 4)), dim3(256), 0, s, mode, channels, ncols,
+                           tile_start, resp, k, cols);
+        return hipGetLastError();
+    }
+    if (column_positions(g) <= kTinyColumn64 && ncols >= kTinyManyColumns) {
+        hipLaunchKernelGGL(k_select_tiny<64>, dim3((unsigned)((ncols + 3) / 4)), dim3(256), 0, s, mode, channels, ncols,
                            tile_start, resp, k, cols);
         return hipGetLastError();
     }
