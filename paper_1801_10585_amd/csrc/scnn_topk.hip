@@ -596,6 +596,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
     __shared__ int s_res[4];
     __shared__ uint2 s_part[4];
     __shared__ uint2 s_more[kSettleLds];
+    __shared__ unsigned s_cnt;
     const int col = blockIdx.x;
     const int b = col / channels, oc = col - b * channels;
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
@@ -631,6 +632,16 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
             for (unsigned i = kSettleRegs + threadIdx.x; i < m; i += kSideThreads) s_more[i - kSettleRegs] = e(i);
             __syncthreads();
         }
+        // the row of a surviving entry of the bracket is marked unless some channel has marked it already
+        auto word_of = [&](uint2 x) { return row_keep + 2 * (size_t)(t0 + (int)(x.y >> 7)) + ((x.y >> 6) & 1u); };
+        auto mark = [&](uint2 x, unsigned long long have) {
+            const unsigned long long bit = 1ull << (x.y & 63u);
+            if (have & bit) return;
+            if (relu && !(col0[(size_t)(x.y >> 7) * pitch + (x.y & 127u)] > 0.0f)) return;
+            atomicOr(word_of(x), bit);
+        };
+        unsigned m_eff = m;        // the entries the marking below runs over, and whether they are the cached ones
+        bool cached_eff = cached;
         bool held;  // the side buffer decides the column
         if ((long long)st.n_nz <= k) {
             // fewer entries than k: all survive (tau = 0, every non-zero key is above it); the rows are all marked if
@@ -640,7 +651,74 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
         } else {
             const long long k_rem = k - (long long)st.n_above;
             held = k_rem >= 1 && k_rem <= (long long)m;
-            if (held)
+            bool settled = false;
+            if (held && !cached) {
+                // A bracket too long to cache (few, very long columns): read it twice instead of once per digit.
+                // First the histogram of the leading digit; then, with the k-th key's bin known, the entries of that
+                // bin go to LDS and the entries above it, which survive whatever the rest of the key, mark their
+                // rows; the remaining digits and the tie cut are settled on the cached bin.
+                const unsigned span = st.tau_hi - st.tau_lo;
+                const int nb = span ? 32 - __clz(span) : 1;
+                const int w = nb < 11 ? nb : 11, shift = nb - w;
+                const unsigned lo = st.tau_lo;
+                auto digit = [=](uint2 x) { return ((x.x - lo) >> shift) & ((1u << w) - 1u); };
+                for (int i = threadIdx.x; i < kHistBins; i += kSideThreads) s_h[i] = 0;
+                if (threadIdx.x == 0) s_cnt = 0;
+                __syncthreads();
+                for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // eight entries in flight per thread
+                    uint2 x[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        const unsigned i = i0 + (unsigned)kSideThreads * u;
+                        x[u] = i < m ? e(i) : make_uint2(0u, 0u);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (x[u].x != 0u) atomicAdd(&s_h[digit(x[u])], 1u);
+                }
+                __syncthreads();
+                int bin;
+                unsigned before;
+                block_pick(s_h, k_rem, true, s_wave, s_res + 2, bin, before);
+                const unsigned in_bin = s_h[bin];
+                if (in_bin <= kSettleLds) {  // (uniform)
+                    for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {
+                        uint2 x[8];
+                        unsigned long long have[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const unsigned i = i0 + (unsigned)kSideThreads * u;
+                            x[u] = i < m ? e(i) : make_uint2(0u, 0u);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            have[u] = ~0ull;
+                            if (row_keep && x[u].x != 0u && (int)digit(x[u]) > bin)
+                                have[u] = __hip_atomic_load(word_of(x[u]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            if (x[u].x == 0u) continue;
+                            const int d = (int)digit(x[u]);
+                            if (d == bin) s_more[atomicAdd(&s_cnt, 1u)] = x[u];
+                            else if (row_keep && d > bin) mark(x[u], have[u]);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kSettleCached; ++u) kept[u] = make_uint2(0u, 0u);
+                    __syncthreads();
+                    const unsigned long long lo2 = (unsigned long long)lo + ((unsigned long long)(unsigned)bin << shift);
+                    unsigned long long hi2 = lo2 + ((1ull << shift) - 1ull);
+                    if (hi2 > st.tau_hi) hi2 = st.tau_hi;
+                    m_eff = kSettleRegs + in_bin;  // (the first kSettleRegs entries are the empty registers)
+                    cached_eff = true;
+                    settle_column(e, m_eff, kept, s_more, true, (unsigned)lo2, (unsigned)hi2, k_rem - (long long)before, s_h,
+                                  s_wave, s_res, st.tau, st.n_eq, st.q, st.cut);
+                    settled = true;
+                }
+            }
+            if (settled) {
+            } else if (held)
                 settle_column(e, m, kept, s_more, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq,
                               st.q, st.cut);
             else
@@ -655,14 +733,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
         if (row_keep && held) {
             // the bracket's entries that survive keep their rows too
             auto survives = [&](uint2 x) { return x.x > st.tau || (x.x == st.tau && x.x != 0u && x.y <= st.cut); };
-            auto word_of = [&](uint2 x) { return row_keep + 2 * (size_t)(t0 + (int)(x.y >> 7)) + ((x.y >> 6) & 1u); };
-            auto mark = [&](uint2 x, unsigned long long have) {
-                const unsigned long long bit = 1ull << (x.y & 63u);
-                if (have & bit) return;
-                if (relu && !(col0[(size_t)(x.y >> 7) * pitch + (x.y & 127u)] > 0.0f)) return;
-                atomicOr(word_of(x), bit);
-            };
-            if (cached) {
+            if (cached_eff) {
 #pragma unroll
                 for (int u0 = 0; u0 < kSettleCached; u0 += 8) {  // eight words in flight per thread
                     unsigned long long have[8];
@@ -676,18 +747,18 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                     for (int u = 0; u < 8; ++u)
                         if (u0 + u < kSettleCached) mark(kept[u0 + u], have[u]);
                 }
-                for (unsigned i = kSettleRegs + threadIdx.x; i < m; i += kSideThreads) {
+                for (unsigned i = kSettleRegs + threadIdx.x; i < m_eff; i += kSideThreads) {
                     const uint2 x = s_more[i - kSettleRegs];
                     if (survives(x)) mark(x, __hip_atomic_load(word_of(x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
                 }
             } else {
-                for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {  // eight entries in flight per thread
+                for (unsigned i0 = threadIdx.x; i0 < m_eff; i0 += kSideThreads * 8) {  // eight entries in flight per thread
                     uint2 x[8];
                     unsigned long long have[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {
                         const unsigned i = i0 + (unsigned)kSideThreads * u;
-                        x[u] = i < m ? e(i) : make_uint2(0u, 0u);
+                        x[u] = i < m_eff ? e(i) : make_uint2(0u, 0u);
                     }
 #pragma unroll
                     for (int u = 0; u < 8; ++u) {

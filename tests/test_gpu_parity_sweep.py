@@ -133,6 +133,31 @@ def test_selection_regimes_bit_exact(case, mode):
         assert np.array_equal(host(gf), of_), (case, k)
 
 
+@pytest.mark.parametrize("channels,levels", [(3, None), (33, None), (20, 3)])
+def test_selection_very_long_columns(channels, levels):
+    """Columns of about 700 000 entries: the bracket holds more entries than the settling pass caches (32768), so
+    it is read twice -- leading digit, then the k-th key's bin into LDS -- or, with few distinct values (a bin longer
+    than LDS), once per digit.  With and without row marks (33 / 3 and 20 channels)."""
+    import oracle
+    from tests.test_gpu_parity import dev, host
+    extent, batch = (128, 128, 64), 1
+    rng = np.random.default_rng(channels)
+    coords = random_sparse_sites(rng, extent, batch, 0.7)
+    if levels:
+        resp = rng.integers(-levels, levels + 1, size=(coords.shape[0], channels)).astype(np.float32) * 0.5
+    else:
+        resp = rng.normal(size=(coords.shape[0], channels)).astype(np.float32)
+    resp = np.ascontiguousarray(resp * (rng.random(resp.shape) < 0.9), dtype=np.float32)
+    rows = coords.shape[0]
+    for mode, k in ((scnn.ABS, rows // 20), (scnn.SIGNED, rows // 3), (scnn.ABS, rows // 2)):
+        say(f"selection very long rows={rows} C={channels} levels={levels} mode={mode} k={k}")
+        gc, gf, n = scnn.attention_topk(extent, batch, dev(coords), dev(resp), k, mode)
+        oc_, of_ = oracle.attention_topk(extent, batch, coords, resp, k, mode)
+        assert int(n[2]) == 0
+        assert np.array_equal(host(gc), oc_), (channels, k)
+        assert np.array_equal(host(gf), of_), (channels, k)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_selection_random_long_columns(seed):
     """Samples of very different sizes in one batch (one of them may be empty or tiny), channels that are all zero
