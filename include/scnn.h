@@ -269,11 +269,12 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
 
 /* Kernel choice for the convolution step of sparse_conv_fwd (and, for 1, of
  * sparse_conv_bwd), for the calling thread:
- * 0 = by shape and size.  Wide layers (C_in >= 32, or C_in = 16 or 24 with
- *     C_out >= 24 on layers whose workspace holds more than 1024 tiles of 128
- *     candidate sites) take the quad matrix-core kernel where C_in is 16, 24,
- *     32, 40, 48 or 64, C_out at most 128, the filter has at most 32 taps and
- *     in_feats is 16-byte aligned; else the pair-list matrix-core
+ * 0 = by shape and size.  Wide layers (C_in >= 32, or C_in = 8, 16 or 24 on
+ *     layers whose workspace holds more than 1024 tiles of 128 candidate
+ *     sites, with C_in * C_out >= 256 and C_out >= 24, or C_in * C_out >= 384)
+ *     take the quad matrix-core kernel where C_in is 8, 16, 24, 32, 40, 48 or
+ *     64, C_out at most 128, the filter has at most 32 taps and in_feats is
+ *     16-byte aligned; else the pair-list matrix-core
  *     kernel where C_in is 16 or a multiple of 32 up to 128 (any number of
  *     taps) and C_out a multiple of 16 up to 64.  Everything else takes the
  *     vector kernels;

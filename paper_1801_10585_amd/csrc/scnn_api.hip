@@ -23,19 +23,22 @@ static thread_local const char* g_last_conv_kernel = "";
 enum class ConvKernel { kValu, kPair, kQuad };
 
 // Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
-// 128 output channels (a launch per 64) with at most 32 taps; the pair-list kernel remains for 96 and 128 input channels.  With 16 or
-// 24 input channels the matrix cores pay only on layers of more than 1024 tiles with at least 24 output channels;
-// narrower and smaller layers are faster on the vector kernels.
+// 128 output channels (a launch per 64) with at most 32 taps; the pair-list kernel remains for 96 and 128 input
+// channels.  With 8, 16 or 24 input channels the matrix cores pay only on layers of more than 1024 tiles with enough
+// output channels; narrower and smaller layers are faster on the vector kernels.
 static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
     if (g_conv_path == 1) return ConvKernel::kValu;
     const bool pair_ok = conv_mfma_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
     const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
-    // 16 and 24 input channels pay for the matrix-core kernels' look-ups and lists only with at least 24 output
-    // channels (two quads then share a matrix instruction whatever the count) on layers of more than 1024 tiles;
-    // below that, and with fewer input channels, the vector kernels are faster
-    const bool wide = c_in >= 32 || ((c_in == 16 || c_in == 24) && c_out >= 24 && tiles_cap > 1024);
+    // 8, 16 and 24 input channels pay for the matrix-core kernels' look-ups and lists only on layers of more than 1024
+    // tiles whose rows carry enough multiply-adds per neighbour: C_in x C_out of at least 256 with at least 24
+    // output channels (8->32, 16->24), or of at least 384 (24->16); narrower layers (8->8, 8->16, 16->16: the first
+    // blocks of the paper's networks) are faster on the vector kernels
+    const int mac = c_in * c_out;
+    const bool wide = c_in >= 32 || ((c_in == 8 || c_in == 16 || c_in == 24) && tiles_cap > 1024 &&
+                                     ((mac >= 256 && c_out >= 24) || mac >= 384));
     if (quad_ok && wide) return ConvKernel::kQuad;
     if (pair_ok && wide) return ConvKernel::kPair;
     return ConvKernel::kValu;

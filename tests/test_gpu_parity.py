@@ -307,6 +307,9 @@ MFMA_CASES = [
     ((16, 16, 16), 1, 24, 96, (3, 3, 3), 0.08, 0.7),
     ((14, 14, 14), 2, 64, 80, (3, 3, 3), 0.08, 1.0),
     ((30, 30), 2, 16, 100, (3, 3), 0.2, 1.0),
+    # eight input channels with many output channels, 24 with few
+    ((20, 20, 20), 2, 8, 64, (3, 3, 3), 0.06, 1.0),
+    ((18, 18, 18), 1, 24, 16, (3, 3, 3), 0.08, 0.8),
 ]
 
 

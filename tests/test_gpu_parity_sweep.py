@@ -203,6 +203,7 @@ def test_selection_random_long_columns(seed):
 WIDE_LONG = [
     ((40, 40, 40), 2, 32, 40, 0.08), ((36, 36, 36), 1, 16, 64, 0.10), ((48, 40, 36), 2, 8, 33, 0.06),
     ((40, 40, 40), 1, 64, 48, 0.05), ((40, 40, 40), 2, 8, 17, 0.08), ((36, 40, 44), 1, 24, 24, 0.10),
+    ((64, 64, 40), 1, 8, 32, 0.08),  # (more than 1024 tiles: the library picks the quad kernel for 8 -> 32 itself)
 ]
 
 
