@@ -203,38 +203,45 @@ __global__ __launch_bounds__(256) void k_pool_gather(Geom g, Geom gp, const unsi
     long long n_out = ctr->n_pool;
     if (n_out > pool_cap) n_out = pool_cap;
     if (n_out > out_capacity) n_out = out_capacity;
-    // four channels per thread where the rows allow 16-byte accesses: a quarter of the child look-ups
+    // Rows that allow 16-byte accesses: eight lanes share a pooled site.  Lane j looks up child j (one look-up per
+    // child and site, whatever the channel count), the eight row indices go round by shuffles, and the lanes then
+    // split the site's groups of four channels.
     if ((channels & 3) == 0 && ((((size_t)feats) | ((size_t)out_feats)) & 15) == 0) {
         const int q = channels >> 2;
-        const long long total4 = n_out * q;
-        for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < total4;
-             i += (long long)gridDim.x * blockDim.x) {
-            const long long o = i / q;
-            const int c = (int)(i - o * q) * 4;
+        const int sub = threadIdx.x & 7;
+        const long long sites_per_pass = (long long)gridDim.x * (blockDim.x / 8);
+        for (long long o = (long long)blockIdx.x * (blockDim.x / 8) + (threadIdx.x >> 3); o < n_out;
+             o += sites_per_pass) {  // (the eight lanes of a site run the same iterations)
             const long long key = pool_key[o];
             const int b = (int)(key / gp.Npad);
             int p0, p1, p2;
             site_of(gp, key - (long long)b * gp.Npad, p0, p1, p2);
-            float best[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-            bool present[4] = {false, false, false, false};
+            const int mine = lookup_row(g, occ, occ_prefix, n_in, b, 2 * p0 + (sub >> 2), 2 * p1 + ((sub >> 1) & 1),
+                                        2 * p2 + (sub & 1));
+            int rows[8];
 #pragma unroll
-            for (int d = 0; d < 8; ++d) {
-                const int row = lookup_row(g, occ, occ_prefix, n_in, b, 2 * p0 + (d >> 2), 2 * p1 + ((d >> 1) & 1),
-                                           2 * p2 + (d & 1));
-                if (row < 0) continue;
-                const float4 v4 = *reinterpret_cast<const float4*>(feats + (size_t)row * channels + c);
-                const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+            for (int d = 0; d < 8; ++d) rows[d] = __shfl(mine, d, 8);
+            for (int cq = sub; cq < q; cq += 8) {
+                const int c = cq * 4;
+                float best[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+                bool present[4] = {false, false, false, false};
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    if (v[j] == 0.0f) continue;
-                    best[j] = present[j] ? fmaxf(best[j], v[j]) : v[j];
-                    present[j] = true;
+                for (int d = 0; d < 8; ++d) {
+                    if (rows[d] < 0) continue;
+                    const float4 v4 = *reinterpret_cast<const float4*>(feats + (size_t)rows[d] * channels + c);
+                    const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (v[j] == 0.0f) continue;
+                        best[j] = present[j] ? fmaxf(best[j], v[j]) : v[j];
+                        present[j] = true;
+                    }
                 }
+                *reinterpret_cast<float4*>(out_feats + o * channels + c) =
+                    make_float4(present[0] ? best[0] : 0.0f, present[1] ? best[1] : 0.0f, present[2] ? best[2] : 0.0f,
+                                present[3] ? best[3] : 0.0f);
             }
-            *reinterpret_cast<float4*>(out_feats + o * channels + c) =
-                make_float4(present[0] ? best[0] : 0.0f, present[1] ? best[1] : 0.0f, present[2] ? best[2] : 0.0f,
-                            present[3] ? best[3] : 0.0f);
-            if (c == 0) store_site(gp, out_coords + o * (1 + gp.ndim), b, p0, p1, p2);
+            if (sub == 0) store_site(gp, out_coords + o * (1 + gp.ndim), b, p0, p1, p2);
         }
         return;
     }
@@ -297,7 +304,9 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
         hipLaunchKernelGGL(k_pool_emit, dim3((unsigned)blocks), dim3(256), 0, s, pbits, pprefix, n_words, pool_key,
                            pool_cap);
     }
-    blocks = (pool_cap * channels + 255) / 256;
+    // (eight lanes per pooled site in the 16-byte form, a thread per value otherwise)
+    const bool vec4 = (channels & 3) == 0 && ((((size_t)feats) | ((size_t)out_feats)) & 15) == 0;
+    blocks = ((vec4 ? pool_cap * 8 : pool_cap * channels) + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 16384) blocks = 16384;
     hipLaunchKernelGGL(k_pool_gather, dim3((unsigned)blocks), dim3(256), 0, s, g, gp, occ, occ_prefix, n_imm, n_dev,
