@@ -449,8 +449,8 @@ static int conv_fwd_impl(int ndim, const int32_t* extent, int batch, const int32
         timer.mark();
         SCNN_TRY(launch_maxpool(g, gp, ws.tmp_coords, ws.tmp_feats, 0, &ws.ctr->n_rows, ws.cand_cap, c_out, 1,
                                 ws.occ_sel, ws.occ_prefix, ws.pbits, ws.pprefix, ws.block_sums, ws.pool_key,
-                                ws.pool_cap, out_coords, out_feats, out_capacity, ws.ctr, s));
-        SCNN_TRY(launch_finish(ws.ctr, 1, 0, 1, out_capacity, (long long*)nnz_out, s));
+                                ws.pool_cap, out_coords, out_feats, out_capacity, ws.ctr, (long long*)nnz_out, 0, 1,
+                                s));
     }
     timer.done();
     return SCNN_OK;
@@ -941,8 +941,7 @@ int sparse_maxpool(int ndim, const int32_t* extent, int batch, int window, const
     SCNN_TRY(launch_zero(workspace, ws.zero_bytes, s));
     SCNN_TRY(launch_maxpool(g, gp, coords, feats, rows, nullptr, rows, channels, 0, ws.occ, ws.occ_prefix, ws.pbits,
                             ws.pprefix, ws.block_sums, ws.pool_key, ws.pool_cap, out_coords, out_feats, out_capacity,
-                            ws.ctr, s));
-    SCNN_TRY(launch_finish(ws.ctr, 1, rows, 0, out_capacity, (long long*)nnz_out, s));
+                            ws.ctr, (long long*)nnz_out, rows, 0, s));
     return SCNN_OK;
 }
 

@@ -407,7 +407,8 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
                           int rows_have_entries, unsigned long long* occ, unsigned* occ_prefix, unsigned long long* pbits,
                           unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
                           int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
-                          hipStream_t s);
+                          long long* nnz_out /* nullable: also write the result counters, as launch_finish would */,
+                          long long aux_imm, int aux_is_cand, hipStream_t s);
 hipError_t launch_to_dense(const Geom& g, const int32_t* coords, const float* feats, long long rows,
                            const long long* rows_dev, int channels, float* dense, hipStream_t s);
 hipError_t launch_validate(const Geom& g, const int32_t* coords, long long rows, Counters* ctr, hipStream_t s);

@@ -101,9 +101,26 @@ __global__ __launch_bounds__(256) void k_pool_mark(Geom g, Geom gp, const int32_
     }
 }
 
+// The result counters of a pooling call, written by the thread that knows the number of pooled rows (nnz_out may be
+// null: a later launch writes them).  Nothing after this point sets a status bit.
+__device__ inline void pool_counters(const Counters* ctr, long long rows, long long* nnz_out, long long aux_imm,
+                                     int aux_is_cand, long long out_capacity) {
+    if (!nnz_out) return;
+    unsigned flags = ctr->flags;
+    if (rows > out_capacity) flags |= SCNN_FLAG_OUT_OVERFLOW;
+    nnz_out[0] = rows;
+    nnz_out[1] = aux_is_cand ? ctr->n_cand : aux_imm;
+    nnz_out[2] = (long long)flags;
+    nnz_out[3] = (long long)ctr->bracket_failed;
+}
+
 __global__ __launch_bounds__(256) void k_pool_emit(const unsigned long long* __restrict__ pbits,
                                                    const unsigned* __restrict__ pprefix, long long n_words,
-                                                   long long* __restrict__ pool_key, long long pool_cap) {
+                                                   long long* __restrict__ pool_key, long long pool_cap,
+                                                   const Counters* __restrict__ ctr, long long* __restrict__ nnz_out,
+                                                   long long aux_imm, int aux_is_cand, long long out_capacity) {
+    if (blockIdx.x == 0 && threadIdx.x == 0)  // (the scan before this launch left the total)
+        pool_counters(ctr, ctr->n_pool, nnz_out, aux_imm, aux_is_cand, out_capacity);
     for (long long w = (long long)blockIdx.x * blockDim.x + threadIdx.x; w < n_words;
          w += (long long)gridDim.x * blockDim.x) {
         unsigned long long bits = pbits[w];
@@ -122,7 +139,8 @@ __global__ __launch_bounds__(256) void k_pool_emit(const unsigned long long* __r
 // word also knows the total.
 __global__ __launch_bounds__(256) void k_pool_emit_small(const unsigned long long* __restrict__ pbits, int n_words,
                                                          long long* __restrict__ pool_key, long long pool_cap,
-                                                         Counters* ctr) {
+                                                         Counters* ctr, long long* __restrict__ nnz_out,
+                                                         long long aux_imm, int aux_is_cand, long long out_capacity) {
     __shared__ unsigned s_wave[4];
     const int w0 = blockIdx.x * 256;
     unsigned below = 0;
@@ -139,7 +157,10 @@ __global__ __launch_bounds__(256) void k_pool_emit_small(const unsigned long lon
     unsigned long long bits = w < n_words ? pbits[w] : 0ull;
     unsigned block_total;
     long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) ctr->n_pool = (long long)before_block + block_total;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        ctr->n_pool = (long long)before_block + block_total;
+        pool_counters(ctr, (long long)before_block + block_total, nnz_out, aux_imm, aux_is_cand, out_capacity);
+    }
     while (bits) {
         const int bit = __ffsll((long long)bits) - 1;
         bits &= bits - 1;
@@ -165,7 +186,8 @@ __global__ __launch_bounds__(256) void k_pool_count_chunks(const unsigned long l
 __global__ __launch_bounds__(256) void k_pool_emit_mid(const unsigned long long* __restrict__ pbits,
                                                        const unsigned* __restrict__ chunk_sums, long long n_words,
                                                        long long* __restrict__ pool_key, long long pool_cap,
-                                                       Counters* ctr) {
+                                                       Counters* ctr, long long* __restrict__ nnz_out,
+                                                       long long aux_imm, int aux_is_cand, long long out_capacity) {
     __shared__ unsigned s_wave[4];
     const int c = blockIdx.x;
     unsigned below = 0;
@@ -182,7 +204,10 @@ __global__ __launch_bounds__(256) void k_pool_emit_mid(const unsigned long long*
     unsigned long long bits = w < n_words ? pbits[w] : 0ull;
     unsigned block_total;
     long long o = (long long)before_block + block_exclusive_scan_256((unsigned)__popcll(bits), s_wave, block_total);
-    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) ctr->n_pool = (long long)before_block + block_total;
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        ctr->n_pool = (long long)before_block + block_total;
+        pool_counters(ctr, (long long)before_block + block_total, nnz_out, aux_imm, aux_is_cand, out_capacity);
+    }
     while (bits) {
         const int bit = __ffsll((long long)bits) - 1;
         bits &= bits - 1;
@@ -276,7 +301,7 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
                           int rows_have_entries, unsigned long long* occ, unsigned* occ_prefix, unsigned long long* pbits,
                           unsigned* pprefix, unsigned* scan_block_sums, long long* pool_key, long long pool_cap,
                           int32_t* out_coords, float* out_feats, long long out_capacity, Counters* ctr,
-                          hipStream_t s) {
+                          long long* nnz_out, long long aux_imm, int aux_is_cand, hipStream_t s) {
     // occ / pbits must be zero on entry
     hipError_t e = launch_index_build(g, coords, n_imm, n_dev, n_cap, occ, occ_prefix, ctr, s);
     if (e != hipSuccess) return e;
@@ -288,12 +313,12 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
     const long long n_words = (long long)gp.batch * gp.Wps;
     if (n_words <= kEmitSmallWords) {
         hipLaunchKernelGGL(k_pool_emit_small, dim3((unsigned)((n_words + 255) / 256)), dim3(256), 0, s, pbits,
-                           (int)n_words, pool_key, pool_cap, ctr);
+                           (int)n_words, pool_key, pool_cap, ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
     } else if (n_words <= kEmitMidWords) {  // (scan_block_sums holds at least a counter per 256 words then)
         const unsigned chunks = (unsigned)((n_words + 255) / 256);
         hipLaunchKernelGGL(k_pool_count_chunks, dim3(chunks), dim3(256), 0, s, pbits, n_words, scan_block_sums);
         hipLaunchKernelGGL(k_pool_emit_mid, dim3(chunks), dim3(256), 0, s, pbits, scan_block_sums, n_words, pool_key,
-                           pool_cap, ctr);
+                           pool_cap, ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
     } else {
         e = launch_popcount(pbits, n_words, pprefix, s);
         if (e != hipSuccess) return e;
@@ -302,7 +327,7 @@ hipError_t launch_maxpool(const Geom& g, const Geom& gp, const int32_t* coords, 
         blocks = (n_words + 255) / 256;
         if (blocks > 4096) blocks = 4096;
         hipLaunchKernelGGL(k_pool_emit, dim3((unsigned)blocks), dim3(256), 0, s, pbits, pprefix, n_words, pool_key,
-                           pool_cap);
+                           pool_cap, ctr, nnz_out, aux_imm, aux_is_cand, out_capacity);
     }
     // (eight lanes per pooled site in the 16-byte form, a thread per value otherwise)
     const bool vec4 = (channels & 3) == 0 && ((((size_t)feats) | ((size_t)out_feats)) & 15) == 0;
