@@ -782,6 +782,8 @@ constexpr int kStreamBlocks = 256 * 32;
 
 // Layers with at most this many work items run the latency-oriented kernel, larger ones the streaming kernel.
 constexpr long long kValuLatencyItems = 1024;
+// Layers whose workspace holds more than this many work items run the streaming kernel alone.
+constexpr long long kValuStreamOnlyItems = 8 * kValuLatencyItems;
 // Layers whose workspace holds at most this many work items (a bound the host knows) run the 32-row form.
 constexpr long long kValuSmallItems = 256;
 
@@ -804,7 +806,10 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
     else if (c_in % 4 == 0 && align_ch >= 8) ch = 4;
     else if (c_in % 2 == 0 && align_ch >= 2) ch = 2;
     const int n_chunks = (c_out_pad + 2 * kOcBlock - 1) / (2 * kOcBlock);
-    const bool both = tiles_cap * n_chunks > kValuLatencyItems;
+    // Far above the latency kernel's regime only the streaming kernel is launched (it takes any number of items; a
+    // layer whose workspace is that much larger than its data runs slower on it, a large layer saves a launch).
+    const bool stream_only = tiles_cap * n_chunks > kValuStreamOnlyItems;
+    const bool both = !stream_only && tiles_cap * n_chunks > kValuLatencyItems;
     if (tiles_cap * n_chunks <= kValuSmallItems && ch >= 2) {  // cannot hold more than a few hundred tiles
         const int blocks = (int)(tiles_cap * n_chunks * (kTileRows / 32));
 #define SCNN_VALU_SMALL(CH_)                                                                                         \
@@ -818,17 +823,19 @@ hipError_t launch_conv_valu(const Geom& g, const unsigned long long* occ, const 
     }
 #define SCNN_VALU_CASE(CH_)                                                                                          \
     do {                                                                                                             \
-        if (both && c_out <= 8)                                                                                      \
+        const long long stream_min = stream_only ? -1 : kValuLatencyItems;                                           \
+        if ((both || stream_only) && c_out <= 8)                                                                     \
             hipLaunchKernelGGL((k_conv_valu_stream<CH_, 8>), dim3(kStreamBlocks), dim3(256), 0, s, g, occ,           \
                                occ_prefix, nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin,    \
-                               cand_start, tile_start, ctr, kValuLatencyItems, resp);                                \
-        else if (both)                                                                                               \
+                               cand_start, tile_start, ctr, stream_min, resp);                                       \
+        else if (both || stream_only)                                                                                \
             hipLaunchKernelGGL((k_conv_valu_stream<CH_, 16>), dim3(kStreamBlocks), dim3(256), 0, s, g, occ,          \
                                occ_prefix, nnz_in, feats, c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin,    \
-                               cand_start, tile_start, ctr, kValuLatencyItems, resp);                                \
-        hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats, c_in, \
-                           wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,            \
-                           kValuLatencyItems, resp);                                                                 \
+                               cand_start, tile_start, ctr, stream_min, resp);                                       \
+        if (!stream_only)                                                                                            \
+            hipLaunchKernelGGL(k_conv_valu<CH_>, dim3(256 * 8), dim3(256), 0, s, g, occ, occ_prefix, nnz_in, feats,  \
+                               c_in, wp, c_out, c_out_pad, bias, tap_active, cand_lin, cand_start, tile_start, ctr,  \
+                               kValuLatencyItems, resp);                                                             \
     } while (0)
     if (ch == 8) SCNN_VALU_CASE(8);
     else if (ch == 4) SCNN_VALU_CASE(4);

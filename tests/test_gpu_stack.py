@@ -191,3 +191,30 @@ def test_chained_layer_ignores_rows_past_the_device_count_on_the_matrix_core_pat
     n_dev.fill_(10 * rows)
     _, _, nnz2 = lay(cin, fin, n_dev)
     assert int(host(nnz2)[2]) & (scnn.FLAG_UNSORTED | scnn.FLAG_BAD_COORD)
+
+
+def test_chained_narrow_layer_with_a_workspace_far_larger_than_its_data():
+    """Narrow channels (vector kernels) through the chained entry point with input arrays sixty times as long as the
+    device-resident row count: the workspace holds thousands of tiles, so only the streaming kernel is launched, and
+    it runs on a layer of a few hundred tiles.  The result must be the plain call's, bit for bit."""
+    from workloads import make_filter, random_sparse_sites
+    rng = np.random.default_rng(17)
+    extent, batch, c_in, c_out = (96, 96, 96), 2, 4, 12
+    coords = random_sparse_sites(rng, extent, batch, 0.0006)
+    rows = coords.shape[0]
+    feats = rng.normal(size=(rows, c_in)).astype(np.float32)
+    w = make_filter(rng, (3, 3, 3), c_in, c_out, 0.8, 0.3)
+    cap = 60 * rows
+    pad_c = np.full((cap - rows, 4), 5, dtype=np.int32)
+    pad_f = rng.normal(size=(cap - rows, c_in)).astype(np.float32)
+    cin, fin = dev(np.concatenate([coords, pad_c])), dev(np.concatenate([feats, pad_f]))
+    lay = scnn.ChainedLayer(extent, batch, cap, c_in, (3, 3, 3), dev(w), rho_up=0.01, relu=True)
+    n_dev = torch.tensor([rows], dtype=torch.int64, device="cuda:0")
+    oc, of, nnz = lay(cin, fin, n_dev)
+    nnz = host(nnz)
+    assert int(nnz[2]) == 0
+    rc, rf, rn = scnn.sparse_conv_fwd(extent, batch, dev(coords), dev(feats), (3, 3, 3), dev(w), rho_up=0.01, relu=True)
+    n = int(nnz[0])
+    say(f"chained narrow layer: {rows} of {cap} rows, {int(nnz[1])} candidate sites, {n} rows out")
+    assert n == rc.shape[0] and int(nnz[1]) == int(rn[1]) and n > 0
+    assert np.array_equal(host(oc)[:n], host(rc)) and np.array_equal(host(of)[:n], host(rf))
