@@ -929,8 +929,9 @@ __global__ __launch_bounds__(kSmallThreads) void k_select_small(int mode, int ch
 // of columns, and a workgroup of 1024 threads with five passes over a 2048-bin histogram costs each of them about
 // 10 us.  The k-th strongest key is found bit by bit, from the top: with the bits above already fixed, the keys
 // that have the next bit set are counted (a ballot per register); the tie cut is the position of the q-th equal key
-// in position order.  kTinyPerLane = 64 (columns of up to 4096 positions: 16^3 grids) is used when there are more
-// than a thousand columns; with few columns a workgroup per column is as fast.
+// in position order.  kTinyPerLane = 64 takes columns of up to 4096 positions (16^3 grids).  Both forms are used
+// when there are a thousand columns or more; with few columns a workgroup per column is as fast or a little faster
+// (the 32 dependent bit steps of a wave against five histogram passes of a workgroup).
 constexpr long long kTinyColumn = 64 * 16;   // positions of a column at most, 16 keys per lane
 constexpr long long kTinyColumn64 = 64 * 64;  // ... 64 keys per lane
 constexpr int kTinyManyColumns = 1024;
@@ -1039,7 +1040,7 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int r
                        hipStream_t s) {
     const int ncols = g.batch * channels;
     if (ncols <= 0) return hipSuccess;
-    if (column_positions(g) <= kTinyColumn) {
+    if (column_positions(g) <= kTinyColumn && ncols >= kTinyManyColumns) {
         hipLaunchKernelGGL(k_select_tiny<16>, dim3((unsigned)((ncols + 3) / 4)), dim3(256), 0, s, mode, channels, ncols,
                            tile_start, resp, k, cols);
         return hipGetLastError();

@@ -140,8 +140,10 @@ def _random_rows(rng, extent, batch, density, channels, levels=None, fill=0.7):
 @pytest.mark.parametrize("extent,batch,channels,density", [
     ((9, 11), 1, 1, 0.5), ((16, 16), 3, 5, 0.4), ((12, 10, 9), 2, 64, 0.3), ((20, 20, 20), 4, 70, 0.12),
     ((33, 17, 5), 2, 130, 0.2), ((40, 40, 40), 2, 16, 0.1), ((48, 48, 32), 2, 40, 0.3), ((64, 64, 12), 1, 64, 0.9),
-    # columns of at most 1024 positions (one wave per column): many samples, exactly 1024 sites, just below and above
-    ((28, 28), 37, 5, 0.4), ((32, 32), 2, 70, 0.6), ((10, 10, 10), 9, 3, 0.5), ((33, 32), 3, 4, 0.5),
+    # a thousand or more columns of at most 1024 positions (one wave per column): exactly 1024 sites, just below,
+    # and just above (a workgroup per column again, as with fewer columns)
+    ((28, 28), 260, 5, 0.4), ((32, 32), 16, 70, 0.6), ((10, 10, 10), 350, 3, 0.5), ((33, 32), 3, 4, 0.5),
+    ((28, 28), 37, 5, 0.4),
     # more than a thousand columns of at most 4096 positions: one wave per column as well
     ((16, 16, 16), 130, 8, 0.2), ((60, 60), 260, 4, 0.3)])
 @pytest.mark.parametrize("mode", [scnn.ABS, scnn.SIGNED])
