@@ -273,7 +273,7 @@ static void carve_conv(void* base, const Geom& g, const Geom& gp, long long nnz_
     w->cand_prefix = c.take<unsigned>(nw);
     w->pprefix = c.take<unsigned>(pool ? nwp : 0);
     long long sb = scan_blocks(nw);
-    if (nw <= kEmitMidWords && cand_chunk_count(nw) > sb) sb = cand_chunk_count(nw);  // per-chunk candidate counts
+    if (nw <= kEmitMidWords && cand_chunk_count(nw, g.Wps) > sb) sb = cand_chunk_count(nw, g.Wps);  // per-chunk candidate counts
     if (scan_blocks(w->tiles_cap) > sb) sb = scan_blocks(w->tiles_cap);
     if (scan_blocks(nwp) > sb) sb = scan_blocks(nwp);
     if (nwp <= kEmitMidWords && (nwp + 255) / 256 > sb) sb = (nwp + 255) / 256;  // (the pooling's chunk counts)

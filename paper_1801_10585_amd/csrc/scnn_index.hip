@@ -460,7 +460,7 @@ __global__ __launch_bounds__(256) void k_cand_dilate_chunks(Geom g, const unsign
 hipError_t launch_cand_dilate(const Geom& g, const unsigned long long* occ, const int* tap_active,
                               unsigned long long* cand, unsigned* cand_count, unsigned* chunk_sums, hipStream_t s) {
     const long long n_words = (long long)g.batch * g.Wps;
-    const int lanes = cand_dilate_lanes(n_words);
+    const int lanes = cand_dilate_lanes(n_words, g.Wps);
     if (chunk_sums) {  // (the caller passes them for kEmitSmallWords < n_words <= kEmitMidWords)
         long long blocks = (n_words * lanes + 255) / 256;
         if (blocks > 8192) blocks = 8192;
@@ -701,7 +701,7 @@ hipError_t launch_cand_emit_mid(const Geom& g, const unsigned long long* cand, c
                                 const unsigned* chunk_sums, long long n_words, unsigned* cand_lin, long long cand_cap,
                                 int* cand_start, int* tile_start, int* rows16_start, Counters* ctr, hipStream_t s) {
     const unsigned blocks = (unsigned)((n_words + 255) / 256);
-    const int chunk_shift = cand_chunk_shift(n_words);
+    const int chunk_shift = cand_chunk_shift(n_words, g.Wps);
     hipLaunchKernelGGL(k_cand_emit_mid, dim3(blocks + 1), dim3(256), 0, s, g, cand, cand_count, chunk_sums,
                        chunk_shift, n_words, cand_lin, cand_cap, cand_start, tile_start, rows16_start, ctr);
     return hipGetLastError();

@@ -298,10 +298,17 @@ constexpr long long kEmitMidWords = (long long)kEmitMidChunks * 256;
 // Lanes that share a bitmap word in the candidate dilation: 16 on small grids, where one lane per word would leave
 // most of the chip idle behind a chain of dependent loads (below about half a wave per SIMD), 1 on large grids.  A
 // chunk, whose candidates the dilation counts, is what one workgroup of 256 threads covers per step: 16 or 256 words.
-inline int cand_dilate_lanes(long long n_words) { return n_words <= 32768 ? 16 : 1; }
-inline int cand_chunk_shift(long long n_words) { return cand_dilate_lanes(n_words) == 16 ? 4 : 8; }
-inline long long cand_chunk_count(long long n_words) {
-    return (n_words + (1ll << cand_chunk_shift(n_words)) - 1) >> cand_chunk_shift(n_words);
+// Batches of many small samples (fewer than 256 words each) also take 16, as long as the chunk counts fit: a sample
+// then starts at most 15 words into a chunk, and those are the words the emit kernel has to add up per sample.
+inline int cand_dilate_lanes(long long n_words, long long words_per_sample) {
+    return (n_words <= 32768 || (words_per_sample < 256 && n_words <= 16ll * kEmitMidChunks)) ? 16 : 1;
+}
+inline int cand_chunk_shift(long long n_words, long long words_per_sample) {
+    return cand_dilate_lanes(n_words, words_per_sample) == 16 ? 4 : 8;
+}
+inline long long cand_chunk_count(long long n_words, long long words_per_sample) {
+    const int sh = cand_chunk_shift(n_words, words_per_sample);
+    return (n_words + (1ll << sh) - 1) >> sh;
 }
 hipError_t launch_cand_emit_mid(const Geom& g, const unsigned long long* cand, const unsigned* cand_count,
                                 const unsigned* chunk_sums, long long n_words, unsigned* cand_lin, long long cand_cap,

@@ -75,6 +75,7 @@ REGIMES = [
     ((9, 8, 7), 37, 4, 24, 0.2),       # many small samples, some of them empty
     ((28, 28), 300, 1, 8, 0.19),       # a batch of small images: per-sample ranges by a scan over the samples
     ((28, 28), 1100, 1, 3, 0.1),       # ... more than 8192 bitmap words of 13-word samples (a sample starts inside a chunk)
+    ((28, 28), 2600, 1, 2, 0.05),      # ... more than 32768 words, still 16-word chunks because the samples are short
 ]
 
 
