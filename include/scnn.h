@@ -273,14 +273,16 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
  *     layers whose workspace holds more than 1024 tiles of 128 candidate
  *     sites, with C_in * C_out >= 256 and C_out >= 24, or C_in * C_out >= 384)
  *     take the quad matrix-core kernel where C_in is 8, 16, 24, 32, 40, 48 or
- *     64, C_out at most 128, the filter has at most 32 taps and in_feats is
- *     16-byte aligned; else the pair-list matrix-core
+ *     64 (or 96 or 128 with a C_out the pair-list kernel does not take), C_out
+ *     at most 128, the filter has at most 32 taps and in_feats is 16-byte
+ *     aligned; else the pair-list matrix-core
  *     kernel where C_in is 16 or a multiple of 32 up to 128 (any number of
  *     taps) and C_out a multiple of 16 up to 64.  Everything else takes the
  *     vector kernels;
  * 1 = always the vector kernels;
  * 2 = a matrix-core kernel whenever one takes the shape, whatever the size:
- *     the quad kernel also for C_in = 8, 16 and 24;
+ *     the quad kernel wherever it takes the shape (also 96 and 128 input
+ *     channels, and 8, 16, 24 on small layers);
  * 3 = the pair-list matrix-core kernel where it takes the shape (C_in = 16 or
  *     a multiple of 32 up to 128, C_out a multiple of 16 up to 64).
  * All compute the same sums to the same rounding rule; the switch exists so

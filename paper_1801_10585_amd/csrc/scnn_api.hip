@@ -23,8 +23,8 @@ static thread_local const char* g_last_conv_kernel = "";
 enum class ConvKernel { kValu, kPair, kQuad };
 
 // Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
-// 128 output channels (a launch per 64) with at most 32 taps; the pair-list kernel remains for 96 and 128 input
-// channels.  With 8, 16 or 24 input channels the matrix cores pay only on layers of more than 1024 tiles with enough
+// 128 output channels (a launch per 64) with at most 32 taps, also C_in = 96 and 128 where the pair-list kernel does
+// not take the output width; the pair-list kernel remains for more than 32 taps and for 96 and 128 input channels.  With 8, 16 or 24 input channels the matrix cores pay only on layers of more than 1024 tiles with enough
 // output channels; narrower and smaller layers are faster on the vector kernels.
 static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
     if (g_conv_path == 1) return ConvKernel::kValu;
@@ -39,6 +39,10 @@ static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long 
     const int mac = c_in * c_out;
     const bool wide = c_in >= 32 || ((c_in == 8 || c_in == 16 || c_in == 24) && tiles_cap > 1024 &&
                                      ((mac >= 256 && c_out >= 24) || mac >= 384));
+    // 96 and 128 input channels: three or four chunks per tap put the quad kernel's sums in fp64 registers (two waves
+    // per SIMD); where the pair-list kernel takes the shape it is 10-35 % faster there, and the quad kernel takes
+    // what it does not (output channels beyond 64 or no multiple of 16), which used to fall to the vector kernels
+    if (pair_ok && wide && c_in > 64) return ConvKernel::kPair;
     if (quad_ok && wide) return ConvKernel::kQuad;
     if (pair_ok && wide) return ConvKernel::kPair;
     return ConvKernel::kValu;

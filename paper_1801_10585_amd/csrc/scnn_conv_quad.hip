@@ -445,7 +445,8 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
 
 bool conv_quad_supported(const Geom& g, int c_in, int c_out, long long nnz_in) {
     if (g.T > kQuadMaxTaps) return false;
-    const bool shape = (c_in == 8 || c_in == 16 || c_in == 24 || c_in == 32 || c_in == 40 || c_in == 48 || c_in == 64) &&
+    const bool shape = (c_in == 8 || c_in == 16 || c_in == 24 || c_in == 32 || c_in == 40 || c_in == 48 || c_in == 64 ||
+                        c_in == 96 || c_in == 128) &&
                        c_out >= 1 && c_out <= kQuadMaxCout;
     return shape && nnz_in > 0 && nnz_in * (long long)c_in * 4 < (1ll << 31);
 }
@@ -491,7 +492,7 @@ hipError_t launch_conv_quad(const Geom& g, const unsigned long long* occ, const 
             e = acc64 ? launch_conv_quad_t<CI, 2, 1>(SCNN_QUAD_ARGS) : launch_conv_quad_t<CI, 2, 0>(SCNN_QUAD_ARGS);  \
     }
         SCNN_QUAD_CASE(8) SCNN_QUAD_CASE(16) SCNN_QUAD_CASE(24) SCNN_QUAD_CASE(32) SCNN_QUAD_CASE(40) SCNN_QUAD_CASE(48)
-        SCNN_QUAD_CASE(64)
+        SCNN_QUAD_CASE(64) SCNN_QUAD_CASE(96) SCNN_QUAD_CASE(128)
 #undef SCNN_QUAD_CASE
 #undef SCNN_QUAD_ARGS
         if (e != hipSuccess) return e;

@@ -309,6 +309,10 @@ MFMA_CASES = [
     ((16, 16, 16), 1, 24, 96, (3, 3, 3), 0.08, 0.7),
     ((14, 14, 14), 2, 64, 80, (3, 3, 3), 0.08, 1.0),
     ((30, 30), 2, 16, 100, (3, 3), 0.2, 1.0),
+    # 96 and 128 input channels with output widths only the quad kernel takes (and, forced, those the pair lists take)
+    ((14, 14, 14), 2, 96, 96, (3, 3, 3), 0.08, 1.0),
+    ((12, 12, 12), 1, 128, 40, (3, 3, 3), 0.1, 0.6),
+    ((24, 24), 2, 128, 128, (3, 3), 0.2, 1.0),
     # eight input channels with many output channels, 24 with few
     ((20, 20, 20), 2, 8, 64, (3, 3, 3), 0.06, 1.0),
     ((18, 18, 18), 1, 24, 16, (3, 3, 3), 0.08, 0.8),
