@@ -485,17 +485,18 @@ struct ColumnEntries {  // slot i of a column of the response matrix (key 0: not
 // that a narrow bracket is settled in two passes.  Between the passes up to kSettleCached entries per thread are held
 // in registers and kSettleLds more per workgroup in LDS (brackets that hold long runs of equal scores run to 30 000
 // entries on the paper's first layers).  (whole workgroup)
-constexpr int kSettleCached = 20;
-constexpr unsigned kSettleRegs = (unsigned)kSettleCached * 1024u;  // entries held in registers at most
-constexpr unsigned kSettleLds = 12288;                             // entries held in LDS behind them
+// Two sizes: 20 per thread + 12288 (one workgroup per compute unit: its registers and LDS), the rule; 4 per thread +
+// 2048 for layers of many columns, whose brackets are short and whose workgroups then fit two to a compute unit.
+template <int kSettleCached> constexpr unsigned kSettleRegsOf = (unsigned)kSettleCached * 1024u;
 
 // held: the entries threadIdx.x + 1024 * u of the column, more: the entries from kSettleRegs on, if cached
 // (m <= kSettleRegs + kSettleLds); both loaded by the caller.
-template <class Entries>
+template <int kSettleCached, class Entries>
 __device__ inline void settle_column(const Entries& entry, unsigned m, const uint2 (&held)[kSettleCached],
                                      const uint2* more, bool cached, unsigned key_lo, unsigned key_hi, long long kk,
                                      unsigned* s_h, unsigned* s_wave, int* s_res, unsigned& tau, unsigned& n_eq,
                                      unsigned& q, unsigned& cut) {
+    constexpr unsigned kSettleRegs = kSettleRegsOf<kSettleCached>;
     auto clear = [&]() {
         for (int i = threadIdx.x; i < kHistBins; i += kSideThreads) s_h[i] = 0;
         __syncthreads();
@@ -584,7 +585,9 @@ __device__ inline void settle_column(const Entries& entry, unsigned m, const uin
     }
 }
 
-__global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int channels, long long k,
+template <int kSettleCached, unsigned kSettleLds>
+__global__ __launch_bounds__(kSideThreads) __attribute__((amdgpu_waves_per_eu(kSettleCached > 8 ? 4 : 8)))
+void k_settle(int mode, int relu, int channels, long long k,
                                                          const int* __restrict__ tile_start,
                                                          const float* __restrict__ resp, ColState* __restrict__ cols,
                                                          const uint2* __restrict__ side,
@@ -595,6 +598,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
     __shared__ unsigned s_wave[4];
     __shared__ int s_res[4];
     __shared__ uint2 s_part[4];
+    constexpr unsigned kSettleRegs = kSettleRegsOf<kSettleCached>;
     __shared__ uint2 s_more[kSettleLds];
     __shared__ unsigned s_cnt;
     const int col = blockIdx.x;
@@ -681,6 +685,7 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                 unsigned before;
                 block_pick(s_h, k_rem, true, s_wave, s_res + 2, bin, before);
                 const unsigned in_bin = s_h[bin];
+                __syncthreads();  // (every thread has read the count before the histogram is cleared again)
                 if (in_bin <= kSettleLds) {  // (uniform)
                     for (unsigned i0 = threadIdx.x; i0 < m; i0 += kSideThreads * 8) {
                         uint2 x[8];
@@ -712,17 +717,17 @@ __global__ __launch_bounds__(kSideThreads) void k_settle(int mode, int relu, int
                     if (hi2 > st.tau_hi) hi2 = st.tau_hi;
                     m_eff = kSettleRegs + in_bin;  // (the first kSettleRegs entries are the empty registers)
                     cached_eff = true;
-                    settle_column(e, m_eff, kept, s_more, true, (unsigned)lo2, (unsigned)hi2, k_rem - (long long)before, s_h,
+                    settle_column<kSettleCached>(e, m_eff, kept, s_more, true, (unsigned)lo2, (unsigned)hi2, k_rem - (long long)before, s_h,
                                   s_wave, s_res, st.tau, st.n_eq, st.q, st.cut);
                     settled = true;
                 }
             }
             if (settled) {
             } else if (held)
-                settle_column(e, m, kept, s_more, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq,
+                settle_column<kSettleCached>(e, m, kept, s_more, cached, st.tau_lo, st.tau_hi, k_rem, s_h, s_wave, s_res, st.tau, st.n_eq,
                               st.q, st.cut);
             else
-                settle_column(ColumnEntries{col0, pitch, mode}, (unsigned)(t1 - t0) * kTileRows, kept, s_more, false, 0u,
+                settle_column<kSettleCached>(ColumnEntries{col0, pitch, mode}, (unsigned)(t1 - t0) * kTileRows, kept, s_more, false, 0u,
                               0xffffffffu, k, s_h, s_wave, s_res, st.tau, st.n_eq, st.q, st.cut);
         }
         if (threadIdx.x == 0) {
@@ -1073,8 +1078,13 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int r
         hipLaunchKernelGGL(k_combine_marks, dim3((unsigned)cb), dim3(64), 0, s, channels, row_plane, 2 * tiles_cap, ctr,
                            row_keep);
     }
-    hipLaunchKernelGGL(k_settle, dim3(ncols), dim3(kSideThreads), 0, s, mode, relu, channels, k, tile_start, resp, cols,
-                       side, part, slices, marks ? row_keep : nullptr, marks ? tile_base : nullptr, ctr);
+    if (ncols > 256)  // (more columns than compute units: two light workgroups per unit)
+        hipLaunchKernelGGL((k_settle<4, 2048u>), dim3(ncols), dim3(kSideThreads), 0, s, mode, relu, channels, k, tile_start,
+                           resp, cols, side, part, slices, marks ? row_keep : nullptr, marks ? tile_base : nullptr, ctr);
+    else
+        hipLaunchKernelGGL((k_settle<20, 12288u>), dim3(ncols), dim3(kSideThreads), 0, s, mode, relu, channels, k,
+                           tile_start, resp, cols, side, part, slices, marks ? row_keep : nullptr,
+                           marks ? tile_base : nullptr, ctr);
     return hipGetLastError();
 }
 

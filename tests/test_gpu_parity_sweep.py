@@ -105,6 +105,9 @@ SELECTION_REGIMES = [
     (128 * 128, 40, None), (128 * 128 + 1, 40, None), (129 * 128, 33, 40), (300 * 128 + 77, 32, None),
     (300 * 128 + 77, 64, 2), (300 * 128 + 77, 65, None), (40000, 48, 2), (40000, 8, 2),
     (129 * 128, 16, None), (40000, 17, 2), (129 * 128 + 5, 24, 3),
+    # more than 256 columns: the settling pass with the small caches (two workgroups per compute unit), on brackets
+    # that fit them and, with few distinct values, on brackets that do not
+    (129 * 128, 150, None), (40000, 140, 2),
 ]
 
 
