@@ -88,8 +88,18 @@ __global__ __launch_bounds__(256) void k_pool_mark(Geom g, Geom gp, const int32_
             load_site(g, coords + r * stride, b, c0, c1, c2);
             bool any = site_in_grid(g, b, c0, c1, c2);
             if (any && !rows_have_entries) {  // a row of zeros holds no entry and creates no output site
+                // (stops at the first non-zero value, which an ordinary row has in its first few channels; 16 bytes
+                // at a time where the rows allow it)
                 any = false;
-                for (int c = 0; c < channels; ++c) any |= feats[r * channels + c] != 0.0f;
+                const float* row = feats + r * channels;
+                if ((channels & 3) == 0 && (((size_t)feats) & 15) == 0) {
+                    for (int c = 0; c < channels && !any; c += 4) {
+                        const float4 v = *reinterpret_cast<const float4*>(row + c);
+                        any = v.x != 0.0f || v.y != 0.0f || v.z != 0.0f || v.w != 0.0f;
+                    }
+                } else {
+                    for (int c = 0; c < channels && !any; ++c) any = row[c] != 0.0f;
+                }
             }
             if (any) key = (long long)b * gp.Npad + lin_of(gp, c0 >> 1, c1 >> 1, c2 >> 1);
         }
