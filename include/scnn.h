@@ -246,8 +246,8 @@ int scnn_validate_rows(int ndim, const int32_t* extent, int batch, const int32_t
  * in_coords / in_feats / w are the forward operands.  bp_data fp32
  * [nnz_in, c_in] and bp_filter fp32 [prod(ksize), c_in, c_out] are overwritten
  * entirely.  Sums are carried in fp64 and rounded to fp32 once, except that the
- * matrix-core kernels (C_out a multiple of 32 up to 128, C_in a multiple of 16
- * up to 64, 16-byte aligned value arrays) first add up to 32 products (bp_data)
+ * matrix-core kernels (C_out = 16 or a multiple of 32 up to 128, C_in a multiple
+ * of 16 up to 64, 16-byte aligned value arrays) first add up to 32 products (bp_data)
  * or the at most 128 products of one tap within one 128-row tile (bp_filter) in
  * fp32.  Error bound of the matrix-core kernels: with A the sum of the
  * magnitudes of the products behind an element, |result - exact| <=

@@ -511,7 +511,8 @@ void carve_bwd(void* base, const Geom& g, long long nnz_in, int c_in, int c_out,
     w->block_cap = w->mfma_shape ? (long long)g.T * (nnz_in / 16 + w->tiles_cap) : 0;
     w->pairs = c.take<unsigned>((size_t)w->block_cap * 16);
     w->block_tap = c.take<unsigned short>((size_t)w->block_cap);
-    w->wb = c.take<float>(w->mfma_shape ? (size_t)n_elem : 0);
+    // (the adjoint filter in matrix-operand order: its input channels, C_out, padded to a whole 32-channel chunk)
+    w->wb = c.take<float>(w->mfma_shape ? (size_t)g.T * round_up(c_out, 32) * c_in : 0);
     w->tile_hdr = c.take<uint2>(w->mfma_shape ? w->tiles_cap : 0);
     w->tap_first = c.take<unsigned short>(w->mfma_shape ? (size_t)w->tiles_cap * (g.T + 1) : 0);
     const int chunks = w->chunks_mfma > w->chunks_valu ? w->chunks_mfma : w->chunks_valu;

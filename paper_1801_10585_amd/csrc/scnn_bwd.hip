@@ -276,7 +276,9 @@ __device__ __forceinline__ void bwd_filter_load(const uint4 ent, const char* __r
 #pragma unroll
             for (int a = 0; a < MT; ++a) o.av[j][a] = live ? o.av[j][a] : 0.0f;
         }
-        if constexpr (NT == 2) {
+        if constexpr (NT == 1) {
+            o.bv[j][0] = *(const float*)(gl + goff);
+        } else if constexpr (NT == 2) {
             const float2 t2 = *(const float2*)(gl + goff);
             o.bv[j][0] = t2.x;
             o.bv[j][1] = t2.y;
@@ -415,12 +417,12 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
 
 // The gradient values are addressed with 32-bit byte offsets.
 bool bwd_filter_mfma_supported(int c_in, int c_out, long long g_rows) {
-    return c_in % 16 == 0 && c_out % 32 == 0 && g_rows * c_out * 4 < (1ll << 32);
+    return c_in % 16 == 0 && c_out % 16 == 0 && g_rows * c_out * 4 < (1ll << 32);
 }
 
 // waves per share of the tiles
 static int bwd_filter_slabs(const Geom& g, int c_in, int c_out) {
-    const int mt = (c_in % 32 == 0) ? 2 : 1, nt = (c_out % 64 == 0) ? 4 : 2;
+    const int mt = (c_in % 32 == 0) ? 2 : 1, nt = (c_out % 64 == 0) ? 4 : (c_out % 32 == 0 ? 2 : 1);
     return g.T * (c_in / (16 * mt)) * (c_out / (16 * nt));
 }
 
@@ -452,9 +454,9 @@ hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const
     hipLaunchKernelGGL((k_bwd_filter_mfma<MT_, NT_>), dim3(blocks), dim3(256), 0, s, g.T, c_in, c_out, x, gf, pairs, \
                        tap_first, tile_hdr, cand_start, tile_start, g.batch, ctr, n_chunks, groups, fpart)
     if (c_in % 32 == 0) {
-        if (c_out % 64 == 0) SCNN_BWD_CASE(2, 4); else SCNN_BWD_CASE(2, 2);
+        if (c_out % 64 == 0) SCNN_BWD_CASE(2, 4); else if (c_out % 32 == 0) SCNN_BWD_CASE(2, 2); else SCNN_BWD_CASE(2, 1);
     } else {
-        if (c_out % 64 == 0) SCNN_BWD_CASE(1, 4); else SCNN_BWD_CASE(1, 2);
+        if (c_out % 64 == 0) SCNN_BWD_CASE(1, 4); else if (c_out % 32 == 0) SCNN_BWD_CASE(1, 2); else SCNN_BWD_CASE(1, 1);
     }
 #undef SCNN_BWD_CASE
     return hipGetLastError();

@@ -119,13 +119,17 @@ def test_backward_small_cases_every_element(case):
 
 
 WIDE = [
-    # shapes that reach the matrix-core kernels: C_out a multiple of 32 (<= 128), C_in a multiple of 16 (<= 64)
+    # shapes that reach the matrix-core kernels: C_out = 16 or a multiple of 32 (<= 128), C_in a multiple of 16 (<= 64)
     ((20, 18, 16), 2, 16, 32, (3, 3, 3), 0.08, 0.5),
     ((24, 20, 22), 2, 32, 64, (3, 3, 3), 0.06, 1.0),
     ((18, 18, 18), 1, 48, 96, (3, 3, 3), 0.06, 0.5),
     ((16, 16, 16), 2, 64, 128, (3, 3, 3), 0.05, 0.3),
     ((48, 40), 3, 32, 32, (5, 5), 0.1, 0.5),
     ((14, 14, 14), 1, 64, 64, (5, 5, 5), 0.04, 0.3),
+    # sixteen output channels: slabs of 16 output channels in the filter gradient, the half-chunk adjoint convolution
+    ((20, 20, 20), 2, 16, 16, (3, 3, 3), 0.08, 1.0),
+    ((18, 16, 20), 1, 32, 16, (3, 3, 3), 0.08, 0.6),
+    ((36, 30), 2, 64, 16, (3, 3), 0.15, 1.0),
 ]
 
 
