@@ -29,6 +29,9 @@ constexpr int kQuadWaves = 4;            // waves per workgroup
 constexpr int kQuadRows = 64;            // candidate sites per wave
 constexpr int kQuadMaxTaps = 32;         // taps per filter (one bit each in a site's neighbour pattern)
 constexpr bool kQuadSingleChain = false;
+constexpr int kQuadSteal = 2;            // XCDs after its own that a wave helps once its own has nothing left
+constexpr int kQuadChunkMin = 128;       // shortest chunk (wave tiles)
+constexpr int kQuadChunks = 8;           // chunks of wave tiles per XCD (see the kernel's tile order)
 constexpr int kLineBatch = 9;            // filter lines whose bitmap words are fetched together
 constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that does not exist: out of range, reads 0
 
@@ -143,17 +146,55 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
     // taps with a non-zero weight, one bit each
     const unsigned act_mask = (unsigned)__ballot(lane < g.T && tap_active[lane < g.T ? lane : 0] != 0);
 
-    // XCD-aware order: workgroup i runs on XCD i % 8; each XCD owns one contiguous span of the wave tiles so that the
-    // input rows shared by neighbouring tiles stay in its L2.  A wave starts with the tile of its slot and then draws
-    // tiles from its span's counter, and from the other spans' once its own is used up.
+    // XCD-aware order: workgroup i runs on XCD i % 8.  The wave tiles are cut into 8 * kQuadChunks chunks of equal
+    // length and XCD x owns the chunks x, x + 8, x + 16, ...: inside a chunk neighbouring tiles share input rows,
+    // which then stay in that XCD's L2, and because an XCD's chunks are spread over the whole batch, samples whose
+    // sites cost more (more taps per quad) are shared out evenly instead of falling to two or three XCDs.  An XCD's
+    // wave tiles are numbered through its chunks (v = 0, 1, ...).
+    //
+    // Units of work.  A wave tile keeps a wave busy for as long as a third of a small layer's whole launch, so what
+    // is left for a last, partial round of the XCD's wave slots would leave most of the chip waiting for a few
+    // waves.  The wave tiles of that round are therefore dealt out in halves or quarters (32 or 16 of the 64 sites:
+    // the other sites are treated like sites past the sample's end, and the unit stores only its own) when that
+    // still gives every piece a slot of its own.  A site's sum does not depend on the sites it shares a quad with
+    // (an absent neighbour adds an exact zero), so the split does not change a single bit of the result.
+    // A wave starts with unit u = its slot and then draws further units from its XCD's counter, and from the next
+    // XCDs' once its own is used up.
     const int n_wt = 2 * (int)ctr->n_tiles;
     const int xcd = blockIdx.x & 7, slot = (blockIdx.x >> 3) * kQuadWaves + wave, per_xcd = (gridDim.x >> 3) * kQuadWaves;
-    const int span = (n_wt + 7) >> 3;
-    const int my_end = (xcd + 1) * span < n_wt ? (xcd + 1) * span : n_wt;
+    // (only where every chunk gets at least kQuadChunkMin wave tiles: shorter chunks lose more at their ends,
+    // where the neighbours' rows belong to another XCD's L2, than the even shares win - measured on 16 -> 32
+    // channels over 3900 wave tiles: 113 us in one chunk per XCD, 117 us in three)
+    const int n_chunks = n_wt >= 8 * kQuadChunks * kQuadChunkMin ? kQuadChunks : 1;
+    const int chunk = n_wt > 0 ? (n_wt + 8 * n_chunks - 1) / (8 * n_chunks) : 1;
+    // unit u of XCD x: its wave tile (-1 past the end: then every later unit of that XCD is past the end as well) and
+    // the sites lo .. hi - 1 of it
+    auto unit_of = [&](int x, int u, int& lo, int& hi) {
+        int vspan = 0;  // wave tiles of XCD x
+        for (int c = 0; c < n_chunks; ++c) {
+            const int left = n_wt - (c * 8 + x) * chunk;
+            vspan += left <= 0 ? 0 : (left < chunk ? left : chunk);
+        }
+        lo = 0;
+        hi = kQuadRows;
+        const int whole = (vspan / per_xcd) * per_xcd, rest = vspan - whole;
+        const int sl = rest * 4 <= per_xcd ? 2 : (rest * 2 <= per_xcd ? 1 : 0);
+        int v = u;
+        if (u >= whole) {
+            const int r = u - whole;
+            v = whole + (r >> sl);
+            lo = (r & ((1 << sl) - 1)) * (kQuadRows >> sl);
+            hi = lo + (kQuadRows >> sl);
+        }
+        if (v >= vspan) return -1;
+        const int c = v / chunk;
+        return (c * 8 + x) * chunk + (v - c * chunk);
+    };
     unsigned* tickets = ctr->conv_ticket + (col0 >> 6) * 8 * kTicketStride;
 
-    bool own_done = xcd * span + per_xcd >= my_end;  // nothing to draw beyond the first tiles
-    for (int wt = xcd * span + slot < my_end ? xcd * span + slot : -1; wt >= 0;) {
+    int row_lo = 0, row_hi = kQuadRows, lo_next = 0, hi_next = 0;
+    bool own_done = unit_of(xcd, per_xcd, lo_next, hi_next) < 0;  // nothing to draw beyond the first units
+    for (int wt = unit_of(xcd, slot, row_lo, row_hi); wt >= 0;) {
         const int tile = wt >> 1, half = wt & 1;
         const int b = sample_of_tile(tile_start, g.batch, tile);
         const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows + half * kQuadRows;
@@ -167,13 +208,13 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
             for (int r = 0; r < 4; ++r) acc[s][r] = (acc_t)0;
         unsigned my_pos = (unsigned)lane;  // sorted position of site `lane` (of the wave's 64)
 
-        if (nrows > 0) {
+        if (nrows > row_lo) {
             // ---- neighbours of site `lane`: buffer offsets into s_tab[tap][lane], pattern bits into `mask`.
             //      The taps of one filter line (t0, t1, .) look at adjacent sites, which sit in at most two adjacent
             //      words of the occupancy bitmap: both words and their row prefixes are fetched for kLineBatch lines
             //      at a time, all loads in flight together, and the lines' taps are resolved from them afterwards.
             int c0 = 0, c1 = 0, c2 = 0;
-            const bool live = lane < nrows;
+            const bool live = lane < nrows && lane >= row_lo && lane < row_hi;
             if (live) site_of(g, cand_lin[first + lane], c0, c1, c2);
             unsigned mask = 0;
             // LDS address of s_tab[0][lane], made opaque per tile: the addresses of the table's rows must not be
@@ -388,6 +429,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
             float* tr_w = s_tr + colh + (QPM == 2 ? 4 * (HC + 1) * (lane >> 5) : 0);
             const float* tr_r = s_tr + my_pos * (HC + 1);
             float* dst = resp + ((size_t)tile * c_out_all + col0) * kTileRows + half * kQuadRows + lane;
+            const bool mine = lane >= row_lo && lane < row_hi;  // (the unit's own sites)
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 if ((col >= HC) == (h == 1)) {
@@ -413,32 +455,39 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
                     float v[8];
 #pragma unroll
                     for (int i = 0; i < 8; ++i) v[i] = tr_r[c - h * HC + i];
+                    if (mine) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) dst[(size_t)(c + i) * kTileRows] = v[i];
+                        for (int i = 0; i < 8; ++i) dst[(size_t)(c + i) * kTileRows] = v[i];
+                    }
                 }
-                for (; c < c_end; ++c) dst[(size_t)c * kTileRows] = tr_r[c - h * HC];
+                for (; c < c_end; ++c) {
+                    const float v = tr_r[c - h * HC];
+                    if (mine) dst[(size_t)c * kTileRows] = v;
+                }
             }
         }
         int next_wt = -1;
         if (!own_done) {
-            const int cand = xcd * span + per_xcd + (int)__builtin_amdgcn_readfirstlane(ticket);
-            if (cand < my_end) next_wt = cand; else own_done = true;
+            next_wt = unit_of(xcd, per_xcd + (int)__builtin_amdgcn_readfirstlane(ticket), lo_next, hi_next);
+            own_done = next_wt < 0;
         }
         if (own_done) {
-            // the own span is used up: help the next spans, so that no XCD ends long before the others (tiles differ
+            // the own units are used up: help the next XCDs, so that none ends long before the others (tiles differ
             // in work).  Only the next two are tried: a wave that finds nothing there retires.
             int got = -1;
             if (lane == 0) {
-                for (int d = 1; d <= 2 && got < 0; ++d) {
+                for (int d = 1; d <= kQuadSteal && got < 0; ++d) {
                     const int x = (xcd + d) & 7;
-                    const int end_x = (x + 1) * span < n_wt ? (x + 1) * span : n_wt;
-                    if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
-                    const int cand = x * span + per_xcd + (int)atomicAdd(&tickets[x * kTicketStride], 1u);
-                    if (cand < end_x) got = cand;
+                    if (unit_of(x, per_xcd, lo_next, hi_next) < 0) continue;  // (an XCD with nothing to draw)
+                    got = unit_of(x, per_xcd + (int)atomicAdd(&tickets[x * kTicketStride], 1u), lo_next, hi_next);
                 }
             }
             next_wt = __builtin_amdgcn_readfirstlane(got);
+            lo_next = __builtin_amdgcn_readfirstlane(lo_next);
+            hi_next = __builtin_amdgcn_readfirstlane(hi_next);
         }
+        row_lo = lo_next;
+        row_hi = hi_next;
         wt = next_wt;
     }
 }
