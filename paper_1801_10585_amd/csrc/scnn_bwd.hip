@@ -318,8 +318,8 @@ __global__ __launch_bounds__(256) void k_bwd_filter_mfma(int taps, int c_in, int
     const int jj = lane & 15, gq = lane >> 4;
     const int n_icb = c_in / (16 * MT), n_ocb = c_out / (16 * NT);
     const int slabs = taps * n_icb * n_ocb;
-    const int xcd = blockIdx.x & 7, j_in_xcd = blockIdx.x >> 3;
-    const int chunk = (j_in_xcd / groups) * 8 + xcd;
+    const int xcd = blockIdx.x % kXcds, j_in_xcd = blockIdx.x / kXcds;
+    const int chunk = (j_in_xcd / groups) * kXcds + xcd;
     const int slab = __builtin_amdgcn_readfirstlane((j_in_xcd % groups) * 4 + (int)(threadIdx.x >> 6));
     if (chunk >= n_chunks || slab >= slabs) return;
     const int ta = slab / (n_icb * n_ocb);  // adjoint tap
@@ -431,8 +431,8 @@ int bwd_filter_chunks(const Geom& g, int c_in, int c_out, long long tiles_cap, b
     if (mfma) {
         const int slabs = bwd_filter_slabs(g, c_in, c_out);
         // all waves resident at once (two per SIMD), the same number of shares on every XCD
-        chunks = (256 * 8) / ((slabs + 3) / 4 * 4) / 8 * 8;
-        if (chunks < 8) chunks = 8;
+        chunks = (device_cu_count() * 8) / ((slabs + 3) / 4 * 4) / kXcds * kXcds;
+        if (chunks < kXcds) chunks = kXcds;
         if (chunks > 256) chunks = 256;
     } else {
         const long long n_eb = ((long long)g.T * c_in * c_out + 255) / 256;
@@ -449,7 +449,7 @@ hipError_t launch_bwd_filter_mfma(const Geom& g, const float* x, int c_in, const
                                   const int* cand_start, const int* tile_start, const Counters* ctr, int n_chunks,
                                   double* fpart, hipStream_t s) {
     const int groups = (bwd_filter_slabs(g, c_in, c_out) + 3) / 4;
-    const unsigned blocks = (unsigned)(8 * groups * ((n_chunks + 7) / 8));
+    const unsigned blocks = (unsigned)(kXcds * groups * ((n_chunks + kXcds - 1) / kXcds));
 #define SCNN_BWD_CASE(MT_, NT_)                                                                                   \
     hipLaunchKernelGGL((k_bwd_filter_mfma<MT_, NT_>), dim3(blocks), dim3(256), 0, s, g.T, c_in, c_out, x, gf, pairs, \
                        tap_first, tile_hdr, cand_start, tile_start, g.batch, ctr, n_chunks, groups, fpart)

@@ -1056,12 +1056,12 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
     // address in its low 32 bits); accumulator addresses are formed once per block, at load time
     const unsigned lane_off = (unsigned)(size_t)s_c + (unsigned)jj * (unsigned)sizeof(double);
 
-    // XCD-aware tile order: workgroup i runs on XCD i % 8; give each XCD one contiguous span of tiles so that
+    // XCD-aware tile order: workgroup i runs on XCD i % kXcds; give each XCD one contiguous span of tiles so that
     // the input rows shared by neighbouring tiles stay in that XCD's L2.  Within its span a workgroup starts with
     // the tile of its slot and then draws tiles, in ascending order, from the span's counter (then from the other
     // spans' counters): tiles differ in work, and a fixed assignment would leave workgroups idle at the end.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, per_xcd = gridDim.x >> 3;
-    const int span = (n_tiles + 7) >> 3;
+    const int xcd = blockIdx.x % kXcds, slot = blockIdx.x / kXcds, per_xcd = gridDim.x / kXcds;
+    const int span = (n_tiles + kXcds - 1) / kXcds;
     const int tile_end = (xcd + 1) * span < n_tiles ? (xcd + 1) * span : n_tiles;
 
     for (int i = threadIdx.x; i < kTileRows * CS; i += NT) s_c[i] = 0.0;  // the dummy row needs no reset
@@ -1242,8 +1242,8 @@ __global__ __launch_bounds__(kConvWaves * 64) void k_conv_mfma(int taps, long lo
         // on average and would otherwise only wait at the barrier, which hides the atomic's round trip.
         if (threadIdx.x == NT - 64) {
             int t = -1;
-            for (int d = 0; d < 8 && t < 0; ++d) {
-                const int x = (xcd + d) & 7;
+            for (int d = 0; d < kXcds && t < 0; ++d) {
+                const int x = (xcd + d) % kXcds;
                 const int end_x = (x + 1) * span < n_tiles ? (x + 1) * span : n_tiles;
                 if (x * span + per_xcd >= end_x) continue;  // (a span with no tiles to draw)
                 const int cand = x * span + per_xcd + (int)atomicAdd(&ctr->conv_ticket[x * kTicketStride], 1u);
@@ -1301,7 +1301,7 @@ static hipError_t launch_conv_mfma_t(int taps, long long nnz_in, const float* fe
     int per_cu = (int)((160 * 1024) / lds);
     if (per_cu < 1) per_cu = 1;
     if (per_cu > 4) per_cu = 4;    // 16 waves per CU
-    const int grid = (device_cu_count() * per_cu + 7) / 8 * 8;  // a multiple of 8 (one span of tiles per XCD)
+    const int grid = (device_cu_count() * per_cu + kXcds - 1) / kXcds * kXcds;  // one span of tiles per XCD
     hipLaunchKernelGGL((k_conv_mfma<KC, NB, HALF>), dim3(grid), dim3(kConvWaves * 64), lds, s, taps, nnz_in, feats, wb,
                        bias,
                        pairs, block_tap, tile_hdr, ctr, resp);

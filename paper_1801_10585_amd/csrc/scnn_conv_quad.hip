@@ -146,8 +146,8 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
     // taps with a non-zero weight, one bit each
     const unsigned act_mask = (unsigned)__ballot(lane < g.T && tap_active[lane < g.T ? lane : 0] != 0);
 
-    // XCD-aware order: workgroup i runs on XCD i % 8.  The wave tiles are cut into 8 * kQuadChunks chunks of equal
-    // length and XCD x owns the chunks x, x + 8, x + 16, ...: inside a chunk neighbouring tiles share input rows,
+    // XCD-aware order: workgroup i runs on XCD i % kXcds.  The wave tiles are cut into kXcds * kQuadChunks chunks of
+    // equal length and XCD x owns the chunks x, x + kXcds, x + 2 kXcds, ...: inside a chunk neighbouring tiles share input rows,
     // which then stay in that XCD's L2, and because an XCD's chunks are spread over the whole batch, samples whose
     // sites cost more (more taps per quad) are shared out evenly instead of falling to two or three XCDs.  An XCD's
     // wave tiles are numbered through its chunks (v = 0, 1, ...).
@@ -161,18 +161,18 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
     // A wave starts with unit u = its slot and then draws further units from its XCD's counter, and from the next
     // XCDs' once its own is used up.
     const int n_wt = 2 * (int)ctr->n_tiles;
-    const int xcd = blockIdx.x & 7, slot = (blockIdx.x >> 3) * kQuadWaves + wave, per_xcd = (gridDim.x >> 3) * kQuadWaves;
+    const int xcd = blockIdx.x % kXcds, slot = (blockIdx.x / kXcds) * kQuadWaves + wave, per_xcd = (gridDim.x / kXcds) * kQuadWaves;
     // (only where every chunk gets at least kQuadChunkMin wave tiles: shorter chunks lose more at their ends,
     // where the neighbours' rows belong to another XCD's L2, than the even shares win - measured on 16 -> 32
     // channels over 3900 wave tiles: 113 us in one chunk per XCD, 117 us in three)
-    const int n_chunks = n_wt >= 8 * kQuadChunks * kQuadChunkMin ? kQuadChunks : 1;
-    const int chunk = n_wt > 0 ? (n_wt + 8 * n_chunks - 1) / (8 * n_chunks) : 1;
+    const int n_chunks = n_wt >= kXcds * kQuadChunks * kQuadChunkMin ? kQuadChunks : 1;
+    const int chunk = n_wt > 0 ? (n_wt + kXcds * n_chunks - 1) / (kXcds * n_chunks) : 1;
     // unit u of XCD x: its wave tile (-1 past the end: then every later unit of that XCD is past the end as well) and
     // the sites lo .. hi - 1 of it
     auto unit_of = [&](int x, int u, int& lo, int& hi) {
         int vspan = 0;  // wave tiles of XCD x
         for (int c = 0; c < n_chunks; ++c) {
-            const int left = n_wt - (c * 8 + x) * chunk;
+            const int left = n_wt - (c * kXcds + x) * chunk;
             vspan += left <= 0 ? 0 : (left < chunk ? left : chunk);
         }
         lo = 0;
@@ -188,9 +188,9 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
         }
         if (v >= vspan) return -1;
         const int c = v / chunk;
-        return (c * 8 + x) * chunk + (v - c * chunk);
+        return (c * kXcds + x) * chunk + (v - c * chunk);
     };
-    unsigned* tickets = ctr->conv_ticket + (col0 >> 6) * 8 * kTicketStride;
+    unsigned* tickets = ctr->conv_ticket + (col0 >> 6) * kXcds * kTicketStride;
 
     int row_lo = 0, row_hi = kQuadRows, lo_next = 0, hi_next = 0;
     bool own_done = unit_of(xcd, per_xcd, lo_next, hi_next) < 0;  // nothing to draw beyond the first units
@@ -477,7 +477,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
             int got = -1;
             if (lane == 0) {
                 for (int d = 1; d <= kQuadSteal && got < 0; ++d) {
-                    const int x = (xcd + d) & 7;
+                    const int x = (xcd + d) % kXcds;
                     if (unit_of(x, per_xcd, lo_next, hi_next) < 0) continue;  // (an XCD with nothing to draw)
                     got = unit_of(x, per_xcd + (int)atomicAdd(&tickets[x * kTicketStride], 1u), lo_next, hi_next);
                 }
@@ -511,7 +511,7 @@ static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* oc
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     // one workgroup (four waves) per SIMD wave slot of every CU; a multiple of 8: one span of tiles per XCD
-    const int grid = (cus * quad_waves_per_simd(C_IN, QPM, ACC64) + 7) / 8 * 8;
+    const int grid = (cus * quad_waves_per_simd(C_IN, QPM, ACC64) + kXcds - 1) / kXcds * kXcds;
     hipLaunchKernelGGL((k_conv_quad<C_IN, QPM, ACC64>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix,
                        nnz_in, feats, wq, bias, c_out, col0, c_out_all, tap_active, cand_lin, cand_start, tile_start, ctr,
                        resp);

@@ -44,6 +44,10 @@ struct ColState {
 };
 
 constexpr int kTicketStride = 32;  // 32-bit words between two ticket counters
+// Accelerator dies (XCDs) of the part the tile orders are laid out for: MI355X has eight, each with its own L2, and
+// deals the workgroups of a launch out to them in turn (workgroup i runs on XCD i % kXcds).  On a part that is
+// partitioned differently the orders are still correct, the spans just stop matching the L2s.
+constexpr int kXcds = 8;
 
 // Device-resident counters produced on the way.
 struct Counters {
@@ -57,18 +61,16 @@ struct Counters {
     unsigned ticket;      // next tile of the compaction pass
     unsigned bracket_failed;  // some column's threshold lay outside its sampled bracket
     unsigned cols_done;       // columns whose selection has ended
-    // tiles handed out so far in each of the contraction kernels' eight tile spans; one counter per 128-byte line:
+    // tiles handed out so far in each of the contraction kernels' tile spans (one per XCD); one counter per 128-byte line:
     // read-modify-writes on one line are served one after the other, whichever word they address
     // (two sets: the quad kernel runs once per group of 64 output channels, up to two groups)
-    unsigned conv_ticket[2 * 8 * kTicketStride];
+    unsigned conv_ticket[2 * kXcds * kTicketStride];
 };
 
 __host__ __device__ inline long long round_up(long long x, long long m) { return (x + m - 1) / m * m; }
 
 // Compute units of the current device (asked once per device; 256, the part the launch shapes were tuned on, if the
-// runtime will not say).  The persistent kernels size their grids from it.  The XCD-aware tile orders assume that
-// workgroup i runs on XCD i % 8, which is how an 8-XCD part deals out workgroups; on another partitioning they are
-// still correct, the spans just stop matching the L2s.
+// runtime will not say).  The persistent kernels size their grids from it.
 int device_cu_count();
 
 __device__ inline long long lin_of(const Geom& g, int c0, int c1, int c2) {
