@@ -389,6 +389,23 @@ def test_matrix_core_kernel_keeps_small_responses_accurate():
                               columns=_sampled_columns(rng, wl.batch, L.c_out, 16), tag="cfg4@48 bypass")
 
 
+@pytest.mark.parametrize("extent, batch, density", [((40, 40, 40), 4, 0.08), ((44, 44, 44), 4, 0.08)])
+def test_matrix_core_kernel_with_a_partial_last_round_of_units(extent, batch, density):
+    """Layers a little larger than one round of the quad kernel's wave slots (one wave takes 64 candidate sites at a
+    time, about 3000 waves run at once on 256 compute units): the sites left for the last, partial round are dealt
+    out in quarters of 16 (about 230 000 candidate sites) or not split at all (about 300 000).  Every column is
+    compared; random sites, so that nearly every site of the grid is a candidate."""
+    rng = np.random.default_rng(4044 + extent[0])
+    coords = random_sparse_sites(rng, extent, batch, density)
+    feats = rng.normal(size=(coords.shape[0], 32)).astype(np.float32)
+    w = make_filter(rng, (3, 3, 3), 32, 64, 1.0, 0.2)
+    n = int(np.prod(extent))
+    k = scnn.k_from_rho(0.2, n)
+    say(f"partial last round extent={extent} B={batch} rows={coords.shape[0]}")
+    check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, None, k, 0.2, scnn.ABS,
+                              tag=f"partial round {extent}")
+
+
 def test_layer_exact_ties_integer_data():
     """Dyadic inputs and weights: fp32 sums are exact on both sides, so the outputs must be bit-identical,
     including the choice among equal scores at the threshold (lower lin wins)."""
