@@ -42,14 +42,15 @@ constexpr int kQuadTabWords = kQuadMaxTaps * kQuadRows;                   // 8 K
 constexpr int kQuadMaxPasses = kQuadMaxTaps * 4;                          // C_in <= 128
 constexpr int kQuadMaxSteps = kQuadMaxPasses * 16 + 4;
 constexpr int kQuadTrWords = kQuadRows * 33;                              // transposition buffer: half the columns, padded rows
-__host__ __device__ constexpr int quad_lds_words(int c_in) {
+__host__ __device__ constexpr int quad_lds_words(int c_in, int taps) {
     const int nch = (c_in + 31) / 32;
-    const int walk = kQuadTabWords + kQuadMaxTaps * nch + (kQuadMaxTaps * nch * 16 + 4) + kQuadRows;
+    const int walk = taps * kQuadRows + taps * nch + (taps * nch * 16 + 4) + kQuadRows;
     return walk > kQuadTrWords ? walk : kQuadTrWords;
 }
 // Waves per SIMD the kernel is built for: its registers are the accumulators (64 sites x 64 channels, 4 or 8 bytes
 // each) plus two sets of weights.
 __host__ __device__ constexpr int quad_waves_per_simd(int c_in, int qpm, int acc64) {
+    if (c_in <= 32 && !acc64) return 4;
     return ((qpm == 1 && acc64) || c_in == 40 || c_in == 48) ? 2 : 3;  // (two chunk widths cost registers too)
 }
 
@@ -124,16 +125,16 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
     constexpr int NA_FULL = 32 / KB, NA_LAST = (KC_LAST + KB - 1) / KB == 3 ? 4 : (KC_LAST + KB - 1) / KB;
     constexpr int NA0 = NCH == 1 ? NA_LAST : NA_FULL;  // of every chunk but the last (of the only chunk)
     static_assert(NA_FULL <= 4 && NA_LAST <= 4 && NA_LAST >= 1, "chunk width");
-    constexpr int LDSW = quad_lds_words(C_IN);
+    const int LDSW = quad_lds_words(C_IN, g.T);
     typedef typename std::conditional<ACC64 != 0, double, float>::type acc_t;
     extern __shared__ __align__(16) unsigned smem_u[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     unsigned* s_tab = smem_u + wave * LDSW;                    // [taps][64] buffer offsets, sorted site order
-    unsigned* s_pass = s_tab + kQuadTabWords;                  // [passes] tap | chunk << 8 | mask of quad sets << 16
-    unsigned* s_step = s_pass + kQuadMaxTaps * NCH;            // [steps + 2] (tap * 64 + set * SET) * 4 | chunk << 20
-    unsigned* s_pos = s_step + (kQuadMaxTaps * NCH * 16 + 4);  // [64] sorted position of a site
+    unsigned* s_pass = s_tab + g.T * kQuadRows;                  // [passes] tap | chunk << 8 | mask of quad sets << 16
+    unsigned* s_step = s_pass + g.T * NCH;            // [steps + 2] (tap * 64 + set * SET) * 4 | chunk << 20
+    unsigned* s_pos = s_step + (g.T * NCH * 16 + 4);  // [64] sorted position of a site
     float* s_tr = (float*)s_tab;                               // [64][COLS / 2 + 1] after the walk
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 
@@ -393,6 +394,19 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
                     else
                         quad_load_b<KC_LAST>(wq, pass_index(info), lane, bw);
                 };
+                if constexpr (quad_waves_per_simd(C_IN, QPM, ACC64) >= 4) {
+                    // one register set: the next pass's weights are asked for when the last step of this pass has
+                    // been issued; the SIMD's other waves cover the wait
+                    unsigned p_info = __builtin_amdgcn_readfirstlane(s_pass[0]);
+                    load_pass(p_info, b0);
+                    for (int p = 0; p < n_pass; ++p) {
+                        run_pass(b0, p_info);
+                        if (p + 1 < n_pass) {
+                            p_info = __builtin_amdgcn_readfirstlane(s_pass[p + 1]);
+                            load_pass(p_info, b0);
+                        }
+                    }
+                } else {
                 // passes in pairs: one register set multiplies while the other receives the next pass's weights
                 unsigned p_info = __builtin_amdgcn_readfirstlane(s_pass[0]);
                 load_pass(p_info, b0);
@@ -409,6 +423,7 @@ __global__ __launch_bounds__(kQuadWaves * 64, quad_waves_per_simd(C_IN, QPM, ACC
                         load_pass(p_info, b0);
                     }
                     run_pass(b1, p_next);
+                }
                 }
             }
         }
@@ -506,12 +521,15 @@ static hipError_t launch_conv_quad_t(const Geom& g, const unsigned long long* oc
                                      int col0, int c_out_all, const int* tap_active, const unsigned* cand_lin,
                                      const int* cand_start, const int* tile_start, Counters* ctr, float* resp, int cus,
                                      hipStream_t s) {
-    const size_t lds = (size_t)quad_lds_words(C_IN) * 4 * kQuadWaves;
+    const size_t lds = (size_t)quad_lds_words(C_IN, g.T) * 4 * kQuadWaves;
     hipError_t e = hipFuncSetAttribute((const void*)k_conv_quad<C_IN, QPM, ACC64>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    // one workgroup (four waves) per SIMD wave slot of every CU; a multiple of 8: one span of tiles per XCD
-    const int grid = (cus * quad_waves_per_simd(C_IN, QPM, ACC64) + kXcds - 1) / kXcds * kXcds;
+    // one workgroup (four waves) per SIMD wave slot of every CU, as far as the CU's 160 KiB of LDS hold them (every
+    // workgroup must be resident: they are persistent); a multiple of kXcds: one span of tiles per XCD
+    int per_cu = quad_waves_per_simd(C_IN, QPM, ACC64);
+    if ((size_t)per_cu * lds > 160 * 1024) per_cu = (int)((160 * 1024) / lds);
+    const int grid = (cus * per_cu + kXcds - 1) / kXcds * kXcds;
     hipLaunchKernelGGL((k_conv_quad<C_IN, QPM, ACC64>), dim3(grid), dim3(kQuadWaves * 64), lds, s, g, occ, occ_prefix,
                        nnz_in, feats, wq, bias, c_out, col0, c_out_all, tap_active, cand_lin, cand_start, tile_start, ctr,
                        resp);
