@@ -38,9 +38,6 @@ constexpr unsigned kAbsent = 0x80000000u;  // buffer offset of a neighbour that 
 // LDS of one wave.  While the taps are walked: neighbour offsets [taps][64 sorted sites], the list of (tap, chunk)
 // passes, the list of (pass, quad set) steps.  Afterwards the same bytes hold the 64 x C_out results for the
 // transposition to the planar tile.
-constexpr int kQuadTabWords = kQuadMaxTaps * kQuadRows;                   // 8 KiB
-constexpr int kQuadMaxPasses = kQuadMaxTaps * 4;                          // C_in <= 128
-constexpr int kQuadMaxSteps = kQuadMaxPasses * 16 + 4;
 constexpr int kQuadTrWords = kQuadRows * 33;                              // transposition buffer: half the columns, padded rows
 __host__ __device__ constexpr int quad_lds_words(int c_in, int taps) {
     const int nch = (c_in + 31) / 32;
@@ -48,7 +45,9 @@ __host__ __device__ constexpr int quad_lds_words(int c_in, int taps) {
     return walk > kQuadTrWords ? walk : kQuadTrWords;
 }
 // Waves per SIMD the kernel is built for: its registers are the accumulators (64 sites x 64 channels, 4 or 8 bytes
-// each) plus two sets of weights.
+// each) plus the weights of a pass.  Up to 32 input channels with fp32 sums fit 128 registers with ONE set of weights
+// (reloaded between passes: the SIMD's other three waves cover the wait); the others hold two sets, one multiplying
+// while the other is loaded.
 __host__ __device__ constexpr int quad_waves_per_simd(int c_in, int qpm, int acc64) {
     if (c_in <= 32 && !acc64) return 4;
     return ((qpm == 1 && acc64) || c_in == 40 || c_in == 48) ? 2 : 3;  // (two chunk widths cost registers too)
