@@ -24,20 +24,23 @@ enum class ConvKernel { kValu, kPair, kQuad };
 
 // Which kernel multiplies.  The quad kernel (output-stationary, registers only) takes C_in in {8, .., 64} and up to
 // 128 output channels (a launch per 64) with at most 32 taps, also C_in = 96 and 128 where the pair-list kernel does
-// not take the output width; the pair-list kernel remains for more than 32 taps and for 96 and 128 input channels.  With 8, 16 or 24 input channels the matrix cores pay only on layers of at least 1024 tiles with enough
-// output channels; narrower and smaller layers are faster on the vector kernels.
+// not take the output width; the pair-list kernel remains for more than 32 taps and for 96 and 128 input channels.  With 8, 16 or 24 input channels the matrix cores pay only on layers of enough tiles (128 or 1024, by
+// shape) with enough output channels; narrower and smaller layers are faster on the vector kernels.
 static ConvKernel conv_kernel_for(const Geom& g, int c_in, int c_out, long long nnz_in, long long tiles_cap) {
     if (g_conv_path == 1) return ConvKernel::kValu;
     const bool pair_ok = conv_mfma_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 3) return pair_ok ? ConvKernel::kPair : ConvKernel::kValu;
     const bool quad_ok = conv_quad_supported(g, c_in, c_out, nnz_in);
     if (g_conv_path == 2) return quad_ok ? ConvKernel::kQuad : (pair_ok ? ConvKernel::kPair : ConvKernel::kValu);
-    // 8, 16 and 24 input channels pay for the matrix-core kernels' look-ups and lists only on layers of at least 1024
-    // tiles (four samples of 32^3 with every site a candidate: 16->24 35 against 43 us, 24->24 40 against 58) whose rows carry enough multiply-adds per neighbour: C_in x C_out of at least 256 with at least 24
-    // output channels (8->32, 16->24), or of at least 384 (24->16); narrower layers (8->8, 8->16, 16->16: the first
-    // blocks of the paper's networks) are faster on the vector kernels
+    // 8, 16 and 24 input channels pay for the matrix-core kernels' look-ups and lists only on layers whose rows carry
+    // enough multiply-adds per neighbour: C_in x C_out of at least 256 with at least 24 output channels (8->32,
+    // 16->24), or of at least 384 (24->16); narrower layers (8->8, 8->16, 16->16: the first blocks of the paper's
+    // networks) are faster on the vector kernels.  The layer must also be large enough: 128 tiles for 16 or 24 input
+    // and at least 24 output channels (four samples of 16^3 with every site a candidate: 16->24 35 -> 31 us, 24->24
+    // 43 -> 33 us; at 64 tiles the vector kernels' 32-row form wins, 24 against 32 us), 1024 tiles for the others
     const int mac = c_in * c_out;
-    const bool wide = c_in >= 32 || ((c_in == 8 || c_in == 16 || c_in == 24) && tiles_cap >= 1024 &&
+    const long long min_tiles = (c_in >= 16 && c_out >= 24) ? 128 : 1024;
+    const bool wide = c_in >= 32 || ((c_in == 8 || c_in == 16 || c_in == 24) && tiles_cap >= min_tiles &&
                                      ((mac >= 256 && c_out >= 24) || mac >= 384));
     // 96 and 128 input channels: three or four chunks per tap put the quad kernel's sums in fp64 registers (two waves
     // per SIMD); where the pair-list kernel takes the shape it is 10-35 % faster there, and the quad kernel takes
