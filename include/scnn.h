@@ -270,8 +270,9 @@ int sparse_conv_bwd(int ndim, const int32_t* extent, int batch, const int32_t* i
 /* Kernel choice for the convolution step of sparse_conv_fwd (and, for 1, of
  * sparse_conv_bwd), for the calling thread:
  * 0 = by shape and size.  Wide layers (C_in >= 32, or C_in = 8, 16 or 24 on
- *     layers whose workspace holds more than 1024 tiles of 128 candidate
- *     sites, with C_in * C_out >= 256 and C_out >= 24, or C_in * C_out >= 384)
+ *     layers whose workspace holds at least 1024 tiles of 128 candidate
+ *     sites - 128 tiles when C_in is 16 or 24 and C_out at least 24 - with
+ *     C_in * C_out >= 256 and C_out >= 24, or C_in * C_out >= 384)
  *     take the quad matrix-core kernel where C_in is 8, 16, 24, 32, 40, 48 or
  *     64 (or 96 or 128 with a C_out the pair-list kernel does not take), C_out
  *     at most 128, the filter has at most 32 taps and in_feats is 16-byte
