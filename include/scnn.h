@@ -106,7 +106,12 @@ size_t sparse_conv_fwd_workspace(int ndim, const int32_t* extent, int batch, int
  * taps on up to 32 input channels, 16 taps on 64: the r = 128 layer's 27 x 1),
  * in fp64 otherwise; the pair-list kernel always adds them in fp64.  All stay
  * within 1e-5 relative + 1e-6 absolute of the exact sum on the workloads this
- * library is tested on.  The vector kernels and the quad kernel add in an order
+ * library is tested on.  In general the error of a matrix-core response follows
+ * the magnitudes it is summed from, not its own: about 2e-8 * A, A = the sum of
+ * |w * in| over its products (fp32 roundings of partial sums of that size),
+ * which the stated tolerance covers while A stays below about 50 (the r = 128
+ * workload: A around 20); scnn_set_conv_path(1) sums everything in fp64 for
+ * data beyond that.  The vector kernels and the quad kernel add in an order
  * fixed by the data alone and are reproducible bit for bit; the pair-list
  * kernel adds its per-tap partial sums with LDS atomics in no fixed order, so a
  * run can differ from another in the last bits of the fp64 sum, which survives
