@@ -328,10 +328,16 @@ __device__ inline float score_bound(unsigned key, int mode) {
     return key <= 0x007fffffu ? -INFINITY : __uint_as_float(~key);
 }
 
-// v with lane `lane` (uniform) replaced by the uniform value x
-__device__ inline unsigned write_lane(unsigned v, unsigned x, int lane) {
-    asm("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(x), "i"(lane));  // (lane: a constant once the loops are unrolled)
-    return v;
+// lo and hi with lane `lane` (a constant once the loops are unrolled) replaced by the halves of the lane mask m.  The
+// mask is copied by scalar moves first: it may come straight from a vector compare, and a lane write that reads a
+// scalar register too soon after a vector instruction wrote it gets the old contents; the compiler, which keeps
+// that distance for its own instructions, does not look inside an asm statement (and has no builtin for the lane
+// write here).  A scalar move waits for the vector instruction by itself.
+__device__ inline void write_lanes(unsigned& lo, unsigned& hi, unsigned long long m, int lane) {
+    unsigned t0, t1;
+    asm("s_mov_b32 %2, %4\n\ts_mov_b32 %3, %5\n\tv_writelane_b32 %0, %2, %6\n\tv_writelane_b32 %1, %3, %6"
+        : "+v"(lo), "+v"(hi), "=&s"(t0), "=&s"(t1)
+        : "s"((unsigned)m), "s"((unsigned)(m >> 32)), "i"(lane));
 }
 
 constexpr int kClassifyWaves = 8;
@@ -345,7 +351,7 @@ __host__ __device__ inline int classify_slice_tiles(int T, int slices) {
     return (per + kClassifyTiles - 1) / kClassifyTiles * kClassifyTiles;
 }
 
-template <int MODE>
+template <int MODE, bool MARKS /* row_plane given: the rows of sure survivors are recorded */>
 __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int channels,
                                                                   const int* __restrict__ tile_start,
                                                                   const float* __restrict__ resp,
@@ -368,9 +374,15 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
     const int t0 = tile_start[b], t1 = tile_start[b + 1];
     const float s_lo = score_bound(st.tau_lo, MODE), s_hi = score_bound(st.tau_hi, MODE);
     const unsigned long long relu_off = relu ? 0ull : ~0ull;
+    // |x| as the score: a row survives for sure when y > sure_hi, y = x under ReLU (a negative value is dropped
+    // later), |x| without; sure_hi = the bracket's upper end where that is a number not below zero (an entry above it
+    // is then non-zero, and positive under ReLU), 0 where it is negative (every entry is above it), infinity where it
+    // is no number (no entry compares above it)
+    const unsigned sure_sign = relu ? 0xffffffffu : 0x7fffffffu;
+    const float sure_hi = s_hi >= 0.0f ? s_hi : (s_hi < 0.0f ? 0.0f : INFINITY);
     uint2* wbuf = s_buf + wave * WCAP;
     int fill = 0;                    // wave-uniform
-    unsigned n_nz = 0, n_above = 0;  // wave-uniform
+    unsigned n_nz = 0, n_above = 0;  // per lane
     // slice y of the column: tiles [first, last)
     const int L = classify_slice_tiles(t1 - t0, (int)gridDim.y);
     const int first = t0 + (int)blockIdx.y * L;
@@ -385,7 +397,7 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
         for (int i = lane; i < fill; i += 64) run[base + i] = wbuf[i];
         fill = 0;
     };
-    unsigned long long* plane = row_plane ? row_plane + (size_t)oc * plane_words : nullptr;
+    unsigned long long* plane = MARKS ? row_plane + (size_t)oc * plane_words : nullptr;
     // the values of tiles tile0 .. tile0 + U - 1 at rows lane and lane + 64 (a tile past the slice: the slice's first)
     auto load = [&](int tile0, float (&v)[U][2]) {
 #pragma unroll
@@ -396,38 +408,43 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
             v[u][1] = seg[64 + lane];
         }
     };
-    // one iteration: the tiles tile0 .. tile0 + U - 1, whose values are in v; FULL: all of them are in the slice
+    // one iteration: the tiles tile0 .. tile0 + U - 1, whose values are in v; FULL: all of them are in the slice.
+    // The loop is bound by scalar instructions (lane masks are combined, counted and turned into branch conditions
+    // there), so whatever can be decided per lane is: the two counts are kept per lane and added up at the end,
+    // the bracket test is one condition whose mask is also the staging order, and with |x| as the score the rows
+    // that survive for sure are one compare (x, or |x| without ReLU, against the bracket's upper end).
     auto process = [&](int tile0, const float (&v)[U][2], auto full) {
         constexpr bool FULL = decltype(full)::value;
         unsigned mark_lo = 0, mark_hi = 0;  // lane j: the marks of tile j / 2, rows (j & 1) * 64 ..
+        const unsigned pos0 = (unsigned)(tile0 - t0) * kTileRows + (unsigned)lane;
 #pragma unroll
         for (int u = 0; u < U; ++u) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 const float x = (FULL || tile0 + u < last) ? v[u][h] : 0.0f;
                 const float sc = MODE == SCNN_TOPK_ABS ? fabsf(x) : x;
-                // (ballots of single compares: the compare writes the mask; the masks are combined as scalars)
-                const unsigned long long nz = __ballot(x != 0.0f);
-                const unsigned long long above = __ballot(sc > s_hi) & nz;
-                const unsigned long long m = __ballot(sc >= s_lo) & nz & ~above;  // inside the bracket
-                const bool hit = x != 0.0f && sc >= s_lo && !(sc > s_hi);
-                n_nz += (unsigned)__popcll(nz);
-                n_above += (unsigned)__popcll(above);
-                if (plane) {
-                    const unsigned long long sure = above & (__ballot(x > 0.0f) | relu_off);
-                    mark_lo = write_lane(mark_lo, (unsigned)sure, u * 2 + h);
-                    mark_hi = write_lane(mark_hi, (unsigned)(sure >> 32), u * 2 + h);
+                const bool nz = x != 0.0f, above = nz && sc > s_hi;
+                const bool hit = nz && sc >= s_lo && !(sc > s_hi);  // inside the bracket
+                const unsigned long long m = __ballot(hit);
+                n_nz += nz ? 1u : 0u;
+                n_above += above ? 1u : 0u;
+                if constexpr (MARKS) {
+                    unsigned long long sure;
+                    if constexpr (MODE == SCNN_TOPK_ABS)
+                        sure = __ballot(__uint_as_float(__float_as_uint(x) & sure_sign) > sure_hi);
+                    else
+                        sure = __ballot(above) & (__ballot(x > 0.0f) | relu_off);
+                    write_lanes(mark_lo, mark_hi, sure, u * 2 + h);
                 }
                 if (hit) {  // the value itself is staged; its key is taken when the entry is read
                     const unsigned rank =
                         __builtin_amdgcn_mbcnt_hi((unsigned)(m >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)m, 0u));
-                    wbuf[fill + (int)rank] = make_uint2(__float_as_uint(x), (unsigned)(tile0 + u - t0) * kTileRows +
-                                                                                 (unsigned)(h * 64 + lane));
+                    wbuf[fill + (int)rank] = make_uint2(__float_as_uint(x), pos0 + (unsigned)(u * kTileRows + h * 64));
                 }
                 fill += __popcll(m);
             }
         }
-        if (plane && lane < 2 * U && (FULL || tile0 + (lane >> 1) < last))
+        if (MARKS && lane < 2 * U && (FULL || tile0 + (lane >> 1) < last))
             plane[2 * (size_t)tile0 + lane] = ((unsigned long long)mark_hi << 32) | mark_lo;
     };
     auto process_any = [&](int tile0, const float (&v)[U][2]) {
@@ -454,6 +471,11 @@ __global__ __launch_bounds__(kClassifyWaves * 64) void k_classify(int relu, int 
         process_any(tile0 + U, vb);
     }
     if (fill > 0) flush();
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        n_nz += __shfl_xor(n_nz, d, 64);
+        n_above += __shfl_xor(n_above, d, 64);
+    }
     if (lane == 0) part[(size_t)col * gridDim.y + blockIdx.y] = make_uint2(n_nz, n_above);
 }
 
@@ -1066,12 +1088,17 @@ hipError_t launch_topk(const Geom& g, int channels, long long k, int mode, int r
     if (slices > kClassifySlicesMax) slices = kClassifySlicesMax;
     const bool marks = row_keep && row_plane && tile_base && k > 0;
     hipLaunchKernelGGL(k_bracket, dim3(ncols), dim3(kBracketThreads), 0, s, mode, channels, tile_start, resp, k, cols);
-    if (mode == SCNN_TOPK_ABS)
-        hipLaunchKernelGGL(k_classify<SCNN_TOPK_ABS>, dim3(groups, slices), dim3(kClassifyWaves * 64), 0, s, relu,
-                           channels, tile_start, resp, cols, side, part, marks ? row_plane : nullptr, 2 * tiles_cap);
-    else
-        hipLaunchKernelGGL(k_classify<SCNN_TOPK_SIGNED>, dim3(groups, slices), dim3(kClassifyWaves * 64), 0, s, relu,
-                           channels, tile_start, resp, cols, side, part, marks ? row_plane : nullptr, 2 * tiles_cap);
+#define SCNN_CLASSIFY(MODE_, MARKS_)                                                                                 \
+    hipLaunchKernelGGL((k_classify<MODE_, MARKS_>), dim3(groups, slices), dim3(kClassifyWaves * 64), 0, s, relu,    \
+                       channels, tile_start, resp, cols, side, part, marks ? row_plane : nullptr, 2 * tiles_cap)
+    if (mode == SCNN_TOPK_ABS) {
+        if (marks) SCNN_CLASSIFY(SCNN_TOPK_ABS, true);
+        else SCNN_CLASSIFY(SCNN_TOPK_ABS, false);
+    } else {
+        if (marks) SCNN_CLASSIFY(SCNN_TOPK_SIGNED, true);
+        else SCNN_CLASSIFY(SCNN_TOPK_SIGNED, false);
+    }
+#undef SCNN_CLASSIFY
     if (marks) {
         long long cb = (2 * tiles_cap + 63) / 64;
         cb = cb < 1 ? 1 : (cb > 2048 ? 2048 : cb);
