@@ -225,3 +225,41 @@ def test_wide_layers_with_long_columns(case):
         say(f"wide/long extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} rho={rho} k={k}")
         check_conv_against_oracle(extent, batch, coords, feats, (3, 3, 3), w, bias, k, rho, scnn.ABS,
                                   columns=_sampled_columns(rng, batch, c_out, 6), tag=f"wide/long {extent} rho={rho}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_matrix_core_and_vector_kernels_agree_over_layer_sizes(seed):
+    """Layer sizes from a hundred to several thousand groups of 64 candidate sites, i.e. on both sides of every point
+    at which the quad kernel changes how it deals its work out (wave tiles in quarters, in halves, whole; an XCD's
+    tiles in one span or in chunks; one or two groups of 64 output channels).  The oracle needs minutes for the
+    larger ones, so this sweep compares the library's two kernel families with each other instead: the vector
+    kernels (fp64 sums; compared with the oracle by every other test here) and the quad kernel, selection bypassed
+    (rho_up = 1), every response within the value tolerance and the same sites.  The oracle comparisons of the quad
+    kernel at full size are the configuration tests."""
+    import torch
+    from tests.parity import ATOL, RTOL
+    rng = np.random.default_rng(7000 + seed)
+    c_in, c_out = [(32, 64), (16, 24), (32, 96), (8, 32), (24, 24), (32, 32)][seed % 6]
+    e = int(rng.integers(20, 72))
+    extent = (e, e, int(rng.integers(8, e + 1)))
+    batch = int(rng.integers(1, 6))
+    coords = random_sparse_sites(rng, extent, batch, float(rng.choice([0.02, 0.05, 0.1, 0.3])))
+    feats = rng.normal(size=(coords.shape[0], c_in)).astype(np.float32)
+    w = (rng.normal(size=(27, c_in, c_out)) * 0.04).astype(np.float32)
+    dev = torch.device("cuda:0")
+    ct, ft, wt = (torch.from_numpy(a).to(dev) for a in (coords, feats, w))
+    out = {}
+    try:
+        for path in (1, 2):
+            scnn.set_conv_path(path)
+            oc, of, n = scnn.sparse_conv_fwd(extent, batch, ct, ft, (3, 3, 3), wt, rho_up=1.0, relu=False, pool=False)
+            assert int(n[2]) == 0
+            out[path] = (oc.cpu().numpy(), of.cpu().numpy(), scnn.last_conv_kernel())
+    finally:
+        scnn.set_conv_path(0)
+    say(f"families seed={seed} extent={extent} B={batch} {c_in}->{c_out} rows={coords.shape[0]} "
+        f"sites out={out[1][0].shape[0]} kernels={out[1][2]}, {out[2][2]}")
+    assert out[1][2] == "k_conv_valu" and out[2][2] == "k_conv_quad"
+    assert np.array_equal(out[1][0], out[2][0]), "the two kernel families disagree on the output sites"
+    ref, got = out[1][1], out[2][1]
+    assert np.all(np.abs(got - ref) <= RTOL * np.abs(ref) + ATOL), "the two kernel families disagree on a value"
