@@ -1593,7 +1593,13 @@ hipError_t launch_finish(const Counters* ctr, int which_rows, long long aux_imm,
 // holds too little data to pay for a ticket, a look-back and three barriers, so a workgroup takes kNarrowTiles
 // consecutive tiles per ticket (a "super-tile", one status word in tile_state) and a thread owns whole rows: it reads
 // a row's channels from the planar tile (coalesced across the wave), decides them, and writes the row itself.
-template <int CMAX, int kNarrowTiles /* tiles per ticket at most: rows per thread = kNarrowTiles / 2 */>
+// UNI: the wave's tile and sample are made scalars, so that the look-ups of the sample's bounds and of the columns'
+// thresholds are scalar loads, once per wave, instead of vector loads per row and channel: fewer instructions, which
+// large layers are bound by (128^3 x 4 with 8 channels: 57 -> 48 us), but a chain of dependent scalar loads per row
+// group, which small layers, bound by latency, pay for (32^3 network: + 8 us with it everywhere); the host picks by
+// the workspace's tile capacity.
+constexpr long long kNarrowUniformTiles = 8192;
+template <int CMAX, int kNarrowTiles /* tiles per ticket at most: rows per thread = kNarrowTiles / 2 */, bool UNI>
 __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int channels, int mode, int relu,
                                                                 const int* __restrict__ cand_start,
                                                                 const int* __restrict__ tile_start,
@@ -1630,12 +1636,14 @@ __global__ __launch_bounds__(256, 4) void k_select_write_narrow(Geom g, int chan
 #pragma unroll
         for (int q = 0; q < RPT; ++q) {
             const int e = q * 256 + threadIdx.x;
-            const int tile = st * tps + (e >> 7), r = e & (kTileRows - 1);
+            const int tile_v = st * tps + (e >> 7), r = e & (kTileRows - 1);
+            const int tile = UNI ? __builtin_amdgcn_readfirstlane(tile_v) : tile_v;
             keep_row[q] = false;
             row_b[q] = 0;
             row_first[q] = -1;
             if ((e >> 7) < tps && tile < n_tiles) {  // (uniform in the wave)
-                const int b = sample_of_tile(tile_start, g.batch, tile);
+                const int b_v = sample_of_tile(tile_start, g.batch, tile);
+                const int b = UNI ? __builtin_amdgcn_readfirstlane(b_v) : b_v;
                 const int first = cand_start[b] + (tile - tile_start[b]) * kTileRows;
                 int nrows = cand_start[b + 1] - first;
                 if (nrows > kTileRows) nrows = kTileRows;
@@ -1729,9 +1737,14 @@ hipError_t launch_select_write(const Geom& g, int channels, int mode, int relu, 
         while (tps < NT_ && tiles_cap > 512ll * tps) tps *= 2;                                                    \
         long long nb = (tiles_cap + tps - 1) / tps;                                                               \
         nb = nb < 1 ? 1 : (nb > cus * 3 ? cus * 3 : nb);                                                          \
-        hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_>), dim3((unsigned)nb), dim3(256), 0, s, g, channels, \
-                           mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state, ctr, out_coords, \
-                           out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);                          \
+        if (tiles_cap >= kNarrowUniformTiles)                                                                     \
+            hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_, true>), dim3((unsigned)nb), dim3(256), 0, s, g, \
+                               channels, mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state,    \
+                               ctr, out_coords, out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);     \
+        else                                                                                                      \
+            hipLaunchKernelGGL((k_select_write_narrow<CMAX_, NT_, false>), dim3((unsigned)nb), dim3(256), 0, s, g, \
+                               channels, mode, relu, cand_start, tile_start, cand_lin, resp, cols, tile_state,    \
+                               ctr, out_coords, out_feats, out_capacity, nnz_out, aux_imm, aux_is_cand, tps);     \
     } while (0)
     if (channels <= 4) SCNN_NARROW_CASE(4, 8);
     else if (channels <= 8) SCNN_NARROW_CASE(8, 8);
