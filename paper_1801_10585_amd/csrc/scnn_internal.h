@@ -84,6 +84,16 @@ __device__ inline void site_of(const Geom& g, long long lin, int& c0, int& c1, i
     c1 = (int)(lin % g.E[1]);
     c0 = (int)(lin / g.E[1]);
 }
+// The same for a site index inside one sample, which fits 32 bits (the candidate lists hold these): two 32-bit
+// divisions instead of two 64-bit ones, which cost several times as many instructions.
+__device__ inline void site_of(const Geom& g, unsigned lin, int& c0, int& c1, int& c2) {
+    const unsigned e2 = (unsigned)g.E[2], e1 = (unsigned)g.E[1];
+    const unsigned q = lin / e2;
+    c2 = (int)(lin - q * e2);
+    const unsigned q1 = q / e1;
+    c1 = (int)(q - q1 * e1);
+    c0 = (int)q1;
+}
 
 // coords rows are (b, c_1..c_ndim); internally sites always use three axes with
 // the real axes right-aligned (2-D: axis 0 has extent 1).
